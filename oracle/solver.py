@@ -1,0 +1,126 @@
+"""Oracle: the layer x discretised-error dynamic program (Algorithm 1 of the paper).
+
+Problem (section "The Constrained Optimization Problem"): choose one candidate c_l per
+layer minimising sum size(l, c_l) subject to sum error(l, c_l) <= E_max.  Errors are
+discretised with step E_max / D (section "The L-GreCo Framework", Overview) and the
+knapsack-style table DP[l][e] = min total size of the first l layers whose binned errors
+sum to exactly e is filled layer by layer; PD keeps the arg-min candidate for the
+back-trace (Algorithm 1).
+
+Readings where the listing is silent or breaks:
+  * bin(l,c) = floor((error * D) / E_max) in fp64, in that operation order; negative errors
+    count as 0; a bin above D makes the candidate unusable for that layer.  With floor the
+    uniform default always stays feasible.  If E_max <= 0 only zero-error candidates are usable
+    (bin 0).
+  * The first layer is treated like every other one, starting from a virtual row
+    DP[0][0] = 0, DP[0][e > 0] = inf.  This equals the listing's initialisation when the first
+    layer's bins are distinct and <= D, and also covers two candidates in one bin (keep the
+    smaller) and bins > D (skip).
+  * Strict '<' with candidates visited in ascending index: the lowest candidate index wins a
+    tie.  The final arg-min takes the lowest e among equal minima.
+Sizes are integers (bytes), so there are no floating-point ties.
+"""
+import math
+
+import numpy as np
+
+INF = np.iinfo(np.int64).max // 4
+UNUSABLE = -1
+
+
+def discretise(errors: np.ndarray, e_max: float, n_bins: int) -> np.ndarray:
+    """int64 [L x P] bins; UNUSABLE where the candidate cannot be taken."""
+    errors = np.asarray(errors, np.float64)
+    bins = np.empty(errors.shape, np.int64)
+    for idx, err in np.ndenumerate(errors):
+        err = max(float(err), 0.0)
+        if e_max > 0.0:
+            b = math.floor((err * float(n_bins)) / float(e_max))
+            bins[idx] = b if b <= n_bins else UNUSABLE
+        else:
+            bins[idx] = 0 if err <= 0.0 else UNUSABLE
+    return bins
+
+
+def dp_tables(bins: np.ndarray, sizes: np.ndarray, n_bins: int):
+    """Fill DP and PD (Algorithm 1, sweep).  Row 0 of DP is the virtual start row."""
+    n_layers, n_cands = bins.shape
+    dp = np.full((n_layers + 1, n_bins + 1), INF, np.int64)
+    pd = np.full((n_layers + 1, n_bins + 1), -1, np.int64)
+    dp[0][0] = 0
+    for l in range(1, n_layers + 1):
+        for c in range(n_cands):
+            b = int(bins[l - 1][c])
+            if b == UNUSABLE or b > n_bins:
+                continue
+            cost = int(sizes[l - 1][c])
+            for e in range(b, n_bins + 1):
+                prev = dp[l - 1][e - b]
+                if prev >= INF:
+                    continue
+                t = prev + cost
+                if t < dp[l][e]:
+                    dp[l][e] = t
+                    pd[l][e] = c
+    return dp, pd
+
+
+def dp_tables_fast(bins: np.ndarray, sizes: np.ndarray, n_bins: int):
+    """Same table, with the innermost loop over e written as one array statement (the cells
+    of a row do not depend on each other).  Used where the scalar loops would take minutes."""
+    n_layers, n_cands = bins.shape
+    dp = np.full((n_layers + 1, n_bins + 1), INF, np.int64)
+    pd = np.full((n_layers + 1, n_bins + 1), -1, np.int64)
+    dp[0][0] = 0
+    for l in range(1, n_layers + 1):
+        for c in range(n_cands):
+            b = int(bins[l - 1][c])
+            if b == UNUSABLE or b > n_bins:
+                continue
+            prev = dp[l - 1][:n_bins + 1 - b]
+            t = np.where(prev >= INF, INF, prev + np.int64(sizes[l - 1][c]))
+            row = dp[l][b:]
+            better = t < row
+            row[better] = t[better]
+            pd[l][b:][better] = c
+    return dp, pd
+
+
+def backtrace(dp: np.ndarray, pd: np.ndarray, bins: np.ndarray):
+    """Algorithm 1, reconstruction: lowest e among the minima of the last row, then walk back.
+    Returns None if no assignment fits."""
+    n_layers = bins.shape[0]
+    last = dp[n_layers]
+    best = int(last.min())
+    if best >= INF:
+        return None
+    e = int(np.argmin(last))                       # numpy argmin: first (lowest e) minimum
+    choice = np.zeros(n_layers, np.int32)
+    for l in range(n_layers, 0, -1):
+        c = int(pd[l][e])
+        choice[l - 1] = c
+        e -= int(bins[l - 1][c])
+    assert e == 0
+    return choice
+
+
+def solve(errors: np.ndarray, sizes: np.ndarray, e_max: float, n_bins: int, fast: bool = True):
+    """Returns (choice int32[L] or None, total_size, total_error)."""
+    errors = np.asarray(errors, np.float64)
+    sizes = np.asarray(sizes, np.int64)
+    bins = discretise(errors, e_max, n_bins)
+    dp, pd = (dp_tables_fast if fast else dp_tables)(bins, sizes, n_bins)
+    choice = backtrace(dp, pd, bins)
+    if choice is None:
+        return None, None, None
+    rows = np.arange(errors.shape[0])
+    return choice, int(sizes[rows, choice].sum()), float(np.sum(errors[rows, choice]))
+
+
+def e_max_uniform(errors: np.ndarray, default: int) -> float:
+    """Error budget: total error of the uniform default setting, summed in layer order
+    (Algorithm 1, second step; section "The Error Bound")."""
+    total = 0.0
+    for l in range(errors.shape[0]):
+        total += float(errors[l][default])
+    return total
