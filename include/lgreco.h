@@ -1,0 +1,172 @@
+/*
+ * lgreco.h - C ABI of the MI355X-native L-GreCo hot path (liblgreco.so).
+ *
+ * L-GreCo (layer-wise adaptive gradient compression) picks, for every layer of a model,
+ * one compression parameter out of a candidate list so that the total compressed size is
+ * minimal while the total squared-L2 compression error stays below the error of a uniform
+ * default setting (paper: sections "Problem Setup" and "The L-GreCo Framework",
+ * Algorithm 1).  This library is the data-parallel hot path of that method on one GPU:
+ *
+ *   lgreco_profile   error(l, c) and size(l, c) for every layer l and candidate c
+ *                    (Algorithm 1: the Costs and Errors matrices; "Implementation":
+ *                    simulated compress -> decompress, squared L2 distance)
+ *   lgreco_emax      E_max = total error of the uniform default (Algorithm 1, step 2)
+ *   lgreco_solve     the layer x discretised-error dynamic program and its back-trace
+ *                    (Algorithm 1, the DP and PD tables)
+ *   lgreco_compress  apply the chosen per-layer setting, produce the payload and update
+ *                    the error-feedback buffer (what the paper's communication engine does
+ *                    with the mapping, section "Implementation")
+ *
+ * Three compression families (section "Experimental Validation"): bucketed quantization
+ * with b bits per value, layer-wise Top-K with density d, PowerSGD-style low rank with rank r.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory on the current device);
+ *     every other pointer is HOST memory.  The caller owns all of them.  The handle owns
+ *     only scratch memory sized at lgreco_create().
+ *   - All kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  Host outputs are valid when the call returns (the call waits for them).
+ *   - Every function returns an lgreco status: 0 on success, negative on error.  Nothing
+ *     throws, nothing prints.  Inputs must be finite; NaN/Inf gradients give undefined
+ *     numerical results (never a fault).
+ *   - Gradients of all layers live in one flat fp32 buffer; layer l is the range
+ *     [offset, offset + numel).  Ranges must not overlap.  16-byte aligned layer starts
+ *     (offset % 4 == 0 with a 16-byte aligned buffer) take the fast path; other offsets work
+ *     through a slower path.
+ */
+#ifndef LGRECO_H
+#define LGRECO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LGRECO_OK            0
+#define LGRECO_EINVAL       (-1)  /* null pointer, negative/zero size, unknown family, bad layer table */
+#define LGRECO_ENOSPACE     (-2)  /* exceeds the limits given to lgreco_create */
+#define LGRECO_EINFEASIBLE  (-3)  /* no assignment fits the error budget */
+#define LGRECO_EHIP         (-4)  /* HIP runtime error (text via lgreco_last_hip_error) */
+#define LGRECO_EUNSUPPORTED (-5)  /* valid request this build does not implement */
+
+#define LGRECO_QUANT   0   /* param = bits per value, integer in [1, 8] */
+#define LGRECO_TOPK    1   /* param = density in (0, 1] */
+#define LGRECO_LOWRANK 2   /* param = rank, integer in [1, r_max] */
+
+#define LGRECO_MAX_CANDS 32
+#define LGRECO_MAX_BINS  16384
+
+typedef struct lgreco_handle lgreco_handle_t;
+
+/* One layer of the flat gradient buffer.  rows*cols == numel gives the matrix view used by
+ * LOWRANK (rows = first tensor dimension, cols = product of the others, row-major);
+ * rows == 0 marks a tensor with no matrix view (LOWRANK candidates are then rejected). */
+typedef struct {
+    int64_t offset;   /* first element in the flat buffer */
+    int64_t numel;    /* > 0, < 2^31 */
+    int32_t rows;
+    int32_t cols;
+} lgreco_layer_t;
+
+typedef struct {
+    int32_t family;   /* LGRECO_QUANT | LGRECO_TOPK | LGRECO_LOWRANK */
+    int32_t reserved; /* must be 0 */
+    double  param;
+} lgreco_cand_t;
+
+typedef struct {
+    int32_t  bucket;       /* quantization bucket size in elements; this build: 128 */
+    int32_t  stochastic;   /* 0: round to nearest (floor(t + 0.5)); 1: floor(t + u), u from
+                              Philox4x32-10 keyed by seed with counter (index/4, layer) */
+    uint64_t seed;
+    int32_t  power_iters;  /* LOWRANK power-iteration steps per call; this build: 1 */
+    int32_t  r_max;        /* columns of the warm-start Q per layer; this build: <= 64 */
+} lgreco_config_t;
+
+/* Create a handle for problems of at most max_elems gradient elements (sum of numel),
+ * max_layers layers and max_cands candidates.  Allocates the scratch memory on the current
+ * device; the handle must be used on that device only, by one thread at a time. */
+int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max_elems,
+                  int32_t max_layers, int32_t max_cands);
+int lgreco_destroy(lgreco_handle_t* h);
+
+/* size(l, c) in bytes, host arithmetic only (Algorithm 1, the Costs matrix):
+ *   QUANT   sum over the layer's buckets of ceil(count*bits/8) + 8   (codes + fp32 min, unit)
+ *   TOPK    8*k, k = min(n, max(1, floor(d*n + 0.5)))               (fp32 value + u32 index)
+ *   LOWRANK 4*(rows + cols)*r
+ * sizes is [L x P] row-major. */
+int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                 int32_t bucket, int64_t* sizes);
+
+/* Profile: errors[l][c] = || C_c(x) - x ||^2 with x = fl32(g + e) for every layer and
+ * candidate, the squared L2 distance between the vector and its compress -> decompress image
+ * (section "Implementation"; additive over layers, section "The Constrained Optimization
+ * Problem").  The error-feedback buffer is read, never updated.
+ *   d_grads  fp32 flat gradient buffer, read only
+ *   d_ef     fp32 error-feedback buffer of the same layout, or NULL (= zeros)
+ *   d_q0     LOWRANK only (else NULL): warm-start Q of every layer, fp32, layer l at element
+ *            offset r_max * (sum of cols of layers before l), [cols x r_max] row-major; rank r
+ *            uses its first r columns
+ *   errors   host [L x P] row-major, fp64
+ *   sizes    host [L x P] row-major, bytes, or NULL to skip */
+int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef,
+                   const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                   const float* d_q0, double* errors, int64_t* sizes, void* stream);
+
+/* E_max: sum over layers, in layer order, of errors[l][default_cand] (Algorithm 1, step 2;
+ * section "The Error Bound").  Host arithmetic. */
+int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand, double* e_max);
+
+/* Solve: minimise sum size(l, c_l) subject to sum bin(l, c_l) <= n_bins, where
+ * bin = floor((error * n_bins) / e_max) in fp64 (discretisation step e_max / n_bins,
+ * section "The L-GreCo Framework"); candidates with bin > n_bins are unusable.  The table is
+ * swept layer by layer with a strict '<' over candidates in index order and the back-trace
+ * starts from the lowest-error minimum of the last row (Algorithm 1).
+ *   choice       host [L]: candidate index per layer
+ *   total_size   sum of the chosen sizes (may be NULL)
+ *   total_error  sum of the chosen real errors (may be NULL)
+ * Returns LGRECO_EINFEASIBLE if no assignment fits; choice then holds each layer's
+ * minimum-error candidate.  n_bins <= LGRECO_MAX_BINS. */
+int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes, int32_t L,
+                 int32_t P, double e_max, int32_t n_bins, int32_t* choice, int64_t* total_size,
+                 double* total_error, void* stream);
+
+/* Byte offset of every layer's payload for a given choice, host arithmetic only.
+ * offsets has L+1 entries; layer l's payload is [offsets[l], offsets[l] + size(l, choice[l]))
+ * and offsets[L] is the buffer size to allocate.  Layer starts are rounded up to 16 bytes. */
+int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
+                          int32_t P, const int32_t* choice, int32_t bucket, int64_t* offsets);
+
+/* Compress every layer with its chosen candidate.
+ *   d_ef       in: error feedback e; out: e' = x - decompress(compress(x)), x = fl32(g + e).
+ *              Required (not NULL).
+ *   d_q        LOWRANK only (else NULL): in: warm-start Q (layout as d_q0); out: the first r
+ *              columns of each layer's block hold the new Q (next warm start)
+ *   d_payload  out, layouts:
+ *     QUANT   per bucket (fp32 min, fp32 unit) for all buckets, then each bucket's codes as
+ *             an LSB-first bit stream (element i at bits [i*b, (i+1)*b)) padded to a byte
+ *     TOPK    fp32 values[k] then uint32 indices[k] (index within the layer), ascending
+ *             index; among equal magnitudes the lower index is kept
+ *     LOWRANK Phat [rows x r] then Q [cols x r], fp32 row-major
+ *   offsets    host [L+1] from lgreco_payload_layout */
+int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
+                    const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                    const int32_t* choice, float* d_q, uint8_t* d_payload, const int64_t* offsets,
+                    void* stream);
+
+/* Timing of the kernels launched by the last profile / solve / compress call on this handle.
+ * lgreco_set_timing(h, 1) makes every call bracket its kernels with HIP events on the call's
+ * stream; lgreco_get_timing returns the number of sections recorded by the last call and
+ * fills names (static strings) and milliseconds for up to `cap` of them. */
+int lgreco_set_timing(lgreco_handle_t* h, int32_t enabled);
+int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap);
+
+const char* lgreco_strerror(int status);
+/* Text of the last HIP error seen by this handle ("" if none). */
+const char* lgreco_last_hip_error(const lgreco_handle_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LGRECO_H */

@@ -1,0 +1,210 @@
+"""ctypes binding of liblgreco.so: argument marshalling only.  Function names and argument
+order follow include/lgreco.h.  Device buffers are torch CUDA(ROCm) tensors (PyTorch is used
+for device memory and streams only); host tables are numpy arrays.
+
+The library is loaded on first use and a missing library is an error: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblgreco.so")
+
+OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+QUANT, TOPK, LOWRANK = 0, 1, 2
+
+EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_emax",
+           "lgreco_solve", "lgreco_payload_layout", "lgreco_compress", "lgreco_set_timing",
+           "lgreco_get_timing", "lgreco_strerror", "lgreco_last_hip_error")
+
+
+class Layer(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("numel", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32)]
+
+
+class Cand(C.Structure):
+    _fields_ = [("family", C.c_int32), ("reserved", C.c_int32), ("param", C.c_double)]
+
+
+class Config(C.Structure):
+    _fields_ = [("bucket", C.c_int32), ("stochastic", C.c_int32), ("seed", C.c_uint64),
+                ("power_iters", C.c_int32), ("r_max", C.c_int32)]
+
+
+class LgrecoError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("lgreco status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("liblgreco.so is not built: run `python -m paper_2210_17357_amd.build` "
+                               "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_double
+        l.lgreco_create.argtypes = [C.POINTER(vp), C.POINTER(Config), i64, i32, i32]
+        l.lgreco_destroy.argtypes = [vp]
+        l.lgreco_sizes.argtypes = [vp, i32, vp, i32, i32, vp]
+        l.lgreco_profile.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp]
+        l.lgreco_emax.argtypes = [vp, i32, i32, i32, C.POINTER(dbl)]
+        l.lgreco_solve.argtypes = [vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64), C.POINTER(dbl), vp]
+        l.lgreco_payload_layout.argtypes = [vp, i32, vp, i32, vp, i32, vp]
+        l.lgreco_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
+        l.lgreco_set_timing.argtypes = [vp, i32]
+        l.lgreco_get_timing.argtypes = [vp, vp, vp, i32]
+        l.lgreco_strerror.argtypes = [C.c_int]
+        l.lgreco_strerror.restype = C.c_char_p
+        l.lgreco_last_hip_error.argtypes = [vp]
+        l.lgreco_last_hip_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if getattr(l, name).restype is C.c_int:
+                pass
+        _lib = l
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().lgreco_strerror(status).decode()
+
+
+def layer_table(offsets, numels, rows, cols):
+    n = len(numels)
+    arr = (Layer * n)()
+    for i in range(n):
+        arr[i] = Layer(int(offsets[i]), int(numels[i]), int(rows[i]), int(cols[i]))
+    return arr
+
+
+def cand_table(cands: Sequence[Tuple[int, float]]):
+    arr = (Cand * len(cands))()
+    for i, (f, p) in enumerate(cands):
+        arr[i] = Cand(int(f), 0, float(p))
+    return arr
+
+
+def _dptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _np(a) -> int:
+    return a.ctypes.data
+
+
+def sizes(layers, cands, bucket: int = 128) -> np.ndarray:
+    out = np.zeros((len(layers), len(cands)), np.int64)
+    st = lib().lgreco_sizes(C.addressof(layers), len(layers), C.addressof(cands), len(cands), bucket, _np(out))
+    if st != OK:
+        raise LgrecoError(st, strerror(st))
+    return out
+
+
+def emax(errors: np.ndarray, default_cand: int) -> float:
+    errors = np.ascontiguousarray(errors, np.float64)
+    v = C.c_double()
+    st = lib().lgreco_emax(_np(errors), errors.shape[0], errors.shape[1], default_cand, C.byref(v))
+    if st != OK:
+        raise LgrecoError(st, strerror(st))
+    return v.value
+
+
+def payload_layout(layers, cands, choice: np.ndarray, bucket: int = 128) -> np.ndarray:
+    choice = np.ascontiguousarray(choice, np.int32)
+    out = np.zeros(len(layers) + 1, np.int64)
+    st = lib().lgreco_payload_layout(C.addressof(layers), len(layers), C.addressof(cands), len(cands),
+                                     _np(choice), bucket, _np(out))
+    if st != OK:
+        raise LgrecoError(st, strerror(st))
+    return out
+
+
+class Handle:
+    """lgreco_handle_t with the entry points as methods."""
+
+    def __init__(self, max_elems: int, max_layers: int, max_cands: int, bucket: int = 128,
+                 stochastic: bool = False, seed: int = 0, power_iters: int = 1, r_max: int = 64):
+        self._h = C.c_void_p()
+        self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max)
+        st = lib().lgreco_create(C.byref(self._h), C.byref(self.cfg), max_elems, max_layers, max_cands)
+        if st != OK:
+            raise LgrecoError(st, strerror(st))
+
+    def close(self):
+        if self._h:
+            lib().lgreco_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int, allow=()):
+        if st != OK and st not in allow:
+            text = strerror(st)
+            if st == EHIP:
+                text += " (" + lib().lgreco_last_hip_error(self._h).decode() + ")"
+            raise LgrecoError(st, text)
+        return st
+
+    def profile(self, d_grads, d_ef, layers, cands, d_q0=None, want_sizes: bool = True):
+        L, P = len(layers), len(cands)
+        errors = np.zeros((L, P), np.float64)
+        szs = np.zeros((L, P), np.int64) if want_sizes else None
+        st = lib().lgreco_profile(self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), L,
+                                  C.addressof(cands), P, _dptr(d_q0), _np(errors),
+                                  _np(szs) if want_sizes else None, _stream())
+        self._check(st)
+        return errors, szs
+
+    def solve(self, errors: np.ndarray, szs: np.ndarray, e_max: float, n_bins: int):
+        errors = np.ascontiguousarray(errors, np.float64)
+        szs = np.ascontiguousarray(szs, np.int64)
+        L, P = errors.shape
+        choice = np.zeros(L, np.int32)
+        tsize, terr = C.c_int64(), C.c_double()
+        st = lib().lgreco_solve(self._h, _np(errors), _np(szs), L, P, float(e_max), int(n_bins),
+                                _np(choice), C.byref(tsize), C.byref(terr), _stream())
+        self._check(st, allow=(EINFEASIBLE,))
+        return st, choice, tsize.value, terr.value
+
+    def compress(self, d_grads, d_ef, layers, cands, choice: np.ndarray, d_payload, offsets: np.ndarray,
+                 d_q=None):
+        choice = np.ascontiguousarray(choice, np.int32)
+        offsets = np.ascontiguousarray(offsets, np.int64)
+        st = lib().lgreco_compress(self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), len(layers),
+                                   C.addressof(cands), len(cands), _np(choice), _dptr(d_q),
+                                   _dptr(d_payload), _np(offsets), _stream())
+        self._check(st)
+
+    def set_timing(self, enabled: bool):
+        self._check(lib().lgreco_set_timing(self._h, int(enabled)))
+
+    def get_timing(self):
+        cap = 32
+        names = (C.c_char_p * cap)()
+        ms = (C.c_float * cap)()
+        n = lib().lgreco_get_timing(self._h, names, ms, cap)
+        if n < 0:
+            self._check(n)
+        return [(names[i].decode(), float(ms[i])) for i in range(min(n, cap))]

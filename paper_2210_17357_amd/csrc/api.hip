@@ -1,0 +1,531 @@
+// C ABI of liblgreco.so: handle, argument checks, host-side tables (sizes, bins, tiles,
+// payload layout) and the launch sequence of each entry point.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "internal.h"
+
+using namespace lgreco;
+
+struct lgreco_handle {
+    lgreco_config_t cfg{};
+    int64_t max_elems = 0;
+    int32_t max_layers = 0, max_cands = 0;
+    int device = 0;
+    std::string hip_error;
+
+    // layer table cache (rebuilt only when the caller's table changes)
+    std::vector<lgreco_layer_t> cached;
+    std::vector<DevLayer> hl;
+    std::vector<Tile> ht;
+    int64_t total_elems = 0;
+    bool layers_dirty = true;       // device copy of hl is stale
+
+    DevLayer* d_layers = nullptr;
+    Tile* d_tiles = nullptr;
+    int32_t max_tiles = 0;
+    double* d_partials = nullptr;   // [max_tiles x max_cands]
+    double* d_errors = nullptr;     // [max_layers x max_cands]
+    double* h_errors = nullptr;     // pinned mirror
+
+    TopkScratch topk;
+    LowrankScratch lowrank;
+
+    // solver
+    int32_t* d_bins = nullptr;
+    int64_t* d_sizes = nullptr;
+    uint8_t* d_pd = nullptr;
+    int32_t* d_choice = nullptr;
+    int64_t* d_result = nullptr;
+    int32_t* h_bins = nullptr;      // pinned
+    int64_t* h_sizes = nullptr;     // pinned
+    int32_t* h_choice = nullptr;    // pinned
+    int64_t* h_result = nullptr;    // pinned
+
+    Timing tm;
+};
+
+namespace {
+
+int hip_fail(lgreco_handle* h, hipError_t e, const char* what) {
+    if (h) h->hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return LGRECO_EHIP;
+}
+#define HIPCHK(expr)                                             \
+    do {                                                         \
+        hipError_t _e = (expr);                                  \
+        if (_e != hipSuccess) return hip_fail(h, _e, #expr);     \
+    } while (0)
+
+int64_t quant_size(int64_t n, int bits, int bucket) {
+    const int64_t full = n / bucket, rem = n % bucket;
+    int64_t s = full * ((int64_t)bucket * bits / 8 + 8);
+    if ((bucket * bits) % 8 != 0) {     // generic bucket sizes: per-bucket byte rounding
+        s = full * (((int64_t)bucket * bits + 7) / 8 + 8);
+    }
+    if (rem) s += (rem * bits + 7) / 8 + 8;
+    return s;
+}
+
+int64_t topk_k(int64_t n, double d) {
+    const double v = std::floor(d * (double)n + 0.5);
+    int64_t k = (v >= 9.0e18) ? n : (int64_t)v;
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}
+
+int check_cand(const lgreco_cand_t& c, const lgreco_layer_t* layer, int r_max) {
+    switch (c.family) {
+        case LGRECO_QUANT:
+            if (!(c.param >= 1.0 && c.param <= 8.0) || c.param != std::floor(c.param)) return LGRECO_EINVAL;
+            return LGRECO_OK;
+        case LGRECO_TOPK:
+            if (!(c.param > 0.0 && c.param <= 1.0)) return LGRECO_EINVAL;
+            return LGRECO_OK;
+        case LGRECO_LOWRANK:
+            if (!(c.param >= 1.0) || c.param != std::floor(c.param)) return LGRECO_EINVAL;
+            if (r_max > 0 && c.param > (double)r_max) return LGRECO_EINVAL;
+            if (layer && (layer->rows <= 0 || layer->cols <= 0)) return LGRECO_EINVAL;
+            return LGRECO_OK;
+        default:
+            return LGRECO_EINVAL;
+    }
+}
+
+int check_layers(const lgreco_layer_t* layers, int32_t L) {
+    if (!layers || L <= 0) return LGRECO_EINVAL;
+    std::vector<std::pair<int64_t, int64_t>> r;
+    r.reserve(L);
+    for (int l = 0; l < L; ++l) {
+        const lgreco_layer_t& a = layers[l];
+        if (a.offset < 0 || a.numel <= 0 || a.numel >= ((int64_t)1 << 31)) return LGRECO_EINVAL;
+        if (a.rows < 0 || a.cols < 0) return LGRECO_EINVAL;
+        if (a.rows > 0 && (int64_t)a.rows * a.cols != a.numel) return LGRECO_EINVAL;
+        r.emplace_back(a.offset, a.offset + a.numel);
+    }
+    std::sort(r.begin(), r.end());
+    for (int l = 1; l < L; ++l)
+        if (r[l].first < r[l - 1].second) return LGRECO_EINVAL;
+    return LGRECO_OK;
+}
+
+// Rebuild the tile table if the caller's layer table differs from the cached one.
+int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
+    if ((int)h->cached.size() == L && std::memcmp(h->cached.data(), layers, sizeof(lgreco_layer_t) * L) == 0)
+        return LGRECO_OK;
+    int st = check_layers(layers, L);
+    if (st != LGRECO_OK) return st;
+    if (L > h->max_layers) return LGRECO_ENOSPACE;
+    int64_t total = 0;
+    for (int l = 0; l < L; ++l) total += layers[l].numel;
+    if (total > h->max_elems) return LGRECO_ENOSPACE;
+
+    h->hl.assign(L, DevLayer{});
+    h->ht.clear();
+    int64_t qoff = 0;
+    for (int l = 0; l < L; ++l) {
+        const lgreco_layer_t& a = layers[l];
+        DevLayer& d = h->hl[l];
+        d.offset = a.offset;
+        d.numel = a.numel;
+        d.rows = a.rows;
+        d.cols = a.cols;
+        d.q_offset = qoff;
+        qoff += (int64_t)a.cols * h->cfg.r_max;
+        d.tile_begin = (int32_t)h->ht.size();
+        const bool aligned = (a.offset % 4) == 0;
+        int64_t pos = 0, n = a.numel;
+        auto push = [&](int64_t cnt, int fast) {
+            h->ht.push_back(Tile{pos, l, (int32_t)cnt, fast, 0});
+            pos += cnt;
+        };
+        while (n - pos >= kTile) push(kTile, aligned ? 1 : 0);
+        const int64_t rem = n - pos;
+        if (aligned) {
+            const int64_t mid = (rem / kChunk) * kChunk;
+            if (mid) push(mid, 1);
+            if (rem - mid) push(rem - mid, 0);
+        } else if (rem) {
+            push(rem, 0);
+        }
+        d.tile_end = (int32_t)h->ht.size();
+    }
+    if ((int64_t)h->ht.size() > h->max_tiles) return LGRECO_ENOSPACE;
+    h->cached.assign(layers, layers + L);
+    h->total_elems = total;
+    h->layers_dirty = true;
+    return LGRECO_OK;
+}
+
+int upload_layers(lgreco_handle* h, hipStream_t s, bool force) {
+    if (!h->layers_dirty && !force) return LGRECO_OK;
+    HIPCHK(hipMemcpyAsync(h->d_layers, h->hl.data(), sizeof(DevLayer) * h->hl.size(), hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(h->d_tiles, h->ht.data(), sizeof(Tile) * h->ht.size(), hipMemcpyHostToDevice, s));
+    // the host vectors may be rewritten by the next call: make the copy complete first
+    HIPCHK(hipStreamSynchronize(s));
+    h->layers_dirty = false;
+    return LGRECO_OK;
+}
+
+void begin_call(lgreco_handle* h, hipStream_t s) {
+    h->tm.n = 0;
+    h->tm.stream = s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lgreco_strerror(int status) {
+    switch (status) {
+        case LGRECO_OK: return "ok";
+        case LGRECO_EINVAL: return "invalid argument";
+        case LGRECO_ENOSPACE: return "problem exceeds the limits given to lgreco_create";
+        case LGRECO_EINFEASIBLE: return "no assignment fits the error budget";
+        case LGRECO_EHIP: return "HIP runtime error";
+        case LGRECO_EUNSUPPORTED: return "not supported by this build";
+        default: return "unknown status";
+    }
+}
+
+const char* lgreco_last_hip_error(const lgreco_handle_t* h) { return h ? h->hip_error.c_str() : ""; }
+
+int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max_elems, int32_t max_layers,
+                  int32_t max_cands) {
+    if (!out || !cfg || max_elems <= 0 || max_layers <= 0 || max_cands <= 0) return LGRECO_EINVAL;
+    if (max_cands > LGRECO_MAX_CANDS) return LGRECO_EINVAL;
+    if (cfg->bucket != kBucket) return LGRECO_EUNSUPPORTED;
+    if (cfg->power_iters != 1) return LGRECO_EUNSUPPORTED;
+    if (cfg->r_max < 0 || cfg->r_max > 64) return LGRECO_EUNSUPPORTED;
+    lgreco_handle* h = new (std::nothrow) lgreco_handle();
+    if (!h) return LGRECO_ENOSPACE;
+    h->cfg = *cfg;
+    h->max_elems = max_elems;
+    h->max_layers = max_layers;
+    h->max_cands = max_cands;
+    *out = h;
+    auto fail = [&](int st) {
+        lgreco_destroy(h);
+        *out = nullptr;
+        return st;
+    };
+#define HIPCHK_C(expr)                                                      \
+    do {                                                                    \
+        hipError_t _e = (expr);                                             \
+        if (_e != hipSuccess) { hip_fail(h, _e, #expr); return fail(LGRECO_EHIP); } \
+    } while (0)
+    HIPCHK_C(hipGetDevice(&h->device));
+    h->max_tiles = (int32_t)std::min<int64_t>(max_elems / kTile + 2 * (int64_t)max_layers + 2, INT32_MAX);
+    HIPCHK_C(hipMalloc(&h->d_layers, sizeof(DevLayer) * max_layers));
+    HIPCHK_C(hipMalloc(&h->d_tiles, sizeof(Tile) * h->max_tiles));
+    HIPCHK_C(hipMalloc(&h->d_partials, sizeof(double) * (size_t)h->max_tiles * max_cands));
+    HIPCHK_C(hipMalloc(&h->d_errors, sizeof(double) * (size_t)max_layers * max_cands));
+    HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
+    const size_t lp = (size_t)max_layers * max_cands;
+    HIPCHK_C(hipMalloc(&h->d_bins, sizeof(int32_t) * lp));
+    HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * lp));
+    HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 1)));
+    HIPCHK_C(hipMalloc(&h->d_choice, sizeof(int32_t) * max_layers));
+    HIPCHK_C(hipMalloc(&h->d_result, sizeof(int64_t) * 4));
+    HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * lp, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_choice, sizeof(int32_t) * max_layers, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_result, sizeof(int64_t) * 4, hipHostMallocDefault));
+    for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&h->tm.ev[i]));
+    h->tm.ready = true;
+    {
+        hipError_t e = topk_scratch_create(&h->topk, max_elems, max_layers, h->max_tiles);
+        if (e != hipSuccess) { hip_fail(h, e, "topk_scratch_create"); return fail(LGRECO_EHIP); }
+        e = lowrank_scratch_create(&h->lowrank, max_elems, max_layers, cfg->r_max);
+        if (e != hipSuccess) { hip_fail(h, e, "lowrank_scratch_create"); return fail(LGRECO_EHIP); }
+    }
+#undef HIPCHK_C
+    return LGRECO_OK;
+}
+
+int lgreco_destroy(lgreco_handle_t* h) {
+    if (!h) return LGRECO_EINVAL;
+    (void)hipFree(h->d_layers);
+    (void)hipFree(h->d_tiles);
+    (void)hipFree(h->d_partials);
+    (void)hipFree(h->d_errors);
+    (void)hipHostFree(h->h_errors);
+    (void)hipFree(h->d_bins);
+    (void)hipFree(h->d_sizes);
+    (void)hipFree(h->d_pd);
+    (void)hipFree(h->d_choice);
+    (void)hipFree(h->d_result);
+    (void)hipHostFree(h->h_bins);
+    (void)hipHostFree(h->h_sizes);
+    (void)hipHostFree(h->h_choice);
+    (void)hipHostFree(h->h_result);
+    if (h->tm.ready)
+        for (int i = 0; i < 2 * Timing::kMaxSections; ++i) (void)hipEventDestroy(h->tm.ev[i]);
+    topk_scratch_destroy(&h->topk);
+    lowrank_scratch_destroy(&h->lowrank);
+    delete h;
+    return LGRECO_OK;
+}
+
+int lgreco_set_timing(lgreco_handle_t* h, int32_t enabled) {
+    if (!h) return LGRECO_EINVAL;
+    h->tm.enabled = enabled != 0;
+    h->tm.n = 0;
+    return LGRECO_OK;
+}
+
+int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap) {
+    if (!h || cap < 0) return LGRECO_EINVAL;
+    const int n = h->tm.n;
+    for (int i = 0; i < n && i < cap; ++i) {
+        float t = 0.0f;
+        hipError_t e = hipEventSynchronize(h->tm.ev[2 * i + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, h->tm.ev[2 * i], h->tm.ev[2 * i + 1]);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
+        if (names) names[i] = h->tm.name[i];
+        if (ms) ms[i] = t;
+    }
+    return n;
+}
+
+int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                 int32_t bucket, int64_t* sizes) {
+    if (!layers || !cands || !sizes || L <= 0 || P <= 0 || bucket <= 0) return LGRECO_EINVAL;
+    for (int l = 0; l < L; ++l) {
+        if (layers[l].numel <= 0) return LGRECO_EINVAL;
+        for (int c = 0; c < P; ++c) {
+            const int st = check_cand(cands[c], &layers[l], 0);
+            if (st != LGRECO_OK) return st;
+            const int64_t n = layers[l].numel;
+            int64_t s = 0;
+            if (cands[c].family == LGRECO_QUANT) s = quant_size(n, (int)cands[c].param, bucket);
+            else if (cands[c].family == LGRECO_TOPK) s = 8 * topk_k(n, cands[c].param);
+            else s = 4 * ((int64_t)layers[l].rows + layers[l].cols) * (int64_t)cands[c].param;
+            sizes[(size_t)l * P + c] = s;
+        }
+    }
+    return LGRECO_OK;
+}
+
+int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand, double* e_max) {
+    if (!errors || !e_max || L <= 0 || P <= 0 || default_cand < 0 || default_cand >= P) return LGRECO_EINVAL;
+    double s = 0.0;
+    for (int l = 0; l < L; ++l) s += errors[(size_t)l * P + default_cand];
+    *e_max = s;
+    return LGRECO_OK;
+}
+
+int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
+                   int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, double* errors,
+                   int64_t* sizes, void* stream) {
+    if (!h || !d_grads || !layers || !cands || !errors || L <= 0 || P <= 0) return LGRECO_EINVAL;
+    if (P > h->max_cands) return LGRECO_ENOSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    begin_call(h, s);
+    int st = prepare_layers(h, layers, L);
+    if (st != LGRECO_OK) return st;
+
+    QuantParams qp{};
+    int tk_col[kMaxTopk];
+    double tk_density[kMaxTopk];
+    int ntk = 0;
+    int lr_col[LGRECO_MAX_CANDS], lr_rank[LGRECO_MAX_CANDS], nlr = 0;
+    uint32_t tile_cols = 0;            // columns produced as per-tile partials
+    for (int c = 0; c < P; ++c) {
+        st = check_cand(cands[c], nullptr, h->cfg.r_max);
+        if (st != LGRECO_OK) return st;
+        if (cands[c].family == LGRECO_QUANT) {
+            if (qp.nq >= kMaxQuant) return LGRECO_ENOSPACE;
+            qp.bits[qp.nq] = (int)cands[c].param;
+            qp.col[qp.nq++] = c;
+            tile_cols |= 1u << c;
+        } else if (cands[c].family == LGRECO_TOPK) {
+            if (ntk >= kMaxTopk) return LGRECO_ENOSPACE;
+            tk_density[ntk] = cands[c].param;
+            tk_col[ntk++] = c;
+            tile_cols |= 1u << c;
+        } else {
+            lr_rank[nlr] = (int)cands[c].param;
+            lr_col[nlr++] = c;
+        }
+    }
+    if (nlr) {
+        if (!d_q0) return LGRECO_EINVAL;
+        for (int l = 0; l < L; ++l)
+            if (layers[l].rows <= 0 || layers[l].cols <= 0) return LGRECO_EINVAL;
+    }
+    if (sizes) {
+        st = lgreco_sizes(layers, L, cands, P, h->cfg.bucket, sizes);
+        if (st != LGRECO_OK) return st;
+    }
+    st = upload_layers(h, s, false);
+    if (st != LGRECO_OK) return st;
+
+    const int n_tiles = (int)h->ht.size();
+    const bool ptr_aligned = ((uintptr_t)d_grads % 16 == 0) && (!d_ef || (uintptr_t)d_ef % 16 == 0);
+    if (!ptr_aligned) return LGRECO_EINVAL;     // device allocations are always 256-byte aligned
+
+    if (ntk) {
+        Section sec(&h->tm, "topk_zero");
+        HIPCHK(topk_profile_begin(&h->topk, L, s));
+    }
+    if (qp.nq || ntk) {
+        qp.g = d_grads;
+        qp.e = d_ef;
+        qp.layers = h->d_layers;
+        qp.tiles = h->d_tiles;
+        qp.partials = h->d_partials;
+        qp.stride = P;
+        qp.stochastic = h->cfg.stochastic;
+        qp.seed_lo = (uint32_t)h->cfg.seed;
+        qp.seed_hi = (uint32_t)(h->cfg.seed >> 32);
+        qp.hist = ntk ? h->topk.d_hist : nullptr;
+        Section sec(&h->tm, ntk ? "quant_profile_hist" : "quant_profile");
+        HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
+    }
+    if (ntk) {
+        HIPCHK(topk_profile_finish(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
+                                   tk_density, tk_col, ntk, h->d_partials, P, h->d_errors, &h->tm, s));
+    }
+    if (tile_cols) {
+        uint32_t qmask = 0;
+        for (int i = 0; i < qp.nq; ++i) qmask |= 1u << qp.col[i];
+        Section sec(&h->tm, "reduce_partials");
+        HIPCHK(launch_reduce_partials(h->d_partials, P, ntk ? tile_cols : qmask, h->d_layers, L, h->d_errors, s));
+    }
+    if (nlr) {
+        HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
+                               lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));
+    }
+    HIPCHK(hipMemcpyAsync(h->h_errors, h->d_errors, sizeof(double) * (size_t)L * P, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
+    return LGRECO_OK;
+}
+
+int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes, int32_t L, int32_t P,
+                 double e_max, int32_t n_bins, int32_t* choice, int64_t* total_size, double* total_error,
+                 void* stream) {
+    if (!h || !errors || !sizes || !choice || L <= 0 || P <= 0) return LGRECO_EINVAL;
+    if (n_bins < 1 || n_bins > LGRECO_MAX_BINS || !(e_max == e_max)) return LGRECO_EINVAL;
+    if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    begin_call(h, s);
+    const size_t lp = (size_t)L * P;
+    const double D = (double)n_bins;
+    for (size_t i = 0; i < lp; ++i) {
+        if (sizes[i] < 0 || sizes[i] >= ((int64_t)1 << 45)) return LGRECO_EINVAL;
+        double err = errors[i];
+        if (!(err == err)) return LGRECO_EINVAL;
+        if (err < 0.0) err = 0.0;
+        int32_t b;
+        if (e_max > 0.0) {
+            const double prod = err * D;
+            const double q = std::floor(prod / e_max);
+            b = (q <= D) ? (int32_t)q : -1;
+        } else {
+            b = (err <= 0.0) ? 0 : -1;
+        }
+        h->h_bins[i] = b;
+        h->h_sizes[i] = sizes[i];
+    }
+    HIPCHK(hipMemcpyAsync(h->d_bins, h->h_bins, sizeof(int32_t) * lp, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(h->d_sizes, h->h_sizes, sizeof(int64_t) * lp, hipMemcpyHostToDevice, s));
+    DpParams dp{h->d_bins, h->d_sizes, h->d_pd, h->d_choice, h->d_result, L, P, n_bins};
+    {
+        Section sec(&h->tm, "dp_solve");
+        HIPCHK(launch_dp(dp, s));
+    }
+    HIPCHK(hipMemcpyAsync(h->h_choice, h->d_choice, sizeof(int32_t) * L, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipMemcpyAsync(h->h_result, h->d_result, sizeof(int64_t) * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if (h->h_result[0] == 1) {
+        for (int l = 0; l < L; ++l) {           // report each layer's minimum-error candidate
+            int best = 0;
+            for (int c = 1; c < P; ++c)
+                if (errors[(size_t)l * P + c] < errors[(size_t)l * P + best]) best = c;
+            choice[l] = best;
+        }
+        return LGRECO_EINFEASIBLE;
+    }
+    if (h->h_result[0] != 0) {
+        h->hip_error = "dp back-trace inconsistent";
+        return LGRECO_EHIP;
+    }
+    double terr = 0.0;
+    for (int l = 0; l < L; ++l) {
+        choice[l] = h->h_choice[l];
+        terr += errors[(size_t)l * P + choice[l]];
+    }
+    if (total_size) *total_size = h->h_result[1];
+    if (total_error) *total_error = terr;
+    return LGRECO_OK;
+}
+
+int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                          const int32_t* choice, int32_t bucket, int64_t* offsets) {
+    if (!layers || !cands || !choice || !offsets || L <= 0 || P <= 0 || bucket <= 0) return LGRECO_EINVAL;
+    int64_t off = 0;
+    for (int l = 0; l < L; ++l) {
+        if (choice[l] < 0 || choice[l] >= P) return LGRECO_EINVAL;
+        int64_t sz = 0;
+        const int st = lgreco_sizes(&layers[l], 1, &cands[choice[l]], 1, bucket, &sz);
+        if (st != LGRECO_OK) return st;
+        offsets[l] = off;
+        off = (off + sz + 15) / 16 * 16;
+    }
+    offsets[L] = off;
+    return LGRECO_OK;
+}
+
+int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const lgreco_layer_t* layers, int32_t L,
+                    const lgreco_cand_t* cands, int32_t P, const int32_t* choice, float* d_q, uint8_t* d_payload,
+                    const int64_t* offsets, void* stream) {
+    if (!h || !d_grads || !d_ef || !layers || !cands || !choice || !d_payload || !offsets || L <= 0 || P <= 0)
+        return LGRECO_EINVAL;
+    if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    begin_call(h, s);
+    int st = prepare_layers(h, layers, L);
+    if (st != LGRECO_OK) return st;
+    bool any[3] = {false, false, false};
+    for (int l = 0; l < L; ++l) {
+        if (choice[l] < 0 || choice[l] >= P) return LGRECO_EINVAL;
+        const lgreco_cand_t& c = cands[choice[l]];
+        st = check_cand(c, &layers[l], h->cfg.r_max);
+        if (st != LGRECO_OK) return st;
+        if (offsets[l] < 0 || offsets[l] % 16) return LGRECO_EINVAL;
+        DevLayer& d = h->hl[l];
+        d.family = c.family;
+        d.payload = offsets[l];
+        d.iparam = (c.family == LGRECO_TOPK) ? (int32_t)topk_k(layers[l].numel, c.param) : (int32_t)c.param;
+        any[c.family] = true;
+    }
+    if (any[LGRECO_LOWRANK] && !d_q) return LGRECO_EINVAL;
+    st = upload_layers(h, s, true);
+    if (st != LGRECO_OK) return st;
+    const int n_tiles = (int)h->ht.size();
+    if (any[LGRECO_QUANT]) {
+        Section sec(&h->tm, "quant_compress");
+        HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
+                                     h->cfg.stochastic != 0, h->cfg.seed, s));
+    }
+    if (any[LGRECO_TOPK]) {
+        HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, h->ht.data(), L,
+                             n_tiles, d_payload, &h->tm, s));
+    }
+    if (any[LGRECO_LOWRANK]) {
+        HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,
+                                d_payload, &h->tm, s));
+    }
+    HIPCHK(hipStreamSynchronize(s));
+    return LGRECO_OK;
+}
+
+}  // extern "C"

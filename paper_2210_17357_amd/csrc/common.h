@@ -1,0 +1,158 @@
+// Internal declarations shared by the HIP translation units of liblgreco.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lgreco.h"
+
+namespace lgreco {
+
+constexpr int kTile = 8192;        // elements per streaming tile (64 buckets of 128)
+constexpr int kBucket = 128;       // quantization bucket (elements)
+constexpr int kChunk = 512;        // elements one wavefront handles per step (4 buckets)
+constexpr int kThreads = 256;      // workgroup size of the streaming kernels (4 wavefronts)
+constexpr int kMaxQuant = 8;       // quantization candidates profiled in one pass
+constexpr int kMaxTopk = 8;        // top-k candidates profiled in one pass
+constexpr int kHistBins = 4096;    // coarse magnitude histogram: top 12 bits of |x|'s pattern
+constexpr int kHistShift = 19;
+
+// One tile = up to kTile consecutive elements of ONE layer, starting at a multiple of
+// kBucket from the layer start, so buckets never straddle tiles or layers.
+struct Tile {
+    int64_t pos;      // first element, relative to the layer start
+    int32_t layer;
+    int32_t count;    // elements in this tile
+    int32_t fast;     // 1: 16-byte aligned and count % kChunk == 0 (vector path)
+    int32_t pad;
+};
+
+struct DevLayer {
+    int64_t offset;       // elements, into the flat gradient buffer
+    int64_t numel;
+    int64_t payload;      // byte offset of the layer's payload (compress only)
+    int64_t q_offset;     // element offset of the layer's warm-start block (low rank)
+    int32_t rows, cols;
+    int32_t tile_begin;   // first tile of this layer
+    int32_t tile_end;
+    int32_t family;       // compress: family of the chosen candidate
+    int32_t iparam;       // compress: bits / k / rank of the chosen candidate
+    int32_t pad0, pad1;
+};
+
+// ------------------------------------------------------------------ cross-lane helpers
+// DPP controls of the gfx9 family.
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// All 16 lanes of a DPP row end up with the row's minimum / maximum / sum.
+__device__ __forceinline__ float row16_min(float v) {
+    v = fminf(v, dpp_f32<kDppQuadXor1>(v));
+    v = fminf(v, dpp_f32<kDppQuadXor2>(v));
+    v = fminf(v, dpp_f32<kDppRowHalfMirror>(v));
+    v = fminf(v, dpp_f32<kDppRowMirror>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_f32<kDppQuadXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppQuadXor2>(v));
+    v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+    v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_f32<kDppQuadXor1>(v);
+    v += dpp_f32<kDppQuadXor2>(v);
+    v += dpp_f32<kDppRowHalfMirror>(v);
+    v += dpp_f32<kDppRowMirror>(v);
+    return v;
+}
+// Value of lane (row base + LANE) for every lane of the row.
+template <int LANE>
+__device__ __forceinline__ float row16_bcast(float v) {
+    return dpp_f32<0x150 + LANE>(v);   // row_newbcast:LANE
+}
+// All 64 lanes end up with the wavefront's sum (fixed order -> reproducible).
+__device__ __forceinline__ float wave_sum(float v) {
+    v = row16_sum(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    for (int o = 1; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+    v = row16_min(v);
+    v = fminf(v, __shfl_xor(v, 16, 64));
+    v = fminf(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+    v = row16_max(v);
+    v = fmaxf(v, __shfl_xor(v, 16, 64));
+    v = fmaxf(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------ Philox4x32-10
+// Counter-based generator of Salmon et al. (SC'11): ten rounds of two 32x32->64 multiplies
+// and a Weyl key schedule.  Written from the published round function.
+struct Philox4 {
+    uint32_t w[4];
+};
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Philox4{{c0, c1, c2, c3}};
+}
+__device__ __forceinline__ uint32_t philox_word(const Philox4& r, int i) {
+    return i == 0 ? r.w[0] : i == 1 ? r.w[1] : i == 2 ? r.w[2] : r.w[3];
+}
+// 24 high bits of a word as a float in [0, 1).
+__device__ __forceinline__ float u01(uint32_t w) { return (float)(w >> 8) * 0x1p-24f; }
+
+// ------------------------------------------------------------------ launch parameters
+struct QuantParams {
+    const float* g;
+    const float* e;            // may be null
+    const DevLayer* layers;
+    const Tile* tiles;
+    double* partials;          // [n_tiles x stride]
+    int32_t stride;            // doubles per tile in partials
+    int32_t nq;                // quantization candidates
+    int32_t bits[kMaxQuant];
+    int32_t col[kMaxQuant];    // column of each candidate in partials
+    int32_t stochastic;
+    uint32_t seed_lo, seed_hi;
+    // fused coarse histogram (top-k candidates present)
+    uint32_t* hist;            // [L x kHistBins] or null
+    int32_t energy_col;        // column receiving sum x^2 of the tile, or -1
+};
+
+}  // namespace lgreco

@@ -1,0 +1,99 @@
+// Interfaces between the translation units of liblgreco.so (host side).
+#pragma once
+
+#include "common.h"
+
+namespace lgreco {
+
+// Optional per-kernel timing: each Section brackets the work enqueued during its lifetime with
+// two HIP events on the call's stream.
+struct Timing {
+    static constexpr int kMaxSections = 32;
+    bool enabled = false;
+    bool ready = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[2 * kMaxSections]{};
+    const char* name[kMaxSections]{};
+    int n = 0;
+};
+struct Section {
+    Timing* t;
+    int idx = -1;
+    Section(Timing* tt, const char* name) : t(tt) {
+        if (t && t->enabled && t->ready && t->n < Timing::kMaxSections) {
+            idx = t->n++;
+            t->name[idx] = name;
+            (void)hipEventRecord(t->ev[2 * idx], t->stream);
+        }
+    }
+    ~Section() {
+        if (idx >= 0) (void)hipEventRecord(t->ev[2 * idx + 1], t->stream);
+    }
+    Section(const Section&) = delete;
+    Section& operator=(const Section&) = delete;
+};
+
+// ---- quant.hip
+hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s);
+hipError_t launch_reduce_partials(const double* partials, int stride, uint32_t colmask,
+                                  const DevLayer* layers, int n_layers, double* errors, hipStream_t s);
+hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
+                                 int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
+                                 hipStream_t s);
+
+// ---- dp.hip
+struct DpParams {
+    const int32_t* bins;    // [L x P], -1 = unusable
+    const int64_t* sizes;   // [L x P]
+    uint8_t* pd;            // [L x (D+1)]
+    int32_t* choice;        // [L]
+    int64_t* result;        // [0] status (0 ok, 1 infeasible), [1] total size, [2] final bin sum
+    int32_t L, P, D;
+};
+hipError_t launch_dp(const DpParams& p, hipStream_t s);
+
+// ---- topk.hip
+struct TopkScratch {
+    uint32_t* d_hist = nullptr;       // [max_layers x kHistBins] coarse magnitude histogram
+    void* d_sel = nullptr;            // per (layer, candidate) selection records
+    uint32_t* d_cand = nullptr;       // candidate bit patterns of the threshold bins [max_elems]
+    uint32_t* d_cursor = nullptr;     // allocation cursors / counters
+    uint32_t* d_tilecnt = nullptr;    // per-tile kept counts (compress)
+    int64_t max_elems = 0;
+    int max_layers = 0, max_tiles = 0;
+};
+hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers, int max_tiles);
+void topk_scratch_destroy(TopkScratch* t);
+// zero the histograms before the fused histogram pass
+hipError_t topk_profile_begin(TopkScratch* t, int L, hipStream_t s);
+// after the histogram pass: thresholds, dropped energy per candidate -> partials columns
+hipError_t topk_profile_finish(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                               const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles,
+                               const double* density, const int* col, int ntk, double* d_partials, int stride,
+                               double* d_errors, Timing* tm, hipStream_t s);
+hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                         const DevLayer* h_layers, const Tile* d_tiles, const Tile* h_tiles, int L, int n_tiles,
+                         uint8_t* payload, Timing* tm, hipStream_t s);
+
+// ---- lowrank.hip
+struct LowrankScratch {
+    float* d_p = nullptr;        // P / Phat of all layers, [sum rows x r_max]
+    float* d_q = nullptr;        // Q of all layers, [sum cols x r_max]
+    double* d_gram = nullptr;    // per layer [r_max x r_max]
+    double* d_norm = nullptr;    // per layer ||M||^2 and column norms
+    void* d_work = nullptr;      // split-K partial sums
+    void* d_table = nullptr;     // per-launch tile tables
+    int64_t max_elems = 0;
+    int max_layers = 0, r_max = 0;
+    size_t work_bytes = 0, table_bytes = 0;
+};
+hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max);
+void lowrank_scratch_destroy(LowrankScratch* t);
+hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                           const DevLayer* h_layers, int L, const float* q0, int r_max, const int* rank,
+                           const int* col, int nlr, double* d_errors, int stride, Timing* tm, hipStream_t s);
+hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                            const DevLayer* h_layers, int L, float* q, int r_max, uint8_t* payload, Timing* tm,
+                            hipStream_t s);
+
+}  // namespace lgreco

@@ -1,0 +1,71 @@
+"""GPU parity, solver: bit-exact choice against the oracle DP on identical tables, brute force on
+tiny tables, infeasible budgets, the configs' table sizes."""
+import numpy as np
+import pytest
+
+from oracle import solver
+
+pytestmark = pytest.mark.gpu
+
+
+def _handle(L, P):
+    from paper_2210_17357_amd import binding as B
+    return B.Handle(1024, L, P)
+
+
+def _compare(h, errors, sizes, e_max, n_bins):
+    from paper_2210_17357_amd import binding as B
+    st, choice, tsize, terr = h.solve(errors, sizes, e_max, n_bins)
+    ref_choice, ref_size, ref_err = solver.solve(errors, sizes, e_max, n_bins)
+    if ref_choice is None:
+        assert st == B.EINFEASIBLE
+        assert np.array_equal(choice, np.argmin(errors, axis=1))
+        return
+    assert st == B.OK
+    assert np.array_equal(choice, ref_choice)
+    assert tsize == ref_size and terr == pytest.approx(ref_err, rel=1e-15)
+
+
+def test_random_small_tables_with_ties_and_unusable_candidates():
+    rng = np.random.default_rng(0)
+    h = _handle(8, 8)
+    for trial in range(200):
+        L, P, D = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 40))
+        errors = rng.integers(0, 12, (L, P)).astype(np.float64) * 0.25
+        if trial % 4 == 0:
+            errors[:, 0] = 0.0
+        sizes = rng.integers(0, 5, (L, P)).astype(np.int64)
+        e_max = float(rng.integers(0, 20)) * 0.5
+        _compare(h, errors, sizes, e_max, D)
+    h.close()
+
+
+@pytest.mark.parametrize("L,P,D", [(62, 7, 1000), (161, 6, 1000), (97, 5, 2000), (292, 13, 4000),
+                                   (40, 32, 10000), (30, 9, 16384), (3, 4, 1023), (3, 4, 1024)])
+def test_config_sized_tables(L, P, D):
+    rng = np.random.default_rng(L * 1000 + P)
+    h = _handle(L, P)
+    base = 10.0 ** rng.uniform(-6, -1, (L, 1))
+    errors = base * np.sort(rng.random((L, P)), axis=1)[:, ::-1] * np.logspace(0, -3, P)
+    sizes = (rng.integers(1, 50, (L, 1)) * np.arange(1, P + 1) * 100).astype(np.int64)
+    e_max = solver.e_max_uniform(errors, P // 2)
+    _compare(h, errors, sizes, e_max, D)
+    _compare(h, errors, sizes, e_max * 0.3, D)
+    # large sizes (beyond 32 bits) and many exact ties
+    _compare(h, errors, (sizes * 0 + (1 << 33)).astype(np.int64), e_max, D)
+    h.close()
+
+
+def test_invalid_arguments():
+    from paper_2210_17357_amd import binding as B
+    h = _handle(4, 4)
+    errors = np.ones((2, 2))
+    sizes = np.ones((2, 2), np.int64)
+    for bad_bins in (0, -1, B.lib() and 16385):
+        with pytest.raises(B.LgrecoError):
+            h.solve(errors, sizes, 1.0, bad_bins)
+    with pytest.raises(B.LgrecoError):
+        h.solve(np.ones((5, 2)), np.ones((5, 2), np.int64), 1.0, 10)       # more layers than created for
+    with pytest.raises(B.LgrecoError):
+        h.solve(errors, -sizes, 1.0, 10)
+    h.close()
