@@ -51,6 +51,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("liblgreco.so is not built: run `python -m paper_2210_17357_amd.build` "
                                "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime; load it first so that this library binds to the
+        # same runtime instance (two runtimes in one process do not share the device).
+        import torch  # noqa: F401
         l = C.CDLL(LIB_PATH)
         vp, i32, i64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_double
         l.lgreco_create.argtypes = [C.POINTER(vp), C.POINTER(Config), i64, i32, i32]

@@ -37,17 +37,22 @@ struct lgreco_handle {
     LowrankScratch lowrank;
 
     // solver
-    int32_t* d_bins = nullptr;
-    int64_t* d_sizes = nullptr;
+    DpEntry* d_entries = nullptr;
+    int32_t* d_count = nullptr;
     uint8_t* d_pd = nullptr;
     int32_t* d_choice = nullptr;
     int64_t* d_result = nullptr;
-    int32_t* h_bins = nullptr;      // pinned
-    int64_t* h_sizes = nullptr;     // pinned
+    int32_t* h_bins = nullptr;      // pinned: original index of every swept layer
+    DpEntry* h_entries = nullptr;   // pinned
+    int32_t* h_count = nullptr;     // pinned
     int32_t* h_choice = nullptr;    // pinned
     int64_t* h_result = nullptr;    // pinned
 
     Timing tm;
+    // sub-sections measured inside a kernel (device clock), appended after the event sections
+    const char* sub_name[4]{};
+    float sub_ms[4]{};
+    int n_sub = 0;
 };
 
 namespace {
@@ -176,6 +181,7 @@ int upload_layers(lgreco_handle* h, hipStream_t s, bool force) {
 void begin_call(lgreco_handle* h, hipStream_t s) {
     h->tm.n = 0;
     h->tm.stream = s;
+    h->n_sub = 0;
 }
 
 }  // namespace
@@ -228,15 +234,17 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_errors, sizeof(double) * (size_t)max_layers * max_cands));
     HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
     const size_t lp = (size_t)max_layers * max_cands;
-    HIPCHK_C(hipMalloc(&h->d_bins, sizeof(int32_t) * lp));
-    HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * lp));
+    HIPCHK_C(hipMalloc(&h->d_entries, sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS));
+    HIPCHK_C(hipMalloc(&h->d_count, sizeof(int32_t) * max_layers));
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 1)));
     HIPCHK_C(hipMalloc(&h->d_choice, sizeof(int32_t) * max_layers));
-    HIPCHK_C(hipMalloc(&h->d_result, sizeof(int64_t) * 4));
+    HIPCHK_C(hipMalloc(&h->d_result, sizeof(int64_t) * 8));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * lp, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_entries, sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS,
+                           hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_count, sizeof(int32_t) * max_layers, hipHostMallocDefault));
     HIPCHK_C(hipHostMalloc(&h->h_choice, sizeof(int32_t) * max_layers, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_result, sizeof(int64_t) * 4, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_result, sizeof(int64_t) * 8, hipHostMallocDefault));
     for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&h->tm.ev[i]));
     h->tm.ready = true;
     {
@@ -256,13 +264,14 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipFree(h->d_partials);
     (void)hipFree(h->d_errors);
     (void)hipHostFree(h->h_errors);
-    (void)hipFree(h->d_bins);
-    (void)hipFree(h->d_sizes);
+    (void)hipFree(h->d_entries);
+    (void)hipFree(h->d_count);
     (void)hipFree(h->d_pd);
     (void)hipFree(h->d_choice);
     (void)hipFree(h->d_result);
     (void)hipHostFree(h->h_bins);
-    (void)hipHostFree(h->h_sizes);
+    (void)hipHostFree(h->h_entries);
+    (void)hipHostFree(h->h_count);
     (void)hipHostFree(h->h_choice);
     (void)hipHostFree(h->h_result);
     if (h->tm.ready)
@@ -291,7 +300,11 @@ int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t
         if (names) names[i] = h->tm.name[i];
         if (ms) ms[i] = t;
     }
-    return n;
+    for (int j = 0; j < h->n_sub && n + j < cap; ++j) {
+        if (names) names[n + j] = h->sub_name[j];
+        if (ms) ms[n + j] = h->sub_ms[j];
+    }
+    return n + h->n_sub;
 }
 
 int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
@@ -419,33 +432,55 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     begin_call(h, s);
     const size_t lp = (size_t)L * P;
     const double D = (double)n_bins;
-    for (size_t i = 0; i < lp; ++i) {
-        if (sizes[i] < 0 || sizes[i] >= ((int64_t)1 << 45)) return LGRECO_EINVAL;
-        double err = errors[i];
-        if (!(err == err)) return LGRECO_EINVAL;
-        if (err < 0.0) err = 0.0;
-        int32_t b;
-        if (e_max > 0.0) {
-            const double prod = err * D;
-            const double q = std::floor(prod / e_max);
-            b = (q <= D) ? (int32_t)q : -1;
-        } else {
-            b = (err <= 0.0) ? 0 : -1;
+    int64_t worst = 0;                  // sum over layers of the largest usable size
+    int max_bin = 0;
+    int n_sweep = 0;                    // layers the kernel sweeps; h_bins[l] = their original index
+    bool dead_layer = false;            // a layer without any usable candidate
+    for (int l = 0; l < L; ++l) {
+        DpEntry* en = h->h_entries + (size_t)n_sweep * LGRECO_MAX_CANDS;
+        int cnt = 0;
+        int64_t lmax = 0;
+        for (int c = 0; c < P; ++c) {
+            const size_t i = (size_t)l * P + c;
+            if (sizes[i] < 0 || sizes[i] >= ((int64_t)1 << 45)) return LGRECO_EINVAL;
+            double err = errors[i];
+            if (!(err == err)) return LGRECO_EINVAL;
+            if (err < 0.0) err = 0.0;
+            int32_t b;
+            if (e_max > 0.0) {
+                const double prod = err * D;
+                const double q = std::floor(prod / e_max);
+                b = (q <= D) ? (int32_t)q : -1;
+            } else {
+                b = (err <= 0.0) ? 0 : -1;
+            }
+            if (b < 0) continue;
+            lmax = std::max(lmax, sizes[i]);
+            max_bin = std::max(max_bin, (int)b);
+            // equal bins: only the smallest size (lowest index among equals) can ever win
+            int same = -1;
+            for (int k = 0; k < cnt; ++k)
+                if (en[k].bin == b) same = k;
+            if (same < 0) {
+                en[cnt++] = DpEntry{b, c, sizes[i]};
+            } else if (sizes[i] < en[same].size) {
+                // the group's representative moves to candidate c: keep the list in index order
+                for (int k = same; k + 1 < cnt; ++k) en[k] = en[k + 1];
+                en[cnt - 1] = DpEntry{b, c, sizes[i]};
+            }
         }
-        h->h_bins[i] = b;
-        h->h_sizes[i] = sizes[i];
+        worst += lmax;
+        if (cnt == 0) {
+            dead_layer = true;
+        } else if (cnt == 1 && en[0].bin == 0) {
+            choice[l] = en[0].cand;             // adds a constant to every cell: fixed here
+        } else {
+            h->h_count[n_sweep] = cnt;
+            h->h_bins[n_sweep] = l;
+            ++n_sweep;
+        }
     }
-    HIPCHK(hipMemcpyAsync(h->d_bins, h->h_bins, sizeof(int32_t) * lp, hipMemcpyHostToDevice, s));
-    HIPCHK(hipMemcpyAsync(h->d_sizes, h->h_sizes, sizeof(int64_t) * lp, hipMemcpyHostToDevice, s));
-    DpParams dp{h->d_bins, h->d_sizes, h->d_pd, h->d_choice, h->d_result, L, P, n_bins};
-    {
-        Section sec(&h->tm, "dp_solve");
-        HIPCHK(launch_dp(dp, s));
-    }
-    HIPCHK(hipMemcpyAsync(h->h_choice, h->d_choice, sizeof(int32_t) * L, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipMemcpyAsync(h->h_result, h->d_result, sizeof(int64_t) * 4, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipStreamSynchronize(s));
-    if (h->h_result[0] == 1) {
+    auto infeasible = [&]() {
         for (int l = 0; l < L; ++l) {           // report each layer's minimum-error candidate
             int best = 0;
             for (int c = 1; c < P; ++c)
@@ -453,17 +488,42 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
             choice[l] = best;
         }
         return LGRECO_EINFEASIBLE;
-    }
-    if (h->h_result[0] != 0) {
-        h->hip_error = "dp back-trace inconsistent";
-        return LGRECO_EHIP;
+    };
+    if (dead_layer) return infeasible();
+    if (n_sweep > 0) {
+        const bool narrow = worst < ((int64_t)1 << 30);
+        HIPCHK(hipMemcpyAsync(h->d_entries, h->h_entries, sizeof(DpEntry) * (size_t)n_sweep * LGRECO_MAX_CANDS,
+                              hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(h->d_count, h->h_count, sizeof(int32_t) * n_sweep, hipMemcpyHostToDevice, s));
+        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0};
+        {
+            Section sec(&h->tm, "dp_solve");
+            HIPCHK(launch_dp(dp, narrow, max_bin, s));
+        }
+        HIPCHK(hipMemcpyAsync(h->h_choice, h->d_choice, sizeof(int32_t) * n_sweep, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipMemcpyAsync(h->h_result, h->d_result, sizeof(int64_t) * 8, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        if (h->tm.enabled) {                        // 100 MHz constant-rate device counter
+            h->sub_name[0] = "dp_solve.sweep";
+            h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
+            h->sub_name[1] = "dp_solve.backtrace";
+            h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
+            h->n_sub = 2;
+        }
+        if (h->h_result[0] == 1) return infeasible();
+        if (h->h_result[0] != 0) {
+            h->hip_error = "dp back-trace inconsistent";
+            return LGRECO_EHIP;
+        }
+        for (int i = 0; i < n_sweep; ++i) choice[h->h_bins[i]] = h->h_choice[i];
     }
     double terr = 0.0;
+    int64_t tsize = 0;
     for (int l = 0; l < L; ++l) {
-        choice[l] = h->h_choice[l];
         terr += errors[(size_t)l * P + choice[l]];
+        tsize += sizes[(size_t)l * P + choice[l]];
     }
-    if (total_size) *total_size = h->h_result[1];
+    if (total_size) *total_size = tsize;
     if (total_error) *total_error = terr;
     return LGRECO_OK;
 }

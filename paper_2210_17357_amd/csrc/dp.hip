@@ -6,70 +6,123 @@
 // the new row in registers while the previous row sits in LDS.  Candidates are visited in index
 // order with a strict '<' (lowest index wins ties); the back-trace starts from the lowest e among
 // the minima of the last row.  PD (arg-min per cell) goes to global memory, one byte per cell.
+//
+// The host hands over, per layer, the list of usable candidates with equal bins merged (for one
+// bin only the smallest size can win, the lowest index among equals; merging keeps the result
+// identical, tie-breaks included).  A layer whose list is a single entry with bin 0 adds a
+// constant to the whole row: the host fixes its choice and leaves it out, so L here counts the
+// swept layers only.  Entry lists are staged through LDS 32 layers at a time.  Costs are 32-bit when the sum of every layer's largest size stays below 2^30, else
+// 64-bit; "infinity" is 2^30 (2^62), so inf + size never overflows and never beats a real value.
+#include <cstdlib>
+
 #include "internal.h"
 
 namespace lgreco {
 
-constexpr int kDpThreads = 1024;
-constexpr int kDpMaxK = (LGRECO_MAX_BINS + 1 + kDpThreads - 1) / kDpThreads;   // 17
-constexpr int64_t kDpInf = (int64_t)1 << 62;
 
-template <int KMAX>
+template <typename T> struct DpInf;
+template <> struct DpInf<uint32_t> { static constexpr uint32_t v = 1u << 30; };
+template <> struct DpInf<int64_t> { static constexpr int64_t v = (int64_t)1 << 62; };
+
+__device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ int64_t readlane_i64(int64_t v, int lane) {
+    const uint32_t lo = readlane_u32((uint32_t)v, lane);
+    const uint32_t hi = readlane_u32((uint32_t)((uint64_t)v >> 32), lane);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+template <typename T> __device__ __forceinline__ T readlane_t(T v, int lane);
+template <> __device__ __forceinline__ uint32_t readlane_t<uint32_t>(uint32_t v, int lane) {
+    return readlane_u32(v, lane);
+}
+template <> __device__ __forceinline__ int64_t readlane_t<int64_t>(int64_t v, int lane) {
+    return readlane_i64(v, lane);
+}
+
+constexpr int kDpStage = 32;    // swept layers whose entry lists are staged in LDS at a time
+
+template <typename T, int KMAX, bool PADDED, int kDpThreads>
 __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
-    extern __shared__ int64_t row[];               // [D+1] previous row
+    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*1024-1 (cells above D stay infinite).
+    // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
+    extern __shared__ unsigned char dp_smem[];
+    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
+    __shared__ DpEntry s_entries[kDpStage][LGRECO_MAX_CANDS];
+    __shared__ int32_t s_count[kDpStage];
     __shared__ int64_t s_val[kDpThreads / 64];
     __shared__ int32_t s_idx[kDpThreads / 64];
-    const int tid = threadIdx.x;
-    const int D = p.D, P = p.P;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int D = p.D;
     const int64_t width = (int64_t)D + 1;
+    constexpr T kInf = DpInf<T>::v;
 
-    for (int e = tid; e <= D; e += kDpThreads) row[e] = (e == 0) ? 0 : kDpInf;
-    __syncthreads();
+    const uint64_t t_begin = wall_clock64();
+    for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
 
-    for (int l = 0; l < p.L; ++l) {
-        const int32_t* __restrict__ lb = p.bins + (size_t)l * P;
-        const int64_t* __restrict__ ls = p.sizes + (size_t)l * P;
-        int64_t nv[KMAX];
-        int32_t na[KMAX];
+    for (int l0 = 0; l0 < p.L; l0 += kDpStage) {
+        const int nl = min(kDpStage, p.L - l0);
+        __syncthreads();                              // previous stage fully consumed, row written
+        for (int i = tid; i < nl * LGRECO_MAX_CANDS; i += kDpThreads)
+            (&s_entries[0][0])[i] = p.entries[(size_t)l0 * LGRECO_MAX_CANDS + i];
+        if (tid < nl) s_count[tid] = p.count[l0 + tid];
+        __syncthreads();
+        for (int ll = 0; ll < nl; ++ll) {
+            const int cn = s_count[ll];
+            int32_t mybin = 0;
+            T mysize = 0;
+            if (lane < cn) {
+                mybin = s_entries[ll][lane].bin;
+                mysize = (T)s_entries[ll][lane].size;
+            }
+            T nv[KMAX];
+            int32_t na[KMAX];
 #pragma unroll
-        for (int k = 0; k < KMAX; ++k) {
-            const int e = tid + k * kDpThreads;
-            int64_t best = kDpInf;
-            int32_t arg = 255;
-            if (e <= D) {
-                for (int c = 0; c < P; ++c) {
-                    const int32_t b = lb[c];
-                    if (b >= 0 && b <= e) {
-                        const int64_t prev = row[e - b];
-                        const int64_t t = prev + ls[c];
-                        if (prev < kDpInf && t < best) {
-                            best = t;
-                            arg = c;
-                        }
+            for (int k = 0; k < KMAX; ++k) { nv[k] = kInf; na[k] = 255; }
+            for (int c = 0; c < cn; ++c) {
+                const int32_t b = (int32_t)readlane_u32((uint32_t)mybin, c);
+                const T sz = readlane_t<T>(mysize, c);
+                if (PADDED) {
+                    const T* __restrict__ src = row + (tid - b);
+#pragma unroll
+                    for (int k = 0; k < KMAX; ++k) {
+                        const T t = src[k * kDpThreads] + sz;
+                        const bool lt = t < nv[k];
+                        nv[k] = lt ? t : nv[k];
+                        na[k] = lt ? c : na[k];
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < KMAX; ++k) {
+                        const int idx = tid + k * kDpThreads - b;
+                        T t = row[max(idx, 0)] + sz;
+                        t = idx >= 0 ? t : kInf;
+                        const bool lt = t < nv[k];
+                        nv[k] = lt ? t : nv[k];
+                        na[k] = lt ? c : na[k];
                     }
                 }
             }
-            nv[k] = best;
-            na[k] = arg;
-        }
-        __syncthreads();
-        uint8_t* __restrict__ pdrow = p.pd + (size_t)l * width;
+            __syncthreads();
+            uint8_t* __restrict__ pdrow = p.pd + (size_t)(l0 + ll) * width;
 #pragma unroll
-        for (int k = 0; k < KMAX; ++k) {
-            const int e = tid + k * kDpThreads;
-            if (e <= D) {
-                row[e] = nv[k];
-                pdrow[e] = (uint8_t)na[k];
+            for (int k = 0; k < KMAX; ++k) {
+                const int e = tid + k * kDpThreads;
+                if (e <= D) {
+                    row[e] = nv[k];                   // never above kInf: only a smaller t replaces it
+                    pdrow[e] = (uint8_t)na[k];        // index into the layer's entry list
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
+    __syncthreads();
 
     // arg-min of the last row, lowest e among equal minima
-    int64_t bv = kDpInf;
+    int64_t bv = (int64_t)kInf;
     int32_t be = 0x7FFFFFFF;
     for (int e = tid; e <= D; e += kDpThreads) {
-        const int64_t v = row[e];
+        const int64_t v = (int64_t)row[e];
         if (v < bv) { bv = v; be = e; }              // e ascending per thread -> keeps the lowest
     }
     for (int o = 1; o < 64; o <<= 1) {
@@ -77,47 +130,75 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         const int32_t oe = __shfl_xor(be, o, 64);
         if (ov < bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
     }
-    if ((tid & 63) == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
+    if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
     __syncthreads();
     if (tid == 0) {
+        const uint64_t t_sweep = wall_clock64();
         for (int w = 1; w < kDpThreads / 64; ++w)
             if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
-        if (bv >= kDpInf) {
+        if (bv >= (int64_t)kInf) {
             p.result[0] = 1;
             p.result[1] = 0;
             p.result[2] = 0;
         } else {
             int e = be;
             for (int l = p.L - 1; l >= 0; --l) {
-                const int c = p.pd[(size_t)l * width + e];
-                p.choice[l] = c;
-                e -= p.bins[(size_t)l * P + c];
+                const int k = p.pd[(size_t)l * width + e];
+                const DpEntry en = p.entries[(size_t)l * LGRECO_MAX_CANDS + k];
+                p.choice[l] = en.cand;
+                e -= en.bin;
             }
             p.result[0] = (e == 0) ? 0 : 2;          // 2 would be an internal inconsistency
             p.result[1] = bv;
             p.result[2] = be;
         }
+        // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace
+        p.result[3] = (int64_t)(t_sweep - t_begin);
+        p.result[4] = (int64_t)(wall_clock64() - t_sweep);
     }
 }
 
-hipError_t launch_dp(const DpParams& p, hipStream_t s) {
-    const size_t lds = (size_t)(p.D + 1) * sizeof(int64_t);
-    const int nk = (p.D + 1 + kDpThreads - 1) / kDpThreads;
+constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static
+
+template <typename T, int THREADS>
+static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
+    constexpr int kMaxK = (LGRECO_MAX_BINS + 1 + THREADS - 1) / THREADS;
+    const int nk = (p.D + 1 + THREADS - 1) / THREADS;
+    int kmax = 1;
+    while (kmax < nk) kmax *= 2;
+    if (kmax > kMaxK) kmax = kMaxK;
+    const int pad = (max_bin + 63) / 64 * 64;
+    const bool padded = ((size_t)pad + (size_t)kmax * THREADS) * sizeof(T) <= kDpLdsBudget;
+    p.pad = padded ? pad : 0;
+    const size_t lds = ((size_t)p.pad + (size_t)kmax * THREADS) * sizeof(T);
     hipError_t err = hipSuccess;
-#define LGRECO_DP(K)                                                                               \
+#define LGRECO_DP2(K, PD)                                                                          \
     do {                                                                                           \
-        err = hipFuncSetAttribute((const void*)dp_kernel<K>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                  (int)lds);                                                       \
+        err = hipFuncSetAttribute((const void*)dp_kernel<T, K, PD, THREADS>,                       \
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
         if (err != hipSuccess) return err;                                                         \
-        hipLaunchKernelGGL((dp_kernel<K>), dim3(1), dim3(kDpThreads), lds, s, p);                  \
+        hipLaunchKernelGGL((dp_kernel<T, K, PD, THREADS>), dim3(1), dim3(THREADS), lds, s, p);     \
     } while (0)
-    if (nk <= 1) LGRECO_DP(1);
-    else if (nk <= 2) LGRECO_DP(2);
-    else if (nk <= 4) LGRECO_DP(4);
-    else if (nk <= 8) LGRECO_DP(8);
-    else LGRECO_DP(kDpMaxK);
+#define LGRECO_DP(K) do { if (padded) LGRECO_DP2(K, true); else LGRECO_DP2(K, false); } while (0)
+    if (kmax == 1) LGRECO_DP(1);
+    else if (kmax == 2) LGRECO_DP(2);
+    else if (kmax == 4) LGRECO_DP(4);
+    else if (kmax == 8) LGRECO_DP(8);
+    else if (kmax == 16) LGRECO_DP(16);
+    else LGRECO_DP(kMaxK);
 #undef LGRECO_DP
+#undef LGRECO_DP2
     return hipGetLastError();
+}
+
+hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s) {
+    static const int threads = [] {
+        const char* e = getenv("LGRECO_DP_THREADS");
+        return e ? atoi(e) : 1024;
+    }();
+    if (threads == 512)
+        return narrow ? launch_dp_t<uint32_t, 512>(p, max_bin, s) : launch_dp_t<int64_t, 512>(p, max_bin, s);
+    return narrow ? launch_dp_t<uint32_t, 1024>(p, max_bin, s) : launch_dp_t<int64_t, 1024>(p, max_bin, s);
 }
 
 }  // namespace lgreco

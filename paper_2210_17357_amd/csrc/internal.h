@@ -42,15 +42,23 @@ hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layer
                                  hipStream_t s);
 
 // ---- dp.hip
-struct DpParams {
-    const int32_t* bins;    // [L x P], -1 = unusable
-    const int64_t* sizes;   // [L x P]
-    uint8_t* pd;            // [L x (D+1)]
-    int32_t* choice;        // [L]
-    int64_t* result;        // [0] status (0 ok, 1 infeasible), [1] total size, [2] final bin sum
-    int32_t L, P, D;
+struct DpEntry {            // one usable candidate of a layer (equal bins merged by the host)
+    int32_t bin;
+    int32_t cand;
+    int64_t size;
 };
-hipError_t launch_dp(const DpParams& p, hipStream_t s);
+struct DpParams {
+    const DpEntry* entries;   // [L x LGRECO_MAX_CANDS] swept layers only, in candidate order
+    const int32_t* count;     // [L] entries per swept layer
+    uint8_t* pd;              // [L x (D+1)] entry index per cell
+    int32_t* choice;          // [L] candidate index per swept layer
+    int64_t* result;          // [0] status (0 ok, 1 infeasible), [1] swept size, [2] final bin sum
+    int32_t L, D;
+    int32_t pad;              // set by launch_dp: cells of infinity in front of the LDS row
+};
+// narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
+// max_bin: largest bin in entries
+hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s);
 
 // ---- topk.hip
 struct TopkScratch {
