@@ -385,10 +385,14 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     if (!ptr_aligned) return LGRECO_EINVAL;     // device allocations are always 256-byte aligned
 
     if (ntk) {
+        std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
+        for (int l = 0; l < L; ++l)
+            for (int j = 0; j < ntk; ++j)
+                ks[(size_t)l * kMaxTopk + j] = (uint32_t)topk_k(layers[l].numel, tk_density[j]);
         Section sec(&h->tm, "topk_zero");
-        HIPCHK(topk_profile_begin(&h->topk, L, s));
+        HIPCHK(topk_begin(&h->topk, h->hl.data(), L, ks.data(), s));
     }
-    if (qp.nq || ntk) {
+    if (qp.nq) {
         qp.g = d_grads;
         qp.e = d_ef;
         qp.layers = h->d_layers;
@@ -401,17 +405,18 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         qp.hist = ntk ? h->topk.d_hist : nullptr;
         Section sec(&h->tm, ntk ? "quant_profile_hist" : "quant_profile");
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
+    } else if (ntk) {
+        Section sec(&h->tm, "topk_hist");
+        HIPCHK(topk_hist(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, s));
     }
-    if (ntk) {
-        HIPCHK(topk_profile_finish(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
-                                   tk_density, tk_col, ntk, h->d_partials, P, h->d_errors, &h->tm, s));
-    }
+    if (ntk)
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, L, n_tiles, ntk, tk_col,
+                           h->d_partials, P, &h->tm, s));
     if (tile_cols) {
-        uint32_t qmask = 0;
-        for (int i = 0; i < qp.nq; ++i) qmask |= 1u << qp.col[i];
         Section sec(&h->tm, "reduce_partials");
-        HIPCHK(launch_reduce_partials(h->d_partials, P, ntk ? tile_cols : qmask, h->d_layers, L, h->d_errors, s));
+        HIPCHK(launch_reduce_partials(h->d_partials, P, tile_cols, h->d_layers, L, h->d_errors, s));
     }
+    if (ntk) HIPCHK(topk_finalize(&h->topk, L, ntk, tk_col, h->d_errors, P, &h->tm, s));
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
                                lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));
@@ -577,8 +582,8 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
                                      h->cfg.stochastic != 0, h->cfg.seed, s));
     }
     if (any[LGRECO_TOPK]) {
-        HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, h->ht.data(), L,
-                             n_tiles, d_payload, &h->tm, s));
+        HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
+                             d_payload, &h->tm, s));
     }
     if (any[LGRECO_LOWRANK]) {
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,

@@ -1,6 +1,9 @@
 // Interfaces between the translation units of liblgreco.so (host side).
 #pragma once
 
+#include <algorithm>
+#include <vector>
+
 #include "common.h"
 
 namespace lgreco {
@@ -63,25 +66,34 @@ hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s)
 // ---- topk.hip
 struct TopkScratch {
     uint32_t* d_hist = nullptr;       // [max_layers x kHistBins] coarse magnitude histogram
-    void* d_sel = nullptr;            // per (layer, candidate) selection records
-    uint32_t* d_cand = nullptr;       // candidate bit patterns of the threshold bins [max_elems]
-    uint32_t* d_cursor = nullptr;     // allocation cursors / counters
-    uint32_t* d_tilecnt = nullptr;    // per-tile kept counts (compress)
+    void* d_tl = nullptr;             // per-layer selection records
+    uint32_t* d_cand = nullptr;       // bit patterns of the threshold bins' elements [max_elems]
+    uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
+    int64_t* d_cand_base = nullptr;   // [max_layers] first candidate slot of every layer
+    void* d_tilecnt = nullptr;        // per tile (above, equal) counts (compress)
+    void* d_tilebase = nullptr;       // per tile exclusive prefix of those counts
+    uint32_t* h_k = nullptr;          // pinned
+    int64_t* h_cand_base = nullptr;   // pinned
     int64_t max_elems = 0;
     int max_layers = 0, max_tiles = 0;
 };
 hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers, int max_tiles);
 void topk_scratch_destroy(TopkScratch* t);
-// zero the histograms before the fused histogram pass
-hipError_t topk_profile_begin(TopkScratch* t, int L, hipStream_t s);
-// after the histogram pass: thresholds, dropped energy per candidate -> partials columns
-hipError_t topk_profile_finish(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                               const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles,
-                               const double* density, const int* col, int ntk, double* d_partials, int stride,
-                               double* d_errors, Timing* tm, hipStream_t s);
+// upload k per (layer, candidate) and clear the histograms
+hipError_t topk_begin(TopkScratch* t, const DevLayer* h_layers, int L, const uint32_t* ks, hipStream_t s);
+// stand-alone coarse histogram (the quantization profile kernel can produce it instead)
+hipError_t topk_hist(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                     const Tile* d_tiles, int n_tiles, hipStream_t s);
+// threshold bins, then pass B: energy below each threshold bin -> partials, candidate lists
+hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
+                       int stride, Timing* tm, hipStream_t s);
+// exact thresholds; adds the candidate lists' dropped energy to errors (if not null)
+hipError_t topk_finalize(TopkScratch* t, int L, int ntk, const int* col, double* d_errors, int stride,
+                         Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
-                         const DevLayer* h_layers, const Tile* d_tiles, const Tile* h_tiles, int L, int n_tiles,
-                         uint8_t* payload, Timing* tm, hipStream_t s);
+                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
+                         Timing* tm, hipStream_t s);
 
 // ---- lowrank.hip
 struct LowrankScratch {

@@ -1,19 +1,707 @@
-// Top-K (stub, replaced below in the build order): radix-histogram threshold search.
+// Layer-wise Top-K: radix-histogram threshold search, dropped-energy profile for several
+// densities at once, and threshold-select compaction.  gfx950 / wave64.
+//
+// Magnitudes are compared as the fp32 bit pattern with the sign cleared (31 bits).  Per layer:
+//   1. coarse histogram of the top 12 bits (exponent + 4 mantissa bits), LDS per tile then
+//      global integer atomics (fused into the quantization profile kernel when both families
+//      are profiled);
+//   2. scan: for every requested k the coarse bin holding the k-th largest magnitude, and how
+//      many entries must still be taken inside that bin;
+//   3. pass B over the data: energy of everything below the lowest threshold bin in registers;
+//      the few elements at or above it are staged in LDS and handled densely: energy below
+//      each threshold bin, and the bit patterns of the threshold bins' elements appended to
+//      per-bin candidate lists (one global atomic per tile and list);
+//   4. finalize: exact radix select (10 + 9 remaining bits) inside each candidate list gives the
+//      exact k-th magnitude, the number of equal magnitudes to keep, and the energy of the
+//      list's dropped part in exact integer arithmetic (entries of one list share the
+//      exponent, so sum of squared 24-bit significands is an integer): results do not depend
+//      on the order the atomics appended the candidates in.
+// Compression then counts kept entries per tile, scans the tile counts, and writes values and
+// indices in ascending index order (equal magnitudes: lowest indices first).
 #include "internal.h"
 
 namespace lgreco {
 
-hipError_t topk_scratch_create(TopkScratch*, int64_t, int, int) { return hipSuccess; }
-void topk_scratch_destroy(TopkScratch*) {}
-hipError_t topk_profile_begin(TopkScratch*, int, hipStream_t) { return hipErrorNotSupported; }
-hipError_t topk_profile_finish(TopkScratch*, const float*, const float*, const DevLayer*, const DevLayer*,
-                               const Tile*, int, int, const double*, const int*, int, double*, int, double*,
-                               Timing*, hipStream_t) {
-    return hipErrorNotSupported;
+struct TopkList {
+    uint32_t bin, count, offset, cursor;
+};
+struct TopkSel {
+    uint32_t k, tbin, need, list;   // need: entries to take from the threshold bin (1..count)
+    uint32_t thr, ties_keep;        // exact threshold pattern; equal entries kept
+    uint32_t pad0, pad1;
+};
+struct TopkLayer {
+    int64_t cand_base;              // first slot of this layer's region in the candidate buffer
+    uint32_t nlists, min_tbin;
+    TopkList lists[kMaxTopk];
+    TopkSel sel[kMaxTopk];
+};
+
+// ------------------------------------------------------------------------ block helpers
+// Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
+// hist lives in LDS, nbins <= 16 * 256.  All 256 threads call; result broadcast through res[2].
+__device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scan,
+                                   uint32_t* res) {
+    const int tid = threadIdx.x;
+    const int per = (nbins + 255) / 256;
+    const int lo = tid * per, hi = min(lo + per, nbins);
+    uint32_t s = 0;
+    for (int b = lo; b < hi; ++b) s += hist[b];
+    // inclusive suffix scan over threads: scan[t] = sum of s over threads >= t
+    scan[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        const uint32_t v = (tid + o < 256) ? scan[tid + o] : 0;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    uint32_t running = (tid + 1 < 256) ? scan[tid + 1] : 0;
+    for (int b = hi - 1; b >= lo; --b) {
+        const uint32_t c = hist[b];
+        if (running < need && running + c >= need) {
+            res[0] = (uint32_t)b;
+            res[1] = running;
+        }
+        running += c;
+    }
+    __syncthreads();
 }
-hipError_t topk_compress(TopkScratch*, const float*, float*, const DevLayer*, const DevLayer*, const Tile*,
-                         const Tile*, int, int, uint8_t*, Timing*, hipStream_t) {
-    return hipErrorNotSupported;
+
+// Exclusive scan of one uint32 per thread over the 256-thread block; returns the prefix and the
+// block total through *total.  tmp: 4 words of LDS.
+__device__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t n = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += n;
+    }
+    __syncthreads();
+    if (lane == 63) tmp[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < wave) base += tmp[w];
+        tot += tmp[w];
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+__device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+// ------------------------------------------------------------------------ kernels
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// Coarse histogram of the active layers (ks[layer * kMaxTopk] != 0).
+__global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __restrict__ g,
+                                                              const float* __restrict__ e,
+                                                              const DevLayer* __restrict__ layers,
+                                                              const Tile* __restrict__ tiles,
+                                                              const uint32_t* __restrict__ ks,
+                                                              uint32_t* __restrict__ hist) {
+    __shared__ uint32_t s_hist[kHistBins];
+    const Tile t = tiles[blockIdx.x];
+    if (ks[(size_t)t.layer * kMaxTopk] == 0) return;
+    const DevLayer L = layers[t.layer];
+    const float* gp = g + L.offset + t.pos;
+    const float* ep = e ? e + L.offset + t.pos : nullptr;
+    for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
+    __syncthreads();
+    if (t.fast) {
+        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) {
+            float4 a = reinterpret_cast<const float4*>(gp)[v];
+            if (ep) {
+                const float4 b = reinterpret_cast<const float4*>(ep)[v];
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            atomicAdd(&s_hist[mag_bits(a.x) >> kHistShift], 1u);
+            atomicAdd(&s_hist[mag_bits(a.y) >> kHistShift], 1u);
+            atomicAdd(&s_hist[mag_bits(a.z) >> kHistShift], 1u);
+            atomicAdd(&s_hist[mag_bits(a.w) >> kHistShift], 1u);
+        }
+    } else {
+        for (int i = threadIdx.x; i < t.count; i += kThreads) {
+            const float x = ep ? gp[i] + ep[i] : gp[i];
+            atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* gh = hist + (size_t)t.layer * kHistBins;
+    for (int b = threadIdx.x; b < kHistBins; b += kThreads) {
+        const uint32_t c = s_hist[b];
+        if (c) atomicAdd(&gh[b], c);
+    }
+}
+
+// One workgroup per layer: threshold bin and in-bin rank for every requested k; candidate lists.
+__global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restrict__ hist,
+                                                        const uint32_t* __restrict__ ks, int ntk,
+                                                        const int64_t* __restrict__ cand_base,
+                                                        TopkLayer* __restrict__ tl) {
+    __shared__ uint32_t s_hist[kHistBins];
+    __shared__ uint32_t s_scan[256];
+    __shared__ uint32_t s_res[2];
+    const int l = blockIdx.x;
+    TopkLayer& T = tl[l];
+    if (ks[(size_t)l * kMaxTopk] == 0) {
+        if (threadIdx.x == 0) { T.nlists = 0; T.min_tbin = 0; for (int j = 0; j < kMaxTopk; ++j) T.sel[j].k = 0; }
+        return;
+    }
+    for (int b = threadIdx.x; b < kHistBins; b += 256) s_hist[b] = hist[(size_t)l * kHistBins + b];
+    __syncthreads();
+    for (int j = 0; j < ntk; ++j) {
+        const uint32_t k = ks[(size_t)l * kMaxTopk + j];
+        block_kth_from_top(s_hist, kHistBins, k, s_scan, s_res);
+        if (threadIdx.x == 0) {
+            TopkSel& S = T.sel[j];
+            S.k = k;
+            S.tbin = s_res[0];
+            S.need = k - s_res[1];
+            S.thr = 0;
+            S.ties_keep = 0;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        uint32_t nl = 0, off = 0, mn = 0xFFFFFFFFu;
+        for (int j = 0; j < ntk; ++j) {
+            TopkSel& S = T.sel[j];
+            uint32_t u = nl;
+            for (uint32_t q = 0; q < nl; ++q)
+                if (T.lists[q].bin == S.tbin) u = q;
+            if (u == nl) {
+                T.lists[nl] = TopkList{S.tbin, s_hist[S.tbin], off, 0u};
+                off += s_hist[S.tbin];
+                ++nl;
+            }
+            S.list = u;
+            mn = min(mn, S.tbin);
+        }
+        for (int j = ntk; j < kMaxTopk; ++j) T.sel[j].k = 0;
+        T.nlists = nl;
+        T.min_tbin = mn;
+        T.cand_base = cand_base[l];
+    }
+}
+
+struct PassBParams {
+    const float* g;
+    const float* e;
+    const DevLayer* layers;
+    const Tile* tiles;
+    TopkLayer* tl;
+    uint32_t* cand;
+    double* partials;       // may be null (compress: no energies)
+    int32_t stride;
+    int32_t ntk;
+    int32_t col[kMaxTopk];
+};
+
+__global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
+    __shared__ uint32_t s_stage[kTile];
+    __shared__ uint32_t s_wn[kThreads / 64];
+    __shared__ uint32_t s_cnt[kMaxTopk], s_cnt2[kMaxTopk], s_gbase[kMaxTopk];
+    __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
+    __shared__ double s_red[kThreads / 64][kMaxTopk + 1];
+
+    const Tile t = p.tiles[blockIdx.x];
+    TopkLayer& T = p.tl[t.layer];
+    if (T.sel[0].k == 0) return;                         // layer not active (uniform)
+    const DevLayer L = p.layers[t.layer];
+    const float* gp = p.g + L.offset + t.pos;
+    const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t min_tbin = T.min_tbin;
+    const uint32_t nlists = T.nlists;
+    if (tid < kMaxTopk) {
+        s_cnt[tid] = 0;
+        s_cnt2[tid] = 0;
+        s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
+        s_tbin[tid] = tid < p.ntk ? T.sel[tid].tbin : 0u;
+    }
+    __syncthreads();
+
+    // Elements at or above the lowest threshold bin are staged per wavefront at positions given
+    // by a ballot prefix count, so the staging order (and with it every floating-point sum
+    // below) is the same on every run.
+    float base = 0.0f;
+    uint32_t wcur = 0;                                   // uniform within the wavefront
+    uint32_t* const wstage = s_stage + wave * (kTile / (kThreads / 64));
+    auto consume = [&](float x, bool valid) {
+        const uint32_t pat = mag_bits(x);
+        const bool rare = valid && (pat >> kHistShift) >= min_tbin;
+        const unsigned long long m = __ballot(rare);
+        if (rare) {
+            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            wstage[wcur + below] = pat;
+        } else if (valid) {
+            base = __builtin_fmaf(x, x, base);
+        }
+        wcur += (uint32_t)__popcll(m);
+    };
+    if (t.fast) {
+        for (int v = tid; v < t.count / 4; v += kThreads) {          // count % 512 == 0: uniform trips
+            float4 a = reinterpret_cast<const float4*>(gp)[v];
+            if (ep) {
+                const float4 b = reinterpret_cast<const float4*>(ep)[v];
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            consume(a.x, true); consume(a.y, true); consume(a.z, true); consume(a.w, true);
+        }
+    } else {
+        for (int i0 = 0; i0 < t.count; i0 += kThreads) {
+            const int i = i0 + tid;
+            const bool valid = i < t.count;
+            float x = 0.0f;
+            if (valid) x = ep ? gp[i] + ep[i] : gp[i];
+            consume(x, valid);
+        }
+    }
+    if (lane == 0) s_wn[wave] = wcur;
+    __syncthreads();
+
+    // dense handling of the staged elements (key >= lowest threshold bin)
+    float extra[kMaxTopk];
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j) extra[j] = 0.0f;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        const uint32_t* const ws = s_stage + w * (kTile / (kThreads / 64));
+        for (uint32_t i = tid; i < s_wn[w]; i += kThreads) {
+            const uint32_t pat = ws[i];
+            const uint32_t key = pat >> kHistShift;
+            const float xf = __uint_as_float(pat);
+            const float x2 = xf * xf;
+#pragma unroll
+            for (int j = 0; j < kMaxTopk; ++j)
+                if (j < p.ntk && key < s_tbin[j]) extra[j] += x2;
+            for (uint32_t u = 0; u < nlists; ++u)
+                if (key == s_bin[u]) atomicAdd(&s_cnt[u], 1u);
+        }
+    }
+    __syncthreads();
+    if (tid < (int)nlists && s_cnt[tid])
+        s_gbase[tid] = atomicAdd(&T.lists[tid].cursor, s_cnt[tid]);
+    __syncthreads();
+    uint32_t* const cand = p.cand + T.cand_base;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        const uint32_t* const ws = s_stage + w * (kTile / (kThreads / 64));
+        for (uint32_t i = tid; i < s_wn[w]; i += kThreads) {
+            const uint32_t pat = ws[i];
+            const uint32_t key = pat >> kHistShift;
+            for (uint32_t u = 0; u < nlists; ++u)
+                if (key == s_bin[u]) {
+                    const uint32_t r = atomicAdd(&s_cnt2[u], 1u);
+                    cand[T.lists[u].offset + s_gbase[u] + r] = pat;
+                }
+        }
+    }
+
+    if (p.partials) {
+        const float b = wave_sum(base);
+        if (lane == 0) s_red[wave][kMaxTopk] = (double)b;
+#pragma unroll
+        for (int j = 0; j < kMaxTopk; ++j) {
+            if (j < p.ntk) {
+                const float s = wave_sum(extra[j]);
+                if (lane == 0) s_red[wave][j] = (double)s;
+            }
+        }
+        __syncthreads();
+        if (tid < p.ntk) {
+            double s = 0.0;
+            for (int w = 0; w < kThreads / 64; ++w) s += s_red[w][kMaxTopk] + s_red[w][tid];
+            p.partials[(size_t)blockIdx.x * p.stride + p.col[tid]] = s;
+        }
+    }
+}
+
+struct FinalizeParams {
+    TopkLayer* tl;
+    const uint32_t* cand;
+    double* errors;          // may be null (compress)
+    int32_t stride;
+    int32_t ntk;
+    int32_t col[kMaxTopk];
+};
+
+// One workgroup per (layer, candidate list): exact selection inside the list.
+__global__ __launch_bounds__(256) void topk_finalize_kernel(FinalizeParams p) {
+    __shared__ uint32_t s_hist[1024];
+    __shared__ uint32_t s_scan[256];
+    __shared__ uint32_t s_res[2];
+    __shared__ unsigned long long s_lo, s_hi;
+    const int l = blockIdx.x / kMaxTopk;
+    const uint32_t u = blockIdx.x % kMaxTopk;
+    TopkLayer& T = p.tl[l];
+    if (u >= T.nlists) return;
+    const TopkList list = T.lists[u];
+    const uint32_t* __restrict__ items = p.cand + T.cand_base + list.offset;
+    const uint32_t n = list.count;
+    const int tid = threadIdx.x;
+    for (int j = 0; j < p.ntk; ++j) {
+        const TopkSel S = T.sel[j];
+        if (S.k == 0 || S.list != u) continue;           // uniform across the block
+        // level A: bits 18..9 of the pattern
+        for (int b = tid; b < 1024; b += 256) s_hist[b] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n; i += 256) atomicAdd(&s_hist[(items[i] >> 9) & 1023u], 1u);
+        __syncthreads();
+        block_kth_from_top(s_hist, 1024, S.need, s_scan, s_res);
+        const uint32_t bin_a = s_res[0];
+        const uint32_t need_a = S.need - s_res[1];
+        __syncthreads();
+        // level B: bits 8..0 among the entries of bin_a
+        for (int b = tid; b < 512; b += 256) s_hist[b] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n; i += 256) {
+            const uint32_t pat = items[i];
+            if (((pat >> 9) & 1023u) == bin_a) atomicAdd(&s_hist[pat & 511u], 1u);
+        }
+        __syncthreads();
+        block_kth_from_top(s_hist, 512, need_a, s_scan, s_res);
+        const uint32_t bin_b = s_res[0];
+        const uint32_t ties_keep = need_a - s_res[1];
+        const uint32_t count_eq = s_hist[bin_b];
+        const uint32_t thr = (list.bin << kHistShift) | (bin_a << 9) | bin_b;
+        __syncthreads();
+        if (p.errors) {
+            // energy of the list's dropped part: entries below thr and the surplus equal entries.
+            // Entries of one list share the exponent field, so with m the 24-bit significand
+            // x^2 = m^2 * 2^(2 (max(E,1) - 150)) and the sum of m^2 is an exact integer.
+            if (tid == 0) { s_lo = 0; s_hi = 0; }
+            __syncthreads();
+            const uint32_t ex = thr >> 23;
+            const uint32_t implicit = ex ? 0x800000u : 0u;
+            unsigned long long lo = 0, hi = 0;
+            for (uint32_t i = tid; i < n; i += 256) {
+                const uint32_t pat = items[i];
+                if (pat < thr) {
+                    const unsigned long long m = (pat & 0x7FFFFFu) | implicit;
+                    const unsigned long long sq = m * m;
+                    lo += sq & 0xFFFFFFFFull;
+                    hi += sq >> 32;
+                }
+            }
+            if (tid == 0) {
+                const unsigned long long m = (thr & 0x7FFFFFu) | implicit;
+                const unsigned long long sq = m * m;
+                const unsigned long long dropped_eq = count_eq - ties_keep;
+                lo += (sq & 0xFFFFFFFFull) * dropped_eq;
+                hi += (sq >> 32) * dropped_eq;
+            }
+            atomicAdd(&s_lo, lo);
+            atomicAdd(&s_hi, hi);
+            __syncthreads();
+            if (tid == 0) {
+                const int sh = 2 * ((int)(ex ? ex : 1u) - 150);
+                const double v = ((double)s_hi * 4294967296.0 + (double)s_lo);
+                p.errors[(size_t)l * p.stride + p.col[j]] += ldexp(v, sh);
+            }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            T.sel[j].thr = thr;
+            T.sel[j].ties_keep = ties_keep;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- compression kernels
+// per tile: entries above the threshold, entries equal to it
+__global__ __launch_bounds__(kThreads) void topk_count_kernel(const float* __restrict__ g,
+                                                               const float* __restrict__ e,
+                                                               const DevLayer* __restrict__ layers,
+                                                               const Tile* __restrict__ tiles,
+                                                               const TopkLayer* __restrict__ tl,
+                                                               uint2* __restrict__ tilecnt) {
+    __shared__ uint32_t s_gt[kThreads / 64], s_eq[kThreads / 64];
+    const Tile t = tiles[blockIdx.x];
+    const DevLayer L = layers[t.layer];
+    if (L.family != LGRECO_TOPK) return;
+    const uint32_t thr = tl[t.layer].sel[0].thr;
+    const float* gp = g + L.offset + t.pos;
+    const float* ep = e + L.offset + t.pos;
+    uint32_t gt = 0, eq = 0;
+    auto consume = [&](float x) {
+        const uint32_t pat = mag_bits(x);
+        gt += pat > thr;
+        eq += pat == thr;
+    };
+    if (t.fast) {
+        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) {
+            const float4 a = reinterpret_cast<const float4*>(gp)[v];
+            const float4 b = reinterpret_cast<const float4*>(ep)[v];
+            consume(a.x + b.x); consume(a.y + b.y); consume(a.z + b.z); consume(a.w + b.w);
+        }
+    } else {
+        for (int i = threadIdx.x; i < t.count; i += kThreads) consume(gp[i] + ep[i]);
+    }
+    for (int o = 1; o < 64; o <<= 1) {
+        gt += __shfl_xor(gt, o, 64);
+        eq += __shfl_xor(eq, o, 64);
+    }
+    if ((threadIdx.x & 63) == 0) { s_gt[threadIdx.x >> 6] = gt; s_eq[threadIdx.x >> 6] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int w = 0; w < kThreads / 64; ++w) { a += s_gt[w]; b += s_eq[w]; }
+        tilecnt[blockIdx.x] = make_uint2(a, b);
+    }
+}
+
+// per layer: exclusive prefix of the tile counts
+__global__ __launch_bounds__(256) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
+                                                            const uint2* __restrict__ tilecnt,
+                                                            uint2* __restrict__ tilebase) {
+    __shared__ uint32_t s_tmp[kThreads / 64];
+    const DevLayer L = layers[blockIdx.x];
+    if (L.family != LGRECO_TOPK) return;
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int t0 = L.tile_begin; t0 < L.tile_end; t0 += 256) {
+        const int t = t0 + threadIdx.x;
+        const uint2 c = t < L.tile_end ? tilecnt[t] : make_uint2(0, 0);
+        uint32_t tot_gt, tot_eq;
+        const uint32_t pg = block_excl_scan(c.x, s_tmp, &tot_gt);
+        const uint32_t pe = block_excl_scan(c.y, s_tmp, &tot_eq);
+        if (t < L.tile_end) tilebase[t] = make_uint2(run_gt + pg, run_eq + pe);
+        run_gt += tot_gt;
+        run_eq += tot_eq;
+    }
+}
+
+// per tile: kept values and indices in ascending index order; error feedback
+__global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __restrict__ g, float* __restrict__ e,
+                                                               const DevLayer* __restrict__ layers,
+                                                               const Tile* __restrict__ tiles,
+                                                               const TopkLayer* __restrict__ tl,
+                                                               const uint2* __restrict__ tilecnt,
+                                                               const uint2* __restrict__ tilebase,
+                                                               uint8_t* __restrict__ payload) {
+    __shared__ uint32_t s_tmp[kThreads / 64];
+    const Tile t = tiles[blockIdx.x];
+    const DevLayer L = layers[t.layer];
+    if (L.family != LGRECO_TOPK) return;
+    const TopkSel S = tl[t.layer].sel[0];
+    const uint32_t thr = S.thr, ties_keep = S.ties_keep, k = S.k;
+    const uint2 cnt = tilecnt[blockIdx.x];
+    const uint2 before = tilebase[blockIdx.x];
+    const float* gp = g + L.offset + t.pos;
+    float* ep = e + L.offset + t.pos;
+    float* const values = reinterpret_cast<float*>(payload + L.payload);
+    uint32_t* const indices = reinterpret_cast<uint32_t*>(payload + L.payload) + k;
+    // equal entries: global rank r (in index order) is kept iff r < ties_keep
+    const bool eq_all = before.y + cnt.y <= ties_keep;       // every equal entry of this tile kept
+    const bool eq_none = before.y >= ties_keep;              // none kept
+    uint32_t out = before.x + min(before.y, ties_keep);      // kept entries before this tile
+    uint32_t eq_seen = before.y;
+    for (int s0 = 0; s0 < t.count; s0 += 4 * kThreads) {
+        const int i0 = s0 + 4 * threadIdx.x;
+        float x[4];
+        bool ok[4];
+        if (t.fast && i0 + 3 < t.count) {
+            const float4 a = *reinterpret_cast<const float4*>(gp + i0);
+            const float4 b = *reinterpret_cast<const float4*>(ep + i0);
+            x[0] = a.x + b.x; x[1] = a.y + b.y; x[2] = a.z + b.z; x[3] = a.w + b.w;
+            ok[0] = ok[1] = ok[2] = ok[3] = true;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                ok[q] = i0 + q < t.count;
+                x[q] = ok[q] ? gp[i0 + q] + ep[i0 + q] : 0.0f;
+            }
+        }
+        bool gt[4], eq[4], keep[4];
+        uint32_t neq = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t pat = mag_bits(x[q]);
+            gt[q] = ok[q] && pat > thr;
+            eq[q] = ok[q] && pat == thr;
+            neq += eq[q];
+        }
+        uint32_t eq_rank = 0;
+        if (!eq_all && !eq_none) {                            // the tie boundary is inside this tile
+            uint32_t tot;
+            eq_rank = eq_seen + block_excl_scan(neq, s_tmp, &tot);
+            eq_seen += tot;
+        }
+        uint32_t nkeep = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bool ke = false;
+            if (eq[q]) {
+                ke = eq_all ? true : eq_none ? false : (eq_rank < ties_keep);
+                ++eq_rank;
+            }
+            keep[q] = gt[q] || ke;
+            nkeep += keep[q];
+        }
+        uint32_t tot;
+        uint32_t pos = out + block_excl_scan(nkeep, s_tmp, &tot);
+        out += tot;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (keep[q]) {
+                values[pos] = x[q];
+                indices[pos] = (uint32_t)(t.pos + i0 + q);
+                ++pos;
+            }
+        }
+        if (t.fast && i0 + 3 < t.count) {
+            *reinterpret_cast<float4*>(ep + i0) = make_float4(keep[0] ? 0.0f : x[0], keep[1] ? 0.0f : x[1],
+                                                              keep[2] ? 0.0f : x[2], keep[3] ? 0.0f : x[3]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (ok[q]) ep[i0 + q] = keep[q] ? 0.0f : x[q];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------ host side
+#define TK_CHECK(expr)                     \
+    do {                                   \
+        hipError_t _e = (expr);            \
+        if (_e != hipSuccess) return _e;   \
+    } while (0)
+
+hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers, int max_tiles) {
+    t->max_elems = max_elems;
+    t->max_layers = max_layers;
+    t->max_tiles = max_tiles;
+    TK_CHECK(hipMalloc(&t->d_hist, sizeof(uint32_t) * (size_t)max_layers * kHistBins));
+    TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
+    TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
+    TK_CHECK(hipMalloc(&t->d_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk));
+    TK_CHECK(hipMalloc(&t->d_cand_base, sizeof(int64_t) * (size_t)max_layers));
+    TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles));
+    TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles));
+    TK_CHECK(hipHostMalloc(&t->h_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk, hipHostMallocDefault));
+    TK_CHECK(hipHostMalloc(&t->h_cand_base, sizeof(int64_t) * (size_t)max_layers, hipHostMallocDefault));
+    return hipSuccess;
+}
+
+void topk_scratch_destroy(TopkScratch* t) {
+    (void)hipFree(t->d_hist);
+    (void)hipFree(t->d_tl);
+    (void)hipFree(t->d_cand);
+    (void)hipFree(t->d_k);
+    (void)hipFree(t->d_cand_base);
+    (void)hipFree(t->d_tilecnt);
+    (void)hipFree(t->d_tilebase);
+    (void)hipHostFree(t->h_k);
+    (void)hipHostFree(t->h_cand_base);
+    *t = TopkScratch{};
+}
+
+// Upload the requested k per (layer, candidate) (0 = layer inactive) and clear the histograms.
+hipError_t topk_begin(TopkScratch* t, const DevLayer* h_layers, int L, const uint32_t* ks, hipStream_t s) {
+    int64_t base = 0;
+    for (int l = 0; l < L; ++l) {
+        for (int j = 0; j < kMaxTopk; ++j) t->h_k[(size_t)l * kMaxTopk + j] = ks[(size_t)l * kMaxTopk + j];
+        t->h_cand_base[l] = base;
+        if (ks[(size_t)l * kMaxTopk]) base += h_layers[l].numel;
+    }
+    TK_CHECK(hipMemcpyAsync(t->d_k, t->h_k, sizeof(uint32_t) * (size_t)L * kMaxTopk, hipMemcpyHostToDevice, s));
+    TK_CHECK(hipMemcpyAsync(t->d_cand_base, t->h_cand_base, sizeof(int64_t) * (size_t)L, hipMemcpyHostToDevice, s));
+    const size_t n = (size_t)L * kHistBins;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
+                       t->d_hist, n, 0u);
+    return hipGetLastError();
+}
+
+hipError_t topk_hist(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                     const Tile* d_tiles, int n_tiles, hipStream_t s) {
+    if (n_tiles <= 0) return hipSuccess;
+    hipLaunchKernelGGL(topk_hist_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
+                       (const uint32_t*)t->d_k, t->d_hist);
+    return hipGetLastError();
+}
+
+hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
+                       int stride, Timing* tm, hipStream_t s) {
+    {
+        Section sec(tm, "topk_scan");
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)t->d_hist,
+                           (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base, (TopkLayer*)t->d_tl);
+        TK_CHECK(hipGetLastError());
+    }
+    PassBParams p{};
+    p.g = g;
+    p.e = e;
+    p.layers = d_layers;
+    p.tiles = d_tiles;
+    p.tl = (TopkLayer*)t->d_tl;
+    p.cand = t->d_cand;
+    p.partials = d_partials;
+    p.stride = stride;
+    p.ntk = ntk;
+    for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
+    {
+        Section sec(tm, "topk_pass_b");
+        hipLaunchKernelGGL(topk_passb_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        TK_CHECK(hipGetLastError());
+    }
+    return hipSuccess;
+}
+
+hipError_t topk_finalize(TopkScratch* t, int L, int ntk, const int* col, double* d_errors, int stride,
+                         Timing* tm, hipStream_t s) {
+    FinalizeParams p{};
+    p.tl = (TopkLayer*)t->d_tl;
+    p.cand = t->d_cand;
+    p.errors = d_errors;
+    p.stride = stride;
+    p.ntk = ntk;
+    for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
+    Section sec(tm, "topk_finalize");
+    hipLaunchKernelGGL(topk_finalize_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
+                         Timing* tm, hipStream_t s) {
+    std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
+    for (int l = 0; l < L; ++l)
+        if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
+    {
+        Section sec(tm, "topk_zero");
+        TK_CHECK(topk_begin(t, h_layers, L, ks.data(), s));
+    }
+    {
+        Section sec(tm, "topk_hist");
+        TK_CHECK(topk_hist(t, g, e, d_layers, d_tiles, n_tiles, s));
+    }
+    TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, nullptr, nullptr, 0, tm, s));
+    TK_CHECK(topk_finalize(t, L, 1, nullptr, nullptr, 0, tm, s));
+    {
+        Section sec(tm, "topk_count");
+        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, (const float*)e, d_layers,
+                           d_tiles, (const TopkLayer*)t->d_tl, (uint2*)t->d_tilecnt);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_tilescan");
+        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(256), 0, s, d_layers, (const uint2*)t->d_tilecnt,
+                           (uint2*)t->d_tilebase);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_write");
+        hipLaunchKernelGGL(topk_write_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
+                           (const TopkLayer*)t->d_tl, (const uint2*)t->d_tilecnt, (const uint2*)t->d_tilebase,
+                           payload);
+        TK_CHECK(hipGetLastError());
+    }
+    return hipSuccess;
 }
 
 }  // namespace lgreco

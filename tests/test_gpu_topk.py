@@ -1,0 +1,108 @@
+"""GPU parity, Top-K family: dropped-energy profile for all densities (1e-4 relative), kept
+indices and values bit-exact (ties to the lowest index), error feedback bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import pipeline, topk
+from paper_2210_17357_amd import workloads as W
+
+from gpu_util import rel_err, tables, to_device, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+def _flat_batch(arrays, efs=None, pad=None):
+    offs, pos = [], 0
+    for i, a in enumerate(arrays):
+        pos += 0 if pad is None else pad[i]
+        offs.append(pos)
+        pos += a.size
+    g = np.zeros(pos, np.float32)
+    e = np.zeros(pos, np.float32)
+    for i, a in enumerate(arrays):
+        g[offs[i]:offs[i] + a.size] = a
+        if efs is not None:
+            e[offs[i]:offs[i] + a.size] = efs[i]
+    n = [a.size for a in arrays]
+    return W.Batch(g, e, np.asarray(offs, np.int64), np.asarray(n, np.int64), np.zeros(len(n), np.int32),
+                   np.zeros(len(n), np.int32), np.arange(len(n), dtype=np.int64))
+
+
+def _check(batch, densities, profile_ef=True):
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    cands = [(W.TOPK, float(d)) for d in densities]
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    h = B.Handle(int(batch.grads.size), L, len(cands))
+    errors, sizes = h.profile(g, e if profile_ef else None, layers, ctab)
+    ref = pipeline.profile(batch.grads, batch.ef if profile_ef else None, batch.offsets, batch.numels,
+                           batch.rows, batch.cols, cands)
+    assert np.array_equal(sizes, pipeline.sizes_table(batch.numels, batch.rows, batch.cols, cands))
+    scale = np.array([[float(np.sum((batch.grads[o:o + n].astype(np.float64)
+                                      + (batch.ef[o:o + n] if profile_ef else 0)) ** 2))]
+                      for o, n in zip(batch.offsets, batch.numels)])
+    bad = (rel_err(errors, ref) > 1e-4) & (np.abs(errors - ref) > 1e-12 * scale)
+    assert not bad.any(), (np.argwhere(bad)[:5], errors[bad][:5], ref[bad][:5])
+    errors2, _ = h.profile(g, e if profile_ef else None, layers, ctab)
+    assert np.array_equal(errors, errors2)                 # reproducible run to run
+
+    for rot in range(min(len(cands), 3)):
+        choice = np.array([(l + rot) % len(cands) for l in range(L)], np.int32)
+        offsets = B.payload_layout(layers, ctab, choice)
+        payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
+        ef_dev = e.clone()
+        h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)
+        pay = payload.cpu().numpy()
+        new_ef = ef_dev.cpu().numpy()
+        for l in range(L):
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            vals, idx, e_ref = topk.compress(batch.grads[off:off + n], batch.ef[off:off + n],
+                                             cands[choice[l]][1])
+            k = idx.size
+            assert sizes[l, choice[l]] == 8 * k
+            got_v = pay[offsets[l]:offsets[l] + 4 * k].view(np.float32)
+            got_i = pay[offsets[l] + 4 * k:offsets[l] + 8 * k].view(np.uint32)
+            assert np.array_equal(got_i, idx), ("indices", l, n, k)
+            assert np.array_equal(got_v.view(np.uint32), vals.view(np.uint32)), ("values", l)
+            assert np.array_equal(new_ef[off:off + n].view(np.uint32), e_ref.view(np.uint32)), ("ef", l)
+    h.close()
+
+
+def test_resnet50_workload():
+    w = W.workload("c2_resnet50_topk")
+    _check(W.generate(w), W.TOPK_DENSITIES)
+
+
+def test_ragged_misaligned_and_tiny_layers():
+    rng = np.random.default_rng(0)
+    sizes = [1, 2, 5, 64, 127, 513, 1000, 8192, 8193, 20000, 3 * 8192 + 700]
+    arrays = [rng.laplace(0, 1e-3, n).astype(np.float32) for n in sizes]
+    efs = [rng.laplace(0, 1e-3, n).astype(np.float32) for n in sizes]
+    _check(_flat_batch(arrays, efs, pad=[0, 1, 1, 0, 3, 2, 0, 1, 0, 5, 2]), (0.001, 0.01, 0.1, 0.5, 1.0))
+    _check(_flat_batch(arrays, efs), W.TOPK_DENSITIES)
+
+
+def test_ties_zeros_and_constant_layers():
+    rng = np.random.default_rng(1)
+    a = (rng.integers(-3, 4, 30000).astype(np.float32) * np.float32(0.5))     # heavy ties, +-0
+    b = np.zeros(5000, np.float32)
+    c = np.full(9000, -0.75, np.float32)
+    d = rng.standard_normal(12000).astype(np.float32)
+    d[::3] = 0.0                                                              # sparse gradient
+    f = np.where(rng.random(40000) < 0.02, rng.standard_normal(40000), 0).astype(np.float32)
+    g = (np.float32(1e-42) * rng.integers(0, 50, 3000)).astype(np.float32)    # denormals
+    _check(_flat_batch([a, b, c, d, f, g]), (0.001, 0.01, 0.05, 0.1, 0.3, 1.0))
+
+
+def test_near_ties_within_the_same_fine_bin():
+    # magnitudes that differ only in the last mantissa bits around the k-th value
+    base = np.float32(1.0)
+    x = np.full(20000, 0.001, np.float32)
+    near = np.nextafter(base, np.float32(2.0), dtype=np.float32)
+    x[100] = base
+    x[200] = near
+    x[300] = np.nextafter(near, np.float32(2.0), dtype=np.float32)
+    x[400:420] = base
+    _check(_flat_batch([x]), (1 / 20000, 2 / 20000, 3 / 20000, 0.001, 0.0011, 0.5))
