@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the L-GreCo hot path on one MI355X.
+
+One "step" = one pass of the whole path over one batch of synthetic gradients:
+    lgreco_profile (every candidate) -> lgreco_emax -> lgreco_solve -> lgreco_payload_layout
+    -> lgreco_compress (chosen per-layer setting, error feedback updated).
+Inputs are resident in HBM before the timed region.  Every step works on its own copy of the
+error-feedback buffer, so all steps do identical work and nothing is restored inside the
+timed region.
+
+Prints ONE JSON line (metric = gradient GB/s = 4 * N bytes / step time), with
+  "roofline"     achieved algorithmic GB/s of the dominant kernel, timed with HIP events on the
+                 launch stream inside the timed region, against the 8 TB/s HBM peak;
+  "cpu_baseline" the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+# algorithmic bytes per gradient element of each kernel (what the step must move, not what a
+# given implementation happens to move); b = mean chosen bits, d = mean chosen density
+ALGO_BYTES = {
+    "quant_profile": 8.0, "quant_profile_hist": 8.0, "topk_hist": 8.0, "topk_pass_b": 8.0,
+    "topk_count": 8.0,
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=14_000_000)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, sample_tensors):
+    """Oracle (as it stands) on a bounded sample: same three phases, wall clock."""
+    from oracle import pipeline, solver
+    from paper_2210_17357_amd import workloads as W
+    b = W.generate(w, sample_tensors)
+    n = int(b.numels.sum())
+    cands = list(w.candidates)
+    kw = dict(bucket=w.bucket, stochastic=w.stochastic, seed=w.seed)
+    if b.q0 is not None:
+        kw.update(q0=b.q0, q_offsets=b.q_offsets, r_max=w.r_max)
+    t0 = time.perf_counter()
+    errors = pipeline.profile(b.grads, b.ef, b.offsets, b.numels, b.rows, b.cols, cands, **kw)
+    sizes = pipeline.sizes_table(b.numels, b.rows, b.cols, cands, w.bucket)
+    t1 = time.perf_counter()
+    e_max = solver.e_max_uniform(errors, w.default)
+    choice, _, _ = solver.solve(errors, sizes, e_max, w.n_bins)
+    t2 = time.perf_counter()
+    for l in range(len(b.numels)):
+        q0l = None
+        if b.q0 is not None:
+            q0l = b.q0[int(b.q_offsets[l]):int(b.q_offsets[l]) + int(b.cols[l]) * w.r_max].reshape(-1, w.r_max)
+        pipeline.compress_layer(b.grads, b.ef, int(b.offsets[l]), int(b.numels[l]), int(b.rows[l]),
+                                int(b.cols[l]), cands[choice[l]], l, w.bucket, w.stochastic, w.seed, q0l)
+    t3 = time.perf_counter()
+    return b, errors, choice, {"profile_s": t1 - t0, "solve_s": t2 - t1, "compress_s": t3 - t2,
+                               "elems": n, "total_s": t3 - t0}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2210_17357_amd import binding as B
+    from paper_2210_17357_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = W.workload(args.workload)
+    cands = list(w.candidates)
+    threads = min(16, os.cpu_count() or 1)
+    t_gen = time.perf_counter()
+    batch = W.generate(w, threads=threads)
+    t_gen = time.perf_counter() - t_gen
+    N = int(batch.numels.sum())
+    L = len(batch.numels)
+    layers = B.layer_table(batch.offsets, batch.numels, batch.rows, batch.cols)
+    ctab = B.cand_table(cands)
+    dev = torch.device("cuda:0")
+    g = torch.from_numpy(batch.grads).to(dev)
+    has_ef = batch.ef is not None
+    ef0 = torch.from_numpy(batch.ef).to(dev) if has_ef else torch.zeros_like(g)
+    q0 = torch.from_numpy(batch.q0).to(dev) if batch.q0 is not None else None
+    n_runs = args.steps + args.warmup
+    ef_pool = [ef0.clone() for _ in range(n_runs)]
+    q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
+    h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
+                 seed=w.seed, r_max=w.r_max)
+    h.set_timing(True)
+    sizes_tab = B.sizes(layers, ctab, w.bucket)
+    payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
+
+    kern = {}          # name -> [total ms, launches]
+    phase = {"profile": 0.0, "solve": 0.0, "compress": 0.0}
+    last = {}
+
+    def step(i, record):
+        ef = ef_pool[i]
+        t0 = time.perf_counter()
+        errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True)
+        tm_p = h.get_timing() if record else []
+        t1 = time.perf_counter()
+        e_max = B.emax(errors, w.default)
+        st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins)
+        tm_s = h.get_timing() if record else []
+        t2 = time.perf_counter()
+        offsets = B.payload_layout(layers, ctab, choice, w.bucket)
+        h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i])
+        tm_c = h.get_timing() if record else []
+        t3 = time.perf_counter()
+        if record:
+            phase["profile"] += t1 - t0
+            phase["solve"] += t2 - t1
+            phase["compress"] += t3 - t2
+            for name, ms in tm_p + tm_s + tm_c:
+                a = kern.setdefault(name, [0.0, 0])
+                a[0] += ms
+                a[1] += 1
+        last.update(errors=errors, sizes=sizes, choice=choice, e_max=e_max, tsize=tsize, terr=terr, st=st)
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = 4.0 * N / (elapsed / args.steps) / 1e9
+
+    choice = last["choice"]
+    fam = np.array([cands[c][0] for c in choice])
+    par = np.array([cands[c][1] for c in choice])
+    numels = batch.numels.astype(np.float64)
+    nq = float(numels[fam == W.QUANT].sum())
+    ntk = float(numels[fam == W.TOPK].sum())
+    mean_bits = float((numels * par)[fam == W.QUANT].sum() / nq) if nq else 0.0
+    mean_dens = float((numels * par)[fam == W.TOPK].sum() / ntk) if ntk else 0.0
+    algo = dict(ALGO_BYTES)
+    # per launch: bytes = per-element figure x elements the launch covers
+    elems = {k: float(N) for k in algo}
+    algo["quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
+    elems["quant_compress"] = nq
+    algo["topk_write"] = 12.0 + 8.0 * mean_dens
+    elems["topk_write"] = ntk
+    kernels = {}
+    for name, (ms, cnt) in kern.items():
+        avg = ms / max(cnt, 1)
+        entry = {"avg_ms": round(avg, 4), "launches": cnt}
+        if name in algo and avg > 0 and "." not in name:
+            gb = algo[name] * elems[name] / 1e9
+            entry["algo_GB"] = round(gb, 4)
+            entry["GBps"] = round(gb / (avg * 1e-3), 1)
+        kernels[name] = entry
+    timed = {k: v for k, v in kernels.items() if "GBps" in v}
+    roofline = None
+    if timed:
+        dom = max(timed, key=lambda k: timed[k]["avg_ms"])
+        ach = timed[dom]["GBps"]
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
+
+    out = {
+        "metric": "profile+solve+compress gradient GB/s at 1 MI355X",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
+                   "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "host_generation_s": round(t_gen, 2)},
+        "roofline": roofline,
+        "phases_ms": {k: round(v * 1e3 / args.steps, 4) for k, v in phase.items()},
+        "kernels": kernels,
+        "result": {"status": int(last["st"]), "total_size_bytes": int(last["tsize"]),
+                   "ratio_vs_fp32": round(4.0 * N / max(int(last["tsize"]), 1), 3),
+                   "uniform_default_bytes": int(last["sizes"][:, w.default].sum()),
+                   "total_error_over_emax": round(float(last["terr"]) / float(last["e_max"]), 5)
+                   if last["e_max"] > 0 else None,
+                   "layers_quant": int((fam == W.QUANT).sum()), "layers_topk": int((fam == W.TOPK).sum()),
+                   "layers_lowrank": int((fam == W.LOWRANK).sum())},
+    }
+
+    if not args.no_cpu_baseline:
+        # bounded sample: leading tensors of the workload up to ~cpu-sample-elems elements,
+        # skipping any single tensor larger than the bound
+        sample, acc = [], 0
+        for t, shape in enumerate(w.shapes):
+            n = int(np.prod(shape))
+            if n > args.cpu_sample_elems:
+                continue
+            if acc + n > args.cpu_sample_elems:
+                break
+            sample.append(t)
+            acc += n
+        sb, o_err, o_choice, tm = cpu_baseline(w, sample)
+        out["cpu_baseline"] = {
+            "value": round(4.0 * tm["elems"] / tm["total_s"] / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "tensors %d..%d of %s (%d elements): oracle profile %.2fs + solve %.2fs + compress %.2fs; "
+                      "numpy element-wise code, single thread (host has %d cores)"
+                      % (sample[0], sample[-1], w.name, tm["elems"], tm["profile_s"], tm["solve_s"],
+                         tm["compress_s"], os.cpu_count() or 0)}
+        # parity of the GPU profile on the sampled layers (same seeded inputs)
+        idx = [int(np.where(batch.tensor_index == t)[0][0]) for t in sb.tensor_index]
+        if not w.stochastic or idx == list(range(len(idx))):     # the RNG is keyed by layer index
+            g_err = last["errors"][idx]
+            rel = np.abs(g_err - o_err) / np.maximum(np.abs(o_err), 1e-300)
+            out["parity"] = {"layers_checked": len(idx), "max_rel_err_profile": float(rel.max())}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -97,15 +97,9 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 
 // ---- lowrank.hip
 struct LowrankScratch {
-    float* d_p = nullptr;        // P / Phat of all layers, [sum rows x r_max]
-    float* d_q = nullptr;        // Q of all layers, [sum cols x r_max]
-    double* d_gram = nullptr;    // per layer [r_max x r_max]
-    double* d_norm = nullptr;    // per layer ||M||^2 and column norms
-    void* d_work = nullptr;      // split-K partial sums
-    void* d_table = nullptr;     // per-launch tile tables
+    void* host = nullptr;        // work tables and scratch buffers (grown on demand)
     int64_t max_elems = 0;
     int max_layers = 0, r_max = 0;
-    size_t work_bytes = 0, table_bytes = 0;
 };
 hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max);
 void lowrank_scratch_destroy(LowrankScratch* t);

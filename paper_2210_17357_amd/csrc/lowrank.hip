@@ -1,17 +1,741 @@
-// Low rank (stub, replaced below in the build order).
+// PowerSGD-style low rank: one power-iteration step per layer on fp32 MFMA, for gfx950.
+//
+//   P = X Q0            X = g + e viewed as [m x n] row-major, Q0 [n x 64] warm start
+//   Phat = orth(P)      Gram-Schmidt on the columns, done in coefficient space: G = P^T P in
+//                       fp64, one wavefront per layer runs the column-by-column elimination
+//                       on the 64 x 64 Gram matrix (lane j owns column j; this is exactly the
+//                       Gram-Schmidt recurrence on the inner products), inverts the triangular
+//                       factor and Phat = P T.  A column whose squared norm after projection is
+//                       0 or below 1e-10 x its squared norm before projection becomes zero.
+//   Q = X^T Phat
+//   error_r = ||X||^2 - sum_{j<r} ||q_j||^2    (Phat orthonormal, Q = X^T Phat, and the factors
+//                       of rank r are the leading columns of the rank-64 run, so one run yields
+//                       every rank's error)
+//   compress: payload Phat[:, :r], Q[:, :r];  e' = X - Phat[:, :r] Q[:, :r]^T
+//
+// The two contractions and the reconstruction use v_mfma_f32_32x32x2f32 (fp32 in, fp32
+// accumulate).  Operand layout of that instruction, lane l of 64:
+//   A (32 x 2): A[i = l % 32][k = l / 32];   B (2 x 32): B[k = l / 32][j = l % 32]
+//   D (32 x 32): register v (0..15) holds D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
+#include <cstring>
+
 #include "internal.h"
 
 namespace lgreco {
 
-hipError_t lowrank_scratch_create(LowrankScratch*, int64_t, int, int) { return hipSuccess; }
-void lowrank_scratch_destroy(LowrankScratch*) {}
-hipError_t lowrank_profile(LowrankScratch*, const float*, const float*, const DevLayer*, const DevLayer*, int,
-                           const float*, int, const int*, const int*, int, double*, int, Timing*, hipStream_t) {
-    return hipErrorNotSupported;
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kLrCols = 64;       // columns computed per layer (r_max <= 64)
+constexpr int kLrBM = 128;        // rows (GEMM1, reconstruction) / columns (GEMM2) per workgroup
+constexpr int kLrBK = 32;         // contraction chunk staged in LDS
+constexpr int kLrGramRows = 128;  // rows per Gram partial
+constexpr int kLrQChunk = 64;     // Q rows per workgroup in the split-K reduction
+
+struct LrLayer {
+    int64_t offset;     // into g / e
+    int64_t q_off;      // into q0 / q (stride r_max)
+    int64_t p_off;      // into the P scratch (rows x 64)
+    int64_t qs_off;     // into the Q scratch (cols x 64)
+    int64_t part_off;   // into the split-K partial buffer (splits x cols x 64)
+    int64_t payload;    // byte offset of the payload (compress)
+    int32_t rows, cols;
+    int32_t rank;       // columns written out (64 when profiling)
+    int32_t splits, ksplit;
+    int32_t gram_begin, gram_end;   // Gram partial range
+    int32_t rt_begin, rt_end;       // row-tile range (||X||^2 partials)
+    int32_t qc_begin, qc_end;       // Q-chunk range (column-norm partials)
+    int32_t vec_ok;     // 16-byte aligned rows: offset % 4 == 0 and cols % 4 == 0
+    int32_t index;      // index in the caller's layer table
+    int32_t pad;
+};
+struct LrTile {
+    int32_t layer, a0, split, pad;
+};
+
+struct LrParams {
+    const float* g;
+    const float* e;          // may be null
+    float* e_out;            // compress: error feedback (same buffer as e)
+    const float* q0;         // warm start (stride r_max)
+    float* q_out;            // compress: new Q (stride r_max), same buffer as q0
+    int32_t r_max;
+    const LrLayer* layers;
+    const LrTile* row_tiles;
+    const LrTile* col_tiles;
+    const LrTile* gram_tiles;
+    const LrTile* q_chunks;
+    float* P;                // scratch [sum rows x 64]
+    float* Q;                // scratch [sum cols x 64]
+    float* part;             // split-K partials
+    double* gram_part;       // [gram tiles x 64 x 64]
+    double* T;               // [layers x 64 x 64]
+    double* xnorm_part;      // [row tiles]
+    double* qnorm_part;      // [q chunks x 64]
+    uint8_t* payload;
+    double* errors;          // [L x stride]
+    int32_t stride;
+    int32_t nrank;
+    int32_t rank[LGRECO_MAX_CANDS];
+    int32_t col[LGRECO_MAX_CANDS];
+};
+
+// 4 consecutive elements of x = g + e starting at idx of a row that has `left` elements left.
+__device__ __forceinline__ float4 load_x4(const float* __restrict__ g, const float* __restrict__ e, int64_t idx,
+                                          int left, bool vec_ok) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (left >= 4 && vec_ok) {
+        v = *reinterpret_cast<const float4*>(g + idx);
+        if (e) {
+            const float4 w = *reinterpret_cast<const float4*>(e + idx);
+            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+    } else {
+        if (left > 0) v.x = e ? g[idx] + e[idx] : g[idx];
+        if (left > 1) v.y = e ? g[idx + 1] + e[idx + 1] : g[idx + 1];
+        if (left > 2) v.z = e ? g[idx + 2] + e[idx + 2] : g[idx + 2];
+        if (left > 3) v.w = e ? g[idx + 3] + e[idx + 3] : g[idx + 3];
+    }
+    return v;
 }
-hipError_t lowrank_compress(LowrankScratch*, const float*, float*, const DevLayer*, const DevLayer*, int, float*,
-                            int, uint8_t*, Timing*, hipStream_t) {
-    return hipErrorNotSupported;
+
+// ------------------------------------------------------------------ P = X Q0 (and ||X||^2)
+__global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
+    __shared__ float Xs[2][kLrBM][kLrBK + 1];
+    __shared__ float Qs[2][kLrBK][kLrCols];
+    __shared__ double s_red[4];
+    const LrTile tile = p.row_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    const int m = L.rows, n = L.cols, row0 = tile.a0;
+    const float* __restrict__ g = p.g + L.offset;
+    const float* __restrict__ e = p.e ? p.e + L.offset : nullptr;
+    const float* __restrict__ q = p.q0 + L.q_off;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool vec = L.vec_ok != 0;
+    const bool qvec = (p.r_max % 4 == 0) && (L.q_off % 4 == 0);
+
+    float4 xr[4], qr[2];
+    float xsq = 0.0f;
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int f = tid + 256 * s;
+            const int r = f >> 3, c = (f & 7) * 4;
+            const int row = row0 + r, colk = k0 + c;
+            xr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < m && colk < n) xr[s] = load_x4(g, e, (int64_t)row * n + colk, n - colk, vec);
+            xsq = __builtin_fmaf(xr[s].x, xr[s].x, xsq);
+            xsq = __builtin_fmaf(xr[s].y, xr[s].y, xsq);
+            xsq = __builtin_fmaf(xr[s].z, xr[s].z, xsq);
+            xsq = __builtin_fmaf(xr[s].w, xr[s].w, xsq);
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int f = tid + 256 * s;
+            const int kr = f >> 4, c = (f & 15) * 4;
+            const int k = k0 + kr;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < n) {
+                const float* src = q + (int64_t)k * p.r_max + c;
+                if (qvec && c + 3 < p.r_max) {
+                    v = *reinterpret_cast<const float4*>(src);
+                } else {
+                    if (c < p.r_max) v.x = src[0];
+                    if (c + 1 < p.r_max) v.y = src[1];
+                    if (c + 2 < p.r_max) v.z = src[2];
+                    if (c + 3 < p.r_max) v.w = src[3];
+                }
+            }
+            qr[s] = v;
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int f = tid + 256 * s;
+            const int r = f >> 3, c = (f & 7) * 4;
+            Xs[buf][r][c] = xr[s].x; Xs[buf][r][c + 1] = xr[s].y;
+            Xs[buf][r][c + 2] = xr[s].z; Xs[buf][r][c + 3] = xr[s].w;
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int f = tid + 256 * s;
+            const int kr = f >> 4, c = (f & 15) * 4;
+            *reinterpret_cast<float4*>(&Qs[buf][kr][c]) = qr[s];
+        }
+    };
+
+    f32x16 acc0 = {0}, acc1 = {0};
+    const int nchunks = (n + kLrBK - 1) / kLrBK;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    const int ar = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) fetch((c + 1) * kLrBK);
+#pragma unroll
+        for (int kk = 0; kk < kLrBK; kk += 2) {
+            const float a = Xs[buf][ar][kk + ak];
+            const float b0 = Qs[buf][kk + ak][bj];
+            const float b1 = Qs[buf][kk + ak][32 + bj];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        }
+        if (c + 1 < nchunks) stash(buf ^ 1);
+        __syncthreads();
+    }
+    float* __restrict__ P = p.P + L.p_off;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row < m) {
+            P[(int64_t)row * kLrCols + bj] = acc0[v];
+            P[(int64_t)row * kLrCols + 32 + bj] = acc1[v];
+        }
+    }
+    const double s = wave_sum((double)xsq);
+    if (lane == 0) s_red[wave] = s;
+    __syncthreads();
+    if (tid == 0) p.xnorm_part[blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+// ------------------------------------------------------------------ partial Gram matrices
+__global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
+    __shared__ float Pl[kLrGramRows][kLrCols];
+    const LrTile tile = p.gram_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    const float* __restrict__ P = p.P + L.p_off;
+    const int row0 = tile.a0, nrows = min(kLrGramRows, L.rows - row0);
+    const int tid = threadIdx.x;
+    for (int f = tid; f < kLrGramRows * kLrCols / 4; f += 256) {
+        const int r = f >> 4, c = (f & 15) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
+        *reinterpret_cast<float4*>(&Pl[r][c]) = v;
+    }
+    __syncthreads();
+    const int bi = (tid >> 4) * 4, bj = (tid & 15) * 4;
+    double acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int r = 0; r < nrows; ++r) {
+        const float4 a = *reinterpret_cast<const float4*>(&Pl[r][bi]);
+        const float4 b = *reinterpret_cast<const float4*>(&Pl[r][bj]);
+        const double av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(av[i], bv[j], acc[i][j]);
+    }
+    double* __restrict__ out = p.gram_part + (size_t)blockIdx.x * kLrCols * kLrCols;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[(bi + i) * kLrCols + bj + j] = acc[i][j];
+}
+
+// ------------------------------------------------------------------ Gram-Schmidt coefficients
+// One wavefront per layer.  Lane j owns column j of the Gram matrix.
+__global__ __launch_bounds__(64) void lr_orth_kernel(LrParams p) {
+    extern __shared__ double lr_orth_smem[];
+    double (*G)[kLrCols + 1] = reinterpret_cast<double (*)[kLrCols + 1]>(lr_orth_smem);
+    double (*Tm)[kLrCols + 1] = G + kLrCols;
+    const LrLayer L = p.layers[blockIdx.x];
+    const int j = threadIdx.x;
+    for (int i = 0; i < kLrCols; ++i) {
+        double s = 0.0;
+        for (int c = L.gram_begin; c < L.gram_end; ++c)
+            s += p.gram_part[(size_t)c * kLrCols * kLrCols + i * kLrCols + j];
+        G[i][j] = s;
+        Tm[i][j] = 0.0;
+    }
+    __syncthreads();
+    const double diag0 = G[j][j];
+    __syncthreads();
+    for (int i = 0; i < kLrCols; ++i) {
+        const double d = G[i][i];
+        const double d0 = __shfl(diag0, i, 64);
+        const bool ok = d > 0.0 && d >= 1e-10 * d0;
+        const double rii = ok ? sqrt(d) : 0.0;
+        const double inv = ok ? 1.0 / rii : 0.0;
+        // row i of the triangular factor
+        const double rij = (j >= i) ? ((j == i) ? rii : G[i][j] * inv) : 0.0;
+        __syncthreads();
+        G[i][j] = rij;
+        __syncthreads();
+        // eliminate: G[k][j] -= R[i][k] R[i][j] for i < k <= j
+        for (int k = i + 1; k < kLrCols; ++k)
+            if (k <= j) G[k][j] -= G[i][k] * rij;
+        __syncthreads();
+    }
+    // T = R^-1 by back substitution, column j; rows of zeroed columns stay zero
+    for (int i = kLrCols - 1; i >= 0; --i) {
+        if (i <= j) {
+            double s = (i == j) ? 1.0 : 0.0;
+            for (int k = i + 1; k <= j; ++k) s -= G[i][k] * Tm[k][j];
+            const double rii = G[i][i];
+            Tm[i][j] = rii != 0.0 ? s / rii : 0.0;
+        }
+    }
+    __syncthreads();
+    double* __restrict__ T = p.T + (size_t)blockIdx.x * kLrCols * kLrCols;
+    for (int i = 0; i < kLrCols; ++i) T[i * kLrCols + j] = Tm[i][j];
+}
+
+// ------------------------------------------------------------------ Phat = P T
+__global__ __launch_bounds__(256) void lr_apply_kernel(LrParams p) {
+    __shared__ float Pl[64][kLrCols];
+    __shared__ double Tl[kLrCols][kLrCols];
+    const LrTile tile = p.row_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    float* __restrict__ P = p.P + L.p_off;
+    const double* __restrict__ T = p.T + (size_t)tile.layer * kLrCols * kLrCols;
+    const int tid = threadIdx.x, j = tid & 63;
+    for (int f = tid; f < kLrCols * kLrCols; f += 256) Tl[f >> 6][f & 63] = T[f];
+    float* pay = p.payload ? reinterpret_cast<float*>(p.payload + L.payload) : nullptr;
+    for (int half = 0; half < kLrBM; half += 64) {
+        const int row0 = tile.a0 + half, nrows = min(64, L.rows - row0);
+        if (nrows <= 0) break;
+        __syncthreads();
+        for (int f = tid; f < 64 * kLrCols / 4; f += 256) {
+            const int r = f >> 4, c = (f & 15) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
+            *reinterpret_cast<float4*>(&Pl[r][c]) = v;
+        }
+        __syncthreads();
+        for (int r = tid >> 6; r < nrows; r += 4) {
+            double s = 0.0;
+            for (int i = 0; i <= j; ++i) s = __builtin_fma((double)Pl[r][i], Tl[i][j], s);
+            const float v = (float)s;
+            P[(int64_t)(row0 + r) * kLrCols + j] = v;
+            if (pay && j < L.rank) pay[(int64_t)(row0 + r) * L.rank + j] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Q partials = X^T Phat
+__global__ __launch_bounds__(256) void lr_gemm2_kernel(LrParams p) {
+    __shared__ float Xs[2][kLrBK][kLrBM];
+    __shared__ float Ps[2][kLrBK][kLrCols];
+    const LrTile tile = p.col_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    const int m = L.rows, n = L.cols, col0 = tile.a0;
+    const int kbeg = tile.split * L.ksplit, kend = min(m, kbeg + L.ksplit);
+    const float* __restrict__ g = p.g + L.offset;
+    const float* __restrict__ e = p.e ? p.e + L.offset : nullptr;
+    const float* __restrict__ P = p.P + L.p_off;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool vec = L.vec_ok != 0;
+
+    float4 xr[4], pr[2];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int f = tid + 256 * s;
+            const int kr = f >> 5, c = (f & 31) * 4;
+            const int row = k0 + kr, col = col0 + c;
+            xr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < kend && col < n) xr[s] = load_x4(g, e, (int64_t)row * n + col, n - col, vec);
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int f = tid + 256 * s;
+            const int kr = f >> 4, c = (f & 15) * 4;
+            const int row = k0 + kr;
+            pr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < kend) pr[s] = *reinterpret_cast<const float4*>(P + (int64_t)row * kLrCols + c);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int f = tid + 256 * s;
+            *reinterpret_cast<float4*>(&Xs[buf][f >> 5][(f & 31) * 4]) = xr[s];
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int f = tid + 256 * s;
+            *reinterpret_cast<float4*>(&Ps[buf][f >> 4][(f & 15) * 4]) = pr[s];
+        }
+    };
+
+    f32x16 acc0 = {0}, acc1 = {0};
+    const int nchunks = (kend - kbeg + kLrBK - 1) / kLrBK;
+    fetch(kbeg);
+    stash(0);
+    __syncthreads();
+    const int ai = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) fetch(kbeg + (c + 1) * kLrBK);
+#pragma unroll
+        for (int kk = 0; kk < kLrBK; kk += 2) {
+            const float a = Xs[buf][kk + ak][ai];
+            const float b0 = Ps[buf][kk + ak][bj];
+            const float b1 = Ps[buf][kk + ak][32 + bj];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        }
+        if (c + 1 < nchunks) stash(buf ^ 1);
+        __syncthreads();
+    }
+    float* __restrict__ out = p.part + L.part_off + (int64_t)tile.split * n * kLrCols;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int col = col0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (col < n) {
+            out[(int64_t)col * kLrCols + bj] = acc0[v];
+            out[(int64_t)col * kLrCols + 32 + bj] = acc1[v];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Q = sum of partials, norms
+__global__ __launch_bounds__(256) void lr_qreduce_kernel(LrParams p) {
+    __shared__ double s_n[4][kLrCols];
+    const LrTile tile = p.q_chunks[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    const int n = L.cols, c0 = tile.a0, nc = min(kLrQChunk, n - c0);
+    const float* __restrict__ part = p.part + L.part_off;
+    float* __restrict__ Q = p.Q + L.qs_off;
+    const int tid = threadIdx.x, j = tid & 63;
+    float* pay = nullptr;
+    if (p.payload) pay = reinterpret_cast<float*>(p.payload + L.payload) + (int64_t)L.rows * L.rank;
+    double norm = 0.0;
+    for (int r = tid >> 6; r < nc; r += 4) {
+        const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
+        float s = 0.0f;
+        for (int sp = 0; sp < L.splits; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
+        Q[idx] = s;
+        norm = __builtin_fma((double)s, (double)s, norm);
+        if (p.payload && j < L.rank) {
+            pay[(int64_t)(c0 + r) * L.rank + j] = s;
+            p.q_out[L.q_off + (int64_t)(c0 + r) * p.r_max + j] = s;
+        }
+    }
+    s_n[tid >> 6][j] = norm;
+    __syncthreads();
+    if (tid < kLrCols)
+        p.qnorm_part[(size_t)blockIdx.x * kLrCols + tid] = s_n[0][tid] + s_n[1][tid] + s_n[2][tid] + s_n[3][tid];
+}
+
+// ------------------------------------------------------------------ errors of every rank
+__global__ __launch_bounds__(64) void lr_errors_kernel(LrParams p) {
+    const LrLayer L = p.layers[blockIdx.x];
+    const int j = threadIdx.x;
+    double qn = 0.0;
+    for (int c = L.qc_begin; c < L.qc_end; ++c) qn += p.qnorm_part[(size_t)c * kLrCols + j];
+    double xn = 0.0;
+    for (int t = L.rt_begin; t < L.rt_end; ++t) xn += p.xnorm_part[t];      // same in every lane
+    // inclusive prefix over columns, in column order
+    double pre = qn;
+    for (int o = 1; o < 64; o <<= 1) {
+        const double v = __shfl_up(pre, o, 64);
+        if (j >= o) pre += v;
+    }
+    for (int c = 0; c < p.nrank; ++c)
+        if (j == p.rank[c] - 1) p.errors[(size_t)L.index * p.stride + p.col[c]] = fmax(xn - pre, 0.0);
+}
+
+// ------------------------------------------------------------------ e' = X - Phat Q^T
+__global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
+    __shared__ float Ps[kLrBM][kLrCols + 1];
+    __shared__ float Qs[kLrCols][kLrCols + 1];
+    const LrTile tile = p.row_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    const int m = L.rows, n = L.cols, row0 = tile.a0, r = L.rank;
+    const int kmax = (r + 1) & ~1;
+    const float* __restrict__ g = p.g + L.offset;
+    float* __restrict__ e = p.e_out + L.offset;
+    const float* __restrict__ P = p.P + L.p_off;
+    const float* __restrict__ Q = p.Q + L.qs_off;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    for (int f = tid; f < kLrBM * kLrCols; f += 256) {
+        const int rr = f >> 6, c = f & 63;
+        Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * kLrCols + c] : 0.0f;
+    }
+    const int ar = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
+    for (int c0 = 0; c0 < n; c0 += kLrCols) {
+        __syncthreads();
+        for (int f = tid; f < kLrCols * kLrCols; f += 256) {
+            const int cc = f >> 6, k = f & 63;
+            Qs[cc][k] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * kLrCols + k] : 0.0f;
+        }
+        __syncthreads();
+        f32x16 acc0 = {0}, acc1 = {0};
+        for (int kk = 0; kk < kmax; kk += 2) {
+            const float a = Ps[ar][kk + ak];
+            const float b0 = Qs[bj][kk + ak];
+            const float b1 = Qs[32 + bj][kk + ak];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (row < m) {
+                const int64_t base = (int64_t)row * n + c0;
+                if (c0 + bj < n) {
+                    const float x = g[base + bj] + e[base + bj];
+                    e[base + bj] = x - acc0[v];
+                }
+                if (c0 + 32 + bj < n) {
+                    const float x = g[base + 32 + bj] + e[base + 32 + bj];
+                    e[base + 32 + bj] = x - acc1[v];
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------ host side
+#define LR_CHECK(expr)                     \
+    do {                                   \
+        hipError_t _e = (expr);            \
+        if (_e != hipSuccess) return _e;   \
+    } while (0)
+
+struct LrHost {
+    std::vector<LrLayer> layers;
+    std::vector<LrTile> row_tiles, col_tiles, gram_tiles, q_chunks;
+    std::vector<int64_t> sig;       // signature of the layer table the tables were built for
+    int64_t p_elems = 0, q_elems = 0, part_elems = 0;
+    // device copies
+    LrLayer* d_layers = nullptr;
+    LrTile* d_tiles = nullptr;      // the four tile tables back to back
+    size_t cap_layers = 0, cap_tiles = 0, cap_p = 0, cap_q = 0, cap_part = 0, cap_gram = 0, cap_T = 0,
+           cap_xn = 0, cap_qn = 0;
+    float* P = nullptr;
+    float* Q = nullptr;
+    float* part = nullptr;
+    double* gram = nullptr;
+    double* T = nullptr;
+    double* xn = nullptr;
+    double* qn = nullptr;
+};
+
+static hipError_t grow(void** ptr, size_t* cap, size_t need) {
+    if (need <= *cap) return hipSuccess;
+    if (*ptr) LR_CHECK(hipFree(*ptr));
+    *ptr = nullptr;
+    *cap = 0;
+    LR_CHECK(hipMalloc(ptr, need));
+    *cap = need;
+    return hipSuccess;
+}
+
+hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max) {
+    t->max_elems = max_elems;
+    t->max_layers = max_layers;
+    t->r_max = r_max;
+    t->host = new LrHost();
+    return hipSuccess;
+}
+
+void lowrank_scratch_destroy(LowrankScratch* t) {
+    LrHost* H = (LrHost*)t->host;
+    if (H) {
+        (void)hipFree(H->d_layers);
+        (void)hipFree(H->d_tiles);
+        (void)hipFree(H->P);
+        (void)hipFree(H->Q);
+        (void)hipFree(H->part);
+        (void)hipFree(H->gram);
+        (void)hipFree(H->T);
+        (void)hipFree(H->xn);
+        (void)hipFree(H->qn);
+        delete H;
+    }
+    *t = LowrankScratch{};
+}
+
+// Build the work tables for the layers with rank[l] > 0 and upload them.  Scratch buffers grow on
+// demand (allocation happens only when a larger layer table arrives).
+static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const int* rank, int r_max,
+                             hipStream_t s) {
+    LrHost* H = (LrHost*)t->host;
+    std::vector<int64_t> sig;
+    sig.reserve((size_t)L * 5 + 1);
+    sig.push_back(r_max);
+    for (int l = 0; l < L; ++l) {
+        sig.push_back(hl[l].offset);
+        sig.push_back(hl[l].rows);
+        sig.push_back(hl[l].cols);
+        sig.push_back(rank[l]);
+        sig.push_back(hl[l].payload);
+    }
+    if (sig == H->sig) return hipSuccess;
+    H->layers.clear();
+    H->row_tiles.clear();
+    H->col_tiles.clear();
+    H->gram_tiles.clear();
+    H->q_chunks.clear();
+    int64_t p_off = 0, q_off = 0, part_off = 0;
+    for (int l = 0; l < L; ++l) {
+        if (rank[l] <= 0) continue;
+        LrLayer a{};
+        a.offset = hl[l].offset;
+        a.q_off = hl[l].q_offset;
+        a.rows = hl[l].rows;
+        a.cols = hl[l].cols;
+        a.rank = rank[l];
+        a.payload = hl[l].payload;
+        a.index = l;
+        a.vec_ok = (a.offset % 4 == 0 && a.cols % 4 == 0) ? 1 : 0;
+        a.p_off = p_off;
+        a.qs_off = q_off;
+        a.part_off = part_off;
+        // split the contraction over rows so that every column tile gets enough workgroups
+        const int col_tiles = (a.cols + kLrBM - 1) / kLrBM;
+        int splits = 1;
+        while (splits < 64 && (int64_t)a.rows / (splits * 2) >= 512 && col_tiles * splits < 128) splits *= 2;
+        a.ksplit = ((a.rows + splits - 1) / splits + kLrBK - 1) / kLrBK * kLrBK;
+        a.splits = (a.rows + a.ksplit - 1) / a.ksplit;
+        const int li = (int)H->layers.size();
+        a.rt_begin = (int)H->row_tiles.size();
+        for (int r0 = 0; r0 < a.rows; r0 += kLrBM) H->row_tiles.push_back(LrTile{li, r0, 0, 0});
+        a.rt_end = (int)H->row_tiles.size();
+        for (int c0 = 0; c0 < a.cols; c0 += kLrBM)
+            for (int sp = 0; sp < a.splits; ++sp) H->col_tiles.push_back(LrTile{li, c0, sp, 0});
+        a.gram_begin = (int)H->gram_tiles.size();
+        for (int r0 = 0; r0 < a.rows; r0 += kLrGramRows) H->gram_tiles.push_back(LrTile{li, r0, 0, 0});
+        a.gram_end = (int)H->gram_tiles.size();
+        a.qc_begin = (int)H->q_chunks.size();
+        for (int c0 = 0; c0 < a.cols; c0 += kLrQChunk) H->q_chunks.push_back(LrTile{li, c0, 0, 0});
+        a.qc_end = (int)H->q_chunks.size();
+        p_off += (int64_t)a.rows * kLrCols;
+        q_off += (int64_t)a.cols * kLrCols;
+        part_off += (int64_t)a.splits * a.cols * kLrCols;
+        H->layers.push_back(a);
+    }
+    H->p_elems = p_off;
+    H->q_elems = q_off;
+    H->part_elems = part_off;
+    const size_t nl = H->layers.size();
+    const size_t nt = H->row_tiles.size() + H->col_tiles.size() + H->gram_tiles.size() + H->q_chunks.size();
+    LR_CHECK(grow((void**)&H->d_layers, &H->cap_layers, sizeof(LrLayer) * std::max<size_t>(nl, 1)));
+    LR_CHECK(grow((void**)&H->d_tiles, &H->cap_tiles, sizeof(LrTile) * std::max<size_t>(nt, 1)));
+    LR_CHECK(grow((void**)&H->P, &H->cap_p, sizeof(float) * std::max<int64_t>(p_off, 1)));
+    LR_CHECK(grow((void**)&H->Q, &H->cap_q, sizeof(float) * std::max<int64_t>(q_off, 1)));
+    LR_CHECK(grow((void**)&H->part, &H->cap_part, sizeof(float) * std::max<int64_t>(part_off, 1)));
+    LR_CHECK(grow((void**)&H->gram, &H->cap_gram,
+                  sizeof(double) * kLrCols * kLrCols * std::max<size_t>(H->gram_tiles.size(), 1)));
+    LR_CHECK(grow((void**)&H->T, &H->cap_T, sizeof(double) * kLrCols * kLrCols * std::max<size_t>(nl, 1)));
+    LR_CHECK(grow((void**)&H->xn, &H->cap_xn, sizeof(double) * std::max<size_t>(H->row_tiles.size(), 1)));
+    LR_CHECK(grow((void**)&H->qn, &H->cap_qn, sizeof(double) * kLrCols * std::max<size_t>(H->q_chunks.size(), 1)));
+    if (nl) {
+        LR_CHECK(hipMemcpyAsync(H->d_layers, H->layers.data(), sizeof(LrLayer) * nl, hipMemcpyHostToDevice, s));
+        size_t o = 0;
+        for (auto* v : {&H->row_tiles, &H->col_tiles, &H->gram_tiles, &H->q_chunks}) {
+            if (!v->empty())
+                LR_CHECK(hipMemcpyAsync(H->d_tiles + o, v->data(), sizeof(LrTile) * v->size(),
+                                        hipMemcpyHostToDevice, s));
+            o += v->size();
+        }
+        LR_CHECK(hipStreamSynchronize(s));
+    }
+    H->sig = std::move(sig);
+    return hipSuccess;
+}
+
+static void lr_fill_params(LrHost* H, LrParams* p) {
+    p->layers = H->d_layers;
+    p->row_tiles = H->d_tiles;
+    p->col_tiles = p->row_tiles + H->row_tiles.size();
+    p->gram_tiles = p->col_tiles + H->col_tiles.size();
+    p->q_chunks = p->gram_tiles + H->gram_tiles.size();
+    p->P = H->P;
+    p->Q = H->Q;
+    p->part = H->part;
+    p->gram_part = H->gram;
+    p->T = H->T;
+    p->xnorm_part = H->xn;
+    p->qnorm_part = H->qn;
+}
+
+static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStream_t s) {
+    {
+        Section sec(tm, "lowrank_gemm_p");
+        hipLaunchKernelGGL(lr_gemm1_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+        LR_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "lowrank_orth");
+        hipLaunchKernelGGL(lr_gram_kernel, dim3((unsigned)H->gram_tiles.size()), dim3(256), 0, s, p);
+        LR_CHECK(hipGetLastError());
+        const size_t orth_lds = 2 * sizeof(double) * kLrCols * (kLrCols + 1);
+        LR_CHECK(hipFuncSetAttribute((const void*)lr_orth_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)orth_lds));
+        hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(64), orth_lds, s, p);
+        LR_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+        LR_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "lowrank_gemm_q");
+        hipLaunchKernelGGL(lr_gemm2_kernel, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
+        LR_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "lowrank_q_reduce");
+        hipLaunchKernelGGL(lr_qreduce_kernel, dim3((unsigned)H->q_chunks.size()), dim3(256), 0, s, p);
+        LR_CHECK(hipGetLastError());
+    }
+    return hipSuccess;
+}
+
+hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                           const DevLayer* h_layers, int L, const float* q0, int r_max, const int* rank,
+                           const int* col, int nlr, double* d_errors, int stride, Timing* tm, hipStream_t s) {
+    (void)d_layers;
+    LrHost* H = (LrHost*)t->host;
+    std::vector<int> ranks(L, kLrCols);
+    std::vector<DevLayer> hl(h_layers, h_layers + L);
+    for (auto& d : hl) d.payload = 0;                 // not part of the profile's signature
+    LR_CHECK(lr_prepare(t, hl.data(), L, ranks.data(), r_max, s));
+    if (H->layers.empty()) return hipSuccess;
+    LrParams p{};
+    lr_fill_params(H, &p);
+    p.g = g;
+    p.e = e;
+    p.q0 = q0;
+    p.r_max = r_max;
+    p.errors = d_errors;
+    p.stride = stride;
+    p.nrank = nlr;
+    for (int c = 0; c < nlr; ++c) { p.rank[c] = rank[c]; p.col[c] = col[c]; }
+    LR_CHECK(lr_factorize(H, p, tm, s));
+    Section sec(tm, "lowrank_errors");
+    hipLaunchKernelGGL(lr_errors_kernel, dim3((unsigned)H->layers.size()), dim3(64), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                            const DevLayer* h_layers, int L, float* q, int r_max, uint8_t* payload, Timing* tm,
+                            hipStream_t s) {
+    (void)d_layers;
+    LrHost* H = (LrHost*)t->host;
+    std::vector<int> ranks(L, 0);
+    for (int l = 0; l < L; ++l)
+        if (h_layers[l].family == LGRECO_LOWRANK) ranks[l] = h_layers[l].iparam;
+    LR_CHECK(lr_prepare(t, h_layers, L, ranks.data(), r_max, s));
+    if (H->layers.empty()) return hipSuccess;
+    LrParams p{};
+    lr_fill_params(H, &p);
+    p.g = g;
+    p.e = e;
+    p.e_out = e;
+    p.q0 = q;
+    p.q_out = q;
+    p.r_max = r_max;
+    p.payload = payload;
+    LR_CHECK(lr_factorize(H, p, tm, s));
+    Section sec(tm, "lowrank_ef");
+    hipLaunchKernelGGL(lr_ef_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+    return hipGetLastError();
 }
 
 }  // namespace lgreco

@@ -228,19 +228,32 @@ def layout(w: Workload, tensors: Optional[Sequence[int]] = None):
             np.asarray(tix, np.int64), raw)
 
 
-def generate(w: Workload, tensors: Optional[Sequence[int]] = None) -> Batch:
-    """Draw the whole workload (or the listed tensors of it) into one flat buffer."""
+def generate(w: Workload, tensors: Optional[Sequence[int]] = None, threads: int = 1) -> Batch:
+    """Draw the whole workload (or the listed tensors of it) into one flat buffer.  Tensors have
+    independent streams, so `threads` > 1 only changes how long this takes."""
     idx = list(range(len(w.shapes))) if tensors is None else list(tensors)
     total, offs, numels, rows, cols, tix, raw = layout(w, idx)
     grads = np.empty(total, np.float32)
     ef = None if w.ef == "none" else np.empty(total, np.float32)
-    pos = 0
+    starts, pos = [], 0
     for t in idx:
-        g, e = draw_tensor(w, t)
-        grads[pos:pos + g.size] = g
+        starts.append(pos)
+        pos += int(np.prod(w.shapes[t]))
+
+    def fill(j):
+        g, e = draw_tensor(w, idx[j])
+        grads[starts[j]:starts[j] + g.size] = g
         if ef is not None:
-            ef[pos:pos + g.size] = e
-        pos += g.size
+            ef[starts[j]:starts[j] + g.size] = e
+
+    if threads > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        order = sorted(range(len(idx)), key=lambda j: -int(np.prod(w.shapes[idx[j]])))
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, order))
+    else:
+        for j in range(len(idx)):
+            fill(j)
     b = Batch(grads, ef, offs, numels, rows, cols, tix, raw)
     if any(f == LOWRANK for f, _ in w.candidates):
         qs, qo, qpos = [], [], 0
