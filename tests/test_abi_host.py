@@ -1,0 +1,80 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and its host-only entry points (sizes, budget, payload layout, status text) agree with the
+oracle's formulas.  No GPU needed."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import pipeline, solver
+from paper_2210_17357_amd import binding as B
+from paper_2210_17357_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2210_17357_amd import build
+        build.build()
+    return B.lib()
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "lgreco.h")).read()
+    declared = set(re.findall(r"\b(lgreco_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_header():
+    import ctypes as C
+    assert C.sizeof(B.Layer) == 24 and C.sizeof(B.Cand) == 16 and C.sizeof(B.Config) == 24
+
+
+@pytest.mark.parametrize("name", W.WORKLOADS)
+def test_sizes_match_oracle_formulas(lib, name):
+    w = W.workload(name)
+    total, offs, numels, rows, cols, tix, raw = W.layout(w)
+    layers = B.layer_table(offs, numels, rows, cols)
+    ctab = B.cand_table(list(w.candidates))
+    got = B.sizes(layers, ctab, w.bucket)
+    assert np.array_equal(got, pipeline.sizes_table(numels, rows, cols, list(w.candidates), w.bucket))
+
+
+def test_emax_and_layout_and_errors(lib):
+    errors = np.random.default_rng(0).random((9, 4))
+    assert B.emax(errors, 2) == solver.e_max_uniform(errors, 2)
+    layers = B.layer_table([0, 1000, 5000], [1000, 4000, 130], [0, 40, 0], [0, 100, 0])
+    cands = B.cand_table([(B.QUANT, 3), (B.TOPK, 0.01), (B.LOWRANK, 4)])
+    off = B.payload_layout(layers, cands, np.array([0, 2, 1], np.int32))
+    s = B.sizes(B.layer_table([0, 1000, 5000], [1000, 4000, 130], [0, 40, 0], [0, 100, 0]),
+                B.cand_table([(B.QUANT, 3), (B.TOPK, 0.01)]))
+    assert off[0] == 0 and off[1] == (s[0, 0] + 15) // 16 * 16
+    assert off[2] == off[1] + (4 * 140 * 4 + 15) // 16 * 16 and off[3] == off[2] + 16
+    with pytest.raises(B.LgrecoError):         # low rank on a tensor without a matrix view
+        B.payload_layout(layers, cands, np.array([2, 2, 1], np.int32))
+    with pytest.raises(B.LgrecoError):         # choice out of range
+        B.payload_layout(layers, cands, np.array([0, 3, 1], np.int32))
+    for bad in ([(B.QUANT, 0)], [(B.QUANT, 9)], [(B.QUANT, 2.5)], [(B.TOPK, 0.0)], [(B.TOPK, 1.5)], [(7, 1.0)]):
+        with pytest.raises(B.LgrecoError):
+            B.sizes(layers, B.cand_table(bad))
+    with pytest.raises(B.LgrecoError):
+        B.emax(errors, 4)
+    assert "budget" in B.strerror(B.EINFEASIBLE) and B.strerror(0) == "ok"
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2210_17357_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+                assert "oracle/" not in text and "oracle." not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2210_17357_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
