@@ -72,6 +72,9 @@ struct TopkScratch {
     int64_t* d_cand_base = nullptr;   // [max_layers] first candidate slot of every layer
     void* d_tilecnt = nullptr;        // per tile (above, equal) counts (compress)
     void* d_tilebase = nullptr;       // per tile exclusive prefix of those counts
+    void* d_tinfo = nullptr;          // per tile candidate counts
+    uint32_t* d_ref = nullptr;        // refinement histograms (counts and integer energies)
+    size_t ref_words = 0;
     uint32_t* h_k = nullptr;          // pinned
     int64_t* h_cand_base = nullptr;   // pinned
     int64_t max_elems = 0;
@@ -89,8 +92,8 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
                        const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
                        int stride, Timing* tm, hipStream_t s);
 // exact thresholds; adds the candidate lists' dropped energy to errors (if not null)
-hipError_t topk_finalize(TopkScratch* t, int L, int ntk, const int* col, double* d_errors, int stride,
-                         Timing* tm, hipStream_t s);
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
+                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
                          Timing* tm, hipStream_t s);

@@ -9,26 +9,31 @@
 //      many entries must still be taken inside that bin;
 //   3. pass B over the data: energy of everything below the lowest threshold bin in registers;
 //      the few elements at or above it are staged in LDS and handled densely: energy below
-//      each threshold bin, and the bit patterns of the threshold bins' elements appended to
-//      per-bin candidate lists (one global atomic per tile and list);
-//   4. finalize: exact radix select (10 + 9 remaining bits) inside each candidate list gives the
-//      exact k-th magnitude, the number of equal magnitudes to keep, and the energy of the
-//      list's dropped part in exact integer arithmetic (entries of one list share the
-//      exponent, so sum of squared 24-bit significands is an integer): results do not depend
-//      on the order the atomics appended the candidates in.
-// Compression then counts kept entries per tile, scans the tile counts, and writes values and
-// indices in ascending index order (equal magnitudes: lowest indices first).
+//      each threshold bin, and the bit patterns of the threshold bins' elements ("candidates")
+//      written to the tile's own slice of a candidate buffer, grouped by bin, with the
+//      per-tile counts alongside (no global atomics: a tile cannot have more candidates than
+//      elements, so the slices never collide);
+//   4. refinement on the candidates only (about 1 % of the data per density): histogram of
+//      the next 10 bits, pick the sub-bin, histogram of the last 9 bits, pick the exact k-th
+//      magnitude and the number of equal magnitudes to keep.  Histograms carry the energy of
+//      each bin as an integer (entries of one candidate list share the exponent, so
+//      x^2 = m^2 2^(2(E-150)) with m the 24-bit significand; sum (m^2 >> 16) is exact integer
+//      arithmetic), so the dropped energy does not depend on the order the candidates were
+//      written or accumulated in.
+// Compression then counts kept entries per tile from the candidates, scans the tile counts, and
+// writes values and indices in ascending index order (equal magnitudes: lowest indices first).
 #include "internal.h"
 
 namespace lgreco {
 
 struct TopkList {
-    uint32_t bin, count, offset, cursor;
+    uint32_t bin, count;
 };
 struct TopkSel {
     uint32_t k, tbin, need, list;   // need: entries to take from the threshold bin (1..count)
+    uint32_t bin_a, need_a;         // refinement level A (bits 18..9)
     uint32_t thr, ties_keep;        // exact threshold pattern; equal entries kept
-    uint32_t pad0, pad1;
+    unsigned long long energy_a;    // integer energy of the list's entries below bin_a
 };
 struct TopkLayer {
     int64_t cand_base;              // first slot of this layer's region in the candidate buffer
@@ -36,6 +41,16 @@ struct TopkLayer {
     TopkList lists[kMaxTopk];
     TopkSel sel[kMaxTopk];
 };
+// per tile: candidates of each list (written list after list into the tile's slice), and the
+// number of elements above the first threshold bin (used by the compressor)
+struct TopkTileInfo {
+    uint32_t cnt[kMaxTopk];
+    uint32_t above;
+    uint32_t pad[3];
+};
+constexpr int kRefSplits = 128;     // workgroups per layer in the refinement passes
+constexpr int kBinsA = 1024, kBinsB = 512;
+constexpr int kRefThreads = 1024;   // refinement workgroup: one tile per wavefront in flight
 
 // ------------------------------------------------------------------------ block helpers
 // Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
@@ -164,19 +179,21 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
             S.need = k - s_res[1];
             S.thr = 0;
             S.ties_keep = 0;
+            S.bin_a = 0;
+            S.need_a = 0;
+            S.energy_a = 0;
         }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        uint32_t nl = 0, off = 0, mn = 0xFFFFFFFFu;
+        uint32_t nl = 0, mn = 0xFFFFFFFFu;
         for (int j = 0; j < ntk; ++j) {
             TopkSel& S = T.sel[j];
             uint32_t u = nl;
             for (uint32_t q = 0; q < nl; ++q)
                 if (T.lists[q].bin == S.tbin) u = q;
             if (u == nl) {
-                T.lists[nl] = TopkList{S.tbin, s_hist[S.tbin], off, 0u};
-                off += s_hist[S.tbin];
+                T.lists[nl] = TopkList{S.tbin, s_hist[S.tbin]};
                 ++nl;
             }
             S.list = u;
@@ -196,6 +213,7 @@ struct PassBParams {
     const Tile* tiles;
     TopkLayer* tl;
     uint32_t* cand;
+    TopkTileInfo* tinfo;
     double* partials;       // may be null (compress: no energies)
     int32_t stride;
     int32_t ntk;
@@ -205,7 +223,8 @@ struct PassBParams {
 __global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
     __shared__ uint32_t s_stage[kTile];
     __shared__ uint32_t s_wn[kThreads / 64];
-    __shared__ uint32_t s_cnt[kMaxTopk], s_cnt2[kMaxTopk], s_gbase[kMaxTopk];
+    __shared__ uint32_t s_cnt[kMaxTopk], s_cnt2[kMaxTopk], s_pre[kMaxTopk];
+    __shared__ uint32_t s_above[kThreads / 64];
     __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
     __shared__ double s_red[kThreads / 64][kMaxTopk + 1];
 
@@ -268,6 +287,7 @@ __global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
 
     // dense handling of the staged elements (key >= lowest threshold bin)
     float extra[kMaxTopk];
+    uint32_t above = 0;
 #pragma unroll
     for (int j = 0; j < kMaxTopk; ++j) extra[j] = 0.0f;
     for (int w = 0; w < kThreads / 64; ++w) {
@@ -280,25 +300,35 @@ __global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
 #pragma unroll
             for (int j = 0; j < kMaxTopk; ++j)
                 if (j < p.ntk && key < s_tbin[j]) extra[j] += x2;
+            above += key > s_tbin[0];
             for (uint32_t u = 0; u < nlists; ++u)
                 if (key == s_bin[u]) atomicAdd(&s_cnt[u], 1u);
         }
     }
+    for (int o = 1; o < 64; o <<= 1) above += __shfl_xor(above, o, 64);
+    if (lane == 0) s_above[wave] = above;
     __syncthreads();
-    if (tid < (int)nlists && s_cnt[tid])
-        s_gbase[tid] = atomicAdd(&T.lists[tid].cursor, s_cnt[tid]);
+    if (tid == 0) {
+        TopkTileInfo ti{};
+        uint32_t run = 0;
+        for (uint32_t u = 0; u < kMaxTopk; ++u) {
+            s_pre[u] = run;
+            ti.cnt[u] = u < nlists ? s_cnt[u] : 0u;
+            run += ti.cnt[u];
+        }
+        ti.above = s_above[0] + s_above[1] + s_above[2] + s_above[3];
+        p.tinfo[blockIdx.x] = ti;
+    }
     __syncthreads();
-    uint32_t* const cand = p.cand + T.cand_base;
+    // the tile's slice of the candidate buffer starts at its own first element
+    uint32_t* const cand = p.cand + T.cand_base + t.pos;
     for (int w = 0; w < kThreads / 64; ++w) {
         const uint32_t* const ws = s_stage + w * (kTile / (kThreads / 64));
         for (uint32_t i = tid; i < s_wn[w]; i += kThreads) {
             const uint32_t pat = ws[i];
             const uint32_t key = pat >> kHistShift;
             for (uint32_t u = 0; u < nlists; ++u)
-                if (key == s_bin[u]) {
-                    const uint32_t r = atomicAdd(&s_cnt2[u], 1u);
-                    cand[T.lists[u].offset + s_gbase[u] + r] = pat;
-                }
+                if (key == s_bin[u]) cand[s_pre[u] + atomicAdd(&s_cnt2[u], 1u)] = pat;
         }
     }
 
@@ -321,138 +351,254 @@ __global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
     }
 }
 
-struct FinalizeParams {
+struct RefineParams {
     TopkLayer* tl;
+    const DevLayer* layers;
+    const Tile* tiles;
+    const TopkTileInfo* tinfo;
     const uint32_t* cand;
-    double* errors;          // may be null (compress)
+    uint32_t* hist_a;                 // [L x kMaxTopk x kBinsA] counts per list
+    unsigned long long* en_a;         // same shape, integer energies
+    uint32_t* hist_b;                 // [L x kMaxTopk x kBinsB] per requested k
+    unsigned long long* en_b;
+    double* errors;                   // may be null (compress)
     int32_t stride;
     int32_t ntk;
     int32_t col[kMaxTopk];
 };
 
-// One workgroup per (layer, candidate list): exact selection inside the list.
-__global__ __launch_bounds__(256) void topk_finalize_kernel(FinalizeParams p) {
-    __shared__ uint32_t s_hist[1024];
+__device__ __forceinline__ uint32_t tile_candidates(const TopkTileInfo& ti, uint32_t nlists) {
+    uint32_t n = 0;
+    for (uint32_t u = 0; u < kMaxTopk; ++u) n += u < nlists ? ti.cnt[u] : 0u;
+    return n;
+}
+
+__device__ __forceinline__ unsigned long long int_energy(uint32_t pat) {
+    const unsigned long long m = (pat & 0x7FFFFFu) | ((pat >> 23) ? 0x800000u : 0u);
+    return (m * m) >> 16;
+}
+
+// Refinement level A: histogram (count, energy) of bits 18..9 of every candidate, per list.
+// Workgroup (layer, split) walks its share of the layer's tiles.
+__global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
+    extern __shared__ unsigned char refine_smem[];
+    const int l = blockIdx.x / kRefSplits, sp = blockIdx.x % kRefSplits;
+    const TopkLayer& T = p.tl[l];
+    const uint32_t nlists = T.nlists;
+    if (nlists == 0) return;
+    const DevLayer L = p.layers[l];
+    const int ntiles = L.tile_end - L.tile_begin;
+    // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
+    // costs less than filling it
+    const int per = max(48, (ntiles + kRefSplits - 1) / kRefSplits);
+    const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
+    if (t0 >= t1) return;
+    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
+    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
+    __shared__ uint32_t s_bin[kMaxTopk];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
+    if (tid < kMaxTopk) s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
+    __syncthreads();
+    // one wavefront per tile; the next tile's counts are fetched while this one is processed, and
+    // each lane keeps 8 candidate loads in flight
+    const int lane = tid & 63;
+    int t = t0 + (tid >> 6);
+    uint32_t n_next = 0;
+    int64_t pos_next = 0;
+    if (t < t1) { n_next = tile_candidates(p.tinfo[t], nlists); pos_next = p.tiles[t].pos; }
+    for (; t < t1; t += kRefThreads / 64) {
+        const uint32_t n = n_next;
+        const uint32_t* __restrict__ items = p.cand + T.cand_base + pos_next;
+        if (t + kRefThreads / 64 < t1) { n_next = tile_candidates(p.tinfo[t + kRefThreads / 64], nlists); pos_next = p.tiles[t + kRefThreads / 64].pos; }
+        for (uint32_t i0 = 0; i0 < n; i0 += 64 * 8) {
+            uint32_t pat[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                pat[q] = i < n ? items[i] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (pat[q] == 0xFFFFFFFFu) continue;
+                const uint32_t key = pat[q] >> kHistShift;
+                uint32_t u = 0;
+                for (uint32_t r = 1; r < nlists; ++r)
+                    if (key == s_bin[r]) u = r;
+                const uint32_t b = u * kBinsA + ((pat[q] >> 9) & (kBinsA - 1));
+                atomicAdd(&s_cnt[b], 1u);
+                atomicAdd(&s_en[b], int_energy(pat[q]));
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* const gh = p.hist_a + (size_t)l * kMaxTopk * kBinsA;
+    unsigned long long* const ge = p.en_a + (size_t)l * kMaxTopk * kBinsA;
+    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) {
+        const uint32_t c = s_cnt[i];
+        if (c) {
+            atomicAdd(&gh[i], c);
+            atomicAdd(&ge[i], s_en[i]);
+        }
+    }
+}
+
+// One workgroup per (layer, requested k): sub-bin of level A holding the k-th magnitude.
+__global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
+    __shared__ uint32_t s_hist[kBinsA];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
-    __shared__ unsigned long long s_lo, s_hi;
-    const int l = blockIdx.x / kMaxTopk;
-    const uint32_t u = blockIdx.x % kMaxTopk;
+    __shared__ unsigned long long s_e;
+    const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
-    if (u >= T.nlists) return;
-    const TopkList list = T.lists[u];
-    const uint32_t* __restrict__ items = p.cand + T.cand_base + list.offset;
-    const uint32_t n = list.count;
+    if (j >= p.ntk || T.sel[j].k == 0) return;
+    const TopkSel S = T.sel[j];
+    const uint32_t* gh = p.hist_a + ((size_t)l * kMaxTopk + S.list) * kBinsA;
+    const unsigned long long* ge = p.en_a + ((size_t)l * kMaxTopk + S.list) * kBinsA;
     const int tid = threadIdx.x;
-    for (int j = 0; j < p.ntk; ++j) {
-        const TopkSel S = T.sel[j];
-        if (S.k == 0 || S.list != u) continue;           // uniform across the block
-        // level A: bits 18..9 of the pattern
-        for (int b = tid; b < 1024; b += 256) s_hist[b] = 0;
-        __syncthreads();
-        for (uint32_t i = tid; i < n; i += 256) atomicAdd(&s_hist[(items[i] >> 9) & 1023u], 1u);
-        __syncthreads();
-        block_kth_from_top(s_hist, 1024, S.need, s_scan, s_res);
-        const uint32_t bin_a = s_res[0];
-        const uint32_t need_a = S.need - s_res[1];
-        __syncthreads();
-        // level B: bits 8..0 among the entries of bin_a
-        for (int b = tid; b < 512; b += 256) s_hist[b] = 0;
-        __syncthreads();
-        for (uint32_t i = tid; i < n; i += 256) {
-            const uint32_t pat = items[i];
-            if (((pat >> 9) & 1023u) == bin_a) atomicAdd(&s_hist[pat & 511u], 1u);
+    for (int b = tid; b < kBinsA; b += 256) s_hist[b] = gh[b];
+    if (tid == 0) s_e = 0;
+    __syncthreads();
+    block_kth_from_top(s_hist, kBinsA, S.need, s_scan, s_res);
+    const uint32_t bin_a = s_res[0];
+    unsigned long long e = 0;
+    for (uint32_t b = tid; b < bin_a; b += 256) e += ge[b];
+    atomicAdd(&s_e, e);
+    __syncthreads();
+    if (tid == 0) {
+        T.sel[j].bin_a = bin_a;
+        T.sel[j].need_a = S.need - s_res[1];
+        T.sel[j].energy_a = s_e;
+    }
+}
+
+// Refinement level B: histogram of bits 8..0 of the candidates inside each k's level-A sub-bin.
+__global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams p) {
+    extern __shared__ unsigned char refine_smem[];
+    const int l = blockIdx.x / kRefSplits, sp = blockIdx.x % kRefSplits;
+    const TopkLayer& T = p.tl[l];
+    const uint32_t nlists = T.nlists;
+    if (nlists == 0) return;
+    const DevLayer L = p.layers[l];
+    const int ntiles = L.tile_end - L.tile_begin;
+    // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
+    // costs less than filling it
+    const int per = max(48, (ntiles + kRefSplits - 1) / kRefSplits);
+    const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
+    if (t0 >= t1) return;
+    const int ntk = p.ntk;
+    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
+    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)ntk * kBinsB);
+    __shared__ uint32_t s_prefix[kMaxTopk];      // top 22 bits (coarse bin, level-A bin) of each k
+    const int tid = threadIdx.x;
+    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
+    if (tid < kMaxTopk)
+        s_prefix[tid] = (tid < ntk && T.sel[tid].k) ? ((T.sel[tid].tbin << 10) | T.sel[tid].bin_a) : 0xFFFFFFFFu;
+    __syncthreads();
+    const int lane = tid & 63;
+    int t = t0 + (tid >> 6);
+    uint32_t n_next = 0;
+    int64_t pos_next = 0;
+    if (t < t1) { n_next = tile_candidates(p.tinfo[t], nlists); pos_next = p.tiles[t].pos; }
+    for (; t < t1; t += kRefThreads / 64) {
+        const uint32_t n = n_next;
+        const uint32_t* __restrict__ items = p.cand + T.cand_base + pos_next;
+        if (t + kRefThreads / 64 < t1) { n_next = tile_candidates(p.tinfo[t + kRefThreads / 64], nlists); pos_next = p.tiles[t + kRefThreads / 64].pos; }
+        for (uint32_t i0 = 0; i0 < n; i0 += 64 * 8) {
+            uint32_t pat[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t i = i0 + q * 64 + lane;
+                pat[q] = i < n ? items[i] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (pat[q] == 0xFFFFFFFFu) continue;
+                const uint32_t pre = pat[q] >> 9;
+                for (int j = 0; j < ntk; ++j)
+                    if (pre == s_prefix[j]) {
+                        atomicAdd(&s_cnt[j * kBinsB + (pat[q] & (kBinsB - 1))], 1u);
+                        atomicAdd(&s_en[j * kBinsB + (pat[q] & (kBinsB - 1))], int_energy(pat[q]));
+                    }
+            }
         }
-        __syncthreads();
-        block_kth_from_top(s_hist, 512, need_a, s_scan, s_res);
-        const uint32_t bin_b = s_res[0];
-        const uint32_t ties_keep = need_a - s_res[1];
+    }
+    __syncthreads();
+    uint32_t* const gh = p.hist_b + (size_t)l * kMaxTopk * kBinsB;
+    unsigned long long* const ge = p.en_b + (size_t)l * kMaxTopk * kBinsB;
+    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) {
+        const uint32_t c = s_cnt[i];
+        if (c) {
+            atomicAdd(&gh[i], c);
+            atomicAdd(&ge[i], s_en[i]);
+        }
+    }
+}
+
+// One workgroup per (layer, requested k): exact threshold, equal entries kept, dropped energy.
+__global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
+    __shared__ uint32_t s_hist[kBinsB];
+    __shared__ uint32_t s_scan[256];
+    __shared__ uint32_t s_res[2];
+    __shared__ unsigned long long s_e;
+    const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
+    TopkLayer& T = p.tl[l];
+    if (j >= p.ntk || T.sel[j].k == 0) return;
+    const TopkSel S = T.sel[j];
+    const uint32_t* gh = p.hist_b + ((size_t)l * kMaxTopk + j) * kBinsB;
+    const unsigned long long* ge = p.en_b + ((size_t)l * kMaxTopk + j) * kBinsB;
+    const int tid = threadIdx.x;
+    for (int b = tid; b < kBinsB; b += 256) s_hist[b] = gh[b];
+    if (tid == 0) s_e = 0;
+    __syncthreads();
+    block_kth_from_top(s_hist, kBinsB, S.need_a, s_scan, s_res);
+    const uint32_t bin_b = s_res[0];
+    unsigned long long e = 0;
+    for (uint32_t b = tid; b < bin_b; b += 256) e += ge[b];
+    atomicAdd(&s_e, e);
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t ties_keep = S.need_a - s_res[1];
         const uint32_t count_eq = s_hist[bin_b];
-        const uint32_t thr = (list.bin << kHistShift) | (bin_a << 9) | bin_b;
-        __syncthreads();
+        const uint32_t thr = (S.tbin << kHistShift) | (S.bin_a << 9) | bin_b;
+        T.sel[j].thr = thr;
+        T.sel[j].ties_keep = ties_keep;
         if (p.errors) {
-            // energy of the list's dropped part: entries below thr and the surplus equal entries.
-            // Entries of one list share the exponent field, so with m the 24-bit significand
-            // x^2 = m^2 * 2^(2 (max(E,1) - 150)) and the sum of m^2 is an exact integer.
-            if (tid == 0) { s_lo = 0; s_hi = 0; }
-            __syncthreads();
+            // entries of the list below the threshold, plus the surplus equal entries
+            const unsigned long long total = S.energy_a + s_e + (unsigned long long)(count_eq - ties_keep) * int_energy(thr);
             const uint32_t ex = thr >> 23;
-            const uint32_t implicit = ex ? 0x800000u : 0u;
-            unsigned long long lo = 0, hi = 0;
-            for (uint32_t i = tid; i < n; i += 256) {
-                const uint32_t pat = items[i];
-                if (pat < thr) {
-                    const unsigned long long m = (pat & 0x7FFFFFu) | implicit;
-                    const unsigned long long sq = m * m;
-                    lo += sq & 0xFFFFFFFFull;
-                    hi += sq >> 32;
-                }
-            }
-            if (tid == 0) {
-                const unsigned long long m = (thr & 0x7FFFFFu) | implicit;
-                const unsigned long long sq = m * m;
-                const unsigned long long dropped_eq = count_eq - ties_keep;
-                lo += (sq & 0xFFFFFFFFull) * dropped_eq;
-                hi += (sq >> 32) * dropped_eq;
-            }
-            atomicAdd(&s_lo, lo);
-            atomicAdd(&s_hi, hi);
-            __syncthreads();
-            if (tid == 0) {
-                const int sh = 2 * ((int)(ex ? ex : 1u) - 150);
-                const double v = ((double)s_hi * 4294967296.0 + (double)s_lo);
-                p.errors[(size_t)l * p.stride + p.col[j]] += ldexp(v, sh);
-            }
-            __syncthreads();
-        }
-        if (tid == 0) {
-            T.sel[j].thr = thr;
-            T.sel[j].ties_keep = ties_keep;
+            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + 16;
+            p.errors[(size_t)l * p.stride + p.col[j]] += ldexp((double)total, sh);
         }
     }
 }
 
 // ---------------------------------------------------------------- compression kernels
-// per tile: entries above the threshold, entries equal to it
-__global__ __launch_bounds__(kThreads) void topk_count_kernel(const float* __restrict__ g,
-                                                               const float* __restrict__ e,
-                                                               const DevLayer* __restrict__ layers,
-                                                               const Tile* __restrict__ tiles,
-                                                               const TopkLayer* __restrict__ tl,
-                                                               uint2* __restrict__ tilecnt) {
-    __shared__ uint32_t s_gt[kThreads / 64], s_eq[kThreads / 64];
+// per tile: entries above the threshold, entries equal to it (from the tile's candidates)
+__global__ __launch_bounds__(64) void topk_count_kernel(const DevLayer* __restrict__ layers,
+                                                         const Tile* __restrict__ tiles,
+                                                         const TopkLayer* __restrict__ tl,
+                                                         const TopkTileInfo* __restrict__ tinfo,
+                                                         const uint32_t* __restrict__ cand,
+                                                         uint2* __restrict__ tilecnt) {
     const Tile t = tiles[blockIdx.x];
     const DevLayer L = layers[t.layer];
     if (L.family != LGRECO_TOPK) return;
-    const uint32_t thr = tl[t.layer].sel[0].thr;
-    const float* gp = g + L.offset + t.pos;
-    const float* ep = e + L.offset + t.pos;
+    const TopkLayer& T = tl[t.layer];
+    const uint32_t thr = T.sel[0].thr;
+    const TopkTileInfo ti = tinfo[blockIdx.x];
+    const uint32_t* __restrict__ items = cand + T.cand_base + t.pos;
     uint32_t gt = 0, eq = 0;
-    auto consume = [&](float x) {
-        const uint32_t pat = mag_bits(x);
+    for (uint32_t i = threadIdx.x; i < ti.cnt[0]; i += 64) {
+        const uint32_t pat = items[i];
         gt += pat > thr;
         eq += pat == thr;
-    };
-    if (t.fast) {
-        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) {
-            const float4 a = reinterpret_cast<const float4*>(gp)[v];
-            const float4 b = reinterpret_cast<const float4*>(ep)[v];
-            consume(a.x + b.x); consume(a.y + b.y); consume(a.z + b.z); consume(a.w + b.w);
-        }
-    } else {
-        for (int i = threadIdx.x; i < t.count; i += kThreads) consume(gp[i] + ep[i]);
     }
     for (int o = 1; o < 64; o <<= 1) {
         gt += __shfl_xor(gt, o, 64);
         eq += __shfl_xor(eq, o, 64);
     }
-    if ((threadIdx.x & 63) == 0) { s_gt[threadIdx.x >> 6] = gt; s_eq[threadIdx.x >> 6] = eq; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t a = 0, b = 0;
-        for (int w = 0; w < kThreads / 64; ++w) { a += s_gt[w]; b += s_eq[w]; }
-        tilecnt[blockIdx.x] = make_uint2(a, b);
-    }
+    if (threadIdx.x == 0) tilecnt[blockIdx.x] = make_uint2(ti.above + gt, eq);
 }
 
 // per layer: exclusive prefix of the tile counts
@@ -582,6 +728,9 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_cand_base, sizeof(int64_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles));
+    TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
+    t->ref_words = (size_t)max_layers * kMaxTopk * (kBinsA + kBinsB) * 3;       // u32 + u64 per bin
+    TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
     TK_CHECK(hipHostMalloc(&t->h_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk, hipHostMallocDefault));
     TK_CHECK(hipHostMalloc(&t->h_cand_base, sizeof(int64_t) * (size_t)max_layers, hipHostMallocDefault));
     return hipSuccess;
@@ -595,6 +744,8 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_cand_base);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
+    (void)hipFree(t->d_tinfo);
+    (void)hipFree(t->d_ref);
     (void)hipHostFree(t->h_k);
     (void)hipHostFree(t->h_cand_base);
     *t = TopkScratch{};
@@ -640,6 +791,7 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
     p.tiles = d_tiles;
     p.tl = (TopkLayer*)t->d_tl;
     p.cand = t->d_cand;
+    p.tinfo = (TopkTileInfo*)t->d_tinfo;
     p.partials = d_partials;
     p.stride = stride;
     p.ntk = ntk;
@@ -652,17 +804,41 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
     return hipSuccess;
 }
 
-hipError_t topk_finalize(TopkScratch* t, int L, int ntk, const int* col, double* d_errors, int stride,
-                         Timing* tm, hipStream_t s) {
-    FinalizeParams p{};
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
+                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
+    RefineParams p{};
     p.tl = (TopkLayer*)t->d_tl;
+    p.layers = d_layers;
+    p.tiles = d_tiles;
+    p.tinfo = (const TopkTileInfo*)t->d_tinfo;
     p.cand = t->d_cand;
+    // refinement histograms of the layers in use: [counts A][counts B][energies A][energies B]
+    const size_t na = (size_t)L * kMaxTopk * kBinsA, nb = (size_t)L * kMaxTopk * kBinsB;
+    p.hist_a = t->d_ref;
+    p.hist_b = p.hist_a + na;
+    p.en_a = reinterpret_cast<unsigned long long*>(p.hist_b + nb);
+    p.en_b = p.en_a + na;
     p.errors = d_errors;
     p.stride = stride;
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
-    Section sec(tm, "topk_finalize");
-    hipLaunchKernelGGL(topk_finalize_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
+    Section sec(tm, "topk_refine");
+    const size_t words = (na + nb) * 3;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 4096)), dim3(256), 0, s,
+                       t->d_ref, words, 0u);
+    TK_CHECK(hipGetLastError());
+    const size_t lds_a = (size_t)kMaxTopk * kBinsA * 12, lds_b = (size_t)kMaxTopk * kBinsB * 12;
+    TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)lds_a));
+    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(L * kRefSplits), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
+    TK_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
+    TK_CHECK(hipGetLastError());
+    TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)lds_b));
+    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(L * kRefSplits), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
+    TK_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -681,11 +857,12 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         TK_CHECK(topk_hist(t, g, e, d_layers, d_tiles, n_tiles, s));
     }
     TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, nullptr, nullptr, 0, tm, s));
-    TK_CHECK(topk_finalize(t, L, 1, nullptr, nullptr, 0, tm, s));
+    TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
-        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, (const float*)e, d_layers,
-                           d_tiles, (const TopkLayer*)t->d_tl, (uint2*)t->d_tilecnt);
+        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(64), 0, s, d_layers, d_tiles,
+                           (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
+                           (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
         TK_CHECK(hipGetLastError());
     }
     {
