@@ -29,12 +29,6 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
-# algorithmic bytes per gradient element of each kernel (what the step must move, not what a
-# given implementation happens to move); b = mean chosen bits, d = mean chosen density
-ALGO_BYTES = {
-    "quant_profile": 8.0, "quant_profile_hist": 8.0, "topk_hist": 8.0, "topk_pass_b": 8.0,
-    "topk_count": 8.0,
-}
 
 
 def parse_args():
@@ -135,7 +129,8 @@ def main():
             phase["profile"] += t1 - t0
             phase["solve"] += t2 - t1
             phase["compress"] += t3 - t2
-            for name, ms in tm_p + tm_s + tm_c:
+            for name, ms in ([("profile/" + n, m) for n, m in tm_p] + [("solve/" + n, m) for n, m in tm_s]
+                             + [("compress/" + n, m) for n, m in tm_c]):
                 a = kern.setdefault(name, [0.0, 0])
                 a[0] += ms
                 a[1] += 1
@@ -160,31 +155,51 @@ def main():
     ntk = float(numels[fam == W.TOPK].sum())
     mean_bits = float((numels * par)[fam == W.QUANT].sum() / nq) if nq else 0.0
     mean_dens = float((numels * par)[fam == W.TOPK].sum() / ntk) if ntk else 0.0
-    algo = dict(ALGO_BYTES)
-    # per launch: bytes = per-element figure x elements the launch covers
-    elems = {k: float(N) for k in algo}
-    algo["quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
-    elems["quant_compress"] = nq
-    algo["topk_write"] = 12.0 + 8.0 * mean_dens
-    elems["topk_write"] = ntk
+    # algorithmic bytes per element and elements covered per launch, per timed section
+    algo, elems = {}, {}
+    for k in ("quant_profile", "quant_profile_hist", "topk_hist", "topk_pass_b"):
+        algo["profile/" + k], elems["profile/" + k] = 8.0, float(N)
+    for k in ("topk_hist", "topk_pass_b"):
+        algo["compress/" + k], elems["compress/" + k] = 8.0, ntk
+    algo["compress/quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
+    elems["compress/quant_compress"] = nq
+    algo["compress/topk_write"] = 12.0 + 8.0 * mean_dens
+    elems["compress/topk_write"] = ntk
+    nlr = float(numels[fam == W.LOWRANK].sum())
+    algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = 12.0, nlr
+    # dense contractions of the low-rank path: flops per launch (64 columns are computed per layer)
+    flops = {}
+    mn2d = float(sum(int(r) * int(c) for r, c in zip(batch.rows, batch.cols)))
+    if any(f == W.LOWRANK for f, _ in cands):
+        for k in ("lowrank_gemm_p", "lowrank_gemm_q"):
+            flops["profile/" + k] = 2.0 * mn2d * 64
+            flops["compress/" + k] = 2.0 * float(sum(int(r) * int(c) for r, c, f_ in
+                                                     zip(batch.rows, batch.cols, fam) if f_ == W.LOWRANK)) * 64
     kernels = {}
     for name, (ms, cnt) in kern.items():
         avg = ms / max(cnt, 1)
         entry = {"avg_ms": round(avg, 4), "launches": cnt}
-        if name in algo and avg > 0 and "." not in name:
+        if name in algo and avg > 0 and elems[name] > 0:
             gb = algo[name] * elems[name] / 1e9
             entry["algo_GB"] = round(gb, 4)
             entry["GBps"] = round(gb / (avg * 1e-3), 1)
+        if name in flops and avg > 0 and flops[name] > 0:
+            entry["TFLOPs"] = round(flops[name] / (avg * 1e-3) / 1e12, 2)
         kernels[name] = entry
-    timed = {k: v for k, v in kernels.items() if "GBps" in v}
+    timed = {k: v for k, v in kernels.items() if "GBps" in v or "TFLOPs" in v}
     roofline = None
     if timed:
         dom = max(timed, key=lambda k: timed[k]["avg_ms"])
-        ach = timed[dom]["GBps"]
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
-                    "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
-
+        if "TFLOPs" in timed[dom]:
+            ach = timed[dom]["TFLOPs"]
+            roofline = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                        "avg_ms": timed[dom]["avg_ms"]}
+        else:
+            ach = timed[dom]["GBps"]
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                        "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
     out = {
         "metric": "profile+solve+compress gradient GB/s at 1 MI355X",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

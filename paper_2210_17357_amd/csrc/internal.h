@@ -92,8 +92,8 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
                        const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
                        int stride, Timing* tm, hipStream_t s);
 // exact thresholds; adds the candidate lists' dropped energy to errors (if not null)
-hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
-                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int max_layer_tiles,
+                         int ntk, const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
                          Timing* tm, hipStream_t s);

@@ -28,7 +28,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kLrCols = 64;       // columns computed per layer (r_max <= 64)
 constexpr int kLrBM = 128;        // rows (GEMM1, reconstruction) / columns (GEMM2) per workgroup
 constexpr int kLrBK = 32;         // contraction chunk staged in LDS
-constexpr int kLrGramRows = 128;  // rows per Gram partial
+constexpr int kLrGramRows = 128;  // rows staged in LDS at a time by the Gram kernel
+constexpr int kLrGramSpan = 1024; // rows per Gram partial (one workgroup)
 constexpr int kLrQChunk = 64;     // Q rows per workgroup in the split-K reduction
 
 struct LrLayer {
@@ -205,29 +206,33 @@ __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
     const LrTile tile = p.gram_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
     const float* __restrict__ P = p.P + L.p_off;
-    const int row0 = tile.a0, nrows = min(kLrGramRows, L.rows - row0);
+    const int span_end = min(L.rows, tile.a0 + kLrGramSpan);
     const int tid = threadIdx.x;
-    for (int f = tid; f < kLrGramRows * kLrCols / 4; f += 256) {
-        const int r = f >> 4, c = (f & 15) * 4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
-        *reinterpret_cast<float4*>(&Pl[r][c]) = v;
-    }
-    __syncthreads();
     const int bi = (tid >> 4) * 4, bj = (tid & 15) * 4;
     double acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-    for (int r = 0; r < nrows; ++r) {
-        const float4 a = *reinterpret_cast<const float4*>(&Pl[r][bi]);
-        const float4 b = *reinterpret_cast<const float4*>(&Pl[r][bj]);
-        const double av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+    for (int row0 = tile.a0; row0 < span_end; row0 += kLrGramRows) {
+        const int nrows = min(kLrGramRows, span_end - row0);
+        __syncthreads();
+        for (int f = tid; f < kLrGramRows * kLrCols / 4; f += 256) {
+            const int r = f >> 4, c = (f & 15) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
+            *reinterpret_cast<float4*>(&Pl[r][c]) = v;
+        }
+        __syncthreads();
+        for (int r = 0; r < nrows; ++r) {
+            const float4 a = *reinterpret_cast<const float4*>(&Pl[r][bi]);
+            const float4 b = *reinterpret_cast<const float4*>(&Pl[r][bj]);
+            const double av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(av[i], bv[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(av[i], bv[j], acc[i][j]);
+        }
     }
     double* __restrict__ out = p.gram_part + (size_t)blockIdx.x * kLrCols * kLrCols;
 #pragma unroll
@@ -238,22 +243,30 @@ __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
 
 // ------------------------------------------------------------------ Gram-Schmidt coefficients
 // One wavefront per layer.  Lane j owns column j of the Gram matrix.
-__global__ __launch_bounds__(64) void lr_orth_kernel(LrParams p) {
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
     extern __shared__ double lr_orth_smem[];
     double (*G)[kLrCols + 1] = reinterpret_cast<double (*)[kLrCols + 1]>(lr_orth_smem);
     double (*Tm)[kLrCols + 1] = G + kLrCols;
     const LrLayer L = p.layers[blockIdx.x];
-    const int j = threadIdx.x;
-    for (int i = 0; i < kLrCols; ++i) {
+    // all 256 threads: G = sum of the layer's Gram partials, in partial order
+    for (int f = threadIdx.x; f < kLrCols * kLrCols; f += 256) {
         double s = 0.0;
-        for (int c = L.gram_begin; c < L.gram_end; ++c)
-            s += p.gram_part[(size_t)c * kLrCols * kLrCols + i * kLrCols + j];
-        G[i][j] = s;
-        Tm[i][j] = 0.0;
+        for (int c = L.gram_begin; c < L.gram_end; ++c) s += p.gram_part[(size_t)c * kLrCols * kLrCols + f];
+        G[f >> 6][f & 63] = s;
+        Tm[f >> 6][f & 63] = 0.0;
     }
     __syncthreads();
+    if (threadIdx.x >= 64) return;
+    // one wavefront from here on: lane j owns column j
+    const int j = threadIdx.x;
     const double diag0 = G[j][j];
-    __syncthreads();
+    wave_sync_lds();
     for (int i = 0; i < kLrCols; ++i) {
         const double d = G[i][i];
         const double d0 = __shfl(diag0, i, 64);
@@ -262,13 +275,13 @@ __global__ __launch_bounds__(64) void lr_orth_kernel(LrParams p) {
         const double inv = ok ? 1.0 / rii : 0.0;
         // row i of the triangular factor
         const double rij = (j >= i) ? ((j == i) ? rii : G[i][j] * inv) : 0.0;
-        __syncthreads();
+        wave_sync_lds();
         G[i][j] = rij;
-        __syncthreads();
+        wave_sync_lds();
         // eliminate: G[k][j] -= R[i][k] R[i][j] for i < k <= j
         for (int k = i + 1; k < kLrCols; ++k)
             if (k <= j) G[k][j] -= G[i][k] * rij;
-        __syncthreads();
+        wave_sync_lds();
     }
     // T = R^-1 by back substitution, column j; rows of zeroed columns stay zero
     for (int i = kLrCols - 1; i >= 0; --i) {
@@ -279,7 +292,7 @@ __global__ __launch_bounds__(64) void lr_orth_kernel(LrParams p) {
             Tm[i][j] = rii != 0.0 ? s / rii : 0.0;
         }
     }
-    __syncthreads();
+    wave_sync_lds();
     double* __restrict__ T = p.T + (size_t)blockIdx.x * kLrCols * kLrCols;
     for (int i = 0; i < kLrCols; ++i) T[i * kLrCols + j] = Tm[i][j];
 }
@@ -601,7 +614,7 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
         for (int c0 = 0; c0 < a.cols; c0 += kLrBM)
             for (int sp = 0; sp < a.splits; ++sp) H->col_tiles.push_back(LrTile{li, c0, sp, 0});
         a.gram_begin = (int)H->gram_tiles.size();
-        for (int r0 = 0; r0 < a.rows; r0 += kLrGramRows) H->gram_tiles.push_back(LrTile{li, r0, 0, 0});
+        for (int r0 = 0; r0 < a.rows; r0 += kLrGramSpan) H->gram_tiles.push_back(LrTile{li, r0, 0, 0});
         a.gram_end = (int)H->gram_tiles.size();
         a.qc_begin = (int)H->q_chunks.size();
         for (int c0 = 0; c0 < a.cols; c0 += kLrQChunk) H->q_chunks.push_back(LrTile{li, c0, 0, 0});
@@ -669,7 +682,7 @@ static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStre
         const size_t orth_lds = 2 * sizeof(double) * kLrCols * (kLrCols + 1);
         LR_CHECK(hipFuncSetAttribute((const void*)lr_orth_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)orth_lds));
-        hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(64), orth_lds, s, p);
+        hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(256), orth_lds, s, p);
         LR_CHECK(hipGetLastError());
         hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());

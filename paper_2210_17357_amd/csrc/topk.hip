@@ -50,6 +50,7 @@ struct TopkTileInfo {
 };
 constexpr int kRefSplits = 128;     // workgroups per layer in the refinement passes
 constexpr int kBinsA = 1024, kBinsB = 512;
+constexpr int kRefTilesMin = 48;    // tiles per refinement workgroup, at least
 constexpr int kRefThreads = 1024;   // refinement workgroup: one tile per wavefront in flight
 
 // ------------------------------------------------------------------------ block helpers
@@ -365,6 +366,7 @@ struct RefineParams {
     int32_t stride;
     int32_t ntk;
     int32_t col[kMaxTopk];
+    int32_t splits;                   // refinement workgroups per layer in this launch
 };
 
 __device__ __forceinline__ uint32_t tile_candidates(const TopkTileInfo& ti, uint32_t nlists) {
@@ -382,7 +384,7 @@ __device__ __forceinline__ unsigned long long int_energy(uint32_t pat) {
 // Workgroup (layer, split) walks its share of the layer's tiles.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
-    const int l = blockIdx.x / kRefSplits, sp = blockIdx.x % kRefSplits;
+    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
     const TopkLayer& T = p.tl[l];
     const uint32_t nlists = T.nlists;
     if (nlists == 0) return;
@@ -390,7 +392,7 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
     const int ntiles = L.tile_end - L.tile_begin;
     // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
     // costs less than filling it
-    const int per = max(48, (ntiles + kRefSplits - 1) / kRefSplits);
+    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
     const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
     if (t0 >= t1) return;
     unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
 // Refinement level B: histogram of bits 8..0 of the candidates inside each k's level-A sub-bin.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
-    const int l = blockIdx.x / kRefSplits, sp = blockIdx.x % kRefSplits;
+    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
     const TopkLayer& T = p.tl[l];
     const uint32_t nlists = T.nlists;
     if (nlists == 0) return;
@@ -483,7 +485,7 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams
     const int ntiles = L.tile_end - L.tile_begin;
     // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
     // costs less than filling it
-    const int per = max(48, (ntiles + kRefSplits - 1) / kRefSplits);
+    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
     const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
     if (t0 >= t1) return;
     const int ntk = p.ntk;
@@ -804,8 +806,8 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
     return hipSuccess;
 }
 
-hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
-                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int max_layer_tiles,
+                         int ntk, const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
     RefineParams p{};
     p.tl = (TopkLayer*)t->d_tl;
     p.layers = d_layers;
@@ -822,6 +824,7 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     p.stride = stride;
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
+    p.splits = std::max(1, std::min(kRefSplits, (max_layer_tiles + kRefTilesMin - 1) / kRefTilesMin));
     Section sec(tm, "topk_refine");
     const size_t words = (na + nb) * 3;
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 4096)), dim3(256), 0, s,
@@ -830,13 +833,13 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     const size_t lds_a = (size_t)kMaxTopk * kBinsA * 12, lds_b = (size_t)kMaxTopk * kBinsB * 12;
     TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                  (int)lds_a));
-    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(L * kRefSplits), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
+    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(L * p.splits), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     TK_CHECK(hipGetLastError());
     TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                  (int)lds_b));
-    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(L * kRefSplits), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
+    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(L * p.splits), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     return hipGetLastError();
@@ -857,7 +860,10 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         TK_CHECK(topk_hist(t, g, e, d_layers, d_tiles, n_tiles, s));
     }
     TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, nullptr, nullptr, 0, tm, s));
-    TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
+    int max_tiles = 0;
+    for (int l = 0; l < L; ++l)
+        if (h_layers[l].family == LGRECO_TOPK) max_tiles = std::max(max_tiles, h_layers[l].tile_end - h_layers[l].tile_begin);
+    TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, max_tiles, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
         hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(64), 0, s, d_layers, d_tiles,
