@@ -31,6 +31,8 @@ constexpr int kLrBK = 32;         // contraction chunk staged in LDS
 constexpr int kLrGramRows = 128;  // rows staged in LDS at a time by the Gram kernel
 constexpr int kLrGramSpan = 1024; // rows per Gram partial (one workgroup)
 constexpr int kLrQChunk = 64;     // Q rows per workgroup in the split-K reduction
+constexpr int kLrPSplit = 512;    // columns contracted per workgroup in P = X Q0
+constexpr int kLrEfSpan = 512;    // columns reconstructed per workgroup
 
 struct LrLayer {
     int64_t offset;     // into g / e
@@ -41,7 +43,9 @@ struct LrLayer {
     int64_t payload;    // byte offset of the payload (compress)
     int32_t rows, cols;
     int32_t rank;       // columns written out (64 when profiling)
-    int32_t splits, ksplit;
+    int32_t splits, ksplit;         // split of the row contraction of Q = X^T Phat
+    int32_t psplits, pksplit;       // split of the column contraction of P = X Q0
+    int64_t ppart_off;              // into the P partial buffer (psplits x rows x 64) when psplits > 1
     int32_t gram_begin, gram_end;   // Gram partial range
     int32_t rt_begin, rt_end;       // row-tile range (||X||^2 partials)
     int32_t qc_begin, qc_end;       // Q-chunk range (column-norm partials)
@@ -61,13 +65,16 @@ struct LrParams {
     float* q_out;            // compress: new Q (stride r_max), same buffer as q0
     int32_t r_max;
     const LrLayer* layers;
-    const LrTile* row_tiles;
+    const LrTile* row_tiles;   // 128-row tiles (orthogonalisation)
+    const LrTile* p_tiles;     // (128-row tile, column split) of P = X Q0
+    const LrTile* ef_tiles;    // (64-row tile, 512-column span) of the reconstruction
     const LrTile* col_tiles;
     const LrTile* gram_tiles;
     const LrTile* q_chunks;
     float* P;                // scratch [sum rows x 64]
     float* Q;                // scratch [sum cols x 64]
-    float* part;             // split-K partials
+    float* part;             // split-K partials of Q
+    float* ppart;            // split-K partials of P
     double* gram_part;       // [gram tiles x 64 x 64]
     double* T;               // [layers x 64 x 64]
     double* xnorm_part;      // [row tiles]
@@ -104,9 +111,10 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
     __shared__ float Xs[2][kLrBM][kLrBK + 1];
     __shared__ float Qs[2][kLrBK][kLrCols];
     __shared__ double s_red[4];
-    const LrTile tile = p.row_tiles[blockIdx.x];
+    const LrTile tile = p.p_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
     const int m = L.rows, n = L.cols, row0 = tile.a0;
+    const int kbeg = tile.split * L.pksplit, kend = min(n, kbeg + L.pksplit);
     const float* __restrict__ g = p.g + L.offset;
     const float* __restrict__ e = p.e ? p.e + L.offset : nullptr;
     const float* __restrict__ q = p.q0 + L.q_off;
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
             const int r = f >> 3, c = (f & 7) * 4;
             const int row = row0 + r, colk = k0 + c;
             xr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < m && colk < n) xr[s] = load_x4(g, e, (int64_t)row * n + colk, n - colk, vec);
+            if (row < m && colk < kend) xr[s] = load_x4(g, e, (int64_t)row * n + colk, kend - colk, vec);
             xsq = __builtin_fmaf(xr[s].x, xr[s].x, xsq);
             xsq = __builtin_fmaf(xr[s].y, xr[s].y, xsq);
             xsq = __builtin_fmaf(xr[s].z, xr[s].z, xsq);
@@ -135,7 +143,7 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
             const int kr = f >> 4, c = (f & 15) * 4;
             const int k = k0 + kr;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < n) {
+            if (k < kend) {
                 const float* src = q + (int64_t)k * p.r_max + c;
                 if (qvec && c + 3 < p.r_max) {
                     v = *reinterpret_cast<const float4*>(src);
@@ -166,14 +174,14 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
     };
 
     f32x16 acc0 = {0}, acc1 = {0};
-    const int nchunks = (n + kLrBK - 1) / kLrBK;
-    fetch(0);
+    const int nchunks = (kend - kbeg + kLrBK - 1) / kLrBK;
+    fetch(kbeg);
     stash(0);
     __syncthreads();
     const int ar = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) fetch((c + 1) * kLrBK);
+        if (c + 1 < nchunks) fetch(kbeg + (c + 1) * kLrBK);
 #pragma unroll
         for (int kk = 0; kk < kLrBK; kk += 2) {
             const float a = Xs[buf][ar][kk + ak];
@@ -185,7 +193,8 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
         if (c + 1 < nchunks) stash(buf ^ 1);
         __syncthreads();
     }
-    float* __restrict__ P = p.P + L.p_off;
+    float* __restrict__ P = L.psplits > 1 ? p.ppart + L.ppart_off + (int64_t)tile.split * m * kLrCols
+                                          : p.P + L.p_off;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int row = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -198,6 +207,25 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
     if (lane == 0) s_red[wave] = s;
     __syncthreads();
     if (tid == 0) p.xnorm_part[blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+// ------------------------------------------------------------------ P = sum of column-split partials
+__global__ __launch_bounds__(256) void lr_preduce_kernel(LrParams p) {
+    const LrTile tile = p.row_tiles[blockIdx.x];
+    const LrLayer L = p.layers[tile.layer];
+    if (L.psplits <= 1) return;
+    const int nrows = min(kLrBM, L.rows - tile.a0);
+    const float* __restrict__ part = p.ppart + L.ppart_off;
+    float* __restrict__ P = p.P + L.p_off;
+    for (int f = threadIdx.x; f < nrows * kLrCols / 4; f += 256) {
+        const int64_t idx = (int64_t)tile.a0 * kLrCols + (int64_t)f * 4;
+        float4 s = *reinterpret_cast<const float4*>(part + idx);
+        for (int sp = 1; sp < L.psplits; ++sp) {
+            const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)sp * L.rows * kLrCols + idx);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        *reinterpret_cast<float4*>(P + idx) = s;
+    }
 }
 
 // ------------------------------------------------------------------ partial Gram matrices
@@ -243,58 +271,70 @@ __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
 
 // ------------------------------------------------------------------ Gram-Schmidt coefficients
 // One wavefront per layer.  Lane j owns column j of the Gram matrix.
-__device__ __forceinline__ void wave_sync_lds() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+__device__ __forceinline__ double lane_value(double v, int lane) {      // v of a given lane, as a scalar
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
 __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
-    extern __shared__ double lr_orth_smem[];
-    double (*G)[kLrCols + 1] = reinterpret_cast<double (*)[kLrCols + 1]>(lr_orth_smem);
-    double (*Tm)[kLrCols + 1] = G + kLrCols;
+    __shared__ double G[kLrCols][kLrCols + 1];
     const LrLayer L = p.layers[blockIdx.x];
     // all 256 threads: G = sum of the layer's Gram partials, in partial order
-    for (int f = threadIdx.x; f < kLrCols * kLrCols; f += 256) {
-        double s = 0.0;
-        for (int c = L.gram_begin; c < L.gram_end; ++c) s += p.gram_part[(size_t)c * kLrCols * kLrCols + f];
-        G[f >> 6][f & 63] = s;
-        Tm[f >> 6][f & 63] = 0.0;
+    {
+        // 16 entries per thread, partials outermost: 16 independent loads in flight per step
+        double acc[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[q] = 0.0;
+        for (int c = L.gram_begin; c < L.gram_end; ++c) {
+            const double* __restrict__ src = p.gram_part + (size_t)c * kLrCols * kLrCols + threadIdx.x;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[q] += src[256 * q];
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int f = threadIdx.x + 256 * q;
+            G[f >> 6][f & 63] = acc[q];
+        }
     }
     __syncthreads();
     if (threadIdx.x >= 64) return;
-    // one wavefront from here on: lane j owns column j
+    // One wavefront from here on; lane j keeps column j in registers (every index below is a
+    // compile-time constant after unrolling, rows of other lanes come through readlane).
     const int j = threadIdx.x;
-    const double diag0 = G[j][j];
-    wave_sync_lds();
+    double col[kLrCols];
+#pragma unroll
+    for (int i = 0; i < kLrCols; ++i) col[i] = G[i][j];
+    double diag0 = 0.0;
+#pragma unroll
+    for (int i = 0; i < kLrCols; ++i) diag0 = (i == j) ? col[i] : diag0;
+#pragma unroll
     for (int i = 0; i < kLrCols; ++i) {
-        const double d = G[i][i];
-        const double d0 = __shfl(diag0, i, 64);
+        const double d = lane_value(col[i], i);
+        const double d0 = lane_value(diag0, i);
         const bool ok = d > 0.0 && d >= 1e-10 * d0;
         const double rii = ok ? sqrt(d) : 0.0;
         const double inv = ok ? 1.0 / rii : 0.0;
-        // row i of the triangular factor
-        const double rij = (j >= i) ? ((j == i) ? rii : G[i][j] * inv) : 0.0;
-        wave_sync_lds();
-        G[i][j] = rij;
-        wave_sync_lds();
-        // eliminate: G[k][j] -= R[i][k] R[i][j] for i < k <= j
-        for (int k = i + 1; k < kLrCols; ++k)
-            if (k <= j) G[k][j] -= G[i][k] * rij;
-        wave_sync_lds();
+        const double rij = (j >= i) ? ((j == i) ? rii : col[i] * inv) : 0.0;   // R[i][j]
+        col[i] = rij;
+        // eliminate: G[k][j] -= R[i][k] R[i][j]; rows k > j hold the unused lower triangle
+#pragma unroll
+        for (int k = i + 1; k < kLrCols; ++k) col[k] = __builtin_fma(-lane_value(rij, k), rij, col[k]);
     }
-    // T = R^-1 by back substitution, column j; rows of zeroed columns stay zero
+    // T = R^-1 by back substitution, column j; rows of zeroed columns stay zero.  col[i] = R[i][j].
+    double t[kLrCols];
+#pragma unroll
     for (int i = kLrCols - 1; i >= 0; --i) {
-        if (i <= j) {
-            double s = (i == j) ? 1.0 : 0.0;
-            for (int k = i + 1; k <= j; ++k) s -= G[i][k] * Tm[k][j];
-            const double rii = G[i][i];
-            Tm[i][j] = rii != 0.0 ? s / rii : 0.0;
-        }
+        double s = (i == j) ? 1.0 : 0.0;
+#pragma unroll
+        for (int k = i + 1; k < kLrCols; ++k) s = __builtin_fma(-lane_value(col[i], k), t[k], s);
+        const double rii = lane_value(col[i], i);
+        t[i] = (i <= j && rii != 0.0) ? s / rii : 0.0;
     }
-    wave_sync_lds();
     double* __restrict__ T = p.T + (size_t)blockIdx.x * kLrCols * kLrCols;
-    for (int i = 0; i < kLrCols; ++i) T[i * kLrCols + j] = Tm[i][j];
+#pragma unroll
+    for (int i = 0; i < kLrCols; ++i) T[i * kLrCols + j] = t[i];
 }
 
 // ------------------------------------------------------------------ Phat = P T
@@ -409,27 +449,49 @@ __global__ __launch_bounds__(256) void lr_gemm2_kernel(LrParams p) {
 // ------------------------------------------------------------------ Q = sum of partials, norms
 __global__ __launch_bounds__(256) void lr_qreduce_kernel(LrParams p) {
     __shared__ double s_n[4][kLrCols];
+    __shared__ float s_p[4][kLrCols];
     const LrTile tile = p.q_chunks[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
-    const int n = L.cols, c0 = tile.a0, nc = min(kLrQChunk, n - c0);
+    const int n = L.cols, c0 = tile.a0, nc = min(tile.split, n - c0);    // tile.split = rows of this chunk
     const float* __restrict__ part = p.part + L.part_off;
     float* __restrict__ Q = p.Q + L.qs_off;
-    const int tid = threadIdx.x, j = tid & 63;
+    const int tid = threadIdx.x, j = tid & 63, grp = tid >> 6;
     float* pay = nullptr;
     if (p.payload) pay = reinterpret_cast<float*>(p.payload + L.payload) + (int64_t)L.rows * L.rank;
     double norm = 0.0;
-    for (int r = tid >> 6; r < nc; r += 4) {
+    auto emit = [&](int r, float s) {
         const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
-        float s = 0.0f;
-        for (int sp = 0; sp < L.splits; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
         Q[idx] = s;
         norm = __builtin_fma((double)s, (double)s, norm);
         if (p.payload && j < L.rank) {
             pay[(int64_t)(c0 + r) * L.rank + j] = s;
             p.q_out[L.q_off + (int64_t)(c0 + r) * p.r_max + j] = s;
         }
+    };
+    if (L.splits <= 4) {
+        // few partials: one thread per (row, column), rows strided over the 4 wavefronts
+        for (int r = grp; r < nc; r += 4) {
+            const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
+            float s = 0.0f;
+            for (int sp = 0; sp < L.splits; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
+            emit(r, s);
+        }
+    } else {
+        // many partials: the 4 wavefronts share one row, each sums a contiguous quarter of the
+        // partials, and wavefront 0 adds the four sums in order
+        const int per = (L.splits + 3) / 4;
+        const int sp0 = grp * per, sp1 = min(L.splits, sp0 + per);
+        for (int r = 0; r < nc; ++r) {
+            const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
+            float s = 0.0f;
+            for (int sp = sp0; sp < sp1; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
+            s_p[grp][j] = s;
+            __syncthreads();
+            if (grp == 0) emit(r, ((s_p[0][j] + s_p[1][j]) + s_p[2][j]) + s_p[3][j]);
+            __syncthreads();
+        }
     }
-    s_n[tid >> 6][j] = norm;
+    s_n[grp][j] = norm;
     __syncthreads();
     if (tid < kLrCols)
         p.qnorm_part[(size_t)blockIdx.x * kLrCols + tid] = s_n[0][tid] + s_n[1][tid] + s_n[2][tid] + s_n[3][tid];
@@ -455,49 +517,68 @@ __global__ __launch_bounds__(64) void lr_errors_kernel(LrParams p) {
 
 // ------------------------------------------------------------------ e' = X - Phat Q^T
 __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
-    __shared__ float Ps[kLrBM][kLrCols + 1];
+    __shared__ float Ps[64][kLrCols + 1];
     __shared__ float Qs[kLrCols][kLrCols + 1];
-    const LrTile tile = p.row_tiles[blockIdx.x];
+    __shared__ float Ms[64][kLrCols + 4];
+    const LrTile tile = p.ef_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
-    const int m = L.rows, n = L.cols, row0 = tile.a0, r = L.rank;
+    const int m = L.rows, n = L.cols, r = L.rank;
     const int kmax = (r + 1) & ~1;
     const float* __restrict__ g = p.g + L.offset;
     float* __restrict__ e = p.e_out + L.offset;
     const float* __restrict__ P = p.P + L.p_off;
     const float* __restrict__ Q = p.Q + L.qs_off;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    for (int f = tid; f < kLrBM * kLrCols; f += 256) {
+    const bool vec = L.vec_ok != 0;
+    // the 4 wavefronts split a 64 x 64 output tile into 32 x 32 quadrants
+    const int wr = wave >> 1, wc = wave & 1;
+    const int ar = 32 * wr + (lane & 31), ak = lane >> 5, bj = 32 * wc + (lane & 31);
+    const int row0 = tile.a0, cbeg = tile.split, cend = min(n, cbeg + kLrEfSpan);
+    for (int f = tid; f < 64 * kLrCols; f += 256) {
         const int rr = f >> 6, c = f & 63;
         Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * kLrCols + c] : 0.0f;
     }
-    const int ar = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
-    for (int c0 = 0; c0 < n; c0 += kLrCols) {
+    for (int c0 = cbeg; c0 < cend; c0 += kLrCols) {
+        // this tile's inputs are requested first, so their latency overlaps the staging of Q
+        float4 x[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int f = tid + 256 * q;
+            const int row = row0 + (f >> 4), colx = c0 + (f & 15) * 4;
+            x[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < m && colx < n) x[q] = load_x4(g, e, (int64_t)row * n + colx, n - colx, vec);
+        }
         __syncthreads();
         for (int f = tid; f < kLrCols * kLrCols; f += 256) {
             const int cc = f >> 6, k = f & 63;
             Qs[cc][k] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * kLrCols + k] : 0.0f;
         }
         __syncthreads();
-        f32x16 acc0 = {0}, acc1 = {0};
-        for (int kk = 0; kk < kmax; kk += 2) {
-            const float a = Ps[ar][kk + ak];
-            const float b0 = Qs[bj][kk + ak];
-            const float b1 = Qs[32 + bj][kk + ak];
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
-        }
+        f32x16 acc = {0};
+        for (int kk = 0; kk < kmax; kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[ar][kk + ak], Qs[bj][kk + ak], acc, 0, 0, 0);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (row < m) {
-                const int64_t base = (int64_t)row * n + c0;
-                if (c0 + bj < n) {
-                    const float x = g[base + bj] + e[base + bj];
-                    e[base + bj] = x - acc0[v];
-                }
-                if (c0 + 32 + bj < n) {
-                    const float x = g[base + 32 + bj] + e[base + 32 + bj];
-                    e[base + 32 + bj] = x - acc1[v];
+        for (int v = 0; v < 16; ++v)
+            Ms[32 * wr + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)][bj] = acc[v];
+        __syncthreads();
+        // coalesced update of the error feedback: 64 rows x 16 float4
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int f = tid + 256 * q;
+            const int rr = f >> 4, c4 = (f & 15) * 4;
+            const int row = row0 + rr, colx = c0 + c4;
+            if (row < m && colx < n) {
+                const int64_t idx = (int64_t)row * n + colx;
+                const int left = n - colx;
+                const float4 mh = *reinterpret_cast<const float4*>(&Ms[rr][c4]);
+                const float4 o = make_float4(x[q].x - mh.x, x[q].y - mh.y, x[q].z - mh.z, x[q].w - mh.w);
+                if (vec && left >= 4) {
+                    *reinterpret_cast<float4*>(e + idx) = o;
+                } else {
+                    e[idx] = o.x;
+                    if (left > 1) e[idx + 1] = o.y;
+                    if (left > 2) e[idx + 2] = o.z;
+                    if (left > 3) e[idx + 3] = o.w;
                 }
             }
         }
@@ -513,17 +594,18 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
 
 struct LrHost {
     std::vector<LrLayer> layers;
-    std::vector<LrTile> row_tiles, col_tiles, gram_tiles, q_chunks;
+    std::vector<LrTile> row_tiles, p_tiles, ef_tiles, col_tiles, gram_tiles, q_chunks;
     std::vector<int64_t> sig;       // signature of the layer table the tables were built for
-    int64_t p_elems = 0, q_elems = 0, part_elems = 0;
+    int64_t p_elems = 0, q_elems = 0, part_elems = 0, ppart_elems = 0;
     // device copies
     LrLayer* d_layers = nullptr;
     LrTile* d_tiles = nullptr;      // the four tile tables back to back
-    size_t cap_layers = 0, cap_tiles = 0, cap_p = 0, cap_q = 0, cap_part = 0, cap_gram = 0, cap_T = 0,
+    size_t cap_layers = 0, cap_tiles = 0, cap_p = 0, cap_q = 0, cap_part = 0, cap_ppart = 0, cap_gram = 0, cap_T = 0,
            cap_xn = 0, cap_qn = 0;
     float* P = nullptr;
     float* Q = nullptr;
     float* part = nullptr;
+    float* ppart = nullptr;
     double* gram = nullptr;
     double* T = nullptr;
     double* xn = nullptr;
@@ -556,6 +638,7 @@ void lowrank_scratch_destroy(LowrankScratch* t) {
         (void)hipFree(H->P);
         (void)hipFree(H->Q);
         (void)hipFree(H->part);
+        (void)hipFree(H->ppart);
         (void)hipFree(H->gram);
         (void)hipFree(H->T);
         (void)hipFree(H->xn);
@@ -583,10 +666,12 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
     if (sig == H->sig) return hipSuccess;
     H->layers.clear();
     H->row_tiles.clear();
+    H->p_tiles.clear();
+    H->ef_tiles.clear();
     H->col_tiles.clear();
     H->gram_tiles.clear();
     H->q_chunks.clear();
-    int64_t p_off = 0, q_off = 0, part_off = 0;
+    int64_t p_off = 0, q_off = 0, part_off = 0, ppart_off = 0;
     for (int l = 0; l < L; ++l) {
         if (rank[l] <= 0) continue;
         LrLayer a{};
@@ -608,16 +693,31 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
         a.ksplit = ((a.rows + splits - 1) / splits + kLrBK - 1) / kLrBK * kLrBK;
         a.splits = (a.rows + a.ksplit - 1) / a.ksplit;
         const int li = (int)H->layers.size();
-        a.rt_begin = (int)H->row_tiles.size();
-        for (int r0 = 0; r0 < a.rows; r0 += kLrBM) H->row_tiles.push_back(LrTile{li, r0, 0, 0});
-        a.rt_end = (int)H->row_tiles.size();
+        // P = X Q0: equal work units of at most kLrPSplit contracted columns
+        a.psplits = (a.cols + kLrPSplit - 1) / kLrPSplit;
+        a.pksplit = ((a.cols + a.psplits - 1) / a.psplits + kLrBK - 1) / kLrBK * kLrBK;
+        a.psplits = (a.cols + a.pksplit - 1) / a.pksplit;
+        a.ppart_off = ppart_off;
+        if (a.psplits > 1) ppart_off += (int64_t)a.psplits * a.rows * kLrCols;
+        a.rt_begin = (int)H->p_tiles.size();            // ||X||^2 partials: one per P tile
+        for (int r0 = 0; r0 < a.rows; r0 += kLrBM) {
+            H->row_tiles.push_back(LrTile{li, r0, 0, 0});
+            for (int sp = 0; sp < a.psplits; ++sp) H->p_tiles.push_back(LrTile{li, r0, sp, 0});
+        }
+        a.rt_end = (int)H->p_tiles.size();
+        for (int r0 = 0; r0 < a.rows; r0 += 64)
+            for (int c0 = 0; c0 < a.cols; c0 += kLrEfSpan) H->ef_tiles.push_back(LrTile{li, r0, c0, 0});
         for (int c0 = 0; c0 < a.cols; c0 += kLrBM)
             for (int sp = 0; sp < a.splits; ++sp) H->col_tiles.push_back(LrTile{li, c0, sp, 0});
         a.gram_begin = (int)H->gram_tiles.size();
         for (int r0 = 0; r0 < a.rows; r0 += kLrGramSpan) H->gram_tiles.push_back(LrTile{li, r0, 0, 0});
         a.gram_end = (int)H->gram_tiles.size();
         a.qc_begin = (int)H->q_chunks.size();
-        for (int c0 = 0; c0 < a.cols; c0 += kLrQChunk) H->q_chunks.push_back(LrTile{li, c0, 0, 0});
+        {
+            // rows per chunk: fewer when many split-K partials have to be summed per row
+            const int qrows = a.splits <= 4 ? kLrQChunk : std::max(2, kLrQChunk / a.splits * 2);
+            for (int c0 = 0; c0 < a.cols; c0 += qrows) H->q_chunks.push_back(LrTile{li, c0, qrows, 0});
+        }
         a.qc_end = (int)H->q_chunks.size();
         p_off += (int64_t)a.rows * kLrCols;
         q_off += (int64_t)a.cols * kLrCols;
@@ -627,22 +727,25 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
     H->p_elems = p_off;
     H->q_elems = q_off;
     H->part_elems = part_off;
+    H->ppart_elems = ppart_off;
     const size_t nl = H->layers.size();
-    const size_t nt = H->row_tiles.size() + H->col_tiles.size() + H->gram_tiles.size() + H->q_chunks.size();
+    const size_t nt = H->row_tiles.size() + H->p_tiles.size() + H->ef_tiles.size() + H->col_tiles.size() +
+                      H->gram_tiles.size() + H->q_chunks.size();
     LR_CHECK(grow((void**)&H->d_layers, &H->cap_layers, sizeof(LrLayer) * std::max<size_t>(nl, 1)));
     LR_CHECK(grow((void**)&H->d_tiles, &H->cap_tiles, sizeof(LrTile) * std::max<size_t>(nt, 1)));
     LR_CHECK(grow((void**)&H->P, &H->cap_p, sizeof(float) * std::max<int64_t>(p_off, 1)));
     LR_CHECK(grow((void**)&H->Q, &H->cap_q, sizeof(float) * std::max<int64_t>(q_off, 1)));
     LR_CHECK(grow((void**)&H->part, &H->cap_part, sizeof(float) * std::max<int64_t>(part_off, 1)));
+    LR_CHECK(grow((void**)&H->ppart, &H->cap_ppart, sizeof(float) * std::max<int64_t>(ppart_off, 1)));
     LR_CHECK(grow((void**)&H->gram, &H->cap_gram,
                   sizeof(double) * kLrCols * kLrCols * std::max<size_t>(H->gram_tiles.size(), 1)));
     LR_CHECK(grow((void**)&H->T, &H->cap_T, sizeof(double) * kLrCols * kLrCols * std::max<size_t>(nl, 1)));
-    LR_CHECK(grow((void**)&H->xn, &H->cap_xn, sizeof(double) * std::max<size_t>(H->row_tiles.size(), 1)));
+    LR_CHECK(grow((void**)&H->xn, &H->cap_xn, sizeof(double) * std::max<size_t>(H->p_tiles.size(), 1)));
     LR_CHECK(grow((void**)&H->qn, &H->cap_qn, sizeof(double) * kLrCols * std::max<size_t>(H->q_chunks.size(), 1)));
     if (nl) {
         LR_CHECK(hipMemcpyAsync(H->d_layers, H->layers.data(), sizeof(LrLayer) * nl, hipMemcpyHostToDevice, s));
         size_t o = 0;
-        for (auto* v : {&H->row_tiles, &H->col_tiles, &H->gram_tiles, &H->q_chunks}) {
+        for (auto* v : {&H->row_tiles, &H->p_tiles, &H->ef_tiles, &H->col_tiles, &H->gram_tiles, &H->q_chunks}) {
             if (!v->empty())
                 LR_CHECK(hipMemcpyAsync(H->d_tiles + o, v->data(), sizeof(LrTile) * v->size(),
                                         hipMemcpyHostToDevice, s));
@@ -657,12 +760,15 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
 static void lr_fill_params(LrHost* H, LrParams* p) {
     p->layers = H->d_layers;
     p->row_tiles = H->d_tiles;
-    p->col_tiles = p->row_tiles + H->row_tiles.size();
+    p->p_tiles = p->row_tiles + H->row_tiles.size();
+    p->ef_tiles = p->p_tiles + H->p_tiles.size();
+    p->col_tiles = p->ef_tiles + H->ef_tiles.size();
     p->gram_tiles = p->col_tiles + H->col_tiles.size();
     p->q_chunks = p->gram_tiles + H->gram_tiles.size();
     p->P = H->P;
     p->Q = H->Q;
     p->part = H->part;
+    p->ppart = H->ppart;
     p->gram_part = H->gram;
     p->T = H->T;
     p->xnorm_part = H->xn;
@@ -672,17 +778,18 @@ static void lr_fill_params(LrHost* H, LrParams* p) {
 static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStream_t s) {
     {
         Section sec(tm, "lowrank_gemm_p");
-        hipLaunchKernelGGL(lr_gemm1_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(lr_gemm1_kernel, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
+        if (H->ppart_elems > 0) {
+            hipLaunchKernelGGL(lr_preduce_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+            LR_CHECK(hipGetLastError());
+        }
     }
     {
         Section sec(tm, "lowrank_orth");
         hipLaunchKernelGGL(lr_gram_kernel, dim3((unsigned)H->gram_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
-        const size_t orth_lds = 2 * sizeof(double) * kLrCols * (kLrCols + 1);
-        LR_CHECK(hipFuncSetAttribute((const void*)lr_orth_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)orth_lds));
-        hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(256), orth_lds, s, p);
+        hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
         hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
@@ -747,7 +854,7 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     p.payload = payload;
     LR_CHECK(lr_factorize(H, p, tm, s));
     Section sec(tm, "lowrank_ef");
-    hipLaunchKernelGGL(lr_ef_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(lr_ef_kernel, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
