@@ -389,8 +389,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         for (int l = 0; l < L; ++l)
             for (int j = 0; j < ntk; ++j)
                 ks[(size_t)l * kMaxTopk + j] = (uint32_t)topk_k(layers[l].numel, tk_density[j]);
-        Section sec(&h->tm, "topk_zero");
-        HIPCHK(topk_begin(&h->topk, h->hl.data(), L, ks.data(), s));
+        HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles, ks.data(),
+                          ntk, &h->tm, s));
     }
     if (qp.nq) {
         qp.g = d_grads;
@@ -402,19 +402,26 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         qp.stochastic = h->cfg.stochastic;
         qp.seed_lo = (uint32_t)h->cfg.seed;
         qp.seed_hi = (uint32_t)(h->cfg.seed >> 32);
-        qp.hist = ntk ? h->topk.d_hist : nullptr;
-        Section sec(&h->tm, ntk ? "quant_profile_hist" : "quant_profile");
+        if (ntk) {
+            qp.hist = h->topk.d_hist;
+            qp.lo = h->topk.d_lo;
+            qp.cand = h->topk.d_cand;
+            qp.cand_base = h->topk.d_cand_base;
+            qp.tinfo = h->topk.d_tinfo;
+            qp.base_part = h->topk.d_base_part;
+        }
+        Section sec(&h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile");
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
     } else if (ntk) {
-        Section sec(&h->tm, "topk_hist");
-        HIPCHK(topk_hist(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, s));
+        Section sec(&h->tm, "topk_collect");
+        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, s));
     }
-    if (ntk)
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, L, n_tiles, ntk, tk_col,
-                           h->d_partials, P, &h->tm, s));
-    if (tile_cols) {
+    if (ntk) HIPCHK(topk_select(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, L, n_tiles, ntk, &h->tm, s));
+    if (qp.nq) {
+        uint32_t qmask = 0;
+        for (int i = 0; i < qp.nq; ++i) qmask |= 1u << qp.col[i];
         Section sec(&h->tm, "reduce_partials");
-        HIPCHK(launch_reduce_partials(h->d_partials, P, tile_cols, h->d_layers, L, h->d_errors, s));
+        HIPCHK(launch_reduce_partials(h->d_partials, P, qmask, h->d_layers, L, h->d_errors, s));
     }
     if (ntk) {
         int max_tiles = 0;

@@ -8,7 +8,7 @@
 
 namespace lgreco {
 
-constexpr int kTile = 8192;        // elements per streaming tile (64 buckets of 128)
+constexpr int kTile = 65536;       // elements per streaming tile (512 buckets of 128)
 constexpr int kBucket = 128;       // quantization bucket (elements)
 constexpr int kChunk = 512;        // elements one wavefront handles per step (4 buckets)
 constexpr int kThreads = 256;      // workgroup size of the streaming kernels (4 wavefronts)
@@ -150,9 +150,13 @@ struct QuantParams {
     int32_t col[kMaxQuant];    // column of each candidate in partials
     int32_t stochastic;
     uint32_t seed_lo, seed_hi;
-    // fused coarse histogram (top-k candidates present)
-    uint32_t* hist;            // [L x kHistBins] or null
-    int32_t energy_col;        // column receiving sum x^2 of the tile, or -1
+    // fused Top-K work (Top-K candidates in the same profile call)
+    uint32_t* hist;            // [L x kHistBins] coarse magnitude histogram, or null
+    const uint32_t* lo;        // [L] lowest coarse key collected as a candidate (collection mode)
+    uint32_t* cand;            // candidate buffer
+    const int64_t* cand_base;  // [L] first candidate slot of every layer
+    void* tinfo;               // [n_tiles] TopkTileInfo
+    double* base_part;         // [n_tiles] energy of the elements below lo
 };
 
 }  // namespace lgreco

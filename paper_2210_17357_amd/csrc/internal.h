@@ -65,14 +65,17 @@ hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s)
 
 // ---- topk.hip
 struct TopkScratch {
-    uint32_t* d_hist = nullptr;       // [max_layers x kHistBins] coarse magnitude histogram
+    uint32_t* d_hist = nullptr;       // [2 x max_layers x kHistBins] exact coarse histogram, then the sample's
     void* d_tl = nullptr;             // per-layer selection records
-    uint32_t* d_cand = nullptr;       // bit patterns of the threshold bins' elements [max_elems]
+    uint32_t* d_cand = nullptr;       // bit patterns of the candidates, tile i at its own first element
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
+    uint32_t* d_lo = nullptr;         // [max_layers] lowest coarse key collected as a candidate
     int64_t* d_cand_base = nullptr;   // [max_layers] first candidate slot of every layer
     void* d_tilecnt = nullptr;        // per tile (above, equal) counts (compress)
     void* d_tilebase = nullptr;       // per tile exclusive prefix of those counts
-    void* d_tinfo = nullptr;          // per tile candidate counts
+    void* d_tinfo = nullptr;          // per tile, per wavefront: candidates written and where
+    double* d_base_part = nullptr;    // per tile energy below the collection bound
+    double* d_below_part = nullptr;   // refinement partial sums
     uint32_t* d_ref = nullptr;        // refinement histograms (counts and integer energies)
     size_t ref_words = 0;
     uint32_t* h_k = nullptr;          // pinned
@@ -82,16 +85,20 @@ struct TopkScratch {
 };
 hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers, int max_tiles);
 void topk_scratch_destroy(TopkScratch* t);
-// upload k per (layer, candidate) and clear the histograms
-hipError_t topk_begin(TopkScratch* t, const DevLayer* h_layers, int L, const uint32_t* ks, hipStream_t s);
-// stand-alone coarse histogram (the quantization profile kernel can produce it instead)
-hipError_t topk_hist(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                     const Tile* d_tiles, int n_tiles, hipStream_t s);
-// threshold bins, then pass B: energy below each threshold bin -> partials, candidate lists
+// upload k per (layer, candidate), clear the histograms, sample the data and predict every
+// layer's collection bound
+hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
+                      int ntk, Timing* tm, hipStream_t s);
+// main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
+// the read; otherwise the quantization profile kernel does the same work
+hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                        const Tile* d_tiles, int n_tiles, hipStream_t s);
+// exact threshold bins from the histogram; layers whose predicted bound was too high are
+// collected again with the exact one
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                       const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
-                       int stride, Timing* tm, hipStream_t s);
-// exact thresholds; adds the candidate lists' dropped energy to errors (if not null)
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, Timing* tm, hipStream_t s);
+// refinement on the candidates: exact thresholds; writes the dropped energy to errors (if not null)
 hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int max_layer_tiles,
                          int ntk, const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,

@@ -16,6 +16,7 @@
 // spread over the row's 16 lanes (lane c: unit of candidate c, lane 8+c: inv of candidate c)
 // and broadcast back with row_newbcast.
 #include "internal.h"
+#include "topk_dev.h"
 
 namespace lgreco {
 
@@ -38,9 +39,11 @@ __device__ __forceinline__ float quant_one(float x, float xm, float m, float inv
     return __builtin_fmaf(q, unit, m);
 }
 
+// HIST: also build the coarse magnitude histogram of the Top-K path and collect its candidates
+// (elements whose coarse key is at or above the layer's predicted bound) in the same read.
 template <bool STOCH, bool HAS_EF, bool HIST>
 __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) {
-    __shared__ double s_part[kThreads / 64][kMaxQuant];
+    __shared__ double s_part[kThreads / 64][kMaxQuant + 1];
     __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
 
     const Tile t = p.tiles[blockIdx.x];
@@ -59,14 +62,25 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #pragma unroll
     for (int c = 0; c < kMaxQuant; ++c) acc[c] = 0.0f;
 
+    Collector col;
+    uint32_t col_start = 0;
+    uint32_t* const slice = HIST ? p.cand + p.cand_base[t.layer] + t.pos : nullptr;
+    const uint32_t col_lo = HIST ? p.lo[t.layer] : 0xFFFFFFFFu;
+
     if (t.fast) {
         // division owned by this lane: candidate (lane & 7), unit for lanes 0-7, inv for 8-15
         const int j = lane & 15;
         const int myc = j & 7;
         const float mylv = (myc < nq) ? (float)((1 << p.bits[myc]) - 1) : 1.0f;
         const bool want_inv = (j >> 3) != 0;
-        const int nchunks = t.count / kChunk;
-        for (int c = wave; c < nchunks; c += kThreads / 64) {
+        // each wavefront owns a contiguous range of the tile's 512-element chunks
+        int c_begin, c_end;
+        wave_range(t.count / kChunk, wave, &c_begin, &c_end);
+        if (HIST) {
+            col_start = (uint32_t)c_begin * kChunk;
+            col.init(slice + col_start, col_lo);
+        }
+        for (int c = c_begin; c < c_end; ++c) {
             const int base = c * kChunk + (lane >> 4) * kBucket + j * 4;
             float4 a = *reinterpret_cast<const float4*>(g + base);
             float4 b = *reinterpret_cast<const float4*>(g + base + 64);
@@ -79,8 +93,10 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             if (HIST) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    atomicAdd(&s_hist[(__float_as_uint(x[k]) & 0x7FFFFFFFu) >> kHistShift], 1u);
+                for (int k = 0; k < 8; ++k) {
+                    atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
+                    col.take(x[k], true);
+                }
             }
             float mn = fminf(fminf(fminf(x[0], x[1]), fminf(x[2], x[3])),
                              fminf(fminf(x[4], x[5]), fminf(x[6], x[7])));
@@ -129,7 +145,13 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         // Slow path (tail of a layer, or a layer that is not 16-byte aligned): one wavefront per
         // bucket, two elements per lane, out-of-range lanes masked.
         const int nb = (t.count + kBucket - 1) / kBucket;
-        for (int bk = wave; bk < nb; bk += kThreads / 64) {
+        int b_begin, b_end;
+        wave_range(nb, wave, &b_begin, &b_end);
+        if (HIST) {
+            col_start = (uint32_t)b_begin * kBucket;
+            col.init(slice + col_start, col_lo);
+        }
+        for (int bk = b_begin; bk < b_end; ++bk) {
             float x[2];
             bool ok[2];
 #pragma unroll
@@ -138,8 +160,10 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                 ok[k] = idx < t.count;
                 x[k] = 0.0f;
                 if (ok[k]) x[k] = HAS_EF ? g[idx] + e[idx] : g[idx];
-                if (HIST && ok[k])
-                    atomicAdd(&s_hist[(__float_as_uint(x[k]) & 0x7FFFFFFFu) >> kHistShift], 1u);
+                if (HIST) {
+                    if (ok[k]) atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
+                    col.take(x[k], ok[k]);
+                }
             }
             const float inf = __builtin_huge_valf();
             const float mn = wave_min(fminf(ok[0] ? x[0] : inf, ok[1] ? x[1] : inf));
@@ -188,6 +212,17 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         p.partials[(size_t)blockIdx.x * p.stride + p.col[threadIdx.x]] = s;
     }
     if (HIST) {
+        const double bs = wave_sum((double)col.base);
+        TopkTileInfo* const ti = reinterpret_cast<TopkTileInfo*>(p.tinfo) + blockIdx.x;
+        if (lane == 0) {
+            s_part[wave][kMaxQuant] = bs;
+            ti->cnt[wave] = col.cur;
+            ti->start[wave] = col_start;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0)
+            p.base_part[blockIdx.x] = (s_part[0][kMaxQuant] + s_part[1][kMaxQuant]) +
+                                      (s_part[2][kMaxQuant] + s_part[3][kMaxQuant]);
         uint32_t* gh = p.hist + (size_t)t.layer * kHistBins;
         for (int b = threadIdx.x; b < kHistBins; b += kThreads) {
             const uint32_t c = s_hist[b];
@@ -250,8 +285,9 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
     if (t.fast) {
         const int j = lane & 15, row = lane >> 4;
         uint8_t* const sc = reinterpret_cast<uint8_t*>(s_codes[wave]);
-        const int nchunks = t.count / kChunk;
-        for (int c = wave; c < nchunks; c += kThreads / 64) {
+        int c_begin, c_end;
+        wave_range(t.count / kChunk, wave, &c_begin, &c_end);
+        for (int c = c_begin; c < c_end; ++c) {
             const int base = c * kChunk + row * kBucket + j * 4;
             float4 a = *reinterpret_cast<const float4*>(g + base);
             float4 b = *reinterpret_cast<const float4*>(g + base + 64);
@@ -318,7 +354,9 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
     } else {
         uint32_t* const sw = s_codes[wave];
         const int nb = (t.count + kBucket - 1) / kBucket;
-        for (int bk = wave; bk < nb; bk += kThreads / 64) {
+        int b_begin, b_end;
+        wave_range(nb, wave, &b_begin, &b_end);
+        for (int bk = b_begin; bk < b_end; ++bk) {
             const int cnt = min(kBucket, t.count - bk * kBucket);
             for (int d = lane; d < 32; d += 64) sw[d] = 0;          // 128 elements x 8 bits max
             float x[2];

@@ -1,28 +1,30 @@
 // Layer-wise Top-K: radix-histogram threshold search, dropped-energy profile for several
 // densities at once, and threshold-select compaction.  gfx950 / wave64.
 //
-// Magnitudes are compared as the fp32 bit pattern with the sign cleared (31 bits).  Per layer:
-//   1. coarse histogram of the top 12 bits (exponent + 4 mantissa bits), LDS per tile then
-//      global integer atomics (fused into the quantization profile kernel when both families
-//      are profiled);
-//   2. scan: for every requested k the coarse bin holding the k-th largest magnitude, and how
-//      many entries must still be taken inside that bin;
-//   3. pass B over the data: energy of everything below the lowest threshold bin in registers;
-//      the few elements at or above it are staged in LDS and handled densely: energy below
-//      each threshold bin, and the bit patterns of the threshold bins' elements ("candidates")
-//      written to the tile's own slice of a candidate buffer, grouped by bin, with the
-//      per-tile counts alongside (no global atomics: a tile cannot have more candidates than
-//      elements, so the slices never collide);
-//   4. refinement on the candidates only (about 1 % of the data per density): histogram of
-//      the next 10 bits, pick the sub-bin, histogram of the last 9 bits, pick the exact k-th
-//      magnitude and the number of equal magnitudes to keep.  Histograms carry the energy of
-//      each bin as an integer (entries of one candidate list share the exponent, so
-//      x^2 = m^2 2^(2(E-150)) with m the 24-bit significand; sum (m^2 >> 16) is exact integer
-//      arithmetic), so the dropped energy does not depend on the order the candidates were
-//      written or accumulated in.
+// Magnitudes are compared as the fp32 bit pattern with the sign cleared (31 bits); the "coarse
+// key" of an element is the top 12 bits (exponent + 4 mantissa bits).  Per call:
+//   1. sample: coarse histogram of 1/16 of the data (one 512-element chunk out of 16).  From it a
+//      cautious lower bound `lo` of the coarse key of the k-th largest magnitude is predicted for
+//      every layer (the largest k asked for, with a wide margin).
+//   2. main pass, ONE read of the data (fused into the quantization profile kernel when both
+//      families are profiled): exact coarse histogram of every element (LDS per tile, integer
+//      atomics to global); elements with key >= lo ("candidates", 10-20 % of the data) are
+//      written, as bit patterns, to the tile's own slice of a candidate buffer in ballot-prefix
+//      order; the energy of everything below lo is summed in registers.
+//   3. scan of the exact histogram: for every requested k the coarse bin holding the k-th largest
+//      magnitude and how many entries to take inside it.  If the prediction was too high for a
+//      layer (lo above its lowest threshold bin) that layer alone is collected again with the
+//      exact bound, so the result never depends on the sample.
+//   4. refinement on the candidates only: energy below each threshold bin (fp64, fixed order),
+//      histogram of the next 10 bits inside each threshold bin, pick the sub-bin, histogram of
+//      the last 9 bits, pick the exact k-th magnitude and the number of equal magnitudes to keep.
+//      Histogram bins carry their energy as integers (entries of one coarse bin share the
+//      exponent: x^2 = m^2 2^(2(E-150)), m the 24-bit significand; sum (m^2 >> 16) is exact), so
+//      nothing depends on the order of atomics.
 // Compression then counts kept entries per tile from the candidates, scans the tile counts, and
 // writes values and indices in ascending index order (equal magnitudes: lowest indices first).
 #include "internal.h"
+#include "topk_dev.h"
 
 namespace lgreco {
 
@@ -34,28 +36,25 @@ struct TopkSel {
     uint32_t bin_a, need_a;         // refinement level A (bits 18..9)
     uint32_t thr, ties_keep;        // exact threshold pattern; equal entries kept
     unsigned long long energy_a;    // integer energy of the list's entries below bin_a
+    double energy_below;            // energy of the candidates below the threshold bin
 };
 struct TopkLayer {
     int64_t cand_base;              // first slot of this layer's region in the candidate buffer
     uint32_t nlists, min_tbin;
+    uint32_t recollect, pad;        // 1: the predicted bound was too high, collect again
     TopkList lists[kMaxTopk];
     TopkSel sel[kMaxTopk];
 };
-// per tile: candidates of each list (written list after list into the tile's slice), and the
-// number of elements above the first threshold bin (used by the compressor)
-struct TopkTileInfo {
-    uint32_t cnt[kMaxTopk];
-    uint32_t above;
-    uint32_t pad[3];
-};
-constexpr int kRefSplits = 128;     // workgroups per layer in the refinement passes
+constexpr int kRefSplits = 128;     // refinement workgroups per layer, at most
+constexpr int kRefTilesMin = 4;     // tiles per refinement workgroup, at least
+constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
-constexpr int kRefTilesMin = 48;    // tiles per refinement workgroup, at least
-constexpr int kRefThreads = 1024;   // refinement workgroup: one tile per wavefront in flight
+constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 
 // ------------------------------------------------------------------------ block helpers
 // Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
-// hist lives in LDS, nbins <= 16 * 256.  All 256 threads call; result broadcast through res[2].
+// hist lives in LDS, nbins <= 16 * 256.  All 256 threads call; result broadcast through res[2];
+// scan[0] is left holding the total.  If fewer than `need` entries exist, res = {0, total - hist[0]}.
 __device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scan,
                                    uint32_t* res) {
     const int tid = threadIdx.x;
@@ -63,15 +62,16 @@ __device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t nee
     const int lo = tid * per, hi = min(lo + per, nbins);
     uint32_t s = 0;
     for (int b = lo; b < hi; ++b) s += hist[b];
-    // inclusive suffix scan over threads: scan[t] = sum of s over threads >= t
     scan[tid] = s;
     __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
+    for (int o = 1; o < 256; o <<= 1) {       // inclusive suffix scan over threads
         const uint32_t v = (tid + o < 256) ? scan[tid + o] : 0;
         __syncthreads();
         scan[tid] += v;
         __syncthreads();
     }
+    if (tid == 0) { res[0] = 0; res[1] = scan[0] - hist[0]; }
+    __syncthreads();
     uint32_t running = (tid + 1 < 256) ? scan[tid + 1] : 0;
     for (int b = hi - 1; b >= lo; --b) {
         const uint32_t c = hist[b];
@@ -105,7 +105,10 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t* total) 
     return base + inc - v;
 }
 
-__device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+__device__ __forceinline__ unsigned long long int_energy(uint32_t pat) {
+    const unsigned long long m = (pat & 0x7FFFFFu) | ((pat >> 23) ? 0x800000u : 0u);
+    return (m * m) >> 16;
+}
 
 // ------------------------------------------------------------------------ kernels
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -113,13 +116,14 @@ __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
         p[i] = v;
 }
 
-// Coarse histogram of the active layers (ks[layer * kMaxTopk] != 0).
-__global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __restrict__ g,
-                                                              const float* __restrict__ e,
-                                                              const DevLayer* __restrict__ layers,
-                                                              const Tile* __restrict__ tiles,
-                                                              const uint32_t* __restrict__ ks,
-                                                              uint32_t* __restrict__ hist) {
+// Coarse histogram of a sample: every kSampleEvery-th 512-element chunk of every tile (chunk 0
+// included, so short tiles are sampled whole or by their first chunk).
+__global__ __launch_bounds__(kThreads) void topk_sample_kernel(const float* __restrict__ g,
+                                                                const float* __restrict__ e,
+                                                                const DevLayer* __restrict__ layers,
+                                                                const Tile* __restrict__ tiles,
+                                                                const uint32_t* __restrict__ ks,
+                                                                uint32_t* __restrict__ shist) {
     __shared__ uint32_t s_hist[kHistBins];
     const Tile t = tiles[blockIdx.x];
     if (ks[(size_t)t.layer * kMaxTopk] == 0) return;
@@ -128,44 +132,157 @@ __global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __rest
     const float* ep = e ? e + L.offset + t.pos : nullptr;
     for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
     __syncthreads();
-    if (t.fast) {
-        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) {
-            float4 a = reinterpret_cast<const float4*>(gp)[v];
-            if (ep) {
-                const float4 b = reinterpret_cast<const float4*>(ep)[v];
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-            }
-            atomicAdd(&s_hist[mag_bits(a.x) >> kHistShift], 1u);
-            atomicAdd(&s_hist[mag_bits(a.y) >> kHistShift], 1u);
-            atomicAdd(&s_hist[mag_bits(a.z) >> kHistShift], 1u);
-            atomicAdd(&s_hist[mag_bits(a.w) >> kHistShift], 1u);
-        }
-    } else {
-        for (int i = threadIdx.x; i < t.count; i += kThreads) {
-            const float x = ep ? gp[i] + ep[i] : gp[i];
+    const int nchunks = (t.count + kChunk - 1) / kChunk;
+    for (int c = 0; c < nchunks; c += kSampleEvery) {
+        const int n = min(kChunk, t.count - c * kChunk);
+        for (int i = threadIdx.x; i < n; i += kThreads) {
+            const int idx = c * kChunk + i;
+            const float x = ep ? gp[idx] + ep[idx] : gp[idx];
             atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
         }
     }
     __syncthreads();
-    uint32_t* gh = hist + (size_t)t.layer * kHistBins;
+    uint32_t* gh = shist + (size_t)t.layer * kHistBins;
     for (int b = threadIdx.x; b < kHistBins; b += kThreads) {
         const uint32_t c = s_hist[b];
         if (c) atomicAdd(&gh[b], c);
     }
 }
 
-// One workgroup per layer: threshold bin and in-bin rank for every requested k; candidate lists.
+// One workgroup per layer: predicted lower bound of the lowest threshold bin.
+__global__ __launch_bounds__(256) void topk_predict_kernel(const uint32_t* __restrict__ shist,
+                                                           const uint32_t* __restrict__ ks, int ntk,
+                                                           const DevLayer* __restrict__ layers,
+                                                           uint32_t* __restrict__ lo) {
+    __shared__ uint32_t s_hist[kHistBins];
+    __shared__ uint32_t s_scan[256];
+    __shared__ uint32_t s_res[2];
+    const int l = blockIdx.x;
+    if (ks[(size_t)l * kMaxTopk] == 0) {
+        if (threadIdx.x == 0) lo[l] = 0xFFFFFFFFu;
+        return;
+    }
+    for (int b = threadIdx.x; b < kHistBins; b += 256) s_hist[b] = shist[(size_t)l * kHistBins + b];
+    __syncthreads();
+    uint32_t kmax = 0;
+    for (int j = 0; j < ntk; ++j) kmax = max(kmax, ks[(size_t)l * kMaxTopk + j]);
+    // sample size = total of the histogram (left in s_scan[0] by a scan for "everything")
+    block_kth_from_top(s_hist, kHistBins, 0xFFFFFFFFu, s_scan, s_res);
+    const double ns = (double)s_scan[0];
+    __syncthreads();
+    const double n = (double)layers[l].numel;
+    const double t = (double)kmax * ns / n;                 // expected sample entries above the threshold
+    const double want = 1.5 * t + 6.0 * sqrt(t) + 16.0;     // wide margin: the sample only has to be roughly right
+    if (want >= ns) {
+        if (threadIdx.x == 0) lo[l] = 0u;
+        return;
+    }
+    block_kth_from_top(s_hist, kHistBins, (uint32_t)want, s_scan, s_res);
+    if (threadIdx.x == 0) lo[l] = s_res[0];
+}
+
+struct CollectParams {
+    const float* g;
+    const float* e;
+    const DevLayer* layers;
+    const Tile* tiles;
+    const uint32_t* ks;
+    const TopkLayer* tl;        // only_flagged: layers to collect again
+    uint32_t* lo;
+    uint32_t* hist;
+    uint32_t* cand;
+    const int64_t* cand_base;
+    TopkTileInfo* tinfo;
+    double* base_part;
+    int32_t only_flagged;
+};
+
+// Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
+// collection.  With only_flagged it collects again the layers whose predicted bound was too high.
+template <bool HIST>
+__global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p) {
+    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
+    __shared__ double s_red[kThreads / 64];
+    const Tile t = p.tiles[blockIdx.x];
+    if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
+    if (p.only_flagged && !p.tl[t.layer].recollect) return;
+    const DevLayer L = p.layers[t.layer];
+    const float* gp = p.g + L.offset + t.pos;
+    const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (HIST) {
+        for (int b = tid; b < kHistBins; b += kThreads) s_hist[b] = 0;
+        __syncthreads();
+    }
+    uint32_t* const slice = p.cand + p.cand_base[t.layer] + t.pos;
+    Collector col;
+    uint32_t start;
+    if (t.fast) {
+        int c0, c1;
+        wave_range(t.count / kChunk, wave, &c0, &c1);
+        start = (uint32_t)c0 * kChunk;
+        col.init(slice + start, p.lo[t.layer]);
+        for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += 64) {     // uniform trip count
+            float4 a = reinterpret_cast<const float4*>(gp)[v];
+            if (ep) {
+                const float4 b = reinterpret_cast<const float4*>(ep)[v];
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            if (HIST) {
+                atomicAdd(&s_hist[mag_bits(a.x) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a.y) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a.z) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a.w) >> kHistShift], 1u);
+            }
+            col.take(a.x, true); col.take(a.y, true); col.take(a.z, true); col.take(a.w, true);
+        }
+    } else {
+        int b0, b1;
+        wave_range((t.count + 63) / 64, wave, &b0, &b1);
+        start = (uint32_t)b0 * 64;
+        col.init(slice + start, p.lo[t.layer]);
+        for (int b = b0; b < b1; ++b) {
+            const int i = b * 64 + lane;
+            const bool valid = i < t.count;
+            float x = 0.0f;
+            if (valid) x = ep ? gp[i] + ep[i] : gp[i];
+            if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
+            col.take(x, valid);
+        }
+    }
+    const double bs = wave_sum((double)col.base);
+    if (lane == 0) {
+        s_red[wave] = bs;
+        p.tinfo[blockIdx.x].cnt[wave] = col.cur;
+        p.tinfo[blockIdx.x].start[wave] = start;
+    }
+    __syncthreads();
+    if (tid == 0) p.base_part[blockIdx.x] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    if (HIST) {
+        uint32_t* gh = p.hist + (size_t)t.layer * kHistBins;
+        for (int b = tid; b < kHistBins; b += kThreads) {
+            const uint32_t c = s_hist[b];
+            if (c) atomicAdd(&gh[b], c);
+        }
+    }
+}
+
+// One workgroup per layer: threshold bin and in-bin rank for every requested k; threshold-bin
+// lists; check of the predicted bound.
 __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restrict__ hist,
                                                         const uint32_t* __restrict__ ks, int ntk,
                                                         const int64_t* __restrict__ cand_base,
-                                                        TopkLayer* __restrict__ tl) {
+                                                        uint32_t* __restrict__ lo, TopkLayer* __restrict__ tl) {
     __shared__ uint32_t s_hist[kHistBins];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     const int l = blockIdx.x;
     TopkLayer& T = tl[l];
     if (ks[(size_t)l * kMaxTopk] == 0) {
-        if (threadIdx.x == 0) { T.nlists = 0; T.min_tbin = 0; for (int j = 0; j < kMaxTopk; ++j) T.sel[j].k = 0; }
+        if (threadIdx.x == 0) {
+            T.nlists = 0; T.min_tbin = 0; T.recollect = 0;
+            for (int j = 0; j < kMaxTopk; ++j) T.sel[j].k = 0;
+        }
         return;
     }
     for (int b = threadIdx.x; b < kHistBins; b += 256) s_hist[b] = hist[(size_t)l * kHistBins + b];
@@ -178,11 +295,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
             S.k = k;
             S.tbin = s_res[0];
             S.need = k - s_res[1];
-            S.thr = 0;
-            S.ties_keep = 0;
-            S.bin_a = 0;
-            S.need_a = 0;
-            S.energy_a = 0;
+            S.thr = 0; S.ties_keep = 0; S.bin_a = 0; S.need_a = 0; S.energy_a = 0; S.energy_below = 0.0;
         }
         __syncthreads();
     }
@@ -204,151 +317,9 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
         T.nlists = nl;
         T.min_tbin = mn;
         T.cand_base = cand_base[l];
-    }
-}
-
-struct PassBParams {
-    const float* g;
-    const float* e;
-    const DevLayer* layers;
-    const Tile* tiles;
-    TopkLayer* tl;
-    uint32_t* cand;
-    TopkTileInfo* tinfo;
-    double* partials;       // may be null (compress: no energies)
-    int32_t stride;
-    int32_t ntk;
-    int32_t col[kMaxTopk];
-};
-
-__global__ __launch_bounds__(kThreads) void topk_passb_kernel(PassBParams p) {
-    __shared__ uint32_t s_stage[kTile];
-    __shared__ uint32_t s_wn[kThreads / 64];
-    __shared__ uint32_t s_cnt[kMaxTopk], s_cnt2[kMaxTopk], s_pre[kMaxTopk];
-    __shared__ uint32_t s_above[kThreads / 64];
-    __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
-    __shared__ double s_red[kThreads / 64][kMaxTopk + 1];
-
-    const Tile t = p.tiles[blockIdx.x];
-    TopkLayer& T = p.tl[t.layer];
-    if (T.sel[0].k == 0) return;                         // layer not active (uniform)
-    const DevLayer L = p.layers[t.layer];
-    const float* gp = p.g + L.offset + t.pos;
-    const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t min_tbin = T.min_tbin;
-    const uint32_t nlists = T.nlists;
-    if (tid < kMaxTopk) {
-        s_cnt[tid] = 0;
-        s_cnt2[tid] = 0;
-        s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
-        s_tbin[tid] = tid < p.ntk ? T.sel[tid].tbin : 0u;
-    }
-    __syncthreads();
-
-    // Elements at or above the lowest threshold bin are staged per wavefront at positions given
-    // by a ballot prefix count, so the staging order (and with it every floating-point sum
-    // below) is the same on every run.
-    float base = 0.0f;
-    uint32_t wcur = 0;                                   // uniform within the wavefront
-    uint32_t* const wstage = s_stage + wave * (kTile / (kThreads / 64));
-    auto consume = [&](float x, bool valid) {
-        const uint32_t pat = mag_bits(x);
-        const bool rare = valid && (pat >> kHistShift) >= min_tbin;
-        const unsigned long long m = __ballot(rare);
-        if (rare) {
-            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            wstage[wcur + below] = pat;
-        } else if (valid) {
-            base = __builtin_fmaf(x, x, base);
-        }
-        wcur += (uint32_t)__popcll(m);
-    };
-    if (t.fast) {
-        for (int v = tid; v < t.count / 4; v += kThreads) {          // count % 512 == 0: uniform trips
-            float4 a = reinterpret_cast<const float4*>(gp)[v];
-            if (ep) {
-                const float4 b = reinterpret_cast<const float4*>(ep)[v];
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-            }
-            consume(a.x, true); consume(a.y, true); consume(a.z, true); consume(a.w, true);
-        }
-    } else {
-        for (int i0 = 0; i0 < t.count; i0 += kThreads) {
-            const int i = i0 + tid;
-            const bool valid = i < t.count;
-            float x = 0.0f;
-            if (valid) x = ep ? gp[i] + ep[i] : gp[i];
-            consume(x, valid);
-        }
-    }
-    if (lane == 0) s_wn[wave] = wcur;
-    __syncthreads();
-
-    // dense handling of the staged elements (key >= lowest threshold bin)
-    float extra[kMaxTopk];
-    uint32_t above = 0;
-#pragma unroll
-    for (int j = 0; j < kMaxTopk; ++j) extra[j] = 0.0f;
-    for (int w = 0; w < kThreads / 64; ++w) {
-        const uint32_t* const ws = s_stage + w * (kTile / (kThreads / 64));
-        for (uint32_t i = tid; i < s_wn[w]; i += kThreads) {
-            const uint32_t pat = ws[i];
-            const uint32_t key = pat >> kHistShift;
-            const float xf = __uint_as_float(pat);
-            const float x2 = xf * xf;
-#pragma unroll
-            for (int j = 0; j < kMaxTopk; ++j)
-                if (j < p.ntk && key < s_tbin[j]) extra[j] += x2;
-            above += key > s_tbin[0];
-            for (uint32_t u = 0; u < nlists; ++u)
-                if (key == s_bin[u]) atomicAdd(&s_cnt[u], 1u);
-        }
-    }
-    for (int o = 1; o < 64; o <<= 1) above += __shfl_xor(above, o, 64);
-    if (lane == 0) s_above[wave] = above;
-    __syncthreads();
-    if (tid == 0) {
-        TopkTileInfo ti{};
-        uint32_t run = 0;
-        for (uint32_t u = 0; u < kMaxTopk; ++u) {
-            s_pre[u] = run;
-            ti.cnt[u] = u < nlists ? s_cnt[u] : 0u;
-            run += ti.cnt[u];
-        }
-        ti.above = s_above[0] + s_above[1] + s_above[2] + s_above[3];
-        p.tinfo[blockIdx.x] = ti;
-    }
-    __syncthreads();
-    // the tile's slice of the candidate buffer starts at its own first element
-    uint32_t* const cand = p.cand + T.cand_base + t.pos;
-    for (int w = 0; w < kThreads / 64; ++w) {
-        const uint32_t* const ws = s_stage + w * (kTile / (kThreads / 64));
-        for (uint32_t i = tid; i < s_wn[w]; i += kThreads) {
-            const uint32_t pat = ws[i];
-            const uint32_t key = pat >> kHistShift;
-            for (uint32_t u = 0; u < nlists; ++u)
-                if (key == s_bin[u]) cand[s_pre[u] + atomicAdd(&s_cnt2[u], 1u)] = pat;
-        }
-    }
-
-    if (p.partials) {
-        const float b = wave_sum(base);
-        if (lane == 0) s_red[wave][kMaxTopk] = (double)b;
-#pragma unroll
-        for (int j = 0; j < kMaxTopk; ++j) {
-            if (j < p.ntk) {
-                const float s = wave_sum(extra[j]);
-                if (lane == 0) s_red[wave][j] = (double)s;
-            }
-        }
-        __syncthreads();
-        if (tid < p.ntk) {
-            double s = 0.0;
-            for (int w = 0; w < kThreads / 64; ++w) s += s_red[w][kMaxTopk] + s_red[w][tid];
-            p.partials[(size_t)blockIdx.x * p.stride + p.col[tid]] = s;
-        }
+        // every element at or above the lowest threshold bin must be among the candidates
+        T.recollect = lo[l] > mn ? 1u : 0u;
+        if (T.recollect) lo[l] = mn;
     }
 }
 
@@ -358,6 +329,8 @@ struct RefineParams {
     const Tile* tiles;
     const TopkTileInfo* tinfo;
     const uint32_t* cand;
+    const double* base_part;          // [n_tiles]
+    double* below_part;               // [L x splits x kMaxTopk] energy of candidates below each threshold bin
     uint32_t* hist_a;                 // [L x kMaxTopk x kBinsA] counts per list
     unsigned long long* en_a;         // same shape, integer energies
     uint32_t* hist_b;                 // [L x kMaxTopk x kBinsB] per requested k
@@ -369,50 +342,18 @@ struct RefineParams {
     int32_t splits;                   // refinement workgroups per layer in this launch
 };
 
-__device__ __forceinline__ uint32_t tile_candidates(const TopkTileInfo& ti, uint32_t nlists) {
-    uint32_t n = 0;
-    for (uint32_t u = 0; u < kMaxTopk; ++u) n += u < nlists ? ti.cnt[u] : 0u;
-    return n;
-}
-
-__device__ __forceinline__ unsigned long long int_energy(uint32_t pat) {
-    const unsigned long long m = (pat & 0x7FFFFFu) | ((pat >> 23) ? 0x800000u : 0u);
-    return (m * m) >> 16;
-}
-
-// Refinement level A: histogram (count, energy) of bits 18..9 of every candidate, per list.
-// Workgroup (layer, split) walks its share of the layer's tiles.
-__global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
-    extern __shared__ unsigned char refine_smem[];
-    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
-    const TopkLayer& T = p.tl[l];
-    const uint32_t nlists = T.nlists;
-    if (nlists == 0) return;
-    const DevLayer L = p.layers[l];
-    const int ntiles = L.tile_end - L.tile_begin;
-    // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
-    // costs less than filling it
-    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
-    const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
-    if (t0 >= t1) return;
-    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
-    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
-    __shared__ uint32_t s_bin[kMaxTopk];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
-    if (tid < kMaxTopk) s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
-    __syncthreads();
-    // one wavefront per tile; the next tile's counts are fetched while this one is processed, and
-    // each lane keeps 8 candidate loads in flight
-    const int lane = tid & 63;
-    int t = t0 + (tid >> 6);
-    uint32_t n_next = 0;
-    int64_t pos_next = 0;
-    if (t < t1) { n_next = tile_candidates(p.tinfo[t], nlists); pos_next = p.tiles[t].pos; }
-    for (; t < t1; t += kRefThreads / 64) {
-        const uint32_t n = n_next;
-        const uint32_t* __restrict__ items = p.cand + T.cand_base + pos_next;
-        if (t + kRefThreads / 64 < t1) { n_next = tile_candidates(p.tinfo[t + kRefThreads / 64], nlists); pos_next = p.tiles[t + kRefThreads / 64].pos; }
+// Walks the candidates of tiles [t0, t1): one (tile, wavefront slice) pair per wavefront at a
+// time, 8 loads in flight per lane; f(pattern) is called for every candidate, in a fixed order
+// per thread.
+template <typename F>
+__device__ __forceinline__ void for_each_candidate(const RefineParams& p, const TopkLayer& T, int t0, int t1, F f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int kSub = kThreads / 64;
+    const int npairs = (t1 - t0) * kSub;
+    for (int pr = wave; pr < npairs; pr += kRefThreads / 64) {
+        const int t = t0 + pr / kSub, sub = pr % kSub;
+        const uint32_t n = p.tinfo[t].cnt[sub];
+        const uint32_t* __restrict__ items = p.cand + T.cand_base + p.tiles[t].pos + p.tinfo[t].start[sub];
         for (uint32_t i0 = 0; i0 < n; i0 += 64 * 8) {
             uint32_t pat[8];
 #pragma unroll
@@ -421,19 +362,78 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
                 pat[q] = i < n ? items[i] : 0xFFFFFFFFu;
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (pat[q] == 0xFFFFFFFFu) continue;
-                const uint32_t key = pat[q] >> kHistShift;
-                uint32_t u = 0;
-                for (uint32_t r = 1; r < nlists; ++r)
-                    if (key == s_bin[r]) u = r;
-                const uint32_t b = u * kBinsA + ((pat[q] >> 9) & (kBinsA - 1));
+            for (int q = 0; q < 8; ++q)
+                if (pat[q] != 0xFFFFFFFFu) f(pat[q]);
+        }
+    }
+}
+
+__device__ __forceinline__ bool refine_range(const DevLayer& L, int sp, int* t0, int* t1) {
+    const int ntiles = L.tile_end - L.tile_begin;
+    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
+    *t0 = L.tile_begin + sp * per;
+    *t1 = min(L.tile_end, *t0 + per);
+    return *t0 < *t1;
+}
+
+// Refinement level A: energy of the candidates below every threshold bin, and histogram
+// (count, energy) of bits 18..9 of the candidates inside each threshold bin.
+__global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
+    extern __shared__ unsigned char refine_smem[];
+    __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
+    __shared__ double s_red[kRefThreads / 64][kMaxTopk];
+    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
+    const TopkLayer& T = p.tl[l];
+    const uint32_t nlists = T.nlists;
+    if (nlists == 0) return;
+    const DevLayer L = p.layers[l];
+    int t0, t1;
+    if (!refine_range(L, sp, &t0, &t1)) return;
+    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
+    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
+    const int tid = threadIdx.x, ntk = p.ntk;
+    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
+    if (tid < kMaxTopk) {
+        s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
+        s_tbin[tid] = (tid < ntk && T.sel[tid].k) ? T.sel[tid].tbin : 0u;
+    }
+    __syncthreads();
+    double below[kMaxTopk];
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j) below[j] = 0.0;
+    double low = 0.0;                 // candidates under the lowest threshold bin: "below" for every k
+    const uint32_t min_tbin = T.min_tbin;
+    for_each_candidate(p, T, t0, t1, [&](uint32_t pat) {
+        const uint32_t key = pat >> kHistShift;
+        const float xf = __uint_as_float(pat);
+        const double x2 = (double)xf * (double)xf;
+        if (key < min_tbin) {
+            low += x2;
+            return;
+        }
+#pragma unroll
+        for (int j = 0; j < kMaxTopk; ++j)
+            if (j < ntk && key < s_tbin[j]) below[j] += x2;
+        for (uint32_t u = 0; u < nlists; ++u)
+            if (key == s_bin[u]) {
+                const uint32_t b = u * kBinsA + ((pat >> 9) & (kBinsA - 1));
                 atomicAdd(&s_cnt[b], 1u);
-                atomicAdd(&s_en[b], int_energy(pat[q]));
+                atomicAdd(&s_en[b], int_energy(pat));
             }
+    });
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j) {
+        if (j < ntk) {
+            const double s = wave_sum(below[j] + low);
+            if ((tid & 63) == 0) s_red[tid >> 6][j] = s;
         }
     }
     __syncthreads();
+    if (tid < ntk) {
+        double s = 0.0;
+        for (int w = 0; w < kRefThreads / 64; ++w) s += s_red[w][tid];
+        p.below_part[((size_t)l * p.splits + sp) * kMaxTopk + tid] = s;
+    }
     uint32_t* const gh = p.hist_a + (size_t)l * kMaxTopk * kBinsA;
     unsigned long long* const ge = p.en_a + (size_t)l * kMaxTopk * kBinsA;
     for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) {
@@ -471,60 +471,45 @@ __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
         T.sel[j].bin_a = bin_a;
         T.sel[j].need_a = S.need - s_res[1];
         T.sel[j].energy_a = s_e;
+        // energy of the candidates below the threshold bin: partial sums in split order
+        const DevLayer L = p.layers[l];
+        double s = 0.0;
+        for (int sp = 0; sp < p.splits; ++sp) {
+            int t0, t1;
+            if (refine_range(L, sp, &t0, &t1)) s += p.below_part[((size_t)l * p.splits + sp) * kMaxTopk + j];
+        }
+        T.sel[j].energy_below = s;
     }
 }
 
 // Refinement level B: histogram of bits 8..0 of the candidates inside each k's level-A sub-bin.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
+    __shared__ uint32_t s_prefix[kMaxTopk];      // top 22 bits (coarse bin, level-A bin) of each k
     const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
     const TopkLayer& T = p.tl[l];
-    const uint32_t nlists = T.nlists;
-    if (nlists == 0) return;
+    if (T.nlists == 0) return;
     const DevLayer L = p.layers[l];
-    const int ntiles = L.tile_end - L.tile_begin;
-    // at least 48 tiles (some 16 K candidates) per workgroup, so that flushing its histogram
-    // costs less than filling it
-    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
-    const int t0 = L.tile_begin + sp * per, t1 = min(L.tile_end, t0 + per);
-    if (t0 >= t1) return;
+    int t0, t1;
+    if (!refine_range(L, sp, &t0, &t1)) return;
     const int ntk = p.ntk;
     unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
     uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)ntk * kBinsB);
-    __shared__ uint32_t s_prefix[kMaxTopk];      // top 22 bits (coarse bin, level-A bin) of each k
     const int tid = threadIdx.x;
     for (int i = tid; i < ntk * kBinsB; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
     if (tid < kMaxTopk)
         s_prefix[tid] = (tid < ntk && T.sel[tid].k) ? ((T.sel[tid].tbin << 10) | T.sel[tid].bin_a) : 0xFFFFFFFFu;
     __syncthreads();
-    const int lane = tid & 63;
-    int t = t0 + (tid >> 6);
-    uint32_t n_next = 0;
-    int64_t pos_next = 0;
-    if (t < t1) { n_next = tile_candidates(p.tinfo[t], nlists); pos_next = p.tiles[t].pos; }
-    for (; t < t1; t += kRefThreads / 64) {
-        const uint32_t n = n_next;
-        const uint32_t* __restrict__ items = p.cand + T.cand_base + pos_next;
-        if (t + kRefThreads / 64 < t1) { n_next = tile_candidates(p.tinfo[t + kRefThreads / 64], nlists); pos_next = p.tiles[t + kRefThreads / 64].pos; }
-        for (uint32_t i0 = 0; i0 < n; i0 += 64 * 8) {
-            uint32_t pat[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint32_t i = i0 + q * 64 + lane;
-                pat[q] = i < n ? items[i] : 0xFFFFFFFFu;
+    const uint32_t min_pre = T.min_tbin << 10;
+    for_each_candidate(p, T, t0, t1, [&](uint32_t pat) {
+        const uint32_t pre = pat >> 9;
+        if (pre < min_pre) return;
+        for (int j = 0; j < ntk; ++j)
+            if (pre == s_prefix[j]) {
+                atomicAdd(&s_cnt[j * kBinsB + (pat & (kBinsB - 1))], 1u);
+                atomicAdd(&s_en[j * kBinsB + (pat & (kBinsB - 1))], int_energy(pat));
             }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (pat[q] == 0xFFFFFFFFu) continue;
-                const uint32_t pre = pat[q] >> 9;
-                for (int j = 0; j < ntk; ++j)
-                    if (pre == s_prefix[j]) {
-                        atomicAdd(&s_cnt[j * kBinsB + (pat[q] & (kBinsB - 1))], 1u);
-                        atomicAdd(&s_en[j * kBinsB + (pat[q] & (kBinsB - 1))], int_energy(pat[q]));
-                    }
-            }
-        }
-    }
+    });
     __syncthreads();
     uint32_t* const gh = p.hist_b + (size_t)l * kMaxTopk * kBinsB;
     unsigned long long* const ge = p.en_b + (size_t)l * kMaxTopk * kBinsB;
@@ -543,6 +528,7 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
+    __shared__ double s_base[256];
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
@@ -558,7 +544,18 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     unsigned long long e = 0;
     for (uint32_t b = tid; b < bin_b; b += 256) e += ge[b];
     atomicAdd(&s_e, e);
+    // energy below the collection bound: the layer's tile partials in tile order (fixed tree)
+    double base = 0.0;
+    if (p.errors) {
+        const DevLayer L = p.layers[l];
+        for (int t = L.tile_begin + tid; t < L.tile_end; t += 256) base += p.base_part[t];
+    }
+    s_base[tid] = base;
     __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) s_base[tid] += s_base[tid + o];
+        __syncthreads();
+    }
     if (tid == 0) {
         const uint32_t ties_keep = S.need_a - s_res[1];
         const uint32_t count_eq = s_hist[bin_b];
@@ -566,32 +563,35 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
         T.sel[j].thr = thr;
         T.sel[j].ties_keep = ties_keep;
         if (p.errors) {
-            // entries of the list below the threshold, plus the surplus equal entries
-            const unsigned long long total = S.energy_a + s_e + (unsigned long long)(count_eq - ties_keep) * int_energy(thr);
+            // entries of the threshold bin below the threshold, plus the surplus equal entries
+            const unsigned long long total =
+                S.energy_a + s_e + (unsigned long long)(count_eq - ties_keep) * int_energy(thr);
             const uint32_t ex = thr >> 23;
             const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + 16;
-            p.errors[(size_t)l * p.stride + p.col[j]] += ldexp((double)total, sh);
+            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + S.energy_below + ldexp((double)total, sh);
         }
     }
 }
 
 // ---------------------------------------------------------------- compression kernels
 // per tile: entries above the threshold, entries equal to it (from the tile's candidates)
-__global__ __launch_bounds__(64) void topk_count_kernel(const DevLayer* __restrict__ layers,
-                                                         const Tile* __restrict__ tiles,
-                                                         const TopkLayer* __restrict__ tl,
-                                                         const TopkTileInfo* __restrict__ tinfo,
-                                                         const uint32_t* __restrict__ cand,
-                                                         uint2* __restrict__ tilecnt) {
+__global__ __launch_bounds__(kThreads) void topk_count_kernel(const DevLayer* __restrict__ layers,
+                                                               const Tile* __restrict__ tiles,
+                                                               const TopkLayer* __restrict__ tl,
+                                                               const TopkTileInfo* __restrict__ tinfo,
+                                                               const uint32_t* __restrict__ cand,
+                                                               uint2* __restrict__ tilecnt) {
+    __shared__ uint32_t s_gt[kThreads / 64], s_eq[kThreads / 64];
     const Tile t = tiles[blockIdx.x];
     const DevLayer L = layers[t.layer];
     if (L.family != LGRECO_TOPK) return;
     const TopkLayer& T = tl[t.layer];
     const uint32_t thr = T.sel[0].thr;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const TopkTileInfo ti = tinfo[blockIdx.x];
-    const uint32_t* __restrict__ items = cand + T.cand_base + t.pos;
+    const uint32_t* __restrict__ items = cand + T.cand_base + t.pos + ti.start[wave];
     uint32_t gt = 0, eq = 0;
-    for (uint32_t i = threadIdx.x; i < ti.cnt[0]; i += 64) {
+    for (uint32_t i = lane; i < ti.cnt[wave]; i += 64) {
         const uint32_t pat = items[i];
         gt += pat > thr;
         eq += pat == thr;
@@ -600,7 +600,10 @@ __global__ __launch_bounds__(64) void topk_count_kernel(const DevLayer* __restri
         gt += __shfl_xor(gt, o, 64);
         eq += __shfl_xor(eq, o, 64);
     }
-    if (threadIdx.x == 0) tilecnt[blockIdx.x] = make_uint2(ti.above + gt, eq);
+    if (lane == 0) { s_gt[wave] = gt; s_eq[wave] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        tilecnt[blockIdx.x] = make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
 }
 
 // per layer: exclusive prefix of the tile counts
@@ -723,14 +726,17 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     t->max_elems = max_elems;
     t->max_layers = max_layers;
     t->max_tiles = max_tiles;
-    TK_CHECK(hipMalloc(&t->d_hist, sizeof(uint32_t) * (size_t)max_layers * kHistBins));
+    TK_CHECK(hipMalloc(&t->d_hist, sizeof(uint32_t) * 2 * (size_t)max_layers * kHistBins));   // exact + sample
     TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk));
+    TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand_base, sizeof(int64_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
+    TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
+    TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)max_layers * kRefSplits * kMaxTopk));
     t->ref_words = (size_t)max_layers * kMaxTopk * (kBinsA + kBinsB) * 3;       // u32 + u64 per bin
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
     TK_CHECK(hipHostMalloc(&t->h_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk, hipHostMallocDefault));
@@ -743,18 +749,24 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_tl);
     (void)hipFree(t->d_cand);
     (void)hipFree(t->d_k);
+    (void)hipFree(t->d_lo);
     (void)hipFree(t->d_cand_base);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
     (void)hipFree(t->d_tinfo);
+    (void)hipFree(t->d_base_part);
+    (void)hipFree(t->d_below_part);
     (void)hipFree(t->d_ref);
     (void)hipHostFree(t->h_k);
     (void)hipHostFree(t->h_cand_base);
     *t = TopkScratch{};
 }
 
-// Upload the requested k per (layer, candidate) (0 = layer inactive) and clear the histograms.
-hipError_t topk_begin(TopkScratch* t, const DevLayer* h_layers, int L, const uint32_t* ks, hipStream_t s) {
+// Upload the requested k per (layer, candidate) (0 = layer inactive), clear both histograms, take
+// the sample and predict the collection bound of every layer.
+hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
+                      int ntk, Timing* tm, hipStream_t s) {
     int64_t base = 0;
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < kMaxTopk; ++j) t->h_k[(size_t)l * kMaxTopk + j] = ks[(size_t)l * kMaxTopk + j];
@@ -763,44 +775,62 @@ hipError_t topk_begin(TopkScratch* t, const DevLayer* h_layers, int L, const uin
     }
     TK_CHECK(hipMemcpyAsync(t->d_k, t->h_k, sizeof(uint32_t) * (size_t)L * kMaxTopk, hipMemcpyHostToDevice, s));
     TK_CHECK(hipMemcpyAsync(t->d_cand_base, t->h_cand_base, sizeof(int64_t) * (size_t)L, hipMemcpyHostToDevice, s));
-    const size_t n = (size_t)L * kHistBins;
+    Section sec(tm, "topk_sample");
+    const size_t n = 2 * (size_t)L * kHistBins;
+    uint32_t* const shist = t->d_hist + (size_t)L * kHistBins;
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
                        t->d_hist, n, 0u);
+    TK_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(topk_sample_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
+                       (const uint32_t*)t->d_k, shist);
+    TK_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(topk_predict_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)shist,
+                       (const uint32_t*)t->d_k, ntk, d_layers, t->d_lo);
     return hipGetLastError();
 }
 
-hipError_t topk_hist(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                     const Tile* d_tiles, int n_tiles, hipStream_t s) {
-    if (n_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL(topk_hist_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
-                       (const uint32_t*)t->d_k, t->d_hist);
-    return hipGetLastError();
-}
-
-hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                       const Tile* d_tiles, int L, int n_tiles, int ntk, const int* col, double* d_partials,
-                       int stride, Timing* tm, hipStream_t s) {
-    {
-        Section sec(tm, "topk_scan");
-        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)t->d_hist,
-                           (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base, (TopkLayer*)t->d_tl);
-        TK_CHECK(hipGetLastError());
-    }
-    PassBParams p{};
+static CollectParams collect_params(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                                    const Tile* d_tiles) {
+    CollectParams p{};
     p.g = g;
     p.e = e;
     p.layers = d_layers;
     p.tiles = d_tiles;
-    p.tl = (TopkLayer*)t->d_tl;
+    p.ks = t->d_k;
+    p.tl = (const TopkLayer*)t->d_tl;
+    p.lo = t->d_lo;
+    p.hist = t->d_hist;
     p.cand = t->d_cand;
+    p.cand_base = t->d_cand_base;
     p.tinfo = (TopkTileInfo*)t->d_tinfo;
-    p.partials = d_partials;
-    p.stride = stride;
-    p.ntk = ntk;
-    for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
+    p.base_part = t->d_base_part;
+    return p;
+}
+
+// main pass without quantization candidates: histogram + collection in one read
+hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                        const Tile* d_tiles, int n_tiles, hipStream_t s) {
+    if (n_tiles <= 0) return hipSuccess;
+    CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
+    hipLaunchKernelGGL((topk_collect_kernel<true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+    return hipGetLastError();
+}
+
+// exact threshold bins; layers whose predicted bound was too high are collected again
+hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, Timing* tm, hipStream_t s) {
     {
-        Section sec(tm, "topk_pass_b");
-        hipLaunchKernelGGL(topk_passb_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        Section sec(tm, "topk_scan");
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)t->d_hist,
+                           (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base, t->d_lo,
+                           (TopkLayer*)t->d_tl);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_recollect");
+        CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
+        p.only_flagged = 1;
+        hipLaunchKernelGGL((topk_collect_kernel<false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
         TK_CHECK(hipGetLastError());
     }
     return hipSuccess;
@@ -814,6 +844,8 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     p.tiles = d_tiles;
     p.tinfo = (const TopkTileInfo*)t->d_tinfo;
     p.cand = t->d_cand;
+    p.base_part = t->d_base_part;
+    p.below_part = t->d_below_part;
     // refinement histograms of the layers in use: [counts A][counts B][energies A][energies B]
     const size_t na = (size_t)L * kMaxTopk * kBinsA, nb = (size_t)L * kMaxTopk * kBinsB;
     p.hist_a = t->d_ref;
@@ -849,24 +881,22 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
                          Timing* tm, hipStream_t s) {
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
-    for (int l = 0; l < L; ++l)
-        if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
-    {
-        Section sec(tm, "topk_zero");
-        TK_CHECK(topk_begin(t, h_layers, L, ks.data(), s));
-    }
-    {
-        Section sec(tm, "topk_hist");
-        TK_CHECK(topk_hist(t, g, e, d_layers, d_tiles, n_tiles, s));
-    }
-    TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, nullptr, nullptr, 0, tm, s));
     int max_tiles = 0;
     for (int l = 0; l < L; ++l)
-        if (h_layers[l].family == LGRECO_TOPK) max_tiles = std::max(max_tiles, h_layers[l].tile_end - h_layers[l].tile_begin);
+        if (h_layers[l].family == LGRECO_TOPK) {
+            ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
+            max_tiles = std::max(max_tiles, h_layers[l].tile_end - h_layers[l].tile_begin);
+        }
+    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, tm, s));
+    {
+        Section sec(tm, "topk_collect");
+        TK_CHECK(topk_collect(t, g, e, d_layers, d_tiles, n_tiles, s));
+    }
+    TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, tm, s));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, max_tiles, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
-        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(64), 0, s, d_layers, d_tiles,
+        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(kThreads), 0, s, d_layers, d_tiles,
                            (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
                            (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
         TK_CHECK(hipGetLastError());

@@ -1,0 +1,50 @@
+// Device-side pieces of the Top-K path shared by the stand-alone collection kernel and the
+// fused quantization-profile kernel.
+#pragma once
+
+#include "common.h"
+
+namespace lgreco {
+
+// Per tile: what each of the 4 wavefronts wrote into the tile's slice of the candidate buffer.
+// A wavefront owns a contiguous range of the tile's elements and writes its candidates from the
+// slot of its own first element on, so slices never collide and no atomics are needed.
+struct TopkTileInfo {
+    uint32_t cnt[kThreads / 64];
+    uint32_t start[kThreads / 64];     // first slot, relative to the tile's slice
+};
+
+__device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+// Candidate collection of one wavefront.  Elements whose coarse key (top 12 bits of |x|) is at or
+// above `lo` are written out in ballot-prefix order (the same order on every run); the energy of
+// the others is summed per lane.
+struct Collector {
+    uint32_t* dst;
+    uint32_t lo;
+    uint32_t cur;      // candidates written so far (uniform over the wavefront)
+    float base;        // this lane's sum of x^2 over elements below lo
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t l) { dst = d; lo = l; cur = 0; base = 0.0f; }
+    __device__ __forceinline__ void take(float x, bool valid) {
+        const uint32_t pat = mag_bits(x);
+        const bool hit = valid && (pat >> kHistShift) >= lo;
+        const unsigned long long m = __ballot(hit);
+        if (hit) {
+            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            dst[cur + below] = pat;
+        } else if (valid) {
+            base = __builtin_fmaf(x, x, base);
+        }
+        cur += (uint32_t)__popcll(m);
+    }
+};
+
+// Contiguous share of `n` work items for wavefront `wave` of 4: [begin, end)
+__device__ __forceinline__ void wave_range(int n, int wave, int* begin, int* end) {
+    const int q = (n + kThreads / 64 - 1) / (kThreads / 64);
+    *begin = min(n, wave * q);
+    *end = min(n, (wave + 1) * q);
+}
+
+}  // namespace lgreco

@@ -107,3 +107,18 @@ def test_near_ties_within_the_same_fine_bin():
     x[300] = np.nextafter(near, np.float32(2.0), dtype=np.float32)
     x[400:420] = base
     _check(_flat_batch([x]), (1 / 20000, 2 / 20000, 3 / 20000, 0.001, 0.0011, 0.5))
+
+
+def test_unrepresentative_sample_is_corrected():
+    # The threshold prediction looks at one 512-element chunk out of 16.  Here exactly those chunks
+    # hold large values and everything else small ones (and the other way round), so the predicted
+    # bound is far off in both directions; results must not change.
+    rng = np.random.default_rng(7)
+    n = 5 * 65536 + 3000
+    sampled = (np.arange(n) % 8192) < 512
+    big = rng.laplace(0, 1.0, n).astype(np.float32)
+    small = rng.laplace(0, 1e-3, n).astype(np.float32)
+    a = np.where(sampled, big, small).astype(np.float32)
+    b = np.where(sampled, small, big).astype(np.float32)
+    c = np.where(sampled, np.float32(0.0), big).astype(np.float32)
+    _check(_flat_batch([a, b, c]), (0.001, 0.01, 0.1, 0.5))
