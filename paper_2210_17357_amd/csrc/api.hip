@@ -414,21 +414,17 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
     } else if (ntk) {
         Section sec(&h->tm, "topk_collect");
-        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, s));
+        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
     }
-    if (ntk) HIPCHK(topk_select(&h->topk, d_grads, d_ef, h->d_layers, h->d_tiles, L, n_tiles, ntk, &h->tm, s));
+    if (ntk)
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, &h->tm, s));
     if (qp.nq) {
         uint32_t qmask = 0;
         for (int i = 0; i < qp.nq; ++i) qmask |= 1u << qp.col[i];
         Section sec(&h->tm, "reduce_partials");
         HIPCHK(launch_reduce_partials(h->d_partials, P, qmask, h->d_layers, L, h->d_errors, s));
     }
-    if (ntk) {
-        int max_tiles = 0;
-        for (int l = 0; l < L; ++l) max_tiles = std::max(max_tiles, h->hl[l].tile_end - h->hl[l].tile_begin);
-        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, max_tiles, ntk, tk_col, h->d_errors, P, &h->tm,
-                             s));
-    }
+    if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, h->d_errors, P, &h->tm, s));
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
                                lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));

@@ -68,6 +68,7 @@ struct TopkScratch {
     uint32_t* d_hist = nullptr;       // [2 x max_layers x kHistBins] exact coarse histogram, then the sample's
     void* d_tl = nullptr;             // per-layer selection records
     uint32_t* d_cand = nullptr;       // bit patterns of the candidates, tile i at its own first element
+    uint32_t* d_cand_idx = nullptr;   // compress: index within the layer (+ sign bit) of every candidate
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
     uint32_t* d_lo = nullptr;         // [max_layers] lowest coarse key collected as a candidate
     int64_t* d_cand_base = nullptr;   // [max_layers] first candidate slot of every layer
@@ -76,8 +77,13 @@ struct TopkScratch {
     void* d_tinfo = nullptr;          // per tile, per wavefront: candidates written and where
     double* d_base_part = nullptr;    // per tile energy below the collection bound
     double* d_below_part = nullptr;   // refinement partial sums
-    uint32_t* d_ref = nullptr;        // refinement histograms (counts and integer energies)
+    uint32_t* d_ref = nullptr;        // per-workgroup refinement histograms (counts, integer energies)
     size_t ref_words = 0;
+    void* d_work = nullptr;           // refinement work table and per-layer ranges
+    void* d_work_range = nullptr;
+    void* h_work = nullptr;           // pinned
+    void* h_work_range = nullptr;     // pinned
+    int max_work = 0, n_work = 0;
     uint32_t* h_k = nullptr;          // pinned
     int64_t* h_cand_base = nullptr;   // pinned
     int64_t max_elems = 0;
@@ -92,15 +98,15 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       int ntk, Timing* tm, hipStream_t s);
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
 // the read; otherwise the quantization profile kernel does the same work
-hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                         const Tile* d_tiles, int n_tiles, hipStream_t s);
 // exact threshold bins from the histogram; layers whose predicted bound was too high are
 // collected again with the exact one
-hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                        const Tile* d_tiles, int L, int n_tiles, int ntk, Timing* tm, hipStream_t s);
 // refinement on the candidates: exact thresholds; writes the dropped energy to errors (if not null)
-hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int max_layer_tiles,
-                         int ntk, const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
+                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
                          Timing* tm, hipStream_t s);

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(t.count / kChunk, wave, &c_begin, &c_end);
         if (HIST) {
             col_start = (uint32_t)c_begin * kChunk;
-            col.init(slice + col_start, col_lo);
+            col.init(slice + col_start, nullptr, col_lo);
         }
         for (int c = c_begin; c < c_end; ++c) {
             const int base = c * kChunk + (lane >> 4) * kBucket + j * 4;
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(nb, wave, &b_begin, &b_end);
         if (HIST) {
             col_start = (uint32_t)b_begin * kBucket;
-            col.init(slice + col_start, col_lo);
+            col.init(slice + col_start, nullptr, col_lo);
         }
         for (int bk = b_begin; bk < b_end; ++bk) {
             float x[2];

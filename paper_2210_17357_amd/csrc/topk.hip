@@ -45,8 +45,7 @@ struct TopkLayer {
     TopkList lists[kMaxTopk];
     TopkSel sel[kMaxTopk];
 };
-constexpr int kRefSplits = 128;     // refinement workgroups per layer, at most
-constexpr int kRefTilesMin = 4;     // tiles per refinement workgroup, at least
+constexpr int kRefTiles = 8;        // tiles per refinement workgroup
 constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
@@ -191,6 +190,9 @@ struct CollectParams {
     uint32_t* lo;
     uint32_t* hist;
     uint32_t* cand;
+    uint32_t* cand_idx;         // compress: index within the layer and sign of every candidate
+    float* ef_out;              // compress: error feedback, written as x everywhere (kept entries are
+                                // zeroed afterwards by the emit kernel)
     const int64_t* cand_base;
     TopkTileInfo* tinfo;
     double* base_part;
@@ -199,7 +201,7 @@ struct CollectParams {
 
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
 // collection.  With only_flagged it collects again the layers whose predicted bound was too high.
-template <bool HIST>
+template <bool HIST, bool EMIT>
 __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p) {
     __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
     __shared__ double s_red[kThreads / 64];
@@ -209,45 +211,51 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
     const DevLayer L = p.layers[t.layer];
     const float* gp = p.g + L.offset + t.pos;
     const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
+    float* const eo = EMIT ? p.ef_out + L.offset + t.pos : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (HIST) {
         for (int b = tid; b < kHistBins; b += kThreads) s_hist[b] = 0;
         __syncthreads();
     }
-    uint32_t* const slice = p.cand + p.cand_base[t.layer] + t.pos;
+    const int64_t slice_off = p.cand_base[t.layer] + t.pos;
+    uint32_t* const slice = p.cand + slice_off;
+    uint32_t* const slice_idx = EMIT ? p.cand_idx + slice_off : nullptr;
     Collector col;
     uint32_t start;
     if (t.fast) {
         int c0, c1;
         wave_range(t.count / kChunk, wave, &c0, &c1);
         start = (uint32_t)c0 * kChunk;
-        col.init(slice + start, p.lo[t.layer]);
+        col.init(slice + start, EMIT ? slice_idx + start : nullptr, p.lo[t.layer]);
         for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += 64) {     // uniform trip count
             float4 a = reinterpret_cast<const float4*>(gp)[v];
             if (ep) {
                 const float4 b = reinterpret_cast<const float4*>(ep)[v];
                 a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
             }
+            if (EMIT) reinterpret_cast<float4*>(eo)[v] = a;
             if (HIST) {
                 atomicAdd(&s_hist[mag_bits(a.x) >> kHistShift], 1u);
                 atomicAdd(&s_hist[mag_bits(a.y) >> kHistShift], 1u);
                 atomicAdd(&s_hist[mag_bits(a.z) >> kHistShift], 1u);
                 atomicAdd(&s_hist[mag_bits(a.w) >> kHistShift], 1u);
             }
-            col.take(a.x, true); col.take(a.y, true); col.take(a.z, true); col.take(a.w, true);
+            const float x[4] = {a.x, a.y, a.z, a.w};
+            col.take4(x, (uint32_t)(t.pos + 4 * (int64_t)v));
         }
     } else {
         int b0, b1;
         wave_range((t.count + 63) / 64, wave, &b0, &b1);
         start = (uint32_t)b0 * 64;
-        col.init(slice + start, p.lo[t.layer]);
+        col.init(slice + start, EMIT ? slice_idx + start : nullptr, p.lo[t.layer]);
         for (int b = b0; b < b1; ++b) {
             const int i = b * 64 + lane;
             const bool valid = i < t.count;
             float x = 0.0f;
             if (valid) x = ep ? gp[i] + ep[i] : gp[i];
+            if (EMIT && valid) eo[i] = x;
             if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
-            col.take(x, valid);
+            col.take(x, valid, (uint32_t)(t.pos + i));
         }
     }
     const double bs = wave_sum((double)col.base);
@@ -323,23 +331,28 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
     }
 }
 
+struct RefWork {                     // one refinement workgroup: tiles [t0, t1) of a layer
+    int32_t layer, t0, t1, pad;
+};
 struct RefineParams {
     TopkLayer* tl;
     const DevLayer* layers;
     const Tile* tiles;
     const TopkTileInfo* tinfo;
     const uint32_t* cand;
+    const RefWork* work;              // [n_work]
+    const int2* work_range;           // [L] the layer's workgroups [x, y)
     const double* base_part;          // [n_tiles]
-    double* below_part;               // [L x splits x kMaxTopk] energy of candidates below each threshold bin
-    uint32_t* hist_a;                 // [L x kMaxTopk x kBinsA] counts per list
-    unsigned long long* en_a;         // same shape, integer energies
-    uint32_t* hist_b;                 // [L x kMaxTopk x kBinsB] per requested k
+    double* below_part;               // [n_work x kMaxTopk] energy of candidates below each threshold bin
+    // per-workgroup partial histograms (plain stores, summed in workgroup order by the pick kernels)
+    uint32_t* cnt_a;                  // [n_work x kMaxTopk x kBinsA]
+    unsigned long long* en_a;
+    uint32_t* cnt_b;                  // [n_work x kMaxTopk x kBinsB]
     unsigned long long* en_b;
     double* errors;                   // may be null (compress)
     int32_t stride;
     int32_t ntk;
     int32_t col[kMaxTopk];
-    int32_t splits;                   // refinement workgroups per layer in this launch
 };
 
 // Walks the candidates of tiles [t0, t1): one (tile, wavefront slice) pair per wavefront at a
@@ -368,27 +381,16 @@ __device__ __forceinline__ void for_each_candidate(const RefineParams& p, const 
     }
 }
 
-__device__ __forceinline__ bool refine_range(const DevLayer& L, int sp, int* t0, int* t1) {
-    const int ntiles = L.tile_end - L.tile_begin;
-    const int per = max(kRefTilesMin, (ntiles + kRefSplits - 1) / kRefSplits);
-    *t0 = L.tile_begin + sp * per;
-    *t1 = min(L.tile_end, *t0 + per);
-    return *t0 < *t1;
-}
-
 // Refinement level A: energy of the candidates below every threshold bin, and histogram
 // (count, energy) of bits 18..9 of the candidates inside each threshold bin.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
     __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
     __shared__ double s_red[kRefThreads / 64][kMaxTopk];
-    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
+    const RefWork w = p.work[blockIdx.x];
+    const int l = w.layer;
     const TopkLayer& T = p.tl[l];
     const uint32_t nlists = T.nlists;
-    if (nlists == 0) return;
-    const DevLayer L = p.layers[l];
-    int t0, t1;
-    if (!refine_range(L, sp, &t0, &t1)) return;
     unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
     uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
     const int tid = threadIdx.x, ntk = p.ntk;
@@ -403,7 +405,7 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
     for (int j = 0; j < kMaxTopk; ++j) below[j] = 0.0;
     double low = 0.0;                 // candidates under the lowest threshold bin: "below" for every k
     const uint32_t min_tbin = T.min_tbin;
-    for_each_candidate(p, T, t0, t1, [&](uint32_t pat) {
+    for_each_candidate(p, T, w.t0, w.t1, [&](uint32_t pat) {
         const uint32_t key = pat >> kHistShift;
         const float xf = __uint_as_float(pat);
         const double x2 = (double)xf * (double)xf;
@@ -431,23 +433,21 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
     __syncthreads();
     if (tid < ntk) {
         double s = 0.0;
-        for (int w = 0; w < kRefThreads / 64; ++w) s += s_red[w][tid];
-        p.below_part[((size_t)l * p.splits + sp) * kMaxTopk + tid] = s;
+        for (int wv = 0; wv < kRefThreads / 64; ++wv) s += s_red[wv][tid];
+        p.below_part[(size_t)blockIdx.x * kMaxTopk + tid] = s;
     }
-    uint32_t* const gh = p.hist_a + (size_t)l * kMaxTopk * kBinsA;
-    unsigned long long* const ge = p.en_a + (size_t)l * kMaxTopk * kBinsA;
+    uint32_t* const gc = p.cnt_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
+    unsigned long long* const ge = p.en_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
     for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) {
-        const uint32_t c = s_cnt[i];
-        if (c) {
-            atomicAdd(&gh[i], c);
-            atomicAdd(&ge[i], s_en[i]);
-        }
+        gc[i] = s_cnt[i];
+        ge[i] = s_en[i];
     }
 }
 
 // One workgroup per (layer, requested k): sub-bin of level A holding the k-th magnitude.
 __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsA];
+    __shared__ unsigned long long s_en[kBinsA];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
@@ -455,29 +455,43 @@ __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
     const TopkSel S = T.sel[j];
-    const uint32_t* gh = p.hist_a + ((size_t)l * kMaxTopk + S.list) * kBinsA;
-    const unsigned long long* ge = p.en_a + ((size_t)l * kMaxTopk + S.list) * kBinsA;
+    const int2 wr = p.work_range[l];
     const int tid = threadIdx.x;
-    for (int b = tid; b < kBinsA; b += 256) s_hist[b] = gh[b];
+    // sum the layer's workgroup partials of this k's list, in workgroup order
+    {
+        // 4 bins per thread, workgroups outermost and unrolled: many independent loads in flight
+        uint32_t c[4] = {0, 0, 0, 0};
+        unsigned long long e[4] = {0, 0, 0, 0};
+        const size_t off = (size_t)S.list * kBinsA + tid;
+#pragma unroll 4
+        for (int wg = wr.x; wg < wr.y; ++wg) {
+            const size_t i = (size_t)wg * kMaxTopk * kBinsA + off;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                c[q] += p.cnt_a[i + 256 * q];
+                e[q] += p.en_a[i + 256 * q];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            s_hist[tid + 256 * q] = c[q];
+            s_en[tid + 256 * q] = e[q];
+        }
+    }
     if (tid == 0) s_e = 0;
     __syncthreads();
     block_kth_from_top(s_hist, kBinsA, S.need, s_scan, s_res);
     const uint32_t bin_a = s_res[0];
     unsigned long long e = 0;
-    for (uint32_t b = tid; b < bin_a; b += 256) e += ge[b];
+    for (uint32_t b = tid; b < bin_a; b += 256) e += s_en[b];
     atomicAdd(&s_e, e);
     __syncthreads();
     if (tid == 0) {
         T.sel[j].bin_a = bin_a;
         T.sel[j].need_a = S.need - s_res[1];
         T.sel[j].energy_a = s_e;
-        // energy of the candidates below the threshold bin: partial sums in split order
-        const DevLayer L = p.layers[l];
-        double s = 0.0;
-        for (int sp = 0; sp < p.splits; ++sp) {
-            int t0, t1;
-            if (refine_range(L, sp, &t0, &t1)) s += p.below_part[((size_t)l * p.splits + sp) * kMaxTopk + j];
-        }
+        double s = 0.0;               // energy of the candidates below the threshold bin
+        for (int wg = wr.x; wg < wr.y; ++wg) s += p.below_part[(size_t)wg * kMaxTopk + j];
         T.sel[j].energy_below = s;
     }
 }
@@ -486,12 +500,8 @@ __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
 __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
     __shared__ uint32_t s_prefix[kMaxTopk];      // top 22 bits (coarse bin, level-A bin) of each k
-    const int l = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
-    const TopkLayer& T = p.tl[l];
-    if (T.nlists == 0) return;
-    const DevLayer L = p.layers[l];
-    int t0, t1;
-    if (!refine_range(L, sp, &t0, &t1)) return;
+    const RefWork w = p.work[blockIdx.x];
+    const TopkLayer& T = p.tl[w.layer];
     const int ntk = p.ntk;
     unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
     uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)ntk * kBinsB);
@@ -501,7 +511,7 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams
         s_prefix[tid] = (tid < ntk && T.sel[tid].k) ? ((T.sel[tid].tbin << 10) | T.sel[tid].bin_a) : 0xFFFFFFFFu;
     __syncthreads();
     const uint32_t min_pre = T.min_tbin << 10;
-    for_each_candidate(p, T, t0, t1, [&](uint32_t pat) {
+    for_each_candidate(p, T, w.t0, w.t1, [&](uint32_t pat) {
         const uint32_t pre = pat >> 9;
         if (pre < min_pre) return;
         for (int j = 0; j < ntk; ++j)
@@ -511,20 +521,18 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams
             }
     });
     __syncthreads();
-    uint32_t* const gh = p.hist_b + (size_t)l * kMaxTopk * kBinsB;
-    unsigned long long* const ge = p.en_b + (size_t)l * kMaxTopk * kBinsB;
+    uint32_t* const gc = p.cnt_b + (size_t)blockIdx.x * kMaxTopk * kBinsB;
+    unsigned long long* const ge = p.en_b + (size_t)blockIdx.x * kMaxTopk * kBinsB;
     for (int i = tid; i < ntk * kBinsB; i += kRefThreads) {
-        const uint32_t c = s_cnt[i];
-        if (c) {
-            atomicAdd(&gh[i], c);
-            atomicAdd(&ge[i], s_en[i]);
-        }
+        gc[i] = s_cnt[i];
+        ge[i] = s_en[i];
     }
 }
 
 // One workgroup per (layer, requested k): exact threshold, equal entries kept, dropped energy.
 __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsB];
+    __shared__ unsigned long long s_en[kBinsB];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
@@ -533,16 +541,33 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
     const TopkSel S = T.sel[j];
-    const uint32_t* gh = p.hist_b + ((size_t)l * kMaxTopk + j) * kBinsB;
-    const unsigned long long* ge = p.en_b + ((size_t)l * kMaxTopk + j) * kBinsB;
+    const int2 wr = p.work_range[l];
     const int tid = threadIdx.x;
-    for (int b = tid; b < kBinsB; b += 256) s_hist[b] = gh[b];
+    {
+        uint32_t c[2] = {0, 0};
+        unsigned long long e[2] = {0, 0};
+        const size_t off = (size_t)j * kBinsB + tid;
+#pragma unroll 8
+        for (int wg = wr.x; wg < wr.y; ++wg) {
+            const size_t i = (size_t)wg * kMaxTopk * kBinsB + off;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                c[q] += p.cnt_b[i + 256 * q];
+                e[q] += p.en_b[i + 256 * q];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            s_hist[tid + 256 * q] = c[q];
+            s_en[tid + 256 * q] = e[q];
+        }
+    }
     if (tid == 0) s_e = 0;
     __syncthreads();
     block_kth_from_top(s_hist, kBinsB, S.need_a, s_scan, s_res);
     const uint32_t bin_b = s_res[0];
     unsigned long long e = 0;
-    for (uint32_t b = tid; b < bin_b; b += 256) e += ge[b];
+    for (uint32_t b = tid; b < bin_b; b += 256) e += s_en[b];
     atomicAdd(&s_e, e);
     // energy below the collection bound: the layer's tile partials in tile order (fixed tree)
     double base = 0.0;
@@ -574,14 +599,17 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
 }
 
 // ---------------------------------------------------------------- compression kernels
-// per tile: entries above the threshold, entries equal to it (from the tile's candidates)
+// The compressor keeps the collector's partition: wavefront w of a tile owns the same contiguous
+// element range it collected candidates from, so everything below is per wavefront and needs no
+// workgroup barrier.
+
+// per (tile, wavefront): entries above the threshold, entries equal to it (from its candidates)
 __global__ __launch_bounds__(kThreads) void topk_count_kernel(const DevLayer* __restrict__ layers,
                                                                const Tile* __restrict__ tiles,
                                                                const TopkLayer* __restrict__ tl,
                                                                const TopkTileInfo* __restrict__ tinfo,
                                                                const uint32_t* __restrict__ cand,
-                                                               uint2* __restrict__ tilecnt) {
-    __shared__ uint32_t s_gt[kThreads / 64], s_eq[kThreads / 64];
+                                                               uint2* __restrict__ wavecnt) {
     const Tile t = tiles[blockIdx.x];
     const DevLayer L = layers[t.layer];
     if (L.family != LGRECO_TOPK) return;
@@ -600,118 +628,91 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(const DevLayer* __
         gt += __shfl_xor(gt, o, 64);
         eq += __shfl_xor(eq, o, 64);
     }
-    if (lane == 0) { s_gt[wave] = gt; s_eq[wave] = eq; }
-    __syncthreads();
-    if (threadIdx.x == 0)
-        tilecnt[blockIdx.x] = make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
+    if (lane == 0) wavecnt[(size_t)blockIdx.x * (kThreads / 64) + wave] = make_uint2(gt, eq);
 }
 
-// per layer: exclusive prefix of the tile counts
+// per layer: exclusive prefix of the per-wavefront counts, in element order
 __global__ __launch_bounds__(256) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
-                                                            const uint2* __restrict__ tilecnt,
-                                                            uint2* __restrict__ tilebase) {
+                                                            const uint2* __restrict__ wavecnt,
+                                                            uint2* __restrict__ wavebase) {
     __shared__ uint32_t s_tmp[kThreads / 64];
     const DevLayer L = layers[blockIdx.x];
     if (L.family != LGRECO_TOPK) return;
     uint32_t run_gt = 0, run_eq = 0;
-    for (int t0 = L.tile_begin; t0 < L.tile_end; t0 += 256) {
-        const int t = t0 + threadIdx.x;
-        const uint2 c = t < L.tile_end ? tilecnt[t] : make_uint2(0, 0);
+    const int q0 = L.tile_begin * (kThreads / 64), q1 = L.tile_end * (kThreads / 64);
+    for (int b = q0; b < q1; b += 256) {
+        const int q = b + threadIdx.x;
+        const uint2 c = q < q1 ? wavecnt[q] : make_uint2(0, 0);
         uint32_t tot_gt, tot_eq;
         const uint32_t pg = block_excl_scan(c.x, s_tmp, &tot_gt);
         const uint32_t pe = block_excl_scan(c.y, s_tmp, &tot_eq);
-        if (t < L.tile_end) tilebase[t] = make_uint2(run_gt + pg, run_eq + pe);
+        if (q < q1) wavebase[q] = make_uint2(run_gt + pg, run_eq + pe);
         run_gt += tot_gt;
         run_eq += tot_eq;
     }
 }
 
-// per tile: kept values and indices in ascending index order; error feedback
-__global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __restrict__ g, float* __restrict__ e,
-                                                               const DevLayer* __restrict__ layers,
-                                                               const Tile* __restrict__ tiles,
-                                                               const TopkLayer* __restrict__ tl,
-                                                               const uint2* __restrict__ tilecnt,
-                                                               const uint2* __restrict__ tilebase,
-                                                               uint8_t* __restrict__ payload) {
-    __shared__ uint32_t s_tmp[kThreads / 64];
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long m, uint32_t add) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, add));
+}
+
+// Kept values and indices in ascending index order, from the candidates alone (every kept entry
+// is a candidate, and a wavefront's candidates are stored in element order); the error feedback,
+// already written as x everywhere by the collection pass, is zeroed at the kept entries.
+__global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ e,
+                                                              const DevLayer* __restrict__ layers,
+                                                              const Tile* __restrict__ tiles,
+                                                              const TopkLayer* __restrict__ tl,
+                                                              const TopkTileInfo* __restrict__ tinfo,
+                                                              const uint32_t* __restrict__ cand,
+                                                              const uint32_t* __restrict__ cand_idx,
+                                                              const uint2* __restrict__ wavecnt,
+                                                              const uint2* __restrict__ wavebase,
+                                                              uint8_t* __restrict__ payload) {
     const Tile t = tiles[blockIdx.x];
     const DevLayer L = layers[t.layer];
     if (L.family != LGRECO_TOPK) return;
-    const TopkSel S = tl[t.layer].sel[0];
+    const TopkLayer& T = tl[t.layer];
+    const TopkSel S = T.sel[0];
     const uint32_t thr = S.thr, ties_keep = S.ties_keep, k = S.k;
-    const uint2 cnt = tilecnt[blockIdx.x];
-    const uint2 before = tilebase[blockIdx.x];
-    const float* gp = g + L.offset + t.pos;
-    float* ep = e + L.offset + t.pos;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint2 cnt = wavecnt[(size_t)blockIdx.x * (kThreads / 64) + wave];
+    const uint2 before = wavebase[(size_t)blockIdx.x * (kThreads / 64) + wave];
+    const TopkTileInfo ti = tinfo[blockIdx.x];
+    const int64_t off = T.cand_base + t.pos + ti.start[wave];
+    const uint32_t* __restrict__ pats = cand + off;
+    const uint32_t* __restrict__ idxs = cand_idx + off;
+    float* const ef = e + L.offset;
     float* const values = reinterpret_cast<float*>(payload + L.payload);
     uint32_t* const indices = reinterpret_cast<uint32_t*>(payload + L.payload) + k;
     // equal entries: global rank r (in index order) is kept iff r < ties_keep
-    const bool eq_all = before.y + cnt.y <= ties_keep;       // every equal entry of this tile kept
-    const bool eq_none = before.y >= ties_keep;              // none kept
-    uint32_t out = before.x + min(before.y, ties_keep);      // kept entries before this tile
+    const bool eq_all = before.y + cnt.y <= ties_keep;
+    const bool eq_none = before.y >= ties_keep;
+    uint32_t out = before.x + min(before.y, ties_keep);
     uint32_t eq_seen = before.y;
-    for (int s0 = 0; s0 < t.count; s0 += 4 * kThreads) {
-        const int i0 = s0 + 4 * threadIdx.x;
-        float x[4];
-        bool ok[4];
-        if (t.fast && i0 + 3 < t.count) {
-            const float4 a = *reinterpret_cast<const float4*>(gp + i0);
-            const float4 b = *reinterpret_cast<const float4*>(ep + i0);
-            x[0] = a.x + b.x; x[1] = a.y + b.y; x[2] = a.z + b.z; x[3] = a.w + b.w;
-            ok[0] = ok[1] = ok[2] = ok[3] = true;
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                ok[q] = i0 + q < t.count;
-                x[q] = ok[q] ? gp[i0 + q] + ep[i0 + q] : 0.0f;
-            }
+    const uint32_t n = ti.cnt[wave];
+    for (uint32_t i0 = 0; i0 < n; i0 += 64) {
+        const uint32_t i = i0 + lane;
+        const bool ok = i < n;
+        const uint32_t pat = ok ? pats[i] : 0u;
+        const uint32_t ix = ok ? idxs[i] : 0u;
+        bool keep = ok && pat > thr;
+        const bool eq = ok && pat == thr;
+        if (eq_all) {
+            keep = keep || eq;
+        } else if (!eq_none) {
+            const unsigned long long bq = __ballot(eq);
+            if (eq) keep = eq_seen + lanes_below(bq, 0u) < ties_keep;
+            eq_seen += (uint32_t)__popcll(bq);
         }
-        bool gt[4], eq[4], keep[4];
-        uint32_t neq = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t pat = mag_bits(x[q]);
-            gt[q] = ok[q] && pat > thr;
-            eq[q] = ok[q] && pat == thr;
-            neq += eq[q];
+        const unsigned long long kq = __ballot(keep);
+        if (keep) {
+            const uint32_t pos = out + lanes_below(kq, 0u);
+            values[pos] = __uint_as_float(pat | (ix & 0x80000000u));
+            indices[pos] = ix & 0x7FFFFFFFu;
+            ef[ix & 0x7FFFFFFFu] = 0.0f;
         }
-        uint32_t eq_rank = 0;
-        if (!eq_all && !eq_none) {                            // the tie boundary is inside this tile
-            uint32_t tot;
-            eq_rank = eq_seen + block_excl_scan(neq, s_tmp, &tot);
-            eq_seen += tot;
-        }
-        uint32_t nkeep = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bool ke = false;
-            if (eq[q]) {
-                ke = eq_all ? true : eq_none ? false : (eq_rank < ties_keep);
-                ++eq_rank;
-            }
-            keep[q] = gt[q] || ke;
-            nkeep += keep[q];
-        }
-        uint32_t tot;
-        uint32_t pos = out + block_excl_scan(nkeep, s_tmp, &tot);
-        out += tot;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (keep[q]) {
-                values[pos] = x[q];
-                indices[pos] = (uint32_t)(t.pos + i0 + q);
-                ++pos;
-            }
-        }
-        if (t.fast && i0 + 3 < t.count) {
-            *reinterpret_cast<float4*>(ep + i0) = make_float4(keep[0] ? 0.0f : x[0], keep[1] ? 0.0f : x[1],
-                                                              keep[2] ? 0.0f : x[2], keep[3] ? 0.0f : x[3]);
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (ok[q]) ep[i0 + q] = keep[q] ? 0.0f : x[q];
-        }
+        out += (uint32_t)__popcll(kq);
     }
 }
 
@@ -729,16 +730,22 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_hist, sizeof(uint32_t) * 2 * (size_t)max_layers * kHistBins));   // exact + sample
     TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
+    TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand_base, sizeof(int64_t) * (size_t)max_layers));
-    TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles));
-    TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles));
+    TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
+    TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
-    TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)max_layers * kRefSplits * kMaxTopk));
-    t->ref_words = (size_t)max_layers * kMaxTopk * (kBinsA + kBinsB) * 3;       // u32 + u64 per bin
+    t->max_work = max_tiles / kRefTiles + max_layers + 1;
+    TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
+    t->ref_words = (size_t)t->max_work * kMaxTopk * (kBinsA + kBinsB) * 3;      // u32 + u64 per bin
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
+    TK_CHECK(hipMalloc(&t->d_work, sizeof(RefWork) * (size_t)t->max_work));
+    TK_CHECK(hipMalloc(&t->d_work_range, sizeof(int2) * (size_t)max_layers));
+    TK_CHECK(hipHostMalloc(&t->h_work, sizeof(RefWork) * (size_t)t->max_work, hipHostMallocDefault));
+    TK_CHECK(hipHostMalloc(&t->h_work_range, sizeof(int2) * (size_t)max_layers, hipHostMallocDefault));
     TK_CHECK(hipHostMalloc(&t->h_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk, hipHostMallocDefault));
     TK_CHECK(hipHostMalloc(&t->h_cand_base, sizeof(int64_t) * (size_t)max_layers, hipHostMallocDefault));
     return hipSuccess;
@@ -748,6 +755,7 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_hist);
     (void)hipFree(t->d_tl);
     (void)hipFree(t->d_cand);
+    (void)hipFree(t->d_cand_idx);
     (void)hipFree(t->d_k);
     (void)hipFree(t->d_lo);
     (void)hipFree(t->d_cand_base);
@@ -757,6 +765,10 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_base_part);
     (void)hipFree(t->d_below_part);
     (void)hipFree(t->d_ref);
+    (void)hipFree(t->d_work);
+    (void)hipFree(t->d_work_range);
+    (void)hipHostFree(t->h_work);
+    (void)hipHostFree(t->h_work_range);
     (void)hipHostFree(t->h_k);
     (void)hipHostFree(t->h_cand_base);
     *t = TopkScratch{};
@@ -768,11 +780,23 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
                       int ntk, Timing* tm, hipStream_t s) {
     int64_t base = 0;
+    RefWork* const work = (RefWork*)t->h_work;
+    int2* const wrange = (int2*)t->h_work_range;
+    int nw = 0;
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < kMaxTopk; ++j) t->h_k[(size_t)l * kMaxTopk + j] = ks[(size_t)l * kMaxTopk + j];
         t->h_cand_base[l] = base;
-        if (ks[(size_t)l * kMaxTopk]) base += h_layers[l].numel;
+        wrange[l].x = nw;
+        if (ks[(size_t)l * kMaxTopk]) {
+            base += h_layers[l].numel;
+            for (int t0 = h_layers[l].tile_begin; t0 < h_layers[l].tile_end; t0 += kRefTiles)
+                work[nw++] = RefWork{l, t0, std::min(h_layers[l].tile_end, t0 + kRefTiles), 0};
+        }
+        wrange[l].y = nw;
     }
+    t->n_work = nw;
+    TK_CHECK(hipMemcpyAsync(t->d_work, work, sizeof(RefWork) * (size_t)std::max(nw, 1), hipMemcpyHostToDevice, s));
+    TK_CHECK(hipMemcpyAsync(t->d_work_range, wrange, sizeof(int2) * (size_t)L, hipMemcpyHostToDevice, s));
     TK_CHECK(hipMemcpyAsync(t->d_k, t->h_k, sizeof(uint32_t) * (size_t)L * kMaxTopk, hipMemcpyHostToDevice, s));
     TK_CHECK(hipMemcpyAsync(t->d_cand_base, t->h_cand_base, sizeof(int64_t) * (size_t)L, hipMemcpyHostToDevice, s));
     Section sec(tm, "topk_sample");
@@ -801,23 +825,29 @@ static CollectParams collect_params(TopkScratch* t, const float* g, const float*
     p.lo = t->d_lo;
     p.hist = t->d_hist;
     p.cand = t->d_cand;
+    p.cand_idx = t->d_cand_idx;
     p.cand_base = t->d_cand_base;
     p.tinfo = (TopkTileInfo*)t->d_tinfo;
     p.base_part = t->d_base_part;
     return p;
 }
 
-// main pass without quantization candidates: histogram + collection in one read
-hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+// main pass without quantization candidates: histogram + collection in one read.  ef_out != null
+// (compress): also records index and sign of every candidate and writes x to the error feedback.
+hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                         const Tile* d_tiles, int n_tiles, hipStream_t s) {
     if (n_tiles <= 0) return hipSuccess;
     CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
-    hipLaunchKernelGGL((topk_collect_kernel<true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+    p.ef_out = ef_out;
+    if (ef_out)
+        hipLaunchKernelGGL((topk_collect_kernel<true, true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+    else
+        hipLaunchKernelGGL((topk_collect_kernel<true, false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
     return hipGetLastError();
 }
 
 // exact threshold bins; layers whose predicted bound was too high are collected again
-hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
+hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                        const Tile* d_tiles, int L, int n_tiles, int ntk, Timing* tm, hipStream_t s) {
     {
         Section sec(tm, "topk_scan");
@@ -830,48 +860,54 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, const Dev
         Section sec(tm, "topk_recollect");
         CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
         p.only_flagged = 1;
-        hipLaunchKernelGGL((topk_collect_kernel<false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        p.ef_out = ef_out;
+        // a second collection reads x = g + e again: in compress e already holds x, so g is not added
+        if (ef_out) {
+            p.g = ef_out;
+            p.e = nullptr;
+            hipLaunchKernelGGL((topk_collect_kernel<false, true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        } else {
+            hipLaunchKernelGGL((topk_collect_kernel<false, false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        }
         TK_CHECK(hipGetLastError());
     }
     return hipSuccess;
 }
 
-hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int max_layer_tiles,
-                         int ntk, const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
+hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
+                         const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
+    if (t->n_work <= 0) return hipSuccess;
     RefineParams p{};
     p.tl = (TopkLayer*)t->d_tl;
     p.layers = d_layers;
     p.tiles = d_tiles;
     p.tinfo = (const TopkTileInfo*)t->d_tinfo;
     p.cand = t->d_cand;
+    p.work = (const RefWork*)t->d_work;
+    p.work_range = (const int2*)t->d_work_range;
     p.base_part = t->d_base_part;
     p.below_part = t->d_below_part;
-    // refinement histograms of the layers in use: [counts A][counts B][energies A][energies B]
-    const size_t na = (size_t)L * kMaxTopk * kBinsA, nb = (size_t)L * kMaxTopk * kBinsB;
-    p.hist_a = t->d_ref;
-    p.hist_b = p.hist_a + na;
-    p.en_a = reinterpret_cast<unsigned long long*>(p.hist_b + nb);
+    // per-workgroup partial histograms: [counts A][counts B][energies A][energies B]
+    const size_t na = (size_t)t->max_work * kMaxTopk * kBinsA, nb = (size_t)t->max_work * kMaxTopk * kBinsB;
+    p.cnt_a = t->d_ref;
+    p.cnt_b = p.cnt_a + na;
+    p.en_a = reinterpret_cast<unsigned long long*>(p.cnt_b + nb);
     p.en_b = p.en_a + na;
     p.errors = d_errors;
     p.stride = stride;
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
-    p.splits = std::max(1, std::min(kRefSplits, (max_layer_tiles + kRefTilesMin - 1) / kRefTilesMin));
     Section sec(tm, "topk_refine");
-    const size_t words = (na + nb) * 3;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((words + 255) / 256, 4096)), dim3(256), 0, s,
-                       t->d_ref, words, 0u);
-    TK_CHECK(hipGetLastError());
     const size_t lds_a = (size_t)kMaxTopk * kBinsA * 12, lds_b = (size_t)kMaxTopk * kBinsB * 12;
     TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                  (int)lds_a));
-    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(L * p.splits), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
+    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     TK_CHECK(hipGetLastError());
     TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                  (int)lds_b));
-    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(L * p.splits), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
+    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     return hipGetLastError();
@@ -881,19 +917,15 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
                          Timing* tm, hipStream_t s) {
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
-    int max_tiles = 0;
     for (int l = 0; l < L; ++l)
-        if (h_layers[l].family == LGRECO_TOPK) {
-            ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
-            max_tiles = std::max(max_tiles, h_layers[l].tile_end - h_layers[l].tile_begin);
-        }
+        if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
     TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, tm, s));
     {
         Section sec(tm, "topk_collect");
-        TK_CHECK(topk_collect(t, g, e, d_layers, d_tiles, n_tiles, s));
+        TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
     }
-    TK_CHECK(topk_select(t, g, e, d_layers, d_tiles, L, n_tiles, 1, tm, s));
-    TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, max_tiles, 1, nullptr, nullptr, 0, tm, s));
+    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, tm, s));
+    TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
         hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(kThreads), 0, s, d_layers, d_tiles,
@@ -908,10 +940,11 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         TK_CHECK(hipGetLastError());
     }
     {
-        Section sec(tm, "topk_write");
-        hipLaunchKernelGGL(topk_write_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
-                           (const TopkLayer*)t->d_tl, (const uint2*)t->d_tilecnt, (const uint2*)t->d_tilebase,
-                           payload);
+        Section sec(tm, "topk_emit");
+        hipLaunchKernelGGL(topk_emit_kernel, dim3(n_tiles), dim3(kThreads), 0, s, e, d_layers, d_tiles,
+                           (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
+                           (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
+                           (const uint2*)t->d_tilebase, payload);
         TK_CHECK(hipGetLastError());
     }
     return hipSuccess;

@@ -21,22 +21,53 @@ __device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x
 // the others is summed per lane.
 struct Collector {
     uint32_t* dst;
+    uint32_t* dst_idx;   // optional: index (within the layer) and sign of every candidate
     uint32_t lo;
     uint32_t cur;      // candidates written so far (uniform over the wavefront)
     float base;        // this lane's sum of x^2 over elements below lo
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t l) { dst = d; lo = l; cur = 0; base = 0.0f; }
-    __device__ __forceinline__ void take(float x, bool valid) {
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t l) {
+        dst = d; dst_idx = di; lo = l; cur = 0; base = 0.0f;
+    }
+    __device__ __forceinline__ static uint32_t below(unsigned long long m, uint32_t add) {
+        return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, add));
+    }
+    // one element per lane
+    __device__ __forceinline__ void take(float x, bool valid, uint32_t idx = 0) {
         const uint32_t pat = mag_bits(x);
         const bool hit = valid && (pat >> kHistShift) >= lo;
         const unsigned long long m = __ballot(hit);
         if (hit) {
-            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            dst[cur + below] = pat;
+            const uint32_t at = cur + below(m, 0u);
+            dst[at] = pat;
+            if (dst_idx) dst_idx[at] = idx | (__float_as_uint(x) & 0x80000000u);
         } else if (valid) {
             base = __builtin_fmaf(x, x, base);
         }
         cur += (uint32_t)__popcll(m);
+    }
+    // four consecutive elements per lane, lanes in element order: candidates come out in element order
+    __device__ __forceinline__ void take4(const float (&x)[4], uint32_t idx0) {
+        bool hit[4];
+        uint32_t pat[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            pat[q] = mag_bits(x[q]);
+            hit[q] = (pat[q] >> kHistShift) >= lo;
+        }
+        const unsigned long long m0 = __ballot(hit[0]), m1 = __ballot(hit[1]), m2 = __ballot(hit[2]),
+                                 m3 = __ballot(hit[3]);
+        uint32_t at = cur + below(m0, below(m1, below(m2, below(m3, 0u))));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (hit[q]) {
+                dst[at] = pat[q];
+                if (dst_idx) dst_idx[at] = (idx0 + q) | (__float_as_uint(x[q]) & 0x80000000u);
+                ++at;
+            } else {
+                base = __builtin_fmaf(x[q], x[q], base);
+            }
+        }
+        cur += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
     }
 };
 
