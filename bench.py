@@ -155,16 +155,15 @@ def main():
     ntk = float(numels[fam == W.TOPK].sum())
     mean_bits = float((numels * par)[fam == W.QUANT].sum() / nq) if nq else 0.0
     mean_dens = float((numels * par)[fam == W.TOPK].sum() / ntk) if ntk else 0.0
-    # algorithmic bytes per element and elements covered per launch, per timed section
+    # algorithmic bytes per element and elements covered per launch, per timed section:
+    # streaming reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g and e and writes e
+    rd = 8.0 if has_ef else 4.0
     algo, elems = {}, {}
-    for k in ("quant_profile", "quant_profile_hist", "topk_hist", "topk_pass_b"):
-        algo["profile/" + k], elems["profile/" + k] = 8.0, float(N)
-    for k in ("topk_hist", "topk_pass_b"):
-        algo["compress/" + k], elems["compress/" + k] = 8.0, ntk
+    for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
+        algo["profile/" + k], elems["profile/" + k] = rd, float(N)
     algo["compress/quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
     elems["compress/quant_compress"] = nq
-    algo["compress/topk_write"] = 12.0 + 8.0 * mean_dens
-    elems["compress/topk_write"] = ntk
+    algo["compress/topk_collect"], elems["compress/topk_collect"] = 12.0, ntk
     nlr = float(numels[fam == W.LOWRANK].sum())
     algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = 12.0, nlr
     # dense contractions of the low-rank path: flops per launch (64 columns are computed per layer)

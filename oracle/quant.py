@@ -9,9 +9,8 @@ integer codes are reproducible in IEEE fp32):
   bucket = 128 consecutive elements of one layer (the last bucket of a layer may be short)
   m, M   = min, max of the bucket;  r = fl32(M - m)
   lv     = 2^b - 1;  unit = fl32(r / lv);  inv = fl32(lv / r);  inv := 0 if lv / r is not finite
-  t      = fl32(fl32(x - m) * inv)
-  q      = floor(fl32(t + 0.5))            deterministic
-         = floor(fl32(t + u))              stochastic, u in [0,1) from Philox(seed, layer, i)
+  q      = floor(fma32(fl32(x - m), inv, 0.5))     deterministic (one rounding inside the floor)
+         = floor(fma32(fl32(x - m), inv, u))       stochastic, u in [0,1) from Philox(seed, layer, i)
   q      = min(max(q, 0), lv)
   xhat   = fma32(q, unit, m)               one rounding
   error  = sum (double(xhat) - double(x))^2
@@ -35,7 +34,7 @@ def form_x(g: np.ndarray, e) -> np.ndarray:
 
 def fma32(a: np.ndarray, b: np.ndarray, c: np.ndarray) -> np.ndarray:
     """round_to_fp32(a*b + c) with a single rounding, for a*b exactly representable in fp64
-    (true here: a < 2^8 is an integer, b has 24 significant bits)."""
+    (true here: two fp32 factors have at most 48 significant bits in their product)."""
     p = a.astype(np.float64) * b.astype(np.float64)         # exact
     c = c.astype(np.float64)
     s = p + c                                               # rounded to fp64
@@ -85,11 +84,11 @@ def quantize(x: np.ndarray, bits: int, bucket: int = 128, u=None):
             inv = F32(lv / r)
         if not np.isfinite(inv):
             inv = F32(0.0)
-        t = (xb - m) * inv
+        xm = xb - m
         if u is None:
-            q = np.floor(t + F32(0.5))
+            q = np.floor(fma32(xm, np.full(xm.shape, inv, F32), np.full(xm.shape, 0.5, F32)))
         else:
-            q = np.floor(t + u[starts[j]:ends[j]])
+            q = np.floor(fma32(xm, np.full(xm.shape, inv, F32), u[starts[j]:ends[j]]))
         q = np.minimum(np.maximum(q, F32(0.0)), lv)
         codes[starts[j]:ends[j]] = q.astype(np.uint8)
         xhat[starts[j]:ends[j]] = fma32(q, np.full(q.shape, unit, F32), np.full(q.shape, m, F32))
@@ -118,11 +117,11 @@ def quantize_fast(x: np.ndarray, bits: int, bucket: int = 128, u=None):
             unit = (r / lv).astype(F32)
             inv = (lv / r).astype(F32)
         inv = np.where(np.isfinite(inv), inv, F32(0.0)).astype(F32)
-        t = (xb - m) * inv
+        xm = xb - m
         if u is None:
-            q = np.floor(t + F32(0.5))
+            q = np.floor(fma32(xm, np.broadcast_to(inv, xm.shape), np.full(xm.shape, 0.5, F32)))
         else:
-            q = np.floor(t + u[:nfull * bucket].reshape(nfull, bucket))
+            q = np.floor(fma32(xm, np.broadcast_to(inv, xm.shape), u[:nfull * bucket].reshape(nfull, bucket)))
         q = np.minimum(np.maximum(q, F32(0.0)), lv)
         codes[:nfull * bucket] = q.astype(np.uint8).reshape(-1)
         xhat[:nfull * bucket] = fma32(q, np.broadcast_to(unit, q.shape),

@@ -168,12 +168,15 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
     return LGRECO_OK;
 }
 
-int upload_layers(lgreco_handle* h, hipStream_t s, bool force) {
-    if (!h->layers_dirty && !force) return LGRECO_OK;
-    HIPCHK(hipMemcpyAsync(h->d_layers, h->hl.data(), sizeof(DevLayer) * h->hl.size(), hipMemcpyHostToDevice, s));
-    HIPCHK(hipMemcpyAsync(h->d_tiles, h->ht.data(), sizeof(Tile) * h->ht.size(), hipMemcpyHostToDevice, s));
-    // the host vectors may be rewritten by the next call: make the copy complete first
-    HIPCHK(hipStreamSynchronize(s));
+// The tile table travels only when it was rebuilt; the layer records also when the caller changed
+// their per-call fields (family, parameter, payload offset).  Every entry point ends with a stream
+// synchronisation before it returns, so the host vectors outlive the copies.
+int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
+    if (h->layers_dirty || layers_changed)
+        HIPCHK(hipMemcpyAsync(h->d_layers, h->hl.data(), sizeof(DevLayer) * h->hl.size(), hipMemcpyHostToDevice,
+                              s));
+    if (h->layers_dirty)
+        HIPCHK(hipMemcpyAsync(h->d_tiles, h->ht.data(), sizeof(Tile) * h->ht.size(), hipMemcpyHostToDevice, s));
     h->layers_dirty = false;
     return LGRECO_OK;
 }

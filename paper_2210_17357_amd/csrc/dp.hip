@@ -174,9 +174,14 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
     hipError_t err = hipSuccess;
 #define LGRECO_DP2(K, PD)                                                                          \
     do {                                                                                           \
-        err = hipFuncSetAttribute((const void*)dp_kernel<T, K, PD, THREADS>,                       \
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
-        if (err != hipSuccess) return err;                                                         \
+        static bool configured = false;   /* the limit is raised once per instantiation */        \
+        if (!configured) {                                                                         \
+            err = hipFuncSetAttribute((const void*)dp_kernel<T, K, PD, THREADS>,                   \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,                  \
+                                      (int)kDpLdsBudget);                                          \
+            if (err != hipSuccess) return err;                                                     \
+            configured = true;                                                                     \
+        }                                                                                          \
         hipLaunchKernelGGL((dp_kernel<T, K, PD, THREADS>), dim3(1), dim3(THREADS), lds, s, p);     \
     } while (0)
 #define LGRECO_DP(K) do { if (padded) LGRECO_DP2(K, true); else LGRECO_DP2(K, false); } while (0)
@@ -192,12 +197,6 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
 }
 
 hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s) {
-    static const int threads = [] {
-        const char* e = getenv("LGRECO_DP_THREADS");
-        return e ? atoi(e) : 1024;
-    }();
-    if (threads == 512)
-        return narrow ? launch_dp_t<uint32_t, 512>(p, max_bin, s) : launch_dp_t<int64_t, 512>(p, max_bin, s);
     return narrow ? launch_dp_t<uint32_t, 1024>(p, max_bin, s) : launch_dp_t<int64_t, 1024>(p, max_bin, s);
 }
 

@@ -5,7 +5,7 @@
 // floating-point contraction; fused multiply-adds are written explicitly):
 //   x = g + e;  m = min, M = max;  r = M - m;  lv = 2^b - 1
 //   unit = r / lv;  inv = lv / r, replaced by 0 when not finite
-//   t = (x - m) * inv;  q = floor(t + 0.5) or floor(t + u);  q = min(max(q, 0), lv)
+//   q = floor(fma(x - m, inv, 0.5)) or floor(fma(x - m, inv, u));  q = min(max(q, 0), lv)
 //     (the clamp is a no-op except for the upper bound under stochastic rounding)
 //   xhat = fma(q, unit, m);  error += (xhat - x)^2
 //
@@ -29,11 +29,10 @@ __device__ __forceinline__ float safe_inv(float lv, float r) {
 template <bool STOCH>
 __device__ __forceinline__ float quant_one(float x, float xm, float m, float inv, float unit, float lv,
                                            float u, float* qout) {
-    const float t = xm * inv;
-    float q = __builtin_floorf(t + (STOCH ? u : 0.5f));
-    // t >= 0 always (x >= m, inv >= 0), so the lower clamp never acts.  The upper clamp can act
-    // only with stochastic rounding: t <= lv * (1 + 2^-23) and floor(t + 0.5) <= lv, whereas
-    // t + u may round up to lv + 1.
+    float q = __builtin_floorf(__builtin_fmaf(xm, inv, STOCH ? u : 0.5f));
+    // (x - m) * inv >= 0 always, so the lower clamp never acts.  The upper clamp can act only with
+    // stochastic rounding: (x - m) * inv <= lv * (1 + 2^-23), so floor(. + 0.5) <= lv, whereas
+    // adding u < 1 may round up to lv + 1.
     if (STOCH) q = fminf(q, lv);
     *qout = q;
     return __builtin_fmaf(q, unit, m);

@@ -899,14 +899,18 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
     Section sec(tm, "topk_refine");
     const size_t lds_a = (size_t)kMaxTopk * kBinsA * 12, lds_b = (size_t)kMaxTopk * kBinsB * 12;
-    TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)lds_a));
+    static bool configured = false;   // the dynamic LDS limits are raised once
+    if (!configured) {
+        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_a));
+        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_b));
+        configured = true;
+    }
     hipLaunchKernelGGL(topk_refine_a_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     TK_CHECK(hipGetLastError());
-    TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)lds_b));
     hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
