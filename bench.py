@@ -29,6 +29,16 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
+# HBM bytes per launch (read + write) of the dominant kernels, from the rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs summarised under profiles/<workload>_kernels_hbm.md (FETCH_SIZE x 2.0 and
+# WRITE_SIZE x 1.0, both calibrated on a copy of known size).  Counters cannot be read from inside
+# this process, so the figures are carried here and apply to the default synthetic input only.
+MEASURED_TRAFFIC_BYTES = {
+    "c4_gpt2_medium_mixed": {"compress/topk_collect": 2185.4e6 + 1145.8e6,
+                             "profile/quant_profile_topk_collect": 2840.0e6 + 265.3e6,
+                             "compress/quant_compress": 655.5e6 + 390.0e6},
+    "c3_transformer_lm_lowrank": {"compress/lowrank_ef": 605.8e6 + 268.4e6},
+}
 
 
 def parse_args():
@@ -197,7 +207,9 @@ def main():
         else:
             ach = timed[dom]["GBps"]
             roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                        "frac": round(ach / HBM_PEAK_GBS, 4),
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
+                        "algorithmic_bytes": round(algo[dom] * elems[dom]),
                         "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
     out = {
         "metric": "profile+solve+compress gradient GB/s at 1 MI355X",
