@@ -86,3 +86,63 @@ def test_forced_mix_of_families_in_compress():
         assert np.array_equal(pay[offsets[l]:offsets[l] + p_ref.size], p_ref), (l, cands[choice[l]])
         assert np.array_equal(new_ef[off:off + n].view(np.uint32), e_ref.view(np.uint32)), l
     h.close()
+
+
+def test_full_size_gpt2_medium_sampled_layers():
+    """The 355 M-element workload in the launch configuration the benchmark times (one handle, one
+    profile call over all 292 layers and 13 candidates, solve with 4000 bins, one compress call).
+    The oracle computes a sample of layers one by one (1-D tensors, the positional table, one of
+    each 2-D block shape); everything else is checked through properties that hold at any size:
+    the size table, the assignment against the oracle's solver on the same tables, and the squared
+    norm of the new error feedback of EVERY layer against the profiled error of its chosen
+    candidate."""
+    import os
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = W.workload("c4_gpt2_medium_mixed")
+    cands = list(w.candidates)
+    batch = W.generate(w, threads=min(16, os.cpu_count() or 1))
+    L = len(batch.numels)
+    assert L == 292 and int(batch.numels.sum()) == 354823168
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    h = B.Handle(int(batch.grads.size), L, len(cands))
+    errors, sizes = h.profile(g, e, layers, ctab)
+    assert np.array_equal(sizes, pipeline.sizes_table(batch.numels, batch.rows, batch.cols, cands))
+    # errors decrease with bits and with density in every layer
+    nq = sum(1 for f, _ in cands if f == W.QUANT)
+    assert (np.diff(errors[:, :nq], axis=1) <= 0).all() and (np.diff(errors[:, nq:], axis=1) <= 0).all()
+    sample = [1, 2, 3, 4, 5, 6, 7, 10, 11, 12, 13, 14 + 10, 14 + 11, L - 2, L - 1]
+    shapes = {w.shapes[int(batch.tensor_index[l])] for l in sample}
+    assert {(1024, 1024), (1024, 3072), (1024, 4096), (4096, 1024), (1024,), (3072,), (4096,)} <= shapes
+    for l in sample:
+        off, n = int(batch.offsets[l]), int(batch.numels[l])
+        ref = pipeline.profile(batch.grads[off:off + n], batch.ef[off:off + n], np.array([0]), np.array([n]),
+                               batch.rows[l:l + 1], batch.cols[l:l + 1], cands)
+        assert rel_err(errors[l], ref[0]).max() < 1e-4, l
+
+    e_max = B.emax(errors, w.default)
+    st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins)
+    assert st == B.OK
+    ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, w.n_bins)
+    assert np.array_equal(choice, ref_choice) and tsize == ref_size
+    assert tsize <= int(sizes[:, w.default].sum())
+    assert terr <= e_max * (1.0 + L / w.n_bins)
+
+    offsets = B.payload_layout(layers, ctab, choice)
+    payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
+    ef_dev = e.clone()
+    h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)
+    # every layer: what compress leaves in the error feedback is the error that was profiled
+    sq = ef_dev.double().pow(2)
+    left = np.array([float(sq[int(o):int(o) + int(n)].sum()) for o, n in zip(batch.offsets, batch.numels)])
+    del sq
+    chosen = errors[np.arange(L), choice]
+    assert (np.abs(left - chosen) <= 1e-4 * chosen + 1e-60).all()
+    pay = payload.cpu().numpy()
+    for l in sample:
+        off, n = int(batch.offsets[l]), int(batch.numels[l])
+        p_ref, e_ref, _ = pipeline.compress_layer(batch.grads, batch.ef, off, n, 0, 0, cands[choice[l]], l)
+        assert np.array_equal(pay[offsets[l]:offsets[l] + p_ref.size], p_ref), (l, cands[choice[l]])
+        assert np.array_equal(ef_dev[off:off + n].cpu().numpy().view(np.uint32), e_ref.view(np.uint32)), l
+    h.close()
