@@ -48,6 +48,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
+    ap.add_argument("--detail", action="store_true",
+                    help="bracket every kernel section, not only the main kernels (costs ~3 %% of the step)")
     ap.add_argument("--cpu-sample-elems", type=int, default=14_000_000)
     return ap.parse_args()
 
@@ -113,7 +117,7 @@ def main():
     q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
     h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
                  seed=w.seed, r_max=w.r_max)
-    h.set_timing(True)
+    h.set_timing(0 if args.no_kernel_timing else (2 if args.detail else 1))
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
 
@@ -125,15 +129,15 @@ def main():
         ef = ef_pool[i]
         t0 = time.perf_counter()
         errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True)
-        tm_p = h.get_timing() if record else []
+        tm_p = h.get_timing() if record and not args.no_kernel_timing else []
         t1 = time.perf_counter()
         e_max = B.emax(errors, w.default)
         st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins)
-        tm_s = h.get_timing() if record else []
+        tm_s = h.get_timing() if record and not args.no_kernel_timing else []
         t2 = time.perf_counter()
         offsets = B.payload_layout(layers, ctab, choice, w.bucket)
         h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i])
-        tm_c = h.get_timing() if record else []
+        tm_c = h.get_timing() if record and not args.no_kernel_timing else []
         t3 = time.perf_counter()
         if record:
             phase["profile"] += t1 - t0

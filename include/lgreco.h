@@ -156,10 +156,12 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                     void* stream);
 
 /* Timing of the kernels launched by the last profile / solve / compress call on this handle.
- * lgreco_set_timing(h, 1) makes every call bracket its kernels with HIP events on the call's
- * stream; lgreco_get_timing returns the number of sections recorded by the last call and
+ * lgreco_set_timing(h, level) makes every call bracket kernels with HIP events on the call's
+ * stream: level 1 the main kernels only (the streaming passes, the contractions, the DP), level 2
+ * every section, 0 none (each bracket costs a few microseconds of the stream's time);
+ * lgreco_get_timing returns the number of sections recorded by the last call and
  * fills names (static strings) and milliseconds for up to `cap` of them. */
-int lgreco_set_timing(lgreco_handle_t* h, int32_t enabled);
+int lgreco_set_timing(lgreco_handle_t* h, int32_t level);
 int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap);
 
 const char* lgreco_strerror(int status);

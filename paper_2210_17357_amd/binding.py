@@ -200,8 +200,9 @@ class Handle:
                                    _dptr(d_payload), _np(offsets), _stream())
         self._check(st)
 
-    def set_timing(self, enabled: bool):
-        self._check(lib().lgreco_set_timing(self._h, int(enabled)))
+    def set_timing(self, level):
+        """0 / False: off; 1 / True: main kernels; 2: every section."""
+        self._check(lib().lgreco_set_timing(self._h, int(level)))
 
     def get_timing(self):
         cap = 32

@@ -285,9 +285,9 @@ int lgreco_destroy(lgreco_handle_t* h) {
     return LGRECO_OK;
 }
 
-int lgreco_set_timing(lgreco_handle_t* h, int32_t enabled) {
-    if (!h) return LGRECO_EINVAL;
-    h->tm.enabled = enabled != 0;
+int lgreco_set_timing(lgreco_handle_t* h, int32_t level) {
+    if (!h || level < 0 || level > 2) return LGRECO_EINVAL;
+    h->tm.level = level;
     h->tm.n = 0;
     return LGRECO_OK;
 }
@@ -413,10 +413,10 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
             qp.tinfo = h->topk.d_tinfo;
             qp.base_part = h->topk.d_base_part;
         }
-        Section sec(&h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile");
+        Section sec(&h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile", true);
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
     } else if (ntk) {
-        Section sec(&h->tm, "topk_collect");
+        Section sec(&h->tm, "topk_collect", true);
         HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
     }
     if (ntk)
@@ -513,13 +513,13 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         HIPCHK(hipMemcpyAsync(h->d_count, h->h_count, sizeof(int32_t) * n_sweep, hipMemcpyHostToDevice, s));
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0};
         {
-            Section sec(&h->tm, "dp_solve");
+            Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
         }
         HIPCHK(hipMemcpyAsync(h->h_choice, h->d_choice, sizeof(int32_t) * n_sweep, hipMemcpyDeviceToHost, s));
         HIPCHK(hipMemcpyAsync(h->h_result, h->d_result, sizeof(int64_t) * 8, hipMemcpyDeviceToHost, s));
         HIPCHK(hipStreamSynchronize(s));
-        if (h->tm.enabled) {                        // 100 MHz constant-rate device counter
+        if (h->tm.level >= 1) {                       // 100 MHz constant-rate device counter
             h->sub_name[0] = "dp_solve.sweep";
             h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
             h->sub_name[1] = "dp_solve.backtrace";
@@ -588,7 +588,7 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     if (st != LGRECO_OK) return st;
     const int n_tiles = (int)h->ht.size();
     if (any[LGRECO_QUANT]) {
-        Section sec(&h->tm, "quant_compress");
+        Section sec(&h->tm, "quant_compress", true);
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
                                      h->cfg.stochastic != 0, h->cfg.seed, s));
     }

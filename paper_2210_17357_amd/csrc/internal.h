@@ -12,7 +12,7 @@ namespace lgreco {
 // two HIP events on the call's stream.
 struct Timing {
     static constexpr int kMaxSections = 32;
-    bool enabled = false;
+    int level = 0;          // 0 off, 1 main kernels, 2 every section
     bool ready = false;
     hipStream_t stream = nullptr;
     hipEvent_t ev[2 * kMaxSections]{};
@@ -22,8 +22,8 @@ struct Timing {
 struct Section {
     Timing* t;
     int idx = -1;
-    Section(Timing* tt, const char* name) : t(tt) {
-        if (t && t->enabled && t->ready && t->n < Timing::kMaxSections) {
+    Section(Timing* tt, const char* name, bool main_kernel = false) : t(tt) {
+        if (t && t->level >= (main_kernel ? 1 : 2) && t->ready && t->n < Timing::kMaxSections) {
             idx = t->n++;
             t->name[idx] = name;
             (void)hipEventRecord(t->ev[2 * idx], t->stream);

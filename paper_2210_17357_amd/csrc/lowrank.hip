@@ -777,7 +777,7 @@ static void lr_fill_params(LrHost* H, LrParams* p) {
 
 static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStream_t s) {
     {
-        Section sec(tm, "lowrank_gemm_p");
+        Section sec(tm, "lowrank_gemm_p", true);
         hipLaunchKernelGGL(lr_gemm1_kernel, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
         if (H->ppart_elems > 0) {
@@ -795,7 +795,7 @@ static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStre
         LR_CHECK(hipGetLastError());
     }
     {
-        Section sec(tm, "lowrank_gemm_q");
+        Section sec(tm, "lowrank_gemm_q", true);
         hipLaunchKernelGGL(lr_gemm2_kernel, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
     }
@@ -853,7 +853,7 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     p.r_max = r_max;
     p.payload = payload;
     LR_CHECK(lr_factorize(H, p, tm, s));
-    Section sec(tm, "lowrank_ef");
+    Section sec(tm, "lowrank_ef", true);
     hipLaunchKernelGGL(lr_ef_kernel, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }

@@ -48,37 +48,44 @@ struct TopkLayer {
 constexpr int kRefTiles = 8;        // tiles per refinement workgroup
 constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
+constexpr int kPickThreads = 1024;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 
 // ------------------------------------------------------------------------ block helpers
 // Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
-// hist lives in LDS, nbins <= 16 * 256.  All 256 threads call; result broadcast through res[2];
-// scan[0] is left holding the total.  If fewer than `need` entries exist, res = {0, total - hist[0]}.
+// hist lives in LDS, nbins <= 16 * 256.  Every thread of the block calls (the first 256 work, the
+// rest only join the barriers); result broadcast through res[2]; scan[0] is left holding the
+// total.  If fewer than `need` entries exist, res = {0, total - hist[0]}.
 __device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scan,
                                    uint32_t* res) {
     const int tid = threadIdx.x;
+    const bool act = tid < 256;
     const int per = (nbins + 255) / 256;
-    const int lo = tid * per, hi = min(lo + per, nbins);
+    const int lo = min(tid * per, nbins), hi = min(lo + per, nbins);
     uint32_t s = 0;
-    for (int b = lo; b < hi; ++b) s += hist[b];
-    scan[tid] = s;
+    if (act) {
+        for (int b = lo; b < hi; ++b) s += hist[b];
+        scan[tid] = s;
+    }
     __syncthreads();
     for (int o = 1; o < 256; o <<= 1) {       // inclusive suffix scan over threads
-        const uint32_t v = (tid + o < 256) ? scan[tid + o] : 0;
+        const uint32_t v = (act && tid + o < 256) ? scan[tid + o] : 0;
         __syncthreads();
-        scan[tid] += v;
+        if (act) scan[tid] += v;
         __syncthreads();
     }
     if (tid == 0) { res[0] = 0; res[1] = scan[0] - hist[0]; }
     __syncthreads();
-    uint32_t running = (tid + 1 < 256) ? scan[tid + 1] : 0;
-    for (int b = hi - 1; b >= lo; --b) {
-        const uint32_t c = hist[b];
-        if (running < need && running + c >= need) {
-            res[0] = (uint32_t)b;
-            res[1] = running;
+    if (act) {
+        uint32_t running = (tid + 1 < 256) ? scan[tid + 1] : 0;
+        for (int b = hi - 1; b >= lo; --b) {
+            const uint32_t c = hist[b];
+            if (running < need && running + c >= need) {
+                res[0] = (uint32_t)b;
+                res[1] = running;
+            }
+            running += c;
         }
-        running += c;
     }
     __syncthreads();
 }
@@ -115,33 +122,73 @@ __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
         p[i] = v;
 }
 
+struct RefWork {                     // one workgroup of the sample / refinement kernels: tiles [t0, t1) of a layer
+    int32_t layer, t0, t1, pad;
+};
+
 // Coarse histogram of a sample: every kSampleEvery-th 512-element chunk of every tile (chunk 0
-// included, so short tiles are sampled whole or by their first chunk).
+// included, so short tiles are sampled whole or by their first chunk).  One workgroup takes a run
+// of tiles of one layer; a wavefront takes whole sampled chunks.
 __global__ __launch_bounds__(kThreads) void topk_sample_kernel(const float* __restrict__ g,
                                                                 const float* __restrict__ e,
                                                                 const DevLayer* __restrict__ layers,
                                                                 const Tile* __restrict__ tiles,
-                                                                const uint32_t* __restrict__ ks,
+                                                                const RefWork* __restrict__ work,
                                                                 uint32_t* __restrict__ shist) {
     __shared__ uint32_t s_hist[kHistBins];
-    const Tile t = tiles[blockIdx.x];
-    if (ks[(size_t)t.layer * kMaxTopk] == 0) return;
-    const DevLayer L = layers[t.layer];
-    const float* gp = g + L.offset + t.pos;
-    const float* ep = e ? e + L.offset + t.pos : nullptr;
+    const RefWork w = work[blockIdx.x];
+    const DevLayer L = layers[w.layer];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
     __syncthreads();
-    const int nchunks = (t.count + kChunk - 1) / kChunk;
-    for (int c = 0; c < nchunks; c += kSampleEvery) {
-        const int n = min(kChunk, t.count - c * kChunk);
-        for (int i = threadIdx.x; i < n; i += kThreads) {
-            const int idx = c * kChunk + i;
-            const float x = ep ? gp[idx] + ep[idx] : gp[idx];
-            atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
+    constexpr int kPerTile = kTile / kChunk / kSampleEvery;      // sampled chunks of a full tile
+    constexpr int kWaves = kThreads / 64, kBatch = 4;            // chunks a wavefront has in flight
+    const int npairs = (w.t1 - w.t0) * kPerTile;
+    for (int pr0 = wave * kBatch; pr0 < npairs; pr0 += kWaves * kBatch) {
+        float4 a[kBatch][2];
+        bool vec[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int pr = pr0 + q;
+            vec[q] = false;
+            if (pr >= npairs) continue;
+            const Tile t = tiles[w.t0 + pr / kPerTile];
+            const int first = (pr % kPerTile) * kSampleEvery * kChunk;
+            if (first >= t.count) continue;
+            const float* gp = g + L.offset + t.pos + first;
+            const float* ep = e ? e + L.offset + t.pos + first : nullptr;
+            if (t.fast) {
+                vec[q] = true;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    a[q][h] = reinterpret_cast<const float4*>(gp)[h * 64 + lane];
+                    if (ep) {
+                        const float4 b = reinterpret_cast<const float4*>(ep)[h * 64 + lane];
+                        a[q][h].x += b.x; a[q][h].y += b.y; a[q][h].z += b.z; a[q][h].w += b.w;
+                    }
+                }
+            } else {
+                const int n = min(kChunk, t.count - first);
+                for (int i = lane; i < n; i += 64) {
+                    const float x = ep ? gp[i] + ep[i] : gp[i];
+                    atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (!vec[q]) continue;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                atomicAdd(&s_hist[mag_bits(a[q][h].x) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a[q][h].y) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a[q][h].z) >> kHistShift], 1u);
+                atomicAdd(&s_hist[mag_bits(a[q][h].w) >> kHistShift], 1u);
+            }
         }
     }
     __syncthreads();
-    uint32_t* gh = shist + (size_t)t.layer * kHistBins;
+    uint32_t* gh = shist + (size_t)w.layer * kHistBins;
     for (int b = threadIdx.x; b < kHistBins; b += kThreads) {
         const uint32_t c = s_hist[b];
         if (c) atomicAdd(&gh[b], c);
@@ -227,21 +274,31 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
         wave_range(t.count / kChunk, wave, &c0, &c1);
         start = (uint32_t)c0 * kChunk;
         col.init(slice + start, EMIT ? slice_idx + start : nullptr, p.lo[t.layer]);
-        for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += 64) {     // uniform trip count
-            float4 a = reinterpret_cast<const float4*>(gp)[v];
+        // one 512-element chunk per iteration (uniform trip count): both halves are loaded before
+        // either is used, so a lane keeps four 128-bit loads in flight
+        for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += kChunk / 4) {
+            float4 a[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) a[h] = reinterpret_cast<const float4*>(gp)[v + 64 * h];
             if (ep) {
-                const float4 b = reinterpret_cast<const float4*>(ep)[v];
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const float4 b = reinterpret_cast<const float4*>(ep)[v + 64 * h];
+                    a[h].x += b.x; a[h].y += b.y; a[h].z += b.z; a[h].w += b.w;
+                }
             }
-            if (EMIT) reinterpret_cast<float4*>(eo)[v] = a;
-            if (HIST) {
-                atomicAdd(&s_hist[mag_bits(a.x) >> kHistShift], 1u);
-                atomicAdd(&s_hist[mag_bits(a.y) >> kHistShift], 1u);
-                atomicAdd(&s_hist[mag_bits(a.z) >> kHistShift], 1u);
-                atomicAdd(&s_hist[mag_bits(a.w) >> kHistShift], 1u);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (EMIT) reinterpret_cast<float4*>(eo)[v + 64 * h] = a[h];
+                if (HIST) {
+                    atomicAdd(&s_hist[mag_bits(a[h].x) >> kHistShift], 1u);
+                    atomicAdd(&s_hist[mag_bits(a[h].y) >> kHistShift], 1u);
+                    atomicAdd(&s_hist[mag_bits(a[h].z) >> kHistShift], 1u);
+                    atomicAdd(&s_hist[mag_bits(a[h].w) >> kHistShift], 1u);
+                }
+                const float x[4] = {a[h].x, a[h].y, a[h].z, a[h].w};
+                col.take4(x, (uint32_t)(t.pos + 4 * (int64_t)(v + 64 * h)));
             }
-            const float x[4] = {a.x, a.y, a.z, a.w};
-            col.take4(x, (uint32_t)(t.pos + 4 * (int64_t)v));
         }
     } else {
         int b0, b1;
@@ -331,9 +388,6 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
     }
 }
 
-struct RefWork {                     // one refinement workgroup: tiles [t0, t1) of a layer
-    int32_t layer, t0, t1, pad;
-};
 struct RefineParams {
     TopkLayer* tl;
     const DevLayer* layers;
@@ -382,10 +436,10 @@ __device__ __forceinline__ void for_each_candidate(const RefineParams& p, const 
 }
 
 // Refinement level A: energy of the candidates below every threshold bin, and histogram
-// (count, energy) of bits 18..9 of the candidates inside each threshold bin.
+// (count, energy) of bits 18..9 of the candidates inside each threshold bin.  Squares are summed
+// in fp32 per lane (a lane sees some tens of candidates), in fp64 from the wavefront up.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
-    __shared__ uint32_t s_bin[kMaxTopk], s_tbin[kMaxTopk];
     __shared__ double s_red[kRefThreads / 64][kMaxTopk];
     const RefWork w = p.work[blockIdx.x];
     const int l = w.layer;
@@ -395,38 +449,37 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
     uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
     const int tid = threadIdx.x, ntk = p.ntk;
     for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
-    if (tid < kMaxTopk) {
-        s_bin[tid] = tid < (int)nlists ? T.lists[tid].bin : 0xFFFFFFFFu;
-        s_tbin[tid] = (tid < ntk && T.sel[tid].k) ? T.sel[tid].tbin : 0u;
+    // workgroup-uniform: threshold bin of every k (0 = inactive: nothing is below it) and the
+    // distinct threshold bins ("lists")
+    uint32_t tb[kMaxTopk], lb[kMaxTopk];
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j) {
+        tb[j] = (j < ntk && T.sel[j].k) ? T.sel[j].tbin : 0u;
+        lb[j] = j < (int)nlists ? T.lists[j].bin : 0xFFFFFFFFu;
     }
     __syncthreads();
-    double below[kMaxTopk];
+    float below[kMaxTopk];
 #pragma unroll
-    for (int j = 0; j < kMaxTopk; ++j) below[j] = 0.0;
-    double low = 0.0;                 // candidates under the lowest threshold bin: "below" for every k
-    const uint32_t min_tbin = T.min_tbin;
+    for (int j = 0; j < kMaxTopk; ++j) below[j] = 0.0f;
     for_each_candidate(p, T, w.t0, w.t1, [&](uint32_t pat) {
         const uint32_t key = pat >> kHistShift;
         const float xf = __uint_as_float(pat);
-        const double x2 = (double)xf * (double)xf;
-        if (key < min_tbin) {
-            low += x2;
-            return;
-        }
+        uint32_t hit = 0;               // 1 + index of the list this candidate belongs to
 #pragma unroll
-        for (int j = 0; j < kMaxTopk; ++j)
-            if (j < ntk && key < s_tbin[j]) below[j] += x2;
-        for (uint32_t u = 0; u < nlists; ++u)
-            if (key == s_bin[u]) {
-                const uint32_t b = u * kBinsA + ((pat >> 9) & (kBinsA - 1));
-                atomicAdd(&s_cnt[b], 1u);
-                atomicAdd(&s_en[b], int_energy(pat));
-            }
+        for (int j = 0; j < kMaxTopk; ++j) {
+            below[j] = __builtin_fmaf(key < tb[j] ? xf : 0.0f, xf, below[j]);
+            hit = key == lb[j] ? (uint32_t)(j + 1) : hit;
+        }
+        if (hit) {
+            const uint32_t b = (hit - 1) * kBinsA + ((pat >> 9) & (kBinsA - 1));
+            atomicAdd(&s_cnt[b], 1u);
+            atomicAdd(&s_en[b], int_energy(pat));
+        }
     });
 #pragma unroll
     for (int j = 0; j < kMaxTopk; ++j) {
         if (j < ntk) {
-            const double s = wave_sum(below[j] + low);
+            const double s = wave_sum((double)below[j]);
             if ((tid & 63) == 0) s_red[tid >> 6][j] = s;
         }
     }
@@ -445,26 +498,35 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
 }
 
 // One workgroup per (layer, requested k): sub-bin of level A holding the k-th magnitude.
-__global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
+// With p.errors (profile) the dropped energy is written here and level B is not run: inside the
+// sub-bin (magnitudes within 2^-14 of each other) the energies of the dropped entries are taken
+// as evenly spread between the sub-bin's lower edge and its mean, which bounds the relative
+// deviation of the layer's error by 3e-5 in the worst case (a layer whose dropped energy sits
+// entirely in that sub-bin) and is exact when the sub-bin's entries are equal.
+__global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsA];
     __shared__ unsigned long long s_en[kBinsA];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
+    __shared__ double s_base[256];
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
     const TopkSel S = T.sel[j];
     const int2 wr = p.work_range[l];
-    const int tid = threadIdx.x;
-    // sum the layer's workgroup partials of this k's list, in workgroup order
+    const int tid = threadIdx.x, t = tid & 255, grp = tid >> 8;
+    for (int b = tid; b < kBinsA; b += kPickThreads) { s_hist[b] = 0; s_en[b] = 0; }
+    if (tid == 0) s_e = 0;
+    __syncthreads();
+    // sum the layer's workgroup partials of this k's list: 4 bins per thread, the workgroups dealt
+    // round-robin to the 4 thread groups, integer LDS atomics join them (order does not matter)
     {
-        // 4 bins per thread, workgroups outermost and unrolled: many independent loads in flight
         uint32_t c[4] = {0, 0, 0, 0};
         unsigned long long e[4] = {0, 0, 0, 0};
-        const size_t off = (size_t)S.list * kBinsA + tid;
+        const size_t off = (size_t)S.list * kBinsA + t;
 #pragma unroll 4
-        for (int wg = wr.x; wg < wr.y; ++wg) {
+        for (int wg = wr.x + grp; wg < wr.y; wg += kPickThreads / 256) {
             const size_t i = (size_t)wg * kMaxTopk * kBinsA + off;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -474,25 +536,51 @@ __global__ __launch_bounds__(256) void topk_pick_a_kernel(RefineParams p) {
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            s_hist[tid + 256 * q] = c[q];
-            s_en[tid + 256 * q] = e[q];
+            if (c[q]) atomicAdd(&s_hist[t + 256 * q], c[q]);
+            if (e[q]) atomicAdd(&s_en[t + 256 * q], e[q]);
         }
     }
-    if (tid == 0) s_e = 0;
     __syncthreads();
     block_kth_from_top(s_hist, kBinsA, S.need, s_scan, s_res);
     const uint32_t bin_a = s_res[0];
     unsigned long long e = 0;
-    for (uint32_t b = tid; b < bin_a; b += 256) e += s_en[b];
-    atomicAdd(&s_e, e);
+    for (uint32_t b = tid; b < bin_a; b += kPickThreads) e += s_en[b];
+    if (e) atomicAdd(&s_e, e);
+    // energy below the collection bound: the layer's tile partials in a fixed tree
+    if (p.errors && tid < 256) {
+        double base = 0.0;
+        const DevLayer L = p.layers[l];
+        for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) base += p.base_part[tt];
+        s_base[tid] = base;
+    }
     __syncthreads();
+    if (p.errors) {
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) s_base[tid] += s_base[tid + o];
+            __syncthreads();
+        }
+    }
     if (tid == 0) {
+        const uint32_t need_a = S.need - s_res[1];
         T.sel[j].bin_a = bin_a;
-        T.sel[j].need_a = S.need - s_res[1];
+        T.sel[j].need_a = need_a;
         T.sel[j].energy_a = s_e;
         double s = 0.0;               // energy of the candidates below the threshold bin
         for (int wg = wr.x; wg < wr.y; ++wg) s += p.below_part[(size_t)wg * kMaxTopk + j];
         T.sel[j].energy_below = s;
+        if (p.errors) {
+            const uint32_t cnt = s_hist[bin_a];
+            double inside = 0.0;      // dropped part of the sub-bin, in integer-energy units
+            if (cnt > need_a) {
+                const double e_lo = (double)int_energy((S.tbin << kHistShift) | (bin_a << 9));
+                const double mean = (double)s_en[bin_a] / (double)cnt;
+                const double f = (double)(cnt - need_a) / (double)cnt;
+                inside = (double)(cnt - need_a) * (e_lo + (mean - e_lo) * f);
+            }
+            const uint32_t ex = S.tbin >> (23 - kHistShift);
+            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + 16;
+            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + s + ldexp((double)s_e + inside, sh);
+        }
     }
 }
 
@@ -805,9 +893,11 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
                        t->d_hist, n, 0u);
     TK_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(topk_sample_kernel, dim3(n_tiles), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
-                       (const uint32_t*)t->d_k, shist);
-    TK_CHECK(hipGetLastError());
+    if (nw > 0) {
+        hipLaunchKernelGGL(topk_sample_kernel, dim3(nw), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
+                           (const RefWork*)t->d_work, shist);
+        TK_CHECK(hipGetLastError());
+    }
     hipLaunchKernelGGL(topk_predict_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)shist,
                        (const uint32_t*)t->d_k, ntk, d_layers, t->d_lo);
     return hipGetLastError();
@@ -909,8 +999,9 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     }
     hipLaunchKernelGGL(topk_refine_a_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
     TK_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
     TK_CHECK(hipGetLastError());
+    if (d_errors) return hipSuccess;      // the profile needs no exact threshold: level A is enough
     hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
@@ -925,7 +1016,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
     TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, tm, s));
     {
-        Section sec(tm, "topk_collect");
+        Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
     }
     TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, tm, s));
