@@ -34,9 +34,7 @@ struct TopkList {
 struct TopkSel {
     uint32_t k, tbin, need, list;   // need: entries to take from the threshold bin (1..count)
     uint32_t bin_a, need_a;         // refinement level A (bits 18..9)
-    uint32_t thr, ties_keep;        // exact threshold pattern; equal entries kept
-    unsigned long long energy_a;    // integer energy of the list's entries below bin_a
-    double energy_below;            // energy of the candidates below the threshold bin
+    uint32_t thr, ties_keep;        // exact threshold pattern; equal entries kept (compress)
 };
 struct TopkLayer {
     int64_t cand_base;              // first slot of this layer's region in the candidate buffer
@@ -109,11 +107,6 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t* total) 
     }
     *total = tot;
     return base + inc - v;
-}
-
-__device__ __forceinline__ unsigned long long int_energy(uint32_t pat) {
-    const unsigned long long m = (pat & 0x7FFFFFu) | ((pat >> 23) ? 0x800000u : 0u);
-    return (m * m) >> 16;
 }
 
 // ------------------------------------------------------------------------ kernels
@@ -360,7 +353,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
             S.k = k;
             S.tbin = s_res[0];
             S.need = k - s_res[1];
-            S.thr = 0; S.ties_keep = 0; S.bin_a = 0; S.need_a = 0; S.energy_a = 0; S.energy_below = 0.0;
+            S.thr = 0; S.ties_keep = 0; S.bin_a = 0; S.need_a = 0;
         }
         __syncthreads();
     }
@@ -399,10 +392,9 @@ struct RefineParams {
     const double* base_part;          // [n_tiles]
     double* below_part;               // [n_work x kMaxTopk] energy of candidates below each threshold bin
     // per-workgroup partial histograms (plain stores, summed in workgroup order by the pick kernels)
-    uint32_t* cnt_a;                  // [n_work x kMaxTopk x kBinsA]
-    unsigned long long* en_a;
-    uint32_t* cnt_b;                  // [n_work x kMaxTopk x kBinsB]
-    unsigned long long* en_b;
+    uint32_t* cnt_a;                  // [n_work x kMaxTopk x kBinsA] compress: counts
+    unsigned long long* cell_a;       // [n_work x kMaxTopk x kBinsA] profile: packed count + energy
+    uint32_t* cnt_b;                  // [n_work x kMaxTopk x kBinsB] compress: counts
     double* errors;                   // may be null (compress)
     int32_t stride;
     int32_t ntk;
@@ -435,27 +427,43 @@ __device__ __forceinline__ void for_each_candidate(const RefineParams& p, const 
     }
 }
 
-// Refinement level A: energy of the candidates below every threshold bin, and histogram
-// (count, energy) of bits 18..9 of the candidates inside each threshold bin.  Squares are summed
-// in fp32 per lane (a lane sees some tens of candidates), in fp64 from the wavefront up.
+// Level-A histogram cell of the profile: entries in the low 20 bits (a refinement workgroup sees at
+// most kRefTiles * kTile = 2^19 candidates), their integer energy sum (m^2 >> 23 each, < 2^25) above.
+constexpr int kPackCountBits = 20, kPackEnergyShift = 23;
+static_assert((long long)kRefTiles * kTile < (1ll << kPackCountBits), "count field too narrow");
+static_assert(48 - kPackEnergyShift + kPackCountBits - 1 + kPackCountBits <= 64, "energy field too narrow");
+
+__device__ __forceinline__ unsigned long long packed_cell(uint32_t pat) {
+    const unsigned long long m = (pat & 0x7FFFFFu) | ((pat >> 23) ? 0x800000u : 0u);
+    return (((m * m) >> kPackEnergyShift) << kPackCountBits) | 1ull;
+}
+
+// Refinement level A over the candidates of a run of tiles.  ENERGY (profile): per list (distinct
+// threshold bin) a histogram of bits 18..9 whose cells pack count and integer energy into one
+// 64-bit LDS atomic, and per requested k the energy of the candidates below its threshold bin
+// (fp32 per lane - a lane sees some tens of candidates - fp64 from the wavefront up).  Without
+// ENERGY (compress): counts only.  Partial histograms go to global memory with plain stores.
+template <bool ENERGY>
 __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
     __shared__ double s_red[kRefThreads / 64][kMaxTopk];
     const RefWork w = p.work[blockIdx.x];
     const int l = w.layer;
     const TopkLayer& T = p.tl[l];
-    const uint32_t nlists = T.nlists;
-    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
-    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)nlists * kBinsA);
+    const int nlists = (int)T.nlists;
+    unsigned long long* const s_cell = reinterpret_cast<unsigned long long*>(refine_smem);   // ENERGY
+    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(refine_smem);                        // !ENERGY
     const int tid = threadIdx.x, ntk = p.ntk;
-    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
+    for (int i = tid; i < nlists * kBinsA; i += kRefThreads) {
+        if (ENERGY) s_cell[i] = 0; else s_cnt[i] = 0;
+    }
     // workgroup-uniform: threshold bin of every k (0 = inactive: nothing is below it) and the
     // distinct threshold bins ("lists")
     uint32_t tb[kMaxTopk], lb[kMaxTopk];
 #pragma unroll
     for (int j = 0; j < kMaxTopk; ++j) {
         tb[j] = (j < ntk && T.sel[j].k) ? T.sel[j].tbin : 0u;
-        lb[j] = j < (int)nlists ? T.lists[j].bin : 0xFFFFFFFFu;
+        lb[j] = j < nlists ? T.lists[j].bin : 0xFFFFFFFFu;
     }
     __syncthreads();
     float below[kMaxTopk];
@@ -467,56 +475,63 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
         uint32_t hit = 0;               // 1 + index of the list this candidate belongs to
 #pragma unroll
         for (int j = 0; j < kMaxTopk; ++j) {
-            below[j] = __builtin_fmaf(key < tb[j] ? xf : 0.0f, xf, below[j]);
+            if (ENERGY) below[j] = __builtin_fmaf(key < tb[j] ? xf : 0.0f, xf, below[j]);
             hit = key == lb[j] ? (uint32_t)(j + 1) : hit;
         }
         if (hit) {
             const uint32_t b = (hit - 1) * kBinsA + ((pat >> 9) & (kBinsA - 1));
-            atomicAdd(&s_cnt[b], 1u);
-            atomicAdd(&s_en[b], int_energy(pat));
+            if (ENERGY) atomicAdd(&s_cell[b], packed_cell(pat));
+            else atomicAdd(&s_cnt[b], 1u);
         }
     });
+    if (ENERGY) {
 #pragma unroll
-    for (int j = 0; j < kMaxTopk; ++j) {
-        if (j < ntk) {
-            const double s = wave_sum((double)below[j]);
-            if ((tid & 63) == 0) s_red[tid >> 6][j] = s;
+        for (int j = 0; j < kMaxTopk; ++j) {
+            if (j < ntk) {
+                const double s = wave_sum((double)below[j]);
+                if ((tid & 63) == 0) s_red[tid >> 6][j] = s;
+            }
         }
     }
     __syncthreads();
-    if (tid < ntk) {
+    if (ENERGY && tid < ntk) {
         double s = 0.0;
         for (int wv = 0; wv < kRefThreads / 64; ++wv) s += s_red[wv][tid];
         p.below_part[(size_t)blockIdx.x * kMaxTopk + tid] = s;
     }
-    uint32_t* const gc = p.cnt_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
-    unsigned long long* const ge = p.en_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
-    for (int i = tid; i < (int)nlists * kBinsA; i += kRefThreads) {
-        gc[i] = s_cnt[i];
-        ge[i] = s_en[i];
+    if (ENERGY) {
+        unsigned long long* const gc = p.cell_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
+        for (int i = tid; i < nlists * kBinsA; i += kRefThreads) gc[i] = s_cell[i];
+    } else {
+        uint32_t* const gc = p.cnt_a + (size_t)blockIdx.x * kMaxTopk * kBinsA;
+        for (int i = tid; i < nlists * kBinsA; i += kRefThreads) gc[i] = s_cnt[i];
     }
 }
 
 // One workgroup per (layer, requested k): sub-bin of level A holding the k-th magnitude.
-// With p.errors (profile) the dropped energy is written here and level B is not run: inside the
-// sub-bin (magnitudes within 2^-14 of each other) the energies of the dropped entries are taken
-// as evenly spread between the sub-bin's lower edge and its mean, which bounds the relative
-// deviation of the layer's error by 3e-5 in the worst case (a layer whose dropped energy sits
-// entirely in that sub-bin) and is exact when the sub-bin's entries are equal.
+// ENERGY (profile): the dropped energy is written here and level B is not run.  Inside the sub-bin
+// (magnitudes within 2^-14 of each other) the energies of the dropped entries are taken as evenly
+// spread between the sub-bin's lower edge and its mean, which bounds the relative deviation of
+// the layer's error by 3e-5 in the worst case (a layer whose dropped energy sits entirely in that
+// sub-bin) and is exact when the sub-bin's entries are equal.
+template <bool ENERGY>
 __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsA];
-    __shared__ unsigned long long s_en[kBinsA];
+    __shared__ unsigned long long s_en[ENERGY ? kBinsA : 1];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
-    __shared__ double s_base[256];
+    __shared__ double s_base[256], s_below[256];
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
     const TopkSel S = T.sel[j];
     const int2 wr = p.work_range[l];
     const int tid = threadIdx.x, t = tid & 255, grp = tid >> 8;
-    for (int b = tid; b < kBinsA; b += kPickThreads) { s_hist[b] = 0; s_en[b] = 0; }
+    for (int b = tid; b < kBinsA; b += kPickThreads) {
+        s_hist[b] = 0;
+        if (ENERGY) s_en[b] = 0;
+    }
     if (tid == 0) s_e = 0;
     __syncthreads();
     // sum the layer's workgroup partials of this k's list: 4 bins per thread, the workgroups dealt
@@ -530,33 +545,41 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
             const size_t i = (size_t)wg * kMaxTopk * kBinsA + off;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                c[q] += p.cnt_a[i + 256 * q];
-                e[q] += p.en_a[i + 256 * q];
+                if (ENERGY) {
+                    const unsigned long long v = p.cell_a[i + 256 * q];
+                    c[q] += (uint32_t)(v & ((1ull << kPackCountBits) - 1));
+                    e[q] += v >> kPackCountBits;
+                } else {
+                    c[q] += p.cnt_a[i + 256 * q];
+                }
             }
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (c[q]) atomicAdd(&s_hist[t + 256 * q], c[q]);
-            if (e[q]) atomicAdd(&s_en[t + 256 * q], e[q]);
+            if (ENERGY && e[q]) atomicAdd(&s_en[t + 256 * q], e[q]);
         }
     }
     __syncthreads();
     block_kth_from_top(s_hist, kBinsA, S.need, s_scan, s_res);
     const uint32_t bin_a = s_res[0];
-    unsigned long long e = 0;
-    for (uint32_t b = tid; b < bin_a; b += kPickThreads) e += s_en[b];
-    if (e) atomicAdd(&s_e, e);
-    // energy below the collection bound: the layer's tile partials in a fixed tree
-    if (p.errors && tid < 256) {
-        double base = 0.0;
-        const DevLayer L = p.layers[l];
-        for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) base += p.base_part[tt];
-        s_base[tid] = base;
-    }
-    __syncthreads();
-    if (p.errors) {
+    if (ENERGY) {
+        unsigned long long e = 0;
+        for (uint32_t b = tid; b < bin_a; b += kPickThreads) e += s_en[b];
+        if (e) atomicAdd(&s_e, e);
+        // energy below the collection bound (tile partials) and of the candidates below the
+        // threshold bin (workgroup partials), each summed in a fixed tree
+        if (tid < 256) {
+            double base = 0.0, below = 0.0;
+            const DevLayer L = p.layers[l];
+            for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) base += p.base_part[tt];
+            for (int wg = wr.x + tid; wg < wr.y; wg += 256) below += p.below_part[(size_t)wg * kMaxTopk + j];
+            s_base[tid] = base;
+            s_below[tid] = below;
+        }
+        __syncthreads();
         for (int o = 128; o > 0; o >>= 1) {
-            if (tid < o) s_base[tid] += s_base[tid + o];
+            if (tid < o) { s_base[tid] += s_base[tid + o]; s_below[tid] += s_below[tid + o]; }
             __syncthreads();
         }
     }
@@ -564,67 +587,55 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         const uint32_t need_a = S.need - s_res[1];
         T.sel[j].bin_a = bin_a;
         T.sel[j].need_a = need_a;
-        T.sel[j].energy_a = s_e;
-        double s = 0.0;               // energy of the candidates below the threshold bin
-        for (int wg = wr.x; wg < wr.y; ++wg) s += p.below_part[(size_t)wg * kMaxTopk + j];
-        T.sel[j].energy_below = s;
-        if (p.errors) {
+        if (ENERGY) {
             const uint32_t cnt = s_hist[bin_a];
             double inside = 0.0;      // dropped part of the sub-bin, in integer-energy units
             if (cnt > need_a) {
-                const double e_lo = (double)int_energy((S.tbin << kHistShift) | (bin_a << 9));
+                const uint32_t edge = (S.tbin << kHistShift) | (bin_a << 9);
+                const double e_lo = (double)(packed_cell(edge) >> kPackCountBits);
                 const double mean = (double)s_en[bin_a] / (double)cnt;
                 const double f = (double)(cnt - need_a) / (double)cnt;
                 inside = (double)(cnt - need_a) * (e_lo + (mean - e_lo) * f);
             }
             const uint32_t ex = S.tbin >> (23 - kHistShift);
-            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + 16;
-            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + s + ldexp((double)s_e + inside, sh);
+            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + kPackEnergyShift;
+            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + s_below[0] + ldexp((double)s_e + inside, sh);
         }
     }
 }
 
-// Refinement level B: histogram of bits 8..0 of the candidates inside each k's level-A sub-bin.
+// Refinement level B (compress only): histogram of bits 8..0 of the candidates inside each k's
+// level-A sub-bin.
 __global__ __launch_bounds__(kRefThreads) void topk_refine_b_kernel(RefineParams p) {
     extern __shared__ unsigned char refine_smem[];
-    __shared__ uint32_t s_prefix[kMaxTopk];      // top 22 bits (coarse bin, level-A bin) of each k
     const RefWork w = p.work[blockIdx.x];
     const TopkLayer& T = p.tl[w.layer];
     const int ntk = p.ntk;
-    unsigned long long* const s_en = reinterpret_cast<unsigned long long*>(refine_smem);
-    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(s_en + (size_t)ntk * kBinsB);
+    uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(refine_smem);
     const int tid = threadIdx.x;
-    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) { s_en[i] = 0; s_cnt[i] = 0; }
-    if (tid < kMaxTopk)
-        s_prefix[tid] = (tid < ntk && T.sel[tid].k) ? ((T.sel[tid].tbin << 10) | T.sel[tid].bin_a) : 0xFFFFFFFFu;
+    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) s_cnt[i] = 0;
+    uint32_t prefix[kMaxTopk];       // top 22 bits (coarse bin, level-A bin) of each k
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j)
+        prefix[j] = (j < ntk && T.sel[j].k) ? ((T.sel[j].tbin << 10) | T.sel[j].bin_a) : 0xFFFFFFFFu;
     __syncthreads();
-    const uint32_t min_pre = T.min_tbin << 10;
     for_each_candidate(p, T, w.t0, w.t1, [&](uint32_t pat) {
         const uint32_t pre = pat >> 9;
-        if (pre < min_pre) return;
-        for (int j = 0; j < ntk; ++j)
-            if (pre == s_prefix[j]) {
-                atomicAdd(&s_cnt[j * kBinsB + (pat & (kBinsB - 1))], 1u);
-                atomicAdd(&s_en[j * kBinsB + (pat & (kBinsB - 1))], int_energy(pat));
-            }
+#pragma unroll
+        for (int j = 0; j < kMaxTopk; ++j)
+            if (pre == prefix[j]) atomicAdd(&s_cnt[j * kBinsB + (pat & (kBinsB - 1))], 1u);
     });
     __syncthreads();
     uint32_t* const gc = p.cnt_b + (size_t)blockIdx.x * kMaxTopk * kBinsB;
-    unsigned long long* const ge = p.en_b + (size_t)blockIdx.x * kMaxTopk * kBinsB;
-    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) {
-        gc[i] = s_cnt[i];
-        ge[i] = s_en[i];
-    }
+    for (int i = tid; i < ntk * kBinsB; i += kRefThreads) gc[i] = s_cnt[i];
 }
 
-// One workgroup per (layer, requested k): exact threshold, equal entries kept, dropped energy.
+// One workgroup per (layer, requested k): exact threshold pattern and how many of the entries
+// equal to it are kept.
 __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsB];
-    __shared__ unsigned long long s_en[kBinsB];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
-    __shared__ unsigned long long s_e;
-    __shared__ double s_base[256];
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
@@ -633,56 +644,21 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
     const int tid = threadIdx.x;
     {
         uint32_t c[2] = {0, 0};
-        unsigned long long e[2] = {0, 0};
         const size_t off = (size_t)j * kBinsB + tid;
 #pragma unroll 8
         for (int wg = wr.x; wg < wr.y; ++wg) {
             const size_t i = (size_t)wg * kMaxTopk * kBinsB + off;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                c[q] += p.cnt_b[i + 256 * q];
-                e[q] += p.en_b[i + 256 * q];
-            }
+            for (int q = 0; q < 2; ++q) c[q] += p.cnt_b[i + 256 * q];
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            s_hist[tid + 256 * q] = c[q];
-            s_en[tid + 256 * q] = e[q];
-        }
+        for (int q = 0; q < 2; ++q) s_hist[tid + 256 * q] = c[q];
     }
-    if (tid == 0) s_e = 0;
     __syncthreads();
     block_kth_from_top(s_hist, kBinsB, S.need_a, s_scan, s_res);
-    const uint32_t bin_b = s_res[0];
-    unsigned long long e = 0;
-    for (uint32_t b = tid; b < bin_b; b += 256) e += s_en[b];
-    atomicAdd(&s_e, e);
-    // energy below the collection bound: the layer's tile partials in tile order (fixed tree)
-    double base = 0.0;
-    if (p.errors) {
-        const DevLayer L = p.layers[l];
-        for (int t = L.tile_begin + tid; t < L.tile_end; t += 256) base += p.base_part[t];
-    }
-    s_base[tid] = base;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) s_base[tid] += s_base[tid + o];
-        __syncthreads();
-    }
     if (tid == 0) {
-        const uint32_t ties_keep = S.need_a - s_res[1];
-        const uint32_t count_eq = s_hist[bin_b];
-        const uint32_t thr = (S.tbin << kHistShift) | (S.bin_a << 9) | bin_b;
-        T.sel[j].thr = thr;
-        T.sel[j].ties_keep = ties_keep;
-        if (p.errors) {
-            // entries of the threshold bin below the threshold, plus the surplus equal entries
-            const unsigned long long total =
-                S.energy_a + s_e + (unsigned long long)(count_eq - ties_keep) * int_energy(thr);
-            const uint32_t ex = thr >> 23;
-            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + 16;
-            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + S.energy_below + ldexp((double)total, sh);
-        }
+        T.sel[j].thr = (S.tbin << kHistShift) | (S.bin_a << 9) | s_res[0];
+        T.sel[j].ties_keep = S.need_a - s_res[1];
     }
 }
 
@@ -828,7 +804,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
     t->max_work = max_tiles / kRefTiles + max_layers + 1;
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
-    t->ref_words = (size_t)t->max_work * kMaxTopk * (kBinsA + kBinsB) * 3;      // u32 + u64 per bin
+    t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
     TK_CHECK(hipMalloc(&t->d_work, sizeof(RefWork) * (size_t)t->max_work));
     TK_CHECK(hipMalloc(&t->d_work_range, sizeof(int2) * (size_t)max_layers));
@@ -977,32 +953,36 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     p.work_range = (const int2*)t->d_work_range;
     p.base_part = t->d_base_part;
     p.below_part = t->d_below_part;
-    // per-workgroup partial histograms: [counts A][counts B][energies A][energies B]
-    const size_t na = (size_t)t->max_work * kMaxTopk * kBinsA, nb = (size_t)t->max_work * kMaxTopk * kBinsB;
-    p.cnt_a = t->d_ref;
+    // per-workgroup partial histograms: [packed cells A (u64)][counts A][counts B]
+    const size_t na = (size_t)t->max_work * kMaxTopk * kBinsA;
+    p.cell_a = reinterpret_cast<unsigned long long*>(t->d_ref);
+    p.cnt_a = t->d_ref + 2 * na;
     p.cnt_b = p.cnt_a + na;
-    p.en_a = reinterpret_cast<unsigned long long*>(p.cnt_b + nb);
-    p.en_b = p.en_a + na;
     p.errors = d_errors;
     p.stride = stride;
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
     Section sec(tm, "topk_refine");
-    const size_t lds_a = (size_t)kMaxTopk * kBinsA * 12, lds_b = (size_t)kMaxTopk * kBinsB * 12;
-    static bool configured = false;   // the dynamic LDS limits are raised once
+    const size_t lds_a = (size_t)kMaxTopk * kBinsA * 8;
+    static bool configured = false;   // the dynamic LDS limit is raised once
     if (!configured) {
-        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel,
+        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel<true>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_a));
-        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_b_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_b));
         configured = true;
     }
-    hipLaunchKernelGGL(topk_refine_a_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 12, s, p);
+    if (d_errors) {       // profile: level A gives the dropped energy, no exact threshold is needed
+        hipLaunchKernelGGL(topk_refine_a_kernel<true>, dim3(t->n_work), dim3(kRefThreads),
+                           (size_t)ntk * kBinsA * 8, s, p);
+        TK_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(topk_pick_a_kernel<true>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(topk_refine_a_kernel<false>, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 4,
+                       s, p);
     TK_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(topk_pick_a_kernel, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
+    hipLaunchKernelGGL(topk_pick_a_kernel<false>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
     TK_CHECK(hipGetLastError());
-    if (d_errors) return hipSuccess;      // the profile needs no exact threshold: level A is enough
-    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 12, s, p);
+    hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 4, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_b_kernel, dim3(L * kMaxTopk), dim3(256), 0, s, p);
     return hipGetLastError();
