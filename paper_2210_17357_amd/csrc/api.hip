@@ -239,7 +239,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     const size_t lp = (size_t)max_layers * max_cands;
     HIPCHK_C(hipMalloc(&h->d_entries, sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS));
     HIPCHK_C(hipMalloc(&h->d_count, sizeof(int32_t) * max_layers));
-    HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 1)));
+    HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
     HIPCHK_C(hipMalloc(&h->d_choice, sizeof(int32_t) * max_layers));
     HIPCHK_C(hipMalloc(&h->d_result, sizeof(int64_t) * 8));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
@@ -485,6 +485,22 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
                 en[cnt - 1] = DpEntry{b, c, sizes[i]};
             }
         }
+        // An entry with both a larger bin and a size that is not smaller than another entry's can
+        // never lie on the path that is traced back: swapping it for the other entry would give a
+        // total that is no larger at a lower bin sum, which the final arg-min (smallest size, then
+        // lowest bin sum) prefers.  Dropping such entries changes only cells off that path.
+        {
+            DpEntry all[LGRECO_MAX_CANDS];
+            for (int k = 0; k < cnt; ++k) all[k] = en[k];
+            int kept = 0;
+            for (int k = 0; k < cnt; ++k) {
+                bool dominated = false;
+                for (int j = 0; j < cnt && !dominated; ++j)
+                    dominated = all[j].bin < all[k].bin && all[j].size <= all[k].size;
+                if (!dominated) en[kept++] = all[k];
+            }
+            cnt = kept;
+        }
         worst += lmax;
         if (cnt == 0) {
             dead_layer = true;
@@ -511,7 +527,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         HIPCHK(hipMemcpyAsync(h->d_entries, h->h_entries, sizeof(DpEntry) * (size_t)n_sweep * LGRECO_MAX_CANDS,
                               hipMemcpyHostToDevice, s));
         HIPCHK(hipMemcpyAsync(h->d_count, h->h_count, sizeof(int32_t) * n_sweep, hipMemcpyHostToDevice, s));
-        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0};
+        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0};
         {
             Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));

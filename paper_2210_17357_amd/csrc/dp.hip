@@ -2,14 +2,15 @@
 //
 // DP[l][e] = min over candidates c with bin(l,c) <= e of DP[l-1][e - bin(l,c)] + size(l,c),
 // starting from a virtual row DP[0] = (0, inf, inf, ...).  Layers are sequential; the bins of a
-// row are independent, so the 1024 threads each own the bins e = tid, tid + 1024, ... and keep
+// row are independent, so the 1024 threads each own a few bins (adjacent pairs, strided by 2048) and keep
 // the new row in registers while the previous row sits in LDS.  Candidates are visited in index
 // order with a strict '<' (lowest index wins ties); the back-trace starts from the lowest e among
 // the minima of the last row.  PD (arg-min per cell) goes to global memory, one byte per cell.
 //
 // The host hands over, per layer, the list of usable candidates with equal bins merged (for one
 // bin only the smallest size can win, the lowest index among equals; merging keeps the result
-// identical, tie-breaks included).  A layer whose list is a single entry with bin 0 adds a
+// identical, tie-breaks included) and entries that another entry beats in both bin and size left
+// out (they cannot lie on the traced-back path).  A layer whose list is a single entry with bin 0 adds a
 // constant to the whole row: the host fixes its choice and leaves it out, so L here counts the
 // swept layers only.  Entry lists are staged through LDS 32 layers at a time.  Costs are 32-bit when the sum of every layer's largest size stays below 2^30, else
 // 64-bit; "infinity" is 2^30 (2^62), so inf + size never overflows and never beats a real value.
@@ -42,9 +43,17 @@ template <> __device__ __forceinline__ int64_t readlane_t<int64_t>(int64_t v, in
 
 constexpr int kDpStage = 32;    // swept layers whose entry lists are staged in LDS at a time
 
+// Thread t owns KMAX cells.  With an even KMAX they come in adjacent pairs (2t, 2t+1), (2t, 2t+1) +
+// 2*threads, ...: the two reads row[e - b], row[e + 1 - b] of a pair are one ds_read2_b32 and the
+// 64 lanes of a wavefront cover 128 consecutive cells without bank conflicts.
+template <int KMAX, int THREADS>
+__device__ __forceinline__ int dp_cell(int tid, int k) {
+    return KMAX % 2 == 0 ? 2 * tid + (k & 1) + (k >> 1) * 2 * THREADS : tid + k * THREADS;
+}
+
 template <typename T, int KMAX, bool PADDED, int kDpThreads>
 __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
-    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*1024-1 (cells above D stay infinite).
+    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*threads-1 (cells above D stay infinite).
     // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
     extern __shared__ unsigned char dp_smem[];
     T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
@@ -54,8 +63,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     __shared__ int32_t s_idx[kDpThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int D = p.D;
-    const int64_t width = (int64_t)D + 1;
+    const int64_t width = p.pd_stride;
     constexpr T kInf = DpInf<T>::v;
+    // back-trace tables behind the row when they fit (the host decides): the bin of every entry
+    // (16 bits: D <= 16384) and the picked entry per layer
+    const bool lds_bins = p.bt_lds != 0;
+    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * LGRECO_MAX_CANDS);
 
     const uint64_t t_begin = wall_clock64();
     for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
@@ -63,8 +77,11 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     for (int l0 = 0; l0 < p.L; l0 += kDpStage) {
         const int nl = min(kDpStage, p.L - l0);
         __syncthreads();                              // previous stage fully consumed, row written
-        for (int i = tid; i < nl * LGRECO_MAX_CANDS; i += kDpThreads)
-            (&s_entries[0][0])[i] = p.entries[(size_t)l0 * LGRECO_MAX_CANDS + i];
+        for (int i = tid; i < nl * LGRECO_MAX_CANDS; i += kDpThreads) {
+            const DpEntry en = p.entries[(size_t)l0 * LGRECO_MAX_CANDS + i];
+            (&s_entries[0][0])[i] = en;
+            if (lds_bins) s_bins[(size_t)l0 * LGRECO_MAX_CANDS + i] = (uint16_t)en.bin;
+        }
         if (tid < nl) s_count[tid] = p.count[l0 + tid];
         __syncthreads();
         for (int ll = 0; ll < nl; ++ll) {
@@ -83,10 +100,10 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 const int32_t b = (int32_t)readlane_u32((uint32_t)mybin, c);
                 const T sz = readlane_t<T>(mysize, c);
                 if (PADDED) {
-                    const T* __restrict__ src = row + (tid - b);
+                    const T* __restrict__ src = row + (dp_cell<KMAX, kDpThreads>(tid, 0) - b);
 #pragma unroll
                     for (int k = 0; k < KMAX; ++k) {
-                        const T t = src[k * kDpThreads] + sz;
+                        const T t = src[dp_cell<KMAX, kDpThreads>(0, k)] + sz;
                         const bool lt = t < nv[k];
                         nv[k] = lt ? t : nv[k];
                         na[k] = lt ? c : na[k];
@@ -94,7 +111,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 } else {
 #pragma unroll
                     for (int k = 0; k < KMAX; ++k) {
-                        const int idx = tid + k * kDpThreads - b;
+                        const int idx = dp_cell<KMAX, kDpThreads>(tid, k) - b;
                         T t = row[max(idx, 0)] + sz;
                         t = idx >= 0 ? t : kInf;
                         const bool lt = t < nv[k];
@@ -105,12 +122,26 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             }
             __syncthreads();
             uint8_t* __restrict__ pdrow = p.pd + (size_t)(l0 + ll) * width;
+            if (KMAX % 2 == 0) {
+                // a pair is written as a whole: cells above D get infinity (they stay out of every
+                // later minimum), their PD bytes fall into the row's padding
 #pragma unroll
-            for (int k = 0; k < KMAX; ++k) {
-                const int e = tid + k * kDpThreads;
-                if (e <= D) {
-                    row[e] = nv[k];                   // never above kInf: only a smaller t replaces it
-                    pdrow[e] = (uint8_t)na[k];        // index into the layer's entry list
+                for (int k = 0; k < KMAX; k += 2) {
+                    const int e = dp_cell<KMAX, kDpThreads>(tid, k);
+                    if (e <= D) {
+                        row[e] = nv[k];
+                        row[e + 1] = (e + 1 <= D) ? nv[k + 1] : kInf;
+                        *reinterpret_cast<uint16_t*>(pdrow + e) = (uint16_t)((na[k] & 255) | ((na[k + 1] & 255) << 8));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k) {
+                    const int e = tid + k * kDpThreads;
+                    if (e <= D) {
+                        row[e] = nv[k];               // never above kInf: only a smaller t replaces it
+                        pdrow[e] = (uint8_t)na[k];    // index into the layer's entry list
+                    }
                 }
             }
             __syncthreads();
@@ -132,25 +163,48 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     }
     if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
     __syncthreads();
+    uint64_t t_sweep = 0;
     if (tid == 0) {
-        const uint64_t t_sweep = wall_clock64();
+        t_sweep = wall_clock64();
         for (int w = 1; w < kDpThreads / 64; ++w)
             if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
-        if (bv >= (int64_t)kInf) {
+        s_val[0] = bv;
+        s_idx[0] = be;
+        if (bv < (int64_t)kInf) {
+            // the walk is a chain of dependent loads: one PD byte per layer from global memory,
+            // the bin it stands for from LDS when the table fits there
+            int e = be;
+            if (lds_bins) {
+                for (int l = p.L - 1; l >= 0; --l) {
+                    const int k = p.pd[(size_t)l * width + e];
+                    s_pick[l] = (uint8_t)k;
+                    e -= s_bins[l * LGRECO_MAX_CANDS + k];
+                }
+            } else {
+                for (int l = p.L - 1; l >= 0; --l) {
+                    const int k = p.pd[(size_t)l * width + e];
+                    const DpEntry en = p.entries[(size_t)l * LGRECO_MAX_CANDS + k];
+                    p.choice[l] = en.cand;
+                    e -= en.bin;
+                }
+            }
+            s_idx[1] = e;
+        }
+    }
+    __syncthreads();
+    const bool feasible = s_val[0] < (int64_t)kInf;
+    if (feasible && lds_bins)
+        for (int l = tid; l < p.L; l += kDpThreads)
+            p.choice[l] = p.entries[(size_t)l * LGRECO_MAX_CANDS + s_pick[l]].cand;
+    if (tid == 0) {
+        if (!feasible) {
             p.result[0] = 1;
             p.result[1] = 0;
             p.result[2] = 0;
         } else {
-            int e = be;
-            for (int l = p.L - 1; l >= 0; --l) {
-                const int k = p.pd[(size_t)l * width + e];
-                const DpEntry en = p.entries[(size_t)l * LGRECO_MAX_CANDS + k];
-                p.choice[l] = en.cand;
-                e -= en.bin;
-            }
-            p.result[0] = (e == 0) ? 0 : 2;          // 2 would be an internal inconsistency
-            p.result[1] = bv;
-            p.result[2] = be;
+            p.result[0] = (s_idx[1] == 0) ? 0 : 2;   // 2 would be an internal inconsistency
+            p.result[1] = s_val[0];
+            p.result[2] = s_idx[0];
         }
         // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace
         p.result[3] = (int64_t)(t_sweep - t_begin);
@@ -158,7 +212,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     }
 }
 
-constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static
+constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static (160 KB per CU)
 
 template <typename T, int THREADS>
 static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
@@ -170,7 +224,11 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
     const int pad = (max_bin + 63) / 64 * 64;
     const bool padded = ((size_t)pad + (size_t)kmax * THREADS) * sizeof(T) <= kDpLdsBudget;
     p.pad = padded ? pad : 0;
-    const size_t lds = ((size_t)p.pad + (size_t)kmax * THREADS) * sizeof(T);
+    p.pd_stride = (p.D + 1 + 3) & ~3;
+    size_t lds = ((size_t)p.pad + (size_t)kmax * THREADS) * sizeof(T);
+    const size_t bt = (size_t)p.L * LGRECO_MAX_CANDS * sizeof(uint16_t) + (size_t)p.L;
+    p.bt_lds = lds + bt <= kDpLdsBudget ? 1 : 0;
+    if (p.bt_lds) lds += bt;
     hipError_t err = hipSuccess;
 #define LGRECO_DP2(K, PD)                                                                          \
     do {                                                                                           \

@@ -53,11 +53,13 @@ struct DpEntry {            // one usable candidate of a layer (equal bins merge
 struct DpParams {
     const DpEntry* entries;   // [L x LGRECO_MAX_CANDS] swept layers only, in candidate order
     const int32_t* count;     // [L] entries per swept layer
-    uint8_t* pd;              // [L x (D+1)] entry index per cell
+    uint8_t* pd;              // [L x pd_stride] entry index per cell
     int32_t* choice;          // [L] candidate index per swept layer
     int64_t* result;          // [0] status (0 ok, 1 infeasible), [1] swept size, [2] final bin sum
     int32_t L, D;
     int32_t pad;              // set by launch_dp: cells of infinity in front of the LDS row
+    int32_t pd_stride;        // set by launch_dp: bytes per PD row, a multiple of 4 and >= D + 2
+    int32_t bt_lds;           // set by launch_dp: back-trace tables live in LDS behind the row
 };
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
 // max_bin: largest bin in entries

@@ -109,3 +109,36 @@ def test_listing_initialisation_is_a_special_case():
     for c in range(3):
         assert dp[1][bins[0][c]] == sizes[0][c] and pd[1][bins[0][c]] == c
     assert np.sum(dp[1] < solver.INF) == 3
+
+
+def test_dominated_candidates_never_lie_on_the_traced_path():
+    """A property the GPU solver's host step relies on: a candidate that another candidate of the
+    same layer beats in bin (strictly) and in size (not larger) can be removed without changing
+    the assignment, tie-breaks included.  Checked on the oracle alone, on tables full of ties."""
+    rng = np.random.default_rng(5)
+    removed = 0
+    for trial in range(400):
+        n_layers = int(rng.integers(1, 7))
+        n_cands = int(rng.integers(2, 7))
+        n_bins = int(rng.integers(1, 41))
+        bins = rng.integers(-1, n_bins + 2, (n_layers, n_cands)).astype(np.int64)
+        bins[bins > n_bins] = solver.UNUSABLE
+        sizes = rng.integers(0, 5, (n_layers, n_cands)).astype(np.int64)
+        pruned = bins.copy()
+        for l in range(n_layers):
+            for c in range(n_cands):
+                if bins[l, c] == solver.UNUSABLE:
+                    continue
+                for o in range(n_cands):
+                    if bins[l, o] != solver.UNUSABLE and bins[l, o] < bins[l, c] and sizes[l, o] <= sizes[l, c]:
+                        pruned[l, c] = solver.UNUSABLE
+                        removed += 1
+                        break
+        dp, pd = solver.dp_tables(bins, sizes, n_bins)
+        full = solver.backtrace(dp, pd, bins)
+        dp2, pd2 = solver.dp_tables(pruned, sizes, n_bins)
+        cut = solver.backtrace(dp2, pd2, pruned)
+        assert (full is None) == (cut is None)
+        if full is not None:
+            assert list(full) == list(cut), trial
+    assert removed > 500
