@@ -37,16 +37,23 @@ struct lgreco_handle {
     LowrankScratch lowrank;
 
     // solver
-    DpEntry* d_entries = nullptr;
+    // input block [count | entries] and output block [result | choice]: one copy each way
+    uint8_t* d_dp_in = nullptr;
+    uint8_t* h_dp_in = nullptr;     // pinned
+    uint8_t* d_dp_out = nullptr;
+    uint8_t* h_dp_out = nullptr;    // pinned
+    size_t dp_entries_off = 0;      // byte offset of the entries inside the input block
+    DpEntry* d_entries = nullptr;   // views into the blocks
     int32_t* d_count = nullptr;
     uint8_t* d_pd = nullptr;
     int32_t* d_choice = nullptr;
     int64_t* d_result = nullptr;
     int32_t* h_bins = nullptr;      // pinned: original index of every swept layer
-    DpEntry* h_entries = nullptr;   // pinned
-    int32_t* h_count = nullptr;     // pinned
-    int32_t* h_choice = nullptr;    // pinned
-    int64_t* h_result = nullptr;    // pinned
+    DpEntry* h_entries = nullptr;
+    int32_t* h_count = nullptr;
+    int32_t* h_choice = nullptr;
+    int64_t* h_result = nullptr;
+    std::vector<DevLayer> hl_uploaded;   // what d_layers holds
 
     Timing tm;
     // sub-sections measured inside a kernel (device clock), appended after the event sections
@@ -172,9 +179,13 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
 // their per-call fields (family, parameter, payload offset).  Every entry point ends with a stream
 // synchronisation before it returns, so the host vectors outlive the copies.
 int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
-    if (h->layers_dirty || layers_changed)
+    if (h->layers_dirty || (layers_changed && (h->hl_uploaded.size() != h->hl.size() ||
+                                               std::memcmp(h->hl_uploaded.data(), h->hl.data(),
+                                                           sizeof(DevLayer) * h->hl.size()) != 0))) {
         HIPCHK(hipMemcpyAsync(h->d_layers, h->hl.data(), sizeof(DevLayer) * h->hl.size(), hipMemcpyHostToDevice,
                               s));
+        h->hl_uploaded = h->hl;
+    }
     if (h->layers_dirty)
         HIPCHK(hipMemcpyAsync(h->d_tiles, h->ht.data(), sizeof(Tile) * h->ht.size(), hipMemcpyHostToDevice, s));
     h->layers_dirty = false;
@@ -237,17 +248,23 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_errors, sizeof(double) * (size_t)max_layers * max_cands));
     HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
     const size_t lp = (size_t)max_layers * max_cands;
-    HIPCHK_C(hipMalloc(&h->d_entries, sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS));
-    HIPCHK_C(hipMalloc(&h->d_count, sizeof(int32_t) * max_layers));
+    h->dp_entries_off = (sizeof(int32_t) * (size_t)max_layers + 15) / 16 * 16;
+    const size_t dp_in = h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS;
+    const size_t dp_out = sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)max_layers;
+    HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
+    HIPCHK_C(hipMalloc(&h->d_dp_out, dp_out));
+    HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
+    h->d_count = reinterpret_cast<int32_t*>(h->d_dp_in);
+    h->d_entries = reinterpret_cast<DpEntry*>(h->d_dp_in + h->dp_entries_off);
+    h->h_count = reinterpret_cast<int32_t*>(h->h_dp_in);
+    h->h_entries = reinterpret_cast<DpEntry*>(h->h_dp_in + h->dp_entries_off);
+    h->d_result = reinterpret_cast<int64_t*>(h->d_dp_out);
+    h->d_choice = reinterpret_cast<int32_t*>(h->d_dp_out + sizeof(int64_t) * 8);
+    h->h_result = reinterpret_cast<int64_t*>(h->h_dp_out);
+    h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * 8);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
-    HIPCHK_C(hipMalloc(&h->d_choice, sizeof(int32_t) * max_layers));
-    HIPCHK_C(hipMalloc(&h->d_result, sizeof(int64_t) * 8));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_entries, sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS,
-                           hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_count, sizeof(int32_t) * max_layers, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_choice, sizeof(int32_t) * max_layers, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_result, sizeof(int64_t) * 8, hipHostMallocDefault));
     for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&h->tm.ev[i]));
     h->tm.ready = true;
     {
@@ -267,16 +284,12 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipFree(h->d_partials);
     (void)hipFree(h->d_errors);
     (void)hipHostFree(h->h_errors);
-    (void)hipFree(h->d_entries);
-    (void)hipFree(h->d_count);
+    (void)hipFree(h->d_dp_in);
+    (void)hipFree(h->d_dp_out);
     (void)hipFree(h->d_pd);
-    (void)hipFree(h->d_choice);
-    (void)hipFree(h->d_result);
     (void)hipHostFree(h->h_bins);
-    (void)hipHostFree(h->h_entries);
-    (void)hipHostFree(h->h_count);
-    (void)hipHostFree(h->h_choice);
-    (void)hipHostFree(h->h_result);
+    (void)hipHostFree(h->h_dp_in);
+    (void)hipHostFree(h->h_dp_out);
     if (h->tm.ready)
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i) (void)hipEventDestroy(h->tm.ev[i]);
     topk_scratch_destroy(&h->topk);
@@ -393,7 +406,7 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
             for (int j = 0; j < ntk; ++j)
                 ks[(size_t)l * kMaxTopk + j] = (uint32_t)topk_k(layers[l].numel, tk_density[j]);
         HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles, ks.data(),
-                          ntk, &h->tm, s));
+                          ntk, 0, &h->tm, s));
     }
     if (qp.nq) {
         qp.g = d_grads;
@@ -524,16 +537,16 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     if (dead_layer) return infeasible();
     if (n_sweep > 0) {
         const bool narrow = worst < ((int64_t)1 << 30);
-        HIPCHK(hipMemcpyAsync(h->d_entries, h->h_entries, sizeof(DpEntry) * (size_t)n_sweep * LGRECO_MAX_CANDS,
+        HIPCHK(hipMemcpyAsync(h->d_dp_in, h->h_dp_in,
+                              h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * LGRECO_MAX_CANDS,
                               hipMemcpyHostToDevice, s));
-        HIPCHK(hipMemcpyAsync(h->d_count, h->h_count, sizeof(int32_t) * n_sweep, hipMemcpyHostToDevice, s));
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0};
         {
             Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
         }
-        HIPCHK(hipMemcpyAsync(h->h_choice, h->d_choice, sizeof(int32_t) * n_sweep, hipMemcpyDeviceToHost, s));
-        HIPCHK(hipMemcpyAsync(h->h_result, h->d_result, sizeof(int64_t) * 8, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipMemcpyAsync(h->h_dp_out, h->d_dp_out, sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)n_sweep,
+                              hipMemcpyDeviceToHost, s));
         HIPCHK(hipStreamSynchronize(s));
         if (h->tm.level >= 1) {                       // 100 MHz constant-rate device counter
             h->sub_name[0] = "dp_solve.sweep";

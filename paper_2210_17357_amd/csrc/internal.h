@@ -81,13 +81,21 @@ struct TopkScratch {
     double* d_below_part = nullptr;   // refinement partial sums
     uint32_t* d_ref = nullptr;        // per-workgroup refinement histograms (counts, integer energies)
     size_t ref_words = 0;
+    // control block, one upload per call and none when it repeats the last one:
+    // [k | cand_base | work_range | work]; the pointers above and below are views into it
+    // (two device copies: profile calls and compress calls alternate and each repeats itself)
+    uint8_t* d_ctl[2] = {nullptr, nullptr};
+    uint8_t* h_ctl = nullptr;         // pinned
+    uint8_t* h_ctl_last[2] = {nullptr, nullptr};    // what each d_ctl holds
+    size_t ctl_bytes = 0, ctl_last_bytes[2] = {0, 0};
+    size_t ctl_off[4] = {0, 0, 0, 0}; // byte offsets of k, cand_base, work_range, work
     void* d_work = nullptr;           // refinement work table and per-layer ranges
     void* d_work_range = nullptr;
-    void* h_work = nullptr;           // pinned
-    void* h_work_range = nullptr;     // pinned
+    void* h_work = nullptr;
+    void* h_work_range = nullptr;
     int max_work = 0, n_work = 0;
-    uint32_t* h_k = nullptr;          // pinned
-    int64_t* h_cand_base = nullptr;   // pinned
+    uint32_t* h_k = nullptr;
+    int64_t* h_cand_base = nullptr;
     int64_t max_elems = 0;
     int max_layers = 0, max_tiles = 0;
 };
@@ -97,7 +105,7 @@ void topk_scratch_destroy(TopkScratch* t);
 // layer's collection bound
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
-                      int ntk, Timing* tm, hipStream_t s);
+                      int ntk, int slot, Timing* tm, hipStream_t s);
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
 // the read; otherwise the quantization profile kernel does the same work
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,

@@ -23,6 +23,9 @@
 //      nothing depends on the order of atomics.
 // Compression then counts kept entries per tile from the candidates, scans the tile counts, and
 // writes values and indices in ascending index order (equal magnitudes: lowest indices first).
+#include <cstdlib>
+#include <cstring>
+
 #include "internal.h"
 #include "topk_dev.h"
 
@@ -795,9 +798,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
-    TK_CHECK(hipMalloc(&t->d_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
-    TK_CHECK(hipMalloc(&t->d_cand_base, sizeof(int64_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
@@ -806,12 +807,25 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
     t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
-    TK_CHECK(hipMalloc(&t->d_work, sizeof(RefWork) * (size_t)t->max_work));
-    TK_CHECK(hipMalloc(&t->d_work_range, sizeof(int2) * (size_t)max_layers));
-    TK_CHECK(hipHostMalloc(&t->h_work, sizeof(RefWork) * (size_t)t->max_work, hipHostMallocDefault));
-    TK_CHECK(hipHostMalloc(&t->h_work_range, sizeof(int2) * (size_t)max_layers, hipHostMallocDefault));
-    TK_CHECK(hipHostMalloc(&t->h_k, sizeof(uint32_t) * (size_t)max_layers * kMaxTopk, hipHostMallocDefault));
-    TK_CHECK(hipHostMalloc(&t->h_cand_base, sizeof(int64_t) * (size_t)max_layers, hipHostMallocDefault));
+    // control block layout (every part a multiple of 16 bytes)
+    const size_t o_k = 0;
+    const size_t o_base = o_k + sizeof(uint32_t) * (size_t)max_layers * kMaxTopk;
+    const size_t o_range = o_base + (sizeof(int64_t) * (size_t)max_layers + 15) / 16 * 16;
+    const size_t o_work = o_range + (sizeof(int2) * (size_t)max_layers + 15) / 16 * 16;
+    t->ctl_bytes = o_work + sizeof(RefWork) * (size_t)t->max_work;
+    t->ctl_off[0] = o_k; t->ctl_off[1] = o_base; t->ctl_off[2] = o_range; t->ctl_off[3] = o_work;
+    TK_CHECK(hipHostMalloc(&t->h_ctl, t->ctl_bytes, hipHostMallocDefault));
+    std::memset(t->h_ctl, 0, t->ctl_bytes);
+    for (int i = 0; i < 2; ++i) {
+        TK_CHECK(hipMalloc(&t->d_ctl[i], t->ctl_bytes));
+        t->h_ctl_last[i] = static_cast<uint8_t*>(std::malloc(t->ctl_bytes));
+        if (!t->h_ctl_last[i]) return hipErrorOutOfMemory;
+        t->ctl_last_bytes[i] = 0;
+    }
+    t->h_k = reinterpret_cast<uint32_t*>(t->h_ctl + o_k);
+    t->h_cand_base = reinterpret_cast<int64_t*>(t->h_ctl + o_base);
+    t->h_work_range = t->h_ctl + o_range;
+    t->h_work = t->h_ctl + o_work;
     return hipSuccess;
 }
 
@@ -820,21 +834,18 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_tl);
     (void)hipFree(t->d_cand);
     (void)hipFree(t->d_cand_idx);
-    (void)hipFree(t->d_k);
     (void)hipFree(t->d_lo);
-    (void)hipFree(t->d_cand_base);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
     (void)hipFree(t->d_tinfo);
     (void)hipFree(t->d_base_part);
     (void)hipFree(t->d_below_part);
     (void)hipFree(t->d_ref);
-    (void)hipFree(t->d_work);
-    (void)hipFree(t->d_work_range);
-    (void)hipHostFree(t->h_work);
-    (void)hipHostFree(t->h_work_range);
-    (void)hipHostFree(t->h_k);
-    (void)hipHostFree(t->h_cand_base);
+    for (int i = 0; i < 2; ++i) {
+        (void)hipFree(t->d_ctl[i]);
+        std::free(t->h_ctl_last[i]);
+    }
+    (void)hipHostFree(t->h_ctl);
     *t = TopkScratch{};
 }
 
@@ -842,7 +853,7 @@ void topk_scratch_destroy(TopkScratch* t) {
 // the sample and predict the collection bound of every layer.
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
-                      int ntk, Timing* tm, hipStream_t s) {
+                      int ntk, int slot, Timing* tm, hipStream_t s) {
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
     int2* const wrange = (int2*)t->h_work_range;
@@ -859,10 +870,19 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
         wrange[l].y = nw;
     }
     t->n_work = nw;
-    TK_CHECK(hipMemcpyAsync(t->d_work, work, sizeof(RefWork) * (size_t)std::max(nw, 1), hipMemcpyHostToDevice, s));
-    TK_CHECK(hipMemcpyAsync(t->d_work_range, wrange, sizeof(int2) * (size_t)L, hipMemcpyHostToDevice, s));
-    TK_CHECK(hipMemcpyAsync(t->d_k, t->h_k, sizeof(uint32_t) * (size_t)L * kMaxTopk, hipMemcpyHostToDevice, s));
-    TK_CHECK(hipMemcpyAsync(t->d_cand_base, t->h_cand_base, sizeof(int64_t) * (size_t)L, hipMemcpyHostToDevice, s));
+    // one upload of the control block up to the last work item, skipped when this slot's device
+    // copy already holds the same bytes
+    uint8_t* const d = t->d_ctl[slot];
+    t->d_k = reinterpret_cast<uint32_t*>(d + t->ctl_off[0]);
+    t->d_cand_base = reinterpret_cast<int64_t*>(d + t->ctl_off[1]);
+    t->d_work_range = d + t->ctl_off[2];
+    t->d_work = d + t->ctl_off[3];
+    const size_t used = (size_t)((uint8_t*)(work + std::max(nw, 1)) - t->h_ctl);
+    if (used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0) {
+        TK_CHECK(hipMemcpyAsync(d, t->h_ctl, used, hipMemcpyHostToDevice, s));
+        std::memcpy(t->h_ctl_last[slot], t->h_ctl, used);
+        t->ctl_last_bytes[slot] = used;
+    }
     Section sec(tm, "topk_sample");
     const size_t n = 2 * (size_t)L * kHistBins;
     uint32_t* const shist = t->d_hist + (size_t)L * kHistBins;
@@ -994,7 +1014,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
     for (int l = 0; l < L; ++l)
         if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
-    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, tm, s));
+    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, 1, tm, s));
     {
         Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
