@@ -132,6 +132,20 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
                  int32_t P, double e_max, int32_t n_bins, int32_t* choice, int64_t* total_size,
                  double* total_error, void* stream);
 
+/* Solve with the time-based objective: minimise sum size(l, c_l) * T(l) under the same
+ * constraint (section "Time optimization": per-bucket coefficients T applied to the layers of
+ * the bucket; appendix "Buckets prioritization": T = index of the bucket the layer travels in).
+ * The coefficients are non-negative integers, so the table stays exact: a caller with real
+ * regression coefficients scales and rounds them.  Everything else is as in lgreco_solve,
+ * with size * T in place of size, tie-breaks included.
+ *   weights     host [L], 0 <= T(l); every size(l,c) * T(l) must stay below 2^45
+ *   total_size  sum of the chosen sizes in bytes, unweighted (may be NULL)
+ *   total_cost  sum of the chosen size * T (may be NULL) */
+int lgreco_solve_weighted(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
+                          const int64_t* weights, int32_t L, int32_t P, double e_max,
+                          int32_t n_bins, int32_t* choice, int64_t* total_size,
+                          int64_t* total_cost, double* total_error, void* stream);
+
 /* Byte offset of every layer's payload for a given choice, host arithmetic only.
  * offsets has L+1 entries; layer l's payload is [offsets[l], offsets[l] + size(l, choice[l]))
  * and offsets[L] is the buffer size to allocate.  Layer starts are rounded up to 16 bytes. */

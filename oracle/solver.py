@@ -117,6 +117,28 @@ def solve(errors: np.ndarray, sizes: np.ndarray, e_max: float, n_bins: int, fast
     return choice, int(sizes[rows, choice].sum()), float(np.sum(errors[rows, choice]))
 
 
+def solve_weighted(errors: np.ndarray, sizes: np.ndarray, weights: np.ndarray, e_max: float, n_bins: int,
+                   fast: bool = True):
+    """Time-based objective (section "Time optimization"; appendix "Buckets prioritization"):
+    minimise sum_l size(l, c_l) * T(l) under the same error constraint.  T(l) are non-negative
+    integers here (the paper's regression coefficients, scaled by the caller; a bucket index in
+    the appendix), so the table stays exact.  Algorithm 1 runs unchanged on the weighted costs.
+    Returns (choice or None, total_size (unweighted bytes), total_cost, total_error)."""
+    errors = np.asarray(errors, np.float64)
+    sizes = np.asarray(sizes, np.int64)
+    weights = np.asarray(weights, np.int64)
+    assert weights.shape == (errors.shape[0],) and (weights >= 0).all()
+    cost = sizes * weights[:, None]
+    bins = discretise(errors, e_max, n_bins)
+    dp, pd = (dp_tables_fast if fast else dp_tables)(bins, cost, n_bins)
+    choice = backtrace(dp, pd, bins)
+    if choice is None:
+        return None, None, None, None
+    rows = np.arange(errors.shape[0])
+    return (choice, int(sizes[rows, choice].sum()), int(cost[rows, choice].sum()),
+            float(np.sum(errors[rows, choice])))
+
+
 def e_max_uniform(errors: np.ndarray, default: int) -> float:
     """Error budget: total error of the uniform default setting, summed in layer order
     (Algorithm 1, second step; section "The Error Bound")."""

@@ -19,7 +19,7 @@ OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 QUANT, TOPK, LOWRANK = 0, 1, 2
 
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_emax",
-           "lgreco_solve", "lgreco_payload_layout", "lgreco_compress", "lgreco_set_timing",
+           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_set_timing",
            "lgreco_get_timing", "lgreco_strerror", "lgreco_last_hip_error")
 
 
@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         l.lgreco_profile.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp]
         l.lgreco_emax.argtypes = [vp, i32, i32, i32, C.POINTER(dbl)]
         l.lgreco_solve.argtypes = [vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64), C.POINTER(dbl), vp]
+        l.lgreco_solve_weighted.argtypes = [vp, vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64),
+                                            C.POINTER(i64), C.POINTER(dbl), vp]
         l.lgreco_payload_layout.argtypes = [vp, i32, vp, i32, vp, i32, vp]
         l.lgreco_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
         l.lgreco_set_timing.argtypes = [vp, i32]
@@ -190,6 +192,20 @@ class Handle:
                                 _np(choice), C.byref(tsize), C.byref(terr), _stream())
         self._check(st, allow=(EINFEASIBLE,))
         return st, choice, tsize.value, terr.value
+
+    def solve_weighted(self, errors: np.ndarray, szs: np.ndarray, weights: np.ndarray, e_max: float,
+                       n_bins: int):
+        errors = np.ascontiguousarray(errors, np.float64)
+        szs = np.ascontiguousarray(szs, np.int64)
+        weights = np.ascontiguousarray(weights, np.int64)
+        L, P = errors.shape
+        choice = np.zeros(L, np.int32)
+        tsize, tcost, terr = C.c_int64(), C.c_int64(), C.c_double()
+        st = lib().lgreco_solve_weighted(self._h, _np(errors), _np(szs), _np(weights), L, P, float(e_max),
+                                         int(n_bins), _np(choice), C.byref(tsize), C.byref(tcost),
+                                         C.byref(terr), _stream())
+        self._check(st, allow=(EINFEASIBLE,))
+        return st, choice, tsize.value, tcost.value, terr.value
 
     def compress(self, d_grads, d_ef, layers, cands, choice: np.ndarray, d_payload, offsets: np.ndarray,
                  d_q=None):

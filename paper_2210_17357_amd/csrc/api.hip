@@ -573,6 +573,33 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     return LGRECO_OK;
 }
 
+int lgreco_solve_weighted(lgreco_handle_t* h, const double* errors, const int64_t* sizes, const int64_t* weights,
+                          int32_t L, int32_t P, double e_max, int32_t n_bins, int32_t* choice,
+                          int64_t* total_size, int64_t* total_cost, double* total_error, void* stream) {
+    if (!h || !errors || !sizes || !weights || !choice || L <= 0 || P <= 0) return LGRECO_EINVAL;
+    const int64_t limit = (int64_t)1 << 45;
+    std::vector<int64_t> cost((size_t)L * P);
+    for (int l = 0; l < L; ++l) {
+        if (weights[l] < 0 || weights[l] >= limit) return LGRECO_EINVAL;
+        for (int c = 0; c < P; ++c) {
+            const int64_t sz = sizes[(size_t)l * P + c];
+            if (sz < 0 || sz >= limit) return LGRECO_EINVAL;
+            if (weights[l] != 0 && sz > (limit - 1) / weights[l]) return LGRECO_EINVAL;
+            cost[(size_t)l * P + c] = sz * weights[l];
+        }
+    }
+    int64_t tcost = 0;
+    const int st = lgreco_solve(h, errors, cost.data(), L, P, e_max, n_bins, choice, &tcost, total_error, stream);
+    if (st != LGRECO_OK) return st;
+    if (total_cost) *total_cost = tcost;
+    if (total_size) {
+        int64_t ts = 0;
+        for (int l = 0; l < L; ++l) ts += sizes[(size_t)l * P + choice[l]];
+        *total_size = ts;
+    }
+    return LGRECO_OK;
+}
+
 int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                           const int32_t* choice, int32_t bucket, int64_t* offsets) {
     if (!layers || !cands || !choice || !offsets || L <= 0 || P <= 0 || bucket <= 0) return LGRECO_EINVAL;

@@ -69,3 +69,41 @@ def test_invalid_arguments():
     with pytest.raises(B.LgrecoError):
         h.solve(errors, -sizes, 1.0, 10)
     h.close()
+
+
+def _compare_weighted(h, errors, sizes, weights, e_max, n_bins):
+    from paper_2210_17357_amd import binding as B
+    st, choice, tsize, tcost, terr = h.solve_weighted(errors, sizes, weights, e_max, n_bins)
+    ref_choice, ref_size, ref_cost, ref_err = solver.solve_weighted(errors, sizes, weights, e_max, n_bins)
+    if ref_choice is None:
+        assert st == B.EINFEASIBLE
+        return
+    assert st == B.OK
+    assert np.array_equal(choice, ref_choice)
+    assert tsize == ref_size and tcost == ref_cost and terr == pytest.approx(ref_err, rel=1e-15)
+
+
+def test_weighted_objective_small_tables_and_bucket_priorities():
+    rng = np.random.default_rng(3)
+    h = _handle(64, 8)
+    for trial in range(150):
+        L, P, D = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 40))
+        errors = rng.integers(0, 12, (L, P)).astype(np.float64) * 0.25
+        sizes = rng.integers(0, 5, (L, P)).astype(np.int64)
+        weights = rng.integers(0, 4, L).astype(np.int64)
+        _compare_weighted(h, errors, sizes, weights, float(rng.integers(0, 20)) * 0.5, D)
+    # 62 layers in 8 communication buckets, coefficient = bucket index (appendix of the paper)
+    L, P, D = 62, 7, 1000
+    base = 10.0 ** rng.uniform(-6, -1, (L, 1))
+    errors = base * np.sort(rng.random((L, P)), axis=1)[:, ::-1] * np.logspace(0, -3, P)
+    sizes = (rng.integers(1, 50, (L, 1)) * np.arange(1, P + 1) * 100).astype(np.int64)
+    e_max = solver.e_max_uniform(errors, 2)
+    bucket = 1 + (np.arange(L)[::-1] * 8) // L
+    _compare_weighted(h, errors, sizes, bucket.astype(np.int64), e_max, D)
+    _compare_weighted(h, errors, sizes, np.ones(L, np.int64), e_max, D)
+    from paper_2210_17357_amd import binding as B
+    with pytest.raises(B.LgrecoError):
+        h.solve_weighted(errors, sizes, -np.ones(L, np.int64), e_max, D)
+    with pytest.raises(B.LgrecoError):
+        h.solve_weighted(errors, sizes, np.full(L, 1 << 44, np.int64), e_max, D)     # product overflow
+    h.close()

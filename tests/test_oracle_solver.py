@@ -142,3 +142,67 @@ def test_dominated_candidates_never_lie_on_the_traced_path():
         if full is not None:
             assert list(full) == list(cut), trial
     assert removed > 500
+
+
+def brute_force_weighted(bins, sizes, weights, n_bins):
+    """Among assignments with sum(bin) <= D minimise (sum size*T, sum bin, c_L, ..., c_1)."""
+    n_layers, n_cands = bins.shape
+    best_key, best = None, None
+    for assign in itertools.product(range(n_cands), repeat=n_layers):
+        b = [int(bins[l][c]) for l, c in enumerate(assign)]
+        if any(v < 0 or v > n_bins for v in b) or sum(b) > n_bins:
+            continue
+        key = (sum(int(sizes[l][c]) * int(weights[l]) for l, c in enumerate(assign)), sum(b)) \
+            + tuple(reversed(assign))
+        if best_key is None or key < best_key:
+            best_key, best = key, assign
+    return None if best is None else np.array(best, np.int32)
+
+
+def test_weighted_objective_against_enumeration():
+    """Section "Time optimization": the objective sum size * T(l).  Brute force over all
+    assignments on tiny tables, weights including 0 and repeated values."""
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        n_layers = int(rng.integers(1, 6))
+        n_cands = int(rng.integers(1, 5))
+        n_bins = int(rng.integers(1, 25))
+        errors = rng.integers(0, n_bins + 3, (n_layers, n_cands)).astype(np.float64)
+        sizes = rng.integers(0, 6, (n_layers, n_cands)).astype(np.int64)
+        weights = rng.integers(0, 4, n_layers).astype(np.int64)
+        e_max = float(n_bins)                       # bin = floor(error)
+        bins = solver.discretise(errors, e_max, n_bins)
+        expect = brute_force_weighted(bins, sizes, weights, n_bins)
+        for fast in (False, True):
+            got, tsize, tcost, terr = solver.solve_weighted(errors, sizes, weights, e_max, n_bins, fast=fast)
+            if expect is None:
+                assert got is None
+            else:
+                assert list(got) == list(expect), trial
+                rows = np.arange(n_layers)
+                assert tsize == int(sizes[rows, got].sum())
+                assert tcost == int((sizes[rows, got] * weights).sum())
+
+
+def test_weighted_objective_special_cases():
+    w = W.workload("c0_tiny_quant")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    errors = pipeline.profile(batch.grads, batch.ef, batch.offsets, batch.numels, batch.rows, batch.cols, cands)
+    sizes = pipeline.sizes_table(batch.numels, batch.rows, batch.cols, cands)
+    e_max = solver.e_max_uniform(errors, w.default)
+    plain, psize, _ = solver.solve(errors, sizes, e_max, w.n_bins)
+    L = len(batch.numels)
+    # equal coefficients: the objective is a multiple of the plain one, same assignment
+    for c in (1, 7):
+        got, tsize, tcost, _ = solver.solve_weighted(errors, sizes, np.full(L, c), e_max, w.n_bins)
+        assert list(got) == list(plain) and tsize == psize and tcost == c * psize
+    # appendix "Buckets prioritization": T = index of the bucket the layer travels in.  The
+    # layers with the larger coefficient end up with sizes no larger than before, in total
+    bucket = np.array([1, 1, 2, 2])
+    got, tsize, tcost, terr = solver.solve_weighted(errors, sizes, bucket, e_max, w.n_bins)
+    rows = np.arange(L)
+    assert tcost <= int((sizes[rows, plain] * bucket).sum())       # optimal for ITS objective
+    assert tsize >= psize                                          # and no better in plain bytes
+    assert sizes[rows, got][bucket == 2].sum() <= sizes[rows, plain][bucket == 2].sum()
+    assert terr <= e_max * (1.0 + L / w.n_bins)
