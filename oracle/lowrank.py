@@ -72,3 +72,12 @@ def compress(g: np.ndarray, e, rows: int, cols: int, q0: np.ndarray, r: int, ite
     phat, q = power_step(m, np.asarray(q0)[:, :r], iters)
     new_e = (m - phat @ q.T).astype(np.float32).reshape(-1)
     return phat.astype(np.float32), q.astype(np.float32), new_e
+
+
+def decompress(payload_bytes: np.ndarray, rows: int, cols: int, r: int) -> np.ndarray:
+    """Receiver side: Phat Q^T from the payload (Phat [m x r] then Q [n x r], fp32), product
+    formed in fp64 and rounded once to fp32, flattened row-major."""
+    buf = np.asarray(payload_bytes, np.uint8)
+    phat = buf[:4 * rows * r].view(np.float32).reshape(rows, r).astype(np.float64)
+    q = buf[4 * rows * r:4 * (rows + cols) * r].view(np.float32).reshape(cols, r).astype(np.float64)
+    return (phat @ q.T).astype(np.float32).reshape(-1)

@@ -71,6 +71,22 @@ def compress_layer(grads, ef, offset, numel, rows, cols, cand, layer_index, buck
     return payload, new_e, {"phat": phat, "q": q}
 
 
+def decompress_layer(payload, numel, rows, cols, cand, bucket=128, out=None):
+    """Receiver side of the codec (the step after compression in the paper's pipeline: every
+    worker turns the payloads it received back into dense gradients and sums them).  Returns the
+    dense fp32 image of one layer's payload, or fl32(out + image) when `out` is given."""
+    fam, par = cand
+    if fam == QUANT:
+        img = quant.unpack(np.asarray(payload, np.uint8), int(numel), int(par), bucket)
+    elif fam == TOPK:
+        img = topk.decompress(payload, int(numel), topk.k_of(int(numel), float(par)))
+    else:
+        img = lowrank.decompress(payload, int(rows), int(cols), int(par))
+    if out is None:
+        return img
+    return (np.asarray(out, np.float32) + img).astype(np.float32)
+
+
 def run(grads, ef, offsets, numels, rows, cols, cands, default, n_bins, **kw):
     """profile -> budget -> solve.  Returns dict with errors, sizes, e_max, choice, totals."""
     errors = profile(grads, ef, offsets, numels, rows, cols, cands, **kw)

@@ -72,3 +72,14 @@ def compress(g: np.ndarray, e, density: float):
 
 def payload(values: np.ndarray, indices: np.ndarray) -> np.ndarray:
     return np.concatenate([values.astype(F32).view(np.uint8), indices.astype(np.uint32).view(np.uint8)])
+
+
+def decompress(payload_bytes: np.ndarray, n: int, k: int) -> np.ndarray:
+    """Receiver side: the dense image of a Top-K payload (values[k] then indices[k]):
+    zero everywhere except the kept positions."""
+    buf = np.asarray(payload_bytes, np.uint8)
+    values = buf[:4 * k].view(F32)
+    indices = buf[4 * k:8 * k].view(np.uint32)
+    out = np.zeros(n, F32)
+    out[indices] = values
+    return out
