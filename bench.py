@@ -234,6 +234,21 @@ def main():
                    "layers_lowrank": int((fam == W.LOWRANK).sum())},
     }
 
+    # receiver side (not part of the step): the last step's payloads back to a dense buffer
+    out_buf = torch.empty_like(g)
+    offsets = B.payload_layout(layers, ctab, choice, w.bucket)
+    h.set_timing(0)
+    for _ in range(2):
+        h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=True)
+    torch.cuda.synchronize()
+    dec_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    out["decompress"] = {"ms": round(dec_ms, 4), "GBps_dense_output": round(4.0 * N / dec_ms / 1e6, 1),
+                         "mode": "accumulate", "payload_bytes": int(last["tsize"])}
+
     if not args.no_cpu_baseline:
         # bounded sample: leading tensors of the workload up to ~cpu-sample-elems elements,
         # skipping any single tensor larger than the bound

@@ -169,6 +169,23 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                     const int32_t* choice, float* d_q, uint8_t* d_payload, const int64_t* offsets,
                     void* stream);
 
+/* Receiver side of the codec: turn the payloads written by lgreco_compress (same layer table,
+ * candidate list, choice and offsets) back into dense gradients, the step that follows the
+ * exchange of compressed gradients in the paper's pipeline (section "Implementation": the
+ * communication engine applies the chosen per-layer parameters on every worker).
+ *   d_payload   device buffer holding every layer's payload at offsets[l]
+ *   d_out       fp32 device buffer with the layout of the gradient buffer; layer l's region
+ *               receives the image of its payload: fma(code, unit, min) per element (QUANT),
+ *               the kept values at their indices and zero elsewhere (TOPK), Phat Q^T (LOWRANK)
+ *   accumulate  0: the image replaces the region; 1: it is added to what the region holds
+ *               (fp32, one rounding per element), as when summing the workers' gradients
+ * Elements of d_out outside the layers are not touched.  A Top-K index at or beyond the
+ * layer's size (a corrupt payload) is skipped. */
+int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_t* offsets,
+                      const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
+                      int32_t P, const int32_t* choice, float* d_out, int32_t accumulate,
+                      void* stream);
+
 /* Timing of the kernels launched by the last profile / solve / compress call on this handle.
  * lgreco_set_timing(h, level) makes every call bracket kernels with HIP events on the call's
  * stream: level 1 the main kernels only (the streaming passes, the contractions, the DP), level 2

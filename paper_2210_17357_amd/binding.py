@@ -19,7 +19,7 @@ OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 QUANT, TOPK, LOWRANK = 0, 1, 2
 
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_emax",
-           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_set_timing",
+           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_set_timing",
            "lgreco_get_timing", "lgreco_strerror", "lgreco_last_hip_error")
 
 
@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
                                             C.POINTER(i64), C.POINTER(dbl), vp]
         l.lgreco_payload_layout.argtypes = [vp, i32, vp, i32, vp, i32, vp]
         l.lgreco_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
+        l.lgreco_decompress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, i32, vp]
         l.lgreco_set_timing.argtypes = [vp, i32]
         l.lgreco_get_timing.argtypes = [vp, vp, vp, i32]
         l.lgreco_strerror.argtypes = [C.c_int]
@@ -214,6 +215,15 @@ class Handle:
         st = lib().lgreco_compress(self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), len(layers),
                                    C.addressof(cands), len(cands), _np(choice), _dptr(d_q),
                                    _dptr(d_payload), _np(offsets), _stream())
+        self._check(st)
+
+    def decompress(self, d_payload, offsets: np.ndarray, layers, cands, choice: np.ndarray, d_out,
+                   accumulate: bool = False):
+        choice = np.ascontiguousarray(choice, np.int32)
+        offsets = np.ascontiguousarray(offsets, np.int64)
+        st = lib().lgreco_decompress(self._h, _dptr(d_payload), _np(offsets), C.addressof(layers), len(layers),
+                                     C.addressof(cands), len(cands), _np(choice), _dptr(d_out),
+                                     int(bool(accumulate)), _stream())
         self._check(st)
 
     def set_timing(self, level):

@@ -660,4 +660,38 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     return LGRECO_OK;
 }
 
+int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_t* offsets,
+                      const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                      const int32_t* choice, float* d_out, int32_t accumulate, void* stream) {
+    if (!h || !d_payload || !offsets || !layers || !cands || !choice || !d_out || L <= 0 || P <= 0)
+        return LGRECO_EINVAL;
+    if ((uintptr_t)d_out % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    begin_call(h, s);
+    int st = prepare_layers(h, layers, L);
+    if (st != LGRECO_OK) return st;
+    bool any[3] = {false, false, false};
+    for (int l = 0; l < L; ++l) {
+        if (choice[l] < 0 || choice[l] >= P) return LGRECO_EINVAL;
+        const lgreco_cand_t& c = cands[choice[l]];
+        st = check_cand(c, &layers[l], h->cfg.r_max);
+        if (st != LGRECO_OK) return st;
+        if (offsets[l] < 0 || offsets[l] % 16) return LGRECO_EINVAL;
+        DevLayer& d = h->hl[l];
+        d.family = c.family;
+        d.payload = offsets[l];
+        d.iparam = (c.family == LGRECO_TOPK) ? (int32_t)topk_k(layers[l].numel, c.param) : (int32_t)c.param;
+        any[c.family] = true;
+    }
+    st = upload_layers(h, s, true);
+    if (st != LGRECO_OK) return st;
+    HIPCHK(launch_decode(d_payload, h->d_layers, h->d_tiles, (int)h->ht.size(), d_out, accumulate != 0,
+                         any[LGRECO_QUANT], any[LGRECO_TOPK], &h->tm, s));
+    if (any[LGRECO_LOWRANK])
+        HIPCHK(lowrank_decompress(&h->lowrank, h->hl.data(), L, h->cfg.r_max, d_payload, d_out, accumulate != 0,
+                                  &h->tm, s));
+    HIPCHK(hipStreamSynchronize(s));
+    return LGRECO_OK;
+}
+
 }  // extern "C"

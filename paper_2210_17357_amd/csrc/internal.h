@@ -135,5 +135,12 @@ hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, co
 hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers,
                             const DevLayer* h_layers, int L, float* q, int r_max, uint8_t* payload, Timing* tm,
                             hipStream_t s);
+// receiver side: out (+)= Phat Q^T from the payload
+hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L, int r_max, const uint8_t* payload,
+                              float* out, bool accumulate, Timing* tm, hipStream_t s);
+
+// ---- decode.hip: receiver side of quantization and Top-K
+hipError_t launch_decode(const uint8_t* payload, const DevLayer* layers, const Tile* tiles, int n_tiles,
+                         float* out, bool accumulate, bool any_quant, bool any_topk, Timing* tm, hipStream_t s);
 
 }  // namespace lgreco

@@ -85,6 +85,7 @@ struct LrParams {
     int32_t nrank;
     int32_t rank[LGRECO_MAX_CANDS];
     int32_t col[LGRECO_MAX_CANDS];
+    int32_t accumulate;      // decode: add the image to the output instead of replacing it
 };
 
 // 4 consecutive elements of x = g + e starting at idx of a row that has `left` elements left.
@@ -516,6 +517,9 @@ __global__ __launch_bounds__(64) void lr_errors_kernel(LrParams p) {
 }
 
 // ------------------------------------------------------------------ e' = X - Phat Q^T
+// DECODE (receiver side): the factors come from the payload (row stride = rank) and the product
+// is written, or added, to the output buffer instead of being subtracted from x.
+template <bool DECODE>
 __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
     __shared__ float Ps[64][kLrCols + 1];
     __shared__ float Qs[kLrCols][kLrCols + 1];
@@ -524,10 +528,13 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
     const LrLayer L = p.layers[tile.layer];
     const int m = L.rows, n = L.cols, r = L.rank;
     const int kmax = (r + 1) & ~1;
-    const float* __restrict__ g = p.g + L.offset;
+    const float* __restrict__ g = DECODE ? (p.accumulate ? p.e_out + L.offset : nullptr) : p.g + L.offset;
+    const float* __restrict__ ein = DECODE ? nullptr : p.e;
     float* __restrict__ e = p.e_out + L.offset;
-    const float* __restrict__ P = p.P + L.p_off;
-    const float* __restrict__ Q = p.Q + L.qs_off;
+    const float* __restrict__ P =
+        DECODE ? reinterpret_cast<const float*>(p.payload + L.payload) : p.P + L.p_off;
+    const float* __restrict__ Q = DECODE ? P + (int64_t)m * r : p.Q + L.qs_off;
+    const int pstride = DECODE ? r : kLrCols;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool vec = L.vec_ok != 0;
     // the 4 wavefronts split a 64 x 64 output tile into 32 x 32 quadrants
@@ -536,7 +543,7 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
     const int row0 = tile.a0, cbeg = tile.split, cend = min(n, cbeg + kLrEfSpan);
     for (int f = tid; f < 64 * kLrCols; f += 256) {
         const int rr = f >> 6, c = f & 63;
-        Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * kLrCols + c] : 0.0f;
+        Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * pstride + c] : 0.0f;
     }
     for (int c0 = cbeg; c0 < cend; c0 += kLrCols) {
         // this tile's inputs are requested first, so their latency overlaps the staging of Q
@@ -546,12 +553,13 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
             const int f = tid + 256 * q;
             const int row = row0 + (f >> 4), colx = c0 + (f & 15) * 4;
             x[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < m && colx < n) x[q] = load_x4(g, e, (int64_t)row * n + colx, n - colx, vec);
+            if (g && row < m && colx < n)
+                x[q] = load_x4(g, ein ? ein + L.offset : nullptr, (int64_t)row * n + colx, n - colx, vec);
         }
         __syncthreads();
         for (int f = tid; f < kLrCols * kLrCols; f += 256) {
             const int cc = f >> 6, k = f & 63;
-            Qs[cc][k] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * kLrCols + k] : 0.0f;
+            Qs[cc][k] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * pstride + k] : 0.0f;
         }
         __syncthreads();
         f32x16 acc = {0};
@@ -571,7 +579,8 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
                 const int64_t idx = (int64_t)row * n + colx;
                 const int left = n - colx;
                 const float4 mh = *reinterpret_cast<const float4*>(&Ms[rr][c4]);
-                const float4 o = make_float4(x[q].x - mh.x, x[q].y - mh.y, x[q].z - mh.z, x[q].w - mh.w);
+                const float4 o = DECODE ? make_float4(x[q].x + mh.x, x[q].y + mh.y, x[q].z + mh.z, x[q].w + mh.w)
+                                        : make_float4(x[q].x - mh.x, x[q].y - mh.y, x[q].z - mh.z, x[q].w - mh.w);
                 if (vec && left >= 4) {
                     *reinterpret_cast<float4*>(e + idx) = o;
                 } else {
@@ -591,6 +600,11 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
         hipError_t _e = (expr);            \
         if (_e != hipSuccess) return _e;   \
     } while (0)
+
+// Work tables and scratch are kept per kind of call (profile, compress, decompress): the three
+// alternate in a training loop and each repeats its own layer table, so nothing is rebuilt.
+constexpr int kLrSlots = 3;
+enum { kLrSlotProfile = 0, kLrSlotCompress = 1, kLrSlotDecode = 2 };
 
 struct LrHost {
     std::vector<LrLayer> layers;
@@ -626,33 +640,36 @@ hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_
     t->max_elems = max_elems;
     t->max_layers = max_layers;
     t->r_max = r_max;
-    t->host = new LrHost();
+    t->host = new LrHost[kLrSlots]();
     return hipSuccess;
 }
 
 void lowrank_scratch_destroy(LowrankScratch* t) {
-    LrHost* H = (LrHost*)t->host;
-    if (H) {
-        (void)hipFree(H->d_layers);
-        (void)hipFree(H->d_tiles);
-        (void)hipFree(H->P);
-        (void)hipFree(H->Q);
-        (void)hipFree(H->part);
-        (void)hipFree(H->ppart);
-        (void)hipFree(H->gram);
-        (void)hipFree(H->T);
-        (void)hipFree(H->xn);
-        (void)hipFree(H->qn);
-        delete H;
+    LrHost* all = (LrHost*)t->host;
+    if (all) {
+        for (int i = 0; i < kLrSlots; ++i) {
+            LrHost* H = &all[i];
+            (void)hipFree(H->d_layers);
+            (void)hipFree(H->d_tiles);
+            (void)hipFree(H->P);
+            (void)hipFree(H->Q);
+            (void)hipFree(H->part);
+            (void)hipFree(H->ppart);
+            (void)hipFree(H->gram);
+            (void)hipFree(H->T);
+            (void)hipFree(H->xn);
+            (void)hipFree(H->qn);
+        }
+        delete[] all;
     }
     *t = LowrankScratch{};
 }
 
 // Build the work tables for the layers with rank[l] > 0 and upload them.  Scratch buffers grow on
 // demand (allocation happens only when a larger layer table arrives).
-static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const int* rank, int r_max,
-                             hipStream_t s) {
-    LrHost* H = (LrHost*)t->host;
+static hipError_t lr_prepare(LowrankScratch* t, int slot, const DevLayer* hl, int L, const int* rank, int r_max,
+                             bool tables_only, hipStream_t s) {
+    LrHost* H = &((LrHost*)t->host)[slot];
     std::vector<int64_t> sig;
     sig.reserve((size_t)L * 5 + 1);
     sig.push_back(r_max);
@@ -733,13 +750,15 @@ static hipError_t lr_prepare(LowrankScratch* t, const DevLayer* hl, int L, const
                       H->gram_tiles.size() + H->q_chunks.size();
     LR_CHECK(grow((void**)&H->d_layers, &H->cap_layers, sizeof(LrLayer) * std::max<size_t>(nl, 1)));
     LR_CHECK(grow((void**)&H->d_tiles, &H->cap_tiles, sizeof(LrTile) * std::max<size_t>(nt, 1)));
+    if (tables_only) { p_off = q_off = part_off = ppart_off = 0; }
     LR_CHECK(grow((void**)&H->P, &H->cap_p, sizeof(float) * std::max<int64_t>(p_off, 1)));
     LR_CHECK(grow((void**)&H->Q, &H->cap_q, sizeof(float) * std::max<int64_t>(q_off, 1)));
     LR_CHECK(grow((void**)&H->part, &H->cap_part, sizeof(float) * std::max<int64_t>(part_off, 1)));
     LR_CHECK(grow((void**)&H->ppart, &H->cap_ppart, sizeof(float) * std::max<int64_t>(ppart_off, 1)));
     LR_CHECK(grow((void**)&H->gram, &H->cap_gram,
-                  sizeof(double) * kLrCols * kLrCols * std::max<size_t>(H->gram_tiles.size(), 1)));
-    LR_CHECK(grow((void**)&H->T, &H->cap_T, sizeof(double) * kLrCols * kLrCols * std::max<size_t>(nl, 1)));
+                  sizeof(double) * kLrCols * kLrCols * (tables_only ? 1 : std::max<size_t>(H->gram_tiles.size(), 1))));
+    LR_CHECK(grow((void**)&H->T, &H->cap_T,
+                  sizeof(double) * kLrCols * kLrCols * (tables_only ? 1 : std::max<size_t>(nl, 1))));
     LR_CHECK(grow((void**)&H->xn, &H->cap_xn, sizeof(double) * std::max<size_t>(H->p_tiles.size(), 1)));
     LR_CHECK(grow((void**)&H->qn, &H->cap_qn, sizeof(double) * kLrCols * std::max<size_t>(H->q_chunks.size(), 1)));
     if (nl) {
@@ -811,11 +830,11 @@ hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, co
                            const DevLayer* h_layers, int L, const float* q0, int r_max, const int* rank,
                            const int* col, int nlr, double* d_errors, int stride, Timing* tm, hipStream_t s) {
     (void)d_layers;
-    LrHost* H = (LrHost*)t->host;
+    LrHost* H = &((LrHost*)t->host)[kLrSlotProfile];
     std::vector<int> ranks(L, kLrCols);
     std::vector<DevLayer> hl(h_layers, h_layers + L);
     for (auto& d : hl) d.payload = 0;                 // not part of the profile's signature
-    LR_CHECK(lr_prepare(t, hl.data(), L, ranks.data(), r_max, s));
+    LR_CHECK(lr_prepare(t, kLrSlotProfile, hl.data(), L, ranks.data(), r_max, false, s));
     if (H->layers.empty()) return hipSuccess;
     LrParams p{};
     lr_fill_params(H, &p);
@@ -837,11 +856,11 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
                             const DevLayer* h_layers, int L, float* q, int r_max, uint8_t* payload, Timing* tm,
                             hipStream_t s) {
     (void)d_layers;
-    LrHost* H = (LrHost*)t->host;
+    LrHost* H = &((LrHost*)t->host)[kLrSlotCompress];
     std::vector<int> ranks(L, 0);
     for (int l = 0; l < L; ++l)
         if (h_layers[l].family == LGRECO_LOWRANK) ranks[l] = h_layers[l].iparam;
-    LR_CHECK(lr_prepare(t, h_layers, L, ranks.data(), r_max, s));
+    LR_CHECK(lr_prepare(t, kLrSlotCompress, h_layers, L, ranks.data(), r_max, false, s));
     if (H->layers.empty()) return hipSuccess;
     LrParams p{};
     lr_fill_params(H, &p);
@@ -854,7 +873,26 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     p.payload = payload;
     LR_CHECK(lr_factorize(H, p, tm, s));
     Section sec(tm, "lowrank_ef", true);
-    hipLaunchKernelGGL(lr_ef_kernel, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(lr_ef_kernel<false>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L, int r_max, const uint8_t* payload,
+                              float* out, bool accumulate, Timing* tm, hipStream_t s) {
+    LrHost* H = &((LrHost*)t->host)[kLrSlotDecode];
+    std::vector<int> ranks(L, 0);
+    for (int l = 0; l < L; ++l)
+        if (h_layers[l].family == LGRECO_LOWRANK) ranks[l] = h_layers[l].iparam;
+    LR_CHECK(lr_prepare(t, kLrSlotDecode, h_layers, L, ranks.data(), r_max, true, s));
+    if (H->layers.empty()) return hipSuccess;
+    LrParams p{};
+    lr_fill_params(H, &p);
+    p.e_out = out;
+    p.payload = const_cast<uint8_t*>(payload);
+    p.accumulate = accumulate ? 1 : 0;
+    p.r_max = r_max;
+    Section sec(tm, "lowrank_decode", true);
+    hipLaunchKernelGGL(lr_ef_kernel<true>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
