@@ -108,8 +108,14 @@ __device__ __forceinline__ float4 load_x4(const float* __restrict__ g, const flo
 }
 
 // ------------------------------------------------------------------ P = X Q0 (and ||X||^2)
+// One workgroup: 128 rows x 64 columns of P over one column range of X; wavefront w owns rows
+// 32w .. 32w+31.  The A operand never passes through LDS: lane l keeps, for row l % 32, the 16
+// consecutive elements X[row][k0 + 16 (l / 32) .. + 15] of the current 32-column chunk in
+// registers (four 128-bit loads; lanes l and l + 32 together read one 128-byte line of the row),
+// and MFMA step s contracts the column pair (k0 + s, k0 + 16 + s).  Only the 32 x 64 chunk of Q0,
+// shared by the four wavefronts, is staged in LDS (double buffered).
+template <bool HAS_E>
 __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
-    __shared__ float Xs[2][kLrBM][kLrBK + 1];
     __shared__ float Qs[2][kLrBK][kLrCols];
     __shared__ double s_red[4];
     const LrTile tile = p.p_tiles[blockIdx.x];
@@ -117,91 +123,109 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
     const int m = L.rows, n = L.cols, row0 = tile.a0;
     const int kbeg = tile.split * L.pksplit, kend = min(n, kbeg + L.pksplit);
     const float* __restrict__ g = p.g + L.offset;
-    const float* __restrict__ e = p.e ? p.e + L.offset : nullptr;
+    const float* __restrict__ e = HAS_E ? p.e + L.offset : nullptr;
     const float* __restrict__ q = p.q0 + L.q_off;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool vec = L.vec_ok != 0;
-    const bool qvec = (p.r_max % 4 == 0) && (L.q_off % 4 == 0);
+    const bool qvec = (p.r_max == kLrCols) && (L.q_off % 4 == 0);
+    const int half = lane >> 5, bj = lane & 31;
+    const int row = row0 + 32 * wave + bj;               // this lane's row of X
+    const bool row_ok = row < m;
+    const float* __restrict__ grow = g + (int64_t)row * n;
+    const float* __restrict__ erow = HAS_E ? e + (int64_t)row * n : nullptr;
 
-    float4 xr[4], qr[2];
-    float xsq = 0.0f;
+    float4 xg[4], xe[HAS_E ? 4 : 1], qr[2];
+    bool add_e = false;
+    // issue the loads of one chunk (their values are first used after the MFMAs of the chunk
+    // that is being multiplied)
     auto fetch = [&](int k0) {
+        const int kx = k0 + 16 * half;
+        add_e = false;
+        if (vec && row_ok && k0 + kLrBK <= kend) {           // uniform except for the row test
+            add_e = HAS_E;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int f = tid + 256 * s;
-            const int r = f >> 3, c = (f & 7) * 4;
-            const int row = row0 + r, colk = k0 + c;
-            xr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < m && colk < kend) xr[s] = load_x4(g, e, (int64_t)row * n + colk, kend - colk, vec);
-            xsq = __builtin_fmaf(xr[s].x, xr[s].x, xsq);
-            xsq = __builtin_fmaf(xr[s].y, xr[s].y, xsq);
-            xsq = __builtin_fmaf(xr[s].z, xr[s].z, xsq);
-            xsq = __builtin_fmaf(xr[s].w, xr[s].w, xsq);
+            for (int s = 0; s < 4; ++s) {
+                xg[s] = *reinterpret_cast<const float4*>(grow + kx + 4 * s);
+                if (HAS_E) xe[s] = *reinterpret_cast<const float4*>(erow + kx + 4 * s);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                xg[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+                const int kk = kx + 4 * s;
+                if (row_ok && kk < kend) xg[s] = load_x4(grow, erow, kk, kend - kk, vec);
+            }
         }
+        if (qvec && k0 + kLrBK <= kend) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int f = tid + 256 * s;
-            const int kr = f >> 4, c = (f & 15) * 4;
-            const int k = k0 + kr;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < kend) {
-                const float* src = q + (int64_t)k * p.r_max + c;
-                if (qvec && c + 3 < p.r_max) {
-                    v = *reinterpret_cast<const float4*>(src);
-                } else {
+            for (int s = 0; s < 2; ++s) {
+                const int f = tid + 256 * s;
+                qr[s] = *reinterpret_cast<const float4*>(q + (int64_t)(k0 + (f >> 4)) * kLrCols + (f & 15) * 4);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int f = tid + 256 * s;
+                const int k = k0 + (f >> 4), c = (f & 15) * 4;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < kend) {
+                    const float* src = q + (int64_t)k * p.r_max + c;
                     if (c < p.r_max) v.x = src[0];
                     if (c + 1 < p.r_max) v.y = src[1];
                     if (c + 2 < p.r_max) v.z = src[2];
                     if (c + 3 < p.r_max) v.w = src[3];
                 }
+                qr[s] = v;
             }
-            qr[s] = v;
         }
     };
-    auto stash = [&](int buf) {
+    float xsq = 0.0f;
+    float cur[16];
+    // take the fetched chunk into use: x = g + e, ||x||^2, Q0 rows to LDS
+    auto commit = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int f = tid + 256 * s;
-            const int r = f >> 3, c = (f & 7) * 4;
-            Xs[buf][r][c] = xr[s].x; Xs[buf][r][c + 1] = xr[s].y;
-            Xs[buf][r][c + 2] = xr[s].z; Xs[buf][r][c + 3] = xr[s].w;
+            float4 v = xg[s];
+            if (HAS_E && add_e) { v.x += xe[s].x; v.y += xe[s].y; v.z += xe[s].z; v.w += xe[s].w; }
+            cur[4 * s] = v.x; cur[4 * s + 1] = v.y; cur[4 * s + 2] = v.z; cur[4 * s + 3] = v.w;
+            xsq = __builtin_fmaf(v.x, v.x, xsq);
+            xsq = __builtin_fmaf(v.y, v.y, xsq);
+            xsq = __builtin_fmaf(v.z, v.z, xsq);
+            xsq = __builtin_fmaf(v.w, v.w, xsq);
         }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int f = tid + 256 * s;
-            const int kr = f >> 4, c = (f & 15) * 4;
-            *reinterpret_cast<float4*>(&Qs[buf][kr][c]) = qr[s];
+            *reinterpret_cast<float4*>(&Qs[buf][f >> 4][(f & 15) * 4]) = qr[s];
         }
     };
 
     f32x16 acc0 = {0}, acc1 = {0};
     const int nchunks = (kend - kbeg + kLrBK - 1) / kLrBK;
     fetch(kbeg);
-    stash(0);
+    commit(0);
     __syncthreads();
-    const int ar = 32 * wave + (lane & 31), ak = lane >> 5, bj = lane & 31;
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         if (c + 1 < nchunks) fetch(kbeg + (c + 1) * kLrBK);
 #pragma unroll
-        for (int kk = 0; kk < kLrBK; kk += 2) {
-            const float a = Xs[buf][ar][kk + ak];
-            const float b0 = Qs[buf][kk + ak][bj];
-            const float b1 = Qs[buf][kk + ak][32 + bj];
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        for (int s = 0; s < 16; ++s) {
+            const float b0 = Qs[buf][16 * half + s][bj];
+            const float b1 = Qs[buf][16 * half + s][32 + bj];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur[s], b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur[s], b1, acc1, 0, 0, 0);
         }
-        if (c + 1 < nchunks) stash(buf ^ 1);
+        if (c + 1 < nchunks) commit(buf ^ 1);
         __syncthreads();
     }
     float* __restrict__ P = L.psplits > 1 ? p.ppart + L.ppart_off + (int64_t)tile.split * m * kLrCols
                                           : p.P + L.p_off;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const int row = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < m) {
-            P[(int64_t)row * kLrCols + bj] = acc0[v];
-            P[(int64_t)row * kLrCols + 32 + bj] = acc1[v];
+        const int orow = row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (orow < m) {
+            P[(int64_t)orow * kLrCols + bj] = acc0[v];
+            P[(int64_t)orow * kLrCols + 32 + bj] = acc1[v];
         }
     }
     const double s = wave_sum((double)xsq);
@@ -371,6 +395,7 @@ __global__ __launch_bounds__(256) void lr_apply_kernel(LrParams p) {
 }
 
 // ------------------------------------------------------------------ Q partials = X^T Phat
+template <bool HAS_E>
 __global__ __launch_bounds__(256) void lr_gemm2_kernel(LrParams p) {
     __shared__ float Xs[2][kLrBK][kLrBM];
     __shared__ float Ps[2][kLrBK][kLrCols];
@@ -379,13 +404,33 @@ __global__ __launch_bounds__(256) void lr_gemm2_kernel(LrParams p) {
     const int m = L.rows, n = L.cols, col0 = tile.a0;
     const int kbeg = tile.split * L.ksplit, kend = min(m, kbeg + L.ksplit);
     const float* __restrict__ g = p.g + L.offset;
-    const float* __restrict__ e = p.e ? p.e + L.offset : nullptr;
+    const float* __restrict__ e = HAS_E ? p.e + L.offset : nullptr;
     const float* __restrict__ P = p.P + L.p_off;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool vec = L.vec_ok != 0;
 
     float4 xr[4], pr[2];
+    const bool cols_full = col0 + kLrBM <= n;
+    float4 er[HAS_E ? 4 : 1];
+    bool add_e = false;
     auto fetch = [&](int k0) {
+        add_e = false;
+        if (vec && cols_full && k0 + kLrBK <= kend) {       // no per-load condition (see lr_gemm1_kernel)
+            add_e = HAS_E;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int f = tid + 256 * s;
+                const int64_t idx = (int64_t)(k0 + (f >> 5)) * n + col0 + (f & 31) * 4;
+                xr[s] = *reinterpret_cast<const float4*>(g + idx);
+                if (HAS_E) er[s] = *reinterpret_cast<const float4*>(e + idx);
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int f = tid + 256 * s;
+                pr[s] = *reinterpret_cast<const float4*>(P + (int64_t)(k0 + (f >> 4)) * kLrCols + (f & 15) * 4);
+            }
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int f = tid + 256 * s;
@@ -404,6 +449,12 @@ __global__ __launch_bounds__(256) void lr_gemm2_kernel(LrParams p) {
         }
     };
     auto stash = [&](int buf) {
+        if (HAS_E && add_e) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                xr[s].x += er[s].x; xr[s].y += er[s].y; xr[s].z += er[s].z; xr[s].w += er[s].w;
+            }
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int f = tid + 256 * s;
@@ -797,7 +848,10 @@ static void lr_fill_params(LrHost* H, LrParams* p) {
 static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStream_t s) {
     {
         Section sec(tm, "lowrank_gemm_p", true);
-        hipLaunchKernelGGL(lr_gemm1_kernel, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
+        if (p.e)
+            hipLaunchKernelGGL(lr_gemm1_kernel<true>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
+        else
+            hipLaunchKernelGGL(lr_gemm1_kernel<false>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
         if (H->ppart_elems > 0) {
             hipLaunchKernelGGL(lr_preduce_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
@@ -815,7 +869,10 @@ static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStre
     }
     {
         Section sec(tm, "lowrank_gemm_q", true);
-        hipLaunchKernelGGL(lr_gemm2_kernel, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
+        if (p.e)
+            hipLaunchKernelGGL(lr_gemm2_kernel<true>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
+        else
+            hipLaunchKernelGGL(lr_gemm2_kernel<false>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
     }
     {
