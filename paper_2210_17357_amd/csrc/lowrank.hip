@@ -28,8 +28,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kLrCols = 64;       // columns computed per layer (r_max <= 64)
 constexpr int kLrBM = 128;        // rows (GEMM1, reconstruction) / columns (GEMM2) per workgroup
 constexpr int kLrBK = 32;         // contraction chunk staged in LDS
-constexpr int kLrGramRows = 128;  // rows staged in LDS at a time by the Gram kernel
-constexpr int kLrGramSpan = 1024; // rows per Gram partial (one workgroup)
+constexpr int kLrGramSpan = 512;  // rows per Gram partial (one workgroup)
 constexpr int kLrQChunk = 64;     // Q rows per workgroup in the split-K reduction
 constexpr int kLrPSplit = 512;    // columns contracted per workgroup in P = X Q0
 constexpr int kLrEfSpan = 512;    // columns reconstructed per workgroup
@@ -254,48 +253,70 @@ __global__ __launch_bounds__(256) void lr_preduce_kernel(LrParams p) {
 }
 
 // ------------------------------------------------------------------ partial Gram matrices
+// G = P^T P over a span of rows, accumulated in fp64 on v_mfma_f64_16x16x4f64.  Operand layout of
+// that instruction, lane l of 64:  A (16 x 4): A[i = l % 16][k = l / 16];  B (4 x 16):
+// B[k = l / 16][j = l % 16];  D (16 x 16): register v (0..3) holds D[4 v + l / 16][l % 16].
+// With A = P^T and B = P both operands of a 4-row step are the same four values per lane
+// (P[row0 + l / 16][16 b + l % 16], b = 0..3), so P goes from global memory straight into the
+// matrix pipe.  The four wavefronts take interleaved 16-row groups and add their results in LDS
+// in wavefront order.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
-    __shared__ float Pl[kLrGramRows][kLrCols];
+    __shared__ double Gs[kLrCols][kLrCols];
     const LrTile tile = p.gram_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
     const float* __restrict__ P = p.P + L.p_off;
     const int span_end = min(L.rows, tile.a0 + kLrGramSpan);
-    const int tid = threadIdx.x;
-    const int bi = (tid >> 4) * 4, bj = (tid & 15) * 4;
-    double acc[4][4];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int lr = lane >> 4, lc = lane & 15;
+    f64x4 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-    for (int row0 = tile.a0; row0 < span_end; row0 += kLrGramRows) {
-        const int nrows = min(kLrGramRows, span_end - row0);
-        __syncthreads();
-        for (int f = tid; f < kLrGramRows * kLrCols / 4; f += 256) {
-            const int r = f >> 4, c = (f & 15) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
-            *reinterpret_cast<float4*>(&Pl[r][c]) = v;
+        for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int r0 = tile.a0 + 16 * wave; r0 < span_end; r0 += 64) {
+        float x[4][4];      // [4-row step][column block]
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const int r = r0 + 4 * st + lr;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) x[st][b] = r < span_end ? P[(int64_t)r * kLrCols + 16 * b + lc] : 0.0f;
         }
-        __syncthreads();
-        for (int r = 0; r < nrows; ++r) {
-            const float4 a = *reinterpret_cast<const float4*>(&Pl[r][bi]);
-            const float4 b = *reinterpret_cast<const float4*>(&Pl[r][bj]);
-            const double av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(av[i], bv[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)x[st][i], (double)x[st][j], acc[i][j],
+                                                                     0, 0, 0);
         }
     }
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        double* g = &Gs[16 * i + 4 * v + lr][16 * j + lc];
+                        *g = (w == 0) ? acc[i][j][v] : *g + acc[i][j][v];
+                    }
+        }
+        __syncthreads();
+    }
     double* __restrict__ out = p.gram_part + (size_t)blockIdx.x * kLrCols * kLrCols;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) out[(bi + i) * kLrCols + bj + j] = acc[i][j];
+    for (int f = tid; f < kLrCols * kLrCols; f += 256) out[f] = Gs[f >> 6][f & 63];
 }
 
 // ------------------------------------------------------------------ Gram-Schmidt coefficients
-// One wavefront per layer.  Lane j owns column j of the Gram matrix.
+// One workgroup per layer.  The Gram matrix sits in registers: thread (wavefront w, lane j) holds
+// G[4 m + w][j], m = 0..15.  Elimination step i (Gram-Schmidt on the inner products): the
+// wavefront that owns row i scales it into row i of R and publishes it in LDS; after one barrier
+// every thread subtracts R[i][k] R[i][j] from its rows k > i.  Then T = R^-1 by back substitution
+// (one wavefront, lane j solves column j against R in LDS).
 __device__ __forceinline__ double lane_value(double v, int lane) {      // v of a given lane, as a scalar
     const uint64_t b = __builtin_bit_cast(uint64_t, v);
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
@@ -304,57 +325,53 @@ __device__ __forceinline__ double lane_value(double v, int lane) {      // v of 
 }
 
 __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
-    __shared__ double G[kLrCols][kLrCols + 1];
+    __shared__ double R[kLrCols][kLrCols];
+    __shared__ double diag0[kLrCols];
     const LrLayer L = p.layers[blockIdx.x];
-    // all 256 threads: G = sum of the layer's Gram partials, in partial order
-    {
-        // 16 entries per thread, partials outermost: 16 independent loads in flight per step
-        double acc[16];
+    const int tid = threadIdx.x, w = tid >> 6, j = tid & 63;
+    // G = sum of the layer's Gram partials, in partial order
+    double g[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[q] = 0.0;
-        for (int c = L.gram_begin; c < L.gram_end; ++c) {
-            const double* __restrict__ src = p.gram_part + (size_t)c * kLrCols * kLrCols + threadIdx.x;
+    for (int m = 0; m < 16; ++m) g[m] = 0.0;
+    for (int c = L.gram_begin; c < L.gram_end; ++c) {
+        const double* __restrict__ src = p.gram_part + (size_t)c * kLrCols * kLrCols + w * kLrCols + j;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[q] += src[256 * q];
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int f = threadIdx.x + 256 * q;
-            G[f >> 6][f & 63] = acc[q];
-        }
+        for (int m = 0; m < 16; ++m) g[m] += src[4 * m * kLrCols];
     }
+#pragma unroll
+    for (int m = 0; m < 16; ++m)
+        if (4 * m + w == j) diag0[j] = g[m];      // squared norms before any projection
     __syncthreads();
-    if (threadIdx.x >= 64) return;
-    // One wavefront from here on; lane j keeps column j in registers (every index below is a
-    // compile-time constant after unrolling, rows of other lanes come through readlane).
-    const int j = threadIdx.x;
-    double col[kLrCols];
-#pragma unroll
-    for (int i = 0; i < kLrCols; ++i) col[i] = G[i][j];
-    double diag0 = 0.0;
-#pragma unroll
-    for (int i = 0; i < kLrCols; ++i) diag0 = (i == j) ? col[i] : diag0;
 #pragma unroll
     for (int i = 0; i < kLrCols; ++i) {
-        const double d = lane_value(col[i], i);
-        const double d0 = lane_value(diag0, i);
-        const bool ok = d > 0.0 && d >= 1e-10 * d0;
-        const double rii = ok ? sqrt(d) : 0.0;
-        const double inv = ok ? 1.0 / rii : 0.0;
-        const double rij = (j >= i) ? ((j == i) ? rii : col[i] * inv) : 0.0;   // R[i][j]
-        col[i] = rij;
-        // eliminate: G[k][j] -= R[i][k] R[i][j]; rows k > j hold the unused lower triangle
+        if (w == (i & 3)) {
+            const double gi = g[i >> 2];                     // G[i][j], current
+            const double d = lane_value(gi, i);
+            const double d0 = diag0[i];
+            const bool ok = d > 0.0 && d >= 1e-10 * d0;
+            const double rii = ok ? sqrt(d) : 0.0;
+            const double inv = ok ? 1.0 / rii : 0.0;
+            R[i][j] = (j >= i) ? ((j == i) ? rii : gi * inv) : 0.0;
+        }
+        __syncthreads();
+        const double rj = R[i][j];
 #pragma unroll
-        for (int k = i + 1; k < kLrCols; ++k) col[k] = __builtin_fma(-lane_value(rij, k), rij, col[k]);
+        for (int m = 0; m < 16; ++m)
+            if (4 * m + 3 > i) {                              // some row of this group lies below i
+                const int k = 4 * m + w;
+                if (k > i) g[m] = __builtin_fma(-R[i][k], rj, g[m]);
+            }
     }
-    // T = R^-1 by back substitution, column j; rows of zeroed columns stay zero.  col[i] = R[i][j].
+    __syncthreads();
+    if (w != 0) return;
+    // T = R^-1, column j; columns that were zeroed stay zero
     double t[kLrCols];
 #pragma unroll
     for (int i = kLrCols - 1; i >= 0; --i) {
         double s = (i == j) ? 1.0 : 0.0;
 #pragma unroll
-        for (int k = i + 1; k < kLrCols; ++k) s = __builtin_fma(-lane_value(col[i], k), t[k], s);
-        const double rii = lane_value(col[i], i);
+        for (int k = i + 1; k < kLrCols; ++k) s = __builtin_fma(-R[i][k], t[k], s);
+        const double rii = R[i][i];
         t[i] = (i <= j && rii != 0.0) ? s / rii : 0.0;
     }
     double* __restrict__ T = p.T + (size_t)blockIdx.x * kLrCols * kLrCols;
@@ -363,34 +380,46 @@ __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
 }
 
 // ------------------------------------------------------------------ Phat = P T
+// fp64 MFMA: a wavefront takes 16 rows of P at a time (A[i][k] = P[row0 + i][k], 16 loads per
+// lane, all issued before the first MFMA and before any store, so the update is in place) against
+// T in LDS; T is upper triangular, so column block b needs only k < 16 (b + 1).
 __global__ __launch_bounds__(256) void lr_apply_kernel(LrParams p) {
-    __shared__ float Pl[64][kLrCols];
     __shared__ double Tl[kLrCols][kLrCols];
     const LrTile tile = p.row_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
     float* __restrict__ P = p.P + L.p_off;
     const double* __restrict__ T = p.T + (size_t)tile.layer * kLrCols * kLrCols;
-    const int tid = threadIdx.x, j = tid & 63;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int lr = lane >> 4, lc = lane & 15;
     for (int f = tid; f < kLrCols * kLrCols; f += 256) Tl[f >> 6][f & 63] = T[f];
     float* pay = p.payload ? reinterpret_cast<float*>(p.payload + L.payload) : nullptr;
-    for (int half = 0; half < kLrBM; half += 64) {
-        const int row0 = tile.a0 + half, nrows = min(64, L.rows - row0);
-        if (nrows <= 0) break;
-        __syncthreads();
-        for (int f = tid; f < 64 * kLrCols / 4; f += 256) {
-            const int r = f >> 4, c = (f & 15) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < nrows) v = *reinterpret_cast<const float4*>(P + (int64_t)(row0 + r) * kLrCols + c);
-            *reinterpret_cast<float4*>(&Pl[r][c]) = v;
+    __syncthreads();
+    for (int blk = wave; blk < kLrBM / 16; blk += 4) {
+        const int row0 = tile.a0 + 16 * blk;
+        if (row0 >= L.rows) break;
+        const int arow = row0 + lc;
+        float a[16];
+#pragma unroll
+        for (int s = 0; s < 16; ++s) a[s] = arow < L.rows ? P[(int64_t)arow * kLrCols + 4 * s + lr] : 0.0f;
+        f64x4 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            acc[b] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int s = 0; s < 4 * (b + 1); ++s)
+                acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a[s], Tl[4 * s + lr][16 * b + lc], acc[b], 0, 0, 0);
         }
-        __syncthreads();
-        for (int r = tid >> 6; r < nrows; r += 4) {
-            double s = 0.0;
-            for (int i = 0; i <= j; ++i) s = __builtin_fma((double)Pl[r][i], Tl[i][j], s);
-            const float v = (float)s;
-            P[(int64_t)(row0 + r) * kLrCols + j] = v;
-            if (pay && j < L.rank) pay[(int64_t)(row0 + r) * L.rank + j] = v;
-        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = row0 + 4 * v + lr, col = 16 * b + lc;
+                if (row < L.rows) {
+                    const float val = (float)acc[b][v];
+                    P[(int64_t)row * kLrCols + col] = val;
+                    if (pay && col < L.rank) pay[(int64_t)row * L.rank + col] = val;
+                }
+            }
     }
 }
 
