@@ -333,6 +333,7 @@ __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
     double g[16];
 #pragma unroll
     for (int m = 0; m < 16; ++m) g[m] = 0.0;
+#pragma unroll 4
     for (int c = L.gram_begin; c < L.gram_end; ++c) {
         const double* __restrict__ src = p.gram_part + (size_t)c * kLrCols * kLrCols + w * kLrCols + j;
 #pragma unroll
@@ -384,8 +385,8 @@ __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
 // lane, all issued before the first MFMA and before any store, so the update is in place) against
 // T in LDS; T is upper triangular, so column block b needs only k < 16 (b + 1).
 __global__ __launch_bounds__(256) void lr_apply_kernel(LrParams p) {
-    __shared__ double Tl[kLrCols][kLrCols];
-    const LrTile tile = p.row_tiles[blockIdx.x];
+    __shared__ double Tl[kLrCols][kLrCols + 2];     // padded: the four k rows of a step on different banks
+    const LrTile tile = p.gram_tiles[blockIdx.x];          // one workgroup per span of kLrGramSpan rows
     const LrLayer L = p.layers[tile.layer];
     float* __restrict__ P = p.P + L.p_off;
     const double* __restrict__ T = p.T + (size_t)tile.layer * kLrCols * kLrCols;
@@ -394,7 +395,7 @@ __global__ __launch_bounds__(256) void lr_apply_kernel(LrParams p) {
     for (int f = tid; f < kLrCols * kLrCols; f += 256) Tl[f >> 6][f & 63] = T[f];
     float* pay = p.payload ? reinterpret_cast<float*>(p.payload + L.payload) : nullptr;
     __syncthreads();
-    for (int blk = wave; blk < kLrBM / 16; blk += 4) {
+    for (int blk = wave; blk < kLrGramSpan / 16; blk += 4) {
         const int row0 = tile.a0 + 16 * blk;
         if (row0 >= L.rows) break;
         const int arow = row0 + lc;
@@ -579,13 +580,33 @@ __global__ __launch_bounds__(256) void lr_qreduce_kernel(LrParams p) {
 }
 
 // ------------------------------------------------------------------ errors of every rank
-__global__ __launch_bounds__(64) void lr_errors_kernel(LrParams p) {
+// One workgroup per layer; the four wavefronts split the partial sums (column norms of Q per
+// chunk, ||X||^2 per tile) into contiguous quarters that are added in a fixed order.
+__global__ __launch_bounds__(256) void lr_errors_kernel(LrParams p) {
+    __shared__ double s_q[4][kLrCols];
+    __shared__ double s_x[4];
     const LrLayer L = p.layers[blockIdx.x];
-    const int j = threadIdx.x;
-    double qn = 0.0;
-    for (int c = L.qc_begin; c < L.qc_end; ++c) qn += p.qnorm_part[(size_t)c * kLrCols + j];
-    double xn = 0.0;
-    for (int t = L.rt_begin; t < L.rt_end; ++t) xn += p.xnorm_part[t];      // same in every lane
+    const int j = threadIdx.x & 63, w = threadIdx.x >> 6;
+    {
+        const int n = L.qc_end - L.qc_begin, per = (n + 3) / 4;
+        const int c0 = L.qc_begin + min(n, w * per), c1 = L.qc_begin + min(n, (w + 1) * per);
+        double qn = 0.0;
+#pragma unroll 8
+        for (int c = c0; c < c1; ++c) qn += p.qnorm_part[(size_t)c * kLrCols + j];
+        s_q[w][j] = qn;
+    }
+    {
+        const int n = L.rt_end - L.rt_begin, per = (n + 3) / 4;
+        const int t0 = L.rt_begin + min(n, w * per), t1 = L.rt_begin + min(n, (w + 1) * per);
+        double xn = 0.0;
+        for (int t = t0 + j; t < t1; t += 64) xn += p.xnorm_part[t];
+        xn = wave_sum(xn);
+        if (j == 0) s_x[w] = xn;
+    }
+    __syncthreads();
+    if (w != 0) return;
+    const double qn = ((s_q[0][j] + s_q[1][j]) + s_q[2][j]) + s_q[3][j];
+    const double xn = ((s_x[0] + s_x[1]) + s_x[2]) + s_x[3];
     // inclusive prefix over columns, in column order
     double pre = qn;
     for (int o = 1; o < 64; o <<= 1) {
@@ -893,7 +914,7 @@ static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStre
         LR_CHECK(hipGetLastError());
         hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->gram_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
     }
     {
@@ -934,7 +955,7 @@ hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, co
     for (int c = 0; c < nlr; ++c) { p.rank[c] = rank[c]; p.col[c] = col[c]; }
     LR_CHECK(lr_factorize(H, p, tm, s));
     Section sec(tm, "lowrank_errors");
-    hipLaunchKernelGGL(lr_errors_kernel, dim3((unsigned)H->layers.size()), dim3(64), 0, s, p);
+    hipLaunchKernelGGL(lr_errors_kernel, dim3((unsigned)H->layers.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
