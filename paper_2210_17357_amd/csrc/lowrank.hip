@@ -646,23 +646,76 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
         const int rr = f >> 6, c = f & 63;
         Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * pstride + c] : 0.0f;
     }
+    // Software pipeline over the 64-column tiles of the span: the loads of tile t+1 (x and the
+    // rows of Q) are issued before the MFMAs of tile t and first touched at the top of the next
+    // iteration.  Interior tiles of aligned layers take a path without per-load conditions.
+    float4 xn[4], en[4], qn[4];
+    float qs[16];
+    bool fast_x = false, fast_q = false, add_e = false;
+    const float* __restrict__ ebase = ein ? ein + L.offset : nullptr;
+    auto fetch = [&](int c0) {
+        fast_x = vec && g != nullptr && row0 + 64 <= m && c0 + kLrCols <= n;
+        add_e = fast_x && ebase != nullptr;
+        if (fast_x) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = tid + 256 * q;
+                const int64_t idx = (int64_t)(row0 + (f >> 4)) * n + c0 + (f & 15) * 4;
+                xn[q] = *reinterpret_cast<const float4*>(g + idx);
+                if (ebase) en[q] = *reinterpret_cast<const float4*>(ebase + idx);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = tid + 256 * q;
+                const int row = row0 + (f >> 4), colx = c0 + (f & 15) * 4;
+                xn[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g && row < m && colx < n) xn[q] = load_x4(g, ebase, (int64_t)row * n + colx, n - colx, vec);
+            }
+        }
+        fast_q = !DECODE && c0 + kLrCols <= n;        // scratch Q: 64 columns per row, 16-byte aligned
+        if (fast_q) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = tid + 256 * q;
+                qn[q] = *reinterpret_cast<const float4*>(Q + (int64_t)(c0 + (f >> 4)) * kLrCols + (f & 15) * 4);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int f = tid + 256 * q;
+                const int cc = f >> 6, k = f & 63;
+                qs[q] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * pstride + k] : 0.0f;
+            }
+        }
+    };
+    fetch(cbeg);
     for (int c0 = cbeg; c0 < cend; c0 += kLrCols) {
-        // this tile's inputs are requested first, so their latency overlaps the staging of Q
         float4 x[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int f = tid + 256 * q;
-            const int row = row0 + (f >> 4), colx = c0 + (f & 15) * 4;
-            x[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (g && row < m && colx < n)
-                x[q] = load_x4(g, ein ? ein + L.offset : nullptr, (int64_t)row * n + colx, n - colx, vec);
+            x[q] = xn[q];
+            if (add_e) { x[q].x += en[q].x; x[q].y += en[q].y; x[q].z += en[q].z; x[q].w += en[q].w; }
+        }
+        if (fast_q) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = tid + 256 * q;
+                const int cc = f >> 4, k = (f & 15) * 4;
+                Qs[cc][k] = k < r ? qn[q].x : 0.0f;
+                Qs[cc][k + 1] = k + 1 < r ? qn[q].y : 0.0f;
+                Qs[cc][k + 2] = k + 2 < r ? qn[q].z : 0.0f;
+                Qs[cc][k + 3] = k + 3 < r ? qn[q].w : 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int f = tid + 256 * q;
+                Qs[f >> 6][f & 63] = qs[q];
+            }
         }
         __syncthreads();
-        for (int f = tid; f < kLrCols * kLrCols; f += 256) {
-            const int cc = f >> 6, k = f & 63;
-            Qs[cc][k] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * pstride + k] : 0.0f;
-        }
-        __syncthreads();
+        if (c0 + kLrCols < cend) fetch(c0 + kLrCols);
         f32x16 acc = {0};
         for (int kk = 0; kk < kmax; kk += 2)
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[ar][kk + ak], Qs[bj][kk + ak], acc, 0, 0, 0);
