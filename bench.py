@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
+    ap.add_argument("--power-iters", type=int, default=1,
+                    help="power-iteration steps of the low-rank family (the configs use 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
@@ -56,7 +58,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(w, sample_tensors):
+def cpu_baseline(w, sample_tensors, power_iters=1):
     """Oracle (as it stands) on a bounded sample: same three phases, wall clock."""
     from oracle import pipeline, solver
     from paper_2210_17357_amd import workloads as W
@@ -65,7 +67,7 @@ def cpu_baseline(w, sample_tensors):
     cands = list(w.candidates)
     kw = dict(bucket=w.bucket, stochastic=w.stochastic, seed=w.seed)
     if b.q0 is not None:
-        kw.update(q0=b.q0, q_offsets=b.q_offsets, r_max=w.r_max)
+        kw.update(q0=b.q0, q_offsets=b.q_offsets, r_max=w.r_max, power_iters=power_iters)
     t0 = time.perf_counter()
     errors = pipeline.profile(b.grads, b.ef, b.offsets, b.numels, b.rows, b.cols, cands, **kw)
     sizes = pipeline.sizes_table(b.numels, b.rows, b.cols, cands, w.bucket)
@@ -78,7 +80,8 @@ def cpu_baseline(w, sample_tensors):
         if b.q0 is not None:
             q0l = b.q0[int(b.q_offsets[l]):int(b.q_offsets[l]) + int(b.cols[l]) * w.r_max].reshape(-1, w.r_max)
         pipeline.compress_layer(b.grads, b.ef, int(b.offsets[l]), int(b.numels[l]), int(b.rows[l]),
-                                int(b.cols[l]), cands[choice[l]], l, w.bucket, w.stochastic, w.seed, q0l)
+                                int(b.cols[l]), cands[choice[l]], l, w.bucket, w.stochastic, w.seed, q0l,
+                                power_iters)
     t3 = time.perf_counter()
     return b, errors, choice, {"profile_s": t1 - t0, "solve_s": t2 - t1, "compress_s": t3 - t2,
                                "elems": n, "total_s": t3 - t0}
@@ -116,7 +119,7 @@ def main():
     ef_pool = [ef0.clone() for _ in range(n_runs)]
     q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
     h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
-                 seed=w.seed, r_max=w.r_max)
+                 seed=w.seed, r_max=w.r_max, power_iters=args.power_iters)
     h.set_timing(0 if args.no_kernel_timing else (2 if args.detail else 1))
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
@@ -221,7 +224,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
-                   "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "host_generation_s": round(t_gen, 2)},
+                   "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
+                   "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
         "phases_ms": {k: round(v * 1e3 / args.steps, 4) for k, v in phase.items()},
         "kernels": kernels,
@@ -261,7 +265,7 @@ def main():
                 break
             sample.append(t)
             acc += n
-        sb, o_err, o_choice, tm = cpu_baseline(w, sample)
+        sb, o_err, o_choice, tm = cpu_baseline(w, sample, args.power_iters)
         out["cpu_baseline"] = {
             "value": round(4.0 * tm["elems"] / tm["total_s"] / 1e9, 4), "unit": "GB/s", "cores": 1,
             "kind": "oracle",

@@ -80,7 +80,9 @@ typedef struct {
     int32_t  stochastic;   /* 0: round to nearest (floor(t + 0.5)); 1: floor(t + u), u from
                               Philox4x32-10 keyed by seed with counter (index/4, layer) */
     uint64_t seed;
-    int32_t  power_iters;  /* LOWRANK power-iteration steps per call; this build: 1 */
+    int32_t  power_iters;  /* LOWRANK power-iteration steps per call (appendix "Low-rank error
+                            * computation", "Power Iteration Steps"): 1..16; every step is P = XQ, Phat = orth(P),
+                            * Q = X^T Phat, with Q feeding the next step */
     int32_t  r_max;        /* columns of the warm-start Q per layer; this build: <= 64 */
 } lgreco_config_t;
 

@@ -221,7 +221,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     if (!out || !cfg || max_elems <= 0 || max_layers <= 0 || max_cands <= 0) return LGRECO_EINVAL;
     if (max_cands > LGRECO_MAX_CANDS) return LGRECO_EINVAL;
     if (cfg->bucket != kBucket) return LGRECO_EUNSUPPORTED;
-    if (cfg->power_iters != 1) return LGRECO_EUNSUPPORTED;
+    if (cfg->power_iters < 1 || cfg->power_iters > 16) return LGRECO_EUNSUPPORTED;
     if (cfg->r_max < 0 || cfg->r_max > 64) return LGRECO_EUNSUPPORTED;
     lgreco_handle* h = new (std::nothrow) lgreco_handle();
     if (!h) return LGRECO_ENOSPACE;
@@ -270,7 +270,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     {
         hipError_t e = topk_scratch_create(&h->topk, max_elems, max_layers, h->max_tiles);
         if (e != hipSuccess) { hip_fail(h, e, "topk_scratch_create"); return fail(LGRECO_EHIP); }
-        e = lowrank_scratch_create(&h->lowrank, max_elems, max_layers, cfg->r_max);
+        e = lowrank_scratch_create(&h->lowrank, max_elems, max_layers, cfg->r_max, cfg->power_iters);
         if (e != hipSuccess) { hip_fail(h, e, "lowrank_scratch_create"); return fail(LGRECO_EHIP); }
     }
 #undef HIPCHK_C

@@ -125,9 +125,10 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 struct LowrankScratch {
     void* host = nullptr;        // work tables and scratch buffers (grown on demand)
     int64_t max_elems = 0;
-    int max_layers = 0, r_max = 0;
+    int max_layers = 0, r_max = 0, power_iters = 1;
 };
-hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max);
+hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max,
+                                  int power_iters);
 void lowrank_scratch_destroy(LowrankScratch* t);
 hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, const DevLayer* d_layers,
                            const DevLayer* h_layers, int L, const float* q0, int r_max, const int* rank,

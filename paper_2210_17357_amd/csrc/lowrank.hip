@@ -85,6 +85,7 @@ struct LrParams {
     int32_t rank[LGRECO_MAX_CANDS];
     int32_t col[LGRECO_MAX_CANDS];
     int32_t accumulate;      // decode: add the image to the output instead of replacing it
+    int32_t q_from_scratch;  // P = X Q reads the previous step's Q instead of the warm start
 };
 
 // 4 consecutive elements of x = g + e starting at idx of a row that has `left` elements left.
@@ -123,10 +124,14 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
     const int kbeg = tile.split * L.pksplit, kend = min(n, kbeg + L.pksplit);
     const float* __restrict__ g = p.g + L.offset;
     const float* __restrict__ e = HAS_E ? p.e + L.offset : nullptr;
-    const float* __restrict__ q = p.q0 + L.q_off;
+    // first power-iteration step: the caller's warm start (row stride r_max); later steps: the Q
+    // of the previous step in the scratch buffer (row stride 64)
+    const bool qscr = p.q_from_scratch != 0;
+    const float* __restrict__ q = qscr ? p.Q + L.qs_off : p.q0 + L.q_off;
+    const int qstride = qscr ? kLrCols : p.r_max;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool vec = L.vec_ok != 0;
-    const bool qvec = (p.r_max == kLrCols) && (L.q_off % 4 == 0);
+    const bool qvec = (qstride == kLrCols) && (qscr || L.q_off % 4 == 0);
     const int half = lane >> 5, bj = lane & 31;
     const int row = row0 + 32 * wave + bj;               // this lane's row of X
     const bool row_ok = row < m;
@@ -168,11 +173,11 @@ __global__ __launch_bounds__(256) void lr_gemm1_kernel(LrParams p) {
                 const int k = k0 + (f >> 4), c = (f & 15) * 4;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (k < kend) {
-                    const float* src = q + (int64_t)k * p.r_max + c;
-                    if (c < p.r_max) v.x = src[0];
-                    if (c + 1 < p.r_max) v.y = src[1];
-                    if (c + 2 < p.r_max) v.z = src[2];
-                    if (c + 3 < p.r_max) v.w = src[3];
+                    const float* src = q + (int64_t)k * qstride + c;
+                    if (c < qstride) v.x = src[0];
+                    if (c + 1 < qstride) v.y = src[1];
+                    if (c + 2 < qstride) v.z = src[2];
+                    if (c + 3 < qstride) v.w = src[3];
                 }
                 qr[s] = v;
             }
@@ -790,7 +795,9 @@ static hipError_t grow(void** ptr, size_t* cap, size_t need) {
     return hipSuccess;
 }
 
-hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max) {
+hipError_t lowrank_scratch_create(LowrankScratch* t, int64_t max_elems, int max_layers, int r_max,
+                                  int power_iters) {
+    t->power_iters = power_iters;
     t->max_elems = max_elems;
     t->max_layers = max_layers;
     t->r_max = r_max;
@@ -948,7 +955,10 @@ static void lr_fill_params(LrHost* H, LrParams* p) {
     p->qnorm_part = H->qn;
 }
 
-static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStream_t s) {
+// `iters` power-iteration steps: P = X Q, Phat = orth(P), Q = X^T Phat, Q feeding the next step.
+static hipError_t lr_factorize(LrHost* H, LrParams p, int iters, Timing* tm, hipStream_t s) {
+  for (int it = 0; it < iters; ++it) {
+    p.q_from_scratch = it > 0 ? 1 : 0;
     {
         Section sec(tm, "lowrank_gemm_p", true);
         if (p.e)
@@ -983,6 +993,7 @@ static hipError_t lr_factorize(LrHost* H, const LrParams& p, Timing* tm, hipStre
         hipLaunchKernelGGL(lr_qreduce_kernel, dim3((unsigned)H->q_chunks.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
     }
+  }
     return hipSuccess;
 }
 
@@ -1006,7 +1017,7 @@ hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, co
     p.stride = stride;
     p.nrank = nlr;
     for (int c = 0; c < nlr; ++c) { p.rank[c] = rank[c]; p.col[c] = col[c]; }
-    LR_CHECK(lr_factorize(H, p, tm, s));
+    LR_CHECK(lr_factorize(H, p, t->power_iters, tm, s));
     Section sec(tm, "lowrank_errors");
     hipLaunchKernelGGL(lr_errors_kernel, dim3((unsigned)H->layers.size()), dim3(256), 0, s, p);
     return hipGetLastError();
@@ -1031,7 +1042,7 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     p.q_out = q;
     p.r_max = r_max;
     p.payload = payload;
-    LR_CHECK(lr_factorize(H, p, tm, s));
+    LR_CHECK(lr_factorize(H, p, t->power_iters, tm, s));
     Section sec(tm, "lowrank_ef", true);
     hipLaunchKernelGGL(lr_ef_kernel<false>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();

@@ -17,17 +17,17 @@ def _frob_rel(a, b):
                  max(np.linalg.norm(b.astype(np.float64)), 1e-300))
 
 
-def _check(w, batch, ranks, compress_cycle=True):
+def _check(w, batch, ranks, compress_cycle=True, power_iters=1):
     from paper_2210_17357_amd import binding as B
     torch = torch_cuda()
     cands = [(W.LOWRANK, float(r)) for r in ranks]
     layers, ctab = tables(batch, cands)
     g, e, q0 = to_device(batch)
     L = len(batch.numels)
-    h = B.Handle(int(batch.grads.size), L, len(cands), r_max=w.r_max)
+    h = B.Handle(int(batch.grads.size), L, len(cands), r_max=w.r_max, power_iters=power_iters)
     errors, sizes = h.profile(g, e, layers, ctab, q0)
     ref = pipeline.profile(batch.grads, batch.ef, batch.offsets, batch.numels, batch.rows, batch.cols, cands,
-                           q0=batch.q0, q_offsets=batch.q_offsets, r_max=w.r_max)
+                           q0=batch.q0, q_offsets=batch.q_offsets, r_max=w.r_max, power_iters=power_iters)
     assert np.array_equal(sizes, pipeline.sizes_table(batch.numels, batch.rows, batch.cols, cands))
     # error_r is a difference of norms: 1e-4 relative, with an absolute floor of 1e-6 ||X||^2
     # (a full-rank layer gives ~1e-30 in the fp64 oracle and exactly 0 here)
@@ -53,7 +53,8 @@ def _check(w, batch, ranks, compress_cycle=True):
             r = int(cands[choice[l]][1])
             q0l = batch.q0[int(batch.q_offsets[l]):int(batch.q_offsets[l]) + n_ * w.r_max].reshape(n_, w.r_max)
             phat, q, e_ref = lowrank.compress(batch.grads[off:off + n],
-                                              None if batch.ef is None else batch.ef[off:off + n], m_, n_, q0l, r)
+                                              None if batch.ef is None else batch.ef[off:off + n], m_, n_, q0l, r,
+                                              power_iters)
             got_p = pay[offsets[l]:offsets[l] + 4 * m_ * r].view(np.float32).reshape(m_, r)
             got_q = pay[offsets[l] + 4 * m_ * r:offsets[l] + 4 * (m_ + n_) * r].view(np.float32).reshape(n_, r)
             assert sizes[l, choice[l]] == 4 * (m_ + n_) * r
@@ -145,3 +146,26 @@ def test_rank_deficient_and_zero_matrices():
     assert float(ef.abs().max()) < 1e-4 * float(np.abs(a).max())
     assert np.all(np.isfinite(pay[:offsets[-1]].view(np.float32)))
     h.close()
+
+
+def test_five_power_iteration_steps_reach_the_svd_tail():
+    """Appendix "Low-rank error computation": with 5 power steps the error of every rank is
+    close to the optimum sum_{i>r} sigma_i^2 of the SVD; parity with the oracle at 5 steps, and the
+    GPU errors against the host SVD directly."""
+    full = W.workload("c3_transformer_lm_lowrank")
+    shapes = tuple(W.transformer_lm_shapes(layers=1, d=128, d_ff=512, vocab=1000)) + ((96, 200), (300, 70))
+    w = W.Workload("lr_small", shapes, full.candidates, full.default, 400, full.values, full.ef, full.scale_exp,
+                   only_2d=True)
+    batch = W.generate(w)
+    errors, ref = _check(w, batch, W.LOWRANK_RANKS, power_iters=5)
+    one, _ = _check(w, batch, W.LOWRANK_RANKS, compress_cycle=False, power_iters=1)
+    for l in range(len(batch.numels)):
+        off, n = int(batch.offsets[l]), int(batch.numels[l])
+        x = batch.grads[off:off + n].astype(np.float64).reshape(int(batch.rows[l]), int(batch.cols[l]))
+        sv = np.linalg.svd(x, compute_uv=False) ** 2
+        for c, r in enumerate(W.LOWRANK_RANKS):
+            tail = float(sv[r:].sum())
+            assert errors[l, c] >= tail * (1 - 1e-4) - 1e-6 * sv.sum()       # Eckart-Young
+            assert errors[l, c] <= one[l, c] * (1 + 1e-4) + 1e-6 * sv.sum()  # more steps never hurt here
+            if r < min(x.shape):
+                assert errors[l, c] - tail <= 0.5 * (one[l, c] - tail) + 1e-6 * sv.sum()
