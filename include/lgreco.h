@@ -54,7 +54,7 @@ extern "C" {
 #define LGRECO_TOPK    1   /* param = density in (0, 1] */
 #define LGRECO_LOWRANK 2   /* param = rank, integer in [1, r_max] */
 
-#define LGRECO_MAX_CANDS 32
+#define LGRECO_MAX_CANDS 128
 #define LGRECO_MAX_BINS  16384
 
 typedef struct lgreco_handle lgreco_handle_t;
@@ -115,6 +115,17 @@ int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* c
 int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef,
                    const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                    const float* d_q0, double* errors, int64_t* sizes, void* stream);
+
+/* Candidate list from a default parameter, the rule of the paper's experiments (section
+ * "Experimental setup", "Parameter ranges"): bits and ranks [D/2, 2 D] in steps of 1 (D/2
+ * rounded down, at least 1; bits at most 8, ranks at most r_max when r_max > 0), densities
+ * [D/10, 10 D] in steps of D/10 (at most 1).  Host arithmetic.
+ *   cands          receives up to cap candidates in increasing parameter order
+ *   count          number of candidates of the range (LGRECO_ENOSPACE if it exceeds cap)
+ *   default_index  position of the default parameter in the list (may be NULL) */
+int lgreco_candidate_range(int32_t family, double default_param, int32_t r_max,
+                           lgreco_cand_t* cands, int32_t cap, int32_t* count,
+                           int32_t* default_index);
 
 /* E_max: sum over layers, in layer order, of errors[l][default_cand] (Algorithm 1, step 2;
  * section "The Error Bound").  Host arithmetic. */
@@ -187,6 +198,13 @@ int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_
                       const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
                       int32_t P, const int32_t* choice, float* d_out, int32_t accumulate,
                       void* stream);
+
+/* Gradient accumulation between two runs of the algorithm (section "Implementation": in
+ * between runs, per-layer gradients are accumulated in auxiliary buffers; the error table is
+ * then built on the accumulated gradients).  d_acc[i] = d_grads[i] when reset != 0 (first step
+ * of a window), else d_acc[i] += d_grads[i]; fp32, n elements, both buffers 16-byte aligned. */
+int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, int64_t n,
+                      int32_t reset, void* stream);
 
 /* Timing of the kernels launched by the last profile / solve / compress call on this handle.
  * lgreco_set_timing(h, level) makes every call bracket kernels with HIP events on the call's

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_HERE, "liblgreco.so")
 OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 QUANT, TOPK, LOWRANK = 0, 1, 2
 
-EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_emax",
-           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_set_timing",
+EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_candidate_range", "lgreco_emax",
+           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing",
            "lgreco_get_timing", "lgreco_strerror", "lgreco_last_hip_error")
 
 
@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         l.lgreco_destroy.argtypes = [vp]
         l.lgreco_sizes.argtypes = [vp, i32, vp, i32, i32, vp]
         l.lgreco_profile.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp]
+        l.lgreco_candidate_range.argtypes = [i32, dbl, i32, vp, i32, C.POINTER(i32), C.POINTER(i32)]
         l.lgreco_emax.argtypes = [vp, i32, i32, i32, C.POINTER(dbl)]
         l.lgreco_solve.argtypes = [vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64), C.POINTER(dbl), vp]
         l.lgreco_solve_weighted.argtypes = [vp, vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64),
@@ -67,6 +68,7 @@ def lib() -> C.CDLL:
         l.lgreco_payload_layout.argtypes = [vp, i32, vp, i32, vp, i32, vp]
         l.lgreco_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
         l.lgreco_decompress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, i32, vp]
+        l.lgreco_accumulate.argtypes = [vp, vp, vp, i64, i32, vp]
         l.lgreco_set_timing.argtypes = [vp, i32]
         l.lgreco_get_timing.argtypes = [vp, vp, vp, i32]
         l.lgreco_strerror.argtypes = [C.c_int]
@@ -122,6 +124,18 @@ def sizes(layers, cands, bucket: int = 128) -> np.ndarray:
     if st != OK:
         raise LgrecoError(st, strerror(st))
     return out
+
+
+def candidate_range(family: int, default_param: float, r_max: int = 0):
+    """[(family, parameter)] of the paper's range rule and the index of the default in it."""
+    cap = 128
+    arr = (Cand * cap)()
+    n, d = C.c_int32(), C.c_int32()
+    st = lib().lgreco_candidate_range(int(family), float(default_param), int(r_max), C.addressof(arr), cap,
+                                      C.byref(n), C.byref(d))
+    if st != OK:
+        raise LgrecoError(st, strerror(st))
+    return [(arr[i].family, arr[i].param) for i in range(n.value)], d.value
 
 
 def emax(errors: np.ndarray, default_cand: int) -> float:
@@ -225,6 +239,12 @@ class Handle:
                                      C.addressof(cands), len(cands), _np(choice), _dptr(d_out),
                                      int(bool(accumulate)), _stream())
         self._check(st)
+
+    def accumulate(self, d_acc, d_grads, reset: bool = False):
+        if d_acc.numel() != d_grads.numel():
+            raise ValueError("buffers differ in size")
+        self._check(lib().lgreco_accumulate(self._h, _dptr(d_acc), _dptr(d_grads), int(d_grads.numel()),
+                                            int(bool(reset)), _stream()))
 
     def set_timing(self, level):
         """0 / False: off; 1 / True: main kernels; 2: every section."""

@@ -54,6 +54,7 @@ struct lgreco_handle {
     int32_t* h_choice = nullptr;
     int64_t* h_result = nullptr;
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
+    std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
     Timing tm;
     // sub-sections measured inside a kernel (device clock), appended after the event sections
@@ -248,6 +249,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_errors, sizeof(double) * (size_t)max_layers * max_cands));
     HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
     const size_t lp = (size_t)max_layers * max_cands;
+    h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
     h->dp_entries_off = (sizeof(int32_t) * (size_t)max_layers + 15) / 16 * 16;
     const size_t dp_in = h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS;
     const size_t dp_out = sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)max_layers;
@@ -342,6 +344,38 @@ int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* c
     return LGRECO_OK;
 }
 
+int lgreco_candidate_range(int32_t family, double default_param, int32_t r_max, lgreco_cand_t* cands,
+                           int32_t cap, int32_t* count, int32_t* default_index) {
+    if (!cands || !count || cap <= 0) return LGRECO_EINVAL;
+    int n = 0, def = -1;
+    auto push = [&](double v, bool is_default) {
+        if (n < cap) cands[n] = lgreco_cand_t{family, 0, v};
+        if (is_default) def = n;
+        ++n;
+    };
+    if (family == LGRECO_QUANT || family == LGRECO_LOWRANK) {
+        if (!(default_param >= 1.0) || default_param != std::floor(default_param) || default_param > 1e6)
+            return LGRECO_EINVAL;
+        const int d = (int)default_param;
+        const int top = family == LGRECO_QUANT ? 8 : (r_max > 0 ? r_max : 2 * d);
+        if (d > top) return LGRECO_EINVAL;
+        const int lo = std::max(1, d / 2), hi = std::min(top, 2 * d);
+        for (int v = lo; v <= hi; ++v) push((double)v, v == d);
+    } else if (family == LGRECO_TOPK) {
+        if (!(default_param > 0.0 && default_param <= 1.0)) return LGRECO_EINVAL;
+        for (int i = 1; i <= 100; ++i) {
+            const double v = (double)i * default_param / 10.0;      // i = 10 reproduces the default exactly
+            if (v > 1.0) break;
+            push(i == 10 ? default_param : v, i == 10);
+        }
+    } else {
+        return LGRECO_EINVAL;
+    }
+    *count = n;
+    if (default_index) *default_index = def;
+    return n > cap ? LGRECO_ENOSPACE : LGRECO_OK;
+}
+
 int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand, double* e_max) {
     if (!errors || !e_max || L <= 0 || P <= 0 || default_cand < 0 || default_cand >= P) return LGRECO_EINVAL;
     double s = 0.0;
@@ -361,11 +395,11 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     if (st != LGRECO_OK) return st;
 
     QuantParams qp{};
-    int tk_col[kMaxTopk];
-    double tk_density[kMaxTopk];
-    int ntk = 0;
+    // Top-K candidates, largest density first: one pass resolves kMaxTopk of them, the rest follow
+    // in further groups on the same collected candidates (the first group has the lowest
+    // thresholds, so its collection bound serves all)
+    std::vector<std::pair<double, int>> tk_all;
     int lr_col[LGRECO_MAX_CANDS], lr_rank[LGRECO_MAX_CANDS], nlr = 0;
-    uint32_t tile_cols = 0;            // columns produced as per-tile partials
     for (int c = 0; c < P; ++c) {
         st = check_cand(cands[c], nullptr, h->cfg.r_max);
         if (st != LGRECO_OK) return st;
@@ -373,12 +407,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
             if (qp.nq >= kMaxQuant) return LGRECO_ENOSPACE;
             qp.bits[qp.nq] = (int)cands[c].param;
             qp.col[qp.nq++] = c;
-            tile_cols |= 1u << c;
         } else if (cands[c].family == LGRECO_TOPK) {
-            if (ntk >= kMaxTopk) return LGRECO_ENOSPACE;
-            tk_density[ntk] = cands[c].param;
-            tk_col[ntk++] = c;
-            tile_cols |= 1u << c;
+            tk_all.emplace_back(cands[c].param, c);
         } else {
             lr_rank[nlr] = (int)cands[c].param;
             lr_col[nlr++] = c;
@@ -400,11 +430,24 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     const bool ptr_aligned = ((uintptr_t)d_grads % 16 == 0) && (!d_ef || (uintptr_t)d_ef % 16 == 0);
     if (!ptr_aligned) return LGRECO_EINVAL;     // device allocations are always 256-byte aligned
 
+    std::stable_sort(tk_all.begin(), tk_all.end(),
+                     [](const std::pair<double, int>& a, const std::pair<double, int>& b) { return a.first > b.first; });
+    const int ntk_all = (int)tk_all.size();
+    const int ntk = std::min(ntk_all, (int)kMaxTopk);          // size of the first group
+    int tk_col[kMaxTopk];
+    std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
+    auto load_group = [&](int first) {                          // fills ks / tk_col, returns the group's size
+        const int cnt = std::min((int)kMaxTopk, ntk_all - first);
+        std::fill(ks.begin(), ks.end(), 0u);
+        for (int j = 0; j < cnt; ++j) {
+            tk_col[j] = tk_all[first + j].second;
+            for (int l = 0; l < L; ++l)
+                ks[(size_t)l * kMaxTopk + j] = (uint32_t)topk_k(layers[l].numel, tk_all[first + j].first);
+        }
+        return cnt;
+    };
     if (ntk) {
-        std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
-        for (int l = 0; l < L; ++l)
-            for (int j = 0; j < ntk; ++j)
-                ks[(size_t)l * kMaxTopk + j] = (uint32_t)topk_k(layers[l].numel, tk_density[j]);
+        load_group(0);
         HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles, ks.data(),
                           ntk, 0, &h->tm, s));
     }
@@ -435,12 +478,16 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     if (ntk)
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, &h->tm, s));
     if (qp.nq) {
-        uint32_t qmask = 0;
-        for (int i = 0; i < qp.nq; ++i) qmask |= 1u << qp.col[i];
         Section sec(&h->tm, "reduce_partials");
-        HIPCHK(launch_reduce_partials(h->d_partials, P, qmask, h->d_layers, L, h->d_errors, s));
+        HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, h->d_errors, s));
     }
     if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, h->d_errors, P, &h->tm, s));
+    for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
+        const int cnt = load_group(first);
+        HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, &h->tm, s));
+        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, &h->tm, s));
+    }
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
                                lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));
@@ -464,9 +511,10 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     int64_t worst = 0;                  // sum over layers of the largest usable size
     int max_bin = 0;
     int n_sweep = 0;                    // layers the kernel sweeps; h_bins[l] = their original index
+    int max_count = 1;                  // most entries of a swept layer
     bool dead_layer = false;            // a layer without any usable candidate
     for (int l = 0; l < L; ++l) {
-        DpEntry* en = h->h_entries + (size_t)n_sweep * LGRECO_MAX_CANDS;
+        DpEntry* en = h->build_entries.data() + (size_t)n_sweep * LGRECO_MAX_CANDS;
         int cnt = 0;
         int64_t lmax = 0;
         for (int c = 0; c < P; ++c) {
@@ -521,6 +569,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
             choice[l] = en[0].cand;             // adds a constant to every cell: fixed here
         } else {
             h->h_count[n_sweep] = cnt;
+            max_count = std::max(max_count, cnt);
             h->h_bins[n_sweep] = l;
             ++n_sweep;
         }
@@ -537,10 +586,14 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     if (dead_layer) return infeasible();
     if (n_sweep > 0) {
         const bool narrow = worst < ((int64_t)1 << 30);
+        // the kernel's table has max_count entries per layer: the upload carries no unused slots
+        for (int i = 0; i < n_sweep; ++i)
+            std::memcpy(h->h_entries + (size_t)i * max_count,
+                        h->build_entries.data() + (size_t)i * LGRECO_MAX_CANDS, sizeof(DpEntry) * max_count);
         HIPCHK(hipMemcpyAsync(h->d_dp_in, h->h_dp_in,
-                              h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * LGRECO_MAX_CANDS,
+                              h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count,
                               hipMemcpyHostToDevice, s));
-        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0};
+        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count};
         {
             Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
@@ -690,6 +743,20 @@ int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_
     if (any[LGRECO_LOWRANK])
         HIPCHK(lowrank_decompress(&h->lowrank, h->hl.data(), L, h->cfg.r_max, d_payload, d_out, accumulate != 0,
                                   &h->tm, s));
+    HIPCHK(hipStreamSynchronize(s));
+    return LGRECO_OK;
+}
+
+int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, int64_t n, int32_t reset,
+                      void* stream) {
+    if (!h || !d_acc || !d_grads || n < 0) return LGRECO_EINVAL;
+    if ((uintptr_t)d_acc % 16 || (uintptr_t)d_grads % 16) return LGRECO_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    begin_call(h, s);
+    {
+        Section sec(&h->tm, "accumulate", true);
+        HIPCHK(launch_accumulate(d_acc, d_grads, n, reset != 0, s));
+    }
     HIPCHK(hipStreamSynchronize(s));
     return LGRECO_OK;
 }

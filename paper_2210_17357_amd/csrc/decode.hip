@@ -7,6 +7,8 @@
 // group of 8 consecutive codes is exactly b bytes, so one thread decodes one group:
 //   xhat = fma(code, unit, min)        (the same single rounding as the sender)
 // Top-K payload: values[k] then indices[k]; the image is zero except at the indices.
+#include <algorithm>
+
 #include "internal.h"
 
 namespace lgreco {
@@ -100,6 +102,33 @@ __global__ __launch_bounds__(kThreads) void topk_decode_scatter_kernel(DecodePar
         const uint32_t ix = indices[i];
         if ((int64_t)ix < L.numel) out[ix] = p.accumulate ? out[ix] + values[i] : values[i];
     }
+}
+
+// Gradient accumulation between two runs of the algorithm (section "Implementation": per-layer
+// gradients are accumulated in auxiliary buffers in between runs).  acc = g or acc += g, fp32.
+__global__ __launch_bounds__(kThreads) void accumulate_kernel(float* __restrict__ acc, const float* __restrict__ g,
+                                                              int64_t n, int reset) {
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < n4; v += stride) {
+        float4 a = reinterpret_cast<const float4*>(g)[v];
+        if (!reset) {
+            const float4 o = reinterpret_cast<const float4*>(acc)[v];
+            a.x += o.x; a.y += o.y; a.z += o.z; a.w += o.w;
+        }
+        reinterpret_cast<float4*>(acc)[v] = a;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - 4 * n4) {
+        const int64_t i = 4 * n4 + threadIdx.x;
+        acc[i] = reset ? g[i] : acc[i] + g[i];
+    }
+}
+
+hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const int64_t blocks = std::min<int64_t>((n / 4 + kThreads - 1) / kThreads + 1, 256 * 16);
+    hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, acc, g, n, reset ? 1 : 0);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode(const uint8_t* payload, const DevLayer* layers, const Tile* tiles, int n_tiles,

@@ -41,7 +41,8 @@ template <> __device__ __forceinline__ int64_t readlane_t<int64_t>(int64_t v, in
     return readlane_i64(v, lane);
 }
 
-constexpr int kDpStage = 32;    // swept layers whose entry lists are staged in LDS at a time
+constexpr int kDpStageEntries = 1024;   // entries staged in LDS at a time (16 KB)
+constexpr int kDpStageMax = 32;         // at most this many layers per stage
 
 // Thread t owns KMAX cells.  With an even KMAX they come in adjacent pairs (2t, 2t+1), (2t, 2t+1) +
 // 2*threads, ...: the two reads row[e - b], row[e + 1 - b] of a pair are one ds_read2_b32 and the
@@ -57,8 +58,8 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
     extern __shared__ unsigned char dp_smem[];
     T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
-    __shared__ DpEntry s_entries[kDpStage][LGRECO_MAX_CANDS];
-    __shared__ int32_t s_count[kDpStage];
+    __shared__ DpEntry s_entries[kDpStageEntries];      // [layers of the stage][max_count]
+    __shared__ int32_t s_count[kDpStageMax];
     __shared__ int64_t s_val[kDpThreads / 64];
     __shared__ int32_t s_idx[kDpThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -69,36 +70,41 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     // (16 bits: D <= 16384) and the picked entry per layer
     const bool lds_bins = p.bt_lds != 0;
     uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
-    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * LGRECO_MAX_CANDS);
+    const int bstride = p.max_count;
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);
 
     const uint64_t t_begin = wall_clock64();
     for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
 
-    for (int l0 = 0; l0 < p.L; l0 += kDpStage) {
-        const int nl = min(kDpStage, p.L - l0);
+    const int stage = min(kDpStageMax, kDpStageEntries / bstride);     // layers per stage
+    for (int l0 = 0; l0 < p.L; l0 += stage) {
+        const int nl = min(stage, p.L - l0);
         __syncthreads();                              // previous stage fully consumed, row written
-        for (int i = tid; i < nl * LGRECO_MAX_CANDS; i += kDpThreads) {
-            const DpEntry en = p.entries[(size_t)l0 * LGRECO_MAX_CANDS + i];
-            (&s_entries[0][0])[i] = en;
-            if (lds_bins) s_bins[(size_t)l0 * LGRECO_MAX_CANDS + i] = (uint16_t)en.bin;
+        for (int i = tid; i < nl * bstride; i += kDpThreads) {
+            const DpEntry en = p.entries[(size_t)l0 * bstride + i];
+            s_entries[i] = en;
+            if (lds_bins) s_bins[(size_t)l0 * bstride + i] = (uint16_t)en.bin;
         }
         if (tid < nl) s_count[tid] = p.count[l0 + tid];
         __syncthreads();
         for (int ll = 0; ll < nl; ++ll) {
             const int cn = s_count[ll];
-            int32_t mybin = 0;
-            T mysize = 0;
+            // entry c of the layer lives in lane c % 64 of register c / 64
+            int32_t mybin = 0, mybin_hi = 0;
+            T mysize = 0, mysize_hi = 0;
             if (lane < cn) {
-                mybin = s_entries[ll][lane].bin;
-                mysize = (T)s_entries[ll][lane].size;
+                mybin = s_entries[ll * bstride + lane].bin;
+                mysize = (T)s_entries[ll * bstride + lane].size;
+            }
+            if (lane + 64 < cn) {
+                mybin_hi = s_entries[ll * bstride + lane + 64].bin;
+                mysize_hi = (T)s_entries[ll * bstride + lane + 64].size;
             }
             T nv[KMAX];
             int32_t na[KMAX];
 #pragma unroll
             for (int k = 0; k < KMAX; ++k) { nv[k] = kInf; na[k] = 255; }
-            for (int c = 0; c < cn; ++c) {
-                const int32_t b = (int32_t)readlane_u32((uint32_t)mybin, c);
-                const T sz = readlane_t<T>(mysize, c);
+            auto relax = [&](int32_t b, T sz, int c) {
                 if (PADDED) {
                     const T* __restrict__ src = row + (dp_cell<KMAX, kDpThreads>(tid, 0) - b);
 #pragma unroll
@@ -119,7 +125,12 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                         na[k] = lt ? c : na[k];
                     }
                 }
-            }
+            };
+            const int cn_lo = min(cn, 64);
+            for (int c = 0; c < cn_lo; ++c)
+                relax((int32_t)readlane_u32((uint32_t)mybin, c), readlane_t<T>(mysize, c), c);
+            for (int c = 64; c < cn; ++c)             // rare: more than 64 entries survive the host's pruning
+                relax((int32_t)readlane_u32((uint32_t)mybin_hi, c - 64), readlane_t<T>(mysize_hi, c - 64), c);
             __syncthreads();
             uint8_t* __restrict__ pdrow = p.pd + (size_t)(l0 + ll) * width;
             if (KMAX % 2 == 0) {
@@ -178,12 +189,12 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 for (int l = p.L - 1; l >= 0; --l) {
                     const int k = p.pd[(size_t)l * width + e];
                     s_pick[l] = (uint8_t)k;
-                    e -= s_bins[l * LGRECO_MAX_CANDS + k];
+                    e -= s_bins[l * bstride + k];
                 }
             } else {
                 for (int l = p.L - 1; l >= 0; --l) {
                     const int k = p.pd[(size_t)l * width + e];
-                    const DpEntry en = p.entries[(size_t)l * LGRECO_MAX_CANDS + k];
+                    const DpEntry en = p.entries[(size_t)l * bstride + k];
                     p.choice[l] = en.cand;
                     e -= en.bin;
                 }
@@ -195,7 +206,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     const bool feasible = s_val[0] < (int64_t)kInf;
     if (feasible && lds_bins)
         for (int l = tid; l < p.L; l += kDpThreads)
-            p.choice[l] = p.entries[(size_t)l * LGRECO_MAX_CANDS + s_pick[l]].cand;
+            p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
     if (tid == 0) {
         if (!feasible) {
             p.result[0] = 1;
@@ -226,7 +237,7 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
     p.pad = padded ? pad : 0;
     p.pd_stride = (p.D + 1 + 3) & ~3;
     size_t lds = ((size_t)p.pad + (size_t)kmax * THREADS) * sizeof(T);
-    const size_t bt = (size_t)p.L * LGRECO_MAX_CANDS * sizeof(uint16_t) + (size_t)p.L;
+    const size_t bt = (size_t)p.L * p.max_count * sizeof(uint16_t) + (size_t)p.L;
     p.bt_lds = lds + bt <= kDpLdsBudget ? 1 : 0;
     if (p.bt_lds) lds += bt;
     hipError_t err = hipSuccess;

@@ -38,7 +38,7 @@ struct Section {
 
 // ---- quant.hip
 hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s);
-hipError_t launch_reduce_partials(const double* partials, int stride, uint32_t colmask,
+hipError_t launch_reduce_partials(const double* partials, int stride, const int* cols, int ncols,
                                   const DevLayer* layers, int n_layers, double* errors, hipStream_t s);
 hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
                                  int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
@@ -51,7 +51,7 @@ struct DpEntry {            // one usable candidate of a layer (equal bins merge
     int64_t size;
 };
 struct DpParams {
-    const DpEntry* entries;   // [L x LGRECO_MAX_CANDS] swept layers only, in candidate order
+    const DpEntry* entries;   // [L x max_count] swept layers only, in candidate order
     const int32_t* count;     // [L] entries per swept layer
     uint8_t* pd;              // [L x pd_stride] entry index per cell
     int32_t* choice;          // [L] candidate index per swept layer
@@ -60,6 +60,7 @@ struct DpParams {
     int32_t pad;              // set by launch_dp: cells of infinity in front of the LDS row
     int32_t pd_stride;        // set by launch_dp: bytes per PD row, a multiple of 4 and >= D + 2
     int32_t bt_lds;           // set by launch_dp: back-trace tables live in LDS behind the row
+    int32_t max_count;        // largest entry count of a swept layer = row stride of `entries`
 };
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
 // max_bin: largest bin in entries
@@ -106,6 +107,8 @@ void topk_scratch_destroy(TopkScratch* t);
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
                       int ntk, int slot, Timing* tm, hipStream_t s);
+// replace the requested k by another group (each k no larger than the first group's largest)
+hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hipStream_t s);
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
 // the read; otherwise the quantization profile kernel does the same work
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
@@ -140,7 +143,8 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
 hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L, int r_max, const uint8_t* payload,
                               float* out, bool accumulate, Timing* tm, hipStream_t s);
 
-// ---- decode.hip: receiver side of quantization and Top-K
+// ---- decode.hip: receiver side of quantization and Top-K, gradient accumulation
+hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s);
 hipError_t launch_decode(const uint8_t* payload, const DevLayer* layers, const Tile* tiles, int n_tiles,
                          float* out, bool accumulate, bool any_quant, bool any_topk, Timing* tm, hipStream_t s);
 

@@ -231,14 +231,18 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 }
 
 // errors[l][c] = sum of the layer's tile partials in tile order (fixed tree -> reproducible).
+struct ReduceCols {
+    int32_t n;
+    int32_t col[kMaxQuant];
+};
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const double* __restrict__ partials,
-                                                               int stride, uint32_t colmask,
+                                                               int stride, ReduceCols cols,
                                                                const DevLayer* __restrict__ layers,
                                                                double* __restrict__ errors) {
     __shared__ double s[256];
     const DevLayer L = layers[blockIdx.x];
-    for (int c = 0; c < stride; ++c) {
-        if (!((colmask >> c) & 1u)) continue;
+    for (int ci = 0; ci < cols.n; ++ci) {
+        const int c = cols.col[ci];
         double a = 0.0;
         for (int t = L.tile_begin + threadIdx.x; t < L.tile_end; t += 256)
             a += partials[(size_t)t * stride + c];
@@ -427,10 +431,13 @@ hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hi
     return hipGetLastError();
 }
 
-hipError_t launch_reduce_partials(const double* partials, int stride, uint32_t colmask,
+hipError_t launch_reduce_partials(const double* partials, int stride, const int* cols, int ncols,
                                   const DevLayer* layers, int n_layers, double* errors, hipStream_t s) {
-    if (n_layers <= 0 || colmask == 0) return hipSuccess;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(n_layers), dim3(256), 0, s, partials, stride, colmask,
+    if (n_layers <= 0 || ncols <= 0) return hipSuccess;
+    ReduceCols rc{};
+    rc.n = ncols < kMaxQuant ? ncols : kMaxQuant;
+    for (int i = 0; i < rc.n; ++i) rc.col[i] = cols[i];
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(n_layers), dim3(256), 0, s, partials, stride, rc,
                        layers, errors);
     return hipGetLastError();
 }

@@ -849,6 +849,33 @@ void topk_scratch_destroy(TopkScratch* t) {
     *t = TopkScratch{};
 }
 
+// One upload of the control block up to the last work item, skipped when this slot's device copy
+// already holds the same bytes.
+static hipError_t upload_ctl(TopkScratch* t, int slot, hipStream_t s) {
+    uint8_t* const d = t->d_ctl[slot];
+    t->d_k = reinterpret_cast<uint32_t*>(d + t->ctl_off[0]);
+    t->d_cand_base = reinterpret_cast<int64_t*>(d + t->ctl_off[1]);
+    t->d_work_range = d + t->ctl_off[2];
+    t->d_work = d + t->ctl_off[3];
+    const size_t used = t->ctl_off[3] + sizeof(RefWork) * (size_t)std::max(t->n_work, 1);
+    if (used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0) {
+        TK_CHECK(hipMemcpyAsync(d, t->h_ctl, used, hipMemcpyHostToDevice, s));
+        std::memcpy(t->h_ctl_last[slot], t->h_ctl, used);
+        t->ctl_last_bytes[slot] = used;
+    }
+    return hipSuccess;
+}
+
+// A further group of requested k for the data that was just collected (more candidates than one
+// pass resolves): only the k table changes.  The group must not ask for more entries than the
+// first one did, so every threshold lies at or above the collection bound.
+hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hipStream_t s) {
+    // the pinned staging block is read when the previous upload executes, not when it was queued
+    TK_CHECK(hipStreamSynchronize(s));
+    for (size_t i = 0; i < (size_t)L * kMaxTopk; ++i) t->h_k[i] = ks[i];
+    return upload_ctl(t, slot, s);
+}
+
 // Upload the requested k per (layer, candidate) (0 = layer inactive), clear both histograms, take
 // the sample and predict the collection bound of every layer.
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
@@ -870,19 +897,7 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
         wrange[l].y = nw;
     }
     t->n_work = nw;
-    // one upload of the control block up to the last work item, skipped when this slot's device
-    // copy already holds the same bytes
-    uint8_t* const d = t->d_ctl[slot];
-    t->d_k = reinterpret_cast<uint32_t*>(d + t->ctl_off[0]);
-    t->d_cand_base = reinterpret_cast<int64_t*>(d + t->ctl_off[1]);
-    t->d_work_range = d + t->ctl_off[2];
-    t->d_work = d + t->ctl_off[3];
-    const size_t used = (size_t)((uint8_t*)(work + std::max(nw, 1)) - t->h_ctl);
-    if (used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0) {
-        TK_CHECK(hipMemcpyAsync(d, t->h_ctl, used, hipMemcpyHostToDevice, s));
-        std::memcpy(t->h_ctl_last[slot], t->h_ctl, used);
-        t->ctl_last_bytes[slot] = used;
-    }
+    TK_CHECK(upload_ctl(t, slot, s));
     Section sec(tm, "topk_sample");
     const size_t n = 2 * (size_t)L * kHistBins;
     uint32_t* const shist = t->d_hist + (size_t)L * kHistBins;

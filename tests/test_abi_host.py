@@ -78,3 +78,24 @@ def test_product_package_does_not_import_the_oracle():
     for f in os.listdir(os.path.join(ROOT, "oracle")):
         if f.endswith(".py"):
             assert "paper_2210_17357_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
+
+
+def test_candidate_range_rule(lib):
+    """Section "Experimental setup", "Parameter ranges": [D/2, 2D] step 1 for bits and ranks,
+    [D/10, 10D] step D/10 for densities; the default is inside with room on both sides."""
+    cands, d = B.candidate_range(W.QUANT, 4)
+    assert [p for _, p in cands] == [2, 3, 4, 5, 6, 7, 8] and cands[d][1] == 4
+    assert tuple(cands) == W.workload("c1_resnet18_quant").candidates          # the configs' bit range
+    cands, d = B.candidate_range(W.LOWRANK, 32, r_max=64)
+    assert [p for _, p in cands] == list(range(16, 65)) and cands[d][1] == 32 and len(cands) == 49
+    cands, d = B.candidate_range(W.LOWRANK, 4)
+    assert [p for _, p in cands] == [2, 3, 4, 5, 6, 7, 8] and cands[d][1] == 4
+    cands, d = B.candidate_range(W.TOPK, 0.01)
+    assert len(cands) == 100 and d == 9 and cands[d][1] == 0.01
+    assert cands[0][1] == pytest.approx(0.001) and cands[-1][1] == pytest.approx(0.1)
+    assert all(b[1] > a[1] for a, b in zip(cands, cands[1:]))
+    cands, d = B.candidate_range(W.TOPK, 0.5)                                  # clipped at density 1
+    assert cands[-1][1] == pytest.approx(1.0) and len(cands) == 20 and cands[d][1] == 0.5
+    for bad in ((W.QUANT, 9), (W.QUANT, 2.5), (W.TOPK, 0.0), (W.TOPK, 1.5), (7, 1)):
+        with pytest.raises(B.LgrecoError):
+            B.candidate_range(*bad)

@@ -41,7 +41,7 @@ def test_random_small_tables_with_ties_and_unusable_candidates():
 
 
 @pytest.mark.parametrize("L,P,D", [(62, 7, 1000), (161, 6, 1000), (97, 5, 2000), (292, 13, 4000),
-                                   (40, 32, 10000), (30, 9, 16384), (3, 4, 1023), (3, 4, 1024)])
+                                   (40, 32, 10000), (97, 49, 10000), (30, 9, 16384), (3, 4, 1023), (3, 4, 1024)])
 def test_config_sized_tables(L, P, D):
     rng = np.random.default_rng(L * 1000 + P)
     h = _handle(L, P)
