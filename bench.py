@@ -56,7 +56,7 @@ def parse_args():
                     help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
     ap.add_argument("--detail", action="store_true",
                     help="bracket every kernel section, not only the main kernels (costs ~3 %% of the step)")
-    ap.add_argument("--cpu-sample-elems", type=int, default=14_000_000)
+    ap.add_argument("--cpu-sample-elems", type=int, default=30_000_000)
     return ap.parse_args()
 
 
