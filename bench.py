@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
     ap.add_argument("--power-iters", type=int, default=1,
                     help="power-iteration steps of the low-rank family (the configs use 1)")
+    ap.add_argument("--sample-every-call", action="store_true",
+                    help="Top-K: sample the data in every call instead of starting from the previous "
+                         "call's thresholds (reuse_thresholds = 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
@@ -121,7 +124,8 @@ def main():
     ef_pool = [ef0.clone() for _ in range(n_runs)]
     q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
     h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
-                 seed=w.seed, r_max=w.r_max, power_iters=args.power_iters)
+                 seed=w.seed, r_max=w.r_max, power_iters=args.power_iters,
+                 reuse_thresholds=not args.sample_every_call)
     h.set_timing(0 if args.no_kernel_timing else (2 if args.detail else 1))
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
@@ -227,6 +231,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
+                   "reuse_thresholds": not args.sample_every_call,
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
         "phases_ms": {k: round(v * 1e3 / args.steps, 4) for k, v in phase.items()},

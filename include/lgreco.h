@@ -84,6 +84,12 @@ typedef struct {
                             * computation", "Power Iteration Steps"): 1..16; every step is P = XQ, Phat = orth(P),
                             * Q = X^T Phat, with Q feeding the next step */
     int32_t  r_max;        /* columns of the warm-start Q per layer; this build: <= 64 */
+    int32_t  reuse_thresholds; /* TOPK: 1 = a call with the same layer table and the same k as the
+                            * previous call of its kind (profile / compress) starts its single
+                            * pass from the thresholds found then, a margin lower, instead of
+                            * sampling the data first.  Results do not depend on it: a layer
+                            * whose data moved past the margin is collected again. */
+    int32_t  reserved;     /* 0 */
 } lgreco_config_t;
 
 /* Create a handle for problems of at most max_elems gradient elements (sum of numel),

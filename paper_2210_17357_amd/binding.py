@@ -33,7 +33,8 @@ class Cand(C.Structure):
 
 class Config(C.Structure):
     _fields_ = [("bucket", C.c_int32), ("stochastic", C.c_int32), ("seed", C.c_uint64),
-                ("power_iters", C.c_int32), ("r_max", C.c_int32)]
+                ("power_iters", C.c_int32), ("r_max", C.c_int32), ("reuse_thresholds", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class LgrecoError(RuntimeError):
@@ -161,9 +162,10 @@ class Handle:
     """lgreco_handle_t with the entry points as methods."""
 
     def __init__(self, max_elems: int, max_layers: int, max_cands: int, bucket: int = 128,
-                 stochastic: bool = False, seed: int = 0, power_iters: int = 1, r_max: int = 64):
+                 stochastic: bool = False, seed: int = 0, power_iters: int = 1, r_max: int = 64,
+                 reuse_thresholds: bool = False):
         self._h = C.c_void_p()
-        self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max)
+        self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max, int(bool(reuse_thresholds)), 0)
         st = lib().lgreco_create(C.byref(self._h), C.byref(self.cfg), max_elems, max_layers, max_cands)
         if st != OK:
             raise LgrecoError(st, strerror(st))

@@ -271,6 +271,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->tm.ready = true;
     {
         hipError_t e = topk_scratch_create(&h->topk, max_elems, max_layers, h->max_tiles);
+        h->topk.reuse_thresholds = cfg->reuse_thresholds != 0;
         if (e != hipSuccess) { hip_fail(h, e, "topk_scratch_create"); return fail(LGRECO_EHIP); }
         e = lowrank_scratch_create(&h->lowrank, max_elems, max_layers, cfg->r_max, cfg->power_iters);
         if (e != hipSuccess) { hip_fail(h, e, "lowrank_scratch_create"); return fail(LGRECO_EHIP); }
@@ -476,7 +477,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
     }
     if (ntk)
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, &h->tm, s));
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true, &h->tm,
+                           s));
     if (qp.nq) {
         Section sec(&h->tm, "reduce_partials");
         HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, h->d_errors, s));
@@ -485,7 +487,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, &h->tm, s));
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false, &h->tm,
+                           s));
         HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, &h->tm, s));
     }
     if (nlr) {

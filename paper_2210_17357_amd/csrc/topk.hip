@@ -51,6 +51,7 @@ constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
 constexpr int kPickThreads = 1024;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
+constexpr uint32_t kHintMargin = 1; // coarse bins between a remembered threshold and the bound derived from it
 
 // ------------------------------------------------------------------------ block helpers
 // Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
@@ -113,6 +114,11 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t* total) 
 }
 
 // ------------------------------------------------------------------------ kernels
+__global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         p[i] = v;
@@ -333,7 +339,8 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
 __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restrict__ hist,
                                                         const uint32_t* __restrict__ ks, int ntk,
                                                         const int64_t* __restrict__ cand_base,
-                                                        uint32_t* __restrict__ lo, TopkLayer* __restrict__ tl) {
+                                                        uint32_t* __restrict__ lo, TopkLayer* __restrict__ tl,
+                                                        uint32_t* __restrict__ hint) {
     __shared__ uint32_t s_hist[kHistBins];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
@@ -343,6 +350,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
         if (threadIdx.x == 0) {
             T.nlists = 0; T.min_tbin = 0; T.recollect = 0;
             for (int j = 0; j < kMaxTopk; ++j) T.sel[j].k = 0;
+            if (hint) hint[l] = 0xFFFFFFFFu;
         }
         return;
     }
@@ -381,6 +389,9 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
         // every element at or above the lowest threshold bin must be among the candidates
         T.recollect = lo[l] > mn ? 1u : 0u;
         if (T.recollect) lo[l] = mn;
+        // collection bound for the next call of this kind: one coarse bin (4.4 % in magnitude)
+        // under the lowest threshold found now
+        if (hint) hint[l] = mn > kHintMargin ? mn - kHintMargin : 0u;
     }
 }
 
@@ -799,6 +810,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
+    for (int i = 0; i < 2; ++i) TK_CHECK(hipMalloc(&t->d_hint[i], sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
@@ -835,6 +847,7 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_cand);
     (void)hipFree(t->d_cand_idx);
     (void)hipFree(t->d_lo);
+    for (int i = 0; i < 2; ++i) (void)hipFree(t->d_hint[i]);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
     (void)hipFree(t->d_tinfo);
@@ -851,18 +864,20 @@ void topk_scratch_destroy(TopkScratch* t) {
 
 // One upload of the control block up to the last work item, skipped when this slot's device copy
 // already holds the same bytes.
-static hipError_t upload_ctl(TopkScratch* t, int slot, hipStream_t s) {
+static hipError_t upload_ctl(TopkScratch* t, int slot, hipStream_t s, bool* changed = nullptr) {
     uint8_t* const d = t->d_ctl[slot];
     t->d_k = reinterpret_cast<uint32_t*>(d + t->ctl_off[0]);
     t->d_cand_base = reinterpret_cast<int64_t*>(d + t->ctl_off[1]);
     t->d_work_range = d + t->ctl_off[2];
     t->d_work = d + t->ctl_off[3];
     const size_t used = t->ctl_off[3] + sizeof(RefWork) * (size_t)std::max(t->n_work, 1);
-    if (used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0) {
+    const bool differs = used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0;
+    if (differs) {
         TK_CHECK(hipMemcpyAsync(d, t->h_ctl, used, hipMemcpyHostToDevice, s));
         std::memcpy(t->h_ctl_last[slot], t->h_ctl, used);
         t->ctl_last_bytes[slot] = used;
     }
+    if (changed) *changed = differs;
     return hipSuccess;
 }
 
@@ -897,10 +912,25 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
         wrange[l].y = nw;
     }
     t->n_work = nw;
-    TK_CHECK(upload_ctl(t, slot, s));
+    bool changed = true;
+    TK_CHECK(upload_ctl(t, slot, s, &changed));
+    t->cur_slot = slot;
     Section sec(tm, "topk_sample");
-    const size_t n = 2 * (size_t)L * kHistBins;
     uint32_t* const shist = t->d_hist + (size_t)L * kHistBins;
+    if (t->reuse_thresholds && t->hint_valid[slot] && !changed) {
+        // Same layers and the same k as the previous call of this kind: start from the thresholds
+        // it found, a margin lower, instead of sampling.  The scan still checks the bound against
+        // the exact histogram and collects a layer again if the data moved past the margin.
+        const size_t n = (size_t)L * kHistBins;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
+                           t->d_hist, n, 0u);
+        TK_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(copy_u32_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0, s, t->d_lo,
+                           (const uint32_t*)t->d_hint[slot], (size_t)L);
+        return hipGetLastError();
+    }
+    t->hint_valid[slot] = false;
+    const size_t n = 2 * (size_t)L * kHistBins;
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
                        t->d_hist, n, 0u);
     TK_CHECK(hipGetLastError());
@@ -949,13 +979,17 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
 
 // exact threshold bins; layers whose predicted bound was too high are collected again
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                       const Tile* d_tiles, int L, int n_tiles, int ntk, Timing* tm, hipStream_t s) {
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, Timing* tm,
+                       hipStream_t s) {
     {
         Section sec(tm, "topk_scan");
+        // the first group of a call holds the lowest thresholds: it leaves the bound for the next call
+        uint32_t* const hint = (first_group && t->reuse_thresholds) ? t->d_hint[t->cur_slot] : nullptr;
         hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)t->d_hist,
                            (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base, t->d_lo,
-                           (TopkLayer*)t->d_tl);
+                           (TopkLayer*)t->d_tl, hint);
         TK_CHECK(hipGetLastError());
+        if (hint) t->hint_valid[t->cur_slot] = true;
     }
     {
         Section sec(tm, "topk_recollect");
@@ -1034,7 +1068,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
     }
-    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, tm, s));
+    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, tm, s));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");

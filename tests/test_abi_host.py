@@ -32,7 +32,7 @@ def test_exports_match_header(lib):
 
 def test_struct_layouts_match_header():
     import ctypes as C
-    assert C.sizeof(B.Layer) == 24 and C.sizeof(B.Cand) == 16 and C.sizeof(B.Config) == 24
+    assert C.sizeof(B.Layer) == 24 and C.sizeof(B.Cand) == 16 and C.sizeof(B.Config) == 32
 
 
 @pytest.mark.parametrize("name", W.WORKLOADS)

@@ -122,3 +122,51 @@ def test_unrepresentative_sample_is_corrected():
     b = np.where(sampled, small, big).astype(np.float32)
     c = np.where(sampled, np.float32(0.0), big).astype(np.float32)
     _check(_flat_batch([a, b, c]), (0.001, 0.01, 0.1, 0.5))
+
+
+def test_reused_thresholds_give_the_same_results_and_survive_data_that_moves():
+    """reuse_thresholds = 1: the second call of a kind starts from the thresholds of the first.
+    Same data -> the same payloads and error feedback bit for bit (errors to rounding) as a handle
+    that samples every time; data scaled far
+    down (every threshold below the remembered bound -> layers are collected again) or far up
+    (everything becomes a candidate) -> still the oracle's results."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    full = W.workload("c2_resnet50_topk")
+    shapes = tuple(W.resnet50_shapes(num_classes=10))[:40] + ((200000,), (65536 * 3 + 77,))
+    w = W.Workload("tk_hint", shapes, full.candidates, full.default, 400, full.values, full.ef, full.scale_exp)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    L = len(batch.numels)
+    plain = B.Handle(int(batch.grads.size), L, len(cands))
+    reuse = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    choice = np.array([l % len(cands) for l in range(L)], np.int32)
+    offsets = B.payload_layout(layers, ctab, choice)
+    for factor in (1.0, 1.0, 1.03, 1e-3, 1.0, 1e3, 1.0):
+        gh = (batch.grads * np.float32(factor)).astype(np.float32)
+        eh = (batch.ef * np.float32(factor)).astype(np.float32)
+        g, e = torch.from_numpy(gh).cuda(), torch.from_numpy(eh).cuda()
+        e1, _ = plain.profile(g, e, layers, ctab)
+        e2, _ = reuse.profile(g, e, layers, ctab)
+        # the two handles split the energy differently between the fp32 sum below the bound and
+        # the integer sums of the candidates: equal to rounding, not bit for bit
+        assert rel_err(e2, e1).max() < 1e-6, factor
+        ref = pipeline.profile(gh, eh, batch.offsets, batch.numels, batch.rows, batch.cols, cands)
+        assert rel_err(e2, ref).max() < 1e-4, factor
+        outs = []
+        for h in (plain, reuse):
+            payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
+            ef_dev = e.clone()
+            h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)
+            outs.append((payload.cpu().numpy(), ef_dev.cpu().numpy()))
+        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1].view(np.uint32),
+                                                                         outs[1][1].view(np.uint32)), factor
+        for l in (0, 5, L - 2, L - 1):
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            vals, idx, e_ref = topk.compress(gh[off:off + n], eh[off:off + n], cands[choice[l]][1])
+            k = idx.size
+            assert np.array_equal(outs[1][0][offsets[l] + 4 * k:offsets[l] + 8 * k].view(np.uint32), idx), (factor, l)
+            assert np.array_equal(outs[1][1][off:off + n].view(np.uint32), e_ref.view(np.uint32)), (factor, l)
+    plain.close()
+    reuse.close()
