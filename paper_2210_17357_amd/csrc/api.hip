@@ -29,6 +29,7 @@ struct lgreco_handle {
     DevLayer* d_layers = nullptr;
     Tile* d_tiles = nullptr;
     int32_t max_tiles = 0;
+    int32_t tile_elems = kTile;     // tile size of the current layer table
     double* d_partials = nullptr;   // [max_tiles x max_cands]
     double* d_errors = nullptr;     // [max_layers x max_cands]
     double* h_errors = nullptr;     // pinned mirror
@@ -139,6 +140,10 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
     for (int l = 0; l < L; ++l) total += layers[l].numel;
     if (total > h->max_elems) return LGRECO_ENOSPACE;
 
+    // tile size: the largest power of two up to kTile that still gives about kTilesWanted tiles
+    int tile = kTile;
+    while (tile > kTileMin && total / tile < kTilesWanted) tile /= 2;
+    h->tile_elems = tile;
     h->hl.assign(L, DevLayer{});
     h->ht.clear();
     int64_t qoff = 0;
@@ -158,7 +163,7 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
             h->ht.push_back(Tile{pos, l, (int32_t)cnt, fast, 0});
             pos += cnt;
         };
-        while (n - pos >= kTile) push(kTile, aligned ? 1 : 0);
+        while (n - pos >= tile) push(tile, aligned ? 1 : 0);
         const int64_t rem = n - pos;
         if (aligned) {
             const int64_t mid = (rem / kChunk) * kChunk;
@@ -242,7 +247,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
         if (_e != hipSuccess) { hip_fail(h, _e, #expr); return fail(LGRECO_EHIP); } \
     } while (0)
     HIPCHK_C(hipGetDevice(&h->device));
-    h->max_tiles = (int32_t)std::min<int64_t>(max_elems / kTile + 2 * (int64_t)max_layers + 2, INT32_MAX);
+    h->max_tiles = (int32_t)std::min<int64_t>(max_elems / kTileMin + 2 * (int64_t)max_layers + 2, INT32_MAX);
     HIPCHK_C(hipMalloc(&h->d_layers, sizeof(DevLayer) * max_layers));
     HIPCHK_C(hipMalloc(&h->d_tiles, sizeof(Tile) * h->max_tiles));
     HIPCHK_C(hipMalloc(&h->d_partials, sizeof(double) * (size_t)h->max_tiles * max_cands));
@@ -449,8 +454,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     };
     if (ntk) {
         load_group(0);
-        HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles, ks.data(),
-                          ntk, 0, &h->tm, s));
+        HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
+                          h->tile_elems, ks.data(), ntk, 0, &h->tm, s));
     }
     if (qp.nq) {
         qp.g = d_grads;
@@ -706,7 +711,7 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     }
     if (any[LGRECO_TOPK]) {
         HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
-                             d_payload, &h->tm, s));
+                             h->tile_elems, d_payload, &h->tm, s));
     }
     if (any[LGRECO_LOWRANK]) {
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,

@@ -8,7 +8,9 @@
 
 namespace lgreco {
 
-constexpr int kTile = 65536;       // elements per streaming tile (512 buckets of 128)
+constexpr int kTile = 65536;       // largest streaming tile in elements (512 buckets of 128)
+constexpr int kTileMin = 8192;     // smallest: small problems get smaller tiles so that the launch still fills the chip
+constexpr int kTilesWanted = 2048; // tiles aimed at when the tile size is chosen
 constexpr int kBucket = 128;       // quantization bucket (elements)
 constexpr int kChunk = 512;        // elements one wavefront handles per step (4 buckets)
 constexpr int kThreads = 256;      // workgroup size of the streaming kernels (4 wavefronts)

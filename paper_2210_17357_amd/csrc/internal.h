@@ -109,8 +109,8 @@ void topk_scratch_destroy(TopkScratch* t);
 // upload k per (layer, candidate), clear the histograms, sample the data and predict every
 // layer's collection bound
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
-                      int ntk, int slot, Timing* tm, hipStream_t s);
+                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
+                      const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s);
 // replace the requested k by another group (each k no larger than the first group's largest)
 hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hipStream_t s);
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
@@ -126,8 +126,8 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
 hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
                          const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
-                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
-                         Timing* tm, hipStream_t s);
+                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
+                         uint8_t* payload, Timing* tm, hipStream_t s);
 
 // ---- lowrank.hip
 struct LowrankScratch {

@@ -46,7 +46,8 @@ struct TopkLayer {
     TopkList lists[kMaxTopk];
     TopkSel sel[kMaxTopk];
 };
-constexpr int kRefTiles = 8;        // tiles per refinement workgroup
+constexpr int kRefTiles = 8;        // largest tiles per refinement / sample workgroup (fewer elements never: with
+                                    // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
 constexpr int kPickThreads = 1024;
@@ -136,14 +137,14 @@ __global__ __launch_bounds__(kThreads) void topk_sample_kernel(const float* __re
                                                                 const DevLayer* __restrict__ layers,
                                                                 const Tile* __restrict__ tiles,
                                                                 const RefWork* __restrict__ work,
-                                                                uint32_t* __restrict__ shist) {
+                                                                int per_tile, uint32_t* __restrict__ shist) {
     __shared__ uint32_t s_hist[kHistBins];
     const RefWork w = work[blockIdx.x];
     const DevLayer L = layers[w.layer];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int b = threadIdx.x; b < kHistBins; b += kThreads) s_hist[b] = 0;
     __syncthreads();
-    constexpr int kPerTile = kTile / kChunk / kSampleEvery;      // sampled chunks of a full tile
+    const int kPerTile = per_tile;                               // sampled chunks of a full tile
     constexpr int kWaves = kThreads / 64, kBatch = 4;            // chunks a wavefront has in flight
     const int npairs = (w.t1 - w.t0) * kPerTile;
     for (int pr0 = wave * kBatch; pr0 < npairs; pr0 += kWaves * kBatch) {
@@ -815,7 +816,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
-    t->max_work = max_tiles / kRefTiles + max_layers + 1;
+    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile)) + 2 * max_layers + 2;
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
     t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
@@ -894,8 +895,9 @@ hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hip
 // Upload the requested k per (layer, candidate) (0 = layer inactive), clear both histograms, take
 // the sample and predict the collection bound of every layer.
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
-                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, const uint32_t* ks,
-                      int ntk, int slot, Timing* tm, hipStream_t s) {
+                      const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
+                      const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
+    const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
     int2* const wrange = (int2*)t->h_work_range;
@@ -906,8 +908,8 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
         wrange[l].x = nw;
         if (ks[(size_t)l * kMaxTopk]) {
             base += h_layers[l].numel;
-            for (int t0 = h_layers[l].tile_begin; t0 < h_layers[l].tile_end; t0 += kRefTiles)
-                work[nw++] = RefWork{l, t0, std::min(h_layers[l].tile_end, t0 + kRefTiles), 0};
+            for (int t0 = h_layers[l].tile_begin; t0 < h_layers[l].tile_end; t0 += group)
+                work[nw++] = RefWork{l, t0, std::min(h_layers[l].tile_end, t0 + group), 0};
         }
         wrange[l].y = nw;
     }
@@ -936,7 +938,7 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
     TK_CHECK(hipGetLastError());
     if (nw > 0) {
         hipLaunchKernelGGL(topk_sample_kernel, dim3(nw), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
-                           (const RefWork*)t->d_work, shist);
+                           (const RefWork*)t->d_work, std::max(1, tile_elems / kChunk / kSampleEvery), shist);
         TK_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(topk_predict_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)shist,
@@ -1058,12 +1060,12 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
 }
 
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
-                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, uint8_t* payload,
-                         Timing* tm, hipStream_t s) {
+                         const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
+                         uint8_t* payload, Timing* tm, hipStream_t s) {
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
     for (int l = 0; l < L; ++l)
         if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
-    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, ks.data(), 1, 1, tm, s));
+    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, tile_elems, ks.data(), 1, 1, tm, s));
     {
         Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
