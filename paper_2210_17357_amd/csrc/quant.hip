@@ -79,13 +79,33 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             col_start = (uint32_t)c_begin * kChunk;
             col.init(slice + col_start, nullptr, col_lo);
         }
-        for (int c = c_begin; c < c_end; ++c) {
-            const int base = c * kChunk + (lane >> 4) * kBucket + j * 4;
-            float4 a = *reinterpret_cast<const float4*>(g + base);
-            float4 b = *reinterpret_cast<const float4*>(g + base + 64);
+        // the next chunk's loads are in flight while the current chunk is worked on
+        const int lane_off = (lane >> 4) * kBucket + j * 4;
+        float4 na, nb, nea, neb;
+        nea = neb = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c_begin < c_end) {
+            const int nbase = c_begin * kChunk + lane_off;
+            na = *reinterpret_cast<const float4*>(g + nbase);
+            nb = *reinterpret_cast<const float4*>(g + nbase + 64);
             if (HAS_EF) {
-                const float4 ea = *reinterpret_cast<const float4*>(e + base);
-                const float4 eb = *reinterpret_cast<const float4*>(e + base + 64);
+                nea = *reinterpret_cast<const float4*>(e + nbase);
+                neb = *reinterpret_cast<const float4*>(e + nbase + 64);
+            }
+        }
+        for (int c = c_begin; c < c_end; ++c) {
+            const int base = c * kChunk + lane_off;
+            float4 a = na, b = nb;
+            const float4 ea = nea, eb = neb;
+            if (c + 1 < c_end) {
+                const int nbase = base + kChunk;
+                na = *reinterpret_cast<const float4*>(g + nbase);
+                nb = *reinterpret_cast<const float4*>(g + nbase + 64);
+                if (HAS_EF) {
+                    nea = *reinterpret_cast<const float4*>(e + nbase);
+                    neb = *reinterpret_cast<const float4*>(e + nbase + 64);
+                }
+            }
+            if (HAS_EF) {
                 a.x += ea.x; a.y += ea.y; a.z += ea.z; a.w += ea.w;
                 b.x += eb.x; b.y += eb.y; b.z += eb.z; b.w += eb.w;
             }
