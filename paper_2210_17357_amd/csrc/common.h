@@ -74,6 +74,37 @@ __device__ __forceinline__ float row16_max(float v) {
     v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
     return v;
 }
+// Minimum and maximum of a DPP row together: one instruction per step and operand.  (Written as
+// min / max of a moved value the compiler spends four instructions per step.)  A DPP read of a
+// register needs two wait states after the write; the s_nop in front of each step provides them,
+// and the last one covers a DPP read the compiler may place behind this block.
+__device__ __forceinline__ void row16_minmax(float& mn, float& mx) {
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(mn), "+v"(mx));
+}
+// min / max of three in one instruction (inputs are results of arithmetic, so already canonical)
+__device__ __forceinline__ float min3f(float a, float b, float c) {
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 __device__ __forceinline__ float row16_sum(float v) {
     v += dpp_f32<kDppQuadXor1>(v);
     v += dpp_f32<kDppQuadXor2>(v);
@@ -84,7 +115,9 @@ __device__ __forceinline__ float row16_sum(float v) {
 // Value of lane (row base + LANE) for every lane of the row.
 template <int LANE>
 __device__ __forceinline__ float row16_bcast(float v) {
-    return dpp_f32<0x150 + LANE>(v);   // row_newbcast:LANE
+    // every lane has a source lane, so no previous value is needed (none is set up)
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + LANE, 0xF, 0xF,
+                                                              true));   // row_newbcast:LANE
 }
 // All 64 lanes end up with the wavefront's sum (fixed order -> reproducible).
 __device__ __forceinline__ float wave_sum(float v) {

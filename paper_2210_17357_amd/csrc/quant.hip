@@ -49,7 +49,9 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
     const DevLayer L = p.layers[t.layer];
     const float* __restrict__ g = p.g + L.offset + t.pos;
     const float* __restrict__ e = HAS_EF ? p.e + L.offset + t.pos : nullptr;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wavefront's number through a scalar register: its share of the tile, the loop over it and
+    // the candidate slice's address are then uniform values
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nq = p.nq;
 
     if (HIST) {
@@ -79,32 +81,9 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             col_start = (uint32_t)c_begin * kChunk;
             col.init(slice + col_start, nullptr, col_lo);
         }
-        // the next chunk's loads are in flight while the current chunk is worked on
-        const int lane_off = (lane >> 4) * kBucket + j * 4;
-        float4 na, nb, nea, neb;
-        nea = neb = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c_begin < c_end) {
-            const int nbase = c_begin * kChunk + lane_off;
-            na = *reinterpret_cast<const float4*>(g + nbase);
-            nb = *reinterpret_cast<const float4*>(g + nbase + 64);
-            if (HAS_EF) {
-                nea = *reinterpret_cast<const float4*>(e + nbase);
-                neb = *reinterpret_cast<const float4*>(e + nbase + 64);
-            }
-        }
-        for (int c = c_begin; c < c_end; ++c) {
-            const int base = c * kChunk + lane_off;
-            float4 a = na, b = nb;
-            const float4 ea = nea, eb = neb;
-            if (c + 1 < c_end) {
-                const int nbase = base + kChunk;
-                na = *reinterpret_cast<const float4*>(g + nbase);
-                nb = *reinterpret_cast<const float4*>(g + nbase + 64);
-                if (HAS_EF) {
-                    nea = *reinterpret_cast<const float4*>(e + nbase);
-                    neb = *reinterpret_cast<const float4*>(e + nbase + 64);
-                }
-            }
+        // One chunk: 8 elements per lane (a: elements 4j..4j+3 of the lane's bucket, b: 64+4j..).
+        auto chunk = [&](float4 a, float4 b, const float4 ea, const float4 eb, const int base)
+            __attribute__((always_inline)) {
             if (HAS_EF) {
                 a.x += ea.x; a.y += ea.y; a.z += ea.z; a.w += ea.w;
                 b.x += eb.x; b.y += eb.y; b.z += eb.z; b.w += eb.w;
@@ -113,18 +92,21 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             if (HIST) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
-                    col.take(x[k], true);
+                    // the masked pattern serves the comparison and, shifted, is the bin's byte offset
+                    uint32_t key = __float_as_uint(x[k]) & Collector::kKeyMask;
+                    asm("" : "+v"(key));
+                    atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_hist) + (key >> (kHistShift - 2))),
+                              1u);
+                    col.take_keyed(x[k], key, true);
                 }
             }
-            float mn = fminf(fminf(fminf(x[0], x[1]), fminf(x[2], x[3])),
-                             fminf(fminf(x[4], x[5]), fminf(x[6], x[7])));
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            mn = row16_min(mn);
-            mx = row16_max(mx);
+            float mn = fminf(min3f(min3f(min3f(x[0], x[1], x[2]), x[3], x[4]), x[5], x[6]), x[7]);
+            float mx = fmaxf(max3f(max3f(max3f(x[0], x[1], x[2]), x[3], x[4]), x[5], x[6]), x[7]);
+            row16_minmax(mn, mx);
             const float r = mx - mn;
-            const float dv = want_inv ? safe_inv(mylv, r) : r / mylv;
+            // one division per lane: r / lv (unit) or lv / r (inv, replaced by 0 when not finite)
+            float dv = (want_inv ? mylv : r) / (want_inv ? r : mylv);
+            if (want_inv && !(__builtin_fabsf(dv) <= 3.402823466e38f)) dv = 0.0f;
 
             float u[8];
             if (STOCH) {
@@ -159,6 +141,29 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             LGRECO_CAND(0) LGRECO_CAND(1) LGRECO_CAND(2) LGRECO_CAND(3)
             LGRECO_CAND(4) LGRECO_CAND(5) LGRECO_CAND(6) LGRECO_CAND(7)
 #undef LGRECO_CAND
+        };
+        // Two register sets take turns: while one chunk is worked on, the loads of the next are in
+        // flight.  Past the range's end the last chunk is loaded once more and not used.
+        const int lane_off = (lane >> 4) * kBucket + j * 4;
+        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        auto load = [&](const int c, float4& a, float4& b, float4& ea, float4& eb)
+            __attribute__((always_inline)) {
+            const int base = min(c, c_end - 1) * kChunk + lane_off;
+            a = *reinterpret_cast<const float4*>(g + base);
+            b = *reinterpret_cast<const float4*>(g + base + 64);
+            ea = HAS_EF ? *reinterpret_cast<const float4*>(e + base) : zero4;
+            eb = HAS_EF ? *reinterpret_cast<const float4*>(e + base + 64) : zero4;
+        };
+        if (c_begin < c_end) {
+            float4 a0, b0, ea0, eb0, a1, b1, ea1, eb1;
+            load(c_begin, a0, b0, ea0, eb0);
+            for (int c = c_begin; c < c_end; c += 2) {
+                load(c + 1, a1, b1, ea1, eb1);
+                chunk(a0, b0, ea0, eb0, c * kChunk + lane_off);
+                if (c + 1 >= c_end) break;
+                load(c + 2, a0, b0, ea0, eb0);
+                chunk(a1, b1, ea1, eb1, (c + 1) * kChunk + lane_off);
+            }
         }
     } else {
         // Slow path (tail of a layer, or a layer that is not 16-byte aligned): one wavefront per

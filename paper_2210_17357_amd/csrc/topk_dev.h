@@ -23,25 +23,34 @@ struct Collector {
     uint32_t* dst;
     uint32_t* dst_idx;   // optional: index (within the layer) and sign of every candidate
     uint32_t lo;
+    uint32_t lo_key;   // lo moved to the key's place in the pattern (all ones: nothing qualifies)
     uint32_t cur;      // candidates written so far (uniform over the wavefront)
     float base;        // this lane's sum of x^2 over elements below lo
+    static constexpr uint32_t kKeyMask = (uint32_t)(kHistBins - 1) << kHistShift;
     __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t l) {
         dst = d; dst_idx = di; lo = l; cur = 0; base = 0.0f;
+        lo_key = (l >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (l << kHistShift);
     }
     __device__ __forceinline__ static uint32_t below(unsigned long long m, uint32_t add) {
         return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, add));
     }
     // one element per lane
     __device__ __forceinline__ void take(float x, bool valid, uint32_t idx = 0) {
-        const uint32_t pat = mag_bits(x);
-        const bool hit = valid && (pat >> kHistShift) >= lo;
+        take_keyed(x, __float_as_uint(x) & kKeyMask, valid, idx);
+    }
+    // the same with the coarse key (pattern & kKeyMask) supplied by the caller
+    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid, uint32_t idx = 0) {
+        const uint32_t bits = __float_as_uint(x);
+        const bool hit = valid && key >= lo_key;
         const unsigned long long m = __ballot(hit);
+        const float low = (hit || !valid) ? 0.0f : x;     // the energy below lo, without a branch
+        base = __builtin_fmaf(low, low, base);
         if (hit) {
-            const uint32_t at = cur + below(m, 0u);
-            dst[at] = pat;
-            if (dst_idx) dst_idx[at] = idx | (__float_as_uint(x) & 0x80000000u);
-        } else if (valid) {
-            base = __builtin_fmaf(x, x, base);
+            // byte offset in 32 bits (a slice holds fewer than 2^30 entries): uniform base + lane offset
+            const uint32_t off = (below(m, 0u) + cur) << 2;
+            *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(dst) + off) = bits & 0x7FFFFFFFu;
+            if (dst_idx)
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(dst_idx) + off) = idx | (bits & 0x80000000u);
         }
         cur += (uint32_t)__popcll(m);
     }
