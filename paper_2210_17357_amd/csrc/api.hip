@@ -31,18 +31,19 @@ struct lgreco_handle {
     int32_t max_tiles = 0;
     int32_t tile_elems = kTile;     // tile size of the current layer table
     double* d_partials = nullptr;   // [max_tiles x max_cands]
-    double* d_errors = nullptr;     // [max_layers x max_cands]
-    double* h_errors = nullptr;     // pinned mirror
+    double* h_errors = nullptr;     // [max_layers x max_cands], pinned host memory
+    double* d_errors = nullptr;     // the same memory as the kernels address it
 
     TopkScratch topk;
     LowrankScratch lowrank;
 
     // solver
-    // input block [count | entries] and output block [result | choice]: one copy each way
+    // input block [count | entries]: one upload; output block [result | choice]: pinned host
+    // memory the kernel writes
     uint8_t* d_dp_in = nullptr;
     uint8_t* h_dp_in = nullptr;     // pinned
-    uint8_t* d_dp_out = nullptr;
     uint8_t* h_dp_out = nullptr;    // pinned
+    uint8_t* d_dp_out = nullptr;    // h_dp_out as the kernel addresses it
     size_t dp_entries_off = 0;      // byte offset of the entries inside the input block
     DpEntry* d_entries = nullptr;   // views into the blocks
     int32_t* d_count = nullptr;
@@ -251,17 +252,19 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_layers, sizeof(DevLayer) * max_layers));
     HIPCHK_C(hipMalloc(&h->d_tiles, sizeof(Tile) * h->max_tiles));
     HIPCHK_C(hipMalloc(&h->d_partials, sizeof(double) * (size_t)h->max_tiles * max_cands));
-    HIPCHK_C(hipMalloc(&h->d_errors, sizeof(double) * (size_t)max_layers * max_cands));
+    // Small results (the error table, the solver's output) are written by the kernels straight into
+    // pinned host memory: no copy operation between the last kernel and the host's wait.
     HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
+    HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_errors), h->h_errors, 0));
     const size_t lp = (size_t)max_layers * max_cands;
     h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
     h->dp_entries_off = (sizeof(int32_t) * (size_t)max_layers + 15) / 16 * 16;
     const size_t dp_in = h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS;
     const size_t dp_out = sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)max_layers;
     HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
-    HIPCHK_C(hipMalloc(&h->d_dp_out, dp_out));
     HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
     HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
+    HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_dp_out), h->h_dp_out, 0));
     h->d_count = reinterpret_cast<int32_t*>(h->d_dp_in);
     h->d_entries = reinterpret_cast<DpEntry*>(h->d_dp_in + h->dp_entries_off);
     h->h_count = reinterpret_cast<int32_t*>(h->h_dp_in);
@@ -290,10 +293,8 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipFree(h->d_layers);
     (void)hipFree(h->d_tiles);
     (void)hipFree(h->d_partials);
-    (void)hipFree(h->d_errors);
     (void)hipHostFree(h->h_errors);
     (void)hipFree(h->d_dp_in);
-    (void)hipFree(h->d_dp_out);
     (void)hipFree(h->d_pd);
     (void)hipHostFree(h->h_bins);
     (void)hipHostFree(h->h_dp_in);
@@ -469,7 +470,7 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         qp.seed_hi = (uint32_t)(h->cfg.seed >> 32);
         if (ntk) {
             qp.hist = h->topk.d_hist;
-            qp.lo = h->topk.d_lo;
+            qp.lo = h->topk.lo_src;
             qp.cand = h->topk.d_cand;
             qp.cand_base = h->topk.d_cand_base;
             qp.tinfo = h->topk.d_tinfo;
@@ -482,8 +483,8 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
         HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
     }
     if (ntk)
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true, &h->tm,
-                           s));
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
+                           ntk_all <= (int)kMaxTopk, &h->tm, s));
     if (qp.nq) {
         Section sec(&h->tm, "reduce_partials");
         HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, h->d_errors, s));
@@ -492,16 +493,15 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false, &h->tm,
-                           s));
+        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
+                           first + (int)kMaxTopk >= ntk_all, &h->tm, s));
         HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, &h->tm, s));
     }
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
                                lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));
     }
-    HIPCHK(hipMemcpyAsync(h->h_errors, h->d_errors, sizeof(double) * (size_t)L * P, hipMemcpyDeviceToHost, s));
-    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipStreamSynchronize(s));      // the kernels wrote h_errors
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     return LGRECO_OK;
 }
@@ -606,9 +606,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
             Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
         }
-        HIPCHK(hipMemcpyAsync(h->h_dp_out, h->d_dp_out, sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)n_sweep,
-                              hipMemcpyDeviceToHost, s));
-        HIPCHK(hipStreamSynchronize(s));
+        HIPCHK(hipStreamSynchronize(s));  // the kernel wrote h_dp_out
         if (h->tm.level >= 1) {                       // 100 MHz constant-rate device counter
             h->sub_name[0] = "dp_solve.sweep";
             h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);

@@ -77,6 +77,8 @@ struct TopkScratch {
     uint32_t* d_hint[2] = {nullptr, nullptr};   // per kind of call: bound derived from the last thresholds
     bool hint_valid[2] = {false, false};
     bool reuse_thresholds = false;
+    const uint32_t* lo_src = nullptr; // bound the main pass of this call collects with: d_lo or a d_hint
+    bool hist_clean = false;          // the exact histogram is all zero (the last scan of a call clears it)
     int cur_slot = 0;
     int64_t* d_cand_base = nullptr;   // [max_layers] first candidate slot of every layer
     void* d_tilecnt = nullptr;        // per tile (above, equal) counts (compress)
@@ -120,8 +122,8 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
 // exact threshold bins from the histogram; layers whose predicted bound was too high are
 // collected again with the exact one
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                       const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, Timing* tm,
-                       hipStream_t s);
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, bool last_group,
+                       Timing* tm, hipStream_t s);
 // refinement on the candidates: exact thresholds; writes the dropped energy to errors (if not null)
 hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
                          const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);

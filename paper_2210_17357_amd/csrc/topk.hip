@@ -237,7 +237,7 @@ struct CollectParams {
     const Tile* tiles;
     const uint32_t* ks;
     const TopkLayer* tl;        // only_flagged: layers to collect again
-    uint32_t* lo;
+    const uint32_t* lo;
     uint32_t* hist;
     uint32_t* cand;
     uint32_t* cand_idx;         // compress: index within the layer and sign of every candidate
@@ -337,11 +337,11 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
 
 // One workgroup per layer: threshold bin and in-bin rank for every requested k; threshold-bin
 // lists; check of the predicted bound.
-__global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restrict__ hist,
+__global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ hist,
                                                         const uint32_t* __restrict__ ks, int ntk,
                                                         const int64_t* __restrict__ cand_base,
-                                                        uint32_t* __restrict__ lo, TopkLayer* __restrict__ tl,
-                                                        uint32_t* __restrict__ hint) {
+                                                        const uint32_t* lo_in, uint32_t* lo_out,
+                                                        TopkLayer* __restrict__ tl, uint32_t* hint, int clear) {
     __shared__ uint32_t s_hist[kHistBins];
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
@@ -351,11 +351,17 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
         if (threadIdx.x == 0) {
             T.nlists = 0; T.min_tbin = 0; T.recollect = 0;
             for (int j = 0; j < kMaxTopk; ++j) T.sel[j].k = 0;
+            lo_out[l] = lo_in[l];
             if (hint) hint[l] = 0xFFFFFFFFu;
         }
+        if (clear)
+            for (int b = threadIdx.x; b < kHistBins; b += 256) hist[(size_t)l * kHistBins + b] = 0u;
         return;
     }
-    for (int b = threadIdx.x; b < kHistBins; b += 256) s_hist[b] = hist[(size_t)l * kHistBins + b];
+    for (int b = threadIdx.x; b < kHistBins; b += 256) {
+        s_hist[b] = hist[(size_t)l * kHistBins + b];
+        if (clear) hist[(size_t)l * kHistBins + b] = 0u;     // the next call's main pass starts from zero
+    }
     __syncthreads();
     for (int j = 0; j < ntk; ++j) {
         const uint32_t k = ks[(size_t)l * kMaxTopk + j];
@@ -388,8 +394,10 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const uint32_t* __restri
         T.min_tbin = mn;
         T.cand_base = cand_base[l];
         // every element at or above the lowest threshold bin must be among the candidates
-        T.recollect = lo[l] > mn ? 1u : 0u;
-        if (T.recollect) lo[l] = mn;
+        // (lo_in may be the same array as hint: it is read before hint is written)
+        const uint32_t used = lo_in[l];
+        T.recollect = used > mn ? 1u : 0u;
+        lo_out[l] = T.recollect ? mn : used;
         // collection bound for the next call of this kind: one coarse bin (4.4 % in magnitude)
         // under the lowest threshold found now
         if (hint) hint[l] = mn > kHintMargin ? mn - kHintMargin : 0u;
@@ -807,6 +815,10 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     t->max_layers = max_layers;
     t->max_tiles = max_tiles;
     TK_CHECK(hipMalloc(&t->d_hist, sizeof(uint32_t) * 2 * (size_t)max_layers * kHistBins));   // exact + sample
+    // Between calls the exact histogram is all zero: cleared here once, and by the last scan of every
+    // call for the layers that call counted.  hist_clean is false only after a call that failed midway.
+    TK_CHECK(hipMemset(t->d_hist, 0, sizeof(uint32_t) * 2 * (size_t)max_layers * kHistBins));
+    t->hist_clean = true;
     TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
@@ -918,24 +930,29 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
     TK_CHECK(upload_ctl(t, slot, s, &changed));
     t->cur_slot = slot;
     Section sec(tm, "topk_sample");
-    uint32_t* const shist = t->d_hist + (size_t)L * kHistBins;
+    // the sample's histogram has its own half of the buffer, whatever L is: a call never leaves
+    // counts where a later call with more layers expects a cleared exact histogram
+    uint32_t* const shist = t->d_hist + (size_t)t->max_layers * kHistBins;
+    auto fill = [&](uint32_t* dst, size_t n) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
+                           dst, n, 0u);
+        return hipGetLastError();
+    };
     if (t->reuse_thresholds && t->hint_valid[slot] && !changed) {
         // Same layers and the same k as the previous call of this kind: start from the thresholds
         // it found, a margin lower, instead of sampling.  The scan still checks the bound against
-        // the exact histogram and collects a layer again if the data moved past the margin.
-        const size_t n = (size_t)L * kHistBins;
-        hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
-                           t->d_hist, n, 0u);
-        TK_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(copy_u32_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0, s, t->d_lo,
-                           (const uint32_t*)t->d_hint[slot], (size_t)L);
-        return hipGetLastError();
+        // the exact histogram and collects a layer again if the data moved past the margin.  The
+        // previous call's last scan left the histogram cleared, so no kernel runs before the main pass.
+        t->lo_src = t->d_hint[slot];
+        if (!t->hist_clean) TK_CHECK(fill(t->d_hist, (size_t)t->max_layers * kHistBins));
+        t->hist_clean = false;
+        return hipSuccess;
     }
+    t->lo_src = t->d_lo;
     t->hint_valid[slot] = false;
-    const size_t n = 2 * (size_t)L * kHistBins;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 2048)), dim3(256), 0, s,
-                       t->d_hist, n, 0u);
-    TK_CHECK(hipGetLastError());
+    if (!t->hist_clean) TK_CHECK(fill(t->d_hist, (size_t)t->max_layers * kHistBins));
+    t->hist_clean = false;
+    TK_CHECK(fill(shist, (size_t)L * kHistBins));
     if (nw > 0) {
         hipLaunchKernelGGL(topk_sample_kernel, dim3(nw), dim3(kThreads), 0, s, g, e, d_layers, d_tiles,
                            (const RefWork*)t->d_work, std::max(1, tile_elems / kChunk / kSampleEvery), shist);
@@ -955,7 +972,7 @@ static CollectParams collect_params(TopkScratch* t, const float* g, const float*
     p.tiles = d_tiles;
     p.ks = t->d_k;
     p.tl = (const TopkLayer*)t->d_tl;
-    p.lo = t->d_lo;
+    p.lo = t->lo_src;
     p.hist = t->d_hist;
     p.cand = t->d_cand;
     p.cand_idx = t->d_cand_idx;
@@ -981,17 +998,19 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
 
 // exact threshold bins; layers whose predicted bound was too high are collected again
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                       const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, Timing* tm,
-                       hipStream_t s) {
+                       const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, bool last_group,
+                       Timing* tm, hipStream_t s) {
     {
         Section sec(tm, "topk_scan");
         // the first group of a call holds the lowest thresholds: it leaves the bound for the next call
         uint32_t* const hint = (first_group && t->reuse_thresholds) ? t->d_hint[t->cur_slot] : nullptr;
-        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, (const uint32_t*)t->d_hist,
-                           (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base, t->d_lo,
-                           (TopkLayer*)t->d_tl, hint);
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, t->d_hist, (const uint32_t*)t->d_k, ntk,
+                           (const int64_t*)t->d_cand_base, first_group ? t->lo_src : (const uint32_t*)t->d_lo,
+                           t->d_lo, (TopkLayer*)t->d_tl, hint, last_group ? 1 : 0);
         TK_CHECK(hipGetLastError());
         if (hint) t->hint_valid[t->cur_slot] = true;
+        if (last_group) t->hist_clean = true;
+        t->lo_src = t->d_lo;                     // a second collection uses the bound the scan wrote
     }
     {
         Section sec(tm, "topk_recollect");
@@ -1070,7 +1089,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
     }
-    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, tm, s));
+    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
