@@ -42,6 +42,7 @@ struct lgreco_handle {
     // memory the kernel writes
     uint8_t* d_dp_in = nullptr;
     uint8_t* h_dp_in = nullptr;     // pinned
+    const uint4* d_dp_in_host = nullptr;   // h_dp_in as the kernel addresses it
     uint8_t* h_dp_out = nullptr;    // pinned
     uint8_t* d_dp_out = nullptr;    // h_dp_out as the kernel addresses it
     size_t dp_entries_off = 0;      // byte offset of the entries inside the input block
@@ -259,12 +260,13 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     const size_t lp = (size_t)max_layers * max_cands;
     h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
     h->dp_entries_off = (sizeof(int32_t) * (size_t)max_layers + 15) / 16 * 16;
-    const size_t dp_in = h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS;
+    const size_t dp_in = (h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS + 15) / 16 * 16;
     const size_t dp_out = sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)max_layers;
     HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
     HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
     HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_dp_out), h->h_dp_out, 0));
+    HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(const_cast<uint4**>(&h->d_dp_in_host)), h->h_dp_in, 0));
     h->d_count = reinterpret_cast<int32_t*>(h->d_dp_in);
     h->d_entries = reinterpret_cast<DpEntry*>(h->d_dp_in + h->dp_entries_off);
     h->h_count = reinterpret_cast<int32_t*>(h->h_dp_in);
@@ -598,10 +600,10 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         for (int i = 0; i < n_sweep; ++i)
             std::memcpy(h->h_entries + (size_t)i * max_count,
                         h->build_entries.data() + (size_t)i * LGRECO_MAX_CANDS, sizeof(DpEntry) * max_count);
-        HIPCHK(hipMemcpyAsync(h->d_dp_in, h->h_dp_in,
-                              h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count,
-                              hipMemcpyHostToDevice, s));
-        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count};
+        // the kernel itself fetches the input block from the pinned staging memory
+        const size_t in_bytes = h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count;
+        DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
+                    h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16)};
         {
             Section sec(&h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));

@@ -74,6 +74,12 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);
 
     const uint64_t t_begin = wall_clock64();
+    if (p.host_in) {
+        // fetch the input block from the host's pinned memory: one 16-byte word per thread and
+        // round, all in flight together; the barrier below orders it before the first read
+        for (int i = tid; i < p.in_vec; i += kDpThreads) p.dev_in[i] = p.host_in[i];
+        __threadfence_block();
+    }
     for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
 
     const int stage = min(kDpStageMax, kDpStageEntries / bstride);     // layers per stage

@@ -61,6 +61,12 @@ struct DpParams {
     int32_t pd_stride;        // set by launch_dp: bytes per PD row, a multiple of 4 and >= D + 2
     int32_t bt_lds;           // set by launch_dp: back-trace tables live in LDS behind the row
     int32_t max_count;        // largest entry count of a swept layer = row stride of `entries`
+    // The input block (count | entries) as the host wrote it in pinned memory and its place in
+    // device memory: the kernel's first step copies it over (in_vec 16-byte words), which saves
+    // the separate copy operation and the wait between it and the kernel.  Null: nothing to copy.
+    const uint4* host_in;
+    uint4* dev_in;
+    int32_t in_vec;
 };
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
 // max_bin: largest bin in entries

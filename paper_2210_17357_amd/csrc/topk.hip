@@ -55,42 +55,72 @@ constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sample
 constexpr uint32_t kHintMargin = 1; // coarse bins between a remembered threshold and the bound derived from it
 
 // ------------------------------------------------------------------------ block helpers
-// Largest bin b with (number of entries in bins >= b) >= need.  `above` = entries in bins > b.
-// hist lives in LDS, nbins <= 16 * 256.  Every thread of the block calls (the first 256 work, the
-// rest only join the barriers); result broadcast through res[2]; scan[0] is left holding the
-// total.  If fewer than `need` entries exist, res = {0, total - hist[0]}.
-__device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scan,
-                                   uint32_t* res) {
+// Suffix sums of a histogram in LDS over the block's first 256 threads: thread t owns the bins
+// [t * per, (t + 1) * per) and scan[t] becomes the number of entries in its bins and all higher
+// ones (scan[0] = total).  nbins <= 16 * 256.  Every thread of the block calls; the threads past
+// the first 256 only join the barriers.
+__device__ void block_suffix(const uint32_t* hist, int nbins, uint32_t* scan) {
+    __shared__ uint32_t wtot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool act = tid < 256;
+    const int per = (nbins + 255) / 256;
+    const int lo = min(tid * per, nbins), hi = min(lo + per, nbins);
+    uint32_t inc = 0;
+    if (act)
+        for (int b = lo; b < hi; ++b) inc += hist[b];
+    for (int o = 1; o < 64; o <<= 1) {        // inclusive suffix scan inside the wavefront
+        const uint32_t n = __shfl_down(inc, o, 64);
+        if (lane + o < 64) inc += n;
+    }
+    if (act && lane == 0) wtot[wave] = inc;
+    __syncthreads();
+    if (act) {
+        for (int w = wave + 1; w < 4; ++w) inc += wtot[w];
+        scan[tid] = inc;
+    }
+    __syncthreads();
+}
+
+// After block_suffix: for each of n requests, the largest bin b with (entries in bins >= b) >=
+// need[j], and `above` = entries in bins > b, written to res[2j], res[2j+1].  If fewer than need[j]
+// entries exist, {0, total - hist[0]}.
+template <int N>
+__device__ void block_find(const uint32_t* hist, int nbins, const uint32_t (&need)[N], int n, const uint32_t* scan,
+                           uint32_t* res) {
     const int tid = threadIdx.x;
     const bool act = tid < 256;
     const int per = (nbins + 255) / 256;
     const int lo = min(tid * per, nbins), hi = min(lo + per, nbins);
-    uint32_t s = 0;
-    if (act) {
-        for (int b = lo; b < hi; ++b) s += hist[b];
-        scan[tid] = s;
+    if (tid == 0) {
+        const uint32_t rest = scan[0] - hist[0];
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j < n) { res[2 * j] = 0; res[2 * j + 1] = rest; }
     }
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {       // inclusive suffix scan over threads
-        const uint32_t v = (act && tid + o < 256) ? scan[tid + o] : 0;
-        __syncthreads();
-        if (act) scan[tid] += v;
-        __syncthreads();
-    }
-    if (tid == 0) { res[0] = 0; res[1] = scan[0] - hist[0]; }
     __syncthreads();
     if (act) {
         uint32_t running = (tid + 1 < 256) ? scan[tid + 1] : 0;
         for (int b = hi - 1; b >= lo; --b) {
             const uint32_t c = hist[b];
-            if (running < need && running + c >= need) {
-                res[0] = (uint32_t)b;
-                res[1] = running;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                if (j < n && running < need[j] && running + c >= need[j]) {
+                    res[2 * j] = (uint32_t)b;
+                    res[2 * j + 1] = running;
+                }
             }
             running += c;
         }
     }
     __syncthreads();
+}
+
+// One request: result broadcast through res[2]; scan[0] is left holding the total.
+__device__ void block_kth_from_top(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scan,
+                                   uint32_t* res) {
+    block_suffix(hist, nbins, scan);
+    const uint32_t one[1] = {need};
+    block_find<1>(hist, nbins, one, 1, scan, res);
 }
 
 // Exclusive scan of one uint32 per thread over the 256-thread block; returns the prefix and the
@@ -344,7 +374,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
                                                         TopkLayer* __restrict__ tl, uint32_t* hint, int clear) {
     __shared__ uint32_t s_hist[kHistBins];
     __shared__ uint32_t s_scan[256];
-    __shared__ uint32_t s_res[2];
+    __shared__ uint32_t s_res[2 * kMaxTopk];
     const int l = blockIdx.x;
     TopkLayer& T = tl[l];
     if (ks[(size_t)l * kMaxTopk] == 0) {
@@ -363,45 +393,52 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
         if (clear) hist[(size_t)l * kHistBins + b] = 0u;     // the next call's main pass starts from zero
     }
     __syncthreads();
-    for (int j = 0; j < ntk; ++j) {
-        const uint32_t k = ks[(size_t)l * kMaxTopk + j];
-        block_kth_from_top(s_hist, kHistBins, k, s_scan, s_res);
-        if (threadIdx.x == 0) {
-            TopkSel& S = T.sel[j];
-            S.k = k;
-            S.tbin = s_res[0];
-            S.need = k - s_res[1];
-            S.thr = 0; S.ties_keep = 0; S.bin_a = 0; S.need_a = 0;
-        }
-        __syncthreads();
-    }
+    // one suffix scan of the histogram serves every requested k
+    uint32_t kk[kMaxTopk];
+#pragma unroll
+    for (int j = 0; j < kMaxTopk; ++j) kk[j] = j < ntk ? ks[(size_t)l * kMaxTopk + j] : 0u;
+    block_suffix(s_hist, kHistBins, s_scan);
+    block_find<kMaxTopk>(s_hist, kHistBins, kk, ntk, s_scan, s_res);
+    // the layer's record is put together in LDS and written out by the whole workgroup
+    __shared__ TopkLayer sT;
     if (threadIdx.x == 0) {
         uint32_t nl = 0, mn = 0xFFFFFFFFu;
-        for (int j = 0; j < ntk; ++j) {
-            TopkSel& S = T.sel[j];
+        for (int j = 0; j < kMaxTopk; ++j) {
+            TopkSel& S = sT.sel[j];
+            S = TopkSel{};
+            if (j >= ntk) continue;
+            const uint32_t k = ks[(size_t)l * kMaxTopk + j];
+            S.k = k;
+            S.tbin = s_res[2 * j];
+            S.need = k - s_res[2 * j + 1];
             uint32_t u = nl;
             for (uint32_t q = 0; q < nl; ++q)
-                if (T.lists[q].bin == S.tbin) u = q;
+                if (sT.lists[q].bin == S.tbin) u = q;
             if (u == nl) {
-                T.lists[nl] = TopkList{S.tbin, s_hist[S.tbin]};
+                sT.lists[nl] = TopkList{S.tbin, s_hist[S.tbin]};
                 ++nl;
             }
             S.list = u;
             mn = min(mn, S.tbin);
         }
-        for (int j = ntk; j < kMaxTopk; ++j) T.sel[j].k = 0;
-        T.nlists = nl;
-        T.min_tbin = mn;
-        T.cand_base = cand_base[l];
+        for (uint32_t q = nl; q < (uint32_t)kMaxTopk; ++q) sT.lists[q] = TopkList{0u, 0u};
+        sT.nlists = nl;
+        sT.min_tbin = mn;
+        sT.cand_base = cand_base[l];
         // every element at or above the lowest threshold bin must be among the candidates
         // (lo_in may be the same array as hint: it is read before hint is written)
         const uint32_t used = lo_in[l];
-        T.recollect = used > mn ? 1u : 0u;
-        lo_out[l] = T.recollect ? mn : used;
+        sT.recollect = used > mn ? 1u : 0u;
+        sT.pad = 0;
+        lo_out[l] = sT.recollect ? mn : used;
         // collection bound for the next call of this kind: one coarse bin (4.4 % in magnitude)
         // under the lowest threshold found now
         if (hint) hint[l] = mn > kHintMargin ? mn - kHintMargin : 0u;
     }
+    __syncthreads();
+    static_assert(sizeof(TopkLayer) % 4 == 0, "copied as 32-bit words");
+    for (int w = threadIdx.x; w < (int)(sizeof(TopkLayer) / 4); w += 256)
+        reinterpret_cast<uint32_t*>(&T)[w] = reinterpret_cast<const uint32_t*>(&sT)[w];
 }
 
 struct RefineParams {
