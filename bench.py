@@ -134,18 +134,20 @@ def main():
     phase = {"profile": 0.0, "solve": 0.0, "compress": 0.0}
     last = {}
 
+    stream = torch.cuda.current_stream().cuda_stream      # the stream every call of the run is given
+
     def step(i, record):
         ef = ef_pool[i]
         t0 = time.perf_counter()
-        errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True)
+        errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
         tm_p = h.get_timing() if record and not args.no_kernel_timing else []
         t1 = time.perf_counter()
         e_max = B.emax(errors, w.default)
-        st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins)
+        st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
         tm_s = h.get_timing() if record and not args.no_kernel_timing else []
         t2 = time.perf_counter()
         offsets = B.payload_layout(layers, ctab, choice, w.bucket)
-        h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i])
+        h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
         tm_c = h.get_timing() if record and not args.no_kernel_timing else []
         t3 = time.perf_counter()
         if record:

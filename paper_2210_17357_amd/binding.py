@@ -110,7 +110,10 @@ def _dptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
-def _stream() -> int:
+def _stream(stream=None) -> int:
+    """The HIP stream handle to pass on: the one given, else torch's current stream."""
+    if stream is not None:
+        return int(stream)
     import torch
     return torch.cuda.current_stream().cuda_stream
 
@@ -189,29 +192,31 @@ class Handle:
             raise LgrecoError(st, text)
         return st
 
-    def profile(self, d_grads, d_ef, layers, cands, d_q0=None, want_sizes: bool = True):
+    # Every GPU entry point takes `stream`: a HIP stream handle (int); default: torch's current stream.
+
+    def profile(self, d_grads, d_ef, layers, cands, d_q0=None, want_sizes: bool = True, stream=None):
         L, P = len(layers), len(cands)
         errors = np.zeros((L, P), np.float64)
         szs = np.zeros((L, P), np.int64) if want_sizes else None
         st = lib().lgreco_profile(self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), L,
                                   C.addressof(cands), P, _dptr(d_q0), _np(errors),
-                                  _np(szs) if want_sizes else None, _stream())
+                                  _np(szs) if want_sizes else None, _stream(stream))
         self._check(st)
         return errors, szs
 
-    def solve(self, errors: np.ndarray, szs: np.ndarray, e_max: float, n_bins: int):
+    def solve(self, errors: np.ndarray, szs: np.ndarray, e_max: float, n_bins: int, stream=None):
         errors = np.ascontiguousarray(errors, np.float64)
         szs = np.ascontiguousarray(szs, np.int64)
         L, P = errors.shape
         choice = np.zeros(L, np.int32)
         tsize, terr = C.c_int64(), C.c_double()
         st = lib().lgreco_solve(self._h, _np(errors), _np(szs), L, P, float(e_max), int(n_bins),
-                                _np(choice), C.byref(tsize), C.byref(terr), _stream())
+                                _np(choice), C.byref(tsize), C.byref(terr), _stream(stream))
         self._check(st, allow=(EINFEASIBLE,))
         return st, choice, tsize.value, terr.value
 
     def solve_weighted(self, errors: np.ndarray, szs: np.ndarray, weights: np.ndarray, e_max: float,
-                       n_bins: int):
+                       n_bins: int, stream=None):
         errors = np.ascontiguousarray(errors, np.float64)
         szs = np.ascontiguousarray(szs, np.int64)
         weights = np.ascontiguousarray(weights, np.int64)
@@ -220,33 +225,33 @@ class Handle:
         tsize, tcost, terr = C.c_int64(), C.c_int64(), C.c_double()
         st = lib().lgreco_solve_weighted(self._h, _np(errors), _np(szs), _np(weights), L, P, float(e_max),
                                          int(n_bins), _np(choice), C.byref(tsize), C.byref(tcost),
-                                         C.byref(terr), _stream())
+                                         C.byref(terr), _stream(stream))
         self._check(st, allow=(EINFEASIBLE,))
         return st, choice, tsize.value, tcost.value, terr.value
 
     def compress(self, d_grads, d_ef, layers, cands, choice: np.ndarray, d_payload, offsets: np.ndarray,
-                 d_q=None):
+                 d_q=None, stream=None):
         choice = np.ascontiguousarray(choice, np.int32)
         offsets = np.ascontiguousarray(offsets, np.int64)
         st = lib().lgreco_compress(self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), len(layers),
                                    C.addressof(cands), len(cands), _np(choice), _dptr(d_q),
-                                   _dptr(d_payload), _np(offsets), _stream())
+                                   _dptr(d_payload), _np(offsets), _stream(stream))
         self._check(st)
 
     def decompress(self, d_payload, offsets: np.ndarray, layers, cands, choice: np.ndarray, d_out,
-                   accumulate: bool = False):
+                   accumulate: bool = False, stream=None):
         choice = np.ascontiguousarray(choice, np.int32)
         offsets = np.ascontiguousarray(offsets, np.int64)
         st = lib().lgreco_decompress(self._h, _dptr(d_payload), _np(offsets), C.addressof(layers), len(layers),
                                      C.addressof(cands), len(cands), _np(choice), _dptr(d_out),
-                                     int(bool(accumulate)), _stream())
+                                     int(bool(accumulate)), _stream(stream))
         self._check(st)
 
-    def accumulate(self, d_acc, d_grads, reset: bool = False):
+    def accumulate(self, d_acc, d_grads, reset: bool = False, stream=None):
         if d_acc.numel() != d_grads.numel():
             raise ValueError("buffers differ in size")
         self._check(lib().lgreco_accumulate(self._h, _dptr(d_acc), _dptr(d_grads), int(d_grads.numel()),
-                                            int(bool(reset)), _stream()))
+                                            int(bool(reset)), _stream(stream)))
 
     def set_timing(self, level):
         """0 / False: off; 1 / True: main kernels; 2: every section."""

@@ -498,32 +498,81 @@ __device__ __forceinline__ unsigned long long packed_cell(uint32_t pat) {
     return (((m * m) >> kPackEnergyShift) << kPackCountBits) | 1ull;
 }
 
-// Refinement level A over the candidates of a run of tiles.  ENERGY (profile): per list (distinct
-// threshold bin) a histogram of bits 18..9 whose cells pack count and integer energy into one
-// 64-bit LDS atomic, and per requested k the energy of the candidates below its threshold bin
-// (fp32 per lane - a lane sees some tens of candidates - fp64 from the wavefront up).  Without
-// ENERGY (compress): counts only.  Partial histograms go to global memory with plain stores.
-template <bool ENERGY>
+// below[j] += x^2 for every j < NTK whose threshold bin lies above the candidate's key.  The
+// requested k do not increase with j, so the threshold bins do not decrease and the sets
+// {key < tb[j]} are nested: walking j downwards, each comparison narrows the set of active lanes
+// (a compare that writes the execution mask) and the add runs under it: two vector instructions
+// per k.  The mask is restored at the end; one asm statement, so nothing else runs under it.
+#define LG_BELOW_STEP(J) "v_cmpx_gt_u32 vcc, %[t" #J "], %[key]\n\tv_fmac_f32 %[b" #J "], %[x], %[x]\n\t"
+#define LG_BELOW_ASM(STEPS)                                                                          \
+    asm volatile("s_mov_b64 %[save], exec\n\t" STEPS "s_mov_b64 exec, %[save]"                       \
+                 : [b0] "+v"(b[0]), [b1] "+v"(b[1]), [b2] "+v"(b[2]), [b3] "+v"(b[3]), [b4] "+v"(b[4]), \
+                   [b5] "+v"(b[5]), [b6] "+v"(b[6]), [b7] "+v"(b[7]), [save] "=&s"(save)              \
+                 : [key] "v"(key), [x] "v"(x), [t0] "s"(tb[0]), [t1] "s"(tb[1]), [t2] "s"(tb[2]),      \
+                   [t3] "s"(tb[3]), [t4] "s"(tb[4]), [t5] "s"(tb[5]), [t6] "s"(tb[6]), [t7] "s"(tb[7]) \
+                 : "vcc")
+template <int NTK>
+__device__ __forceinline__ void below_chain(float (&b)[kMaxTopk], const uint32_t (&tb)[kMaxTopk], uint32_t key,
+                                            float x) {
+    static_assert(kMaxTopk == 8 && NTK >= 1 && NTK <= 8, "written out for 8");
+    unsigned long long save;
+    if constexpr (NTK == 1) LG_BELOW_ASM(LG_BELOW_STEP(0));
+    if constexpr (NTK == 2) LG_BELOW_ASM(LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+    if constexpr (NTK == 3) LG_BELOW_ASM(LG_BELOW_STEP(2) LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+    if constexpr (NTK == 4) LG_BELOW_ASM(LG_BELOW_STEP(3) LG_BELOW_STEP(2) LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+    if constexpr (NTK == 5)
+        LG_BELOW_ASM(LG_BELOW_STEP(4) LG_BELOW_STEP(3) LG_BELOW_STEP(2) LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+    if constexpr (NTK == 6)
+        LG_BELOW_ASM(LG_BELOW_STEP(5) LG_BELOW_STEP(4) LG_BELOW_STEP(3) LG_BELOW_STEP(2) LG_BELOW_STEP(1)
+                         LG_BELOW_STEP(0));
+    if constexpr (NTK == 7)
+        LG_BELOW_ASM(LG_BELOW_STEP(6) LG_BELOW_STEP(5) LG_BELOW_STEP(4) LG_BELOW_STEP(3) LG_BELOW_STEP(2)
+                         LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+    if constexpr (NTK == 8)
+        LG_BELOW_ASM(LG_BELOW_STEP(7) LG_BELOW_STEP(6) LG_BELOW_STEP(5) LG_BELOW_STEP(4) LG_BELOW_STEP(3)
+                         LG_BELOW_STEP(2) LG_BELOW_STEP(1) LG_BELOW_STEP(0));
+}
+#undef LG_BELOW_ASM
+#undef LG_BELOW_STEP
+
+// Refinement level A over the candidates of a run of tiles.  NTK > 0 (profile, NTK = number of
+// requested k): per list (distinct threshold bin) a histogram of bits 18..9 whose cells pack count
+// and integer energy into one 64-bit LDS atomic, and per requested k the energy of the candidates
+// below its threshold bin (fp32 per lane - a lane sees some tens of candidates - fp64 from the
+// wavefront up).  NTK = 0 (compress): counts only.  Which list a candidate belongs to comes from a
+// table over the 4096 coarse keys the workgroup builds first.  Partial histograms go to global
+// memory with plain stores.
+__host__ __device__ constexpr size_t refine_a_lds(int ntk, bool energy) {
+    return (size_t)ntk * kBinsA * (energy ? 8 : 4) + kHistBins;
+}
+template <int NTK>
 __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
+    constexpr bool ENERGY = NTK > 0;
     extern __shared__ unsigned char refine_smem[];
     __shared__ double s_red[kRefThreads / 64][kMaxTopk];
     const RefWork w = p.work[blockIdx.x];
     const int l = w.layer;
     const TopkLayer& T = p.tl[l];
     const int nlists = (int)T.nlists;
+    const int tid = threadIdx.x, ntk = p.ntk;
     unsigned long long* const s_cell = reinterpret_cast<unsigned long long*>(refine_smem);   // ENERGY
     uint32_t* const s_cnt = reinterpret_cast<uint32_t*>(refine_smem);                        // !ENERGY
-    const int tid = threadIdx.x, ntk = p.ntk;
+    uint8_t* const s_tab = refine_smem + (size_t)ntk * kBinsA * (ENERGY ? 8 : 4);
     for (int i = tid; i < nlists * kBinsA; i += kRefThreads) {
         if (ENERGY) s_cell[i] = 0; else s_cnt[i] = 0;
     }
-    // workgroup-uniform: threshold bin of every k (0 = inactive: nothing is below it) and the
-    // distinct threshold bins ("lists")
+    // workgroup-uniform: threshold bin of every k and the distinct threshold bins ("lists")
     uint32_t tb[kMaxTopk], lb[kMaxTopk];
 #pragma unroll
     for (int j = 0; j < kMaxTopk; ++j) {
-        tb[j] = (j < ntk && T.sel[j].k) ? T.sel[j].tbin : 0u;
+        tb[j] = __builtin_amdgcn_readfirstlane(j < ntk ? T.sel[j].tbin : 0u);
         lb[j] = j < nlists ? T.lists[j].bin : 0xFFFFFFFFu;
+    }
+    for (uint32_t key = tid; key < (uint32_t)kHistBins; key += kRefThreads) {
+        uint32_t hit = 0;               // 1 + index of the list whose bin the key is
+#pragma unroll
+        for (int j = 0; j < kMaxTopk; ++j) hit = key == lb[j] ? (uint32_t)(j + 1) : hit;
+        s_tab[key] = (uint8_t)hit;
     }
     __syncthreads();
     float below[kMaxTopk];
@@ -531,13 +580,8 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
     for (int j = 0; j < kMaxTopk; ++j) below[j] = 0.0f;
     for_each_candidate(p, T, w.t0, w.t1, [&](uint32_t pat) {
         const uint32_t key = pat >> kHistShift;
-        const float xf = __uint_as_float(pat);
-        uint32_t hit = 0;               // 1 + index of the list this candidate belongs to
-#pragma unroll
-        for (int j = 0; j < kMaxTopk; ++j) {
-            if (ENERGY) below[j] = __builtin_fmaf(key < tb[j] ? xf : 0.0f, xf, below[j]);
-            hit = key == lb[j] ? (uint32_t)(j + 1) : hit;
-        }
+        const uint32_t hit = s_tab[key];
+        if constexpr (ENERGY) below_chain<NTK>(below, tb, key, __uint_as_float(pat));
         if (hit) {
             const uint32_t b = (hit - 1) * kBinsA + ((pat >> 9) & (kBinsA - 1));
             if (ENERGY) atomicAdd(&s_cell[b], packed_cell(pat));
@@ -953,6 +997,12 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
     int nw = 0;
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < kMaxTopk; ++j) t->h_k[(size_t)l * kMaxTopk + j] = ks[(size_t)l * kMaxTopk + j];
+        // the refinement relies on this order: an active layer asks for ntk values of k, none larger
+        // than the one before it
+        if (ks[(size_t)l * kMaxTopk])
+            for (int j = 1; j < ntk; ++j)
+                if (ks[(size_t)l * kMaxTopk + j] == 0 || ks[(size_t)l * kMaxTopk + j] > ks[(size_t)l * kMaxTopk + j - 1])
+                    return hipErrorInvalidValue;
         t->h_cand_base[l] = base;
         wrange[l].x = nw;
         if (ks[(size_t)l * kMaxTopk]) {
@@ -1090,22 +1140,29 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
     Section sec(tm, "topk_refine");
-    const size_t lds_a = (size_t)kMaxTopk * kBinsA * 8;
-    static bool configured = false;   // the dynamic LDS limit is raised once
-    if (!configured) {
-        TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel<true>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_a));
-        configured = true;
-    }
     if (d_errors) {       // profile: level A gives the dropped energy, no exact threshold is needed
-        hipLaunchKernelGGL(topk_refine_a_kernel<true>, dim3(t->n_work), dim3(kRefThreads),
-                           (size_t)ntk * kBinsA * 8, s, p);
+        const size_t lds = refine_a_lds(ntk, true);
+        static bool configured[kMaxTopk + 1] = {};   // the dynamic LDS limit is raised once per variant
+#define LG_REFINE_A(N)                                                                                   \
+    case N:                                                                                              \
+        if (!configured[N]) {                                                                            \
+            TK_CHECK(hipFuncSetAttribute((const void*)topk_refine_a_kernel<N>,                           \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));         \
+            configured[N] = true;                                                                        \
+        }                                                                                                \
+        hipLaunchKernelGGL(topk_refine_a_kernel<N>, dim3(t->n_work), dim3(kRefThreads), lds, s, p);      \
+        break;
+        switch (ntk) {
+            LG_REFINE_A(1) LG_REFINE_A(2) LG_REFINE_A(3) LG_REFINE_A(4)
+            LG_REFINE_A(5) LG_REFINE_A(6) LG_REFINE_A(7) LG_REFINE_A(8)
+            default: return hipErrorInvalidValue;
+        }
+#undef LG_REFINE_A
         TK_CHECK(hipGetLastError());
         hipLaunchKernelGGL(topk_pick_a_kernel<true>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(topk_refine_a_kernel<false>, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsA * 4,
-                       s, p);
+    hipLaunchKernelGGL(topk_refine_a_kernel<0>, dim3(t->n_work), dim3(kRefThreads), refine_a_lds(ntk, false), s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_pick_a_kernel<false>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
     TK_CHECK(hipGetLastError());
