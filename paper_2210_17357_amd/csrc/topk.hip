@@ -50,7 +50,7 @@ constexpr int kRefTiles = 8;        // largest tiles per refinement / sample wor
                                     // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
-constexpr int kPickThreads = 1024;
+constexpr int kPickThreads = 512;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 constexpr uint32_t kHintMargin = 1; // coarse bins between a remembered threshold and the bound derived from it
 
@@ -625,7 +625,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
-    __shared__ double s_base[256], s_below[256];
+    __shared__ double s_sum[4];
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
@@ -637,9 +637,18 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         if (ENERGY) s_en[b] = 0;
     }
     if (tid == 0) s_e = 0;
+    // energy below the collection bound (tile partials) and of the candidates below the threshold
+    // bin (workgroup partials): loaded first so that the histogram work hides the latency; both
+    // are summed in a fixed order (per thread, then a fixed tree)
+    double part = 0.0;
+    if (ENERGY && tid < 256) {
+        const DevLayer L = p.layers[l];
+        for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) part += p.base_part[tt];
+        for (int wg = wr.x + tid; wg < wr.y; wg += 256) part += p.below_part[(size_t)wg * kMaxTopk + j];
+    }
     __syncthreads();
     // sum the layer's workgroup partials of this k's list: 4 bins per thread, the workgroups dealt
-    // round-robin to the 4 thread groups, integer LDS atomics join them (order does not matter)
+    // round-robin to the thread groups, integer LDS atomics join them (order does not matter)
     {
         uint32_t c[4] = {0, 0, 0, 0};
         unsigned long long e[4] = {0, 0, 0, 0};
@@ -671,21 +680,11 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         unsigned long long e = 0;
         for (uint32_t b = tid; b < bin_a; b += kPickThreads) e += s_en[b];
         if (e) atomicAdd(&s_e, e);
-        // energy below the collection bound (tile partials) and of the candidates below the
-        // threshold bin (workgroup partials), each summed in a fixed tree
         if (tid < 256) {
-            double base = 0.0, below = 0.0;
-            const DevLayer L = p.layers[l];
-            for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) base += p.base_part[tt];
-            for (int wg = wr.x + tid; wg < wr.y; wg += 256) below += p.below_part[(size_t)wg * kMaxTopk + j];
-            s_base[tid] = base;
-            s_below[tid] = below;
+            const double w = wave_sum(part);                 // xor tree inside the wavefront
+            if ((tid & 63) == 0) s_sum[tid >> 6] = w;
         }
         __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if (tid < o) { s_base[tid] += s_base[tid + o]; s_below[tid] += s_below[tid + o]; }
-            __syncthreads();
-        }
     }
     if (tid == 0) {
         const uint32_t need_a = S.need - s_res[1];
@@ -703,7 +702,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
             }
             const uint32_t ex = S.tbin >> (23 - kHistShift);
             const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + kPackEnergyShift;
-            p.errors[(size_t)l * p.stride + p.col[j]] = s_base[0] + s_below[0] + ldexp((double)s_e + inside, sh);
+            p.errors[(size_t)l * p.stride + p.col[j]] =
+                ((s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3])) + ldexp((double)s_e + inside, sh);
         }
     }
 }
