@@ -63,7 +63,8 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #pragma unroll
     for (int c = 0; c < kMaxQuant; ++c) acc[c] = 0.0f;
 
-    Collector col;
+    __shared__ uint32_t s_stage[HIST ? kThreads / 64 : 1][HIST ? kStageWords : 1];
+    StagedCollector col;
     uint32_t col_start = 0;
     uint32_t* const slice = HIST ? p.cand + p.cand_base[t.layer] + t.pos : nullptr;
     const uint32_t col_lo = HIST ? p.lo[t.layer] : 0xFFFFFFFFu;
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(t.count / kChunk, wave, &c_begin, &c_end);
         if (HIST) {
             col_start = (uint32_t)c_begin * kChunk;
-            col.init(slice + col_start, nullptr, col_lo);
+            col.init(slice + col_start, s_stage[wave], col_lo);
         }
         // One chunk: 8 elements per lane (a: elements 4j..4j+3 of the lane's bucket, b: 64+4j..).
         auto chunk = [&](float4 a, float4 b, const float4 ea, const float4 eb, const int base)
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(nb, wave, &b_begin, &b_end);
         if (HIST) {
             col_start = (uint32_t)b_begin * kBucket;
-            col.init(slice + col_start, nullptr, col_lo);
+            col.init(slice + col_start, s_stage[wave], col_lo);
         }
         for (int bk = b_begin; bk < b_end; ++bk) {
             float x[2];
@@ -236,6 +237,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         p.partials[(size_t)blockIdx.x * p.stride + p.col[threadIdx.x]] = s;
     }
     if (HIST) {
+        col.finish();
         const double bs = wave_sum((double)col.base);
         TopkTileInfo* const ti = reinterpret_cast<TopkTileInfo*>(p.tinfo) + blockIdx.x;
         if (lane == 0) {

@@ -80,6 +80,55 @@ struct Collector {
     }
 };
 
+// The same collection with the candidates staged in LDS: a wavefront appends to its own buffer of
+// kStageWords words and writes 128 candidates at a time, as two full 256-byte stores, instead of a
+// few scattered words per element slot.  Order and content of the slice are those of Collector.
+// (Patterns only: the variant that also records indices keeps the direct stores.)
+constexpr int kStageFlush = 128;
+constexpr int kStageWords = kStageFlush + 64;     // below kStageFlush before an append of at most 64
+struct StagedCollector {
+    uint32_t* dst;       // the wavefront's slice in global memory
+    uint32_t* stage;     // the wavefront's kStageWords words of LDS
+    uint32_t lo_key;
+    uint32_t cur;        // candidates written to global memory so far (uniform over the wavefront)
+    uint32_t fill;       // candidates waiting in the buffer (uniform)
+    float base;          // this lane's sum of x^2 over elements below the bound
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* st, uint32_t l) {
+        dst = d; stage = st; cur = 0; fill = 0; base = 0.0f;
+        lo_key = (l >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (l << kHistShift);
+    }
+    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid) {
+        const uint32_t bits = __float_as_uint(x);
+        const bool hit = valid && key >= lo_key;
+        const unsigned long long m = __ballot(hit);
+        const float low = (hit || !valid) ? 0.0f : x;
+        base = __builtin_fmaf(low, low, base);
+        if (hit) stage[fill + Collector::below(m, 0u)] = bits & 0x7FFFFFFFu;
+        fill += (uint32_t)__popcll(m);
+        if (fill >= (uint32_t)kStageFlush) {          // uniform
+            const uint32_t lane = threadIdx.x & 63u;
+            const uint32_t rem = fill - kStageFlush;  // < 64
+            const uint32_t v0 = stage[lane], v1 = stage[64 + lane];
+            const uint32_t v2 = stage[kStageFlush + lane];
+            dst[cur + lane] = v0;
+            dst[cur + 64 + lane] = v1;
+            if (lane < rem) stage[lane] = v2;         // what is left moves to the front
+            cur += kStageFlush;
+            fill = rem;
+        }
+    }
+    __device__ __forceinline__ void take(float x, bool valid) {
+        take_keyed(x, __float_as_uint(x) & Collector::kKeyMask, valid);
+    }
+    // writes out what is left; afterwards cur is the wavefront's candidate count
+    __device__ __forceinline__ void finish() {
+        const uint32_t lane = threadIdx.x & 63u;
+        for (uint32_t i = lane; i < fill; i += 64) dst[cur + i] = stage[i];
+        cur += fill;
+        fill = 0;
+    }
+};
+
 // Contiguous share of `n` work items for wavefront `wave` of 4: [begin, end)
 __device__ __forceinline__ void wave_range(int n, int wave, int* begin, int* end) {
     const int q = (n + kThreads / 64 - 1) / (kThreads / 64);
