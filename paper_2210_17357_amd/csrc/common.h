@@ -49,6 +49,18 @@ constexpr int kDppQuadXor2 = 0x4E;       // quad_perm:[2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141;
 constexpr int kDppRowMirror = 0x140;
 
+// 128-bit loads and stores marked as streaming (the data is used once): the caches need not keep it
+typedef float f32x4_native __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+    const f32x4_native v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_native*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float4* p, const float4 v) {
+    f32x4_native n;
+    n.x = v.x; n.y = v.y; n.z = v.z; n.w = v.w;
+    __builtin_nontemporal_store(n, reinterpret_cast<f32x4_native*>(p));
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __builtin_bit_cast(

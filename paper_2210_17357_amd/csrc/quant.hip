@@ -150,10 +150,10 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         auto load = [&](const int c, float4& a, float4& b, float4& ea, float4& eb)
             __attribute__((always_inline)) {
             const int base = min(c, c_end - 1) * kChunk + lane_off;
-            a = *reinterpret_cast<const float4*>(g + base);
-            b = *reinterpret_cast<const float4*>(g + base + 64);
-            ea = HAS_EF ? *reinterpret_cast<const float4*>(e + base) : zero4;
-            eb = HAS_EF ? *reinterpret_cast<const float4*>(e + base + 64) : zero4;
+            a = load_stream(reinterpret_cast<const float4*>(g + base));
+            b = load_stream(reinterpret_cast<const float4*>(g + base + 64));
+            ea = HAS_EF ? load_stream(reinterpret_cast<const float4*>(e + base)) : zero4;
+            eb = HAS_EF ? load_stream(reinterpret_cast<const float4*>(e + base + 64)) : zero4;
         };
         if (c_begin < c_end) {
             float4 a0, b0, ea0, eb0, a1, b1, ea1, eb1;
@@ -319,10 +319,10 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
         wave_range(t.count / kChunk, wave, &c_begin, &c_end);
         for (int c = c_begin; c < c_end; ++c) {
             const int base = c * kChunk + row * kBucket + j * 4;
-            float4 a = *reinterpret_cast<const float4*>(g + base);
-            float4 b = *reinterpret_cast<const float4*>(g + base + 64);
-            const float4 ea = *reinterpret_cast<const float4*>(e + base);
-            const float4 eb = *reinterpret_cast<const float4*>(e + base + 64);
+            float4 a = load_stream(reinterpret_cast<const float4*>(g + base));
+            float4 b = load_stream(reinterpret_cast<const float4*>(g + base + 64));
+            const float4 ea = load_stream(reinterpret_cast<const float4*>(e + base));
+            const float4 eb = load_stream(reinterpret_cast<const float4*>(e + base + 64));
             a.x += ea.x; a.y += ea.y; a.z += ea.z; a.w += ea.w;
             b.x += eb.x; b.y += eb.y; b.z += eb.z; b.w += eb.w;
             float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -357,8 +357,8 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
                 if (k < 4) wa |= qi << (bits * k);
                 else wb |= qi << (bits * (k - 4));
             }
-            *reinterpret_cast<float4*>(e + base) = make_float4(ne[0], ne[1], ne[2], ne[3]);
-            *reinterpret_cast<float4*>(e + base + 64) = make_float4(ne[4], ne[5], ne[6], ne[7]);
+            store_stream(reinterpret_cast<float4*>(e + base), make_float4(ne[0], ne[1], ne[2], ne[3]));
+            store_stream(reinterpret_cast<float4*>(e + base + 64), make_float4(ne[4], ne[5], ne[6], ne[7]));
             const int64_t bk = bucket0 + (int64_t)c * 4 + row;
             if (j == 0) meta[bk] = make_float2(mn, unit);
 

@@ -312,17 +312,17 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
         for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += kChunk / 4) {
             float4 a[2];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) a[h] = reinterpret_cast<const float4*>(gp)[v + 64 * h];
+            for (int h = 0; h < 2; ++h) a[h] = load_stream(reinterpret_cast<const float4*>(gp) + v + 64 * h);
             if (ep) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const float4 b = reinterpret_cast<const float4*>(ep)[v + 64 * h];
+                    const float4 b = load_stream(reinterpret_cast<const float4*>(ep) + v + 64 * h);
                     a[h].x += b.x; a[h].y += b.y; a[h].z += b.z; a[h].w += b.w;
                 }
             }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (EMIT) reinterpret_cast<float4*>(eo)[v + 64 * h] = a[h];
+                if (EMIT) store_stream(reinterpret_cast<float4*>(eo) + v + 64 * h, a[h]);
                 if (HIST) {
                     atomicAdd(&s_hist[mag_bits(a[h].x) >> kHistShift], 1u);
                     atomicAdd(&s_hist[mag_bits(a[h].y) >> kHistShift], 1u);
