@@ -170,3 +170,44 @@ def test_reused_thresholds_give_the_same_results_and_survive_data_that_moves():
             assert np.array_equal(outs[1][1][off:off + n].view(np.uint32), e_ref.view(np.uint32)), (factor, l)
     plain.close()
     reuse.close()
+
+
+@pytest.mark.parametrize("reuse", [False, True])
+def test_one_handle_serves_layer_tables_of_different_lengths(reuse):
+    """One handle, calls whose layer tables differ in length and content, profile and compress
+    interleaved: the histograms a call leaves behind (cleared by its last scan, kept between
+    calls) and the bounds kept per kind of call must never leak into a later call with more
+    layers.  Every result is checked against the oracle."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    rng = np.random.default_rng(77)
+    sizes_all = [70000, 4096, 131072 + 5, 33, 9000, 262144, 1500, 50000]
+    arrays = [(rng.standard_normal(n) * 10.0 ** rng.uniform(-3, 0)).astype(np.float32) for n in sizes_all]
+    efs = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for n in sizes_all]
+    dens = (0.1, 0.01, 0.001)
+    cands = [(W.TOPK, d) for d in dens]
+    total = int(sum(sizes_all))
+    h = B.Handle(total, len(sizes_all), len(cands), reuse_thresholds=reuse)
+    subsets = [(0, 1, 2), tuple(range(8)), (3, 4), tuple(range(8)), (5, 6, 7, 0, 1), tuple(range(8)), (0, 1, 2)]
+    for rep, sub in enumerate(subsets):
+        batch = _flat_batch([arrays[i] for i in sub], [efs[i] for i in sub])
+        layers, ctab = tables(batch, cands)
+        g, e, _ = to_device(batch)
+        L = len(sub)
+        errors, _ = h.profile(g, e, layers, ctab)
+        ref = pipeline.profile(batch.grads, batch.ef, batch.offsets, batch.numels, batch.rows, batch.cols, cands)
+        assert rel_err(errors, ref).max() < 1e-4, (rep, sub)
+        choice = np.array([(l + rep) % len(cands) for l in range(L)], np.int32)
+        offsets = B.payload_layout(layers, ctab, choice)
+        payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
+        ef_dev = e.clone()
+        h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)
+        pay, new_ef = payload.cpu().numpy(), ef_dev.cpu().numpy()
+        for l in range(L):
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            vals, idx, e_ref = topk.compress(batch.grads[off:off + n], batch.ef[off:off + n], cands[choice[l]][1])
+            k = idx.size
+            assert np.array_equal(pay[offsets[l] + 4 * k:offsets[l] + 8 * k].view(np.uint32), idx), (rep, l)
+            assert np.array_equal(pay[offsets[l]:offsets[l] + 4 * k].view(np.uint32), vals.view(np.uint32)), (rep, l)
+            assert np.array_equal(new_ef[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (rep, l)
+    h.close()
