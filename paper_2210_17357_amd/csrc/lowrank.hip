@@ -28,7 +28,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kLrCols = 64;       // columns computed per layer (r_max <= 64)
 constexpr int kLrBM = 128;        // rows (GEMM1, reconstruction) / columns (GEMM2) per workgroup
 constexpr int kLrBK = 32;         // contraction chunk staged in LDS
-constexpr int kLrGramSpan = 512;  // rows per Gram partial (one workgroup)
+constexpr int kLrGramSpan = 256;  // rows per Gram partial (one workgroup)
 constexpr int kLrQChunk = 64;     // Q rows per workgroup in the split-K reduction
 constexpr int kLrPSplit = 512;    // columns contracted per workgroup in P = X Q0
 constexpr int kLrEfSpan = 512;    // columns reconstructed per workgroup
@@ -280,14 +280,19 @@ __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
-    for (int r0 = tile.a0 + 16 * wave; r0 < span_end; r0 += 64) {
-        float x[4][4];      // [4-row step][column block]
+    // the loads of the next 16-row group are in flight while the current one is multiplied
+    auto fetch = [&](int r0, float (&x)[4][4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             const int r = r0 + 4 * st + lr;
 #pragma unroll
             for (int b = 0; b < 4; ++b) x[st][b] = r < span_end ? P[(int64_t)r * kLrCols + 16 * b + lc] : 0.0f;
         }
+    };
+    float x[4][4], xn[4][4];      // [4-row step][column block]
+    fetch(tile.a0 + 16 * wave, x);          // rows past the span's end read as zero
+    for (int r0 = tile.a0 + 16 * wave; r0 < span_end; r0 += 64) {
+        fetch(r0 + 64, xn);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
 #pragma unroll
@@ -297,6 +302,10 @@ __global__ __launch_bounds__(256) void lr_gram_kernel(LrParams p) {
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)x[st][i], (double)x[st][j], acc[i][j],
                                                                      0, 0, 0);
         }
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) x[st][b] = xn[st][b];
     }
     for (int w = 0; w < 4; ++w) {
         if (wave == w) {
@@ -329,20 +338,40 @@ __device__ __forceinline__ double lane_value(double v, int lane) {      // v of 
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
+// G = sum of a layer's Gram partials in partial order, one matrix element per thread (16
+// workgroups per layer), left in the layer's first partial.  A layer of many rows has many
+// partials: summed here their loads run eight deep on 4096 threads instead of serially in the
+// one workgroup that eliminates.
+__global__ __launch_bounds__(256) void lr_gram_reduce_kernel(LrParams p) {
+    const LrLayer L = p.layers[blockIdx.x / 16];
+    if (L.gram_end - L.gram_begin < 2) return;
+    const int f = (blockIdx.x % 16) * 256 + threadIdx.x;
+    double* const first = p.gram_part + (size_t)L.gram_begin * kLrCols * kLrCols + f;
+    const int n = L.gram_end - L.gram_begin;
+    double s = 0.0;
+    int c = 0;
+    for (; c + 8 <= n; c += 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = first[(size_t)(c + u) * kLrCols * kLrCols];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < n; ++c) s += first[(size_t)c * kLrCols * kLrCols];
+    *first = s;
+}
+
 __global__ __launch_bounds__(256) void lr_orth_kernel(LrParams p) {
     __shared__ double R[kLrCols][kLrCols];
     __shared__ double diag0[kLrCols];
     const LrLayer L = p.layers[blockIdx.x];
     const int tid = threadIdx.x, w = tid >> 6, j = tid & 63;
-    // G = sum of the layer's Gram partials, in partial order
+    // G: the layer's Gram matrix (its partials already summed into the first)
     double g[16];
+    {
+        const double* __restrict__ src = p.gram_part + (size_t)L.gram_begin * kLrCols * kLrCols + w * kLrCols + j;
 #pragma unroll
-    for (int m = 0; m < 16; ++m) g[m] = 0.0;
-#pragma unroll 4
-    for (int c = L.gram_begin; c < L.gram_end; ++c) {
-        const double* __restrict__ src = p.gram_part + (size_t)c * kLrCols * kLrCols + w * kLrCols + j;
-#pragma unroll
-        for (int m = 0; m < 16; ++m) g[m] += src[4 * m * kLrCols];
+        for (int m = 0; m < 16; ++m) g[m] = src[4 * m * kLrCols];
     }
 #pragma unroll
     for (int m = 0; m < 16; ++m)
@@ -975,6 +1004,10 @@ static hipError_t lr_factorize(LrHost* H, LrParams p, int iters, Timing* tm, hip
         Section sec(tm, "lowrank_orth");
         hipLaunchKernelGGL(lr_gram_kernel, dim3((unsigned)H->gram_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
+        if (H->gram_tiles.size() > H->layers.size()) {      // some layer has more than one partial
+            hipLaunchKernelGGL(lr_gram_reduce_kernel, dim3((unsigned)H->layers.size() * 16), dim3(256), 0, s, p);
+            LR_CHECK(hipGetLastError());
+        }
         hipLaunchKernelGGL(lr_orth_kernel, dim3((unsigned)H->layers.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
         hipLaunchKernelGGL(lr_apply_kernel, dim3((unsigned)H->gram_tiles.size()), dim3(256), 0, s, p);
