@@ -584,13 +584,46 @@ __global__ __launch_bounds__(256) void lr_qreduce_kernel(LrParams p) {
             p.q_out[L.q_off + (int64_t)(c0 + r) * p.r_max + j] = s;
         }
     };
+    // sum of partials [sp0, sp1) of one element in partial order, the loads eight deep
+    auto sum_partials = [&](int64_t idx, int sp0, int sp1) {
+        const int64_t stride = (int64_t)n * kLrCols;
+        float s = 0.0f;
+        int sp = sp0;
+        for (; sp + 8 <= sp1; sp += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(sp + u) * stride + idx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; sp < sp1; ++sp) s += part[(int64_t)sp * stride + idx];
+        return s;
+    };
     if (L.splits <= 4) {
         // few partials: one thread per (row, column), rows strided over the 4 wavefronts
-        for (int r = grp; r < nc; r += 4) {
-            const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
-            float s = 0.0f;
-            for (int sp = 0; sp < L.splits; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
-            emit(r, s);
+        // (four rows per pass: their up to 16 loads are in flight together)
+        const int64_t stride = (int64_t)n * kLrCols;
+        for (int r = grp; r < nc; r += 16) {
+            float v[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int rr = r + 4 * u;
+                const int64_t idx = (int64_t)(c0 + rr) * kLrCols + j;
+#pragma unroll
+                for (int sp = 0; sp < 4; ++sp)
+                    v[u][sp] = (rr < nc && sp < L.splits) ? part[(int64_t)sp * stride + idx] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int rr = r + 4 * u;
+                if (rr < nc) {
+                    float s = 0.0f;
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp)
+                        if (sp < L.splits) s += v[u][sp];
+                    emit(rr, s);
+                }
+            }
         }
     } else {
         // many partials: the 4 wavefronts share one row, each sums a contiguous quarter of the
@@ -599,9 +632,7 @@ __global__ __launch_bounds__(256) void lr_qreduce_kernel(LrParams p) {
         const int sp0 = grp * per, sp1 = min(L.splits, sp0 + per);
         for (int r = 0; r < nc; ++r) {
             const int64_t idx = (int64_t)(c0 + r) * kLrCols + j;
-            float s = 0.0f;
-            for (int sp = sp0; sp < sp1; ++sp) s += part[(int64_t)sp * n * kLrCols + idx];
-            s_p[grp][j] = s;
+            s_p[grp][j] = sum_partials(idx, sp0, sp1);
             __syncthreads();
             if (grp == 0) emit(r, ((s_p[0][j] + s_p[1][j]) + s_p[2][j]) + s_p[3][j]);
             __syncthreads();
