@@ -59,12 +59,12 @@ __global__ __launch_bounds__(kThreads) void quant_decode_kernel(DecodeParams p) 
             float4* o = reinterpret_cast<float4*>(out + first);
             float4 a = make_float4(x[0], x[1], x[2], x[3]), b = make_float4(x[4], x[5], x[6], x[7]);
             if (p.accumulate) {
-                const float4 oa = o[0], ob = o[1];
+                const float4 oa = load_stream(o), ob = load_stream(o + 1);
                 a.x += oa.x; a.y += oa.y; a.z += oa.z; a.w += oa.w;
                 b.x += ob.x; b.y += ob.y; b.z += ob.z; b.w += ob.w;
             }
-            o[0] = a;
-            o[1] = b;
+            store_stream(o, a);
+            store_stream(o + 1, b);
         } else {
 #pragma unroll
             for (int k = 0; k < 8; ++k)
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void topk_decode_zero_kernel(DecodeParams
     float* const out = p.out + L.offset + t.pos;
     if (t.fast) {
         const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) reinterpret_cast<float4*>(out)[v] = z;
+        for (int v = threadIdx.x; v < t.count / 4; v += kThreads) store_stream(reinterpret_cast<float4*>(out) + v, z);
     } else {
         for (int i = threadIdx.x; i < t.count; i += kThreads) out[i] = 0.0f;
     }
@@ -111,12 +111,12 @@ __global__ __launch_bounds__(kThreads) void accumulate_kernel(float* __restrict_
     const int64_t n4 = n / 4;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < n4; v += stride) {
-        float4 a = reinterpret_cast<const float4*>(g)[v];
+        float4 a = load_stream(reinterpret_cast<const float4*>(g) + v);
         if (!reset) {
-            const float4 o = reinterpret_cast<const float4*>(acc)[v];
+            const float4 o = load_stream(reinterpret_cast<const float4*>(acc) + v);
             a.x += o.x; a.y += o.y; a.z += o.z; a.w += o.w;
         }
-        reinterpret_cast<float4*>(acc)[v] = a;
+        store_stream(reinterpret_cast<float4*>(acc) + v, a);
     }
     if (blockIdx.x == 0 && threadIdx.x < n - 4 * n4) {
         const int64_t i = 4 * n4 + threadIdx.x;
