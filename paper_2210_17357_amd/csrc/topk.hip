@@ -473,12 +473,20 @@ __device__ __forceinline__ void for_each_candidate(const RefineParams& p, const 
         const int t = t0 + pr / kSub, sub = pr % kSub;
         const uint32_t n = p.tinfo[t].cnt[sub];
         const uint32_t* __restrict__ items = p.cand + T.cand_base + p.tiles[t].pos + p.tinfo[t].start[sub];
-        for (uint32_t i0 = 0; i0 < n; i0 += 64 * 8) {
+        uint32_t i0 = 0;
+        for (; i0 + 64 * 8 <= n; i0 += 64 * 8) {          // full batches: no range checks
+            uint32_t pat[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) pat[q] = items[i0 + q * 64 + lane];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) f(pat[q]);
+        }
+        if (i0 < n) {
             uint32_t pat[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const uint32_t i = i0 + q * 64 + lane;
-                pat[q] = i < n ? items[i] : 0xFFFFFFFFu;
+                pat[q] = i < n ? items[i] : 0xFFFFFFFFu;      // never a candidate's pattern (sign bit cleared)
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q)
@@ -502,10 +510,12 @@ __device__ __forceinline__ unsigned long long packed_cell(uint32_t pat) {
 // requested k do not increase with j, so the threshold bins do not decrease and the sets
 // {key < tb[j]} are nested: walking j downwards, each comparison narrows the set of active lanes
 // (a compare that writes the execution mask) and the add runs under it: two vector instructions
-// per k.  The mask is restored at the end; one asm statement, so nothing else runs under it.
+// per k.  The mask is restored at the end; one asm statement, so nothing else runs under it.  The
+// closing s_nop keeps the wait states a DPP instruction needs after a vector write of the mask,
+// should the compiler place one right behind the block.
 #define LG_BELOW_STEP(J) "v_cmpx_gt_u32 vcc, %[t" #J "], %[key]\n\tv_fmac_f32 %[b" #J "], %[x], %[x]\n\t"
 #define LG_BELOW_ASM(STEPS)                                                                          \
-    asm volatile("s_mov_b64 %[save], exec\n\t" STEPS "s_mov_b64 exec, %[save]"                       \
+    asm volatile("s_mov_b64 %[save], exec\n\t" STEPS "s_mov_b64 exec, %[save]\n\ts_nop 3"            \
                  : [b0] "+v"(b[0]), [b1] "+v"(b[1]), [b2] "+v"(b[2]), [b3] "+v"(b[3]), [b4] "+v"(b[4]), \
                    [b5] "+v"(b[5]), [b6] "+v"(b[6]), [b7] "+v"(b[7]), [save] "=&s"(save)              \
                  : [key] "v"(key), [x] "v"(x), [t0] "s"(tb[0]), [t1] "s"(tb[1]), [t2] "s"(tb[2]),      \
