@@ -25,7 +25,9 @@
  *     every other pointer is HOST memory.  The caller owns all of them.  The handle owns
  *     only scratch memory sized at lgreco_create().
  *   - All kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = default
- *     stream).  Host outputs are valid when the call returns (the call waits for them).
+ *     stream).  Host outputs are valid when the call returns (the call waits for them); a call
+ *     without host outputs (lgreco_compress) does not wait.  Calls on one handle must not
+ *     overlap: use one stream per handle, or order the streams yourself.
  *   - Every function returns an lgreco status: 0 on success, negative on error.  Nothing
  *     throws, nothing prints.  Inputs must be finite; NaN/Inf gradients give undefined
  *     numerical results (never a fault).
@@ -182,7 +184,11 @@ int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_
  *     TOPK    fp32 values[k] then uint32 indices[k] (index within the layer), ascending
  *             index; among equal magnitudes the lower index is kept
  *     LOWRANK Phat [rows x r] then Q [cols x r], fp32 row-major
- *   offsets    host [L+1] from lgreco_payload_layout */
+ *   offsets    host [L+1] from lgreco_payload_layout
+ * The call has no host output and returns with its kernels queued on `stream`: d_payload, d_ef
+ * and d_q are complete in stream order (for the next call on this stream, or after the caller
+ * waits on the stream).  The host arrays are read before the call returns.  An error of the
+ * queued work surfaces at the next call that waits. */
 int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                     const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                     const int32_t* choice, float* d_q, uint8_t* d_payload, const int64_t* offsets,
@@ -220,6 +226,14 @@ int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, in
  * fills names (static strings) and milliseconds for up to `cap` of them. */
 int lgreco_set_timing(lgreco_handle_t* h, int32_t level);
 int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap);
+/* The same for the last call of one kind (the handle keeps one set of brackets per kind, so a
+ * lgreco_compress that returned with its kernels still queued can be read after a later profile
+ * or solve call).  Both functions wait for the brackets they read. */
+#define LGRECO_CALL_PROFILE  0
+#define LGRECO_CALL_SOLVE    1
+#define LGRECO_CALL_COMPRESS 2
+#define LGRECO_CALL_RECEIVE  3   /* lgreco_decompress, lgreco_accumulate */
+int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, float* ms, int32_t cap);
 
 const char* lgreco_strerror(int status);
 /* Text of the last HIP error seen by this handle ("" if none). */

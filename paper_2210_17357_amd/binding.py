@@ -17,10 +17,11 @@ LIB_PATH = os.path.join(_HERE, "liblgreco.so")
 
 OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 QUANT, TOPK, LOWRANK = 0, 1, 2
+CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_candidate_range", "lgreco_emax",
            "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing",
-           "lgreco_get_timing", "lgreco_strerror", "lgreco_last_hip_error")
+           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_strerror", "lgreco_last_hip_error")
 
 
 class Layer(C.Structure):
@@ -72,6 +73,7 @@ def lib() -> C.CDLL:
         l.lgreco_accumulate.argtypes = [vp, vp, vp, i64, i32, vp]
         l.lgreco_set_timing.argtypes = [vp, i32]
         l.lgreco_get_timing.argtypes = [vp, vp, vp, i32]
+        l.lgreco_get_timing_of.argtypes = [vp, i32, vp, vp, i32]
         l.lgreco_strerror.argtypes = [C.c_int]
         l.lgreco_strerror.restype = C.c_char_p
         l.lgreco_last_hip_error.argtypes = [vp]
@@ -257,11 +259,16 @@ class Handle:
         """0 / False: off; 1 / True: main kernels; 2: every section."""
         self._check(lib().lgreco_set_timing(self._h, int(level)))
 
-    def get_timing(self):
+    def get_timing(self, call=None):
+        """Sections of the last call, or of the last call of one kind (CALL_PROFILE, CALL_SOLVE,
+        CALL_COMPRESS, CALL_RECEIVE); waits for the brackets it reads."""
         cap = 32
         names = (C.c_char_p * cap)()
         ms = (C.c_float * cap)()
-        n = lib().lgreco_get_timing(self._h, names, ms, cap)
+        if call is None:
+            n = lib().lgreco_get_timing(self._h, names, ms, cap)
+        else:
+            n = lib().lgreco_get_timing_of(self._h, int(call), names, ms, cap)
         if n < 0:
             self._check(n)
         return [(names[i].decode(), float(ms[i])) for i in range(min(n, cap))]

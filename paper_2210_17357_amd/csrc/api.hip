@@ -59,8 +59,12 @@ struct lgreco_handle {
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
-    Timing tm;
-    // sub-sections measured inside a kernel (device clock), appended after the event sections
+    // One set of timing events per kind of call (LGRECO_CALL_*): a call that returns before its
+    // kernels have finished (lgreco_compress) keeps its brackets while the next call of another
+    // kind records its own.  tm is the set of the call in progress / the last call.
+    Timing tms[4];
+    Timing* tm = &tms[0];
+    // sub-sections measured inside a kernel (device clock), appended after the solve call's event sections
     const char* sub_name[4]{};
     float sub_ms[4]{};
     int n_sub = 0;
@@ -200,10 +204,11 @@ int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
     return LGRECO_OK;
 }
 
-void begin_call(lgreco_handle* h, hipStream_t s) {
-    h->tm.n = 0;
-    h->tm.stream = s;
-    h->n_sub = 0;
+void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
+    h->tm = &h->tms[kind];
+    h->tm->n = 0;
+    h->tm->stream = s;
+    if (kind == LGRECO_CALL_SOLVE) h->n_sub = 0;
 }
 
 }  // namespace
@@ -277,8 +282,10 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * 8);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
-    for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&h->tm.ev[i]));
-    h->tm.ready = true;
+    for (Timing& t : h->tms) {
+        for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&t.ev[i]));
+        t.ready = true;
+    }
     {
         hipError_t e = topk_scratch_create(&h->topk, max_elems, max_layers, h->max_tiles);
         h->topk.reuse_thresholds = cfg->reuse_thresholds != 0;
@@ -301,8 +308,9 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipHostFree(h->h_bins);
     (void)hipHostFree(h->h_dp_in);
     (void)hipHostFree(h->h_dp_out);
-    if (h->tm.ready)
-        for (int i = 0; i < 2 * Timing::kMaxSections; ++i) (void)hipEventDestroy(h->tm.ev[i]);
+    for (Timing& t : h->tms)
+        for (int i = 0; i < 2 * Timing::kMaxSections; ++i)
+            if (t.ev[i]) (void)hipEventDestroy(t.ev[i]);
     topk_scratch_destroy(&h->topk);
     lowrank_scratch_destroy(&h->lowrank);
     delete h;
@@ -311,27 +319,43 @@ int lgreco_destroy(lgreco_handle_t* h) {
 
 int lgreco_set_timing(lgreco_handle_t* h, int32_t level) {
     if (!h || level < 0 || level > 2) return LGRECO_EINVAL;
-    h->tm.level = level;
-    h->tm.n = 0;
+    for (Timing& t : h->tms) {
+        t.level = level;
+        t.n = 0;
+    }
+    h->n_sub = 0;
     return LGRECO_OK;
+}
+
+static int read_timing(lgreco_handle_t* h, Timing& tm, bool with_sub, const char** names, float* ms, int32_t cap) {
+    const int n = tm.n;
+    for (int i = 0; i < n && i < cap; ++i) {
+        float t = 0.0f;
+        hipError_t e = hipEventSynchronize(tm.ev[2 * i + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, tm.ev[2 * i], tm.ev[2 * i + 1]);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
+        if (names) names[i] = tm.name[i];
+        if (ms) ms[i] = t;
+    }
+    int total = n;
+    if (with_sub) {
+        for (int j = 0; j < h->n_sub && n + j < cap; ++j) {
+            if (names) names[n + j] = h->sub_name[j];
+            if (ms) ms[n + j] = h->sub_ms[j];
+        }
+        total += h->n_sub;
+    }
+    return total;
 }
 
 int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap) {
     if (!h || cap < 0) return LGRECO_EINVAL;
-    const int n = h->tm.n;
-    for (int i = 0; i < n && i < cap; ++i) {
-        float t = 0.0f;
-        hipError_t e = hipEventSynchronize(h->tm.ev[2 * i + 1]);
-        if (e == hipSuccess) e = hipEventElapsedTime(&t, h->tm.ev[2 * i], h->tm.ev[2 * i + 1]);
-        if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
-        if (names) names[i] = h->tm.name[i];
-        if (ms) ms[i] = t;
-    }
-    for (int j = 0; j < h->n_sub && n + j < cap; ++j) {
-        if (names) names[n + j] = h->sub_name[j];
-        if (ms) ms[n + j] = h->sub_ms[j];
-    }
-    return n + h->n_sub;
+    return read_timing(h, *h->tm, h->tm == &h->tms[LGRECO_CALL_SOLVE], names, ms, cap);
+}
+
+int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, float* ms, int32_t cap) {
+    if (!h || cap < 0 || call < 0 || call > LGRECO_CALL_RECEIVE) return LGRECO_EINVAL;
+    return read_timing(h, h->tms[call], call == LGRECO_CALL_SOLVE, names, ms, cap);
 }
 
 int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
@@ -399,7 +423,7 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     if (!h || !d_grads || !layers || !cands || !errors || L <= 0 || P <= 0) return LGRECO_EINVAL;
     if (P > h->max_cands) return LGRECO_ENOSPACE;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s);
+    begin_call(h, s, LGRECO_CALL_PROFILE);
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
 
@@ -458,7 +482,7 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     if (ntk) {
         load_group(0);
         HIPCHK(topk_begin(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
-                          h->tile_elems, ks.data(), ntk, 0, &h->tm, s));
+                          h->tile_elems, ks.data(), ntk, 0, h->tm, s));
     }
     if (qp.nq) {
         qp.g = d_grads;
@@ -478,30 +502,30 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
             qp.tinfo = h->topk.d_tinfo;
             qp.base_part = h->topk.d_base_part;
         }
-        Section sec(&h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile", true);
+        Section sec(h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile", true);
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
     } else if (ntk) {
-        Section sec(&h->tm, "topk_collect", true);
+        Section sec(h->tm, "topk_collect", true);
         HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
     }
     if (ntk)
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
-                           ntk_all <= (int)kMaxTopk, &h->tm, s));
+                           ntk_all <= (int)kMaxTopk, h->tm, s));
     if (qp.nq) {
-        Section sec(&h->tm, "reduce_partials");
+        Section sec(h->tm, "reduce_partials");
         HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, h->d_errors, s));
     }
-    if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, h->d_errors, P, &h->tm, s));
+    if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, h->d_errors, P, h->tm, s));
     for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
-                           first + (int)kMaxTopk >= ntk_all, &h->tm, s));
-        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, &h->tm, s));
+                           first + (int)kMaxTopk >= ntk_all, h->tm, s));
+        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, h->tm, s));
     }
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
-                               lr_rank, lr_col, nlr, h->d_errors, P, &h->tm, s));
+                               lr_rank, lr_col, nlr, h->d_errors, P, h->tm, s));
     }
     HIPCHK(hipStreamSynchronize(s));      // the kernels wrote h_errors
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
@@ -515,7 +539,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     if (n_bins < 1 || n_bins > LGRECO_MAX_BINS || !(e_max == e_max)) return LGRECO_EINVAL;
     if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s);
+    begin_call(h, s, LGRECO_CALL_SOLVE);
     const size_t lp = (size_t)L * P;
     const double D = (double)n_bins;
     int64_t worst = 0;                  // sum over layers of the largest usable size
@@ -605,11 +629,11 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
                     h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16)};
         {
-            Section sec(&h->tm, "dp_solve", true);
+            Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
         }
         HIPCHK(hipStreamSynchronize(s));  // the kernel wrote h_dp_out
-        if (h->tm.level >= 1) {                       // 100 MHz constant-rate device counter
+        if (h->tm->level >= 1) {                       // 100 MHz constant-rate device counter
             h->sub_name[0] = "dp_solve.sweep";
             h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
             h->sub_name[1] = "dp_solve.backtrace";
@@ -684,7 +708,7 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
         return LGRECO_EINVAL;
     if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s);
+    begin_call(h, s, LGRECO_CALL_COMPRESS);
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
     bool any[3] = {false, false, false};
@@ -705,19 +729,20 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     if (st != LGRECO_OK) return st;
     const int n_tiles = (int)h->ht.size();
     if (any[LGRECO_QUANT]) {
-        Section sec(&h->tm, "quant_compress", true);
+        Section sec(h->tm, "quant_compress", true);
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
                                      h->cfg.stochastic != 0, h->cfg.seed, s));
     }
     if (any[LGRECO_TOPK]) {
         HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
-                             h->tile_elems, d_payload, &h->tm, s));
+                             h->tile_elems, d_payload, h->tm, s));
     }
     if (any[LGRECO_LOWRANK]) {
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,
-                                d_payload, &h->tm, s));
+                                d_payload, h->tm, s));
     }
-    HIPCHK(hipStreamSynchronize(s));
+    // No host output: the call returns with its kernels queued.  Payload, error feedback and q are
+    // ready in stream order; the caller's next call on this stream (or its own wait) sees them.
     return LGRECO_OK;
 }
 
@@ -728,7 +753,7 @@ int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_
         return LGRECO_EINVAL;
     if ((uintptr_t)d_out % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s);
+    begin_call(h, s, LGRECO_CALL_RECEIVE);
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
     bool any[3] = {false, false, false};
@@ -747,10 +772,10 @@ int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_
     st = upload_layers(h, s, true);
     if (st != LGRECO_OK) return st;
     HIPCHK(launch_decode(d_payload, h->d_layers, h->d_tiles, (int)h->ht.size(), d_out, accumulate != 0,
-                         any[LGRECO_QUANT], any[LGRECO_TOPK], &h->tm, s));
+                         any[LGRECO_QUANT], any[LGRECO_TOPK], h->tm, s));
     if (any[LGRECO_LOWRANK])
         HIPCHK(lowrank_decompress(&h->lowrank, h->hl.data(), L, h->cfg.r_max, d_payload, d_out, accumulate != 0,
-                                  &h->tm, s));
+                                  h->tm, s));
     HIPCHK(hipStreamSynchronize(s));
     return LGRECO_OK;
 }
@@ -760,9 +785,9 @@ int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, in
     if (!h || !d_acc || !d_grads || n < 0) return LGRECO_EINVAL;
     if ((uintptr_t)d_acc % 16 || (uintptr_t)d_grads % 16) return LGRECO_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s);
+    begin_call(h, s, LGRECO_CALL_RECEIVE);
     {
-        Section sec(&h->tm, "accumulate", true);
+        Section sec(h->tm, "accumulate", true);
         HIPCHK(launch_accumulate(d_acc, d_grads, n, reset != 0, s));
     }
     HIPCHK(hipStreamSynchronize(s));

@@ -99,6 +99,8 @@ struct TopkScratch {
     // (two device copies: profile calls and compress calls alternate and each repeats itself)
     uint8_t* d_ctl[2] = {nullptr, nullptr};
     uint8_t* h_ctl = nullptr;         // pinned
+    hipEvent_t ctl_copied = nullptr;  // recorded behind every upload from h_ctl
+    bool ctl_pending = false;         // an upload was queued since h_ctl was last known to be free
     uint8_t* h_ctl_last[2] = {nullptr, nullptr};    // what each d_ctl holds
     size_t ctl_bytes = 0, ctl_last_bytes[2] = {0, 0};
     size_t ctl_off[4] = {0, 0, 0, 0}; // byte offsets of k, cand_base, work_range, work

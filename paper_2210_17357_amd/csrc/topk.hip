@@ -931,6 +931,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     t->ctl_bytes = o_work + sizeof(RefWork) * (size_t)t->max_work;
     t->ctl_off[0] = o_k; t->ctl_off[1] = o_base; t->ctl_off[2] = o_range; t->ctl_off[3] = o_work;
     TK_CHECK(hipHostMalloc(&t->h_ctl, t->ctl_bytes, hipHostMallocDefault));
+    TK_CHECK(hipEventCreateWithFlags(&t->ctl_copied, hipEventDisableTiming));
     std::memset(t->h_ctl, 0, t->ctl_bytes);
     for (int i = 0; i < 2; ++i) {
         TK_CHECK(hipMalloc(&t->d_ctl[i], t->ctl_bytes));
@@ -963,7 +964,18 @@ void topk_scratch_destroy(TopkScratch* t) {
         std::free(t->h_ctl_last[i]);
     }
     (void)hipHostFree(t->h_ctl);
+    if (t->ctl_copied) (void)hipEventDestroy(t->ctl_copied);
     *t = TopkScratch{};
+}
+
+// The pinned control block may be written again once the last upload that was queued from it has
+// executed (a call may return, and a stream may be busy, with that copy still pending).
+static hipError_t ctl_writable(TopkScratch* t) {
+    if (t->ctl_pending) {
+        TK_CHECK(hipEventSynchronize(t->ctl_copied));
+        t->ctl_pending = false;
+    }
+    return hipSuccess;
 }
 
 // One upload of the control block up to the last work item, skipped when this slot's device copy
@@ -978,6 +990,9 @@ static hipError_t upload_ctl(TopkScratch* t, int slot, hipStream_t s, bool* chan
     const bool differs = used != t->ctl_last_bytes[slot] || std::memcmp(t->h_ctl, t->h_ctl_last[slot], used) != 0;
     if (differs) {
         TK_CHECK(hipMemcpyAsync(d, t->h_ctl, used, hipMemcpyHostToDevice, s));
+        // the copy reads the pinned block when it executes: the next writer waits for this event
+        TK_CHECK(hipEventRecord(t->ctl_copied, s));
+        t->ctl_pending = true;
         std::memcpy(t->h_ctl_last[slot], t->h_ctl, used);
         t->ctl_last_bytes[slot] = used;
     }
@@ -989,8 +1004,7 @@ static hipError_t upload_ctl(TopkScratch* t, int slot, hipStream_t s, bool* chan
 // pass resolves): only the k table changes.  The group must not ask for more entries than the
 // first one did, so every threshold lies at or above the collection bound.
 hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hipStream_t s) {
-    // the pinned staging block is read when the previous upload executes, not when it was queued
-    TK_CHECK(hipStreamSynchronize(s));
+    TK_CHECK(ctl_writable(t));
     for (size_t i = 0; i < (size_t)L * kMaxTopk; ++i) t->h_k[i] = ks[i];
     return upload_ctl(t, slot, s);
 }
@@ -1001,6 +1015,7 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                       const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
     const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
+    TK_CHECK(ctl_writable(t));
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
     int2* const wrange = (int2*)t->h_work_range;
