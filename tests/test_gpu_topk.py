@@ -211,3 +211,43 @@ def test_one_handle_serves_layer_tables_of_different_lengths(reuse):
             assert np.array_equal(pay[offsets[l]:offsets[l] + 4 * k].view(np.uint32), vals.view(np.uint32)), (rep, l)
             assert np.array_equal(new_ef[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (rep, l)
     h.close()
+
+
+def test_compress_calls_queued_back_to_back():
+    """lgreco_compress returns with its kernels queued.  Two calls with different choices (so the
+    second rewrites the pinned control block the first uploaded from), no wait in between, each
+    into its own payload and error-feedback buffers: both must come out right; the brackets of the
+    call are readable afterwards."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    rng = np.random.default_rng(5)
+    sizes_all = [300000, 70001, 131072, 999]
+    arrays = [(rng.standard_normal(n) * 0.1).astype(np.float32) for n in sizes_all]
+    efs = [(rng.standard_normal(n) * 0.01).astype(np.float32) for n in sizes_all]
+    batch = _flat_batch(arrays, efs)
+    cands = [(W.TOPK, d) for d in (0.2, 0.03, 0.002)]
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(sizes_all)
+    h = B.Handle(int(batch.grads.size), L, len(cands))
+    h.set_timing(1)
+    runs = []
+    for rot in (0, 1, 2, 0):
+        choice = np.array([(l + rot) % len(cands) for l in range(L)], np.int32)
+        offsets = B.payload_layout(layers, ctab, choice)
+        payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
+        ef_dev = e.clone()
+        h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)      # no wait
+        runs.append((choice, offsets, payload, ef_dev))
+    names = [n for n, _ in h.get_timing(B.CALL_COMPRESS)]
+    assert "topk_collect" in names
+    for choice, offsets, payload, ef_dev in runs:
+        pay, new_ef = payload.cpu().numpy(), ef_dev.cpu().numpy()
+        for l in range(L):
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            vals, idx, e_ref = topk.compress(batch.grads[off:off + n], batch.ef[off:off + n], cands[choice[l]][1])
+            k = idx.size
+            assert np.array_equal(pay[offsets[l] + 4 * k:offsets[l] + 8 * k].view(np.uint32), idx), l
+            assert np.array_equal(pay[offsets[l]:offsets[l] + 4 * k].view(np.uint32), vals.view(np.uint32)), l
+            assert np.array_equal(new_ef[off:off + n].view(np.uint32), e_ref.view(np.uint32)), l
+    h.close()
