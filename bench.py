@@ -46,6 +46,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="lgreco_profile, lgreco_emax, lgreco_solve as three calls instead of lgreco_profile_solve")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
@@ -148,19 +150,24 @@ def main():
     def step(i, record):
         ef = ef_pool[i]
         t0 = time.perf_counter()
-        errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
+        if args.separate_calls:
+            errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
+            t1 = time.perf_counter()
+            e_max = B.emax(errors, w.default)
+            st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
+        else:
+            # profile, E_max and solve as one call: no host round trip between their kernels
+            st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
+                g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
+            t1 = time.perf_counter()
         if record and timing:
             add("profile/", h.get_timing(B.CALL_PROFILE))
+            add("solve/", h.get_timing(B.CALL_SOLVE))
         if pending["compress"]:
-            # compress returns with its kernels queued; profile has waited on the stream since, so
-            # the previous step's compress brackets are complete and reading them stalls nothing
+            # compress returns with its kernels queued; the calls above have waited on the stream
+            # since, so the previous step's compress brackets are complete and reading them stalls nothing
             add("compress/", h.get_timing(B.CALL_COMPRESS))
             pending["compress"] = False
-        t1 = time.perf_counter()
-        e_max = B.emax(errors, w.default)
-        st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
-        if record and timing:
-            add("solve/", h.get_timing(B.CALL_SOLVE))
         t2 = time.perf_counter()
         offsets = B.payload_layout(layers, ctab, choice, w.bucket)
         h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
@@ -168,7 +175,8 @@ def main():
         t3 = time.perf_counter()
         if record:
             # host clocks: compress only queues its kernels, their GPU time falls into the wait of
-            # the next step's profile call (or the final synchronize)
+            # the next step's profile call (or the final synchronize); with the one-call form
+            # "profile" covers profile + solve and "solve" only the reading of the brackets
             phase["profile"] += t1 - t0
             phase["solve"] += t2 - t1
             phase["compress"] += t3 - t2
@@ -249,6 +257,7 @@ def main():
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
                    "reuse_thresholds": not args.sample_every_call,
+                   "profile_and_solve": "three calls" if args.separate_calls else "one call",
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
         # host wall clock per call; compress returns with its kernels queued, so most of its GPU

@@ -13,6 +13,8 @@
  *   lgreco_emax      E_max = total error of the uniform default (Algorithm 1, step 2)
  *   lgreco_solve     the layer x discretised-error dynamic program and its back-trace
  *                    (Algorithm 1, the DP and PD tables)
+ *   lgreco_profile_solve  the three calls above as one, without a host round trip between
+ *                    the profile's kernels and the solver's
  *   lgreco_compress  apply the chosen per-layer setting, produce the payload and update
  *                    the error-feedback buffer (what the paper's communication engine does
  *                    with the mapping, section "Implementation")
@@ -166,6 +168,25 @@ int lgreco_solve_weighted(lgreco_handle_t* h, const double* errors, const int64_
                           const int64_t* weights, int32_t L, int32_t P, double e_max,
                           int32_t n_bins, int32_t* choice, int64_t* total_size,
                           int64_t* total_cost, double* total_error, void* stream);
+
+/* lgreco_profile, lgreco_emax and lgreco_solve in one call (Algorithm 1 from the Errors matrix to
+ * the traced-back assignment): the solve follows the profile on the stream without the host round
+ * trip in between - E_max, the discretised errors and the solver's candidate lists are formed on
+ * the device from the error table the profile kernels just wrote.  Arguments as in the three
+ * calls; results are the same as theirs, tie-breaks included.
+ *   default_cand  candidate index whose uniform use defines E_max
+ *   errors        host out [L x P] (required)
+ *   sizes         host out [L x P] (required here: the solver needs them)
+ *   e_max         host out (required)
+ *   choice        host out [L]
+ * Returns LGRECO_EINFEASIBLE with the minimum-error choice as lgreco_solve does.  Problems the
+ * device-side step does not take (more than 1024 layers, more than 16 candidates, more than 4096
+ * table entries, total size of 2^30 bytes or more) go through the three calls internally. */
+int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* d_ef,
+                         const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
+                         int32_t P, const float* d_q0, int32_t default_cand, int32_t n_bins,
+                         double* errors, int64_t* sizes, double* e_max, int32_t* choice,
+                         int64_t* total_size, double* total_error, void* stream);
 
 /* Byte offset of every layer's payload for a given choice, host arithmetic only.
  * offsets has L+1 entries; layer l's payload is [offsets[l], offsets[l] + size(l, choice[l]))

@@ -56,6 +56,16 @@ struct lgreco_handle {
     int32_t* h_count = nullptr;
     int32_t* h_choice = nullptr;
     int64_t* h_result = nullptr;
+    // lgreco_profile_solve: error and size tables in device memory for the device-side entry build
+    // (the sizes with a pinned staging copy, uploaded when they change), what the build reports back
+    // (pinned: sweep_layer | fixed_choice) and the swept-layer count / status it hands the sweep
+    int64_t* h_sizes = nullptr;
+    int64_t* d_sizes = nullptr;
+    size_t sizes_count = 0;            // entries of h_sizes / d_sizes in use
+    double* d_errors_dev = nullptr;    // error table in device memory (the build forwards it to h_errors)
+    int32_t* h_build = nullptr;
+    int32_t* d_build_host = nullptr;
+    int32_t* d_nsweep = nullptr;
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
@@ -260,7 +270,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_partials, sizeof(double) * (size_t)h->max_tiles * max_cands));
     // Small results (the error table, the solver's output) are written by the kernels straight into
     // pinned host memory: no copy operation between the last kernel and the host's wait.
-    HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_errors), h->h_errors, 0));
     const size_t lp = (size_t)max_layers * max_cands;
     h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
@@ -281,6 +291,12 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->h_result = reinterpret_cast<int64_t*>(h->h_dp_out);
     h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * 8);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
+    HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
+    HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16));
+    HIPCHK_C(hipMalloc(&h->d_errors_dev, sizeof(double) * (size_t)max_layers * max_cands + 16));
+    HIPCHK_C(hipHostMalloc(&h->h_build, sizeof(int32_t) * 2 * (size_t)max_layers, hipHostMallocDefault));
+    HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_build_host), h->h_build, 0));
+    HIPCHK_C(hipMalloc(&h->d_nsweep, sizeof(int32_t) * 2));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
     for (Timing& t : h->tms) {
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&t.ev[i]));
@@ -305,6 +321,11 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipHostFree(h->h_errors);
     (void)hipFree(h->d_dp_in);
     (void)hipFree(h->d_pd);
+    (void)hipHostFree(h->h_sizes);
+    (void)hipFree(h->d_sizes);
+    (void)hipFree(h->d_errors_dev);
+    (void)hipHostFree(h->h_build);
+    (void)hipFree(h->d_nsweep);
     (void)hipHostFree(h->h_bins);
     (void)hipHostFree(h->h_dp_in);
     (void)hipHostFree(h->h_dp_out);
@@ -417,12 +438,13 @@ int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand
     return LGRECO_OK;
 }
 
-int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
-                   int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, double* errors,
-                   int64_t* sizes, void* stream) {
-    if (!h || !d_grads || !layers || !cands || !errors || L <= 0 || P <= 0) return LGRECO_EINVAL;
+// Queues every kernel of the profile on s; they write the error table to d_err (device memory, or
+// the pinned host table as the kernels address it).
+static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
+                           int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, int64_t* sizes,
+                           double* d_err, hipStream_t s) {
+    if (!h || !d_grads || !layers || !cands || L <= 0 || P <= 0) return LGRECO_EINVAL;
     if (P > h->max_cands) return LGRECO_ENOSPACE;
-    hipStream_t s = (hipStream_t)stream;
     begin_call(h, s, LGRECO_CALL_PROFILE);
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
@@ -513,20 +535,30 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
                            ntk_all <= (int)kMaxTopk, h->tm, s));
     if (qp.nq) {
         Section sec(h->tm, "reduce_partials");
-        HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, h->d_errors, s));
+        HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, d_err, s));
     }
-    if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, h->d_errors, P, h->tm, s));
+    if (ntk) HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, ntk, tk_col, d_err, P, h->tm, s));
     for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
                            first + (int)kMaxTopk >= ntk_all, h->tm, s));
-        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, h->d_errors, P, h->tm, s));
+        HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, d_err, P, h->tm, s));
     }
     if (nlr) {
         HIPCHK(lowrank_profile(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q0, h->cfg.r_max,
-                               lr_rank, lr_col, nlr, h->d_errors, P, h->tm, s));
+                               lr_rank, lr_col, nlr, d_err, P, h->tm, s));
     }
+    return LGRECO_OK;
+}
+
+int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
+                   int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, double* errors,
+                   int64_t* sizes, void* stream) {
+    if (!errors) return LGRECO_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int st = profile_enqueue(h, d_grads, d_ef, layers, L, cands, P, d_q0, sizes, h->d_errors, s);
+    if (st != LGRECO_OK) return st;
     HIPCHK(hipStreamSynchronize(s));      // the kernels wrote h_errors
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     return LGRECO_OK;
@@ -627,7 +659,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         // the kernel itself fetches the input block from the pinned staging memory
         const size_t in_bytes = h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count;
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
-                    h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16)};
+                    h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr};
         {
             Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s));
@@ -650,6 +682,106 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     double terr = 0.0;
     int64_t tsize = 0;
     for (int l = 0; l < L; ++l) {
+        terr += errors[(size_t)l * P + choice[l]];
+        tsize += sizes[(size_t)l * P + choice[l]];
+    }
+    if (total_size) *total_size = tsize;
+    if (total_error) *total_error = terr;
+    return LGRECO_OK;
+}
+
+int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
+                         int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, int32_t default_cand,
+                         int32_t n_bins, double* errors, int64_t* sizes, double* e_max, int32_t* choice,
+                         int64_t* total_size, double* total_error, void* stream) {
+    if (!h || !errors || !sizes || !e_max || !choice || L <= 0 || P <= 0) return LGRECO_EINVAL;
+    if (default_cand < 0 || default_cand >= P || n_bins < 1 || n_bins > LGRECO_MAX_BINS) return LGRECO_EINVAL;
+    if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    // the device-side build reads the error table from device memory and passes it on to the host
+    const bool on_device = L <= kBuildThreads && P <= kBuildMaxP && L * P <= kBuildMaxLP;
+    int st = profile_enqueue(h, d_grads, d_ef, layers, L, cands, P, d_q0, sizes,
+                             on_device ? h->d_errors_dev : h->d_errors, s);
+    if (st != LGRECO_OK) return st;
+    // The device-side build takes 32-bit costs only; anything it does not take goes the three
+    // calls' route (same results, one more host round trip).
+    int64_t worst = 0;
+    for (int l = 0; l < L; ++l) {
+        int64_t lmax = 0;
+        for (int c = 0; c < P; ++c) {
+            const int64_t sz = sizes[(size_t)l * P + c];
+            if (sz < 0 || sz >= ((int64_t)1 << 45)) return LGRECO_EINVAL;
+            lmax = std::max(lmax, sz);
+        }
+        worst += lmax;
+    }
+    if (!on_device || worst >= ((int64_t)1 << 30)) {
+        if (on_device)      // (the rare wide-cost case: fetch the table the kernels left on the device)
+            HIPCHK(hipMemcpyAsync(h->h_errors, h->d_errors_dev, sizeof(double) * (size_t)L * P,
+                                  hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
+        st = lgreco_emax(errors, L, P, default_cand, e_max);
+        if (st != LGRECO_OK) return st;
+        return lgreco_solve(h, errors, sizes, L, P, *e_max, n_bins, choice, total_size, total_error, stream);
+    }
+    begin_call(h, s, LGRECO_CALL_SOLVE);
+    // the size table lives on the device and is uploaded when it changes (a training loop repeats it)
+    if (h->sizes_count != (size_t)L * P || std::memcmp(h->h_sizes, sizes, sizeof(int64_t) * (size_t)L * P) != 0) {
+        std::memcpy(h->h_sizes, sizes, sizeof(int64_t) * (size_t)L * P);
+        h->sizes_count = (size_t)L * P;
+        HIPCHK(hipMemcpyAsync(h->d_sizes, h->h_sizes, sizeof(int64_t) * (size_t)L * P, hipMemcpyHostToDevice, s));
+        HIPCHK(hipStreamSynchronize(s));      // h_sizes may be rewritten by the next call
+    }
+    DpBuildParams bp{h->d_errors_dev, h->d_sizes, h->d_errors, L, P, n_bins, default_cand, P, h->d_entries,
+                     h->d_count, h->d_build_host, h->d_build_host + L, h->d_nsweep, h->d_result};
+    DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, L, n_bins, 0, 0, 0, P,
+                nullptr, nullptr, 0, h->d_nsweep};
+    {
+        Section sec(h->tm, "dp_solve", true);
+        HIPCHK(launch_dp_build(bp, s));
+        HIPCHK(launch_dp(dp, true, n_bins, s));
+    }
+    HIPCHK(hipStreamSynchronize(s));      // error table, build report and solver output are in pinned memory
+    std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
+    const int64_t status = h->h_result[0];
+    {
+        const uint64_t bits = (uint64_t)h->h_result[6];
+        std::memcpy(e_max, &bits, sizeof(double));
+    }
+    if (status == 3) return LGRECO_EINVAL;                  // a NaN in the error table
+    if (h->tm->level >= 1 && status == 0) {
+        h->sub_name[0] = "dp_solve.sweep";
+        h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
+        h->sub_name[1] = "dp_solve.backtrace";
+        h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
+        h->n_sub = 2;
+    }
+    if (status == 1) {                                      // report each layer's minimum-error candidate
+        for (int l = 0; l < L; ++l) {
+            int best = 0;
+            for (int c = 1; c < P; ++c)
+                if (errors[(size_t)l * P + c] < errors[(size_t)l * P + best]) best = c;
+            choice[l] = best;
+        }
+        return LGRECO_EINFEASIBLE;
+    }
+    if (status != 0) {
+        h->hip_error = "dp back-trace inconsistent";
+        return LGRECO_EHIP;
+    }
+    const int n_sweep = (int)h->h_result[5];
+    const int32_t* const sweep_layer = h->h_build;
+    const int32_t* const fixed_choice = h->h_build + L;
+    for (int l = 0; l < L; ++l) choice[l] = fixed_choice[l];
+    for (int i = 0; i < n_sweep; ++i) choice[sweep_layer[i]] = h->h_choice[i];
+    double terr = 0.0;
+    int64_t tsize = 0;
+    for (int l = 0; l < L; ++l) {
+        if (choice[l] < 0 || choice[l] >= P) {
+            h->hip_error = "device-side entry build left a layer without a choice";
+            return LGRECO_EHIP;
+        }
         terr += errors[(size_t)l * P + choice[l]];
         tsize += sizes[(size_t)l * P + choice[l]];
     }

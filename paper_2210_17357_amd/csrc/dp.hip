@@ -71,7 +71,14 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     const bool lds_bins = p.bt_lds != 0;
     uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
     const int bstride = p.max_count;
-    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
+    // Entry lists built on the device (dp_build_kernel): the number of swept layers and the status
+    // it found come from memory; anything but "ok" there ends the solve.
+    int L = p.L;
+    if (p.L_dev) {
+        if (p.L_dev[1] != 0) return;
+        L = p.L_dev[0];
+    }
 
     const uint64_t t_begin = wall_clock64();
     if (p.host_in) {
@@ -83,8 +90,8 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
 
     const int stage = min(kDpStageMax, kDpStageEntries / bstride);     // layers per stage
-    for (int l0 = 0; l0 < p.L; l0 += stage) {
-        const int nl = min(stage, p.L - l0);
+    for (int l0 = 0; l0 < L; l0 += stage) {
+        const int nl = min(stage, L - l0);
         __syncthreads();                              // previous stage fully consumed, row written
         for (int i = tid; i < nl * bstride; i += kDpThreads) {
             const DpEntry en = p.entries[(size_t)l0 * bstride + i];
@@ -192,13 +199,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             // the bin it stands for from LDS when the table fits there
             int e = be;
             if (lds_bins) {
-                for (int l = p.L - 1; l >= 0; --l) {
+                for (int l = L - 1; l >= 0; --l) {
                     const int k = p.pd[(size_t)l * width + e];
                     s_pick[l] = (uint8_t)k;
                     e -= s_bins[l * bstride + k];
                 }
             } else {
-                for (int l = p.L - 1; l >= 0; --l) {
+                for (int l = L - 1; l >= 0; --l) {
                     const int k = p.pd[(size_t)l * width + e];
                     const DpEntry en = p.entries[(size_t)l * bstride + k];
                     p.choice[l] = en.cand;
@@ -211,7 +218,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     __syncthreads();
     const bool feasible = s_val[0] < (int64_t)kInf;
     if (feasible && lds_bins)
-        for (int l = tid; l < p.L; l += kDpThreads)
+        for (int l = tid; l < L; l += kDpThreads)
             p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
     if (tid == 0) {
         if (!feasible) {
@@ -227,6 +234,155 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         p.result[3] = (int64_t)(t_sweep - t_begin);
         p.result[4] = (int64_t)(wall_clock64() - t_sweep);
     }
+}
+
+// ------------------------------------------------------------------ entry lists on the device
+// What lgreco_solve does on the host between the error table and the sweep, for a solve that
+// follows the profile on the same stream without a host round trip: E_max (the default
+// candidate's errors summed in layer order), bins = floor(err * D / E_max) in fp64, equal bins
+// merged (smallest size, lowest index among equals), entries beaten in both bin and size dropped,
+// layers with a single entry of bin 0 fixed, the others compacted into the sweep's tables.  One
+// workgroup.  Binning, merging and pruning run with one thread per (layer, candidate), each
+// comparing itself with the layer's other candidates in LDS; then one thread per layer counts
+// what is left, the swept layers are numbered in layer order and their entries written in
+// candidate order, as on the host.
+__global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p) {
+    // tables from device memory into LDS; the error table is passed on to the host's pinned copy
+    // on the way (posted writes; reading the tables from there instead took 30 us)
+    __shared__ __align__(16) double s_err[kBuildMaxLP];
+    __shared__ __align__(16) int64_t s_size[kBuildMaxLP];
+    __shared__ int32_t s_bin[kBuildMaxLP];
+    __shared__ uint8_t s_keep[kBuildMaxLP], s_kept[kBuildMaxLP];
+    __shared__ double s_emax;
+    __shared__ int32_t s_wave[kBuildThreads / 64];
+    __shared__ int32_t s_flags[2];          // [0] a layer without usable candidate, [1] invalid input
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int L = p.L, P = p.P, LP = L * P;
+    const double D = (double)p.D;
+    if (tid < 2) s_flags[tid] = 0;
+    {
+        const int n16 = (LP + 1) / 2;             // the tables are allocated in whole 16-byte words
+        const uint4* const ge = reinterpret_cast<const uint4*>(p.errors);
+        const uint4* const gs = reinterpret_cast<const uint4*>(p.sizes);
+        uint4* const he = reinterpret_cast<uint4*>(p.errors_host);
+        for (int i = tid; i < n16; i += kBuildThreads) {
+            const uint4 e = ge[i];
+            reinterpret_cast<uint4*>(s_err)[i] = e;
+            he[i] = e;
+            reinterpret_cast<uint4*>(s_size)[i] = gs[i];
+        }
+    }
+    __syncthreads();
+    // E_max: errors[l][default] summed for l = 0 .. L-1 in that order (bit-identical to the host loop)
+    if (wave == 0) {
+        double v[kBuildThreads / 64];
+#pragma unroll
+        for (int k = 0; k < kBuildThreads / 64; ++k) {
+            const int l = lane + 64 * k;
+            v[k] = l < L ? s_err[l * P + p.default_cand] : 0.0;
+        }
+        double sum = 0.0;
+#pragma unroll
+        for (int k = 0; k < kBuildThreads / 64; ++k) {
+            const int n = min(64, L - 64 * k);
+            for (int i = 0; i < n; ++i) {
+                const uint64_t b = __builtin_bit_cast(uint64_t, v[k]);
+                const uint32_t lo = readlane_u32((uint32_t)b, i), hi = readlane_u32((uint32_t)(b >> 32), i);
+                sum += __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+            }
+        }
+        if (lane == 0) s_emax = sum;
+    }
+    __syncthreads();
+    const double e_max = s_emax;
+    if (!(e_max == e_max) && tid == 0) s_flags[1] = 1;
+    // bins, one (layer, candidate) per thread and pass
+    for (int i = tid; i < LP; i += kBuildThreads) {
+        double e = s_err[i];
+        if (!(e == e)) s_flags[1] = 1;
+        if (e < 0.0) e = 0.0;
+        int32_t b;
+        if (e_max > 0.0) {
+            const double q = floor((e * D) / e_max);
+            b = (q <= D) ? (int32_t)q : -1;
+        } else {
+            b = (e <= 0.0) ? 0 : -1;
+        }
+        s_bin[i] = (e == e) ? b : -1;
+    }
+    __syncthreads();
+    // representative of every bin value: smallest size, lowest index among equals
+    for (int i = tid; i < LP; i += kBuildThreads) {
+        const int l = i / P, c = i - l * P;
+        const int32_t b = s_bin[i];
+        const int64_t sz = s_size[i];
+        bool k = b >= 0;
+        for (int o = 0; o < P; ++o) {
+            const int32_t bo = s_bin[l * P + o];
+            const int64_t so = s_size[l * P + o];
+            if (o != c && bo == b && (so < sz || (so == sz && o < c))) k = false;
+        }
+        s_keep[i] = k ? 1 : 0;
+    }
+    __syncthreads();
+    // a representative that another one beats in both bin and size never lies on the traced path
+    for (int i = tid; i < LP; i += kBuildThreads) {
+        const int l = i / P, c = i - l * P;
+        const int32_t b = s_bin[i];
+        const int64_t sz = s_size[i];
+        bool k = s_keep[i] != 0;
+        for (int o = 0; o < P; ++o)
+            if (o != c && s_keep[l * P + o] && s_bin[l * P + o] < b && s_size[l * P + o] <= sz) k = false;
+        s_kept[i] = k ? 1 : 0;
+    }
+    __syncthreads();
+    // one thread per layer: what is left of its list
+    const bool active = tid < L;
+    int cnt = 0, first_bin = -1, first_cand = -1;
+    if (active) {
+        for (int c = P - 1; c >= 0; --c)
+            if (s_kept[tid * P + c]) { ++cnt; first_bin = s_bin[tid * P + c]; first_cand = c; }
+    }
+    const bool dead = active && cnt == 0;
+    const bool fixed = active && cnt == 1 && first_bin == 0;
+    const bool swept = active && !dead && !fixed;
+    if (dead) s_flags[0] = 1;
+    // position among the swept layers, in layer order
+    const unsigned long long m = __ballot(swept);
+    const int before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (lane == 0) s_wave[wave] = (int)__popcll(m);
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kBuildThreads / 64; ++w) {
+        if (w < wave) base += s_wave[w];
+        total += s_wave[w];
+    }
+    const int slot = base + before;
+    if (active) p.fixed_choice[tid] = fixed ? first_cand : -1;
+    if (swept) {
+        p.count[slot] = cnt;
+        p.sweep_layer[slot] = tid;
+        DpEntry* const en = p.entries + (size_t)slot * p.stride;
+        int r = 0;
+        for (int c = 0; c < P; ++c)
+            if (s_kept[tid * P + c]) en[r++] = DpEntry{s_bin[tid * P + c], c, s_size[tid * P + c]};
+    }
+    if (tid == 0) {
+        const int status = s_flags[1] ? 3 : (s_flags[0] ? 1 : 0);  // 3: invalid input, 1: infeasible
+        p.n_sweep[0] = total;
+        p.n_sweep[1] = status;
+        p.result[0] = status;
+        p.result[5] = total;
+        p.result[6] = (int64_t)__builtin_bit_cast(uint64_t, e_max);
+    }
+}
+
+hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s) {
+    if (p.L < 1 || p.L > kBuildThreads || p.P < 1 || p.P > kBuildMaxP || p.L * p.P > kBuildMaxLP)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dp_build_kernel, dim3(1), dim3(kBuildThreads), 0, s, p);
+    return hipGetLastError();
 }
 
 constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static (160 KB per CU)

@@ -67,7 +67,30 @@ struct DpParams {
     const uint4* host_in;
     uint4* dev_in;
     int32_t in_vec;
+    // Not null: the entry lists were built on the device; [0] is the number of swept layers (L above
+    // is then only the capacity the LDS tables are sized for), [1] the status the build found
+    // (not 0: nothing to solve).
+    const int32_t* L_dev;
 };
+// Entry lists built on the device from the error table (see dp_build_kernel).
+constexpr int kBuildThreads = 1024;   // layers per solve on this path
+constexpr int kBuildMaxP = 16;        // candidates per layer on this path
+constexpr int kBuildMaxLP = 4096;     // table entries (layers x candidates) on this path: 64 KB of LDS
+struct DpBuildParams {
+    const double* errors;     // [L x P] device memory
+    const int64_t* sizes;     // [L x P] device memory
+    double* errors_host;      // [L x P] the host's pinned copy of the error table, written here
+    int32_t L, P, D, default_cand;
+    int32_t stride;           // row stride of `entries` (>= P)
+    DpEntry* entries;         // out: swept layers, compacted
+    int32_t* count;           // out [swept]
+    int32_t* sweep_layer;     // out [swept] original index of every swept layer
+    int32_t* fixed_choice;    // out [L] candidate of a layer fixed here, -1 otherwise
+    int32_t* n_sweep;         // out, device memory, read by the sweep: [0] swept layers, [1] status
+    int64_t* result;          // out: [0] status (0 ok, 1 infeasible, 3 invalid input), [5] swept layers,
+                              //      [6] bit pattern of E_max
+};
+hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s);
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
 // max_bin: largest bin in entries
 hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s);

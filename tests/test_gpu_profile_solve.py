@@ -1,0 +1,94 @@
+"""GPU parity of lgreco_profile_solve: the one-call form of profile + E_max + solve.  Its
+candidate lists are formed on the device; everything it returns must equal what the three
+separate calls return on the same data (and through them the oracle): the error table bit for
+bit, E_max bit for bit, the assignment, the totals, and the infeasible / fixed-layer cases."""
+import numpy as np
+import pytest
+
+from oracle import solver
+from paper_2210_17357_amd import workloads as W
+
+from gpu_util import tables, to_device, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(kind):
+    if kind == "mixed":
+        w = W.workload("c4_gpt2_medium_mixed")
+        shapes = tuple(W.gpt2_medium_shapes(layers=3, d=128, d_ff=512, vocab=2000, ctx=64))
+        return W.Workload("ps_mixed", shapes, w.candidates, w.default, 400, w.values, w.ef, w.scale_exp)
+    if kind == "topk":
+        w = W.workload("c2_resnet50_topk")
+        shapes = tuple(W.resnet50_shapes(num_classes=10))[:60]
+        return W.Workload("ps_topk", shapes, w.candidates, w.default, 1000, w.values, w.ef, w.scale_exp)
+    w = W.workload("c1_resnet18_quant")
+    return W.Workload("ps_quant", w.shapes, w.candidates, w.default, w.n_bins, w.values, w.ef, w.scale_exp)
+
+
+def _both(w, batch, n_bins, default):
+    from paper_2210_17357_amd import binding as B
+    torch_cuda()
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    h = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed)
+    errors, sizes = h.profile(g, e, layers, ctab)
+    e_max = B.emax(errors, default)
+    st, choice, tsize, terr = h.solve(errors, sizes, e_max, n_bins)
+    one = h.profile_solve(g, e, layers, ctab, default, n_bins)
+    h.close()
+    return (st, errors, sizes, e_max, choice, tsize, terr), one
+
+
+@pytest.mark.parametrize("kind", ["mixed", "topk", "quant"])
+def test_one_call_equals_three(kind):
+    from paper_2210_17357_amd import binding as B
+    w = _workload(kind)
+    batch = W.generate(w)
+    three, one = _both(w, batch, w.n_bins, w.default)
+    st3, errors3, sizes3, emax3, choice3, tsize3, terr3 = three
+    st1, errors1, sizes1, emax1, choice1, tsize1, terr1 = one
+    assert st3 == B.OK and st1 == B.OK
+    assert np.array_equal(errors1, errors3) and np.array_equal(sizes1, sizes3)
+    assert emax1 == emax3                                   # summed in the same order
+    assert np.array_equal(choice1, choice3) and tsize1 == tsize3 and terr1 == terr3
+    ref_choice, ref_size, _ = solver.solve(errors1, sizes1, emax1, w.n_bins)
+    assert np.array_equal(choice1, ref_choice) and tsize1 == ref_size
+
+
+def test_coarse_bins_and_other_defaults():
+    """Few bins merge many candidates into equal bins and fix whole layers (single entry of bin 0);
+    every candidate as the default moves E_max over orders of magnitude."""
+    from paper_2210_17357_amd import binding as B
+    w = _workload("mixed")
+    batch = W.generate(w)
+    for n_bins in (1, 2, 7, 50, 4000, 16384):
+        for default in (0, len(w.candidates) // 2, len(w.candidates) - 1):
+            three, one = _both(w, batch, n_bins, default)
+            assert one[0] == three[0], (n_bins, default)
+            assert one[3] == three[3]
+            assert np.array_equal(one[4], three[4]), (n_bins, default)
+            if one[0] == B.OK:
+                assert one[5] == three[5] and one[6] == three[6]
+                ref_choice, ref_size, _ = solver.solve(one[1], one[2], one[3], n_bins)
+                assert np.array_equal(one[4], ref_choice) and one[5] == ref_size
+
+
+def test_zero_gradient_layers_and_zero_budget():
+    """All-zero layers have zero error for every candidate (every bin 0: one entry survives, the
+    layer is fixed); an all-zero model makes E_max = 0."""
+    from paper_2210_17357_amd import binding as B
+    w = _workload("quant")
+    batch = W.generate(w)
+    o, n = int(batch.offsets[3]), int(batch.numels[3])
+    batch.grads[o:o + n] = 0
+    batch.ef[o:o + n] = 0
+    three, one = _both(w, batch, 100, w.default)
+    assert one[0] == three[0] == B.OK and np.array_equal(one[4], three[4]) and one[5] == three[5]
+    batch.grads[:] = 0
+    batch.ef[:] = 0
+    three, one = _both(w, batch, 100, w.default)
+    assert one[3] == three[3] == 0.0
+    assert one[0] == three[0] and np.array_equal(one[4], three[4])
