@@ -251,7 +251,7 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     // on the way (posted writes; reading the tables from there instead took 30 us)
     __shared__ __align__(16) double s_err[kBuildMaxLP];
     __shared__ __align__(16) int64_t s_size[kBuildMaxLP];
-    __shared__ int32_t s_bin[kBuildMaxLP];
+    __shared__ int32_t s_bin[kBuildMaxLP], s_sz32[kBuildMaxLP];   // sizes below 2^30 on this path
     __shared__ uint8_t s_keep[kBuildMaxLP], s_kept[kBuildMaxLP];
     __shared__ double s_emax;
     __shared__ int32_t s_wave[kBuildThreads / 64];
@@ -273,25 +273,20 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         }
     }
     __syncthreads();
-    // E_max: errors[l][default] summed for l = 0 .. L-1 in that order (bit-identical to the host loop)
-    if (wave == 0) {
-        double v[kBuildThreads / 64];
-#pragma unroll
-        for (int k = 0; k < kBuildThreads / 64; ++k) {
-            const int l = lane + 64 * k;
-            v[k] = l < L ? s_err[l * P + p.default_cand] : 0.0;
-        }
+    // E_max: errors[l][default] summed for l = 0 .. L-1 in that order (bit-identical to the host
+    // loop): one thread, the LDS reads issued in batches ahead of the dependent adds
+    if (tid == 0) {
         double sum = 0.0;
+        int l = 0;
+        for (; l + 32 <= L; l += 32) {
+            double v[32];
 #pragma unroll
-        for (int k = 0; k < kBuildThreads / 64; ++k) {
-            const int n = min(64, L - 64 * k);
-            for (int i = 0; i < n; ++i) {
-                const uint64_t b = __builtin_bit_cast(uint64_t, v[k]);
-                const uint32_t lo = readlane_u32((uint32_t)b, i), hi = readlane_u32((uint32_t)(b >> 32), i);
-                sum += __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-            }
+            for (int u = 0; u < 32; ++u) v[u] = s_err[(l + u) * P + p.default_cand];
+#pragma unroll
+            for (int u = 0; u < 32; ++u) sum += v[u];
         }
-        if (lane == 0) s_emax = sum;
+        for (; l < L; ++l) sum += s_err[l * P + p.default_cand];
+        s_emax = sum;
     }
     __syncthreads();
     const double e_max = s_emax;
@@ -309,19 +304,27 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
             b = (e <= 0.0) ? 0 : -1;
         }
         s_bin[i] = (e == e) ? b : -1;
+        s_sz32[i] = (int32_t)s_size[i];
     }
     __syncthreads();
     // representative of every bin value: smallest size, lowest index among equals
     for (int i = tid; i < LP; i += kBuildThreads) {
         const int l = i / P, c = i - l * P;
         const int32_t b = s_bin[i];
-        const int64_t sz = s_size[i];
+        const int32_t sz = s_sz32[i];
         bool k = b >= 0;
-        for (int o = 0; o < P; ++o) {
-            const int32_t bo = s_bin[l * P + o];
-            const int64_t so = s_size[l * P + o];
-            if (o != c && bo == b && (so < sz || (so == sz && o < c))) k = false;
+        // all of the layer's candidates are read before the first comparison (fixed trip count;
+        // reads past the layer's last candidate are clamped and not used)
+        int32_t bo[kBuildMaxP], so[kBuildMaxP];
+#pragma unroll
+        for (int o = 0; o < kBuildMaxP; ++o) {
+            const int j = min(l * P + o, LP - 1);
+            bo[o] = s_bin[j];
+            so[o] = s_sz32[j];
         }
+#pragma unroll
+        for (int o = 0; o < kBuildMaxP; ++o)
+            if (o < P && o != c && bo[o] == b && (so[o] < sz || (so[o] == sz && o < c))) k = false;
         s_keep[i] = k ? 1 : 0;
     }
     __syncthreads();
@@ -329,10 +332,20 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     for (int i = tid; i < LP; i += kBuildThreads) {
         const int l = i / P, c = i - l * P;
         const int32_t b = s_bin[i];
-        const int64_t sz = s_size[i];
+        const int32_t sz = s_sz32[i];
         bool k = s_keep[i] != 0;
-        for (int o = 0; o < P; ++o)
-            if (o != c && s_keep[l * P + o] && s_bin[l * P + o] < b && s_size[l * P + o] <= sz) k = false;
+        int32_t bo[kBuildMaxP], so[kBuildMaxP];
+        uint8_t ko[kBuildMaxP];
+#pragma unroll
+        for (int o = 0; o < kBuildMaxP; ++o) {
+            const int j = min(l * P + o, LP - 1);
+            bo[o] = s_bin[j];
+            so[o] = s_sz32[j];
+            ko[o] = s_keep[j];
+        }
+#pragma unroll
+        for (int o = 0; o < kBuildMaxP; ++o)
+            if (o < P && o != c && ko[o] && bo[o] < b && so[o] <= sz) k = false;
         s_kept[i] = k ? 1 : 0;
     }
     __syncthreads();
