@@ -46,9 +46,9 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--one-call", action="store_true",
-                    help="lgreco_profile_solve instead of lgreco_profile, lgreco_emax and lgreco_solve "
-                         "(the same rate on this host: the device-side list build costs what the host round trip costs)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="lgreco_profile, lgreco_emax and lgreco_solve as three calls instead of "
+                         "lgreco_profile_solve (same results; about 8 us per step slower on the largest workload)")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
@@ -151,7 +151,7 @@ def main():
     def step(i, record):
         ef = ef_pool[i]
         t0 = time.perf_counter()
-        if not args.one_call:
+        if args.separate_calls:
             errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
             t1 = time.perf_counter()
             e_max = B.emax(errors, w.default)
@@ -258,7 +258,7 @@ def main():
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
                    "reuse_thresholds": not args.sample_every_call,
-                   "profile_and_solve": "one call" if args.one_call else "three calls",
+                   "profile_and_solve": "three calls" if args.separate_calls else "one call",
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
         # host wall clock per call; compress returns with its kernels queued, so most of its GPU
