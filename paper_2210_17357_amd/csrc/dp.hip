@@ -242,8 +242,8 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
 // candidate's errors summed in layer order), bins = floor(err * D / E_max) in fp64, equal bins
 // merged (smallest size, lowest index among equals), entries beaten in both bin and size dropped,
 // layers with a single entry of bin 0 fixed, the others compacted into the sweep's tables.  One
-// workgroup.  Binning, merging and pruning run with one thread per (layer, candidate), each
-// comparing itself with the layer's other candidates in LDS; then one thread per layer counts
+// workgroup.  Binning, then merging and pruning in one pass, run with one thread per (layer,
+// candidate), each comparing itself with the layer's other candidates in LDS; then one thread per layer counts
 // what is left, the swept layers are numbered in layer order and their entries written in
 // candidate order, as on the host.
 __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p) {
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     __shared__ __align__(16) double s_err[kBuildMaxLP];
     __shared__ __align__(16) int64_t s_size[kBuildMaxLP];
     __shared__ int32_t s_bin[kBuildMaxLP], s_sz32[kBuildMaxLP];   // sizes below 2^30 on this path
-    __shared__ uint8_t s_keep[kBuildMaxLP], s_kept[kBuildMaxLP];
+    __shared__ uint8_t s_kept[kBuildMaxLP];
     __shared__ double s_emax;
     __shared__ int32_t s_wave[kBuildThreads / 64];
     __shared__ int32_t s_flags[2];          // [0] a layer without usable candidate, [1] invalid input
@@ -307,7 +307,10 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         s_sz32[i] = (int32_t)s_size[i];
     }
     __syncthreads();
-    // representative of every bin value: smallest size, lowest index among equals
+    // What stays of a layer's list: a candidate goes when another usable one has the same bin and
+    // a smaller size (or the same size and a lower index: one representative per bin), or a smaller
+    // bin and a size that is not larger.  (The host states the second rule for representatives
+    // only; a usable candidate that beats this one has a representative that does, too.)
     for (int i = tid; i < LP; i += kBuildThreads) {
         const int l = i / P, c = i - l * P;
         const int32_t b = s_bin[i];
@@ -323,29 +326,11 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
             so[o] = s_sz32[j];
         }
 #pragma unroll
-        for (int o = 0; o < kBuildMaxP; ++o)
-            if (o < P && o != c && bo[o] == b && (so[o] < sz || (so[o] == sz && o < c))) k = false;
-        s_keep[i] = k ? 1 : 0;
-    }
-    __syncthreads();
-    // a representative that another one beats in both bin and size never lies on the traced path
-    for (int i = tid; i < LP; i += kBuildThreads) {
-        const int l = i / P, c = i - l * P;
-        const int32_t b = s_bin[i];
-        const int32_t sz = s_sz32[i];
-        bool k = s_keep[i] != 0;
-        int32_t bo[kBuildMaxP], so[kBuildMaxP];
-        uint8_t ko[kBuildMaxP];
-#pragma unroll
         for (int o = 0; o < kBuildMaxP; ++o) {
-            const int j = min(l * P + o, LP - 1);
-            bo[o] = s_bin[j];
-            so[o] = s_sz32[j];
-            ko[o] = s_keep[j];
+            const bool same = bo[o] == b && (so[o] < sz || (so[o] == sz && o < c));
+            const bool lower = bo[o] >= 0 && bo[o] < b && so[o] <= sz;
+            if (o < P && o != c && (same || lower)) k = false;
         }
-#pragma unroll
-        for (int o = 0; o < kBuildMaxP; ++o)
-            if (o < P && o != c && ko[o] && bo[o] < b && so[o] <= sz) k = false;
         s_kept[i] = k ? 1 : 0;
     }
     __syncthreads();
