@@ -92,3 +92,18 @@ def test_zero_gradient_layers_and_zero_budget():
     three, one = _both(w, batch, 100, w.default)
     assert one[3] == three[3] == 0.0
     assert one[0] == three[0] and np.array_equal(one[4], three[4])
+
+
+def test_more_candidates_than_the_device_side_step_takes():
+    """17 or more candidates per layer: the call goes through the three calls internally."""
+    from paper_2210_17357_amd import binding as B
+    base = _workload("mixed")
+    cands = tuple((W.QUANT, float(b)) for b in range(2, 9)) + tuple(
+        (W.TOPK, d) for d in (0.3, 0.2, 0.1, 0.05, 0.03, 0.02, 0.01, 0.005, 0.003, 0.002, 0.001))
+    assert len(cands) == 18
+    w = W.Workload("ps_wide", base.shapes, cands, 2, 500, base.values, base.ef, base.scale_exp)
+    batch = W.generate(w)
+    three, one = _both(w, batch, w.n_bins, w.default)
+    assert one[0] == three[0] == B.OK
+    assert np.array_equal(one[1], three[1]) and one[3] == three[3]
+    assert np.array_equal(one[4], three[4]) and one[5] == three[5] and one[6] == three[6]
