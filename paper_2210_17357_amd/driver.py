@@ -4,7 +4,7 @@ every `period` steps, once `warmup` steps have passed, the error table is built 
 accumulated gradients (no error feedback), the budget is the uniform default's error, the DP picks
 the per-layer parameters, and the communication engine uses them until the next run.
 
-This class only sequences calls of the C ABI (accumulate, profile, emax, solve, payload_layout,
+This class only sequences calls of the C ABI (accumulate, profile_solve, payload_layout,
 compress); it does no arithmetic on gradients itself.
 """
 from __future__ import annotations
@@ -43,9 +43,8 @@ class PeriodicRun:
         self.in_window += 1
         self.step_count += 1
         if self.step_count >= self.warmup and self.in_window >= self.period:
-            errors, sizes = self.h.profile(self.acc, None, self.layers, self.cands, d_q0)
-            e_max = B.emax(errors, self.default)
-            st, choice, _, _ = self.h.solve(errors, sizes, e_max, self.n_bins)
+            st, errors, sizes, e_max, choice, _, _ = self.h.profile_solve(
+                self.acc, None, self.layers, self.cands, self.default, self.n_bins, d_q0)
             if st == B.OK:
                 self.choice = choice
                 self.offsets = B.payload_layout(self.layers, self.cands, choice, self.bucket)
