@@ -266,22 +266,29 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const double* __re
                                                                int stride, ReduceCols cols,
                                                                const DevLayer* __restrict__ layers,
                                                                double* __restrict__ errors) {
-    __shared__ double s[256];
+    // all columns together: per thread the same strided sums, then the same tree per column
+    __shared__ double s[kMaxQuant][256];
     const DevLayer L = layers[blockIdx.x];
-    for (int ci = 0; ci < cols.n; ++ci) {
-        const int c = cols.col[ci];
-        double a = 0.0;
-        for (int t = L.tile_begin + threadIdx.x; t < L.tile_end; t += 256)
-            a += partials[(size_t)t * stride + c];
-        s[threadIdx.x] = a;
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if (threadIdx.x < o) s[threadIdx.x] += s[threadIdx.x + o];
-            __syncthreads();
+    double a[kMaxQuant];
+#pragma unroll
+    for (int ci = 0; ci < kMaxQuant; ++ci) a[ci] = 0.0;
+    for (int t = L.tile_begin + threadIdx.x; t < L.tile_end; t += 256) {
+#pragma unroll
+        for (int ci = 0; ci < kMaxQuant; ++ci)
+            if (ci < cols.n) a[ci] += partials[(size_t)t * stride + cols.col[ci]];
+    }
+#pragma unroll
+    for (int ci = 0; ci < kMaxQuant; ++ci) s[ci][threadIdx.x] = a[ci];
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) {
+#pragma unroll
+            for (int ci = 0; ci < kMaxQuant; ++ci)
+                if (ci < cols.n) s[ci][threadIdx.x] += s[ci][threadIdx.x + o];
         }
-        if (threadIdx.x == 0) errors[(size_t)blockIdx.x * stride + c] = s[0];
         __syncthreads();
     }
+    if (threadIdx.x < cols.n) errors[(size_t)blockIdx.x * stride + cols.col[threadIdx.x]] = s[threadIdx.x][0];
 }
 
 // ------------------------------------------------------------------------- compressor
