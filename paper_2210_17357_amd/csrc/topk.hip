@@ -809,24 +809,47 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(const DevLayer* __
     if (lane == 0) wavecnt[(size_t)blockIdx.x * (kThreads / 64) + wave] = make_uint2(gt, eq);
 }
 
-// per layer: exclusive prefix of the per-wavefront counts, in element order
+// per layer: exclusive prefix of the per-wavefront counts, in element order.  Both counts travel
+// in one 64-bit word (each stays below 2^31: a layer has fewer elements than that) and a thread
+// takes four consecutive entries, so a round of the 256 threads covers 1024 entries with one scan.
 __global__ __launch_bounds__(256) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
                                                             const uint2* __restrict__ wavecnt,
                                                             uint2* __restrict__ wavebase) {
-    __shared__ uint32_t s_tmp[kThreads / 64];
+    __shared__ unsigned long long s_tmp[kThreads / 64];
     const DevLayer L = layers[blockIdx.x];
     if (L.family != LGRECO_TOPK) return;
-    uint32_t run_gt = 0, run_eq = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long run = 0;             // (entries above the threshold) << 32 | entries equal to it
     const int q0 = L.tile_begin * (kThreads / 64), q1 = L.tile_end * (kThreads / 64);
-    for (int b = q0; b < q1; b += 256) {
-        const int q = b + threadIdx.x;
-        const uint2 c = q < q1 ? wavecnt[q] : make_uint2(0, 0);
-        uint32_t tot_gt, tot_eq;
-        const uint32_t pg = block_excl_scan(c.x, s_tmp, &tot_gt);
-        const uint32_t pe = block_excl_scan(c.y, s_tmp, &tot_eq);
-        if (q < q1) wavebase[q] = make_uint2(run_gt + pg, run_eq + pe);
-        run_gt += tot_gt;
-        run_eq += tot_eq;
+    for (int b = q0; b < q1; b += 4 * 256) {
+        const int first = b + 4 * (int)threadIdx.x;
+        unsigned long long c[4], mine = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint2 v = first + i < q1 ? wavecnt[first + i] : make_uint2(0, 0);
+            c[i] = ((unsigned long long)v.x << 32) | v.y;
+            mine += c[i];
+        }
+        unsigned long long inc = mine;
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long n = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += n;
+        }
+        __syncthreads();                     // the previous round is done with s_tmp
+        if (lane == 63) s_tmp[wave] = inc;
+        __syncthreads();
+        unsigned long long before = run, total = 0;
+        for (int w = 0; w < kThreads / 64; ++w) {
+            if (w < wave) before += s_tmp[w];
+            total += s_tmp[w];
+        }
+        before += inc - mine;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (first + i < q1) wavebase[first + i] = make_uint2((uint32_t)(before >> 32), (uint32_t)before);
+            before += c[i];
+        }
+        run += total;
     }
 }
 
