@@ -350,10 +350,14 @@ int lgreco_set_timing(lgreco_handle_t* h, int32_t level) {
 
 static int read_timing(lgreco_handle_t* h, Timing& tm, bool with_sub, const char** names, float* ms, int32_t cap) {
     const int n = tm.n;
+    // the brackets were recorded on one stream in order: waiting for the last one covers all
+    if (n > 0) {
+        const hipError_t e = hipEventSynchronize(tm.ev[2 * (n - 1) + 1]);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventSynchronize");
+    }
     for (int i = 0; i < n && i < cap; ++i) {
         float t = 0.0f;
-        hipError_t e = hipEventSynchronize(tm.ev[2 * i + 1]);
-        if (e == hipSuccess) e = hipEventElapsedTime(&t, tm.ev[2 * i], tm.ev[2 * i + 1]);
+        hipError_t e = hipEventElapsedTime(&t, tm.ev[2 * i], tm.ev[2 * i + 1]);
         if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
         if (names) names[i] = tm.name[i];
         if (ms) ms[i] = t;
