@@ -209,7 +209,9 @@ int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_
  * The call has no host output and returns with its kernels queued on `stream`: d_payload, d_ef
  * and d_q are complete in stream order (for the next call on this stream, or after the caller
  * waits on the stream).  The host arrays are read before the call returns.  An error of the
- * queued work surfaces at the next call that waits. */
+ * queued work surfaces at the next call that waits.  A call whose layer table, choice or offsets
+ * differ from the previous call's uploads them first and waits for that copy, hence for whatever
+ * was queued on `stream` before it; a loop that repeats them does not wait. */
 int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                     const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                     const int32_t* choice, float* d_q, uint8_t* d_payload, const int64_t* offsets,

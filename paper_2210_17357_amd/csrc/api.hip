@@ -198,19 +198,26 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
 }
 
 // The tile table travels only when it was rebuilt; the layer records also when the caller changed
-// their per-call fields (family, parameter, payload offset).  Every entry point ends with a stream
-// synchronisation before it returns, so the host vectors outlive the copies.
+// their per-call fields (family, parameter, payload offset).  The copies read the handle's host
+// vectors, which the next call may rewrite while this call's kernels are still queued
+// (lgreco_compress does not wait at its end): a call that uploads waits for its copies here.  In a
+// loop that repeats one table and one choice nothing is uploaded and nothing waits.
 int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
+    bool copied = false;
     if (h->layers_dirty || (layers_changed && (h->hl_uploaded.size() != h->hl.size() ||
                                                std::memcmp(h->hl_uploaded.data(), h->hl.data(),
                                                            sizeof(DevLayer) * h->hl.size()) != 0))) {
         HIPCHK(hipMemcpyAsync(h->d_layers, h->hl.data(), sizeof(DevLayer) * h->hl.size(), hipMemcpyHostToDevice,
                               s));
         h->hl_uploaded = h->hl;
+        copied = true;
     }
-    if (h->layers_dirty)
+    if (h->layers_dirty) {
         HIPCHK(hipMemcpyAsync(h->d_tiles, h->ht.data(), sizeof(Tile) * h->ht.size(), hipMemcpyHostToDevice, s));
+        copied = true;
+    }
     h->layers_dirty = false;
+    if (copied) HIPCHK(hipStreamSynchronize(s));
     return LGRECO_OK;
 }
 
