@@ -781,32 +781,72 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
 // element range it collected candidates from, so everything below is per wavefront and needs no
 // workgroup barrier.
 
+// Both kernels below are chains of dependent loads (tile -> layer record -> a few tens of
+// candidates per wavefront), so a workgroup takes kSliceBatch consecutive tiles and every
+// wavefront walks its slice of each of them side by side: the loads of one level are in flight
+// together and the chain's latency is paid once per batch.
+constexpr int kSliceBatch = 4;
+
 // per (tile, wavefront): entries above the threshold, entries equal to it (from its candidates)
-__global__ __launch_bounds__(kThreads) void topk_count_kernel(const DevLayer* __restrict__ layers,
-                                                               const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(kThreads) void topk_count_kernel(const Tile* __restrict__ tiles, int n_tiles,
                                                                const TopkLayer* __restrict__ tl,
                                                                const TopkTileInfo* __restrict__ tinfo,
                                                                const uint32_t* __restrict__ cand,
                                                                uint2* __restrict__ wavecnt) {
-    const Tile t = tiles[blockIdx.x];
-    const DevLayer L = layers[t.layer];
-    if (L.family != LGRECO_TOPK) return;
-    const TopkLayer& T = tl[t.layer];
-    const uint32_t thr = T.sel[0].thr;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const TopkTileInfo ti = tinfo[blockIdx.x];
-    const uint32_t* __restrict__ items = cand + T.cand_base + t.pos + ti.start[wave];
-    uint32_t gt = 0, eq = 0;
-    for (uint32_t i = lane; i < ti.cnt[wave]; i += 64) {
-        const uint32_t pat = items[i];
-        gt += pat > thr;
-        eq += pat == thr;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int first = blockIdx.x * kSliceBatch;
+    const uint32_t* items[kSliceBatch];
+    uint32_t n[kSliceBatch], thr[kSliceBatch], gt[kSliceBatch], eq[kSliceBatch];
+    bool active[kSliceBatch];
+    uint32_t nmax = 0;
+    // every load of a level is unconditional (indices clamped to the table), so that the levels
+    // of the batch's chains are issued together
+    int64_t pos[kSliceBatch], base[kSliceBatch];
+    int layer[kSliceBatch];
+    uint32_t start[kSliceBatch], k[kSliceBatch];
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        const int ti = min(first + q, n_tiles - 1);
+        layer[q] = tiles[ti].layer;
+        pos[q] = tiles[ti].pos;
+        n[q] = tinfo[ti].cnt[wave];
+        start[q] = tinfo[ti].start[wave];
     }
-    for (int o = 1; o < 64; o <<= 1) {
-        gt += __shfl_xor(gt, o, 64);
-        eq += __shfl_xor(eq, o, 64);
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        const TopkLayer& T = tl[layer[q]];
+        k[q] = T.sel[0].k;
+        thr[q] = T.sel[0].thr;
+        base[q] = T.cand_base;
     }
-    if (lane == 0) wavecnt[(size_t)blockIdx.x * (kThreads / 64) + wave] = make_uint2(gt, eq);
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        // a layer that is not compressed with Top-K has k = 0 in its record (and no candidates)
+        active[q] = first + q < n_tiles && k[q] != 0;
+        n[q] = active[q] ? n[q] : 0u;
+        items[q] = active[q] ? cand + base[q] + pos[q] + start[q] : cand;
+        gt[q] = eq[q] = 0;
+        nmax = max(nmax, n[q]);
+    }
+    for (uint32_t i = lane; i < nmax; i += 64) {
+        uint32_t pat[kSliceBatch];
+#pragma unroll
+        for (int q = 0; q < kSliceBatch; ++q) pat[q] = i < n[q] ? items[q][i] : 0xFFFFFFFFu;   // never a pattern
+#pragma unroll
+        for (int q = 0; q < kSliceBatch; ++q) {
+            gt[q] += (pat[q] != 0xFFFFFFFFu) & (pat[q] > thr[q]);
+            eq[q] += pat[q] == thr[q];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        for (int o = 1; o < 64; o <<= 1) {
+            gt[q] += __shfl_xor(gt[q], o, 64);
+            eq[q] += __shfl_xor(eq[q], o, 64);
+        }
+        if (lane == 0 && active[q])
+            wavecnt[(size_t)(first + q) * (kThreads / 64) + wave] = make_uint2(gt[q], eq[q]);
+    }
 }
 
 // per layer: exclusive prefix of the per-wavefront counts, in element order.  Both counts travel
@@ -862,7 +902,7 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long m, uint32_t a
 // already written as x everywhere by the collection pass, is zeroed at the kept entries.
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ e,
                                                               const DevLayer* __restrict__ layers,
-                                                              const Tile* __restrict__ tiles,
+                                                              const Tile* __restrict__ tiles, int n_tiles,
                                                               const TopkLayer* __restrict__ tl,
                                                               const TopkTileInfo* __restrict__ tinfo,
                                                               const uint32_t* __restrict__ cand,
@@ -870,50 +910,88 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
                                                               const uint2* __restrict__ wavecnt,
                                                               const uint2* __restrict__ wavebase,
                                                               uint8_t* __restrict__ payload) {
-    const Tile t = tiles[blockIdx.x];
-    const DevLayer L = layers[t.layer];
-    if (L.family != LGRECO_TOPK) return;
-    const TopkLayer& T = tl[t.layer];
-    const TopkSel S = T.sel[0];
-    const uint32_t thr = S.thr, ties_keep = S.ties_keep, k = S.k;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint2 cnt = wavecnt[(size_t)blockIdx.x * (kThreads / 64) + wave];
-    const uint2 before = wavebase[(size_t)blockIdx.x * (kThreads / 64) + wave];
-    const TopkTileInfo ti = tinfo[blockIdx.x];
-    const int64_t off = T.cand_base + t.pos + ti.start[wave];
-    const uint32_t* __restrict__ pats = cand + off;
-    const uint32_t* __restrict__ idxs = cand_idx + off;
-    float* const ef = e + L.offset;
-    float* const values = reinterpret_cast<float*>(payload + L.payload);
-    uint32_t* const indices = reinterpret_cast<uint32_t*>(payload + L.payload) + k;
-    // equal entries: global rank r (in index order) is kept iff r < ties_keep
-    const bool eq_all = before.y + cnt.y <= ties_keep;
-    const bool eq_none = before.y >= ties_keep;
-    uint32_t out = before.x + min(before.y, ties_keep);
-    uint32_t eq_seen = before.y;
-    const uint32_t n = ti.cnt[wave];
-    for (uint32_t i0 = 0; i0 < n; i0 += 64) {
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int first = blockIdx.x * kSliceBatch;
+    struct Slice {
+        const uint32_t* pats;
+        const uint32_t* idxs;
+        float* ef;
+        float* values;
+        uint32_t* indices;
+        uint32_t n, thr, ties_keep, out, eq_seen;
+        bool eq_all, eq_none;
+    } S[kSliceBatch];
+    uint32_t nmax = 0;
+    // every load of a level is unconditional (indices clamped to the tables; the count arrays
+    // cover every tile), so that the levels of the batch's chains are issued together
+    int64_t pos[kSliceBatch];
+    int layer[kSliceBatch];
+    uint32_t start[kSliceBatch];
+    uint2 cnt[kSliceBatch], before[kSliceBatch];
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        const int ti = min(first + q, n_tiles - 1);
+        const size_t slot = (size_t)ti * (kThreads / 64) + wave;
+        layer[q] = tiles[ti].layer;
+        pos[q] = tiles[ti].pos;
+        S[q].n = tinfo[ti].cnt[wave];
+        start[q] = tinfo[ti].start[wave];
+        cnt[q] = wavecnt[slot];
+        before[q] = wavebase[slot];
+    }
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        const DevLayer& L = layers[layer[q]];
+        const TopkLayer& T = tl[layer[q]];
+        const bool active = first + q < n_tiles && L.family == LGRECO_TOPK;
+        const int64_t off = active ? T.cand_base + pos[q] + start[q] : 0;
+        const uint32_t keep_eq = T.sel[0].ties_keep;
+        S[q].pats = cand + off;
+        S[q].idxs = cand_idx + off;
+        S[q].ef = e + L.offset;
+        S[q].values = reinterpret_cast<float*>(payload + L.payload);
+        S[q].indices = reinterpret_cast<uint32_t*>(payload + L.payload) + T.sel[0].k;
+        S[q].n = active ? S[q].n : 0u;
+        S[q].thr = T.sel[0].thr;
+        S[q].ties_keep = keep_eq;
+        // equal entries: global rank r (in index order) is kept iff r < ties_keep
+        S[q].eq_all = before[q].y + cnt[q].y <= keep_eq;
+        S[q].eq_none = before[q].y >= keep_eq;
+        S[q].out = before[q].x + min(before[q].y, keep_eq);
+        S[q].eq_seen = before[q].y;
+        nmax = max(nmax, S[q].n);
+    }
+    for (uint32_t i0 = 0; i0 < nmax; i0 += 64) {
         const uint32_t i = i0 + lane;
-        const bool ok = i < n;
-        const uint32_t pat = ok ? pats[i] : 0u;
-        const uint32_t ix = ok ? idxs[i] : 0u;
-        bool keep = ok && pat > thr;
-        const bool eq = ok && pat == thr;
-        if (eq_all) {
-            keep = keep || eq;
-        } else if (!eq_none) {
-            const unsigned long long bq = __ballot(eq);
-            if (eq) keep = eq_seen + lanes_below(bq, 0u) < ties_keep;
-            eq_seen += (uint32_t)__popcll(bq);
+        uint32_t pat[kSliceBatch], ix[kSliceBatch];
+#pragma unroll
+        for (int q = 0; q < kSliceBatch; ++q) {
+            const bool ok = i < S[q].n;
+            pat[q] = ok ? S[q].pats[i] : 0u;
+            ix[q] = ok ? S[q].idxs[i] : 0u;
         }
-        const unsigned long long kq = __ballot(keep);
-        if (keep) {
-            const uint32_t pos = out + lanes_below(kq, 0u);
-            values[pos] = __uint_as_float(pat | (ix & 0x80000000u));
-            indices[pos] = ix & 0x7FFFFFFFu;
-            ef[ix & 0x7FFFFFFFu] = 0.0f;
+#pragma unroll
+        for (int q = 0; q < kSliceBatch; ++q) {
+            if (i0 >= S[q].n) continue;                      // wavefront-uniform
+            const bool ok = i < S[q].n;
+            bool keep = ok && pat[q] > S[q].thr;
+            const bool eq = ok && pat[q] == S[q].thr;
+            if (S[q].eq_all) {
+                keep = keep || eq;
+            } else if (!S[q].eq_none) {
+                const unsigned long long bq = __ballot(eq);
+                if (eq) keep = S[q].eq_seen + lanes_below(bq, 0u) < S[q].ties_keep;
+                S[q].eq_seen += (uint32_t)__popcll(bq);
+            }
+            const unsigned long long kq = __ballot(keep);
+            if (keep) {
+                const uint32_t pos = S[q].out + lanes_below(kq, 0u);
+                S[q].values[pos] = __uint_as_float(pat[q] | (ix[q] & 0x80000000u));
+                S[q].indices[pos] = ix[q] & 0x7FFFFFFFu;
+                S[q].ef[ix[q] & 0x7FFFFFFFu] = 0.0f;
+            }
+            S[q].out += (uint32_t)__popcll(kq);
         }
-        out += (uint32_t)__popcll(kq);
     }
 }
 
@@ -1235,8 +1313,8 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
-        hipLaunchKernelGGL(topk_count_kernel, dim3(n_tiles), dim3(kThreads), 0, s, d_layers, d_tiles,
-                           (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
+        hipLaunchKernelGGL(topk_count_kernel, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s,
+                           d_tiles, n_tiles, (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
                            (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
         TK_CHECK(hipGetLastError());
     }
@@ -1248,8 +1326,9 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     }
     {
         Section sec(tm, "topk_emit");
-        hipLaunchKernelGGL(topk_emit_kernel, dim3(n_tiles), dim3(kThreads), 0, s, e, d_layers, d_tiles,
-                           (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
+        hipLaunchKernelGGL(topk_emit_kernel, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s, e,
+                           d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
+                           (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
                            (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
                            (const uint2*)t->d_tilebase, payload);
         TK_CHECK(hipGetLastError());
