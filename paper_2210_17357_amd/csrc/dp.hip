@@ -188,36 +188,77 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
     __syncthreads();
     uint64_t t_sweep = 0;
-    if (tid == 0) {
-        t_sweep = wall_clock64();
+    if (tid < 64) {
+        // the first wavefront: every lane joins the per-wavefront minima the same way
+        if (tid == 0) t_sweep = wall_clock64();
         for (int w = 1; w < kDpThreads / 64; ++w)
             if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
-        s_val[0] = bv;
-        s_idx[0] = be;
+        if (tid == 0) {
+            s_val[0] = bv;
+            s_idx[0] = be;
+        }
         if (bv < (int64_t)kInf) {
-            // the walk is a chain of dependent loads: one PD byte per layer from global memory,
-            // the bin it stands for from LDS when the table fits there
-            int e = be;
-            if (lds_bins) {
-                for (int l = L - 1; l >= 0; --l) {
-                    const int k = p.pd[(size_t)l * width + e];
-                    s_pick[l] = (uint8_t)k;
-                    e -= s_bins[l * bstride + k];
+            // The walk is a chain of dependent loads: one PD byte per layer from global memory,
+            // the bin it stands for from LDS when the table fits there.
+            int e = __builtin_amdgcn_readfirstlane(be);
+            if (lds_bins && bstride <= 64) {
+                // Two layers per load latency: lane j holds the bin of entry j of layer l, so
+                // while PD[l][e] is on its way lane j already fetches PD[l-1][e - bin_j], the
+                // byte the walk needs next if entry j is the one picked.  One wavefront runs
+                // alone here and every instruction costs its full issue latency, so the loop is
+                // kept short: rows by a running pointer, no branches, consistency checks joined
+                // into one flag (a bad byte still gives in-row addresses: e only shrinks and is
+                // clamped at 0, lanes past the list hold bin 0).
+                auto bins_of = [&](int layer) -> uint32_t {
+                    return lane < bstride ? (uint32_t)s_bins[max(layer, 0) * bstride + lane] : 0u;
+                };
+                int l = L - 1;
+                uint32_t bins_cur = bins_of(l), bins_prev = bins_of(l - 1);
+                const uint8_t* __restrict__ row_l = p.pd + (size_t)max(l, 0) * width;
+                int bad = 0;
+                for (; l >= 1; l -= 2, row_l -= 2 * width) {
+                    const uint32_t bins_n1 = bins_of(l - 2), bins_n2 = bins_of(l - 3);
+                    const uint32_t ka_v = row_l[e];
+                    const uint32_t kb_v = (row_l - width)[max(e - (int)bins_cur, 0)];
+                    const int ka = __builtin_amdgcn_readfirstlane((int)ka_v);
+                    const int kb = (int)readlane_u32(kb_v, ka);
+                    s_pick[l] = (uint8_t)ka;               // every lane writes the same byte
+                    s_pick[l - 1] = (uint8_t)kb;
+                    e -= (int)readlane_u32(bins_cur, ka) + (int)readlane_u32(bins_prev, kb);
+                    bad |= (ka >= bstride) | (kb >= bstride) | (e < 0);
+                    e = max(e, 0);
+                    bins_cur = bins_n1;
+                    bins_prev = bins_n2;
                 }
-            } else {
-                for (int l = L - 1; l >= 0; --l) {
-                    const int k = p.pd[(size_t)l * width + e];
-                    const DpEntry en = p.entries[(size_t)l * bstride + k];
-                    p.choice[l] = en.cand;
-                    e -= en.bin;
+                if (l == 0) {
+                    const int ka = __builtin_amdgcn_readfirstlane((int)row_l[e]);
+                    s_pick[0] = (uint8_t)ka;
+                    e -= (int)readlane_u32(bins_cur, ka);
+                    bad |= (ka >= bstride) | (e < 0);
+                }
+                if (bad) e = -1;                            // an internal inconsistency
+            } else if (tid == 0) {
+                if (lds_bins) {
+                    for (int l = L - 1; l >= 0; --l) {
+                        const int k = p.pd[(size_t)l * width + e];
+                        s_pick[l] = (uint8_t)k;
+                        e -= s_bins[l * bstride + k];
+                    }
+                } else {
+                    for (int l = L - 1; l >= 0; --l) {
+                        const int k = p.pd[(size_t)l * width + e];
+                        const DpEntry en = p.entries[(size_t)l * bstride + k];
+                        p.choice[l] = en.cand;
+                        e -= en.bin;
+                    }
                 }
             }
-            s_idx[1] = e;
+            if (tid == 0) s_idx[1] = e;
         }
     }
     __syncthreads();
     const bool feasible = s_val[0] < (int64_t)kInf;
-    if (feasible && lds_bins)
+    if (feasible && lds_bins && s_idx[1] == 0)
         for (int l = tid; l < L; l += kDpThreads)
             p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
     if (tid == 0) {
