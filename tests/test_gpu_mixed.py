@@ -146,3 +146,35 @@ def test_full_size_gpt2_medium_sampled_layers():
         assert np.array_equal(pay[offsets[l]:offsets[l] + p_ref.size], p_ref), (l, cands[choice[l]])
         assert np.array_equal(ef_dev[off:off + n].cpu().numpy().view(np.uint32), e_ref.view(np.uint32)), l
     h.close()
+
+    # The benchmark's loop itself: a handle that starts every call from the thresholds of the
+    # previous one, profile + solve as one call, compress queued behind it on the same stream, a
+    # fresh copy of the error feedback per step.  Every step reproduces what was verified above:
+    # errors to rounding (the bound under which energies are summed in fp32 moves), the oracle's
+    # assignment for the step's own tables, payload and error feedback bit for bit.
+    h2 = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    n_pay = int(offsets[-1])
+    for step in range(3):
+        ef2 = e.clone()
+        payload2 = torch.zeros_like(payload)
+        st2, err2, sizes2, emax2, choice2, tsize2, terr2 = h2.profile_solve(
+            g, e, layers, ctab, w.default, w.n_bins, stream=stream)
+        assert st2 == B.OK, step
+        assert np.array_equal(sizes2, sizes) and rel_err(err2, errors).max() < 1e-6, step
+        assert emax2 == B.emax(err2, w.default), step          # summed in layer order on both sides
+        if not np.array_equal(err2, errors):
+            ref_choice, ref_size, _ = solver.solve(err2, sizes2, emax2, w.n_bins)
+        assert np.array_equal(choice2, ref_choice) and tsize2 == ref_size, step
+        offsets2 = B.payload_layout(layers, ctab, choice2)
+        h2.compress(g, ef2, layers, ctab, choice2, payload2, offsets2, stream=stream)
+        torch.cuda.synchronize()
+        if np.array_equal(choice2, choice):
+            assert torch.equal(payload2[:n_pay], payload[:n_pay]), step
+            assert torch.equal(ef2.view(torch.int32), ef_dev.view(torch.int32)), step
+        else:       # rounding moved an error across a bin edge: the invariant of every layer instead
+            sq = ef2.double().pow(2)
+            left = np.array([float(sq[int(o):int(o) + int(n)].sum()) for o, n in zip(batch.offsets, batch.numels)])
+            ch = err2[np.arange(L), choice2]
+            assert (np.abs(left - ch) <= 1e-4 * ch + 1e-60).all(), step
+    h2.close()
