@@ -10,7 +10,9 @@ timed region.
 
 Prints ONE JSON line (metric = gradient GB/s = 4 * N bytes / step time), with
   "roofline"     achieved algorithmic GB/s of the dominant kernel, timed with HIP events on the
-                 launch stream inside the timed region, against the 8 TB/s HBM peak;
+                 launch stream inside the timed region (the kernels of every --time-every-th step
+                 carry the events; the library sums them, the loop never stops to read them),
+                 against the 8 TB/s HBM peak;
   "cpu_baseline" the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -60,6 +62,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
+    ap.add_argument("--time-every", type=int, default=4,
+                    help="kernels carry HIP events in every n-th step only (a timed kernel leaves ~5 us of the "
+                         "stream idle on either side: ~45 us per step on the largest workload when every step is timed)")
     ap.add_argument("--detail", action="store_true",
                     help="bracket every kernel section, not only the main kernels (costs ~3 %% of the step)")
     ap.add_argument("--cpu-sample-elems", type=int, default=30_000_000)
@@ -129,24 +134,19 @@ def main():
     h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
                  seed=w.seed, r_max=w.r_max, power_iters=args.power_iters,
                  reuse_thresholds=not args.sample_every_call)
-    h.set_timing(0 if args.no_kernel_timing else (2 if args.detail else 1))
+    level = 0 if args.no_kernel_timing else (2 if args.detail else 1)
+    h.set_timing(level)
+    h.set_timing_stride(max(1, args.time_every))
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
 
-    kern = {}          # name -> [total ms, launches]
+    kern = {}          # name -> [total ms, calls]
     phase = {"profile": 0.0, "solve": 0.0, "compress": 0.0}
     last = {}
 
     stream = torch.cuda.current_stream().cuda_stream      # the stream every call of the run is given
 
     timing = not args.no_kernel_timing
-    pending = {"compress": False}      # a recorded compress call whose brackets were not read yet
-
-    def add(prefix, sections):
-        for n, ms in sections:
-            a = kern.setdefault(prefix + n, [0.0, 0])
-            a[0] += ms
-            a[1] += 1
 
     def step(i, record):
         ef = ef_pool[i]
@@ -161,24 +161,14 @@ def main():
             st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
                 g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
             t1 = time.perf_counter()
-        if pending["compress"]:
-            # compress returns with its kernels queued; the calls above have waited on the stream
-            # since, so the previous step's compress brackets are complete and reading them stalls nothing
-            add("compress/", h.get_timing(B.CALL_COMPRESS))
-            pending["compress"] = False
         t2 = time.perf_counter()
         offsets = B.payload_layout(layers, ctab, choice, w.bucket)
         h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
-        pending["compress"] = record and timing
         t3 = time.perf_counter()
-        if record and timing:
-            # read while compress runs (the brackets of the two earlier calls are complete)
-            add("profile/", h.get_timing(B.CALL_PROFILE))
-            add("solve/", h.get_timing(B.CALL_SOLVE))
         if record:
             # host clocks: compress only queues its kernels, their GPU time falls into the wait of
             # the next step's profile call (or the final synchronize); with the one-call form
-            # "profile" covers profile + solve and "solve" only the reading of the brackets
+            # "profile" covers profile + solve
             phase["profile"] += t1 - t0
             phase["solve"] += t2 - t1
             phase["compress"] += t3 - t2
@@ -187,13 +177,19 @@ def main():
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
+    h.set_timing(level)          # clears the library's per-section totals: the warm-up does not count
     t_start = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    if pending["compress"]:
-        add("compress/", h.get_timing(B.CALL_COMPRESS))
+    # Kernel times: the library keeps the events of every call (the main kernels' events ride on
+    # the launches themselves) and sums them per section while it waits for the GPU anyway; the
+    # loop above never asks for them, the totals over the timed steps are read here.
+    if timing:
+        for prefix, call in (("profile/", B.CALL_PROFILE), ("solve/", B.CALL_SOLVE), ("compress/", B.CALL_COMPRESS)):
+            for name, total_ms, cnt in h.get_timing_totals(call):
+                kern[prefix + name] = [total_ms, cnt]
     ms_per_step = elapsed * 1e3 / args.steps
     value = 4.0 * N / (elapsed / args.steps) / 1e9
 
@@ -260,6 +256,7 @@ def main():
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
                    "reuse_thresholds": not args.sample_every_call,
                    "profile_and_solve": "three calls" if args.separate_calls else "one call",
+                   "kernels_timed_every_n_steps": None if args.no_kernel_timing else max(1, args.time_every),
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
         # host wall clock per call; compress returns with its kernels queued, so most of its GPU

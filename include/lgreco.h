@@ -242,21 +242,36 @@ int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, in
                       int32_t reset, void* stream);
 
 /* Timing of the kernels launched by the last profile / solve / compress call on this handle.
- * lgreco_set_timing(h, level) makes every call bracket kernels with HIP events on the call's
- * stream: level 1 the main kernels only (the streaming passes, the contractions, the DP), level 2
- * every section, 0 none (each bracket costs a few microseconds of the stream's time);
+ * lgreco_set_timing(h, level) makes every call time its kernels with HIP events on the call's
+ * stream: level 1 the main kernels only (the streaming passes, the contractions, the DP), whose
+ * events ride on the kernel launches themselves (the kernel's own begin and end timestamps);
+ * level 2 every section, each further bracket a pair of recorded events; 0 none.  Either kind of
+ * event costs a few microseconds of the stream's time.  Setting the level also clears the totals below.
  * lgreco_get_timing returns the number of sections recorded by the last call and
  * fills names (static strings) and milliseconds for up to `cap` of them. */
 int lgreco_set_timing(lgreco_handle_t* h, int32_t level);
+/* Time only every `every`-th call of each kind, counted from the last lgreco_set_timing (the
+ * first call after it is timed); 1 = every call, the default.  A kernel that carries events
+ * leaves a few microseconds of the stream idle on either side of it, so a loop that wants its
+ * own throughput undisturbed samples. */
+int lgreco_set_timing_stride(lgreco_handle_t* h, int32_t every);
 int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t cap);
-/* The same for the last call of one kind (the handle keeps one set of brackets per kind, so a
+/* The same for the last call of one kind (the handle keeps one set of events per kind, so a
  * lgreco_compress that returned with its kernels still queued can be read after a later profile
- * or solve call).  Both functions wait for the brackets they read. */
+ * or solve call).  Both functions wait for the events they read.  The library itself reads a
+ * call's events out when the next call of that kind starts (which therefore waits for the
+ * earlier one while timing is on) or when a call of another kind is about to wait for the
+ * stream anyway, whichever comes first. */
 #define LGRECO_CALL_PROFILE  0
 #define LGRECO_CALL_SOLVE    1
 #define LGRECO_CALL_COMPRESS 2
 #define LGRECO_CALL_RECEIVE  3   /* lgreco_decompress, lgreco_accumulate */
 int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, float* ms, int32_t cap);
+/* Totals per section over all calls of one kind since lgreco_set_timing: names, summed
+ * milliseconds and how many calls contributed, for up to `cap` sections; returns the number of
+ * sections.  A loop can run untouched and be read once at its end. */
+int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** names, double* total_ms,
+                             int64_t* count, int32_t cap);
 
 const char* lgreco_strerror(int status);
 /* Text of the last HIP error seen by this handle ("" if none). */

@@ -21,8 +21,8 @@ CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve",
            "lgreco_candidate_range", "lgreco_emax",
-           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing",
-           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_strerror", "lgreco_last_hip_error")
+           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
+           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error")
 
 
 class Layer(C.Structure):
@@ -75,8 +75,10 @@ def lib() -> C.CDLL:
         l.lgreco_decompress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, i32, vp]
         l.lgreco_accumulate.argtypes = [vp, vp, vp, i64, i32, vp]
         l.lgreco_set_timing.argtypes = [vp, i32]
+        l.lgreco_set_timing_stride.argtypes = [vp, i32]
         l.lgreco_get_timing.argtypes = [vp, vp, vp, i32]
         l.lgreco_get_timing_of.argtypes = [vp, i32, vp, vp, i32]
+        l.lgreco_get_timing_totals.argtypes = [vp, i32, vp, vp, vp, i32]
         l.lgreco_strerror.argtypes = [C.c_int]
         l.lgreco_strerror.restype = C.c_char_p
         l.lgreco_last_hip_error.argtypes = [vp]
@@ -278,6 +280,9 @@ class Handle:
         """0 / False: off; 1 / True: main kernels; 2: every section."""
         self._check(lib().lgreco_set_timing(self._h, int(level)))
 
+    def set_timing_stride(self, every: int):
+        self._check(lib().lgreco_set_timing_stride(self._h, int(every)))
+
     def get_timing(self, call=None):
         """Sections of the last call, or of the last call of one kind (CALL_PROFILE, CALL_SOLVE,
         CALL_COMPRESS, CALL_RECEIVE); waits for the brackets it reads."""
@@ -291,3 +296,14 @@ class Handle:
         if n < 0:
             self._check(n)
         return [(names[i].decode(), float(ms[i])) for i in range(min(n, cap))]
+
+    def get_timing_totals(self, call):
+        """(name, total milliseconds, calls) of every section of one kind of call since set_timing."""
+        cap = 48
+        names = (C.c_char_p * cap)()
+        ms = (C.c_double * cap)()
+        cnt = (C.c_int64 * cap)()
+        n = lib().lgreco_get_timing_totals(self._h, int(call), names, ms, cnt, cap)
+        if n < 0:
+            self._check(n)
+        return [(names[i].decode(), float(ms[i]), int(cnt[i])) for i in range(min(n, cap))]

@@ -221,11 +221,50 @@ int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
     return LGRECO_OK;
 }
 
+// Turns the brackets of the last call of one kind into milliseconds (waits for them) and adds
+// them to the totals.  Does nothing when that was done already or nothing was recorded.
+hipError_t harvest(Timing& tm) {
+    if (tm.harvested || tm.n == 0) return hipSuccess;
+    tm.harvested = true;
+    // the brackets were recorded on one stream in order: waiting for the last one covers all
+    hipError_t e = hipEventSynchronize(tm.ev[2 * (tm.n - 1) + 1]);
+    for (int i = 0; i < tm.n && e == hipSuccess; ++i) {
+        e = hipEventElapsedTime(&tm.ms[i], tm.ev[2 * i], tm.ev[2 * i + 1]);
+        if (e == hipSuccess) tm.add_total(tm.name[i], (double)tm.ms[i]);
+    }
+    if (e != hipSuccess) tm.n = 0;
+    return e;
+}
+
+// Brackets of asynchronous calls (lgreco_compress) that are still unread: a call that is about to
+// wait for the stream anyway reads them first - their kernels were queued before its own, so the
+// wait costs it nothing - and a loop that alternates the calls never waits for timing elsewhere.
+void harvest_others(lgreco_handle* h) {
+    if (h->tm->level == 0) return;
+    for (Timing& t : h->tms)
+        if (&t != h->tm) (void)harvest(t);
+}
+
+// A call starts: its kind's brackets of the previous call are read out if nobody did (with timing
+// on, a call therefore waits for the previous call of its kind), then the set is reused.
 void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
     h->tm = &h->tms[kind];
+    (void)harvest(*h->tm);
     h->tm->n = 0;
+    h->tm->active = h->tm->level > 0 && (h->tm->calls++ % h->tm->every) == 0;
+    h->tm->harvested = !h->tm->active;
     h->tm->stream = s;
     if (kind == LGRECO_CALL_SOLVE) h->n_sub = 0;
+}
+
+// Device-clock sub-sections of the solve (100 MHz constant-rate counter).
+void record_dp_sub(lgreco_handle* h) {
+    h->sub_name[0] = "dp_solve.sweep";
+    h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
+    h->sub_name[1] = "dp_solve.backtrace";
+    h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
+    h->n_sub = 2;
+    for (int j = 0; j < 2; ++j) h->tms[LGRECO_CALL_SOLVE].add_total(h->sub_name[j], (double)h->sub_ms[j]);
 }
 
 }  // namespace
@@ -350,24 +389,30 @@ int lgreco_set_timing(lgreco_handle_t* h, int32_t level) {
     for (Timing& t : h->tms) {
         t.level = level;
         t.n = 0;
+        t.calls = 0;
+        t.active = false;
+        t.harvested = true;
+        t.n_totals = 0;
     }
     h->n_sub = 0;
     return LGRECO_OK;
 }
 
+int lgreco_set_timing_stride(lgreco_handle_t* h, int32_t every) {
+    if (!h || every < 1) return LGRECO_EINVAL;
+    for (Timing& t : h->tms) t.every = every;
+    return LGRECO_OK;
+}
+
 static int read_timing(lgreco_handle_t* h, Timing& tm, bool with_sub, const char** names, float* ms, int32_t cap) {
-    const int n = tm.n;
-    // the brackets were recorded on one stream in order: waiting for the last one covers all
-    if (n > 0) {
-        const hipError_t e = hipEventSynchronize(tm.ev[2 * (n - 1) + 1]);
-        if (e != hipSuccess) return hip_fail(h, e, "hipEventSynchronize");
+    {
+        const hipError_t e = harvest(tm);
+        if (e != hipSuccess) return hip_fail(h, e, "reading timing events");
     }
+    const int n = tm.n;
     for (int i = 0; i < n && i < cap; ++i) {
-        float t = 0.0f;
-        hipError_t e = hipEventElapsedTime(&t, tm.ev[2 * i], tm.ev[2 * i + 1]);
-        if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
         if (names) names[i] = tm.name[i];
-        if (ms) ms[i] = t;
+        if (ms) ms[i] = tm.ms[i];
     }
     int total = n;
     if (with_sub) {
@@ -388,6 +433,20 @@ int lgreco_get_timing(lgreco_handle_t* h, const char** names, float* ms, int32_t
 int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, float* ms, int32_t cap) {
     if (!h || cap < 0 || call < 0 || call > LGRECO_CALL_RECEIVE) return LGRECO_EINVAL;
     return read_timing(h, h->tms[call], call == LGRECO_CALL_SOLVE, names, ms, cap);
+}
+
+int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** names, double* total_ms,
+                             int64_t* count, int32_t cap) {
+    if (!h || cap < 0 || call < 0 || call > LGRECO_CALL_RECEIVE) return LGRECO_EINVAL;
+    Timing& tm = h->tms[call];
+    const hipError_t e = harvest(tm);
+    if (e != hipSuccess) return hip_fail(h, e, "reading timing events");
+    for (int i = 0; i < tm.n_totals && i < cap; ++i) {
+        if (names) names[i] = tm.total_name[i];
+        if (total_ms) total_ms[i] = tm.total_ms[i];
+        if (count) count[i] = tm.total_count[i];
+    }
+    return tm.n_totals;
 }
 
 int lgreco_sizes(const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
@@ -536,10 +595,10 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
             qp.base_part = h->topk.d_base_part;
         }
         Section sec(h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile", true);
-        HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s));
+        HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s, &sec));
     } else if (ntk) {
         Section sec(h->tm, "topk_collect", true);
-        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s));
+        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s, &sec));
     }
     if (ntk)
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
@@ -570,6 +629,7 @@ int lgreco_profile(lgreco_handle_t* h, const float* d_grads, const float* d_ef, 
     hipStream_t s = (hipStream_t)stream;
     const int st = profile_enqueue(h, d_grads, d_ef, layers, L, cands, P, d_q0, sizes, h->d_errors, s);
     if (st != LGRECO_OK) return st;
+    harvest_others(h);
     HIPCHK(hipStreamSynchronize(s));      // the kernels wrote h_errors
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     return LGRECO_OK;
@@ -673,16 +733,11 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
                     h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr};
         {
             Section sec(h->tm, "dp_solve", true);
-            HIPCHK(launch_dp(dp, narrow, max_bin, s));
+            HIPCHK(launch_dp(dp, narrow, max_bin, s, &sec, true));
         }
+        harvest_others(h);
         HIPCHK(hipStreamSynchronize(s));  // the kernel wrote h_dp_out
-        if (h->tm->level >= 1) {                       // 100 MHz constant-rate device counter
-            h->sub_name[0] = "dp_solve.sweep";
-            h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
-            h->sub_name[1] = "dp_solve.backtrace";
-            h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
-            h->n_sub = 2;
-        }
+        if (h->tm->active) record_dp_sub(h);
         if (h->h_result[0] == 1) return infeasible();
         if (h->h_result[0] != 0) {
             h->hip_error = "dp back-trace inconsistent";
@@ -750,9 +805,10 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
                 nullptr, nullptr, 0, h->d_nsweep};
     {
         Section sec(h->tm, "dp_solve", true);
-        HIPCHK(launch_dp_build(bp, s));
-        HIPCHK(launch_dp(dp, true, n_bins, s));
+        HIPCHK(launch_dp_build(bp, s, &sec));
+        HIPCHK(launch_dp(dp, true, n_bins, s, &sec, false));
     }
+    harvest_others(h);
     HIPCHK(hipStreamSynchronize(s));      // error table, build report and solver output are in pinned memory
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     const int64_t status = h->h_result[0];
@@ -761,13 +817,7 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
         std::memcpy(e_max, &bits, sizeof(double));
     }
     if (status == 3) return LGRECO_EINVAL;                  // a NaN in the error table
-    if (h->tm->level >= 1 && status == 0) {
-        h->sub_name[0] = "dp_solve.sweep";
-        h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
-        h->sub_name[1] = "dp_solve.backtrace";
-        h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
-        h->n_sub = 2;
-    }
+    if (h->tm->active && status == 0) record_dp_sub(h);
     if (status == 1) {                                      // report each layer's minimum-error candidate
         for (int l = 0; l < L; ++l) {
             int best = 0;
@@ -874,7 +924,7 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     if (any[LGRECO_QUANT]) {
         Section sec(h->tm, "quant_compress", true);
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
-                                     h->cfg.stochastic != 0, h->cfg.seed, s));
+                                     h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
     }
     if (any[LGRECO_TOPK]) {
         HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
@@ -931,7 +981,7 @@ int lgreco_accumulate(lgreco_handle_t* h, float* d_acc, const float* d_grads, in
     begin_call(h, s, LGRECO_CALL_RECEIVE);
     {
         Section sec(h->tm, "accumulate", true);
-        HIPCHK(launch_accumulate(d_acc, d_grads, n, reset != 0, s));
+        HIPCHK(launch_accumulate(d_acc, d_grads, n, reset != 0, s, &sec));
     }
     HIPCHK(hipStreamSynchronize(s));
     return LGRECO_OK;

@@ -124,10 +124,10 @@ __global__ __launch_bounds__(kThreads) void accumulate_kernel(float* __restrict_
     }
 }
 
-hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s) {
+hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s, Section* sec) {
     if (n <= 0) return hipSuccess;
     const int64_t blocks = std::min<int64_t>((n / 4 + kThreads - 1) / kThreads + 1, 256 * 16);
-    hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, acc, g, n, reset ? 1 : 0);
+    launch_timed(sec, true, true, accumulate_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, acc, g, n, reset ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -137,18 +137,18 @@ hipError_t launch_decode(const uint8_t* payload, const DevLayer* layers, const T
     DecodeParams p{payload, layers, tiles, out, accumulate ? 1 : 0};
     if (any_quant) {
         Section sec(tm, "quant_decode", true);
-        hipLaunchKernelGGL(quant_decode_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(&sec, true, true, quant_decode_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (any_topk) {
         Section sec(tm, "topk_decode", true);
         if (!accumulate) {
-            hipLaunchKernelGGL(topk_decode_zero_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+            launch_timed(&sec, true, false, topk_decode_zero_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(topk_decode_scatter_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(&sec, true, true, topk_decode_scatter_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

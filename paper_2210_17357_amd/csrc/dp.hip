@@ -417,17 +417,17 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     }
 }
 
-hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s) {
+hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s, Section* sec) {
     if (p.L < 1 || p.L > kBuildThreads || p.P < 1 || p.P > kBuildMaxP || p.L * p.P > kBuildMaxLP)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL(dp_build_kernel, dim3(1), dim3(kBuildThreads), 0, s, p);
+    launch_timed(sec, true, false, dp_build_kernel, dim3(1), dim3(kBuildThreads), 0, s, p);
     return hipGetLastError();
 }
 
 constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static (160 KB per CU)
 
 template <typename T, int THREADS>
-static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
+static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* sec, bool first) {
     constexpr int kMaxK = (LGRECO_MAX_BINS + 1 + THREADS - 1) / THREADS;
     const int nk = (p.D + 1 + THREADS - 1) / THREADS;
     int kmax = 1;
@@ -452,7 +452,7 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
             if (err != hipSuccess) return err;                                                     \
             configured = true;                                                                     \
         }                                                                                          \
-        hipLaunchKernelGGL((dp_kernel<T, K, PD, THREADS>), dim3(1), dim3(THREADS), lds, s, p);     \
+        launch_timed(sec, first, true, dp_kernel<T, K, PD, THREADS>, dim3(1), dim3(THREADS), lds, s, p); \
     } while (0)
 #define LGRECO_DP(K) do { if (padded) LGRECO_DP2(K, true); else LGRECO_DP2(K, false); } while (0)
     if (kmax == 1) LGRECO_DP(1);
@@ -466,8 +466,9 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s) {
-    return narrow ? launch_dp_t<uint32_t, 1024>(p, max_bin, s) : launch_dp_t<int64_t, 1024>(p, max_bin, s);
+hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s, Section* sec, bool first_in_section) {
+    return narrow ? launch_dp_t<uint32_t, 1024>(p, max_bin, s, sec, first_in_section)
+                  : launch_dp_t<int64_t, 1024>(p, max_bin, s, sec, first_in_section);
 }
 
 }  // namespace lgreco

@@ -2,47 +2,117 @@
 #pragma once
 
 #include <algorithm>
+#include <cstring>
 #include <vector>
+
+#include <hip/hip_ext.h>
 
 #include "common.h"
 
 namespace lgreco {
 
-// Optional per-kernel timing: each Section brackets the work enqueued during its lifetime with
-// two HIP events on the call's stream.
+// Optional per-kernel timing.  A Section covers the work enqueued during its lifetime with two HIP
+// events of the call's stream.  A main-kernel section (the level-1 sections a benchmark keeps on
+// inside its timed region) puts its events on the kernels themselves: launch_timed below hands
+// the start event to the section's first kernel and the stop event to its last one, and
+// hipExtLaunchKernelGGL takes the kernel's own begin and end timestamps, so the figure is the
+// kernels' time without launch gaps.  The other sections record their events as separate stream
+// operations.  Either way a timed kernel leaves about 5 us of the stream idle on either side
+// (measured), which is why a call kind can be timed every n-th call only.
 struct Timing {
     static constexpr int kMaxSections = 32;
     int level = 0;          // 0 off, 1 main kernels, 2 every section
+    int every = 1;          // only every `every`-th call of this kind is timed
+    int64_t calls = 0;      // calls of this kind since the level was set
+    bool active = false;    // the call in progress is one of the timed ones
     bool ready = false;
     hipStream_t stream = nullptr;
     hipEvent_t ev[2 * kMaxSections]{};
     const char* name[kMaxSections]{};
     int n = 0;
+    // Read-out: the events of the last call are turned into milliseconds once ("harvested"), at a
+    // moment when the host has nothing better to do, and added to the totals since the level was set.
+    bool harvested = true;
+    float ms[kMaxSections]{};
+    static constexpr int kMaxNames = 48;
+    const char* total_name[kMaxNames]{};
+    double total_ms[kMaxNames]{};
+    int64_t total_count[kMaxNames]{};
+    int n_totals = 0;
+    void add_total(const char* nm, double v) {
+        int i = 0;
+        while (i < n_totals && total_name[i] != nm && std::strcmp(total_name[i], nm) != 0) ++i;
+        if (i == n_totals) {
+            if (n_totals == kMaxNames) return;
+            total_name[n_totals++] = nm;
+            total_ms[i] = 0.0;
+            total_count[i] = 0;
+        }
+        total_ms[i] += v;
+        total_count[i] += 1;
+    }
 };
 struct Section {
     Timing* t;
     int idx = -1;
+    bool on_kernels = false;            // events are bound to kernels, not recorded
+    bool start_taken = false, stop_taken = false;
     Section(Timing* tt, const char* name, bool main_kernel = false) : t(tt) {
-        if (t && t->level >= (main_kernel ? 1 : 2) && t->ready && t->n < Timing::kMaxSections) {
+        if (t && t->active && t->level >= (main_kernel ? 1 : 2) && t->ready && t->n < Timing::kMaxSections) {
             idx = t->n++;
             t->name[idx] = name;
-            (void)hipEventRecord(t->ev[2 * idx], t->stream);
+            on_kernels = main_kernel;
+            if (!on_kernels) (void)hipEventRecord(t->ev[2 * idx], t->stream);
         }
     }
     ~Section() {
-        if (idx >= 0) (void)hipEventRecord(t->ev[2 * idx + 1], t->stream);
+        if (idx < 0) return;
+        if (!on_kernels) {
+            (void)hipEventRecord(t->ev[2 * idx + 1], t->stream);
+        } else if (!start_taken && !stop_taken) {
+            // nothing was launched inside: an empty bracket
+            (void)hipEventRecord(t->ev[2 * idx], t->stream);
+            (void)hipEventRecord(t->ev[2 * idx + 1], t->stream);
+        } else if (!stop_taken) {
+            (void)hipEventRecord(t->ev[2 * idx + 1], t->stream);
+        }
+    }
+    hipEvent_t start_event() {
+        if (idx < 0 || !on_kernels || start_taken) return nullptr;
+        start_taken = true;
+        return t->ev[2 * idx];
+    }
+    hipEvent_t stop_event() {
+        if (idx < 0 || !on_kernels) return nullptr;
+        stop_taken = true;
+        return t->ev[2 * idx + 1];
     }
     Section(const Section&) = delete;
     Section& operator=(const Section&) = delete;
 };
 
+// Kernel launch inside a main-kernel section (sec may be null = plain launch): `first` / `last`
+// say whether this is the section's first / last kernel.
+template <typename... P, typename... A>
+inline void launch_timed(Section* sec, bool first, bool last, void (*kernel)(P...), dim3 grid, dim3 block,
+                         size_t lds, hipStream_t s, A&&... args) {
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    hipEvent_t a = (sec && first) ? sec->start_event() : nullptr;
+    hipEvent_t b = (sec && last) ? sec->stop_event() : nullptr;
+    if (a || b)
+        hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, s, a, b, 0u, static_cast<P>(args)...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, static_cast<P>(args)...);
+}
+
 // ---- quant.hip
-hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s);
+// sec (may be null): the main-kernel section the launch belongs to
+hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s, Section* sec);
 hipError_t launch_reduce_partials(const double* partials, int stride, const int* cols, int ncols,
                                   const DevLayer* layers, int n_layers, double* errors, hipStream_t s);
 hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
                                  int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
-                                 hipStream_t s);
+                                 hipStream_t s, Section* sec);
 
 // ---- dp.hip
 struct DpEntry {            // one usable candidate of a layer (equal bins merged by the host)
@@ -90,10 +160,12 @@ struct DpBuildParams {
     int64_t* result;          // out: [0] status (0 ok, 1 infeasible, 3 invalid input), [5] swept layers,
                               //      [6] bit pattern of E_max
 };
-hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s);
+hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s, Section* sec);
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
 // max_bin: largest bin in entries
-hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s);
+// sec (may be null): the section's last kernel, and its first one too when `first_in_section`
+hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s, Section* sec,
+                     bool first_in_section);
 
 // ---- topk.hip
 struct TopkScratch {
@@ -149,7 +221,7 @@ hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hip
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
 // the read; otherwise the quantization profile kernel does the same work
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                        const Tile* d_tiles, int n_tiles, hipStream_t s);
+                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec);
 // exact threshold bins from the histogram; layers whose predicted bound was too high are
 // collected again with the exact one
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
@@ -182,7 +254,7 @@ hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L
                               float* out, bool accumulate, Timing* tm, hipStream_t s);
 
 // ---- decode.hip: receiver side of quantization and Top-K, gradient accumulation
-hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s);
+hipError_t launch_accumulate(float* acc, const float* g, int64_t n, bool reset, hipStream_t s, Section* sec);
 hipError_t launch_decode(const uint8_t* payload, const DevLayer* layers, const Tile* tiles, int n_tiles,
                          float* out, bool accumulate, bool any_quant, bool any_topk, Timing* tm, hipStream_t s);
 

@@ -1021,13 +1021,14 @@ static hipError_t lr_factorize(LrHost* H, LrParams p, int iters, Timing* tm, hip
     p.q_from_scratch = it > 0 ? 1 : 0;
     {
         Section sec(tm, "lowrank_gemm_p", true);
+        const bool reduce = H->ppart_elems > 0;        // split-K partials: a second kernel ends the section
         if (p.e)
-            hipLaunchKernelGGL(lr_gemm1_kernel<true>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
+            launch_timed(&sec, true, !reduce, lr_gemm1_kernel<true>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
         else
-            hipLaunchKernelGGL(lr_gemm1_kernel<false>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
+            launch_timed(&sec, true, !reduce, lr_gemm1_kernel<false>, dim3((unsigned)H->p_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
-        if (H->ppart_elems > 0) {
-            hipLaunchKernelGGL(lr_preduce_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
+        if (reduce) {
+            launch_timed(&sec, false, true, lr_preduce_kernel, dim3((unsigned)H->row_tiles.size()), dim3(256), 0, s, p);
             LR_CHECK(hipGetLastError());
         }
     }
@@ -1047,9 +1048,9 @@ static hipError_t lr_factorize(LrHost* H, LrParams p, int iters, Timing* tm, hip
     {
         Section sec(tm, "lowrank_gemm_q", true);
         if (p.e)
-            hipLaunchKernelGGL(lr_gemm2_kernel<true>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
+            launch_timed(&sec, true, true, lr_gemm2_kernel<true>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
         else
-            hipLaunchKernelGGL(lr_gemm2_kernel<false>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
+            launch_timed(&sec, true, true, lr_gemm2_kernel<false>, dim3((unsigned)H->col_tiles.size()), dim3(256), 0, s, p);
         LR_CHECK(hipGetLastError());
     }
     {
@@ -1108,7 +1109,7 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     p.payload = payload;
     LR_CHECK(lr_factorize(H, p, t->power_iters, tm, s));
     Section sec(tm, "lowrank_ef", true);
-    hipLaunchKernelGGL(lr_ef_kernel<false>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
+    launch_timed(&sec, true, true, lr_ef_kernel<false>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -1127,7 +1128,7 @@ hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L
     p.accumulate = accumulate ? 1 : 0;
     p.r_max = r_max;
     Section sec(tm, "lowrank_decode", true);
-    hipLaunchKernelGGL(lr_ef_kernel<true>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
+    launch_timed(&sec, true, true, lr_ef_kernel<true>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

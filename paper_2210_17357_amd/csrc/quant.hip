@@ -448,12 +448,12 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
 }
 
 // ------------------------------------------------------------------------- launchers
-hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s) {
+hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hipStream_t s, Section* sec) {
     if (n_tiles <= 0) return hipSuccess;
     const dim3 grid(n_tiles), block(kThreads);
     const bool st = p.stochastic != 0, ef = p.e != nullptr;
 #define LGRECO_LAUNCH(S, E, H) \
-    hipLaunchKernelGGL((quant_profile_kernel<S, E, H>), grid, block, 0, s, p)
+    launch_timed(sec, true, true, quant_profile_kernel<S, E, H>, grid, block, 0, s, p)
     if (st) {
         if (ef) { if (hist) LGRECO_LAUNCH(true, true, true); else LGRECO_LAUNCH(true, true, false); }
         else    { if (hist) LGRECO_LAUNCH(true, false, true); else LGRECO_LAUNCH(true, false, false); }
@@ -478,13 +478,13 @@ hipError_t launch_reduce_partials(const double* partials, int stride, const int*
 
 hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
                                  int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
-                                 hipStream_t s) {
+                                 hipStream_t s, Section* sec) {
     if (n_tiles <= 0) return hipSuccess;
     QuantCompressParams p{g, e, layers, tiles, payload, (uint32_t)seed, (uint32_t)(seed >> 32)};
     if (stochastic)
-        hipLaunchKernelGGL((quant_compress_kernel<true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, quant_compress_kernel<true>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     else
-        hipLaunchKernelGGL((quant_compress_kernel<false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, quant_compress_kernel<false>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     return hipGetLastError();
 }
 

@@ -1198,14 +1198,14 @@ static CollectParams collect_params(TopkScratch* t, const float* g, const float*
 // main pass without quantization candidates: histogram + collection in one read.  ef_out != null
 // (compress): also records index and sign of every candidate and writes x to the error feedback.
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                        const Tile* d_tiles, int n_tiles, hipStream_t s) {
+                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec) {
     if (n_tiles <= 0) return hipSuccess;
     CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
     p.ef_out = ef_out;
     if (ef_out)
-        hipLaunchKernelGGL((topk_collect_kernel<true, true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, topk_collect_kernel<true, true>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     else
-        hipLaunchKernelGGL((topk_collect_kernel<true, false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, topk_collect_kernel<true, false>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     return hipGetLastError();
 }
 
@@ -1307,7 +1307,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, tile_elems, ks.data(), 1, 1, tm, s));
     {
         Section sec(tm, "topk_collect", true);
-        TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s));
+        TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s, &sec));
     }
     TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));

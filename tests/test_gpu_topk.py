@@ -214,10 +214,11 @@ def test_one_handle_serves_layer_tables_of_different_lengths(reuse):
 
 
 def test_compress_calls_queued_back_to_back():
-    """lgreco_compress returns with its kernels queued.  Two calls with different choices (so the
-    second rewrites the pinned control block the first uploaded from), no wait in between, each
-    into its own payload and error-feedback buffers: both must come out right; the brackets of the
-    call are readable afterwards."""
+    """lgreco_compress returns with its kernels queued.  Calls without a wait in between, each
+    into its own payload and error-feedback buffers: a repeated choice is queued straight behind
+    the previous call (nothing is uploaded, nothing waits), a changed choice uploads the new layer
+    records and the Top-K control block first.  All must come out right; with timing switched on
+    afterwards, the events of a queued call are readable."""
     from paper_2210_17357_amd import binding as B
     torch = torch_cuda()
     rng = np.random.default_rng(5)
@@ -230,17 +231,20 @@ def test_compress_calls_queued_back_to_back():
     g, e, _ = to_device(batch)
     L = len(sizes_all)
     h = B.Handle(int(batch.grads.size), L, len(cands))
-    h.set_timing(1)
     runs = []
-    for rot in (0, 1, 2, 0):
+    for rot in (0, 0, 0, 1, 1, 2, 0):
         choice = np.array([(l + rot) % len(cands) for l in range(L)], np.int32)
         offsets = B.payload_layout(layers, ctab, choice)
         payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
         ef_dev = e.clone()
         h.compress(g, ef_dev, layers, ctab, choice, payload, offsets)      # no wait
         runs.append((choice, offsets, payload, ef_dev))
+        if len(runs) == 5:
+            h.set_timing(1)             # from here on the calls carry events
     names = [n for n, _ in h.get_timing(B.CALL_COMPRESS)]
     assert "topk_collect" in names
+    totals = {n: (ms, c) for n, ms, c in h.get_timing_totals(B.CALL_COMPRESS)}
+    assert totals["topk_collect"][1] == 2 and totals["topk_collect"][0] > 0.0
     for choice, offsets, payload, ef_dev in runs:
         pay, new_ef = payload.cpu().numpy(), ef_dev.cpu().numpy()
         for l in range(L):
