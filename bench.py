@@ -3,7 +3,9 @@
 
 One "step" = one pass of the whole path over one batch of synthetic gradients:
     lgreco_profile (every candidate) -> lgreco_emax -> lgreco_solve -> lgreco_payload_layout
-    -> lgreco_compress (chosen per-layer setting, error feedback updated).
+    -> lgreco_compress (chosen per-layer setting, error feedback updated),
+by default through lgreco_profile_solve_compress, which is those calls in one (--calls two / four
+go through the separate entry points; same kernels, same results).
 Inputs are resident in HBM before the timed region.  Every step works on its own copy of the
 error-feedback buffer, so all steps do identical work and nothing is restored inside the
 timed region.
@@ -48,9 +50,11 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--separate-calls", action="store_true",
-                    help="lgreco_profile, lgreco_emax and lgreco_solve as three calls instead of "
-                         "lgreco_profile_solve (same results; about 8 us per step slower on the largest workload)")
+    ap.add_argument("--calls", choices=("one", "two", "four"), default="one",
+                    help="one: lgreco_profile_solve_compress; two: lgreco_profile_solve, then layout + "
+                         "lgreco_compress; four: lgreco_profile, lgreco_emax, lgreco_solve, then layout + "
+                         "lgreco_compress (same results; each return to the caller between the solver and the "
+                         "compression kernels leaves the GPU idle for some tens of microseconds)")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
@@ -134,6 +138,9 @@ def main():
     h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
                  seed=w.seed, r_max=w.r_max, power_iters=args.power_iters,
                  reuse_thresholds=not args.sample_every_call)
+    # The one-call form hands one error-feedback buffer to profile and compression; a workload whose
+    # profile runs without one (NULL, half the read traffic) keeps the two-call form.
+    calls = "two" if (args.calls == "one" and not has_ef) else args.calls
     level = 0 if args.no_kernel_timing else (2 if args.detail else 1)
     h.set_timing(level)
     h.set_timing_stride(max(1, args.time_every))
@@ -151,24 +158,31 @@ def main():
     def step(i, record):
         ef = ef_pool[i]
         t0 = time.perf_counter()
-        if args.separate_calls:
-            errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
-            t1 = time.perf_counter()
-            e_max = B.emax(errors, w.default)
-            st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
+        if calls == "one":
+            # the whole path as one call: nothing runs in the caller between the solver's result
+            # and the compression kernels
+            st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
+                g, ef, layers, ctab, w.default, w.n_bins, payload, q_pool[i], stream=stream)
+            t1 = t2 = t3 = time.perf_counter()
         else:
-            # profile, E_max and solve as one call: no host round trip between their kernels
-            st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
-                g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
-            t1 = time.perf_counter()
-        t2 = time.perf_counter()
-        offsets = B.payload_layout(layers, ctab, choice, w.bucket)
-        h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
-        t3 = time.perf_counter()
+            if calls == "four":
+                errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
+                t1 = time.perf_counter()
+                e_max = B.emax(errors, w.default)
+                st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
+            else:
+                # profile, E_max and solve as one call: no host round trip between their kernels
+                st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
+                    g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
+                t1 = time.perf_counter()
+            t2 = time.perf_counter()
+            offsets = B.payload_layout(layers, ctab, choice, w.bucket)
+            h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
+            t3 = time.perf_counter()
         if record:
             # host clocks: compress only queues its kernels, their GPU time falls into the wait of
-            # the next step's profile call (or the final synchronize); with the one-call form
-            # "profile" covers profile + solve
+            # the next step's profile call (or the final synchronize); with --calls two "profile"
+            # covers profile + solve, with --calls one everything
             phase["profile"] += t1 - t0
             phase["solve"] += t2 - t1
             phase["compress"] += t3 - t2
@@ -255,7 +269,7 @@ def main():
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
                    "reuse_thresholds": not args.sample_every_call,
-                   "profile_and_solve": "three calls" if args.separate_calls else "one call",
+                   "calls_per_step": calls,
                    "kernels_timed_every_n_steps": None if args.no_kernel_timing else max(1, args.time_every),
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,

@@ -27,8 +27,9 @@
  *     every other pointer is HOST memory.  The caller owns all of them.  The handle owns
  *     only scratch memory sized at lgreco_create().
  *   - All kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = default
- *     stream).  Host outputs are valid when the call returns (the call waits for them); a call
- *     without host outputs (lgreco_compress) does not wait.  Calls on one handle must not
+ *     stream).  Host outputs are valid when the call returns (the call waits for them, not
+ *     necessarily for the stream to drain); a call without host outputs (lgreco_compress) does
+ *     not wait.  Calls on one handle must not
  *     overlap: use one stream per handle, or order the streams yourself.
  *   - Every function returns an lgreco status: 0 on success, negative on error.  Nothing
  *     throws, nothing prints.  Inputs must be finite; NaN/Inf gradients give undefined
@@ -216,6 +217,26 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                     const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                     const int32_t* choice, float* d_q, uint8_t* d_payload, const int64_t* offsets,
                     void* stream);
+
+/* One pass of the whole path as one call: lgreco_profile_solve, lgreco_payload_layout and
+ * lgreco_compress with the choice just found (Algorithm 1 followed by the step that applies its
+ * result, section "Implementation"), so that no time passes in the caller between the solver's
+ * result and the compression kernels.  Arguments as in those calls, except:
+ *   d_ef      required: read by the profile, then updated by the compression
+ *   d_q       LOWRANK (else NULL): warm start of the profile, then in/out of the compression
+ *   d_payload device buffer of payload_capacity bytes; the layout depends on the choice, so it must
+ *             hold the largest total any choice gives (sum over layers of the largest size, plus
+ *             16 bytes of padding per layer); a choice that does not fit: LGRECO_ENOSPACE, nothing
+ *             compressed
+ *   offsets   host out [L+1], the layout used
+ * Host outputs of the profile and the solve are valid on return; the compression kernels are
+ * queued as with lgreco_compress.  LGRECO_EINFEASIBLE: as lgreco_solve, nothing compressed. */
+int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
+                                  const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
+                                  int32_t P, float* d_q, int32_t default_cand, int32_t n_bins,
+                                  double* errors, int64_t* sizes, double* e_max, int32_t* choice,
+                                  int64_t* total_size, double* total_error, uint8_t* d_payload,
+                                  int64_t payload_capacity, int64_t* offsets, void* stream);
 
 /* Receiver side of the codec: turn the payloads written by lgreco_compress (same layer table,
  * candidate list, choice and offsets) back into dense gradients, the step that follows the

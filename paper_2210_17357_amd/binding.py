@@ -19,7 +19,7 @@ OK, EINVAL, ENOSPACE, EINFEASIBLE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 QUANT, TOPK, LOWRANK = 0, 1, 2
 CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 
-EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve",
+EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve", "lgreco_profile_solve_compress",
            "lgreco_candidate_range", "lgreco_emax",
            "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
            "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error")
@@ -65,6 +65,9 @@ def lib() -> C.CDLL:
         l.lgreco_profile.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp]
         l.lgreco_profile_solve.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, i32, i32, vp, vp, C.POINTER(dbl), vp,
                                            C.POINTER(i64), C.POINTER(dbl), vp]
+        l.lgreco_profile_solve_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, i32, i32, vp, vp,
+                                                    C.POINTER(dbl), vp, C.POINTER(i64), C.POINTER(dbl), vp, i64, vp,
+                                                    vp]
         l.lgreco_candidate_range.argtypes = [i32, dbl, i32, vp, i32, C.POINTER(i32), C.POINTER(i32)]
         l.lgreco_emax.argtypes = [vp, i32, i32, i32, C.POINTER(dbl)]
         l.lgreco_solve.argtypes = [vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64), C.POINTER(dbl), vp]
@@ -226,6 +229,24 @@ class Handle:
                                         C.byref(terr), _stream(stream))
         self._check(st, allow=(EINFEASIBLE,))
         return st, errors, szs, e_max.value, choice, tsize.value, terr.value
+
+    def profile_solve_compress(self, d_grads, d_ef, layers, cands, default_cand: int, n_bins: int, d_payload,
+                               d_q=None, stream=None):
+        """The whole path as one call: (status, errors, sizes, e_max, choice, total_size,
+        total_error, offsets); the compression kernels are queued when it returns."""
+        L, P = len(layers), len(cands)
+        errors = np.zeros((L, P), np.float64)
+        szs = np.zeros((L, P), np.int64)
+        choice = np.zeros(L, np.int32)
+        offsets = np.zeros(L + 1, np.int64)
+        e_max, tsize, terr = C.c_double(), C.c_int64(), C.c_double()
+        st = lib().lgreco_profile_solve_compress(
+            self._h, _dptr(d_grads), _dptr(d_ef), C.addressof(layers), L, C.addressof(cands), P, _dptr(d_q),
+            int(default_cand), int(n_bins), _np(errors), _np(szs), C.byref(e_max), _np(choice), C.byref(tsize),
+            C.byref(terr), _dptr(d_payload), int(d_payload.numel() * d_payload.element_size()), _np(offsets),
+            _stream(stream))
+        self._check(st, allow=(EINFEASIBLE,))
+        return st, errors, szs, e_max.value, choice, tsize.value, terr.value, offsets
 
     def solve(self, errors: np.ndarray, szs: np.ndarray, e_max: float, n_bins: int, stream=None):
         errors = np.ascontiguousarray(errors, np.float64)

@@ -1,6 +1,7 @@
 // C ABI of liblgreco.so: handle, argument checks, host-side tables (sizes, bins, tiles,
 // payload layout) and the launch sequence of each entry point.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -66,6 +67,7 @@ struct lgreco_handle {
     int32_t* h_build = nullptr;
     int32_t* d_build_host = nullptr;
     int32_t* d_nsweep = nullptr;
+    int64_t dp_seq = 0;                  // sequence number of the last solver launch
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
@@ -257,6 +259,31 @@ void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
     if (kind == LGRECO_CALL_SOLVE) h->n_sub = 0;
 }
 
+// Waits for the solver launch `seq` to hand over its result block.  The kernel writes the block
+// straight into pinned host memory and stores its sequence number last, behind a system-scope
+// fence: polling that word sees the end of the solve several microseconds before a stream
+// synchronisation returns (the stream is still retiring the kernel then; the caller's next
+// launches queue behind it as usual).  The stream is queried now and then, so a launch that
+// failed ends the wait through the ordinary error path.
+int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s) {
+    volatile const int64_t* const flag = h->h_result + 7;
+    for (uint32_t polls = 1; *flag != seq; ++polls) {
+        if ((polls & 0xFFFu) == 0 && hipStreamQuery(s) != hipErrorNotReady) break;
+#if !defined(__HIP_DEVICE_COMPILE__) && (defined(__x86_64__) || defined(__i386__))
+        asm volatile("pause");
+#endif
+    }
+    if (*flag != seq) {
+        HIPCHK(hipStreamSynchronize(s));
+        if (*flag != seq) {
+            h->hip_error = "the solver kernel did not report";
+            return LGRECO_EHIP;
+        }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return LGRECO_OK;
+}
+
 // Device-clock sub-sections of the solve (100 MHz constant-rate counter).
 void record_dp_sub(lgreco_handle* h) {
     h->sub_name[0] = "dp_solve.sweep";
@@ -326,6 +353,9 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
     HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
     HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
+    // (pinned allocations are not cleared, and a freed block of an earlier handle may come back:
+    // the hand-over word the host polls must not hold an old sequence number)
+    std::memset(h->h_dp_out, 0, dp_out);
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_dp_out), h->h_dp_out, 0));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(const_cast<uint4**>(&h->d_dp_in_host)), h->h_dp_in, 0));
     h->d_count = reinterpret_cast<int32_t*>(h->d_dp_in);
@@ -730,13 +760,17 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         // the kernel itself fetches the input block from the pinned staging memory
         const size_t in_bytes = h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count;
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
-                    h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr};
+                    h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr,
+                    ++h->dp_seq};
         {
             Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s, &sec, true));
         }
         harvest_others(h);
-        HIPCHK(hipStreamSynchronize(s));  // the kernel wrote h_dp_out
+        {
+            const int wst = wait_for_solver(h, h->dp_seq, s);     // the kernel wrote h_dp_out
+            if (wst != LGRECO_OK) return wst;
+        }
         if (h->tm->active) record_dp_sub(h);
         if (h->h_result[0] == 1) return infeasible();
         if (h->h_result[0] != 0) {
@@ -802,14 +836,18 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
     DpBuildParams bp{h->d_errors_dev, h->d_sizes, h->d_errors, L, P, n_bins, default_cand, P, h->d_entries,
                      h->d_count, h->d_build_host, h->d_build_host + L, h->d_nsweep, h->d_result};
     DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, L, n_bins, 0, 0, 0, P,
-                nullptr, nullptr, 0, h->d_nsweep};
+                nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq};
     {
         Section sec(h->tm, "dp_solve", true);
         HIPCHK(launch_dp_build(bp, s, &sec));
         HIPCHK(launch_dp(dp, true, n_bins, s, &sec, false));
     }
     harvest_others(h);
-    HIPCHK(hipStreamSynchronize(s));      // error table, build report and solver output are in pinned memory
+    {
+        // error table, build report and solver output are in pinned memory
+        const int wst = wait_for_solver(h, h->dp_seq, s);
+        if (wst != LGRECO_OK) return wst;
+    }
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     const int64_t status = h->h_result[0];
     {
@@ -937,6 +975,21 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     // No host output: the call returns with its kernels queued.  Payload, error feedback and q are
     // ready in stream order; the caller's next call on this stream (or its own wait) sees them.
     return LGRECO_OK;
+}
+
+int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
+                                  const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                                  float* d_q, int32_t default_cand, int32_t n_bins, double* errors, int64_t* sizes,
+                                  double* e_max, int32_t* choice, int64_t* total_size, double* total_error,
+                                  uint8_t* d_payload, int64_t payload_capacity, int64_t* offsets, void* stream) {
+    if (!d_ef || !d_payload || !offsets || payload_capacity < 0) return LGRECO_EINVAL;
+    int st = lgreco_profile_solve(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
+                                  e_max, choice, total_size, total_error, stream);
+    if (st != LGRECO_OK) return st;
+    st = lgreco_payload_layout(layers, L, cands, P, choice, h->cfg.bucket, offsets);
+    if (st != LGRECO_OK) return st;
+    if (offsets[L] > payload_capacity) return LGRECO_ENOSPACE;
+    return lgreco_compress(h, d_grads, d_ef, layers, L, cands, P, choice, d_q, d_payload, offsets, stream);
 }
 
 int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_t* offsets,

@@ -76,7 +76,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     // it found come from memory; anything but "ok" there ends the solve.
     int L = p.L;
     if (p.L_dev) {
-        if (p.L_dev[1] != 0) return;
+        if (p.L_dev[1] != 0) {            // the build kernel reported the status; only the hand-over is left
+            if (tid == 0) {
+                __threadfence_system();
+                p.result[7] = p.seq;
+            }
+            return;
+        }
         L = p.L_dev[0];
     }
 
@@ -275,6 +281,11 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         p.result[3] = (int64_t)(t_sweep - t_begin);
         p.result[4] = (int64_t)(wall_clock64() - t_sweep);
     }
+    // hand-over to a polling host: every thread's stores to the result block first, then the
+    // launch's sequence number
+    __threadfence_system();
+    __syncthreads();
+    if (tid == 0) p.result[7] = p.seq;
 }
 
 // ------------------------------------------------------------------ entry lists on the device

@@ -141,6 +141,9 @@ struct DpParams {
     // is then only the capacity the LDS tables are sized for), [1] the status the build found
     // (not 0: nothing to solve).
     const int32_t* L_dev;
+    // Written to result[7] as the kernel's last store (after a system-scope fence): the host
+    // may poll the pinned result block for it instead of waiting for the stream.
+    int64_t seq;
 };
 // Entry lists built on the device from the error table (see dp_build_kernel).
 constexpr int kBuildThreads = 1024;   // layers per solve on this path

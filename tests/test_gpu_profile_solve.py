@@ -107,3 +107,69 @@ def test_more_candidates_than_the_device_side_step_takes():
     assert one[0] == three[0] == B.OK
     assert np.array_equal(one[1], three[1]) and one[3] == three[3]
     assert np.array_equal(one[4], three[4]) and one[5] == three[5] and one[6] == three[6]
+
+
+@pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
+def test_whole_path_as_one_call_equals_the_separate_calls(kind):
+    """lgreco_profile_solve_compress against lgreco_profile_solve + lgreco_payload_layout +
+    lgreco_compress on the same inputs (which the other tests hold against the oracle): tables,
+    assignment, layout, payload bytes, error feedback and the new Q bit for bit; twice in a row on
+    one handle; a payload buffer that is too small is reported without touching the error feedback."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    if kind == "lowrank":
+        base = W.workload("c3_transformer_lm_lowrank")
+        shapes = tuple(s for s in W.transformer_lm_shapes(layers=1, d=256, d_ff=512, vocab=1024) if len(s) == 2)
+        w = W.Workload("psc_lowrank", shapes, base.candidates, base.default, 200, base.values, base.ef,
+                       base.scale_exp, only_2d=True, r_max=base.r_max)
+    else:
+        w = _workload(kind)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, q0 = to_device(batch)
+    if e is None:
+        e = torch.zeros_like(g)
+    L = len(batch.numels)
+    sizes_tab = B.sizes(layers, ctab)
+    capacity = int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1)
+
+    def handle():
+        return B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, r_max=w.r_max)
+
+    h = handle()
+    st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(g, e, layers, ctab, w.default, w.n_bins, q0)
+    assert st == B.OK
+    offsets = B.payload_layout(layers, ctab, choice)
+    ref_pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ref_ef = e.clone()
+    ref_q = q0.clone() if q0 is not None else None
+    h.compress(g, ref_ef, layers, ctab, choice, ref_pay, offsets, ref_q)
+    torch.cuda.synchronize()
+    h.close()
+
+    h = handle()
+    for rep in range(2):
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        q = q0.clone() if q0 is not None else None
+        out = h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, pay, q)
+        torch.cuda.synchronize()
+        st1, errors1, sizes1, emax1, choice1, tsize1, terr1, offsets1 = out
+        assert st1 == B.OK
+        assert np.array_equal(errors1, errors) and np.array_equal(sizes1, sizes) and emax1 == e_max
+        assert np.array_equal(choice1, choice) and tsize1 == tsize and terr1 == terr
+        assert np.array_equal(offsets1, offsets)
+        assert torch.equal(pay, ref_pay), rep
+        assert torch.equal(ef.view(torch.int32), ref_ef.view(torch.int32)), rep
+        if q is not None:
+            assert torch.equal(q.view(torch.int32), ref_q.view(torch.int32)), rep
+    # a payload buffer too small for the chosen layout
+    small = torch.zeros(max(int(offsets[-1]) - 16, 16), dtype=torch.uint8, device="cuda")
+    ef = e.clone()
+    with pytest.raises(B.LgrecoError) as err:
+        h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, small, q0.clone() if q0 is not None else None)
+    assert err.value.status == B.ENOSPACE
+    torch.cuda.synchronize()
+    assert torch.equal(ef.view(torch.int32), e.view(torch.int32)) and int(small.count_nonzero()) == 0
+    h.close()

@@ -40,6 +40,21 @@ def test_random_small_tables_with_ties_and_unusable_candidates():
     h.close()
 
 
+def test_handles_created_one_after_another():
+    """Each handle's first solves after an earlier handle was destroyed (its pinned result block
+    may be handed to the new one with the old contents): the solver's hand-over to the host must
+    not take anything left there for its own result."""
+    rng = np.random.default_rng(11)
+    for trial in range(6):
+        L, P, D = 20 + trial, 6, 300
+        h = _handle(L, P)
+        for _ in range(1 + trial % 3):
+            errors = np.sort(rng.random((L, P)), axis=1)[:, ::-1] * 10.0 ** rng.uniform(-4, -1, (L, 1))
+            sizes = (rng.integers(1, 30, (L, 1)) * np.arange(1, P + 1) * 10).astype(np.int64)
+            _compare(h, errors, sizes, solver.e_max_uniform(errors, 2), D)
+        h.close()
+
+
 @pytest.mark.parametrize("L,P,D", [(62, 7, 1000), (161, 6, 1000), (97, 5, 2000), (292, 13, 4000),
                                    (40, 32, 10000), (97, 49, 10000), (30, 9, 16384), (3, 4, 1023), (3, 4, 1024)])
 def test_config_sized_tables(L, P, D):
