@@ -986,9 +986,14 @@ int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, floa
     int st = lgreco_profile_solve(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
                                   e_max, choice, total_size, total_error, stream);
     if (st != LGRECO_OK) return st;
-    st = lgreco_payload_layout(layers, L, cands, P, choice, h->cfg.bucket, offsets);
-    if (st != LGRECO_OK) return st;
-    if (offsets[L] > payload_capacity) return LGRECO_ENOSPACE;
+    // the layout of lgreco_payload_layout, from the size table the profile just filled
+    int64_t off = 0;
+    for (int l = 0; l < L; ++l) {
+        offsets[l] = off;
+        off = (off + sizes[(size_t)l * P + choice[l]] + 15) / 16 * 16;
+    }
+    offsets[L] = off;
+    if (off > payload_capacity) return LGRECO_ENOSPACE;
     return lgreco_compress(h, d_grads, d_ef, layers, L, cands, P, choice, d_q, d_payload, offsets, stream);
 }
 

@@ -263,9 +263,14 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         }
     }
     __syncthreads();
+    // The result block lies in the host's pinned memory and the host may be polling it: the first
+    // wavefront alone writes it (the other writer of host memory, the back-trace without LDS
+    // tables, is its thread 0), puts a system-scope fence behind its stores and the launch's
+    // sequence number behind the fence.
+    if (tid >= 64) return;
     const bool feasible = s_val[0] < (int64_t)kInf;
     if (feasible && lds_bins && s_idx[1] == 0)
-        for (int l = tid; l < L; l += kDpThreads)
+        for (int l = lane; l < L; l += 64)
             p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
     if (tid == 0) {
         if (!feasible) {
@@ -281,10 +286,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         p.result[3] = (int64_t)(t_sweep - t_begin);
         p.result[4] = (int64_t)(wall_clock64() - t_sweep);
     }
-    // hand-over to a polling host: every thread's stores to the result block first, then the
-    // launch's sequence number
     __threadfence_system();
-    __syncthreads();
     if (tid == 0) p.result[7] = p.seq;
 }
 
