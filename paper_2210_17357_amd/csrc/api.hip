@@ -2,6 +2,7 @@
 // payload layout) and the launch sequence of each entry point.
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -68,6 +69,14 @@ struct lgreco_handle {
     int32_t* d_build_host = nullptr;
     int32_t* d_nsweep = nullptr;
     int64_t dp_seq = 0;                  // sequence number of the last solver launch
+    // lgreco_profile_solve_compress: what the solver kernel needs to write the compression's layer
+    // records itself - device copies of the build's report and, per (layer, candidate), the integer
+    // parameter a choice stands for plus the family per candidate (pinned staging copy, uploaded
+    // when it changes)
+    int32_t* d_build_dev = nullptr;      // [2 x max_layers] sweep_layer | fixed_choice
+    int32_t* h_apply = nullptr;          // pinned [max_layers x max_cands | max_cands] iparam | family
+    int32_t* d_apply = nullptr;
+    size_t apply_count = 0;              // int32 entries of h_apply / d_apply in use
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
@@ -83,6 +92,17 @@ struct lgreco_handle {
 };
 
 namespace {
+
+constexpr int kDpResultSlots = 16;      // int64 words at the head of the solver's result block
+
+// lgreco_profile_solve_compress: the compression's first kernel queued behind the solver.
+struct EarlyCompress {
+    float* d_ef;
+    uint8_t* d_payload;
+    int64_t capacity;
+    bool launched = false;   // the quantization kernel was queued right behind the solver kernel
+    bool applied = false;    // ... and ran on layer records the solver kernel wrote from its result
+};
 
 int hip_fail(lgreco_handle* h, hipError_t e, const char* what) {
     if (h) h->hip_error = std::string(what) + ": " + hipGetErrorString(e);
@@ -263,12 +283,15 @@ void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
 // straight into pinned host memory and stores its sequence number last, behind a system-scope
 // fence: polling that word sees the end of the solve several microseconds before a stream
 // synchronisation returns (the stream is still retiring the kernel then; the caller's next
-// launches queue behind it as usual).  The stream is queried now and then, so a launch that
-// failed ends the wait through the ordinary error path.
+// launches queue behind it as usual).  Nothing else is asked of the stream meanwhile - a status
+// query can put a marker into the queue, which then sits between this call's kernels and the
+// next ones.  A word that does not arrive within the limit (a solve that long, or a launch that
+// failed) ends in an ordinary stream synchronisation, which also brings up any error.
 int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s) {
     volatile const int64_t* const flag = h->h_result + 7;
+    const auto t0 = std::chrono::steady_clock::now();
     for (uint32_t polls = 1; *flag != seq; ++polls) {
-        if ((polls & 0xFFFu) == 0 && hipStreamQuery(s) != hipErrorNotReady) break;
+        if ((polls & 0x3FFu) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(50)) break;
 #if !defined(__HIP_DEVICE_COMPILE__) && (defined(__x86_64__) || defined(__i386__))
         asm volatile("pause");
 #endif
@@ -349,7 +372,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
     h->dp_entries_off = (sizeof(int32_t) * (size_t)max_layers + 15) / 16 * 16;
     const size_t dp_in = (h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS + 15) / 16 * 16;
-    const size_t dp_out = sizeof(int64_t) * 8 + sizeof(int32_t) * (size_t)max_layers;
+    const size_t dp_out = sizeof(int64_t) * kDpResultSlots + sizeof(int32_t) * (size_t)max_layers;
     HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
     HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
     HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
@@ -363,9 +386,9 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->h_count = reinterpret_cast<int32_t*>(h->h_dp_in);
     h->h_entries = reinterpret_cast<DpEntry*>(h->h_dp_in + h->dp_entries_off);
     h->d_result = reinterpret_cast<int64_t*>(h->d_dp_out);
-    h->d_choice = reinterpret_cast<int32_t*>(h->d_dp_out + sizeof(int64_t) * 8);
+    h->d_choice = reinterpret_cast<int32_t*>(h->d_dp_out + sizeof(int64_t) * kDpResultSlots);
     h->h_result = reinterpret_cast<int64_t*>(h->h_dp_out);
-    h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * 8);
+    h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * kDpResultSlots);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
     HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
     HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16));
@@ -373,6 +396,9 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipHostMalloc(&h->h_build, sizeof(int32_t) * 2 * (size_t)max_layers, hipHostMallocDefault));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_build_host), h->h_build, 0));
     HIPCHK_C(hipMalloc(&h->d_nsweep, sizeof(int32_t) * 2));
+    HIPCHK_C(hipMalloc(&h->d_build_dev, sizeof(int32_t) * 2 * (size_t)max_layers));
+    HIPCHK_C(hipHostMalloc(&h->h_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + max_cands), hipHostMallocDefault));
+    HIPCHK_C(hipMalloc(&h->d_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + max_cands)));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
     for (Timing& t : h->tms) {
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&t.ev[i]));
@@ -402,6 +428,9 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipFree(h->d_errors_dev);
     (void)hipHostFree(h->h_build);
     (void)hipFree(h->d_nsweep);
+    (void)hipFree(h->d_build_dev);
+    (void)hipHostFree(h->h_apply);
+    (void)hipFree(h->d_apply);
     (void)hipHostFree(h->h_bins);
     (void)hipHostFree(h->h_dp_in);
     (void)hipHostFree(h->h_dp_out);
@@ -790,10 +819,12 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     return LGRECO_OK;
 }
 
-int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
-                         int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, int32_t default_cand,
-                         int32_t n_bins, double* errors, int64_t* sizes, double* e_max, int32_t* choice,
-                         int64_t* total_size, double* total_error, void* stream) {
+// lgreco_profile_solve; with `ec`, also the compression's first kernel (see EarlyCompress).
+static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const float* d_ef,
+                              const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
+                              const float* d_q0, int32_t default_cand, int32_t n_bins, double* errors,
+                              int64_t* sizes, double* e_max, int32_t* choice, int64_t* total_size,
+                              double* total_error, void* stream, EarlyCompress* ec) {
     if (!h || !errors || !sizes || !e_max || !choice || L <= 0 || P <= 0) return LGRECO_EINVAL;
     if (default_cand < 0 || default_cand >= P || n_bins < 1 || n_bins > LGRECO_MAX_BINS) return LGRECO_EINVAL;
     if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
@@ -834,13 +865,52 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
         HIPCHK(hipStreamSynchronize(s));      // h_sizes may be rewritten by the next call
     }
     DpBuildParams bp{h->d_errors_dev, h->d_sizes, h->d_errors, L, P, n_bins, default_cand, P, h->d_entries,
-                     h->d_count, h->d_build_host, h->d_build_host + L, h->d_nsweep, h->d_result};
+                     h->d_count, h->d_build_host, h->d_build_host + L, h->d_build_dev, h->d_build_dev + L,
+                     h->d_nsweep, h->d_result};
     DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, L, n_bins, 0, 0, 0, P,
-                nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq};
+                nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq, DpApply{}};
+    if (ec) {
+        // what every (layer, candidate) means to the compression kernels, as lgreco_compress works
+        // it out for a choice: the solver kernel picks the chosen column
+        const size_t n_apply = (size_t)L * P + P;
+        std::vector<int32_t> tab(n_apply);
+        for (int l = 0; l < L; ++l)
+            for (int c = 0; c < P; ++c)
+                tab[(size_t)l * P + c] = cands[c].family == LGRECO_TOPK ? (int32_t)topk_k(layers[l].numel, cands[c].param)
+                                                                        : (int32_t)cands[c].param;
+        for (int c = 0; c < P; ++c) tab[(size_t)L * P + c] = cands[c].family;
+        if (h->apply_count != n_apply || std::memcmp(h->h_apply, tab.data(), sizeof(int32_t) * n_apply) != 0) {
+            std::memcpy(h->h_apply, tab.data(), sizeof(int32_t) * n_apply);
+            h->apply_count = n_apply;
+            HIPCHK(hipMemcpyAsync(h->d_apply, h->h_apply, sizeof(int32_t) * n_apply, hipMemcpyHostToDevice, s));
+            HIPCHK(hipStreamSynchronize(s));      // h_apply may be rewritten by the next call
+        }
+        dp.apply = DpApply{h->d_layers, h->d_build_dev, h->d_build_dev + L, h->d_sizes, h->d_apply,
+                           h->d_apply + (size_t)L * P, L, P, ec->capacity};
+    }
     {
         Section sec(h->tm, "dp_solve", true);
         HIPCHK(launch_dp_build(bp, s, &sec));
         HIPCHK(launch_dp(dp, true, n_bins, s, &sec, false));
+    }
+    if (ec) {
+        // The quantization kernel of the compression, queued behind the solver: it reads the layer
+        // records the solver kernel writes (layers of other families, or all of them after a
+        // failed solve, are skipped).  From here on the host no longer knows what the device's
+        // layer table holds, until lgreco_compress has worked out the same records.
+        Timing* const solve_tm = h->tm;
+        begin_call(h, s, LGRECO_CALL_COMPRESS);
+        h->hl_uploaded.clear();
+        {
+            Section sec(h->tm, "quant_compress", true);
+            HIPCHK(launch_quant_compress(d_grads, ec->d_ef, h->d_layers, h->d_tiles, (int)h->ht.size(), ec->d_payload,
+                                         h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
+        }
+        ec->launched = true;
+        // the compress call stays open until lgreco_compress's part has queued the rest: nobody
+        // reads its events out before (that would wait for the kernel just queued)
+        h->tm->harvested = true;
+        h->tm = solve_tm;
     }
     harvest_others(h);
     {
@@ -850,6 +920,7 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
     }
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     const int64_t status = h->h_result[0];
+    if (ec) ec->applied = h->h_result[8] == 1;
     {
         const uint64_t bits = (uint64_t)h->h_result[6];
         std::memcpy(e_max, &bits, sizeof(double));
@@ -887,6 +958,14 @@ int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* 
     if (total_size) *total_size = tsize;
     if (total_error) *total_error = terr;
     return LGRECO_OK;
+}
+
+int lgreco_profile_solve(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
+                         int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, int32_t default_cand,
+                         int32_t n_bins, double* errors, int64_t* sizes, double* e_max, int32_t* choice,
+                         int64_t* total_size, double* total_error, void* stream) {
+    return profile_solve_impl(h, d_grads, d_ef, layers, L, cands, P, d_q0, default_cand, n_bins, errors, sizes, e_max,
+                              choice, total_size, total_error, stream, nullptr);
 }
 
 int lgreco_solve_weighted(lgreco_handle_t* h, const double* errors, const int64_t* sizes, const int64_t* weights,
@@ -932,14 +1011,21 @@ int lgreco_payload_layout(const lgreco_layer_t* layers, int32_t L, const lgreco_
     return LGRECO_OK;
 }
 
-int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const lgreco_layer_t* layers, int32_t L,
-                    const lgreco_cand_t* cands, int32_t P, const int32_t* choice, float* d_q, uint8_t* d_payload,
-                    const int64_t* offsets, void* stream) {
+// lgreco_compress; `ec` (may be null): the quantization kernel was already queued (EarlyCompress).
+static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, const lgreco_layer_t* layers,
+                         int32_t L, const lgreco_cand_t* cands, int32_t P, const int32_t* choice, float* d_q,
+                         uint8_t* d_payload, const int64_t* offsets, void* stream, const EarlyCompress* ec) {
     if (!h || !d_grads || !d_ef || !layers || !cands || !choice || !d_payload || !offsets || L <= 0 || P <= 0)
         return LGRECO_EINVAL;
     if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    begin_call(h, s, LGRECO_CALL_COMPRESS);
+    const bool early = ec && ec->launched;
+    if (early) {                                            // the call began with that launch
+        h->tm = &h->tms[LGRECO_CALL_COMPRESS];
+        h->tm->harvested = !h->tm->active;
+    } else {
+        begin_call(h, s, LGRECO_CALL_COMPRESS);
+    }
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
     bool any[3] = {false, false, false};
@@ -956,10 +1042,14 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
         any[c.family] = true;
     }
     if (any[LGRECO_LOWRANK] && !d_q) return LGRECO_EINVAL;
+    // the solver kernel wrote these very records into the device's table (same tables, same
+    // arithmetic) and the quantization kernel has run on them: nothing to upload, nothing to repeat
+    const bool quant_done = early && ec->applied && !h->layers_dirty;
+    if (quant_done) h->hl_uploaded = h->hl;
     st = upload_layers(h, s, true);
     if (st != LGRECO_OK) return st;
     const int n_tiles = (int)h->ht.size();
-    if (any[LGRECO_QUANT]) {
+    if (any[LGRECO_QUANT] && !quant_done) {
         Section sec(h->tm, "quant_compress", true);
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
                                      h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
@@ -977,14 +1067,22 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const
     return LGRECO_OK;
 }
 
+int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef, const lgreco_layer_t* layers, int32_t L,
+                    const lgreco_cand_t* cands, int32_t P, const int32_t* choice, float* d_q, uint8_t* d_payload,
+                    const int64_t* offsets, void* stream) {
+    return compress_impl(h, d_grads, d_ef, layers, L, cands, P, choice, d_q, d_payload, offsets, stream, nullptr);
+}
+
 int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                                   const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands, int32_t P,
                                   float* d_q, int32_t default_cand, int32_t n_bins, double* errors, int64_t* sizes,
                                   double* e_max, int32_t* choice, int64_t* total_size, double* total_error,
                                   uint8_t* d_payload, int64_t payload_capacity, int64_t* offsets, void* stream) {
-    if (!d_ef || !d_payload || !offsets || payload_capacity < 0) return LGRECO_EINVAL;
-    int st = lgreco_profile_solve(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
-                                  e_max, choice, total_size, total_error, stream);
+    if (!h || !d_grads || !d_ef || !d_payload || !offsets || payload_capacity < 0) return LGRECO_EINVAL;
+    if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
+    EarlyCompress ec{d_ef, d_payload, payload_capacity};
+    int st = profile_solve_impl(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
+                                e_max, choice, total_size, total_error, stream, &ec);
     if (st != LGRECO_OK) return st;
     // the layout of lgreco_payload_layout, from the size table the profile just filled
     int64_t off = 0;
@@ -994,7 +1092,7 @@ int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, floa
     }
     offsets[L] = off;
     if (off > payload_capacity) return LGRECO_ENOSPACE;
-    return lgreco_compress(h, d_grads, d_ef, layers, L, cands, P, choice, d_q, d_payload, offsets, stream);
+    return compress_impl(h, d_grads, d_ef, layers, L, cands, P, choice, d_q, d_payload, offsets, stream, &ec);
 }
 
 int lgreco_decompress(lgreco_handle_t* h, const uint8_t* d_payload, const int64_t* offsets,

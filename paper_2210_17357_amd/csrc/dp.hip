@@ -77,7 +77,10 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     int L = p.L;
     if (p.L_dev) {
         if (p.L_dev[1] != 0) {            // the build kernel reported the status; only the hand-over is left
+            if (p.apply.layers)
+                for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
             if (tid == 0) {
+                p.result[8] = 0;
                 __threadfence_system();
                 p.result[7] = p.seq;
             }
@@ -263,13 +266,68 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         }
     }
     __syncthreads();
+    const bool feasible = s_val[0] < (int64_t)kInf;
+    const bool traced = feasible && lds_bins && s_idx[1] == 0;
+    if (p.apply.layers) {
+        // The compression's layer records from the assignment (see DpApply), one thread per
+        // layer.  The staging area of the entry lists is free now: candidate per layer first
+        // (fixed layers from the build's report, swept ones from the back-trace), then the payload
+        // offsets, a running sum of the chosen sizes rounded up to 16 bytes.
+        const DpApply& A = p.apply;
+        static_assert(kDpThreads >= kBuildThreads, "one thread per layer");
+        static_assert(sizeof(s_entries) >= kDpThreads + 8 * (kDpThreads / 64) + 8, "staging area too small");
+        uint8_t* const s_chosen = reinterpret_cast<uint8_t*>(s_entries);                          // [threads]
+        int64_t* const s_wtot = reinterpret_cast<int64_t*>(s_entries) + kDpThreads / 8;            // [waves]
+        int32_t* const s_bad = reinterpret_cast<int32_t*>(s_wtot + kDpThreads / 64);
+        const int wave = tid >> 6;
+        bool ok = traced && A.L <= kDpThreads;          // workgroup-uniform
+        int c = 0;
+        int64_t off = 0;
+        if (ok) {
+            s_chosen[tid] = tid < A.L ? (uint8_t)A.fixed_choice[tid] : (uint8_t)0;
+            if (tid == 0) *s_bad = 0;
+            __syncthreads();
+            if (tid < L) s_chosen[A.sweep_layer[tid]] = (uint8_t)p.entries[(size_t)tid * bstride + s_pick[tid]].cand;
+            __syncthreads();
+            c = s_chosen[tid];
+            const bool mine = tid < A.L;
+            const bool bad = mine && c >= A.P;           // a layer neither fixed nor swept
+            const int64_t sz = (mine && !bad) ? (A.sizes[(size_t)tid * A.P + c] + 15) / 16 * 16 : 0;
+            int64_t inc = sz;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int64_t n = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += n;
+            }
+            if (lane == 63) s_wtot[wave] = inc;
+            if (bad) *s_bad = 1;
+            __syncthreads();
+            int64_t base = 0, total = 0;
+            for (int w = 0; w < kDpThreads / 64; ++w) {
+                if (w < wave) base += s_wtot[w];
+                total += s_wtot[w];
+            }
+            off = base + inc - sz;
+            ok = *s_bad == 0 && total <= A.capacity;
+        }
+        if (tid < A.L) {
+            if (ok) {
+                A.layers[tid].payload = off;
+                A.layers[tid].family = A.family[c];
+                A.layers[tid].iparam = A.iparam[(size_t)tid * A.P + c];
+            } else {
+                A.layers[tid].family = -1;
+            }
+        }
+        if (A.L > kDpThreads)
+            for (int l = kDpThreads + tid; l < A.L; l += kDpThreads) A.layers[l].family = -1;
+        if (tid == 0) p.result[8] = ok ? 1 : 0;
+    }
     // The result block lies in the host's pinned memory and the host may be polling it: the first
     // wavefront alone writes it (the other writer of host memory, the back-trace without LDS
     // tables, is its thread 0), puts a system-scope fence behind its stores and the launch's
     // sequence number behind the fence.
     if (tid >= 64) return;
-    const bool feasible = s_val[0] < (int64_t)kInf;
-    if (feasible && lds_bins && s_idx[1] == 0)
+    if (traced)
         for (int l = lane; l < L; l += 64)
             p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
     if (tid == 0) {
@@ -411,10 +469,14 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         total += s_wave[w];
     }
     const int slot = base + before;
-    if (active) p.fixed_choice[tid] = fixed ? first_cand : -1;
+    if (active) {
+        p.fixed_choice[tid] = fixed ? first_cand : -1;
+        p.fixed_choice_dev[tid] = fixed ? first_cand : -1;
+    }
     if (swept) {
         p.count[slot] = cnt;
         p.sweep_layer[slot] = tid;
+        p.sweep_layer_dev[slot] = tid;
         DpEntry* const en = p.entries + (size_t)slot * p.stride;
         int r = 0;
         for (int c = 0; c < P; ++c)

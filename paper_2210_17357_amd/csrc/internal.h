@@ -120,6 +120,22 @@ struct DpEntry {            // one usable candidate of a layer (equal bins merge
     int32_t cand;
     int64_t size;
 };
+// Optional last step of the solver kernel: turn the assignment into the per-layer records the
+// compression kernels read (family, parameter, payload offset), so that a compression kernel
+// queued right behind the solver needs nothing from the host.  The tables hold, per (layer,
+// candidate), what the host would compute for that choice.  If the solve fails, the layout does
+// not fit `capacity`, or the back-trace ran without its LDS tables, every record gets family -1
+// (no compression kernel touches such a layer) and result[8] stays 0; otherwise result[8] = 1.
+struct DpApply {
+    DevLayer* layers;             // null: off
+    const int32_t* sweep_layer;   // [swept] device copy of the build's report
+    const int32_t* fixed_choice;  // [L]
+    const int64_t* sizes;         // [L x P] bytes
+    const int32_t* iparam;        // [L x P] bits / k / rank
+    const int32_t* family;        // [P]
+    int32_t L, P;
+    int64_t capacity;             // bytes the payload buffer holds
+};
 struct DpParams {
     const DpEntry* entries;   // [L x max_count] swept layers only, in candidate order
     const int32_t* count;     // [L] entries per swept layer
@@ -144,6 +160,7 @@ struct DpParams {
     // Written to result[7] as the kernel's last store (after a system-scope fence): the host
     // may poll the pinned result block for it instead of waiting for the stream.
     int64_t seq;
+    DpApply apply;
 };
 // Entry lists built on the device from the error table (see dp_build_kernel).
 constexpr int kBuildThreads = 1024;   // layers per solve on this path
@@ -159,6 +176,8 @@ struct DpBuildParams {
     int32_t* count;           // out [swept]
     int32_t* sweep_layer;     // out [swept] original index of every swept layer
     int32_t* fixed_choice;    // out [L] candidate of a layer fixed here, -1 otherwise
+    int32_t* sweep_layer_dev; // the same two in device memory, for the solver's apply step
+    int32_t* fixed_choice_dev;
     int32_t* n_sweep;         // out, device memory, read by the sweep: [0] swept layers, [1] status
     int64_t* result;          // out: [0] status (0 ok, 1 infeasible, 3 invalid input), [5] swept layers,
                               //      [6] bit pattern of E_max

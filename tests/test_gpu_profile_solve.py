@@ -173,3 +173,49 @@ def test_whole_path_as_one_call_equals_the_separate_calls(kind):
     torch.cuda.synchronize()
     assert torch.equal(ef.view(torch.int32), e.view(torch.int32)) and int(small.count_nonzero()) == 0
     h.close()
+
+
+def test_whole_path_call_compresses_nothing_when_the_solve_fails():
+    """A non-finite gradient makes the error table unusable (the solve reports invalid input or
+    an infeasible budget).  The quantization kernel of the one-call form is queued before the
+    host knows: it must find no layer to work on.  Error feedback and payload stay as they were,
+    and the handle goes on working."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload("quant")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    h = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed)
+    good = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef_good = e.clone()
+    ref = h.profile_solve_compress(g, ef_good, layers, ctab, w.default, w.n_bins, good)
+    assert ref[0] == B.OK
+    bad_g = g.clone()
+    bad_g[int(batch.offsets[5]) + 17] = float("inf")
+    pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef = e.clone()
+    try:
+        st = h.profile_solve_compress(bad_g, ef, layers, ctab, w.default, w.n_bins, pay)[0]
+    except B.LgrecoError as err:
+        st = err.status
+    assert st in (B.EINVAL, B.EINFEASIBLE)
+    torch.cuda.synchronize()
+    assert torch.equal(ef.view(torch.int32), e.view(torch.int32)) and int(pay.count_nonzero()) == 0
+    # the same handle, good data again: the layer records are uploaded anew
+    pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef2 = e.clone()
+    out = h.profile_solve_compress(g, ef2, layers, ctab, w.default, w.n_bins, pay2)
+    torch.cuda.synchronize()
+    assert out[0] == B.OK and np.array_equal(out[4], ref[4])
+    assert torch.equal(pay2, good) and torch.equal(ef2.view(torch.int32), ef_good.view(torch.int32))
+    # and the separate calls after it see the same device state as ever
+    pay3 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef3 = e.clone()
+    h.compress(g, ef3, layers, ctab, out[4], pay3, out[7])
+    torch.cuda.synchronize()
+    assert torch.equal(pay3, good) and torch.equal(ef3.view(torch.int32), ef_good.view(torch.int32))
+    h.close()
