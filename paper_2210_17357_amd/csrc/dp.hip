@@ -89,6 +89,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         L = p.L_dev[0];
     }
 
+    // for the apply step at the end (see DpApply): the build's report for this thread's layer,
+    // fetched now so that the tail does not wait for it
+    int32_t pre_fixed = 0, pre_sweep = 0;
+    if (p.apply.layers) {
+        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
+        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
+    }
     const uint64_t t_begin = wall_clock64();
     if (p.host_in) {
         // fetch the input block from the host's pinned memory: one 16-byte word per thread and
@@ -282,17 +289,24 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         const int wave = tid >> 6;
         bool ok = traced && A.L <= kDpThreads;          // workgroup-uniform
         int c = 0;
+        int32_t fam = 0, ipar = 0;
         int64_t off = 0;
         if (ok) {
-            s_chosen[tid] = tid < A.L ? (uint8_t)A.fixed_choice[tid] : (uint8_t)0;
+            const int32_t swept_cand = tid < L ? p.entries[(size_t)tid * bstride + s_pick[tid]].cand : 0;
+            s_chosen[tid] = tid < A.L ? (uint8_t)pre_fixed : (uint8_t)0;
             if (tid == 0) *s_bad = 0;
             __syncthreads();
-            if (tid < L) s_chosen[A.sweep_layer[tid]] = (uint8_t)p.entries[(size_t)tid * bstride + s_pick[tid]].cand;
+            if (tid < L) s_chosen[pre_sweep] = (uint8_t)swept_cand;
             __syncthreads();
             c = s_chosen[tid];
             const bool mine = tid < A.L;
             const bool bad = mine && c >= A.P;           // a layer neither fixed nor swept
-            const int64_t sz = (mine && !bad) ? (A.sizes[(size_t)tid * A.P + c] + 15) / 16 * 16 : 0;
+            const int cc = bad ? 0 : c;
+            // the three table reads of the chosen column go out together
+            const int64_t raw = mine ? A.sizes[(size_t)tid * A.P + cc] : 0;
+            fam = mine ? A.family[cc] : 0;
+            ipar = mine ? A.iparam[(size_t)tid * A.P + cc] : 0;
+            const int64_t sz = (mine && !bad) ? (raw + 15) / 16 * 16 : 0;
             int64_t inc = sz;
             for (int o = 1; o < 64; o <<= 1) {
                 const int64_t n = __shfl_up(inc, o, 64);
@@ -312,8 +326,8 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         if (tid < A.L) {
             if (ok) {
                 A.layers[tid].payload = off;
-                A.layers[tid].family = A.family[c];
-                A.layers[tid].iparam = A.iparam[(size_t)tid * A.P + c];
+                A.layers[tid].family = fam;
+                A.layers[tid].iparam = ipar;
             } else {
                 A.layers[tid].family = -1;
             }
