@@ -219,3 +219,39 @@ def test_whole_path_call_compresses_nothing_when_the_solve_fails():
     torch.cuda.synchronize()
     assert torch.equal(pay3, good) and torch.equal(ef3.view(torch.int32), ef_good.view(torch.int32))
     h.close()
+
+
+@pytest.mark.parametrize("L", [1024, 1025])
+def test_whole_path_call_at_the_layer_limit_of_the_device_side_step(L):
+    """1024 layers with 4 candidates is the most the device-side list building and the solver's
+    layer-record step take (one thread per layer); 1025 layers go the host's way.  Both must give
+    what the separate calls give."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    rng = np.random.default_rng(L)
+    shapes = tuple((int(n),) for n in rng.integers(100, 700, L))
+    cands = ((W.QUANT, 2.0), (W.QUANT, 4.0), (W.QUANT, 8.0), (W.TOPK, 0.05))
+    base = W.workload("c4_gpt2_medium_mixed")
+    w = W.Workload("many_layers", shapes, cands, 1, 2000, base.values, base.ef, base.scale_exp)
+    batch = W.generate(w)
+    layers, ctab = tables(batch, list(cands))
+    g, e, _ = to_device(batch)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    h = B.Handle(int(batch.grads.size), L, len(cands))
+    st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(g, e, layers, ctab, w.default, w.n_bins)
+    assert st == B.OK
+    ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, w.n_bins)
+    assert np.array_equal(choice, ref_choice) and tsize == ref_size
+    offsets = B.payload_layout(layers, ctab, choice)
+    ref_pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ref_ef = e.clone()
+    h.compress(g, ref_ef, layers, ctab, choice, ref_pay, offsets)
+    for rep in range(2):
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        out = h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, pay)
+        torch.cuda.synchronize()
+        assert out[0] == B.OK and np.array_equal(out[4], choice) and np.array_equal(out[7], offsets)
+        assert np.array_equal(out[1], errors) and out[3] == e_max
+        assert torch.equal(pay, ref_pay) and torch.equal(ef.view(torch.int32), ref_ef.view(torch.int32)), rep
+    h.close()
