@@ -702,7 +702,6 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
     if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
     hipStream_t s = (hipStream_t)stream;
     begin_call(h, s, LGRECO_CALL_SOLVE);
-    const size_t lp = (size_t)L * P;
     const double D = (double)n_bins;
     int64_t worst = 0;                  // sum over layers of the largest usable size
     int max_bin = 0;
@@ -790,7 +789,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         const size_t in_bytes = h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count;
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
                     h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr,
-                    ++h->dp_seq};
+                    ++h->dp_seq, DpApply{}};
         {
             Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s, &sec, true));

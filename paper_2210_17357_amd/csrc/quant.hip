@@ -25,10 +25,10 @@ __device__ __forceinline__ float safe_inv(float lv, float r) {
     return (__builtin_fabsf(inv) <= 3.402823466e38f) ? inv : 0.0f;   // inf or nan -> 0
 }
 
-// One candidate, one element: returns xhat; q (as float) through *qout.
+// One candidate, one element (xm = x - m): returns xhat; q (as float) through *qout.
 template <bool STOCH>
-__device__ __forceinline__ float quant_one(float x, float xm, float m, float inv, float unit, float lv,
-                                           float u, float* qout) {
+__device__ __forceinline__ float quant_one(float xm, float m, float inv, float unit, float lv, float u,
+                                           float* qout) {
     float q = __builtin_floorf(__builtin_fmaf(xm, inv, STOCH ? u : 0.5f));
     // (x - m) * inv >= 0 always, so the lower clamp never acts.  The upper clamp can act only with
     // stochastic rounding: (x - m) * inv <= lv * (1 + 2^-23), so floor(. + 0.5) <= lv, whereas
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                 float s = acc[C];                                                       \
                 _Pragma("unroll") for (int k = 0; k < 8; ++k) {                         \
                     float q;                                                            \
-                    const float xh = quant_one<STOCH>(x[k], xm[k], mn, inv, unit, lv,   \
+                    const float xh = quant_one<STOCH>(xm[k], mn, inv, unit, lv,         \
                                                       STOCH ? u[k] : 0.0f, &q);         \
                     const float d = xh - x[k];                                          \
                     s = __builtin_fmaf(d, d, s);                                        \
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
                         float q;
-                        const float xh = quant_one<STOCH>(x[k], x[k] - mn, mn, inv, unit, lv, u[k], &q);
+                        const float xh = quant_one<STOCH>(x[k] - mn, mn, inv, unit, lv, u[k], &q);
                         const float d = xh - x[k];
                         if (ok[k]) acc[c] = __builtin_fmaf(d, d, acc[c]);
                     }
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         }
     }
     __syncthreads();
-    if (threadIdx.x < nq) {
+    if ((int)threadIdx.x < nq) {
         double s = 0.0;
         for (int w = 0; w < kThreads / 64; ++w) s += s_part[w][threadIdx.x];
         p.partials[(size_t)blockIdx.x * p.stride + p.col[threadIdx.x]] = s;
@@ -281,14 +281,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const double* __re
     for (int ci = 0; ci < kMaxQuant; ++ci) s[ci][threadIdx.x] = a[ci];
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
-        if (threadIdx.x < o) {
+        if ((int)threadIdx.x < o) {
 #pragma unroll
             for (int ci = 0; ci < kMaxQuant; ++ci)
                 if (ci < cols.n) s[ci][threadIdx.x] += s[ci][threadIdx.x + o];
         }
         __syncthreads();
     }
-    if (threadIdx.x < cols.n) errors[(size_t)blockIdx.x * stride + cols.col[threadIdx.x]] = s[threadIdx.x][0];
+    if ((int)threadIdx.x < cols.n) errors[(size_t)blockIdx.x * stride + cols.col[threadIdx.x]] = s[threadIdx.x][0];
 }
 
 // ------------------------------------------------------------------------- compressor
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 float q;
-                const float xh = quant_one<STOCH>(x[k], x[k] - mn, mn, inv, unit, lv, STOCH ? u[k] : 0.0f, &q);
+                const float xh = quant_one<STOCH>(x[k] - mn, mn, inv, unit, lv, STOCH ? u[k] : 0.0f, &q);
                 ne[k] = x[k] - xh;
                 const uint32_t qi = (uint32_t)q;
                 if (k < 4) wa |= qi << (bits * k);
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
                     u = u01(philox_word(rr, (int)(gi & 3)));
                 }
                 float q;
-                const float xh = quant_one<STOCH>(x[k], x[k] - mn, mn, inv, unit, lv, u, &q);
+                const float xh = quant_one<STOCH>(x[k] - mn, mn, inv, unit, lv, u, &q);
                 e[bk * kBucket + i] = x[k] - xh;
                 const uint32_t qi = (uint32_t)q;
                 const int bit = i * bits;

@@ -1115,6 +1115,7 @@ hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hip
 hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevLayer* d_layers,
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                       const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
+    (void)n_tiles;
     const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
     TK_CHECK(ctl_writable(t));
     int64_t base = 0;
