@@ -38,9 +38,9 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # WRITE_SIZE x 1.0, both calibrated on a copy of known size).  Counters cannot be read from inside
 # this process, so the figures are carried here and apply to the default synthetic input only.
 MEASURED_TRAFFIC_BYTES = {
-    "c4_gpt2_medium_mixed": {"compress/topk_collect": 2185.4e6 + 1122.7e6,
-                             "profile/quant_profile_topk_collect": 2910.9e6 + 192.9e6,
-                             "compress/quant_compress": 655.5e6 + 381.2e6},
+    "c4_gpt2_medium_mixed": {"compress/topk_collect": 2186.3e6 + 1130.5e6,
+                             "profile/quant_profile_topk_collect": 2983.2e6 + 200.3e6,
+                             "compress/quant_compress": 656.2e6 + 382.1e6},
     "c3_transformer_lm_lowrank": {"compress/lowrank_ef": 656.6e6 + 268.5e6},
     "c2_resnet50_topk": {"compress/topk_collect": 205.3e6 + 106.7e6, "profile/topk_collect": 205.2e6 + 17.2e6},
     "c1_resnet18_quant": {"profile/quant_profile": 110.3e6, "compress/quant_compress": 93.9e6 + 52.1e6},
