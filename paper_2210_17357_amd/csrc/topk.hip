@@ -282,10 +282,8 @@ struct CollectParams {
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
 // collection.  With only_flagged it collects again the layers whose predicted bound was too high.
 template <bool HIST, bool EMIT>
-__global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p) {
-    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
-    __shared__ double s_red[kThreads / 64];
-    const Tile t = p.tiles[blockIdx.x];
+__device__ __forceinline__ void collect_tile(const CollectParams& p, const int tile, uint32_t* s_hist, double* s_red) {
+    const Tile t = p.tiles[tile];
     if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
     if (p.only_flagged && !p.tl[t.layer].recollect) return;
     const DevLayer L = p.layers[t.layer];
@@ -351,17 +349,52 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
     const double bs = wave_sum((double)col.base);
     if (lane == 0) {
         s_red[wave] = bs;
-        p.tinfo[blockIdx.x].cnt[wave] = col.cur;
-        p.tinfo[blockIdx.x].start[wave] = start;
+        p.tinfo[tile].cnt[wave] = col.cur;
+        p.tinfo[tile].start[wave] = start;
     }
     __syncthreads();
-    if (tid == 0) p.base_part[blockIdx.x] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    if (tid == 0) p.base_part[tile] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
     if (HIST) {
         uint32_t* gh = p.hist + (size_t)t.layer * kHistBins;
         for (int b = tid; b < kHistBins; b += kThreads) {
             const uint32_t c = s_hist[b];
             if (c) atomicAdd(&gh[b], c);
         }
+    }
+}
+
+template <bool HIST, bool EMIT>
+__global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p) {
+    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
+    __shared__ double s_red[kThreads / 64];
+    collect_tile<HIST, EMIT>(p, (int)blockIdx.x, s_hist, s_red);
+}
+
+// The second collection (layers whose predicted bound was too high; none in the usual call): a
+// workgroup looks at kRecollectBatch consecutive tiles, so that the launch that finds nothing to
+// do is short however many tiles there are.
+constexpr int kRecollectBatch = 8;
+template <bool EMIT>
+__global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams p, int n_tiles) {
+    __shared__ uint32_t s_hist[1];
+    __shared__ double s_red[kThreads / 64];
+    const int first = (int)blockIdx.x * kRecollectBatch;
+    // the flags of the batch's tiles first, every load of a level unconditional (indices clamped)
+    // so that the chains tile -> layer -> flag run side by side
+    int layer[kRecollectBatch];
+    uint32_t todo = 0;
+#pragma unroll
+    for (int q = 0; q < kRecollectBatch; ++q) layer[q] = p.tiles[min(first + q, n_tiles - 1)].layer;
+#pragma unroll
+    for (int q = 0; q < kRecollectBatch; ++q) {
+        const uint32_t flagged = p.tl[layer[q]].recollect;
+        const uint32_t k = p.ks[(size_t)layer[q] * kMaxTopk];
+        if (flagged && k && first + q < n_tiles) todo |= 1u << q;
+    }
+    for (int q = 0; q < kRecollectBatch; ++q) {
+        if (!(todo >> q & 1u)) continue;                // workgroup-uniform
+        collect_tile<false, EMIT>(p, first + q, s_hist, s_red);
+        __syncthreads();                                // s_red is reused
     }
 }
 
@@ -851,17 +884,19 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(const Tile* __rest
 
 // per layer: exclusive prefix of the per-wavefront counts, in element order.  Both counts travel
 // in one 64-bit word (each stays below 2^31: a layer has fewer elements than that) and a thread
-// takes four consecutive entries, so a round of the 256 threads covers 1024 entries with one scan.
-__global__ __launch_bounds__(256) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
+// takes four consecutive entries, so a round of the 1024 threads covers 4096 entries with one scan
+// (the largest layer's entries, tiles x 4, are the critical path of this kernel).
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
                                                             const uint2* __restrict__ wavecnt,
                                                             uint2* __restrict__ wavebase) {
-    __shared__ unsigned long long s_tmp[kThreads / 64];
+    __shared__ unsigned long long s_tmp[kScanThreads / 64];
     const DevLayer L = layers[blockIdx.x];
     if (L.family != LGRECO_TOPK) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned long long run = 0;             // (entries above the threshold) << 32 | entries equal to it
     const int q0 = L.tile_begin * (kThreads / 64), q1 = L.tile_end * (kThreads / 64);
-    for (int b = q0; b < q1; b += 4 * 256) {
+    for (int b = q0; b < q1; b += 4 * kScanThreads) {
         const int first = b + 4 * (int)threadIdx.x;
         unsigned long long c[4], mine = 0;
 #pragma unroll
@@ -879,7 +914,7 @@ __global__ __launch_bounds__(256) void topk_tilescan_kernel(const DevLayer* __re
         if (lane == 63) s_tmp[wave] = inc;
         __syncthreads();
         unsigned long long before = run, total = 0;
-        for (int w = 0; w < kThreads / 64; ++w) {
+        for (int w = 0; w < kScanThreads / 64; ++w) {
             if (w < wave) before += s_tmp[w];
             total += s_tmp[w];
         }
@@ -1232,12 +1267,13 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         p.only_flagged = 1;
         p.ef_out = ef_out;
         // a second collection reads x = g + e again: in compress e already holds x, so g is not added
+        const dim3 grid((n_tiles + kRecollectBatch - 1) / kRecollectBatch);
         if (ef_out) {
             p.g = ef_out;
             p.e = nullptr;
-            hipLaunchKernelGGL((topk_collect_kernel<false, true>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+            hipLaunchKernelGGL(topk_recollect_kernel<true>, grid, dim3(kThreads), 0, s, p, n_tiles);
         } else {
-            hipLaunchKernelGGL((topk_collect_kernel<false, false>), dim3(n_tiles), dim3(kThreads), 0, s, p);
+            hipLaunchKernelGGL(topk_recollect_kernel<false>, grid, dim3(kThreads), 0, s, p, n_tiles);
         }
         TK_CHECK(hipGetLastError());
     }
@@ -1321,7 +1357,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     }
     {
         Section sec(tm, "topk_tilescan");
-        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(256), 0, s, d_layers, (const uint2*)t->d_tilecnt,
+        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(kScanThreads), 0, s, d_layers, (const uint2*)t->d_tilecnt,
                            (uint2*)t->d_tilebase);
         TK_CHECK(hipGetLastError());
     }
