@@ -178,9 +178,10 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
     for (int l = 0; l < L; ++l) total += layers[l].numel;
     if (total > h->max_elems) return LGRECO_ENOSPACE;
 
-    // tile size: the largest power of two up to kTile that still gives about kTilesWanted tiles
+    // tile size: see kTilesFill / kTilesWanted
     int tile = kTile;
-    while (tile > kTileMin && total / tile < kTilesWanted) tile /= 2;
+    while (tile > kTileMin && total / tile < kTilesFill) tile /= 2;
+    while (tile > kTileSmooth && total / tile < kTilesWanted) tile /= 2;
     h->tile_elems = tile;
     h->hl.assign(L, DevLayer{});
     h->ht.clear();
