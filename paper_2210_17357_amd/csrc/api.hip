@@ -367,7 +367,10 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipMalloc(&h->d_partials, sizeof(double) * (size_t)h->max_tiles * max_cands));
     // Small results (the error table, the solver's output) are written by the kernels straight into
     // pinned host memory: no copy operation between the last kernel and the host's wait.
-    HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
+    // Memory the kernels write and the host reads (or the other way round) while kernels may still
+    // be running is asked for as coherent whatever the process's default is: the solver's
+    // hand-over is polled, not fenced by a stream synchronisation.
+    HIPCHK_C(hipHostMalloc(&h->h_errors, sizeof(double) * (size_t)max_layers * max_cands + 16, hipHostMallocCoherent));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_errors), h->h_errors, 0));
     const size_t lp = (size_t)max_layers * max_cands;
     h->build_entries.assign((size_t)max_layers * LGRECO_MAX_CANDS, DpEntry{});
@@ -375,8 +378,8 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     const size_t dp_in = (h->dp_entries_off + sizeof(DpEntry) * (size_t)max_layers * LGRECO_MAX_CANDS + 15) / 16 * 16;
     const size_t dp_out = sizeof(int64_t) * kDpResultSlots + sizeof(int32_t) * (size_t)max_layers;
     HIPCHK_C(hipMalloc(&h->d_dp_in, dp_in));
-    HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocDefault));
-    HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_dp_in, dp_in, hipHostMallocCoherent));
+    HIPCHK_C(hipHostMalloc(&h->h_dp_out, dp_out, hipHostMallocCoherent));
     // (pinned allocations are not cleared, and a freed block of an earlier handle may come back:
     // the hand-over word the host polls must not hold an old sequence number)
     std::memset(h->h_dp_out, 0, dp_out);
@@ -394,7 +397,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
     HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16));
     HIPCHK_C(hipMalloc(&h->d_errors_dev, sizeof(double) * (size_t)max_layers * max_cands + 16));
-    HIPCHK_C(hipHostMalloc(&h->h_build, sizeof(int32_t) * 2 * (size_t)max_layers, hipHostMallocDefault));
+    HIPCHK_C(hipHostMalloc(&h->h_build, sizeof(int32_t) * 2 * (size_t)max_layers, hipHostMallocCoherent));
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_build_host), h->h_build, 0));
     HIPCHK_C(hipMalloc(&h->d_nsweep, sizeof(int32_t) * 2));
     HIPCHK_C(hipMalloc(&h->d_build_dev, sizeof(int32_t) * 2 * (size_t)max_layers));
