@@ -164,6 +164,14 @@ def test_whole_path_as_one_call_equals_the_separate_calls(kind):
         assert torch.equal(ef.view(torch.int32), ref_ef.view(torch.int32)), rep
         if q is not None:
             assert torch.equal(q.view(torch.int32), ref_q.view(torch.int32)), rep
+    # the receiver side on the same handle reads the layer records the solver kernel wrote
+    dense = torch.zeros_like(g)
+    h.decompress(pay, offsets, layers, ctab, choice, dense)
+    fresh = handle()
+    dense_ref = torch.zeros_like(g)
+    fresh.decompress(ref_pay, offsets, layers, ctab, choice, dense_ref)
+    fresh.close()
+    assert torch.equal(dense.view(torch.int32), dense_ref.view(torch.int32))
     # a payload buffer too small for the chosen layout
     small = torch.zeros(max(int(offsets[-1]) - 16, 16), dtype=torch.uint8, device="cuda")
     ef = e.clone()
