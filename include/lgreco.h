@@ -170,6 +170,32 @@ int lgreco_solve_weighted(lgreco_handle_t* h, const double* errors, const int64_
                           int32_t n_bins, int32_t* choice, int64_t* total_size,
                           int64_t* total_cost, double* total_error, void* stream);
 
+/* lgreco_emax + lgreco_solve for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  No handle: every intermediate
+ * table (candidate lists, the arg-min table PD) lives in one array in the library's device image,
+ * LGRECO_STATIC_MAX_PD_BYTES + 82432 bytes (4.08 MiB) per GPU the library runs on, held until the
+ * process ends.  The call allocates nothing, copies nothing to or from the host and does not wait:
+ * its three kernels are queued on `stream` and the outputs are complete in stream order.
+ *   d_errors      device [L x P] fp64, row-major, 16-byte aligned (e.g. the table a profile left)
+ *   d_sizes       device [L x P] int64 bytes, 16-byte aligned; every size in [0, 2^30) and the sum
+ *                 over layers of each layer's largest size below 2^30 (else d_result[0] = 3)
+ *   default_cand  E_max = sum over layers, in layer order, of d_errors[l][default_cand]
+ *   d_choice      device out [L]: candidate per layer; each layer's minimum-error candidate when
+ *                 no assignment fits; -1 on invalid input
+ *   d_result      device out [4] int64: [0] 0 ok, 1 no assignment fits the budget, 2 internal
+ *                 inconsistency, 3 invalid table (a NaN, a size out of range); [1] total size;
+ *                 [2] bit pattern of the fp64 total error; [3] bit pattern of the fp64 E_max
+ * Limits (beyond them: LGRECO_ENOSPACE, nothing queued): L <= 1024, P <= 16, L * P <= 4096,
+ * n_bins <= LGRECO_MAX_BINS and L * ((n_bins + 4) & ~3) <= LGRECO_STATIC_MAX_PD_BYTES.
+ * Results equal lgreco_emax + lgreco_solve on the same tables, tie-breaks included.  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU (different streams
+ * without ordering, several threads) race.  The array keeps the last call's contents; the call
+ * rewrites every word it later reads, nothing needs clearing. */
+#define LGRECO_STATIC_MAX_PD_BYTES (4 << 20)
+int lgreco_solve_static(const double* d_errors, const int64_t* d_sizes, int32_t L, int32_t P,
+                        int32_t default_cand, int32_t n_bins, int32_t* d_choice, int64_t* d_result,
+                        void* stream);
+
 /* lgreco_profile, lgreco_emax and lgreco_solve in one call (Algorithm 1 from the Errors matrix to
  * the traced-back assignment): the solve follows the profile on the stream without the host round
  * trip in between - E_max, the discretised errors and the solver's candidate lists are formed on

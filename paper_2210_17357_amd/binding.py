@@ -21,7 +21,7 @@ CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve", "lgreco_profile_solve_compress",
            "lgreco_candidate_range", "lgreco_emax",
-           "lgreco_solve", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
+           "lgreco_solve", "lgreco_solve_static", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
            "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error")
 
 
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
         l.lgreco_solve.argtypes = [vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64), C.POINTER(dbl), vp]
         l.lgreco_solve_weighted.argtypes = [vp, vp, vp, vp, i32, i32, dbl, i32, vp, C.POINTER(i64),
                                             C.POINTER(i64), C.POINTER(dbl), vp]
+        l.lgreco_solve_static.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
         l.lgreco_payload_layout.argtypes = [vp, i32, vp, i32, vp, i32, vp]
         l.lgreco_compress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
         l.lgreco_decompress.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, i32, vp]
@@ -169,6 +170,14 @@ def payload_layout(layers, cands, choice: np.ndarray, bucket: int = 128) -> np.n
     if st != OK:
         raise LgrecoError(st, strerror(st))
     return out
+
+
+def solve_static(d_errors, d_sizes, default_cand: int, n_bins: int, d_choice, d_result, stream=None) -> int:
+    """lgreco_solve_static: device tables in, device choice [L] (int32) and result [4] (int64) out;
+    nothing is allocated, nothing waits.  Returns the status (OK = queued)."""
+    L, P = d_errors.shape
+    return lib().lgreco_solve_static(_dptr(d_errors), _dptr(d_sizes), int(L), int(P), int(default_cand),
+                                     int(n_bins), _dptr(d_choice), _dptr(d_result), _stream(stream))
 
 
 class Handle:

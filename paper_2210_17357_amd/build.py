@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblgreco.so")
 
-SOURCES = ["api.hip", "quant.hip", "topk.hip", "lowrank.hip", "dp.hip", "decode.hip"]
+SOURCES = ["api.hip", "quant.hip", "topk.hip", "lowrank.hip", "dp.hip", "decode.hip", "solve_static.hip"]
 
 # -ffp-contract=off: every fp32 step of the quantizer is a separately rounded operation, fused
 #   multiply-adds are written explicitly where they are meant.

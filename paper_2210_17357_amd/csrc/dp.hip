@@ -387,18 +387,45 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     const double D = (double)p.D;
     if (tid < 2) s_flags[tid] = 0;
     {
-        const int n16 = (LP + 1) / 2;             // the tables are allocated in whole 16-byte words
+        // whole 16-byte words, then the odd last entry on its own: a caller's table ends at LP entries
+        const int n16 = LP / 2;
         const uint4* const ge = reinterpret_cast<const uint4*>(p.errors);
         const uint4* const gs = reinterpret_cast<const uint4*>(p.sizes);
         uint4* const he = reinterpret_cast<uint4*>(p.errors_host);
         for (int i = tid; i < n16; i += kBuildThreads) {
             const uint4 e = ge[i];
             reinterpret_cast<uint4*>(s_err)[i] = e;
-            he[i] = e;
+            if (he) he[i] = e;
             reinterpret_cast<uint4*>(s_size)[i] = gs[i];
+        }
+        if ((LP & 1) && tid == 0) {
+            const double e = p.errors[LP - 1];
+            s_err[LP - 1] = e;
+            if (p.errors_host) p.errors_host[LP - 1] = e;
+            s_size[LP - 1] = p.sizes[LP - 1];
         }
     }
     __syncthreads();
+    // This path sweeps with 32-bit costs.  A caller whose size table the host has not seen asks for
+    // the check here: sizes must be non-negative and every layer's largest, summed, below 2^30.
+    if (p.check_sizes) {
+        int64_t lmax = 0;
+        if (tid < L)
+            for (int c = 0; c < P; ++c) {
+                const int64_t sz = s_size[tid * P + c];
+                if (sz < 0 || sz >= ((int64_t)1 << 30)) s_flags[1] = 1;
+                lmax = sz > lmax ? sz : lmax;
+            }
+        for (int o = 1; o < 64; o <<= 1) lmax += __shfl_xor(lmax, o, 64);
+        __shared__ int64_t s_lmax[kBuildThreads / 64];
+        if (lane == 0) s_lmax[wave] = lmax;
+        __syncthreads();
+        if (tid == 0) {
+            int64_t worst = 0;
+            for (int w = 0; w < kBuildThreads / 64; ++w) worst += s_lmax[w];
+            if (worst >= ((int64_t)1 << 30)) s_flags[1] = 1;
+        }
+    }
     // E_max: errors[l][default] summed for l = 0 .. L-1 in that order (bit-identical to the host
     // loop): one thread, the LDS reads issued in batches ahead of the dependent adds
     if (tid == 0) {

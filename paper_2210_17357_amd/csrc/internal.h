@@ -169,7 +169,7 @@ constexpr int kBuildMaxLP = 4096;     // table entries (layers x candidates) on 
 struct DpBuildParams {
     const double* errors;     // [L x P] device memory
     const int64_t* sizes;     // [L x P] device memory
-    double* errors_host;      // [L x P] the host's pinned copy of the error table, written here
+    double* errors_host;      // [L x P] the host's pinned copy of the error table, written here (may be null)
     int32_t L, P, D, default_cand;
     int32_t stride;           // row stride of `entries` (>= P)
     DpEntry* entries;         // out: swept layers, compacted
@@ -181,6 +181,7 @@ struct DpBuildParams {
     int32_t* n_sweep;         // out, device memory, read by the sweep: [0] swept layers, [1] status
     int64_t* result;          // out: [0] status (0 ok, 1 infeasible, 3 invalid input), [5] swept layers,
                               //      [6] bit pattern of E_max
+    int32_t check_sizes;      // 1: also reject (status 3) sizes this path's 32-bit costs cannot hold
 };
 hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s, Section* sec);
 // narrow: 32-bit costs (sum of the layers' largest sizes < 2^30)
