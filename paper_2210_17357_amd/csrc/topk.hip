@@ -17,7 +17,9 @@
 //      exact bound, so the result never depends on the sample.
 //   4. refinement on the candidates only: energy below each threshold bin (fp64, fixed order),
 //      histogram of the next 10 bits inside each threshold bin, pick the sub-bin, histogram of
-//      the last 9 bits, pick the exact k-th magnitude and the number of equal magnitudes to keep.
+//      the last 9 bits, pick the exact k-th magnitude and the number of equal magnitudes to keep
+//      (compress always; the profile only for a sub-bin whose share of the layer's dropped energy
+//      is not provably negligible, see topk_pick_a_kernel).
 //      Histogram bins carry their energy as integers (entries of one coarse bin share the
 //      exponent: x^2 = m^2 2^(2(E-150)), m the 24-bit significand; sum (m^2 >> 16) is exact), so
 //      nothing depends on the order of atomics.
@@ -656,11 +658,19 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
 }
 
 // One workgroup per (layer, requested k): sub-bin of level A holding the k-th magnitude.
-// ENERGY (profile): the dropped energy is written here and level B is not run.  Inside the sub-bin
-// (magnitudes within 2^-14 of each other) the energies of the dropped entries are taken as evenly
-// spread between the sub-bin's lower edge and its mean, which bounds the relative deviation of
-// the layer's error by 3e-5 in the worst case (a layer whose dropped energy sits entirely in that
-// sub-bin) and is exact when the sub-bin's entries are equal.
+// ENERGY (profile): the dropped energy is written here.  Everything outside the boundary sub-bin is
+// summed exactly (integer energies).  Inside it the dropped entries are the `drop` smallest of
+// `cnt` entries whose integer energies lie in [e_lo, e_hi] and sum to S, so their sum lies in
+//     [ max(drop * e_lo, S - keep * e_hi),  drop * S / cnt ]
+// (the kept ones are the largest: their mean is at least the overall mean, and none exceeds e_hi).
+// The midpoint is taken when half the interval is within 1e-5 of the layer's error - for data
+// without clusters the sub-bin holds a vanishing share of the dropped energy and this is always so.
+// Otherwise (a constant or clipped layer, quantised values) the workgroup resolves the sub-bin
+// exactly: it histograms the last 9 pattern bits of the layer's candidates that fall into the
+// sub-bin - every cell is one fp32 value, so its energy is count * value^2 - and sums the `drop`
+// smallest.  The deviation from the exact dropped energy is therefore at most 1e-5 relative from
+// this step (plus 1.2e-7 from the truncated integer energies and the fp32 sums below the bound).
+constexpr double kInsideTolerance = 1e-5;
 template <bool ENERGY>
 __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsA];
@@ -668,7 +678,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2];
     __shared__ unsigned long long s_e;
-    __shared__ double s_sum[4];
+    __shared__ double s_sum[kPickThreads / 64];
+    __shared__ double s_outside;        // error without the boundary sub-bin's dropped part
+    __shared__ uint32_t s_exact[3];     // [0] resolve the sub-bin exactly, [1] its prefix (pattern >> 9), [2] entries kept in it
     const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
     TopkLayer& T = p.tl[l];
     if (j >= p.ntk || T.sel[j].k == 0) return;
@@ -679,7 +691,10 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         s_hist[b] = 0;
         if (ENERGY) s_en[b] = 0;
     }
-    if (tid == 0) s_e = 0;
+    if (tid == 0) {
+        s_e = 0;
+        s_exact[0] = 0;
+    }
     // energy below the collection bound (tile partials) and of the candidates below the threshold
     // bin (workgroup partials): loaded first so that the histogram work hides the latency; both
     // are summed in a fixed order (per thread, then a fixed tree)
@@ -729,25 +744,82 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         }
         __syncthreads();
     }
+    const uint32_t ex = S.tbin >> (23 - kHistShift);
+    const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + kPackEnergyShift;    // integer energy units -> x^2
     if (tid == 0) {
         const uint32_t need_a = S.need - s_res[1];
         T.sel[j].bin_a = bin_a;
         T.sel[j].need_a = need_a;
         if (ENERGY) {
             const uint32_t cnt = s_hist[bin_a];
+            const double outside = ((s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3])) + ldexp((double)s_e, sh);
             double inside = 0.0;      // dropped part of the sub-bin, in integer-energy units
+            bool exact = false;
             if (cnt > need_a) {
                 const uint32_t edge = (S.tbin << kHistShift) | (bin_a << 9);
                 const double e_lo = (double)(packed_cell(edge) >> kPackCountBits);
-                const double mean = (double)s_en[bin_a] / (double)cnt;
-                const double f = (double)(cnt - need_a) / (double)cnt;
-                inside = (double)(cnt - need_a) * (e_lo + (mean - e_lo) * f);
+                const double e_hi = (double)(packed_cell(edge | 0x1FFu) >> kPackCountBits);
+                const double sum = (double)s_en[bin_a];
+                const double drop = (double)(cnt - need_a), keep = (double)need_a;
+                const double lower = fmax(drop * e_lo, sum - keep * e_hi);
+                const double upper = drop * (sum / (double)cnt);
+                inside = 0.5 * (lower + upper);
+                const double half = 0.5 * (upper - lower);
+                exact = ldexp(half, sh) > kInsideTolerance * (outside + ldexp(inside, sh));
             }
-            const uint32_t ex = S.tbin >> (23 - kHistShift);
-            const int sh = 2 * ((int)(ex ? ex : 1u) - 150) + kPackEnergyShift;
-            p.errors[(size_t)l * p.stride + p.col[j]] =
-                ((s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3])) + ldexp((double)s_e + inside, sh);
+            if (exact) {
+                s_outside = outside;
+                s_exact[1] = (S.tbin << 10) | bin_a;
+                s_exact[2] = need_a;
+                s_exact[0] = 1;
+            } else {
+                p.errors[(size_t)l * p.stride + p.col[j]] = outside + ldexp(inside, sh);
+            }
         }
+    }
+    if (!ENERGY) return;
+    __syncthreads();
+    if (!s_exact[0]) return;                                  // workgroup-uniform
+    // ---- the rare exact route: last 9 bits of the candidates inside the sub-bin
+    const uint32_t prefix = s_exact[1], need_a = s_exact[2];
+    for (int b = tid; b < kBinsB; b += kPickThreads) s_hist[b] = 0;      // kBinsB <= kBinsA
+    __syncthreads();
+    {
+        const DevLayer L = p.layers[l];
+        const int lane = tid & 63, wave = tid >> 6;
+        constexpr int kSub = kThreads / 64;
+        const int npairs = (L.tile_end - L.tile_begin) * kSub;
+        for (int pr = wave; pr < npairs; pr += kPickThreads / 64) {
+            const int tt = L.tile_begin + pr / kSub, sub = pr % kSub;
+            const uint32_t n = p.tinfo[tt].cnt[sub];
+            const uint32_t* __restrict__ items = p.cand + T.cand_base + p.tiles[tt].pos + p.tinfo[tt].start[sub];
+            for (uint32_t i = lane; i < n; i += 64) {
+                const uint32_t pat = items[i];
+                if ((pat >> 9) == prefix) atomicAdd(&s_hist[pat & (kBinsB - 1)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    block_kth_from_top(s_hist, kBinsB, need_a, s_scan, s_res);
+    const uint32_t thr_b = s_res[0], keep_at_thr = need_a - s_res[1];
+    // dropped inside the sub-bin: every pattern below the threshold pattern, and the entries equal
+    // to it that are not kept; one cell per thread (kBinsB == kPickThreads), fixed tree
+    static_assert(kBinsB == kPickThreads, "one cell per thread");
+    double mine = 0.0;
+    {
+        const uint32_t c = s_hist[tid];
+        const uint32_t n_drop = (uint32_t)tid < thr_b ? c : ((uint32_t)tid == thr_b ? c - keep_at_thr : 0u);
+        const double v = (double)__uint_as_float((prefix << 9) | (uint32_t)tid);
+        mine = (double)n_drop * (v * v);
+    }
+    const double w = wave_sum(mine);
+    __syncthreads();                                          // s_sum was read by thread 0 above
+    if ((tid & 63) == 0) s_sum[tid >> 6] = w;
+    __syncthreads();
+    if (tid == 0) {
+        double inside = 0.0;
+        for (int q = 0; q < kPickThreads / 64; ++q) inside += s_sum[q];
+        p.errors[(size_t)l * p.stride + p.col[j]] = s_outside + inside;
     }
 }
 
