@@ -29,12 +29,13 @@ def _check(w, batch, ranks, compress_cycle=True, power_iters=1):
     ref = pipeline.profile(batch.grads, batch.ef, batch.offsets, batch.numels, batch.rows, batch.cols, cands,
                            q0=batch.q0, q_offsets=batch.q_offsets, r_max=w.r_max, power_iters=power_iters)
     assert np.array_equal(sizes, pipeline.sizes_table(batch.numels, batch.rows, batch.cols, cands))
-    # error_r is a difference of norms: 1e-4 relative, with an absolute floor of 1e-6 ||X||^2
-    # (a full-rank layer gives ~1e-30 in the fp64 oracle and exactly 0 here)
+    # error_r is a difference of norms: 1e-4 relative.  Only where the oracle's error is itself
+    # rounding noise (below 1e-8 ||X||^2: a full-rank layer gives ~1e-30 in fp64 and exactly 0 or
+    # fp32 noise here) an absolute bound of 1e-6 ||X||^2 takes its place.
     xnorm = np.array([[float(np.sum((batch.grads[o:o + n].astype(np.float64)
                                       + (0 if batch.ef is None else batch.ef[o:o + n])) ** 2))]
                       for o, n in zip(batch.offsets, batch.numels)])
-    bad = (rel_err(errors, ref) > 1e-4) & (np.abs(errors - ref) > 1e-6 * xnorm)
+    bad = (rel_err(errors, ref) > 1e-4) & ~((ref < 1e-8 * xnorm) & (np.abs(errors - ref) <= 1e-6 * xnorm))
     assert not bad.any(), (np.argwhere(bad)[:5], errors[bad][:5], ref[bad][:5])
     errors2, _ = h.profile(g, e, layers, ctab, q0)
     assert np.array_equal(errors, errors2)
@@ -165,7 +166,7 @@ def test_five_power_iteration_steps_reach_the_svd_tail():
         sv = np.linalg.svd(x, compute_uv=False) ** 2
         for c, r in enumerate(W.LOWRANK_RANKS):
             tail = float(sv[r:].sum())
-            assert errors[l, c] >= tail * (1 - 1e-4) - 1e-6 * sv.sum()       # Eckart-Young
-            assert errors[l, c] <= one[l, c] * (1 + 1e-4) + 1e-6 * sv.sum()  # more steps never hurt here
+            assert errors[l, c] >= tail * (1 - 1e-4) - 1e-7 * sv.sum()       # Eckart-Young
+            assert errors[l, c] <= one[l, c] * (1 + 1e-4) + 1e-7 * sv.sum()  # more steps never hurt here
             if r < min(x.shape):
-                assert errors[l, c] - tail <= 0.5 * (one[l, c] - tail) + 1e-6 * sv.sum()
+                assert errors[l, c] - tail <= 0.5 * (one[l, c] - tail) + 1e-7 * sv.sum()

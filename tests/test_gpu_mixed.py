@@ -38,10 +38,16 @@ def _run(w, batch):
     ref_choice, ref_size, ref_err = solver.solve(errors, sizes, e_max, w.n_bins)
     assert np.array_equal(choice, ref_choice) and tsize == ref_size
     assert tsize <= int(sizes[:, w.default].sum())
-    # end to end (oracle tables): differences must be explained by 1e-4-level error differences
-    oc, _, _ = solver.solve(ref, sizes, solver.e_max_uniform(ref, w.default), w.n_bins)
+    # end to end (oracle tables): an assignment that differs from the oracle's own is explained iff
+    # the oracle's solver reproduces the GPU's choice on the GPU's table (asserted above) and the
+    # 1e-4-level error differences moved at least one candidate across a bin edge; report which
+    ref_emax = solver.e_max_uniform(ref, w.default)
+    oc, _, _ = solver.solve(ref, sizes, ref_emax, w.n_bins)
     if not np.array_equal(oc, choice):
-        assert np.mean(oc != choice) < 0.2
+        flipped = np.argwhere(solver.discretise(errors, e_max, w.n_bins) != solver.discretise(ref, ref_emax, w.n_bins))
+        print("assignment differs from the oracle's end-to-end one in layers", np.flatnonzero(oc != choice).tolist(),
+              "; (layer, candidate) whose bin moved:", flipped.tolist())
+        assert len(flipped) > 0
 
     offsets = B.payload_layout(layers, ctab, choice)
     payload = torch.zeros(int(offsets[-1]) + 16, dtype=torch.uint8, device="cuda")
@@ -92,8 +98,8 @@ def test_full_size_gpt2_medium_sampled_layers():
     """The 355 M-element workload, first through the separate calls (one handle, one profile call
     over all 292 layers and 13 candidates, solve with 4000 bins, one compress call), then in the
     launch configuration the benchmark times (see the end).
-    The oracle computes a sample of layers one by one (1-D tensors, the positional table, one of
-    each 2-D block shape); everything else is checked through properties that hold at any size:
+    The oracle computes a sample of layers one by one (the 51.5 M-element token embedding, 1-D
+    tensors, the positional table, one of each 2-D block shape); everything else is checked through properties that hold at any size:
     the size table, the assignment against the oracle's solver on the same tables, and the squared
     norm of the new error feedback of EVERY layer against the profiled error of its chosen
     candidate."""
@@ -113,14 +119,29 @@ def test_full_size_gpt2_medium_sampled_layers():
     # errors decrease with bits and with density in every layer
     nq = sum(1 for f, _ in cands if f == W.QUANT)
     assert (np.diff(errors[:, :nq], axis=1) <= 0).all() and (np.diff(errors[:, nq:], axis=1) <= 0).all()
-    sample = [1, 2, 3, 4, 5, 6, 7, 10, 11, 12, 13, 14 + 10, 14 + 11, L - 2, L - 1]
+    # layer 0 is the token embedding, 51.5 M elements, the only layer of ~1600 tiles: the scan,
+    # refinement and offset paths over many work items are compared element by element there
+    sample = [0, 1, 2, 3, 4, 5, 6, 7, 10, 11, 12, 13, 14 + 10, 14 + 11, L - 2, L - 1]
+    assert int(batch.numels[0]) == 50257 * 1024
     shapes = {w.shapes[int(batch.tensor_index[l])] for l in sample}
     assert {(1024, 1024), (1024, 3072), (1024, 4096), (4096, 1024), (1024,), (3072,), (4096,)} <= shapes
-    for l in sample:
+    from concurrent.futures import ThreadPoolExecutor
+
+    def oracle_row(l, groups):
         off, n = int(batch.offsets[l]), int(batch.numels[l])
-        ref = pipeline.profile(batch.grads[off:off + n], batch.ef[off:off + n], np.array([0]), np.array([n]),
-                               batch.rows[l:l + 1], batch.cols[l:l + 1], cands)
-        assert rel_err(errors[l], ref[0]).max() < 1e-4, l
+        return [pipeline.profile(batch.grads[off:off + n], batch.ef[off:off + n], np.array([0]), np.array([n]),
+                                 batch.rows[l:l + 1], batch.cols[l:l + 1], [cands[p] for p in ps])[0] for ps in groups]
+    for l in sample:
+        if l == 0:
+            # two minutes of single-threaded numpy: the bit-widths one per thread, the densities (one
+            # sort serves all) in another; the same oracle calls, candidate lists of their own
+            groups = [[p] for p in range(nq)] + [list(range(nq, len(cands)))]
+            with ThreadPoolExecutor(len(groups)) as ex:
+                rows_ = list(ex.map(lambda ps: oracle_row(0, [ps])[0], groups))
+            ref = np.concatenate(rows_)
+        else:
+            ref = oracle_row(l, [list(range(len(cands)))])[0]
+        assert rel_err(errors[l], ref).max() < 1e-4, (l, rel_err(errors[l], ref))
 
     e_max = B.emax(errors, w.default)
     st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins)

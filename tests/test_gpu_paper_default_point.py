@@ -63,7 +63,7 @@ def test_forty_nine_ranks_lowrank():
                            q0=batch.q0, q_offsets=batch.q_offsets, r_max=64)
     xnorm = np.array([[float(np.sum(batch.grads[o:o + n].astype(np.float64) ** 2))]
                       for o, n in zip(batch.offsets, batch.numels)])
-    bad = (rel_err(errors, ref) > 1e-4) & (np.abs(errors - ref) > 1e-6 * xnorm)
+    bad = (rel_err(errors, ref) > 1e-4) & ~((ref < 1e-8 * xnorm) & (np.abs(errors - ref) <= 1e-6 * xnorm))
     assert not bad.any(), np.argwhere(bad)[:5]
     _solve_both(h, errors, sizes, default)
     h.close()
