@@ -6,22 +6,32 @@ One "step" = one pass of the whole path over one batch of synthetic gradients:
     -> lgreco_compress (chosen per-layer setting, error feedback updated),
 by default through lgreco_profile_solve_compress, which is those calls in one (--calls two / four
 go through the separate entry points; same kernels, same results).
-Inputs are resident in HBM before the timed region.  Every step works on its own copy of the
-error-feedback buffer, so all steps do identical work and nothing is restored inside the
-timed region.
+Inputs are resident in HBM before the timed region.  The data MOVES from step to step as in a
+training loop: the steps rotate over --grad-buffers independent draws of the workload (same
+per-layer scales, fresh values and error feedback, each scaled by 1, 1.03, 0.97, ...), so the Top-K
+thresholds a call remembers from the previous one are never exactly right.  Every step works on
+its own copy of the error-feedback buffer, so nothing is restored inside the timed region.
 
 Prints ONE JSON line (metric = gradient GB/s = 4 * N bytes / step time), with
-  "roofline"     achieved algorithmic GB/s of the dominant kernel, timed with HIP events on the
-                 launch stream inside the timed region (the kernels of every --time-every-th step
-                 carry the events; the library sums them, the loop never stops to read them),
-                 against the 8 TB/s HBM peak;
-  "cpu_baseline" the CPU oracle timed on a bounded sample of the same workload.
+  "roofline"        achieved algorithmic GB/s of the dominant kernel, timed with HIP events on the
+                    launch stream inside the timed region (the kernels of every --time-every-th step
+                    carry the events; the library sums them, the loop never stops to read them),
+                    against the 8 TB/s HBM peak;
+  "phases_gpu_ms"   GPU time of the profile, solve and compress phases (events around everything a
+                    phase queues: main kernels, the Top-K chains, list building, the DP);
+  "roofline_phase"  algorithmic bytes of a phase (and of the whole step) / its time / 8 TB/s;
+  "cold"            the same loop with reuse_thresholds = 0 (every call samples the data first);
+  "other_workloads" the smaller workloads of BASELINE.json, same measurement, a few ms each;
+  "cpu_baseline"    the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
+import gc
 import json
 import os
+import re
 import sys
 import time
 
@@ -32,19 +42,28 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
+DEFAULT_WORKLOAD = "c4_gpt2_medium_mixed"
+OTHER_WORKLOADS = ("c1_resnet18_quant", "c2_resnet50_topk", "c3_transformer_lm_lowrank")
+DRIFT = (1.0, 1.03, 0.97, 1.015, 0.985)      # scale of gradient buffer v (and of its error feedback)
 
-# HBM bytes per launch (read + write) of the dominant kernels, from the rocprofv3 FETCH_SIZE /
-# WRITE_SIZE runs summarised under profiles/<workload>_kernels_hbm.md (FETCH_SIZE x 2.0 and
-# WRITE_SIZE x 1.0, both calibrated on a copy of known size).  Counters cannot be read from inside
-# this process, so the figures are carried here and apply to the default synthetic input only.
-MEASURED_TRAFFIC_BYTES = {
-    "c4_gpt2_medium_mixed": {"compress/topk_collect": 2186.3e6 + 1130.5e6,
-                             "profile/quant_profile_topk_collect": 2983.2e6 + 200.3e6,
-                             "compress/quant_compress": 656.2e6 + 382.1e6},
-    "c3_transformer_lm_lowrank": {"compress/lowrank_ef": 656.6e6 + 268.5e6},
-    "c2_resnet50_topk": {"compress/topk_collect": 205.3e6 + 106.7e6, "profile/topk_collect": 205.2e6 + 17.2e6},
-    "c1_resnet18_quant": {"profile/quant_profile": 110.3e6, "compress/quant_compress": 93.9e6 + 52.1e6},
-}
+
+def measured_traffic(workload: str) -> dict:
+    """HBM bytes per launch (read + write) per timed section, from the rocprofv3 FETCH_SIZE /
+    WRITE_SIZE summary under profiles/ (counters cannot be read from inside this process).  The
+    summary's table carries the bench section of every kernel in its last column."""
+    path = os.path.join(ROOT, "profiles", workload + "_kernels_hbm.md")
+    out = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 9 or not re.match(r"^(profile|compress)/", cells[-1]):
+            continue
+        try:
+            out[cells[-1]] = (float(cells[-3]) + float(cells[-2])) * 1e6
+        except ValueError:
+            pass
+    return out
 
 
 def parse_args():
@@ -57,12 +76,17 @@ def parse_args():
                          "compression kernels leaves the GPU idle for some tens of microseconds)")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c4_gpt2_medium_mixed")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--grad-buffers", type=int, default=3,
+                    help="independent draws of the workload the steps rotate over (1: the same data every step)")
     ap.add_argument("--power-iters", type=int, default=1,
                     help="power-iteration steps of the low-rank family (the configs use 1)")
     ap.add_argument("--sample-every-call", action="store_true",
-                    help="Top-K: sample the data in every call instead of starting from the previous "
-                         "call's thresholds (reuse_thresholds = 0)")
+                    help="Top-K: the main loop itself runs with reuse_thresholds = 0 (the default run reports "
+                         "that case under \"cold\")")
+    ap.add_argument("--no-cold", action="store_true", help="leave out the reuse_thresholds = 0 loop")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="leave out the smaller workloads (they run only next to the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave out the HIP-event brackets around kernel sections (no roofline in the output)")
@@ -71,7 +95,7 @@ def parse_args():
                          "stream idle on either side: ~45 us per step on the largest workload when every step is timed)")
     ap.add_argument("--detail", action="store_true",
                     help="bracket every kernel section, not only the main kernels (costs ~3 %% of the step)")
-    ap.add_argument("--cpu-sample-elems", type=int, default=30_000_000)
+    ap.add_argument("--cpu-sample-elems", type=int, default=66_000_000)
     return ap.parse_args()
 
 
@@ -104,108 +128,101 @@ def cpu_baseline(w, sample_tensors, power_iters=1):
                                "elems": n, "total_s": t3 - t0}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def measure(wname, args, steps, warmup, with_cold, with_decompress):
+    """The timed loop on one workload.  Returns (result dict, context for the CPU baseline)."""
     import torch
     from paper_2210_17357_amd import binding as B
     from paper_2210_17357_amd import workloads as W
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(3)
-    w = W.workload(args.workload)
+    w = W.workload(wname)
     cands = list(w.candidates)
     threads = min(16, os.cpu_count() or 1)
+    n_buf = max(1, min(args.grad_buffers, len(DRIFT)))
+    dev = torch.device("cuda:0")
     t_gen = time.perf_counter()
-    batch = W.generate(w, threads=threads)
+    batch = None
+    g_list, ef0_list = [], []
+    for v in range(n_buf):
+        b = W.generate(dataclasses.replace(w, variant=v), threads=threads)
+        if v == 0:
+            batch = b
+        g_list.append(torch.from_numpy(b.grads).to(dev).mul_(DRIFT[v]))
+        ef0_list.append(torch.from_numpy(b.ef).to(dev).mul_(DRIFT[v]) if b.ef is not None else None)
+        if v > 0:
+            del b
     t_gen = time.perf_counter() - t_gen
     N = int(batch.numels.sum())
     L = len(batch.numels)
     layers = B.layer_table(batch.offsets, batch.numels, batch.rows, batch.cols)
     ctab = B.cand_table(cands)
-    dev = torch.device("cuda:0")
-    g = torch.from_numpy(batch.grads).to(dev)
     has_ef = batch.ef is not None
-    ef0 = torch.from_numpy(batch.ef).to(dev) if has_ef else torch.zeros_like(g)
     q0 = torch.from_numpy(batch.q0).to(dev) if batch.q0 is not None else None
-    n_runs = args.steps + args.warmup
-    ef_pool = [ef0.clone() for _ in range(n_runs)]
-    q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
-    h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
-                 seed=w.seed, r_max=w.r_max, power_iters=args.power_iters,
-                 reuse_thresholds=not args.sample_every_call)
+    n_runs = steps + warmup
+    zeros = None if has_ef else torch.zeros_like(g_list[0])
+
+    def fresh_ef(i):
+        return ef0_list[i % n_buf].clone() if has_ef else zeros.clone()
     # The one-call form hands one error-feedback buffer to profile and compression; a workload whose
     # profile runs without one (NULL, half the read traffic) keeps the two-call form.
     calls = "two" if (args.calls == "one" and not has_ef) else args.calls
     level = 0 if args.no_kernel_timing else (2 if args.detail else 1)
-    h.set_timing(level)
-    h.set_timing_stride(max(1, args.time_every))
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
-
-    kern = {}          # name -> [total ms, calls]
-    phase = {"profile": 0.0, "solve": 0.0, "compress": 0.0}
-    last = {}
-
     stream = torch.cuda.current_stream().cuda_stream      # the stream every call of the run is given
+    has_topk = any(f == W.TOPK for f, _ in cands)
 
-    timing = not args.no_kernel_timing
+    def loop(reuse, timing_level):
+        """warm-up + timed steps on a handle of its own; returns (elapsed s, kernel totals, last results)."""
+        h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
+                     seed=w.seed, r_max=w.r_max, power_iters=args.power_iters, reuse_thresholds=reuse)
+        h.set_timing(timing_level)
+        h.set_timing_stride(max(1, args.time_every))
+        ef_pool = [fresh_ef(i) for i in range(n_runs)]
+        q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
+        last = {}
 
-    def step(i, record):
-        ef = ef_pool[i]
-        t0 = time.perf_counter()
-        if calls == "one":
-            # the whole path as one call: nothing runs in the caller between the solver's result
-            # and the compression kernels
-            st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
-                g, ef, layers, ctab, w.default, w.n_bins, payload, q_pool[i], stream=stream)
-            t1 = t2 = t3 = time.perf_counter()
-        else:
-            if calls == "four":
-                errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True, stream=stream)
-                t1 = time.perf_counter()
-                e_max = B.emax(errors, w.default)
-                st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
+        def step(i):
+            g, ef = g_list[i % n_buf], ef_pool[i]
+            if calls == "one":
+                st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
+                    g, ef, layers, ctab, w.default, w.n_bins, payload, q_pool[i], stream=stream)
             else:
-                # profile, E_max and solve as one call: no host round trip between their kernels
-                st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
-                    g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
-                t1 = time.perf_counter()
-            t2 = time.perf_counter()
-            offsets = B.payload_layout(layers, ctab, choice, w.bucket)
-            h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
-            t3 = time.perf_counter()
-        if record:
-            # host clocks: compress only queues its kernels, their GPU time falls into the wait of
-            # the next step's profile call (or the final synchronize); with --calls two "profile"
-            # covers profile + solve, with --calls one everything
-            phase["profile"] += t1 - t0
-            phase["solve"] += t2 - t1
-            phase["compress"] += t3 - t2
-        last.update(errors=errors, sizes=sizes, choice=choice, e_max=e_max, tsize=tsize, terr=terr, st=st)
+                if calls == "four":
+                    errors, sizes = h.profile(g, ef if has_ef else None, layers, ctab, q0, want_sizes=True,
+                                              stream=stream)
+                    e_max = B.emax(errors, w.default)
+                    st, choice, tsize, terr = h.solve(errors, sizes, e_max, w.n_bins, stream=stream)
+                else:
+                    st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(
+                        g, ef if has_ef else None, layers, ctab, w.default, w.n_bins, q0, stream=stream)
+                offsets = B.payload_layout(layers, ctab, choice, w.bucket)
+                h.compress(g, ef, layers, ctab, choice, payload, offsets, q_pool[i], stream=stream)
+            last.update(errors=errors, sizes=sizes, choice=choice, e_max=e_max, tsize=tsize, terr=terr, st=st,
+                        buffer=i % n_buf)
 
-    for i in range(args.warmup):
-        step(i, False)
-    torch.cuda.synchronize()
-    h.set_timing(level)          # clears the library's per-section totals: the warm-up does not count
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, True)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    # Kernel times: the library keeps the events of every call (the main kernels' events ride on
-    # the launches themselves) and sums them per section while it waits for the GPU anyway; the
-    # loop above never asks for them, the totals over the timed steps are read here.
-    if timing:
-        for prefix, call in (("profile/", B.CALL_PROFILE), ("solve/", B.CALL_SOLVE), ("compress/", B.CALL_COMPRESS)):
-            for name, total_ms, cnt in h.get_timing_totals(call):
-                kern[prefix + name] = [total_ms, cnt]
-    ms_per_step = elapsed * 1e3 / args.steps
-    value = 4.0 * N / (elapsed / args.steps) / 1e9
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        h.set_timing(timing_level)   # clears the library's per-section totals: the warm-up does not count
+        t_start = time.perf_counter()
+        for i in range(steps):
+            step(warmup + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        # Kernel times: the library keeps the events of every timed call and sums them per section
+        # while it waits for the GPU anyway; the loop above never asks for them.
+        kern = {}
+        if timing_level:
+            for prefix, call in (("profile/", B.CALL_PROFILE), ("solve/", B.CALL_SOLVE),
+                                 ("compress/", B.CALL_COMPRESS)):
+                for name, total_ms, cnt in h.get_timing_totals(call):
+                    kern[prefix + name] = [total_ms, cnt]
+        del ef_pool, q_pool
+        return h, elapsed, kern, last
+
+    h, elapsed, kern, last = loop(not args.sample_every_call, level)
+    ms_per_step = elapsed * 1e3 / steps
+    value = 4.0 * N / (elapsed / steps) / 1e9
 
     choice = last["choice"]
     fam = np.array([cands[c][0] for c in choice])
@@ -213,10 +230,12 @@ def main():
     numels = batch.numels.astype(np.float64)
     nq = float(numels[fam == W.QUANT].sum())
     ntk = float(numels[fam == W.TOPK].sum())
+    nlr = float(numels[fam == W.LOWRANK].sum())
     mean_bits = float((numels * par)[fam == W.QUANT].sum() / nq) if nq else 0.0
-    mean_dens = float((numels * par)[fam == W.TOPK].sum() / ntk) if ntk else 0.0
-    # algorithmic bytes per element and elements covered per launch, per timed section:
-    # streaming reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g and e and writes e
+    chosen_bytes = last["sizes"][np.arange(L), choice].astype(np.float64)
+    # algorithmic bytes per element and elements covered per launch, per timed section: streaming
+    # reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g
+    # and e and writes e
     rd = 8.0 if has_ef else 4.0
     algo, elems = {}, {}
     for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
@@ -224,16 +243,17 @@ def main():
     algo["compress/quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
     elems["compress/quant_compress"] = nq
     algo["compress/topk_collect"], elems["compress/topk_collect"] = 12.0, ntk
-    nlr = float(numels[fam == W.LOWRANK].sum())
     algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = 12.0, nlr
-    # dense contractions of the low-rank path: flops per launch (64 columns are computed per layer)
+    # dense contractions of the low-rank path: flops per launch
     flops = {}
+    lowrank = any(f == W.LOWRANK for f, _ in cands)
     mn2d = float(sum(int(r) * int(c) for r, c in zip(batch.rows, batch.cols)))
-    if any(f == W.LOWRANK for f, _ in cands):
+    if lowrank:
         for k in ("lowrank_gemm_p", "lowrank_gemm_q"):
-            flops["profile/" + k] = 2.0 * mn2d * 64
-            flops["compress/" + k] = 2.0 * float(sum(int(r) * int(c) for r, c, f_ in
-                                                     zip(batch.rows, batch.cols, fam) if f_ == W.LOWRANK)) * 64
+            flops["profile/" + k] = 2.0 * mn2d * w.r_max
+            # the compression contracts as many columns as the largest chosen rank rounded up to 32
+            flops["compress/" + k] = 2.0 * float(sum(int(r) * int(c) * p for r, c, f_, p in
+                                                     zip(batch.rows, batch.cols, fam, par) if f_ == W.LOWRANK))
     kernels = {}
     for name, (ms, cnt) in kern.items():
         avg = ms / max(cnt, 1)
@@ -258,25 +278,51 @@ def main():
             ach = timed[dom]["GBps"]
             roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": round(ach / HBM_PEAK_GBS, 4),
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(dom),
+                        "traffic": measured_traffic(w.name).get(dom),
                         "algorithmic_bytes": round(algo[dom] * elems[dom]),
                         "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
+
+    # per phase: GPU time between the first and the last thing the phase queues, and what the phase
+    # must move (profile: one read of g and e for every candidate; compress: read g, e, write e and
+    # the payload; low rank: the matrix twice for the factors, read and write for the error feedback)
+    phase_ms = {}
+    for key, name in (("profile", "profile/phase_profile"), ("solve", "solve/dp_solve"),
+                      ("compress", "compress/phase_compress")):
+        if name in kern and kern[name][1] > 0:
+            phase_ms[key] = kern[name][0] / kern[name][1]
+    profile_bytes = rd * N * (2.0 * args.power_iters if lowrank else 1.0)
+    compress_bytes = (float(((12.0 * numels + chosen_bytes)[fam != W.LOWRANK]).sum())
+                      + float(((12.0 + 8.0 * args.power_iters) * numels + chosen_bytes)[fam == W.LOWRANK].sum()))
+    roofline_phase = {}
+    for key, nbytes in (("profile", profile_bytes), ("compress", compress_bytes)):
+        if key in phase_ms and phase_ms[key] > 0:
+            gbps = nbytes / (phase_ms[key] * 1e-3) / 1e9
+            roofline_phase[key] = {"algorithmic_bytes": round(nbytes), "ms": round(phase_ms[key], 4),
+                                   "GBps": round(gbps, 1), "frac": round(gbps / HBM_PEAK_GBS, 4)}
+    step_gbps = (profile_bytes + compress_bytes) / (ms_per_step * 1e-3) / 1e9
+    roofline_phase["step"] = {"algorithmic_bytes": round(profile_bytes + compress_bytes), "ms": round(ms_per_step, 4),
+                              "GBps": round(step_gbps, 1), "frac": round(step_gbps / HBM_PEAK_GBS, 4)}
+    if lowrank:
+        # the contraction-bound part: flops of the factor GEMMs over the time of the whole phase
+        for key, fl in (("profile", 4.0 * mn2d * w.r_max * args.power_iters),
+                        ("compress", sum(flops.get("compress/" + k, 0.0) for k in ("lowrank_gemm_p", "lowrank_gemm_q"))
+                         * args.power_iters + flops.get("compress/lowrank_gemm_p", 0.0))):
+            if key in phase_ms and phase_ms[key] > 0:
+                tf = fl / (phase_ms[key] * 1e-3) / 1e12
+                roofline_phase[key].update(flops=round(fl), TFLOPs=round(tf, 2),
+                                           frac_mfma=round(tf / FP32_MFMA_PEAK_TFLOPS, 4))
+
     out = {
-        "metric": "profile+solve+compress gradient GB/s at 1 MI355X",
-        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "value": round(value, 2), "unit": "GB/s", "ms_per_step": round(ms_per_step, 4),
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
-                   "reuse_thresholds": not args.sample_every_call,
-                   "calls_per_step": calls,
+                   "reuse_thresholds": not args.sample_every_call, "grad_buffers": n_buf,
+                   "calls_per_step": calls, "steps": steps, "warmup": warmup,
                    "kernels_timed_every_n_steps": None if args.no_kernel_timing else max(1, args.time_every),
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,
-        # host wall clock per call; compress returns with its kernels queued, so most of its GPU
-        # time shows up under the next step's profile
-        "phases_ms": ({"profile_solve_compress": round(phase["profile"] * 1e3 / args.steps, 4)} if calls == "one"
-                      else {k: round(v * 1e3 / args.steps, 4) for k, v in phase.items()}),
+        "phases_gpu_ms": {k: round(v, 4) for k, v in phase_ms.items()},
+        "roofline_phase": roofline_phase,
         "kernels": kernels,
         "result": {"status": int(last["st"]), "total_size_bytes": int(last["tsize"]),
                    "ratio_vs_fp32": round(4.0 * N / max(int(last["tsize"]), 1), 3),
@@ -287,30 +333,84 @@ def main():
                    "layers_lowrank": int((fam == W.LOWRANK).sum())},
     }
 
-    # receiver side (not part of the step): the last step's payloads back to a dense buffer
-    out_buf = torch.empty_like(g)
-    offsets = B.payload_layout(layers, ctab, choice, w.bucket)
-    h.set_timing(0)
-    for _ in range(2):
-        h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=True)
-    torch.cuda.synchronize()
-    dec_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    out["decompress"] = {"ms": round(dec_ms, 4), "GBps_dense_output": round(4.0 * N / dec_ms / 1e6, 1),
-                         "mode": "accumulate", "payload_bytes": int(last["tsize"])}
+    errors0 = None
+    if with_decompress:
+        # (for the parity figure of the CPU baseline: the profile of buffer 0, the oracle's input)
+        errors0, _ = h.profile(g_list[0], ef0_list[0], layers, ctab, q0, want_sizes=False, stream=stream)
+        # receiver side (not part of the step): the last step's payloads back to a dense buffer
+        out_buf = torch.empty_like(g_list[0])
+        offsets = B.payload_layout(layers, ctab, choice, w.bucket)
+        h.set_timing(0)
+        for _ in range(2):
+            h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            h.decompress(payload, offsets, layers, ctab, choice, out_buf, accumulate=True)
+        torch.cuda.synchronize()
+        dec_ms = (time.perf_counter() - t0) * 1e3 / steps
+        out["decompress"] = {"ms": round(dec_ms, 4), "GBps_dense_output": round(4.0 * N / dec_ms / 1e6, 1),
+                             "mode": "accumulate", "payload_bytes": int(last["tsize"])}
+        del out_buf
+    h.close()
+
+    if with_cold and has_topk and not args.sample_every_call:
+        # the same loop when no call may start from the previous call's thresholds
+        hc, el_c, _, _ = loop(False, 0)
+        hc.close()
+        out["cold"] = {"reuse_thresholds": False, "ms_per_step": round(el_c * 1e3 / steps, 4),
+                       "value": round(4.0 * N / (el_c / steps) / 1e9, 2), "unit": "GB/s"}
+    ctx = {"w": w, "batch": batch, "last": last, "errors0": errors0}
+    del g_list, ef0_list, payload
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out, ctx
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    res, ctx = measure(args.workload, args, args.steps, args.warmup, with_cold=not args.no_cold,
+                       with_decompress=True)
+    w, batch, last = ctx["w"], ctx["batch"], ctx["last"]
+    out = {
+        "metric": "profile+solve+compress gradient GB/s at 1 MI355X",
+        "value": res["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+    }
+    for k in ("config", "roofline", "phases_gpu_ms", "roofline_phase", "cold", "kernels", "result", "decompress"):
+        if k in res:
+            out[k] = res[k]
+
+    if args.workload == DEFAULT_WORKLOAD and not args.no_other_workloads:
+        # the other workloads of the baseline's list (the smallest one is a parity case of a few
+        # microseconds): same loop, milliseconds each
+        others = {}
+        for name in OTHER_WORKLOADS:
+            r, _ = measure(name, args, max(args.steps, 20), max(args.warmup, 3), with_cold=not args.no_cold,
+                           with_decompress=False)
+            others[name] = {k: r[k] for k in ("value", "unit", "ms_per_step", "roofline", "phases_gpu_ms",
+                                              "roofline_phase", "cold", "result") if k in r}
+            others[name]["elements"] = r["config"]["elements"]
+            others[name]["kernels"] = {k: v for k, v in r["kernels"].items() if "GBps" in v or "TFLOPs" in v}
+        out["other_workloads"] = others
 
     if not args.no_cpu_baseline:
-        # bounded sample: leading tensors of the workload up to ~cpu-sample-elems elements,
-        # skipping any single tensor larger than the bound
+        # bounded sample: leading tensors of the workload up to ~cpu-sample-elems elements (the
+        # largest tensor first in every workload here, so the sample holds it)
         sample, acc = [], 0
         for t, shape in enumerate(w.shapes):
             n = int(np.prod(shape))
-            if n > args.cpu_sample_elems:
-                continue
-            if acc + n > args.cpu_sample_elems:
+            if acc + n > args.cpu_sample_elems and sample:
                 break
             sample.append(t)
             acc += n
@@ -318,14 +418,14 @@ def main():
         out["cpu_baseline"] = {
             "value": round(4.0 * tm["elems"] / tm["total_s"] / 1e9, 4), "unit": "GB/s", "cores": 1,
             "kind": "oracle",
-            "sample": "tensors %d..%d of %s (%d elements): oracle profile %.2fs + solve %.2fs + compress %.2fs; "
-                      "numpy element-wise code, single thread (host has %d cores)"
-                      % (sample[0], sample[-1], w.name, tm["elems"], tm["profile_s"], tm["solve_s"],
-                         tm["compress_s"], os.cpu_count() or 0)}
-        # parity of the GPU profile on the sampled layers (same seeded inputs)
+            "sample": "tensors %d..%d of %s (%d elements, largest tensor %d): oracle profile %.2fs + solve %.2fs + "
+                      "compress %.2fs; numpy element-wise code, single thread (host has %d cores)"
+                      % (sample[0], sample[-1], w.name, tm["elems"], int(sb.numels.max()), tm["profile_s"],
+                         tm["solve_s"], tm["compress_s"], os.cpu_count() or 0)}
+        # parity of the GPU profile on the sampled layers (gradient buffer 0 is the oracle's input)
         idx = [int(np.where(batch.tensor_index == t)[0][0]) for t in sb.tensor_index]
-        if not w.stochastic or idx == list(range(len(idx))):     # the RNG is keyed by layer index
-            g_err = last["errors"][idx]
+        if ctx["errors0"] is not None and (not w.stochastic or idx == list(range(len(idx)))):
+            g_err = ctx["errors0"][idx]
             rel = np.abs(g_err - o_err) / np.maximum(np.abs(o_err), 1e-300)
             out["parity"] = {"layers_checked": len(idx), "max_rel_err_profile": float(rel.max())}
 

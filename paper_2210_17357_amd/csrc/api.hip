@@ -100,6 +100,7 @@ struct EarlyCompress {
     float* d_ef;
     uint8_t* d_payload;
     int64_t capacity;
+    int phase = -1;          // the compress call's phase bracket, opened with that kernel
     bool launched = false;   // the quantization kernel was queued right behind the solver kernel
     bool applied = false;    // ... and ran on layer records the solver kernel wrote from its result
 };
@@ -249,9 +250,11 @@ int upload_layers(lgreco_handle* h, hipStream_t s, bool layers_changed) {
 hipError_t harvest(Timing& tm) {
     if (tm.harvested || tm.n == 0) return hipSuccess;
     tm.harvested = true;
-    // the brackets were recorded on one stream in order: waiting for the last one covers all
-    hipError_t e = hipEventSynchronize(tm.ev[2 * (tm.n - 1) + 1]);
+    // (a phase bracket closes after the sections opened inside it: every stop event is waited for)
+    hipError_t e = hipSuccess;
     for (int i = 0; i < tm.n && e == hipSuccess; ++i) {
+        e = hipEventSynchronize(tm.ev[2 * i + 1]);
+        if (e != hipSuccess) break;
         e = hipEventElapsedTime(&tm.ms[i], tm.ev[2 * i], tm.ev[2 * i + 1]);
         if (e == hipSuccess) tm.add_total(tm.name[i], (double)tm.ms[i]);
     }
@@ -581,6 +584,12 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
     begin_call(h, s, LGRECO_CALL_PROFILE);
     int st = prepare_layers(h, layers, L);
     if (st != LGRECO_OK) return st;
+    // everything the profile queues, chains between the kernels included
+    struct Phase {
+        Timing* t;
+        int idx;
+        ~Phase() { t->close_phase(idx); }
+    } phase{h->tm, -1};
 
     QuantParams qp{};
     // Top-K candidates, largest density first: one pass resolves kMaxTopk of them, the rest follow
@@ -613,6 +622,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
     }
     st = upload_layers(h, s, false);
     if (st != LGRECO_OK) return st;
+    phase.idx = h->tm->open_phase("phase_profile");
 
     const int n_tiles = (int)h->ht.size();
     const bool ptr_aligned = ((uintptr_t)d_grads % 16 == 0) && (!d_ef || (uintptr_t)d_ef % 16 == 0);
@@ -904,6 +914,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         Timing* const solve_tm = h->tm;
         begin_call(h, s, LGRECO_CALL_COMPRESS);
         h->hl_uploaded.clear();
+        ec->phase = h->tm->open_phase("phase_compress");
         {
             Section sec(h->tm, "quant_compress", true);
             HIPCHK(launch_quant_compress(d_grads, ec->d_ef, h->d_layers, h->d_tiles, (int)h->ht.size(), ec->d_payload,
@@ -1052,6 +1063,7 @@ static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, 
     st = upload_layers(h, s, true);
     if (st != LGRECO_OK) return st;
     const int n_tiles = (int)h->ht.size();
+    const int phase = early ? ec->phase : h->tm->open_phase("phase_compress");
     if (any[LGRECO_QUANT] && !quant_done) {
         Section sec(h->tm, "quant_compress", true);
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
@@ -1065,6 +1077,7 @@ static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, 
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,
                                 d_payload, h->tm, s));
     }
+    h->tm->close_phase(phase);
     // No host output: the call returns with its kernels queued.  Payload, error feedback and q are
     // ready in stream order; the caller's next call on this stream (or its own wait) sees them.
     return LGRECO_OK;

@@ -39,6 +39,19 @@ struct Timing {
     double total_ms[kMaxNames]{};
     int64_t total_count[kMaxNames]{};
     int n_totals = 0;
+    // A phase bracket: two recorded events around everything a call (or a part of it) queues,
+    // kept at level 1 like the main kernels.  Opened and closed by hand because one phase can
+    // span two functions (the compression whose first kernel is queued behind the solver).
+    int open_phase(const char* nm) {
+        if (!(active && level >= 1 && ready && n < kMaxSections)) return -1;
+        const int idx = n++;
+        name[idx] = nm;
+        (void)hipEventRecord(ev[2 * idx], stream);
+        return idx;
+    }
+    void close_phase(int idx) {
+        if (idx >= 0) (void)hipEventRecord(ev[2 * idx + 1], stream);
+    }
     void add_total(const char* nm, double v) {
         int i = 0;
         while (i < n_totals && total_name[i] != nm && std::strcmp(total_name[i], nm) != 0) ++i;

@@ -15,7 +15,8 @@ Recipe (every tensor t of a workload with seed s has its own stream):
     values  = distribution(rng_t) * scale_t        (drawn second, fp64 -> fp32)
     ef      = ef_distribution(rng_t)               (drawn third, if the workload has one)
 Per-tensor streams let a test generate one layer of the 355 M-element workload
-without drawing the others.
+without drawing the others.  `variant` v > 0 stands for a later step of the same run: scale_t as
+above, values and ef from Generator(PCG64(SeedSequence([s, t, v]))).
 """
 from __future__ import annotations
 
@@ -112,6 +113,7 @@ class Workload:
     only_2d: bool = False                          # 1-D tensors are sent raw, not profiled
     q_seed: int = 1
     r_max: int = 64
+    variant: int = 0                               # another draw of the same model: see draw_tensor
 
 
 def _cands(family: int, params: Sequence[float]) -> Tuple[Tuple[int, float], ...]:
@@ -168,6 +170,10 @@ def draw_tensor(w: Workload, t: int) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     n = int(np.prod(shape))
     rng = tensor_rng(w.seed, t)
     scale = 10.0 ** rng.uniform(*w.scale_exp)
+    if w.variant:
+        # a later step of the same training run: every tensor keeps its scale, values and error
+        # feedback are a fresh draw from a stream of their own (variant 0 is the recipe above)
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(w.seed), int(t), int(w.variant)])))
     if w.values == "student_t3":
         v = rng.standard_t(3, n)
     elif w.values == "laplace":

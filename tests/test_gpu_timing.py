@@ -73,9 +73,14 @@ def test_brackets_leave_results_alone_and_fit_the_host_clock(kind):
                 for n, ms in prof + solve + comp:
                     assert np.isfinite(ms) and ms >= 0.0, (n, ms)
                 # sections of one call do not overlap: their sum fits in the call's wall clock
-                main = [ms for n, ms in prof + solve if "." not in n]
-                assert sum(main) <= (t1 - t0) * 1e3 + 0.05, (level, main, t1 - t0)
-                assert sum(ms for _, ms in comp) <= (t2 - t1) * 1e3 + 0.05, (level, comp, t2 - t1)
+                # (a phase bracket spans the sections of its call; the dotted names are parts of dp_solve)
+                def inner(secs):
+                    return [ms for n, ms in secs if "." not in n and not n.startswith("phase_")]
+                assert sum(inner(prof + solve)) <= (t1 - t0) * 1e3 + 0.05, (level, prof, solve, t1 - t0)
+                assert sum(inner(comp)) <= (t2 - t1) * 1e3 + 0.05, (level, comp, t2 - t1)
+                phase_p, phase_c = dict(prof)["phase_profile"], dict(comp)["phase_compress"]
+                assert sum(inner(prof)) <= phase_p + 0.02 and phase_p <= (t1 - t0) * 1e3 + 0.05, (prof, t1 - t0)
+                assert sum(inner(comp)) <= phase_c + 0.02 and phase_c <= (t2 - t1) * 1e3 + 0.05, (comp, t2 - t1)
                 # the main kernels do real work: none of them reads as zero
                 assert all(ms > 0.0 for n, ms in prof + comp if n in
                            ("quant_profile_topk_collect", "quant_compress", "topk_collect", "lowrank_gemm_p",
