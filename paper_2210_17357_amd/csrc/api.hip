@@ -74,10 +74,14 @@ struct lgreco_handle {
     // parameter a choice stands for plus the family per candidate (pinned staging copy, uploaded
     // when it changes)
     int32_t* d_build_dev = nullptr;      // [2 x max_layers] sweep_layer | fixed_choice
-    int32_t* h_apply = nullptr;          // pinned [max_layers x max_cands | max_cands] iparam | family
+    int32_t* h_apply = nullptr;          // pinned [max_layers x max_cands | max_cands | max_cands] iparam | family | Top-K slot
     int32_t* d_apply = nullptr;
     size_t apply_count = 0;              // int32 entries of h_apply / d_apply in use
     std::vector<DevLayer> hl_uploaded;   // what d_layers holds
+    // Top-K candidates of the last profile call: how many, and the candidate column of each of the
+    // selection records it left on the device (valid while they number at most one group)
+    int last_ntk = 0;
+    int last_tk_col[kMaxTopk] = {};
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
     // One set of timing events per kind of call (LGRECO_CALL_*): a call that returns before its
@@ -101,6 +105,7 @@ struct EarlyCompress {
     uint8_t* d_payload;
     int64_t capacity;
     int phase = -1;          // the compress call's phase bracket, opened with that kernel
+    bool topk_known = false; // the Top-K layers' kernels were queued too (see topk_compress_known)
     bool launched = false;   // the quantization kernel was queued right behind the solver kernel
     bool applied = false;    // ... and ran on layer records the solver kernel wrote from its result
 };
@@ -404,8 +409,8 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     HIPCHK_C(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->d_build_host), h->h_build, 0));
     HIPCHK_C(hipMalloc(&h->d_nsweep, sizeof(int32_t) * 2));
     HIPCHK_C(hipMalloc(&h->d_build_dev, sizeof(int32_t) * 2 * (size_t)max_layers));
-    HIPCHK_C(hipHostMalloc(&h->h_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + max_cands), hipHostMallocDefault));
-    HIPCHK_C(hipMalloc(&h->d_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + max_cands)));
+    HIPCHK_C(hipHostMalloc(&h->h_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + 2 * max_cands), hipHostMallocDefault));
+    HIPCHK_C(hipMalloc(&h->d_apply, sizeof(int32_t) * ((size_t)max_layers * max_cands + 2 * max_cands)));
     HIPCHK_C(hipHostMalloc(&h->h_bins, sizeof(int32_t) * lp, hipHostMallocDefault));
     for (Timing& t : h->tms) {
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&t.ev[i]));
@@ -632,6 +637,8 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
                      [](const std::pair<double, int>& a, const std::pair<double, int>& b) { return a.first > b.first; });
     const int ntk_all = (int)tk_all.size();
     const int ntk = std::min(ntk_all, (int)kMaxTopk);          // size of the first group
+    h->last_ntk = ntk_all;
+    for (int j = 0; j < ntk; ++j) h->last_tk_col[j] = tk_all[j].second;
     int tk_col[kMaxTopk];
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
     auto load_group = [&](int first) {                          // fills ks / tk_col, returns the group's size
@@ -885,13 +892,19 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     if (ec) {
         // what every (layer, candidate) means to the compression kernels, as lgreco_compress works
         // it out for a choice: the solver kernel picks the chosen column
-        const size_t n_apply = (size_t)L * P + P;
+        const size_t n_apply = (size_t)L * P + 2 * (size_t)P;
         std::vector<int32_t> tab(n_apply);
         for (int l = 0; l < L; ++l)
             for (int c = 0; c < P; ++c)
                 tab[(size_t)l * P + c] = cands[c].family == LGRECO_TOPK ? (int32_t)topk_k(layers[l].numel, cands[c].param)
                                                                         : (int32_t)cands[c].param;
         for (int c = 0; c < P; ++c) tab[(size_t)L * P + c] = cands[c].family;
+        // where the profile left the selection record of every Top-K candidate (one group only)
+        const bool topk_known = h->last_ntk >= 1 && h->last_ntk <= (int)kMaxTopk;
+        for (int c = 0; c < P; ++c) tab[(size_t)L * P + P + c] = -1;
+        if (topk_known)
+            for (int j = 0; j < h->last_ntk; ++j) tab[(size_t)L * P + P + h->last_tk_col[j]] = j;
+        ec->topk_known = topk_known;
         if (h->apply_count != n_apply || std::memcmp(h->h_apply, tab.data(), sizeof(int32_t) * n_apply) != 0) {
             std::memcpy(h->h_apply, tab.data(), sizeof(int32_t) * n_apply);
             h->apply_count = n_apply;
@@ -899,7 +912,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
             HIPCHK(hipStreamSynchronize(s));      // h_apply may be rewritten by the next call
         }
         dp.apply = DpApply{h->d_layers, h->d_build_dev, h->d_build_dev + L, h->d_sizes, h->d_apply,
-                           h->d_apply + (size_t)L * P, L, P, ec->capacity};
+                           h->d_apply + (size_t)L * P, h->d_apply + (size_t)L * P + P, L, P, ec->capacity};
     }
     {
         Section sec(h->tm, "dp_solve", true);
@@ -921,6 +934,12 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
                                          h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
         }
         ec->launched = true;
+        if (ec->topk_known) {
+            // ... and the Top-K layers' part, from the selection records the profile left for
+            // this very data: the chosen density's record is picked on the device
+            HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
+                                       ec->d_payload, h->tm, s));
+        }
         // the compress call stays open until lgreco_compress's part has queued the rest: nobody
         // reads its events out before (that would wait for the kernel just queued)
         h->tm->harvested = true;
@@ -1069,7 +1088,7 @@ static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, 
         HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
                                      h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
     }
-    if (any[LGRECO_TOPK]) {
+    if (any[LGRECO_TOPK] && !(quant_done && ec->topk_known)) {
         HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
                              h->tile_elems, d_payload, h->tm, s));
     }

@@ -47,7 +47,9 @@ struct DevLayer {
     int32_t tile_end;
     int32_t family;       // compress: family of the chosen candidate
     int32_t iparam;       // compress: bits / k / rank of the chosen candidate
-    int32_t pad0, pad1;
+    int32_t slot;         // compress right behind a profile: index of the chosen density in the profile's
+                          // Top-K selection records (written by the solver kernel; -1 otherwise)
+    int32_t pad1;
 };
 
 // ------------------------------------------------------------------ cross-lane helpers

@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
         const int wave = tid >> 6;
         bool ok = traced && A.L <= kDpThreads;          // workgroup-uniform
         int c = 0;
-        int32_t fam = 0, ipar = 0;
+        int32_t fam = 0, ipar = 0, tslot = -1;
         int64_t off = 0;
         if (ok) {
             const int32_t swept_cand = tid < L ? p.entries[(size_t)tid * bstride + s_pick[tid]].cand : 0;
@@ -305,6 +305,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             // the three table reads of the chosen column go out together
             const int64_t raw = mine ? A.sizes[(size_t)tid * A.P + cc] : 0;
             fam = mine ? A.family[cc] : 0;
+            tslot = mine ? A.topk_slot[cc] : -1;
             ipar = mine ? A.iparam[(size_t)tid * A.P + cc] : 0;
             const int64_t sz = (mine && !bad) ? (raw + 15) / 16 * 16 : 0;
             int64_t inc = sz;
@@ -328,6 +329,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 A.layers[tid].payload = off;
                 A.layers[tid].family = fam;
                 A.layers[tid].iparam = ipar;
+                A.layers[tid].slot = tslot;
             } else {
                 A.layers[tid].family = -1;
             }

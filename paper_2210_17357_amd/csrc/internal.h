@@ -146,6 +146,7 @@ struct DpApply {
     const int64_t* sizes;         // [L x P] bytes
     const int32_t* iparam;        // [L x P] bits / k / rank
     const int32_t* family;        // [P]
+    const int32_t* topk_slot;     // [P] position of a Top-K candidate in the profile's selection records, else -1
     int32_t L, P;
     int64_t capacity;             // bytes the payload buffer holds
 };
@@ -207,6 +208,7 @@ hipError_t launch_dp(const DpParams& p, bool narrow, int max_bin, hipStream_t s,
 struct TopkScratch {
     uint32_t* d_hist = nullptr;       // [2 x max_layers x kHistBins] exact coarse histogram, then the sample's
     void* d_tl = nullptr;             // per-layer selection records
+    uint32_t* d_cnt_known = nullptr;  // [max_layers x 512] sub-bin counts of topk_compress_known
     uint32_t* d_cand = nullptr;       // bit patterns of the candidates, tile i at its own first element
     uint32_t* d_cand_idx = nullptr;   // compress: index within the layer (+ sign bit) of every candidate
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
@@ -269,6 +271,12 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                          uint8_t* payload, Timing* tm, hipStream_t s);
+
+// Top-K layers of a compression queued right behind a profile of the same data and the solver
+// kernel that wrote the layer records (family, k, payload offset, slot of the chosen density in
+// the profile's selection records): nothing here needs the host to know the assignment.
+hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s);
 
 // ---- lowrank.hip
 struct LowrankScratch {

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
     StagedCollector col;
     uint32_t col_start = 0;
     uint32_t* const slice = HIST ? p.cand + p.cand_base[t.layer] + t.pos : nullptr;
-    const uint32_t col_lo = HIST ? p.lo[t.layer] : 0xFFFFFFFFu;
+    const uint32_t col_lo = HIST ? bound_of_key(p.lo[t.layer]) : 0xFFFFFFFFu;
 
     if (t.fast) {
         // division owned by this lane: candidate (lane & 7), unit for lanes 0-7, inv for 8-15

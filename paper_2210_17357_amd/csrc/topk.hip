@@ -54,7 +54,7 @@ constexpr int kRefThreads = 1024;
 constexpr int kBinsA = 1024, kBinsB = 512;
 constexpr int kPickThreads = 512;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
-constexpr uint32_t kHintMargin = 1; // coarse bins between a remembered threshold and the bound derived from it
+constexpr uint32_t kHintMargin = 2; // coarse bins (4.4 % in magnitude each) between a remembered threshold and the bound derived from it
 
 // ------------------------------------------------------------------------ block helpers
 // Suffix sums of a histogram in LDS over the block's first 256 threads: thread t owns the bins
@@ -279,22 +279,37 @@ struct CollectParams {
     TopkTileInfo* tinfo;
     double* base_part;
     int32_t only_flagged;
+    uint32_t* cnt_b;            // KNOWN: [L x kBinsB] last 9 pattern bits inside each layer's boundary sub-bin
 };
 
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
 // collection.  With only_flagged it collects again the layers whose predicted bound was too high.
-template <bool HIST, bool EMIT>
+// KNOWN (compression right behind a profile of the same data): which layers take part and what
+// they keep comes from the layer records (family, slot of the chosen density in the profile's
+// selection records), the bound is the 22-bit prefix the profile resolved the k-th magnitude to
+// (nearly exactly the kept set qualifies), and the elements inside that boundary sub-bin are
+// counted by their last 9 pattern bits (s_hist: kBinsB cells) for the exact threshold.
+template <bool HIST, bool EMIT, bool KNOWN = false>
 __device__ __forceinline__ void collect_tile(const CollectParams& p, const int tile, uint32_t* s_hist, double* s_red) {
+    static_assert(!(HIST && KNOWN), "the coarse histogram is not built when the thresholds are known");
     const Tile t = p.tiles[tile];
-    if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
-    if (p.only_flagged && !p.tl[t.layer].recollect) return;
     const DevLayer L = p.layers[t.layer];
+    uint32_t bound;
+    if (KNOWN) {
+        if (L.family != LGRECO_TOPK || L.slot < 0 || L.slot >= kMaxTopk) return;
+        const TopkSel& S = p.tl[t.layer].sel[L.slot];
+        bound = ((S.tbin << 10) | S.bin_a) << 9;
+    } else {
+        if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
+        if (p.only_flagged && !p.tl[t.layer].recollect) return;
+        bound = bound_of_key(p.lo[t.layer]);
+    }
     const float* gp = p.g + L.offset + t.pos;
     const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
     float* const eo = EMIT ? p.ef_out + L.offset + t.pos : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (HIST) {
-        for (int b = tid; b < kHistBins; b += kThreads) s_hist[b] = 0;
+    if (HIST || KNOWN) {
+        for (int b = tid; b < (KNOWN ? kBinsB : kHistBins); b += kThreads) s_hist[b] = 0;
         __syncthreads();
     }
     const int64_t slice_off = p.cand_base[t.layer] + t.pos;
@@ -306,7 +321,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
         int c0, c1;
         wave_range(t.count / kChunk, wave, &c0, &c1);
         start = (uint32_t)c0 * kChunk;
-        col.init(slice + start, EMIT ? slice_idx + start : nullptr, p.lo[t.layer]);
+        col.init(slice + start, EMIT ? slice_idx + start : nullptr, bound);
         // one 512-element chunk per iteration (uniform trip count): both halves are loaded before
         // either is used, so a lane keeps four 128-bit loads in flight
         for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += kChunk / 4) {
@@ -330,6 +345,13 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
                     atomicAdd(&s_hist[mag_bits(a[h].w) >> kHistShift], 1u);
                 }
                 const float x[4] = {a[h].x, a[h].y, a[h].z, a[h].w};
+                if (KNOWN) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t in = mag_bits(x[q]) - bound;      // below the bound: wraps to a large value
+                        if (in < (uint32_t)kBinsB) atomicAdd(&s_hist[in], 1u);
+                    }
+                }
                 col.take4(x, (uint32_t)(t.pos + 4 * (int64_t)(v + 64 * h)));
             }
         }
@@ -337,7 +359,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
         int b0, b1;
         wave_range((t.count + 63) / 64, wave, &b0, &b1);
         start = (uint32_t)b0 * 64;
-        col.init(slice + start, EMIT ? slice_idx + start : nullptr, p.lo[t.layer]);
+        col.init(slice + start, EMIT ? slice_idx + start : nullptr, bound);
         for (int b = b0; b < b1; ++b) {
             const int i = b * 64 + lane;
             const bool valid = i < t.count;
@@ -345,6 +367,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             if (valid) x = ep ? gp[i] + ep[i] : gp[i];
             if (EMIT && valid) eo[i] = x;
             if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
+            if (KNOWN && valid && mag_bits(x) - bound < (uint32_t)kBinsB) atomicAdd(&s_hist[mag_bits(x) - bound], 1u);
             col.take(x, valid, (uint32_t)(t.pos + i));
         }
     }
@@ -362,6 +385,45 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             const uint32_t c = s_hist[b];
             if (c) atomicAdd(&gh[b], c);
         }
+    }
+    if (KNOWN) {
+        uint32_t* gh = p.cnt_b + (size_t)t.layer * kBinsB;
+        for (int b = tid; b < kBinsB; b += kThreads) {
+            const uint32_t c = s_hist[b];
+            if (c) atomicAdd(&gh[b], c);
+        }
+    }
+}
+
+// Main pass of the compression when the profile's selection records are valid for the same data.
+__global__ __launch_bounds__(kThreads) void topk_collect_known_kernel(CollectParams p) {
+    __shared__ uint32_t s_hist[kBinsB];
+    __shared__ double s_red[kThreads / 64];
+    collect_tile<false, true, true>(p, (int)blockIdx.x, s_hist, s_red);
+}
+
+// One workgroup per layer: the exact threshold pattern and the number of entries equal to it that
+// are kept, from the counts the main pass above left; the counts are cleared for the next call.
+__global__ __launch_bounds__(256) void topk_pick_known_kernel(const DevLayer* __restrict__ layers,
+                                                              TopkLayer* __restrict__ tl,
+                                                              uint32_t* __restrict__ cnt_b) {
+    __shared__ uint32_t s_hist[kBinsB];
+    __shared__ uint32_t s_scan[256];
+    __shared__ uint32_t s_res[2];
+    const int l = blockIdx.x;
+    const DevLayer L = layers[l];
+    if (L.family != LGRECO_TOPK || L.slot < 0 || L.slot >= kMaxTopk) return;
+    TopkSel& S = tl[l].sel[L.slot];
+    for (int b = threadIdx.x; b < kBinsB; b += 256) {
+        s_hist[b] = cnt_b[(size_t)l * kBinsB + b];
+        cnt_b[(size_t)l * kBinsB + b] = 0u;
+    }
+    __syncthreads();
+    const uint32_t need_a = S.need_a, prefix = (S.tbin << 10) | S.bin_a;
+    block_kth_from_top(s_hist, kBinsB, need_a, s_scan, s_res);
+    if (threadIdx.x == 0) {
+        S.thr = (prefix << 9) | s_res[0];
+        S.ties_keep = need_a - s_res[1];
     }
 }
 
@@ -466,7 +528,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
         sT.recollect = used > mn ? 1u : 0u;
         sT.pad = 0;
         lo_out[l] = sT.recollect ? mn : used;
-        // collection bound for the next call of this kind: one coarse bin (4.4 % in magnitude)
+        // collection bound for the next call of this kind: kHintMargin coarse bins (4.4 % in magnitude each)
         // under the lowest threshold found now
         if (hint) hint[l] = mn > kHintMargin ? mn - kHintMargin : 0u;
     }
@@ -893,7 +955,10 @@ __global__ __launch_bounds__(256) void topk_pick_b_kernel(RefineParams p) {
 constexpr int kSliceBatch = 4;
 
 // per (tile, wavefront): entries above the threshold, entries equal to it (from its candidates)
+// KNOWN: the layer records say which layers take part and which selection record holds the threshold.
+template <bool KNOWN>
 __global__ __launch_bounds__(kThreads) void topk_count_kernel(const Tile* __restrict__ tiles, int n_tiles,
+                                                               const DevLayer* __restrict__ layers,
                                                                const TopkLayer* __restrict__ tl,
                                                                const TopkTileInfo* __restrict__ tinfo,
                                                                const uint32_t* __restrict__ cand,
@@ -917,11 +982,21 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(const Tile* __rest
         n[q] = tinfo[ti].cnt[wave];
         start[q] = tinfo[ti].start[wave];
     }
+    int slot[kSliceBatch];
+#pragma unroll
+    for (int q = 0; q < kSliceBatch; ++q) {
+        slot[q] = 0;
+        if (KNOWN) {
+            const DevLayer& L = layers[layer[q]];
+            k[q] = (L.family == LGRECO_TOPK && L.slot >= 0 && L.slot < kMaxTopk) ? 1u : 0u;
+            slot[q] = k[q] ? L.slot : 0;
+        }
+    }
 #pragma unroll
     for (int q = 0; q < kSliceBatch; ++q) {
         const TopkLayer& T = tl[layer[q]];
-        k[q] = T.sel[0].k;
-        thr[q] = T.sel[0].thr;
+        if (!KNOWN) k[q] = T.sel[0].k;
+        thr[q] = T.sel[slot[q]].thr;
         base[q] = T.cand_base;
     }
 #pragma unroll
@@ -1007,6 +1082,7 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long m, uint32_t a
 // Kept values and indices in ascending index order, from the candidates alone (every kept entry
 // is a candidate, and a wavefront's candidates are stored in element order); the error feedback,
 // already written as x everywhere by the collection pass, is zeroed at the kept entries.
+template <bool KNOWN>
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ e,
                                                               const DevLayer* __restrict__ layers,
                                                               const Tile* __restrict__ tiles, int n_tiles,
@@ -1050,16 +1126,18 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
     for (int q = 0; q < kSliceBatch; ++q) {
         const DevLayer& L = layers[layer[q]];
         const TopkLayer& T = tl[layer[q]];
-        const bool active = first + q < n_tiles && L.family == LGRECO_TOPK;
+        const bool active = first + q < n_tiles && L.family == LGRECO_TOPK &&
+                            (!KNOWN || (L.slot >= 0 && L.slot < kMaxTopk));
         const int64_t off = active ? T.cand_base + pos[q] + start[q] : 0;
-        const uint32_t keep_eq = T.sel[0].ties_keep;
+        const TopkSel& Sel = T.sel[(KNOWN && active) ? L.slot : 0];
+        const uint32_t keep_eq = Sel.ties_keep;
         S[q].pats = cand + off;
         S[q].idxs = cand_idx + off;
         S[q].ef = e + L.offset;
         S[q].values = reinterpret_cast<float*>(payload + L.payload);
-        S[q].indices = reinterpret_cast<uint32_t*>(payload + L.payload) + T.sel[0].k;
+        S[q].indices = reinterpret_cast<uint32_t*>(payload + L.payload) + Sel.k;
         S[q].n = active ? S[q].n : 0u;
-        S[q].thr = T.sel[0].thr;
+        S[q].thr = Sel.thr;
         S[q].ties_keep = keep_eq;
         // equal entries: global rank r (in index order) is kept iff r < ties_keep
         S[q].eq_all = before[q].y + cnt[q].y <= keep_eq;
@@ -1119,6 +1197,9 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMemset(t->d_hist, 0, sizeof(uint32_t) * 2 * (size_t)max_layers * kHistBins));
     t->hist_clean = true;
     TK_CHECK(hipMalloc(&t->d_tl, sizeof(TopkLayer) * (size_t)max_layers));
+    // counts of the known-threshold compression: all zero between calls (the pick kernel clears what it reads)
+    TK_CHECK(hipMalloc(&t->d_cnt_known, sizeof(uint32_t) * (size_t)max_layers * kBinsB));
+    TK_CHECK(hipMemset(t->d_cnt_known, 0, sizeof(uint32_t) * (size_t)max_layers * kBinsB));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
@@ -1157,6 +1238,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
 void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_hist);
     (void)hipFree(t->d_tl);
+    (void)hipFree(t->d_cnt_known);
     (void)hipFree(t->d_cand);
     (void)hipFree(t->d_cand_idx);
     (void)hipFree(t->d_lo);
@@ -1422,8 +1504,8 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
-        hipLaunchKernelGGL(topk_count_kernel, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s,
-                           d_tiles, n_tiles, (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
+        hipLaunchKernelGGL(topk_count_kernel<false>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0,
+                           s, d_tiles, n_tiles, d_layers, (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
                            (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
         TK_CHECK(hipGetLastError());
     }
@@ -1435,7 +1517,68 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     }
     {
         Section sec(tm, "topk_emit");
-        hipLaunchKernelGGL(topk_emit_kernel, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s, e,
+        hipLaunchKernelGGL(topk_emit_kernel<false>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s, e,
+                           d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
+                           (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
+                           (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
+                           (const uint2*)t->d_tilebase, payload);
+        TK_CHECK(hipGetLastError());
+    }
+    return hipSuccess;
+}
+
+// Compression of the Top-K layers right behind a profile of the same data (the one-call entry
+// point): the layer records the solver kernel wrote say which layers take part and which of the
+// profile's selection records (threshold bin, sub-bin, entries to take) applies, so nothing is
+// sampled, no histogram is built and nothing depends on the host knowing the assignment.  One
+// pass writes x to the error feedback and collects what lies at or above the sub-bin's lower
+// edge, counting the sub-bin's entries by their last 9 bits; then the exact threshold, the
+// per-wavefront counts, their scan and the ordered emit, as in topk_compress.
+hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
+                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s) {
+    if (n_tiles <= 0) return hipSuccess;
+    // the profile's control block (slot 0) holds every layer's candidate region
+    uint8_t* const d = t->d_ctl[0];
+    CollectParams p{};
+    p.g = g;
+    p.e = e;
+    p.ef_out = e;
+    p.layers = d_layers;
+    p.tiles = d_tiles;
+    p.tl = (const TopkLayer*)t->d_tl;
+    p.cand = t->d_cand;
+    p.cand_idx = t->d_cand_idx;
+    p.cand_base = reinterpret_cast<const int64_t*>(d + t->ctl_off[1]);
+    p.tinfo = (TopkTileInfo*)t->d_tinfo;
+    p.base_part = t->d_base_part;
+    p.cnt_b = t->d_cnt_known;
+    {
+        Section sec(tm, "topk_collect", true);
+        launch_timed(&sec, true, true, topk_collect_known_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_pick");
+        hipLaunchKernelGGL(topk_pick_known_kernel, dim3(L), dim3(256), 0, s, d_layers, (TopkLayer*)t->d_tl,
+                           t->d_cnt_known);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_count");
+        hipLaunchKernelGGL(topk_count_kernel<true>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0,
+                           s, d_tiles, n_tiles, d_layers, (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
+                           (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_tilescan");
+        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(kScanThreads), 0, s, d_layers, (const uint2*)t->d_tilecnt,
+                           (uint2*)t->d_tilebase);
+        TK_CHECK(hipGetLastError());
+    }
+    {
+        Section sec(tm, "topk_emit");
+        hipLaunchKernelGGL(topk_emit_kernel<true>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s, e,
                            d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
                            (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
                            (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,

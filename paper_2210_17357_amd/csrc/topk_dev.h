@@ -19,26 +19,33 @@ __device__ __forceinline__ uint32_t mag_bits(float x) { return __float_as_uint(x
 // Candidate collection of one wavefront.  Elements whose coarse key (top 12 bits of |x|) is at or
 // above `lo` are written out in ballot-prefix order (the same order on every run); the energy of
 // the others is summed per lane.
+// A collection bound given as a coarse key, as the lowest magnitude pattern that qualifies (all
+// ones: nothing does - patterns have the sign bit cleared).
+__device__ __forceinline__ uint32_t bound_of_key(uint32_t lo) {
+    return (lo >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (lo << kHistShift);
+}
+
 struct Collector {
     uint32_t* dst;
     uint32_t* dst_idx;   // optional: index (within the layer) and sign of every candidate
-    uint32_t lo;
-    uint32_t lo_key;   // lo moved to the key's place in the pattern (all ones: nothing qualifies)
+    uint32_t lo_key;   // lowest magnitude pattern collected (a multiple of a coarse key where the caller
+                       // compares keys only; any pattern where it compares whole patterns)
     uint32_t cur;      // candidates written so far (uniform over the wavefront)
-    float base;        // this lane's sum of x^2 over elements below lo
+    float base;        // this lane's sum of x^2 over elements below the bound
     static constexpr uint32_t kKeyMask = (uint32_t)(kHistBins - 1) << kHistShift;
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t l) {
-        dst = d; dst_idx = di; lo = l; cur = 0; base = 0.0f;
-        lo_key = (l >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (l << kHistShift);
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t bound) {
+        dst = d; dst_idx = di; cur = 0; base = 0.0f;
+        lo_key = bound;
     }
     __device__ __forceinline__ static uint32_t below(unsigned long long m, uint32_t add) {
         return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, add));
     }
     // one element per lane
     __device__ __forceinline__ void take(float x, bool valid, uint32_t idx = 0) {
-        take_keyed(x, __float_as_uint(x) & kKeyMask, valid, idx);
+        take_keyed(x, mag_bits(x), valid, idx);
     }
-    // the same with the coarse key (pattern & kKeyMask) supplied by the caller
+    // the same with the value compared against the bound supplied by the caller: the magnitude
+    // pattern, or just its coarse key (pattern & kKeyMask) when the bound is a coarse key
     __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid, uint32_t idx = 0) {
         const uint32_t bits = __float_as_uint(x);
         const bool hit = valid && key >= lo_key;
@@ -61,7 +68,7 @@ struct Collector {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             pat[q] = mag_bits(x[q]);
-            hit[q] = (pat[q] >> kHistShift) >= lo;
+            hit[q] = pat[q] >= lo_key;
         }
         const unsigned long long m0 = __ballot(hit[0]), m1 = __ballot(hit[1]), m2 = __ballot(hit[2]),
                                  m3 = __ballot(hit[3]);
@@ -93,9 +100,9 @@ struct StagedCollector {
     uint32_t cur;        // candidates written to global memory so far (uniform over the wavefront)
     uint32_t fill;       // candidates waiting in the buffer (uniform)
     float base;          // this lane's sum of x^2 over elements below the bound
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t* st, uint32_t l) {
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* st, uint32_t bound) {
         dst = d; stage = st; cur = 0; fill = 0; base = 0.0f;
-        lo_key = (l >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (l << kHistShift);
+        lo_key = bound;
     }
     __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid) {
         const uint32_t bits = __float_as_uint(x);
