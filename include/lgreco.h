@@ -94,7 +94,10 @@ typedef struct {
                             * pass from the thresholds found then, a margin lower, instead of
                             * sampling the data first.  Results do not depend on it: a layer
                             * whose data moved past the margin is collected again. */
-    int32_t  reserved;     /* 0 */
+    int32_t  dp_groups;    /* solver: 0 = decide per solve from its size; 1 = always one sequential
+                            * sweep; 2, 4, 8 = sweep the layers in that many groups side by side and
+                            * join the groups' tables (results are the same in every case,
+                            * Algorithm 1's tie-breaks included) */
 } lgreco_config_t;
 
 /* Create a handle for problems of at most max_elems gradient elements (sum of numel),
@@ -319,6 +322,12 @@ int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, f
  * sections.  A loop can run untouched and be read once at its end. */
 int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** names, double* total_ms,
                              int64_t* count, int32_t cap);
+
+/* How the last successful solve on this handle swept its table: 0 sequentially, G > 0 in G layer
+ * groups, 1000 + G in G groups where ties between ways of sharing the error bins among the groups
+ * had to be resolved by Algorithm 1's tie-breaks, -G sequentially after that resolution gave up.
+ * Diagnostics only. */
+int lgreco_last_solve_groups(const lgreco_handle_t* h);
 
 const char* lgreco_strerror(int status);
 /* Text of the last HIP error seen by this handle ("" if none). */

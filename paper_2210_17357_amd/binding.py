@@ -22,7 +22,7 @@ CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve", "lgreco_profile_solve_compress",
            "lgreco_candidate_range", "lgreco_emax",
            "lgreco_solve", "lgreco_solve_static", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
-           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error")
+           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error", "lgreco_last_solve_groups")
 
 
 class Layer(C.Structure):
@@ -36,7 +36,7 @@ class Cand(C.Structure):
 class Config(C.Structure):
     _fields_ = [("bucket", C.c_int32), ("stochastic", C.c_int32), ("seed", C.c_uint64),
                 ("power_iters", C.c_int32), ("r_max", C.c_int32), ("reuse_thresholds", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("dp_groups", C.c_int32)]
 
 
 class LgrecoError(RuntimeError):
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
         l.lgreco_get_timing_totals.argtypes = [vp, i32, vp, vp, vp, i32]
         l.lgreco_strerror.argtypes = [C.c_int]
         l.lgreco_strerror.restype = C.c_char_p
+        l.lgreco_last_solve_groups.argtypes = [vp]
         l.lgreco_last_hip_error.argtypes = [vp]
         l.lgreco_last_hip_error.restype = C.c_char_p
         for name in EXPORTS:
@@ -185,9 +186,10 @@ class Handle:
 
     def __init__(self, max_elems: int, max_layers: int, max_cands: int, bucket: int = 128,
                  stochastic: bool = False, seed: int = 0, power_iters: int = 1, r_max: int = 64,
-                 reuse_thresholds: bool = False):
+                 reuse_thresholds: bool = False, dp_groups: int = 0):
         self._h = C.c_void_p()
-        self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max, int(bool(reuse_thresholds)), 0)
+        self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max, int(bool(reuse_thresholds)),
+                          int(dp_groups))
         st = lib().lgreco_create(C.byref(self._h), C.byref(self.cfg), max_elems, max_layers, max_cands)
         if st != OK:
             raise LgrecoError(st, strerror(st))
@@ -305,6 +307,11 @@ class Handle:
             raise ValueError("buffers differ in size")
         self._check(lib().lgreco_accumulate(self._h, _dptr(d_acc), _dptr(d_grads), int(d_grads.numel()),
                                             int(bool(reset)), _stream(stream)))
+
+    def last_solve_groups(self) -> int:
+        """0: sequential sweep; G: G layer groups; 1000 + G: groups with ties resolved; -G: sequential
+        after the tie resolution gave up."""
+        return int(lib().lgreco_last_solve_groups(self._h))
 
     def set_timing(self, level):
         """0 / False: off; 1 / True: main kernels; 2: every section."""

@@ -69,6 +69,10 @@ struct lgreco_handle {
     int32_t* d_build_host = nullptr;
     int32_t* d_nsweep = nullptr;
     int64_t dp_seq = 0;                  // sequence number of the last solver launch
+    int64_t last_solve_groups = 0;       // how the last solve swept its table (the kernel's report)
+    // layer groups of the solver (see DpGroups): tree nodes, group ranges
+    uint32_t* d_dp_nodes = nullptr;
+    int32_t* d_dp_range = nullptr;
     // lgreco_profile_solve_compress: what the solver kernel needs to write the compression's layer
     // records itself - device copies of the build's report and, per (layer, candidate), the integer
     // parameter a choice stands for plus the family per candidate (pinned staging copy, uploaded
@@ -98,6 +102,15 @@ struct lgreco_handle {
 namespace {
 
 constexpr int kDpResultSlots = 16;      // int64 words at the head of the solver's result block
+constexpr int kMaxDpGroups = 8;         // layer groups the solver may sweep side by side
+
+DpGroups dp_groups(const lgreco_handle* h) {
+    DpGroups g;
+    g.G = h->cfg.dp_groups;             // 0: chosen per solve from its size
+    g.nodes = h->d_dp_nodes;
+    g.range = h->d_dp_range;
+    return g;
+}
 
 // lgreco_profile_solve_compress: the compression's first kernel queued behind the solver.
 struct EarlyCompress {
@@ -344,6 +357,11 @@ const char* lgreco_strerror(int status) {
 
 const char* lgreco_last_hip_error(const lgreco_handle_t* h) { return h ? h->hip_error.c_str() : ""; }
 
+int lgreco_last_solve_groups(const lgreco_handle_t* h) {
+    if (!h) return LGRECO_EINVAL;
+    return (int)h->last_solve_groups;
+}
+
 int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max_elems, int32_t max_layers,
                   int32_t max_cands) {
     if (!out || !cfg || max_elems <= 0 || max_layers <= 0 || max_cands <= 0) return LGRECO_EINVAL;
@@ -351,6 +369,9 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     if (cfg->bucket != kBucket) return LGRECO_EUNSUPPORTED;
     if (cfg->power_iters < 1 || cfg->power_iters > 16) return LGRECO_EUNSUPPORTED;
     if (cfg->r_max < 0 || cfg->r_max > 64) return LGRECO_EUNSUPPORTED;
+    if (cfg->dp_groups != 0 && cfg->dp_groups != 1 && cfg->dp_groups != 2 && cfg->dp_groups != 4 &&
+        cfg->dp_groups != 8)
+        return LGRECO_EINVAL;
     lgreco_handle* h = new (std::nothrow) lgreco_handle();
     if (!h) return LGRECO_ENOSPACE;
     h->cfg = *cfg;
@@ -402,6 +423,8 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->h_result = reinterpret_cast<int64_t*>(h->h_dp_out);
     h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * kDpResultSlots);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
+    HIPCHK_C(hipMalloc(&h->d_dp_nodes, sizeof(uint32_t) * (2 * kMaxDpGroups - 1) * (LGRECO_MAX_BINS + 4)));
+    HIPCHK_C(hipMalloc(&h->d_dp_range, sizeof(int32_t) * 2 * kMaxDpGroups));
     HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
     HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16));
     HIPCHK_C(hipMalloc(&h->d_errors_dev, sizeof(double) * (size_t)max_layers * max_cands + 16));
@@ -435,6 +458,8 @@ int lgreco_destroy(lgreco_handle_t* h) {
     (void)hipHostFree(h->h_errors);
     (void)hipFree(h->d_dp_in);
     (void)hipFree(h->d_pd);
+    (void)hipFree(h->d_dp_nodes);
+    (void)hipFree(h->d_dp_range);
     (void)hipHostFree(h->h_sizes);
     (void)hipFree(h->d_sizes);
     (void)hipFree(h->d_errors_dev);
@@ -810,7 +835,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         const size_t in_bytes = h->dp_entries_off + sizeof(DpEntry) * (size_t)n_sweep * max_count;
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
                     h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr,
-                    ++h->dp_seq, DpApply{}};
+                    ++h->dp_seq, DpApply{}, dp_groups(h)};
         {
             Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s, &sec, true));
@@ -820,6 +845,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
             const int wst = wait_for_solver(h, h->dp_seq, s);     // the kernel wrote h_dp_out
             if (wst != LGRECO_OK) return wst;
         }
+        h->last_solve_groups = h->h_result[9];
         if (h->tm->active) record_dp_sub(h);
         if (h->h_result[0] == 1) return infeasible();
         if (h->h_result[0] != 0) {
@@ -888,7 +914,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
                      h->d_count, h->d_build_host, h->d_build_host + L, h->d_build_dev, h->d_build_dev + L,
                      h->d_nsweep, h->d_result};
     DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, L, n_bins, 0, 0, 0, P,
-                nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq, DpApply{}};
+                nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq, DpApply{}, dp_groups(h)};
     if (ec) {
         // what every (layer, candidate) means to the compression kernels, as lgreco_compress works
         // it out for a choice: the solver kernel picks the chosen column
@@ -953,6 +979,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     }
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
     const int64_t status = h->h_result[0];
+    h->last_solve_groups = status == 0 ? h->h_result[9] : 0;
     if (ec) ec->applied = h->h_result[8] == 1;
     {
         const uint64_t bits = (uint64_t)h->h_result[6];

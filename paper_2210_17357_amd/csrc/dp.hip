@@ -43,6 +43,7 @@ template <> __device__ __forceinline__ int64_t readlane_t<int64_t>(int64_t v, in
 
 constexpr int kDpStageEntries = 1024;   // entries staged in LDS at a time (16 KB)
 constexpr int kDpStageMax = 32;         // at most this many layers per stage
+constexpr int kDpMaxGroups = 8;         // layer groups swept side by side (a power of two)
 
 // Thread t owns KMAX cells.  With an even KMAX they come in adjacent pairs (2t, 2t+1), (2t, 2t+1) +
 // 2*threads, ...: the two reads row[e - b], row[e + 1 - b] of a pair are one ds_read2_b32 and the
@@ -52,67 +53,27 @@ __device__ __forceinline__ int dp_cell(int tid, int k) {
     return KMAX % 2 == 0 ? 2 * tid + (k & 1) + (k >> 1) * 2 * THREADS : tid + k * THREADS;
 }
 
+// Sweep of the swept layers [l_begin, l_end) over the row in LDS (the caller has written the row the
+// first of them starts from): per layer the new row is formed in registers from the entries'
+// shifted reads, then written back together with the arg-min bytes PD[l][0..D].  With s_bins the
+// bin of every entry is also kept in LDS for the back-trace.  Every thread of the block calls.
 template <typename T, int KMAX, bool PADDED, int kDpThreads>
-__global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
-    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*threads-1 (cells above D stay infinite).
-    // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
-    extern __shared__ unsigned char dp_smem[];
-    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
-    __shared__ DpEntry s_entries[kDpStageEntries];      // [layers of the stage][max_count]
-    __shared__ int32_t s_count[kDpStageMax];
-    __shared__ int64_t s_val[kDpThreads / 64];
-    __shared__ int32_t s_idx[kDpThreads / 64];
+__device__ __forceinline__ void dp_sweep_layers(const DpParams& p, T* const row, DpEntry* const s_entries,
+                                                int32_t* const s_count, uint16_t* const s_bins, const int l_begin,
+                                                const int l_end) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int D = p.D;
     const int64_t width = p.pd_stride;
     constexpr T kInf = DpInf<T>::v;
-    // back-trace tables behind the row when they fit (the host decides): the bin of every entry
-    // (16 bits: D <= 16384) and the picked entry per layer
-    const bool lds_bins = p.bt_lds != 0;
-    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
     const int bstride = p.max_count;
-    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
-    // Entry lists built on the device (dp_build_kernel): the number of swept layers and the status
-    // it found come from memory; anything but "ok" there ends the solve.
-    int L = p.L;
-    if (p.L_dev) {
-        if (p.L_dev[1] != 0) {            // the build kernel reported the status; only the hand-over is left
-            if (p.apply.layers)
-                for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
-            if (tid == 0) {
-                p.result[8] = 0;
-                __threadfence_system();
-                p.result[7] = p.seq;
-            }
-            return;
-        }
-        L = p.L_dev[0];
-    }
-
-    // for the apply step at the end (see DpApply): the build's report for this thread's layer,
-    // fetched now so that the tail does not wait for it
-    int32_t pre_fixed = 0, pre_sweep = 0;
-    if (p.apply.layers) {
-        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
-        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
-    }
-    const uint64_t t_begin = wall_clock64();
-    if (p.host_in) {
-        // fetch the input block from the host's pinned memory: one 16-byte word per thread and
-        // round, all in flight together; the barrier below orders it before the first read
-        for (int i = tid; i < p.in_vec; i += kDpThreads) p.dev_in[i] = p.host_in[i];
-        __threadfence_block();
-    }
-    for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
-
     const int stage = min(kDpStageMax, kDpStageEntries / bstride);     // layers per stage
-    for (int l0 = 0; l0 < L; l0 += stage) {
-        const int nl = min(stage, L - l0);
+    for (int l0 = l_begin; l0 < l_end; l0 += stage) {
+        const int nl = min(stage, l_end - l0);
         __syncthreads();                              // previous stage fully consumed, row written
         for (int i = tid; i < nl * bstride; i += kDpThreads) {
             const DpEntry en = p.entries[(size_t)l0 * bstride + i];
             s_entries[i] = en;
-            if (lds_bins) s_bins[(size_t)l0 * bstride + i] = (uint16_t)en.bin;
+            if (s_bins) s_bins[(size_t)l0 * bstride + i] = (uint16_t)en.bin;
         }
         if (tid < nl) s_count[tid] = p.count[l0 + tid];
         __syncthreads();
@@ -187,72 +148,449 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             __syncthreads();
         }
     }
-    __syncthreads();
+}
 
-    // arg-min of the last row, lowest e among equal minima
-    int64_t bv = (int64_t)kInf;
-    int32_t be = 0x7FFFFFFF;
-    for (int e = tid; e <= D; e += kDpThreads) {
-        const int64_t v = (int64_t)row[e];
-        if (v < bv) { bv = v; be = e; }              // e ascending per thread -> keeps the lowest
+// ---- grouped sweep: G workgroups, each sweeping its share of the layers from the virtual start row
+// Block g takes the swept layers whose running entry count falls into the g-th of G equal parts
+// (the sweep costs one pass over the row per entry), writes their arg-min rows like the
+// sequential sweep and leaves, per exact bin sum e, the smallest size of its layers alone.
+// 32-bit costs and the padded row only (what the host turns groups on for).
+template <int KMAX, int kDpThreads>
+__global__ __launch_bounds__(kDpThreads) void dp_group_kernel(DpParams p) {
+    using T = uint32_t;
+    extern __shared__ unsigned char dp_smem[];
+    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
+    __shared__ DpEntry s_entries[kDpStageEntries];
+    __shared__ int32_t s_count[kDpStageMax];
+    __shared__ int32_t s_wsum[kDpThreads / 64];
+    __shared__ int32_t s_lb[kDpMaxGroups + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = p.groups.G, g = blockIdx.x;
+    constexpr T kInf = DpInf<T>::v;
+    int L = p.L;
+    if (p.L_dev) {
+        if (p.L_dev[1] != 0) return;                  // nothing to solve: the last kernel reports
+        L = p.L_dev[0];
     }
+    // group boundaries from the exclusive prefix of the entry counts (L <= kDpThreads)
+    const int c = tid < L ? p.count[tid] : 0;
+    int inc = c;
     for (int o = 1; o < 64; o <<= 1) {
-        const int64_t ov = __shfl_xor(bv, o, 64);
-        const int32_t oe = __shfl_xor(be, o, 64);
-        if (ov < bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        const int n = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += n;
     }
-    if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
+    if (lane == 63) s_wsum[wave] = inc;
+    if (tid <= G) s_lb[tid] = L;
     __syncthreads();
-    uint64_t t_sweep = 0;
-    if (tid < 64) {
-        // the first wavefront: every lane joins the per-wavefront minima the same way
-        if (tid == 0) t_sweep = wall_clock64();
-        for (int w = 1; w < kDpThreads / 64; ++w)
-            if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
-        if (tid == 0) {
-            s_val[0] = bv;
-            s_idx[0] = be;
+    int base = 0, total = 0;
+    for (int w = 0; w < kDpThreads / 64; ++w) {
+        if (w < wave) base += s_wsum[w];
+        total += s_wsum[w];
+    }
+    if (tid < L) {
+        const int gid = total > 0 ? min(G - 1, (int)(((int64_t)(base + inc - c) * G) / total)) : 0;
+        atomicMin(&s_lb[gid], tid);
+    }
+    __syncthreads();
+    if (tid == 0)
+        for (int q = G - 1; q >= 0; --q)              // a group without layers begins where the next one does
+            if (s_lb[q] > s_lb[q + 1]) s_lb[q] = s_lb[q + 1];
+    __syncthreads();
+    const int lb = s_lb[g], le = s_lb[g + 1];
+    for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
+    dp_sweep_layers<T, KMAX, true, kDpThreads>(p, row, s_entries, s_count, nullptr, lb, le);
+    __syncthreads();
+    T* const out = p.groups.nodes + (size_t)(G - 1 + g) * p.groups.stride;
+    for (int e = tid; e < p.groups.stride; e += kDpThreads) out[e] = e <= p.D ? row[e] : kInf;
+    if (tid == 0) {
+        p.groups.range[2 * g] = lb;
+        p.groups.range[2 * g + 1] = le;
+    }
+}
+
+// One level of the tree: node = first_node + blockIdx.y joins its children X (lower layers) and Y,
+//     T[e] = min over e2 <= e of Y[e2] + X[e - e2].
+// Which e2 attains it is looked up later, for the few cells the trace passes through.  Both
+// children sit in LDS; a wavefront takes whole cells (interleaved over the grid: a cell costs
+// e + 1 terms), its lanes the terms of a cell.
+constexpr int kConvThreads = 1024;
+__global__ __launch_bounds__(kConvThreads) void dp_conv_kernel(DpGroups gr, int first_node, int D,
+                                                                const int32_t* __restrict__ L_dev) {
+    extern __shared__ uint32_t conv_smem[];
+    constexpr uint32_t kInf = DpInf<uint32_t>::v;
+    if (L_dev && L_dev[1] != 0) return;
+    const int node = first_node + blockIdx.y;
+    const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
+    const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
+    uint32_t* const sX = conv_smem;
+    uint32_t* const sY = conv_smem + (D + 1);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i <= D; i += kConvThreads) {
+        sX[i] = X[i];
+        sY[i] = Y[i];
+    }
+    __syncthreads();
+    uint32_t* const T = gr.nodes + (size_t)node * gr.stride;
+    const int nw = gridDim.x * (kConvThreads / 64);
+    for (int e = blockIdx.x * (kConvThreads / 64) + wave; e <= D; e += nw) {
+        uint32_t best = kInf;                        // a sum with an infinite term is at least kInf
+#pragma unroll 4
+        for (int e2 = lane; e2 <= e; e2 += 64) best = min(best, sY[e2] + sX[e - e2]);
+        for (int o = 1; o < 64; o <<= 1) best = min(best, (uint32_t)__shfl_xor(best, o, 64));
+        if (lane == 0) T[e] = best;
+    }
+}
+
+// The host's input block from pinned memory into device memory (grouped solves of lgreco_solve:
+// every group reads the lists, so they are fetched once, ahead of the groups).
+__global__ __launch_bounds__(256) void dp_fetch_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) dst[i] = src[i];
+}
+
+template <typename T, int KMAX, bool PADDED, int kDpThreads>
+__global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
+    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*threads-1 (cells above D stay infinite).
+    // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
+    extern __shared__ unsigned char dp_smem[];
+    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
+    __shared__ DpEntry s_entries[kDpStageEntries];      // [layers of the stage][max_count]
+    __shared__ int32_t s_count[kDpStageMax];
+    __shared__ int64_t s_val[kDpThreads / 64];
+    __shared__ int32_t s_idx[kDpThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int D = p.D;
+    const int64_t width = p.pd_stride;
+    constexpr T kInf = DpInf<T>::v;
+    // back-trace tables behind the row when they fit (the host decides): the bin of every entry
+    // (16 bits: D <= 16384) and the picked entry per layer
+    const bool lds_bins = p.bt_lds != 0;
+    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
+    const int bstride = p.max_count;
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
+    // Entry lists built on the device (dp_build_kernel): the number of swept layers and the status
+    // it found come from memory; anything but "ok" there ends the solve.
+    int L = p.L;
+    if (p.L_dev) {
+        if (p.L_dev[1] != 0) {            // the build kernel reported the status; only the hand-over is left
+            if (p.apply.layers)
+                for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
+            if (tid == 0) {
+                p.result[8] = 0;
+                __threadfence_system();
+                p.result[7] = p.seq;
+            }
+            return;
         }
-        if (bv < (int64_t)kInf) {
-            // The walk is a chain of dependent loads: one PD byte per layer from global memory,
-            // the bin it stands for from LDS when the table fits there.
-            int e = __builtin_amdgcn_readfirstlane(be);
+        L = p.L_dev[0];
+    }
+
+    // for the apply step at the end (see DpApply): the build's report for this thread's layer,
+    // fetched now so that the tail does not wait for it
+    int32_t pre_fixed = 0, pre_sweep = 0;
+    if (p.apply.layers) {
+        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
+        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
+    }
+    const uint64_t t_begin = wall_clock64();
+    if (p.host_in) {
+        // fetch the input block from the host's pinned memory: one 16-byte word per thread and
+        // round, all in flight together; the barrier below orders it before the first read
+        for (int i = tid; i < p.in_vec; i += kDpThreads) p.dev_in[i] = p.host_in[i];
+        __threadfence_block();
+    }
+
+    // arg-min of the row in LDS, lowest e among equal minima -> s_val[0], s_idx[0] (all threads call)
+    auto argmin_row = [&]() {
+        int64_t bv = (int64_t)kInf;
+        int32_t be = 0x7FFFFFFF;
+        for (int e = tid; e <= D; e += kDpThreads) {
+            const int64_t v = (int64_t)row[e];
+            if (v < bv) { bv = v; be = e; }              // e ascending per thread -> keeps the lowest
+        }
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t ov = __shfl_xor(bv, o, 64);
+            const int32_t oe = __shfl_xor(be, o, 64);
+            if (ov < bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        __syncthreads();                              // earlier readers of s_val / s_idx are done
+        if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
+        __syncthreads();
+        if (tid < 64) {
+            // the first wavefront: every lane joins the per-wavefront minima the same way
+            for (int w = 1; w < kDpThreads / 64; ++w)
+                if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
+        }
+        __syncthreads();
+        if (tid == 0) { s_val[0] = bv; s_idx[0] = be; }
+        __syncthreads();
+    };
+
+    // The walk is a chain of dependent loads: one PD byte per layer from global memory, the bin it
+    // stands for from LDS when the table fits there.  One wavefront walks the swept layers
+    // [l_lo, l_hi) downwards from cell e, writes the picked entry of every layer to out[layer]
+    // and returns the cell it ends in (0 if all is consistent).
+    // Two layers per load latency: lane j holds the bin of entry j of layer l, so while PD[l][e]
+    // is on its way lane j already fetches PD[l-1][e - bin_j], the byte the walk needs next if
+    // entry j is the one picked.  A wavefront runs alone here and every instruction costs its
+    // full issue latency, so the loop is kept short: rows by a running pointer, no branches,
+    // consistency checks joined into one flag (a bad byte still gives in-row addresses: e only
+    // shrinks and is clamped at 0, lanes past the list hold bin 0).
+    auto walk = [&](const int l_hi, const int l_lo, int e, uint8_t* const out) -> int {
+        auto bins_of = [&](int layer) -> uint32_t {
+            return lane < bstride ? (uint32_t)s_bins[max(layer, 0) * bstride + lane] : 0u;
+        };
+        int l = l_hi - 1;
+        uint32_t bins_cur = bins_of(l), bins_prev = bins_of(l - 1);
+        const uint8_t* __restrict__ row_l = p.pd + (size_t)max(l, 0) * width;
+        int bad = 0;
+        for (; l >= l_lo + 1; l -= 2, row_l -= 2 * width) {
+            const uint32_t bins_n1 = bins_of(l - 2), bins_n2 = bins_of(l - 3);
+            const uint32_t ka_v = row_l[e];
+            const uint32_t kb_v = (row_l - width)[max(e - (int)bins_cur, 0)];
+            const int ka = __builtin_amdgcn_readfirstlane((int)ka_v);
+            const int kb = (int)readlane_u32(kb_v, ka);
+            out[l] = (uint8_t)ka;                  // every lane writes the same byte
+            out[l - 1] = (uint8_t)kb;
+            e -= (int)readlane_u32(bins_cur, ka) + (int)readlane_u32(bins_prev, kb);
+            bad |= (ka >= bstride) | (kb >= bstride) | (e < 0);
+            e = max(e, 0);
+            bins_cur = bins_n1;
+            bins_prev = bins_n2;
+        }
+        if (l == l_lo && l_hi > l_lo) {
+            const int ka = __builtin_amdgcn_readfirstlane((int)row_l[e]);
+            out[l] = (uint8_t)ka;
+            e -= (int)readlane_u32(bins_cur, ka);
+            bad |= (ka >= bstride) | (e < 0);
+        }
+        return bad ? -1 : e;                        // -1: an internal inconsistency
+    };
+
+    // Grouped mode (see dp_group_kernel / dp_conv_kernel): the layers were swept in G groups side
+    // by side and the groups' cost functions joined pairwise; node 0 of the tree is the last row of
+    // the whole table.  Walking down the tree gives every group its share of the bins: at an inner
+    // node holding e bins the split is the e2 with Y[e2] + X[e - e2] = T[e].  Where several e2
+    // attain it, Algorithm 1's tie-breaks decide (lowest candidate index, last layer first): the
+    // split whose higher-layer child Y traces back to the lexicographically smallest sequence of
+    // picks, compared from Y's last layer down (slow path below).  A solve the slow path gives up
+    // on (too many candidates) is swept here as if there were no groups.
+    constexpr int kSplitCap = 16, kWalkBudget = 96, kTreeDepth = 3;
+    static_assert((1 << kTreeDepth) == kDpMaxGroups, "the slow path is written out for this depth");
+    __shared__ int32_t s_alloc[2 * kDpMaxGroups], s_ncnt[2 * kDpMaxGroups], s_nlast[2 * kDpMaxGroups];
+    __shared__ int32_t s_tie, s_walk_bad, s_slow_ok;
+    const int G = p.groups.G;
+    const DpGroups& gr = p.groups;
+    // every e2 with Y[e2] + X[e - e2] = T[e] of an inner node, up to kSplitCap of them in out[] (in
+    // no particular order); the whole block scans (every thread calls, with the same arguments);
+    // returns how many there are, which may be more than fit out[]
+    __shared__ int32_t s_nsplit;
+    auto splits_of = [&](const int node, const int e, int32_t* const out) -> int {
+        const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
+        const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
+        const uint32_t target = gr.nodes[(size_t)node * gr.stride + e];
+        __syncthreads();                              // earlier readers of s_nsplit / out are done
+        if (tid == 0) s_nsplit = 0;
+        __syncthreads();
+        if (target < (uint32_t)kInf) {
+#pragma unroll 4
+            for (int e2 = tid; e2 <= e; e2 += kDpThreads) {
+                if (Y[e2] + X[e - e2] == target) {
+                    const int pos = atomicAdd(&s_nsplit, 1);
+                    if (pos < kSplitCap) out[pos] = e2;
+                }
+            }
+        }
+        __syncthreads();
+        return s_nsplit;
+    };
+    // first and last swept layer of the leaves under a node of the tree
+    auto layers_of = [&](int node, int* lo, int* hi) {
+        int a = node, b = node;
+        while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
+        *lo = gr.range[2 * (a - (G - 1))];
+        *hi = gr.range[2 * (b - (G - 1)) + 1];
+    };
+    enum { kSeq = 0, kGroupedWalk = 1, kGroupedInfeasible = 3 };
+    int mode = kSeq;                                  // block-uniform
+    bool resolved = false;                            // ambiguous splits were met and resolved
+    if (G > 1) {
+        for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads)
+            row[e] = (e >= 0 && e <= D) ? (T)gr.nodes[e] : kInf;
+        if (tid == 0) { s_tie = 0; s_walk_bad = 0; s_slow_ok = 0; }
+        __syncthreads();
+        argmin_row();
+        if (s_val[0] >= (int64_t)kInf) {
+            mode = kGroupedInfeasible;                // no assignment fits: nothing to trace
+        } else {
+            // the bin of every entry, for the walks (in sequential mode the sweep leaves them)
+            for (int i = tid; i < L * bstride; i += kDpThreads) s_bins[i] = (uint16_t)p.entries[i].bin;
+            if (tid == 0) s_alloc[0] = s_idx[0];
+            // fast path, level by level: the threads share out the nodes of a level and each node's
+            // e2 range; a node where not exactly one e2 matches ends it
+            for (int first = 0; first < G - 1; first = 2 * first + 1) {         // nodes first .. 2 first
+                if (tid < 2 * kDpMaxGroups) { s_ncnt[tid] = 0; s_nlast[tid] = -1; }
+                __syncthreads();
+                const int tpn = kDpThreads / (first + 1);                       // threads per node
+                const int node = first + tid / tpn, t_in = tid % tpn;
+                const int a = s_alloc[node];
+                const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
+                const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
+                const uint32_t target = gr.nodes[(size_t)node * gr.stride + a];
+                int cnt = 0, last = -1;
+                if (s_tie == 0) {
+#pragma unroll 4
+                    for (int e2 = t_in; e2 <= a; e2 += tpn) {
+                        const bool ok = Y[e2] + X[a - e2] == target;
+                        cnt += ok ? 1 : 0;
+                        last = ok ? e2 : last;
+                    }
+                }
+                if (cnt) {
+                    atomicAdd(&s_ncnt[node], cnt);
+                    atomicMax(&s_nlast[node], last);
+                }
+                __syncthreads();
+                if (t_in == 0) {
+                    if (s_ncnt[node] != 1) {
+                        s_tie = 1;
+                    } else {
+                        s_alloc[2 * node + 2] = s_nlast[node];
+                        s_alloc[2 * node + 1] = a - s_nlast[node];
+                    }
+                }
+                __syncthreads();
+            }
+            __syncthreads();
+            if (s_tie == 0) {
+                mode = kGroupedWalk;
+            } else {
+                // slow path: resolve every ambiguous split by comparing the sequences of picks its
+                // candidates lead to in the higher-layer child, then walk as above.  Every thread
+                // runs the same control flow (all decisions come from LDS); the scans use the whole
+                // block, the walks one wavefront per group, the comparisons the first wavefront.
+                {
+                    uint8_t* const bufs = reinterpret_cast<uint8_t*>(s_entries) + 1024;     // [depth][2][L <= 1024]
+                    int32_t* const cands = reinterpret_cast<int32_t*>(s_entries) + 2048;    // behind the buffers: [depth][cap]
+                    int32_t* const saved = cands + kTreeDepth * kSplitCap;                  // [depth][2 G] shares of the best candidate
+                    static_assert(sizeof(s_entries) >= 8192 + 4 * kTreeDepth * (kSplitCap + 2 * kDpMaxGroups),
+                                  "staging area too small");
+                    int budget = kWalkBudget;         // candidates looked at; the same in every thread
+                    // picks of [lo, hi) compared from the last layer down: is a before b?
+                    auto before = [&](const uint8_t* a, const uint8_t* b, int lo, int hi) -> bool {
+                        if (tid < 64) {
+                            int res = 0;
+                            for (int top = hi - 1; top >= lo; top -= 64) {
+                                const int l = top - lane;
+                                const int da = l >= lo ? a[l] : 0, db = l >= lo ? b[l] : 0;
+                                const unsigned long long m = __ballot(da != db);
+                                if (m) {
+                                    const int firstl = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+                                    res = (int)readlane_u32((uint32_t)(da < db), firstl);
+                                    break;
+                                }
+                            }
+                            if (lane == 0) s_nlast[0] = res;
+                        }
+                        __syncthreads();
+                        const bool r = s_nlast[0] != 0;
+                        __syncthreads();
+                        return r;
+                    };
+                    // picks of every group under `node`, each from the share s_alloc gives it: one
+                    // wavefront per group, side by side
+                    auto walk_under = [&](int node, uint8_t* out) -> bool {
+                        int a = node, b = node;
+                        while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
+                        if (tid == 0) s_nlast[1] = 0;
+                        __syncthreads();
+                        const int leafn = a + (tid >> 6);
+                        if (leafn <= b) {
+                            const int g = leafn - (G - 1);
+                            const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
+                                                   __builtin_amdgcn_readfirstlane(s_alloc[leafn]), out);
+                            if (lane == 0 && e_end != 0) s_nlast[1] = 1;
+                        }
+                        __syncthreads();
+                        const bool ok = s_nlast[1] == 0;
+                        __syncthreads();
+                        return ok;
+                    };
+                    // the shares of every node under `node` holding e bins -> s_alloc
+                    auto share = [&](auto&& deeper, int level, int node, int e) -> bool {
+                        if (tid == 0) s_alloc[node] = e;
+                        if (node >= G - 1) return true;
+                        int32_t* const cd = cands + level * kSplitCap;
+                        const int cnt = splits_of(node, e, cd);
+                        if (cnt < 1 || cnt > kSplitCap) return false;
+                        int pick = 0;
+                        if (cnt > 1) {
+                            int lo, hi;
+                            layers_of(2 * node + 2, &lo, &hi);
+                            uint8_t* best = bufs + (size_t)(2 * level) * 1024;
+                            uint8_t* cur = bufs + (size_t)(2 * level + 1) * 1024;
+                            int32_t* const keep = saved + level * 2 * kDpMaxGroups;
+                            for (int i = 0; i < cnt; ++i) {
+                                if (--budget < 0) return false;
+                                if (!deeper(2 * node + 2, cd[i])) return false;
+                                if (!walk_under(2 * node + 2, i == 0 ? best : cur)) return false;
+                                const bool better = i > 0 && before(cur, best, lo, hi);
+                                if (better) {
+                                    uint8_t* t = best; best = cur; cur = t;
+                                    pick = i;
+                                }
+                                if (i == 0 || better) {
+                                    if (tid < 2 * kDpMaxGroups) keep[tid] = s_alloc[tid];
+                                    __syncthreads();
+                                }
+                            }
+                            if (tid < 2 * kDpMaxGroups) s_alloc[tid] = keep[tid];     // the best candidate's shares
+                            __syncthreads();
+                        } else if (!deeper(2 * node + 2, cd[0])) {
+                            return false;
+                        }
+                        return deeper(2 * node + 1, e - cd[pick]);
+                    };
+                    auto leaf_share = [&](int n, int ee) -> bool {
+                        if (tid == 0) s_alloc[n] = ee;
+                        return true;
+                    };
+                    auto share2 = [&](int node, int e) -> bool { return share(leaf_share, 2, node, e); };
+                    auto share1 = [&](int node, int e) -> bool { return share(share2, 1, node, e); };
+                    const bool ok = share(share1, 0, 0, s_idx[0]);
+                    __syncthreads();
+                    if (tid == 0) s_slow_ok = ok ? 1 : 0;
+                }
+                __syncthreads();
+                mode = s_slow_ok ? kGroupedWalk : kSeq;
+                resolved = s_slow_ok != 0;
+            }
+        }
+    }
+    if (mode == kSeq) {
+        for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
+        dp_sweep_layers<T, KMAX, PADDED, kDpThreads>(p, row, s_entries, s_count, lds_bins ? s_bins : nullptr, 0, L);
+        __syncthreads();
+        argmin_row();
+    }
+    const bool grouped = mode != kSeq;
+    uint64_t t_sweep = 0;
+    if (tid == 0) t_sweep = wall_clock64();
+
+    if (mode == kGroupedWalk) {
+        // (the host turns groups on only when the bin table fits LDS and lists have at most 64 entries)
+        const int g = tid >> 6;
+        if (g < G) {
+            const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
+                                   __builtin_amdgcn_readfirstlane(s_alloc[G - 1 + g]), s_pick);
+            if (lane == 0 && e_end != 0) s_walk_bad = 1;
+        }
+        __syncthreads();
+        if (tid == 0) s_idx[1] = s_walk_bad ? -1 : 0;
+    } else if (mode == kSeq && tid < 64) {
+        if (s_val[0] < (int64_t)kInf) {
+            int e = __builtin_amdgcn_readfirstlane(s_idx[0]);
             if (lds_bins && bstride <= 64) {
-                // Two layers per load latency: lane j holds the bin of entry j of layer l, so
-                // while PD[l][e] is on its way lane j already fetches PD[l-1][e - bin_j], the
-                // byte the walk needs next if entry j is the one picked.  One wavefront runs
-                // alone here and every instruction costs its full issue latency, so the loop is
-                // kept short: rows by a running pointer, no branches, consistency checks joined
-                // into one flag (a bad byte still gives in-row addresses: e only shrinks and is
-                // clamped at 0, lanes past the list hold bin 0).
-                auto bins_of = [&](int layer) -> uint32_t {
-                    return lane < bstride ? (uint32_t)s_bins[max(layer, 0) * bstride + lane] : 0u;
-                };
-                int l = L - 1;
-                uint32_t bins_cur = bins_of(l), bins_prev = bins_of(l - 1);
-                const uint8_t* __restrict__ row_l = p.pd + (size_t)max(l, 0) * width;
-                int bad = 0;
-                for (; l >= 1; l -= 2, row_l -= 2 * width) {
-                    const uint32_t bins_n1 = bins_of(l - 2), bins_n2 = bins_of(l - 3);
-                    const uint32_t ka_v = row_l[e];
-                    const uint32_t kb_v = (row_l - width)[max(e - (int)bins_cur, 0)];
-                    const int ka = __builtin_amdgcn_readfirstlane((int)ka_v);
-                    const int kb = (int)readlane_u32(kb_v, ka);
-                    s_pick[l] = (uint8_t)ka;               // every lane writes the same byte
-                    s_pick[l - 1] = (uint8_t)kb;
-                    e -= (int)readlane_u32(bins_cur, ka) + (int)readlane_u32(bins_prev, kb);
-                    bad |= (ka >= bstride) | (kb >= bstride) | (e < 0);
-                    e = max(e, 0);
-                    bins_cur = bins_n1;
-                    bins_prev = bins_n2;
-                }
-                if (l == 0) {
-                    const int ka = __builtin_amdgcn_readfirstlane((int)row_l[e]);
-                    s_pick[0] = (uint8_t)ka;
-                    e -= (int)readlane_u32(bins_cur, ka);
-                    bad |= (ka >= bstride) | (e < 0);
-                }
-                if (bad) e = -1;                            // an internal inconsistency
+                e = walk(L, 0, e, s_pick);
             } else if (tid == 0) {
                 if (lds_bins) {
                     for (int l = L - 1; l >= 0; --l) {
@@ -356,9 +694,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             p.result[1] = s_val[0];
             p.result[2] = s_idx[0];
         }
-        // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace
+        // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace;
+        // how the table was swept: 0 in this kernel, G in G groups, 1000 + G in G groups with
+        // ambiguous splits resolved by comparing traced sequences, -G in this kernel after that
+        // resolution gave up
         p.result[3] = (int64_t)(t_sweep - t_begin);
         p.result[4] = (int64_t)(wall_clock64() - t_sweep);
+        p.result[9] = G > 1 ? (grouped ? (resolved ? 1000 + G : G) : -G) : 0;
     }
     __threadfence_system();
     if (tid == 0) p.result[7] = p.seq;
@@ -544,6 +886,13 @@ hipError_t launch_dp_build(const DpBuildParams& p, hipStream_t s, Section* sec) 
 
 constexpr size_t kDpLdsBudget = 140 * 1024;     // dynamic LDS; ~17 KB more is static (160 KB per CU)
 
+// How many layer groups a solve is split into: worth it once the sequential sweep (one pass over
+// the row per entry: layers x entries x cells) takes several times what the extra launches cost.
+static int auto_groups(const DpParams& p) {
+    const double work = (double)p.L * p.max_count * (p.D + 1);
+    return work >= 6e6 ? 8 : (work >= 3e6 ? 4 : 1);
+}
+
 template <typename T, int THREADS>
 static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* sec, bool first) {
     constexpr int kMaxK = (LGRECO_MAX_BINS + 1 + THREADS - 1) / THREADS;
@@ -556,10 +905,70 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* s
     p.pad = padded ? pad : 0;
     p.pd_stride = (p.D + 1 + 3) & ~3;
     size_t lds = ((size_t)p.pad + (size_t)kmax * THREADS) * sizeof(T);
+    const size_t row_lds = lds;
     const size_t bt = (size_t)p.L * p.max_count * sizeof(uint16_t) + (size_t)p.L;
     p.bt_lds = lds + bt <= kDpLdsBudget ? 1 : 0;
     if (p.bt_lds) lds += bt;
     hipError_t err = hipSuccess;
+    // layer groups: 32-bit costs, the padded row, the back-trace tables in LDS, one thread per layer
+    int G = p.groups.G;
+    const bool can_group = sizeof(T) == 4 && padded && p.bt_lds && p.max_count <= 64 && p.L <= THREADS &&
+                           p.groups.nodes && p.groups.range &&
+                           2 * (size_t)(p.D + 1) * sizeof(uint32_t) <= kDpLdsBudget;
+    if (G == 0) G = auto_groups(p);
+    if (!can_group || G < 2) G = 1;
+    if (G > kDpMaxGroups) G = kDpMaxGroups;
+    while (G & (G - 1)) G &= G - 1;                  // a power of two
+    p.groups.G = G;
+    p.groups.stride = p.pd_stride;
+    bool first_pending = first;
+    if (G > 1) {
+        if (p.host_in) {
+            launch_timed(sec, first_pending, false, dp_fetch_kernel, dim3((p.in_vec + 255) / 256), dim3(256), 0, s,
+                         p.host_in, p.dev_in, (int)p.in_vec);
+            first_pending = false;
+            p.host_in = nullptr;
+        }
+#define LGRECO_DPG(K)                                                                              \
+    do {                                                                                           \
+        static bool configured = false;                                                            \
+        if (!configured) {                                                                         \
+            err = hipFuncSetAttribute((const void*)dp_group_kernel<K, THREADS>,                    \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDpLdsBudget); \
+            if (err != hipSuccess) return err;                                                     \
+            configured = true;                                                                     \
+        }                                                                                          \
+        launch_timed(sec, first_pending, false, dp_group_kernel<K, THREADS>, dim3(G), dim3(THREADS), row_lds, s, p); \
+    } while (0)
+        if (kmax == 1) LGRECO_DPG(1);
+        else if (kmax == 2) LGRECO_DPG(2);
+        else if (kmax == 4) LGRECO_DPG(4);
+        else if (kmax == 8) LGRECO_DPG(8);
+        else if (kmax == 16) LGRECO_DPG(16);
+        else LGRECO_DPG(kMaxK);
+#undef LGRECO_DPG
+        first_pending = false;
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        {
+            static bool configured = false;
+            if (!configured) {
+                err = hipFuncSetAttribute((const void*)dp_conv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)kDpLdsBudget);
+                if (err != hipSuccess) return err;
+                configured = true;
+            }
+        }
+        const size_t conv_lds = 2 * (size_t)(p.D + 1) * sizeof(uint32_t);
+        for (int nodes = G / 2; nodes >= 1; nodes /= 2) {      // the level above the leaves first, the root last
+            // two cells per wavefront or more, and no more workgroups than fit the chip at once
+            const int per_node = std::max(1, std::min(256 / nodes, (p.D + 1 + 31) / 32));
+            hipLaunchKernelGGL(dp_conv_kernel, dim3(per_node, nodes), dim3(kConvThreads), conv_lds, s, p.groups,
+                               nodes - 1, (int)p.D, p.L_dev);
+        }
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
 #define LGRECO_DP2(K, PD)                                                                          \
     do {                                                                                           \
         static bool configured = false;   /* the limit is raised once per instantiation */        \
@@ -570,7 +979,7 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* s
             if (err != hipSuccess) return err;                                                     \
             configured = true;                                                                     \
         }                                                                                          \
-        launch_timed(sec, first, true, dp_kernel<T, K, PD, THREADS>, dim3(1), dim3(THREADS), lds, s, p); \
+        launch_timed(sec, first_pending, true, dp_kernel<T, K, PD, THREADS>, dim3(1), dim3(THREADS), lds, s, p); \
     } while (0)
 #define LGRECO_DP(K) do { if (padded) LGRECO_DP2(K, true); else LGRECO_DP2(K, false); } while (0)
     if (kmax == 1) LGRECO_DP(1);

@@ -150,6 +150,15 @@ struct DpApply {
     int32_t L, P;
     int64_t capacity;             // bytes the payload buffer holds
 };
+// Layer groups swept side by side (dp_group_kernel) and joined pairwise (dp_conv_kernel): a
+// complete binary tree in heap order, node 0 the whole table, leaves G-1 .. 2G-2 the groups in
+// layer order, the left child of a node holding the lower layers.
+struct DpGroups {
+    int32_t G = 0;                // in: 0 = let launch_dp decide, 1 = off, 2 / 4 / 8 = forced; out: groups used (0 / 1: none)
+    int32_t stride = 0;           // cells per node array (set by launch_dp, > D)
+    uint32_t* nodes = nullptr;    // [(2G-1) x stride] smallest size of a node's layers per exact bin sum (null: groups off)
+    int32_t* range = nullptr;     // [G x 2] swept layers [begin, end) of every group, written by the group sweeps
+};
 struct DpParams {
     const DpEntry* entries;   // [L x max_count] swept layers only, in candidate order
     const int32_t* count;     // [L] entries per swept layer
@@ -175,6 +184,7 @@ struct DpParams {
     // may poll the pinned result block for it instead of waiting for the stream.
     int64_t seq;
     DpApply apply;
+    DpGroups groups;
 };
 // Entry lists built on the device from the error table (see dp_build_kernel).
 constexpr int kBuildThreads = 1024;   // layers per solve on this path

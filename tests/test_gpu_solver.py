@@ -8,9 +8,9 @@ from oracle import solver
 pytestmark = pytest.mark.gpu
 
 
-def _handle(L, P):
+def _handle(L, P, dp_groups=0):
     from paper_2210_17357_amd import binding as B
-    return B.Handle(1024, L, P)
+    return B.Handle(1024, L, P, dp_groups=dp_groups)
 
 
 def _compare(h, errors, sizes, e_max, n_bins):
@@ -122,3 +122,58 @@ def test_weighted_objective_small_tables_and_bucket_priorities():
     with pytest.raises(B.LgrecoError):
         h.solve_weighted(errors, sizes, np.full(L, 1 << 44, np.int64), e_max, D)     # product overflow
     h.close()
+
+
+@pytest.mark.parametrize("groups", [2, 4, 8])
+def test_layer_groups_give_the_sequential_result_ties_included(groups):
+    """The layers swept in G groups side by side and the groups' tables joined pairwise must give
+    Algorithm 1's assignment bit for bit.  Small integer tables are full of exact ties between
+    different ways of sharing the bins among the groups: those solves must resolve them the way
+    Algorithm 1 would (reported as 1000 + G, or -G if they give up and sweep sequentially), the
+    others go straight through the groups (+G)."""
+    rng = np.random.default_rng(100 + groups)
+    h = _handle(64, 8, dp_groups=groups)
+    modes = []
+    for trial in range(150):
+        L, P, D = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(1, 60))
+        errors = rng.integers(0, 12, (L, P)).astype(np.float64) * 0.25
+        if trial % 4 == 0:
+            errors[:, 0] = 0.0
+        sizes = rng.integers(0, 5, (L, P)).astype(np.int64)
+        _compare(h, errors, sizes, float(rng.integers(0, 40)) * 0.5, D)
+        modes.append(h.last_solve_groups())
+    # tables without structure: real-valued errors, sizes spread over many values -> no ties expected
+    for trial in range(30):
+        L, P, D = int(rng.integers(20, 64)), int(rng.integers(3, 9)), int(rng.integers(200, 3000))
+        base = 10.0 ** rng.uniform(-6, -1, (L, 1))
+        errors = base * np.sort(rng.random((L, P)), axis=1)[:, ::-1] * np.logspace(0, -3, P)
+        sizes = np.sort(rng.integers(1, 1 << 22, (L, P)), axis=1).astype(np.int64)
+        _compare(h, errors, sizes, solver.e_max_uniform(errors, P // 2) * float(rng.uniform(0.3, 1.5)), D)
+        modes.append(h.last_solve_groups())
+    h.close()
+    modes = np.array(modes)
+    assert set(np.unique(modes)) <= {groups, 1000 + groups, -groups, 0}
+    assert (modes[:150] == 1000 + groups).sum() > 5, "no ambiguous split met: the tie-breaks are not exercised"
+    assert (modes[150:] == groups).sum() > 20, "the plain grouped route is hardly taken"
+    print("modes:", {int(m): int((modes == m).sum()) for m in np.unique(modes)})
+
+
+@pytest.mark.parametrize("L,P,D", [(292, 13, 4000), (161, 6, 10000), (97, 49, 10000), (1024, 4, 4090), (300, 9, 16384)])
+def test_layer_groups_on_large_tables(L, P, D):
+    rng = np.random.default_rng(L + P)
+    base = 10.0 ** rng.uniform(-6, -1, (L, 1))
+    errors = base * np.sort(rng.random((L, P)), axis=1)[:, ::-1] * np.logspace(0, -3, P)
+    sizes = (rng.integers(1, 50, (L, 1)) * np.arange(1, P + 1) * 100).astype(np.int64)
+    e_max = solver.e_max_uniform(errors, P // 2)
+    seen = set()
+    for groups in (0, 1, 2, 8):
+        h = _handle(L, P, dp_groups=groups)
+        _compare(h, errors, sizes, e_max, D)
+        seen.add(h.last_solve_groups())
+        _compare(h, errors, sizes, e_max * 0.3, D)
+        # identical layers: wherever two layers differ in their candidate, swapping them ties
+        same_e = np.tile(errors[:1], (L, 1))
+        same_s = np.tile(sizes[:1], (L, 1))
+        _compare(h, same_e, same_s, solver.e_max_uniform(same_e, P // 2), D)
+        h.close()
+    assert seen & {8, 1008, -8}
