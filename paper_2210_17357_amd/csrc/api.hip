@@ -705,10 +705,12 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
         Section sec(h->tm, "topk_collect", true);
         HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s, &sec));
     }
-    if (ntk)
+    if (ntk) {
+        // (the per-layer sums of the quantization errors ride on the scan's launch)
+        const QuantReduce qr{h->d_partials, d_err, P, qp.col, qp.nq};
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
-                           ntk_all <= (int)kMaxTopk, h->tm, s));
-    if (qp.nq) {
+                           ntk_all <= (int)kMaxTopk, h->tm, s, qp.nq ? &qr : nullptr));
+    } else if (qp.nq) {
         Section sec(h->tm, "reduce_partials");
         HIPCHK(launch_reduce_partials(h->d_partials, P, qp.col, qp.nq, h->d_layers, L, d_err, s));
     }
@@ -717,7 +719,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
         HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
-                           first + (int)kMaxTopk >= ntk_all, h->tm, s));
+                           first + (int)kMaxTopk >= ntk_all, h->tm, s, nullptr));
         HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, d_err, P, h->tm, s));
     }
     if (nlr) {

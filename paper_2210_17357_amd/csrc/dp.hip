@@ -432,12 +432,13 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 __syncthreads();
                 const int tpn = kDpThreads / (first + 1);                       // threads per node
                 const int node = first + tid / tpn, t_in = tid % tpn;
-                const int a = s_alloc[node];
+                const bool live = s_tie == 0;                                   // else the shares above are not set
+                const int a = live ? s_alloc[node] : 0;
                 const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
                 const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
                 const uint32_t target = gr.nodes[(size_t)node * gr.stride + a];
                 int cnt = 0, last = -1;
-                if (s_tie == 0) {
+                if (live) {
 #pragma unroll 4
                     for (int e2 = t_in; e2 <= a; e2 += tpn) {
                         const bool ok = Y[e2] + X[a - e2] == target;
@@ -450,7 +451,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                     atomicMax(&s_nlast[node], last);
                 }
                 __syncthreads();
-                if (t_in == 0) {
+                if (t_in == 0 && live) {
                     if (s_ncnt[node] != 1) {
                         s_tie = 1;
                     } else {
@@ -564,6 +565,51 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                 mode = s_slow_ok ? kGroupedWalk : kSeq;
                 resolved = s_slow_ok != 0;
             }
+            if (mode == kGroupedWalk) {
+                // every group walked back from its share, one wavefront each
+                const int g = tid >> 6;
+                if (g < G) {
+                    const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
+                                           __builtin_amdgcn_readfirstlane(s_alloc[G - 1 + g]), s_pick);
+                    if (lane == 0 && e_end != 0) s_walk_bad = 1;
+                }
+                __syncthreads();
+                // The assignment must add up to the root's cell: bins to e*, sizes to the minimum
+                // found there.  Whatever does not (it never should) is swept sequentially instead.
+                long long sum_b = 0, sum_s = 0;
+                int ok = 1;
+                for (int l = tid; l < L; l += kDpThreads) {
+                    const int k = s_pick[l];
+                    ok &= k < p.count[l] ? 1 : 0;
+                    const DpEntry en = p.entries[(size_t)l * bstride + min(k, bstride - 1)];
+                    sum_b += en.bin;
+                    sum_s += en.size;
+                }
+                for (int o = 1; o < 64; o <<= 1) {
+                    sum_b += __shfl_xor(sum_b, o, 64);
+                    sum_s += __shfl_xor(sum_s, o, 64);
+                    ok &= __shfl_xor(ok, o, 64);
+                }
+                long long* const s_tot = reinterpret_cast<long long*>(s_entries);      // [waves][2]: staging is free
+                if (lane == 0) {
+                    s_tot[2 * (tid >> 6)] = sum_b;
+                    s_tot[2 * (tid >> 6) + 1] = sum_s;
+                    if (!ok) s_walk_bad = 1;
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    long long tb = 0, ts = 0;
+                    for (int w = 0; w < kDpThreads / 64; ++w) { tb += s_tot[2 * w]; ts += s_tot[2 * w + 1]; }
+                    if (tb != (long long)s_idx[0] || ts != (long long)s_val[0]) s_walk_bad = 1;
+                }
+                __syncthreads();
+                if (s_walk_bad) {
+                    mode = kSeq;
+                    resolved = false;
+                } else if (tid == 0) {
+                    s_idx[1] = 0;
+                }
+            }
         }
     }
     if (mode == kSeq) {
@@ -576,17 +622,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     uint64_t t_sweep = 0;
     if (tid == 0) t_sweep = wall_clock64();
 
-    if (mode == kGroupedWalk) {
-        // (the host turns groups on only when the bin table fits LDS and lists have at most 64 entries)
-        const int g = tid >> 6;
-        if (g < G) {
-            const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
-                                   __builtin_amdgcn_readfirstlane(s_alloc[G - 1 + g]), s_pick);
-            if (lane == 0 && e_end != 0) s_walk_bad = 1;
-        }
-        __syncthreads();
-        if (tid == 0) s_idx[1] = s_walk_bad ? -1 : 0;
-    } else if (mode == kSeq && tid < 64) {
+    if (mode == kSeq && tid < 64) {
         if (s_val[0] < (int64_t)kInf) {
             int e = __builtin_amdgcn_readfirstlane(s_idx[0]);
             if (lds_bins && bstride <= 64) {

@@ -272,9 +272,18 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
                         const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec);
 // exact threshold bins from the histogram; layers whose predicted bound was too high are
 // collected again with the exact one
+// quant (may be null): the quantization profile's per-tile partial sums, reduced per layer by extra
+// workgroups of the scan's launch instead of a kernel of their own
+struct QuantReduce {
+    const double* partials;
+    double* errors;
+    int stride;
+    const int* cols;
+    int ncols;
+};
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                        const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, bool last_group,
-                       Timing* tm, hipStream_t s);
+                       Timing* tm, hipStream_t s, const QuantReduce* quant);
 // refinement on the candidates: exact thresholds; writes the dropped energy to errors (if not null)
 hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
                          const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);

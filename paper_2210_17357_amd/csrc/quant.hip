@@ -16,6 +16,7 @@
 // spread over the row's 16 lanes (lane c: unit of candidate c, lane 8+c: inv of candidate c)
 // and broadcast back with row_newbcast.
 #include "internal.h"
+#include "reduce_dev.h"
 #include "topk_dev.h"
 
 namespace lgreco {
@@ -257,38 +258,12 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
     }
 }
 
-// errors[l][c] = sum of the layer's tile partials in tile order (fixed tree -> reproducible).
-struct ReduceCols {
-    int32_t n;
-    int32_t col[kMaxQuant];
-};
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const double* __restrict__ partials,
                                                                int stride, ReduceCols cols,
                                                                const DevLayer* __restrict__ layers,
                                                                double* __restrict__ errors) {
-    // all columns together: per thread the same strided sums, then the same tree per column
     __shared__ double s[kMaxQuant][256];
-    const DevLayer L = layers[blockIdx.x];
-    double a[kMaxQuant];
-#pragma unroll
-    for (int ci = 0; ci < kMaxQuant; ++ci) a[ci] = 0.0;
-    for (int t = L.tile_begin + threadIdx.x; t < L.tile_end; t += 256) {
-#pragma unroll
-        for (int ci = 0; ci < kMaxQuant; ++ci)
-            if (ci < cols.n) a[ci] += partials[(size_t)t * stride + cols.col[ci]];
-    }
-#pragma unroll
-    for (int ci = 0; ci < kMaxQuant; ++ci) s[ci][threadIdx.x] = a[ci];
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) {
-#pragma unroll
-            for (int ci = 0; ci < kMaxQuant; ++ci)
-                if (ci < cols.n) s[ci][threadIdx.x] += s[ci][threadIdx.x + o];
-        }
-        __syncthreads();
-    }
-    if ((int)threadIdx.x < cols.n) errors[(size_t)blockIdx.x * stride + cols.col[threadIdx.x]] = s[threadIdx.x][0];
+    reduce_partials_block(partials, stride, cols, layers, errors, (int)blockIdx.x, s);
 }
 
 // ------------------------------------------------------------------------- compressor

@@ -29,6 +29,7 @@
 #include <cstring>
 
 #include "internal.h"
+#include "reduce_dev.h"
 #include "topk_dev.h"
 
 namespace lgreco {
@@ -51,8 +52,9 @@ struct TopkLayer {
 constexpr int kRefTiles = 8;        // largest tiles per refinement / sample workgroup (fewer elements never: with
                                     // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
+constexpr int kRefSlots = 512;      // refinement workgroups the chip runs at a time (256 CUs x 2)
 constexpr int kBinsA = 1024, kBinsB = 512;
-constexpr int kPickThreads = 512;
+constexpr int kPickThreads = 1024;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 constexpr uint32_t kHintMargin = 2; // coarse bins (4.4 % in magnitude each) between a remembered threshold and the bound derived from it
 
@@ -337,7 +339,18 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (EMIT) store_stream(reinterpret_cast<float4*>(eo) + v + 64 * h, a[h]);
+                if (EMIT && KNOWN) {
+                    // nearly every candidate is kept here: candidates are written as zero at once, the
+                    // emit step puts the few that are not kept back
+                    float4 w = a[h];
+                    w.x = mag_bits(w.x) >= bound ? 0.0f : w.x;
+                    w.y = mag_bits(w.y) >= bound ? 0.0f : w.y;
+                    w.z = mag_bits(w.z) >= bound ? 0.0f : w.z;
+                    w.w = mag_bits(w.w) >= bound ? 0.0f : w.w;
+                    store_stream(reinterpret_cast<float4*>(eo) + v + 64 * h, w);
+                } else if (EMIT) {
+                    store_stream(reinterpret_cast<float4*>(eo) + v + 64 * h, a[h]);
+                }
                 if (HIST) {
                     atomicAdd(&s_hist[mag_bits(a[h].x) >> kHistShift], 1u);
                     atomicAdd(&s_hist[mag_bits(a[h].y) >> kHistShift], 1u);
@@ -365,7 +378,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             const bool valid = i < t.count;
             float x = 0.0f;
             if (valid) x = ep ? gp[i] + ep[i] : gp[i];
-            if (EMIT && valid) eo[i] = x;
+            if (EMIT && valid) eo[i] = (KNOWN && mag_bits(x) >= bound) ? 0.0f : x;
             if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
             if (KNOWN && valid && mag_bits(x) - bound < (uint32_t)kBinsB) atomicAdd(&s_hist[mag_bits(x) - bound], 1u);
             col.take(x, valid, (uint32_t)(t.pos + i));
@@ -464,12 +477,29 @@ __global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams 
 
 // One workgroup per layer: threshold bin and in-bin rank for every requested k; threshold-bin
 // lists; check of the predicted bound.
+// Workgroups past the first n_layers (when the call also profiles quantization) sum that family's
+// tile partials per layer instead: the two jobs depend on the main pass only and share a launch.
+struct ScanReduce {
+    const double* partials;     // null: no such workgroups
+    double* errors;
+    const DevLayer* layers;
+    int32_t stride;
+    ReduceCols cols;
+};
 __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ hist,
                                                         const uint32_t* __restrict__ ks, int ntk,
                                                         const int64_t* __restrict__ cand_base,
                                                         const uint32_t* lo_in, uint32_t* lo_out,
-                                                        TopkLayer* __restrict__ tl, uint32_t* hint, int clear) {
-    __shared__ uint32_t s_hist[kHistBins];
+                                                        TopkLayer* __restrict__ tl, uint32_t* hint, int clear,
+                                                        int n_layers, ScanReduce red) {
+    __shared__ __align__(16) unsigned char s_raw[sizeof(uint32_t) * kHistBins];   // 16 KB: the histogram, or the reduction's tree
+    static_assert(sizeof(s_raw) >= sizeof(double) * kMaxQuant * 256, "shared by both jobs");
+    if ((int)blockIdx.x >= n_layers) {
+        reduce_partials_block(red.partials, red.stride, red.cols, red.layers, red.errors, (int)blockIdx.x - n_layers,
+                              reinterpret_cast<double(*)[256]>(s_raw));
+        return;
+    }
+    uint32_t* const s_hist = reinterpret_cast<uint32_t*>(s_raw);
     __shared__ uint32_t s_scan[256];
     __shared__ uint32_t s_res[2 * kMaxTopk];
     const int l = blockIdx.x;
@@ -773,7 +803,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
         uint32_t c[4] = {0, 0, 0, 0};
         unsigned long long e[4] = {0, 0, 0, 0};
         const size_t off = (size_t)S.list * kBinsA + t;
-#pragma unroll 4
+#pragma unroll 8
         for (int wg = wr.x + grp; wg < wr.y; wg += kPickThreads / 256) {
             const size_t i = (size_t)wg * kMaxTopk * kBinsA + off;
 #pragma unroll
@@ -865,10 +895,10 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     block_kth_from_top(s_hist, kBinsB, need_a, s_scan, s_res);
     const uint32_t thr_b = s_res[0], keep_at_thr = need_a - s_res[1];
     // dropped inside the sub-bin: every pattern below the threshold pattern, and the entries equal
-    // to it that are not kept; one cell per thread (kBinsB == kPickThreads), fixed tree
-    static_assert(kBinsB == kPickThreads, "one cell per thread");
+    // to it that are not kept; one cell per thread, fixed tree
+    static_assert(kBinsB <= kPickThreads, "one cell per thread");
     double mine = 0.0;
-    {
+    if (tid < kBinsB) {
         const uint32_t c = s_hist[tid];
         const uint32_t n_drop = (uint32_t)tid < thr_b ? c : ((uint32_t)tid == thr_b ? c - keep_at_thr : 0u);
         const double v = (double)__uint_as_float((prefix << 9) | (uint32_t)tid);
@@ -1081,7 +1111,8 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long m, uint32_t a
 
 // Kept values and indices in ascending index order, from the candidates alone (every kept entry
 // is a candidate, and a wavefront's candidates are stored in element order); the error feedback,
-// already written as x everywhere by the collection pass, is zeroed at the kept entries.
+// already written as x everywhere by the collection pass, is zeroed at the kept entries (KNOWN:
+// written as zero at every candidate by that pass, and set back to x at those not kept).
 template <bool KNOWN>
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ e,
                                                               const DevLayer* __restrict__ layers,
@@ -1173,7 +1204,10 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
                 const uint32_t pos = S[q].out + lanes_below(kq, 0u);
                 S[q].values[pos] = __uint_as_float(pat[q] | (ix[q] & 0x80000000u));
                 S[q].indices[pos] = ix[q] & 0x7FFFFFFFu;
-                S[q].ef[ix[q] & 0x7FFFFFFFu] = 0.0f;
+                if (!KNOWN) S[q].ef[ix[q] & 0x7FFFFFFFu] = 0.0f;
+            } else if (KNOWN && ok) {
+                // the main pass wrote zero for every candidate: the ones that are not kept get x back
+                S[q].ef[ix[q] & 0x7FFFFFFFu] = __uint_as_float(pat[q] | (ix[q] & 0x80000000u));
             }
             S[q].out += (uint32_t)__popcll(kq);
         }
@@ -1208,7 +1242,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
-    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile)) + 2 * max_layers + 2;
+    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile / 4)) + 2 * max_layers + 2;   // smallest work items
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
     t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
@@ -1305,7 +1339,29 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                       const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
     (void)n_tiles;
-    const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
+    // Tiles per work item of the sample / refinement kernels: at most 2^19 elements, and no less than
+    // a quarter of that.  Those kernels run two 1024-thread workgroups per CU, kRefSlots at a time,
+    // and take (rounds of kRefSlots work items) x (tiles per item): the size is picked to fill its
+    // last round (355 M elements in 292 layers: 11 tiles of 32768 instead of 16, two full rounds
+    // instead of one and a third).
+    const int group_max = kRefTiles * (kTile / tile_elems);
+    int group = group_max;
+    {
+        double best = 0.0;
+        for (int g = group_max; g >= std::max(1, group_max / 4); --g) {
+            int64_t items = 0;                                   // work items that hold at least half a share
+            for (int l = 0; l < L; ++l) {
+                if (!ks[(size_t)l * kMaxTopk]) continue;
+                const int nt = h_layers[l].tile_end - h_layers[l].tile_begin;
+                items += nt / g + ((nt % g) * 2 >= g ? 1 : 0);
+            }
+            const double cost = (double)((items + kRefSlots - 1) / kRefSlots) * g;
+            if (g == group_max || cost < best * 0.97) {          // a smaller size has to pay for its extra partial sums
+                best = cost;
+                group = g;
+            }
+        }
+    }
     TK_CHECK(ctl_writable(t));
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
@@ -1402,14 +1458,24 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
 // exact threshold bins; layers whose predicted bound was too high are collected again
 hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
                        const Tile* d_tiles, int L, int n_tiles, int ntk, bool first_group, bool last_group,
-                       Timing* tm, hipStream_t s) {
+                       Timing* tm, hipStream_t s, const QuantReduce* quant) {
     {
         Section sec(tm, "topk_scan");
         // the first group of a call holds the lowest thresholds: it leaves the bound for the next call
         uint32_t* const hint = (first_group && t->reuse_thresholds) ? t->d_hint[t->cur_slot] : nullptr;
-        hipLaunchKernelGGL(topk_scan_kernel, dim3(L), dim3(256), 0, s, t->d_hist, (const uint32_t*)t->d_k, ntk,
-                           (const int64_t*)t->d_cand_base, first_group ? t->lo_src : (const uint32_t*)t->d_lo,
-                           t->d_lo, (TopkLayer*)t->d_tl, hint, last_group ? 1 : 0);
+        ScanReduce red{};
+        if (quant) {
+            red.partials = quant->partials;
+            red.errors = quant->errors;
+            red.layers = d_layers;
+            red.stride = quant->stride;
+            red.cols.n = std::min(quant->ncols, (int)kMaxQuant);
+            for (int i = 0; i < red.cols.n; ++i) red.cols.col[i] = quant->cols[i];
+        }
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(quant ? 2 * L : L), dim3(256), 0, s, t->d_hist,
+                           (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base,
+                           first_group ? t->lo_src : (const uint32_t*)t->d_lo, t->d_lo, (TopkLayer*)t->d_tl, hint,
+                           last_group ? 1 : 0, L, red);
         TK_CHECK(hipGetLastError());
         if (hint) t->hint_valid[t->cur_slot] = true;
         if (last_group) t->hist_clean = true;
@@ -1500,7 +1566,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
         Section sec(tm, "topk_collect", true);
         TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s, &sec));
     }
-    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s));
+    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s, nullptr));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
