@@ -162,9 +162,9 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
 
     def fresh_ef(i):
         return ef0_list[i % n_buf].clone() if has_ef else zeros.clone()
-    # The one-call form hands one error-feedback buffer to profile and compression; a workload whose
-    # profile runs without one (NULL, half the read traffic) keeps the two-call form.
-    calls = "two" if (args.calls == "one" and not has_ef) else args.calls
+    # The one-call form hands one error-feedback buffer to profile and compression: a workload that
+    # states none gets a buffer of zeros (x = g + 0), as in the first step of a training run.
+    calls = args.calls
     level = 0 if args.no_kernel_timing else (2 if args.detail else 1)
     sizes_tab = B.sizes(layers, ctab, w.bucket)
     payload = torch.empty(int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1), dtype=torch.uint8, device=dev)
@@ -236,7 +236,7 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     # algorithmic bytes per element and elements covered per launch, per timed section: streaming
     # reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g
     # and e and writes e
-    rd = 8.0 if has_ef else 4.0
+    rd = 8.0 if (has_ef or calls == "one") else 4.0
     algo, elems = {}, {}
     for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
         algo["profile/" + k], elems["profile/" + k] = rd, float(N)

@@ -86,6 +86,7 @@ struct lgreco_handle {
     // selection records it left on the device (valid while they number at most one group)
     int last_ntk = 0;
     int last_tk_col[kMaxTopk] = {};
+    int last_nlr = 0;                    // low-rank candidates of the last profile call
     std::vector<DpEntry> build_entries;  // [max_layers x LGRECO_MAX_CANDS] host scratch of lgreco_solve
 
     // One set of timing events per kind of call (LGRECO_CALL_*): a call that returns before its
@@ -109,6 +110,7 @@ DpGroups dp_groups(const lgreco_handle* h) {
     g.G = h->cfg.dp_groups;             // 0: chosen per solve from its size
     g.nodes = h->d_dp_nodes;
     g.range = h->d_dp_range;
+    g.flag = h->d_dp_range + 2 * kMaxDpGroups;
     return g;
 }
 
@@ -119,6 +121,8 @@ struct EarlyCompress {
     int64_t capacity;
     int phase = -1;          // the compress call's phase bracket, opened with that kernel
     bool topk_known = false; // the Top-K layers' kernels were queued too (see topk_compress_known)
+    bool lowrank_known = false;   // ... and the low-rank layers' (see lowrank_compress_known)
+    float* d_q = nullptr;    // warm start, updated by the low-rank compression
     bool launched = false;   // the quantization kernel was queued right behind the solver kernel
     bool applied = false;    // ... and ran on layer records the solver kernel wrote from its result
 };
@@ -424,7 +428,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     h->h_choice = reinterpret_cast<int32_t*>(h->h_dp_out + sizeof(int64_t) * kDpResultSlots);
     HIPCHK_C(hipMalloc(&h->d_pd, (size_t)max_layers * (LGRECO_MAX_BINS + 4)));
     HIPCHK_C(hipMalloc(&h->d_dp_nodes, sizeof(uint32_t) * (2 * kMaxDpGroups - 1) * (LGRECO_MAX_BINS + 4)));
-    HIPCHK_C(hipMalloc(&h->d_dp_range, sizeof(int32_t) * 2 * kMaxDpGroups));
+    HIPCHK_C(hipMalloc(&h->d_dp_range, sizeof(int32_t) * (2 * kMaxDpGroups + 4)));
     HIPCHK_C(hipHostMalloc(&h->h_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16, hipHostMallocDefault));
     HIPCHK_C(hipMalloc(&h->d_sizes, sizeof(int64_t) * (size_t)max_layers * max_cands + 16));
     HIPCHK_C(hipMalloc(&h->d_errors_dev, sizeof(double) * (size_t)max_layers * max_cands + 16));
@@ -641,6 +645,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
             lr_col[nlr++] = c;
         }
     }
+    h->last_nlr = nlr;
     if (nlr) {
         if (!d_q0) return LGRECO_EINVAL;
         for (int l = 0; l < L; ++l)
@@ -956,7 +961,9 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         begin_call(h, s, LGRECO_CALL_COMPRESS);
         h->hl_uploaded.clear();
         ec->phase = h->tm->open_phase("phase_compress");
-        {
+        bool any_quant = false;
+        for (int c = 0; c < P; ++c) any_quant = any_quant || cands[c].family == LGRECO_QUANT;
+        if (any_quant) {
             Section sec(h->tm, "quant_compress", true);
             HIPCHK(launch_quant_compress(d_grads, ec->d_ef, h->d_layers, h->d_tiles, (int)h->ht.size(), ec->d_payload,
                                          h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
@@ -967,6 +974,13 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
             // this very data: the chosen density's record is picked on the device
             HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
                                        ec->d_payload, h->tm, s));
+        }
+        ec->lowrank_known = h->last_nlr > 0 && ec->d_q != nullptr;
+        if (ec->lowrank_known) {
+            // ... and the low-rank layers': the factors of every rank are the leading columns of
+            // the rank-64 run the profile just made on this data
+            HIPCHK(lowrank_compress_known(&h->lowrank, d_grads, ec->d_ef, h->d_layers, ec->d_q, h->cfg.r_max,
+                                          ec->d_payload, h->tm, s));
         }
         // the compress call stays open until lgreco_compress's part has queued the rest: nobody
         // reads its events out before (that would wait for the kernel just queued)
@@ -1121,7 +1135,7 @@ static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, 
         HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
                              h->tile_elems, d_payload, h->tm, s));
     }
-    if (any[LGRECO_LOWRANK]) {
+    if (any[LGRECO_LOWRANK] && !(quant_done && ec->lowrank_known)) {
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,
                                 d_payload, h->tm, s));
     }
@@ -1145,6 +1159,7 @@ int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, floa
     if (!h || !d_grads || !d_ef || !d_payload || !offsets || payload_capacity < 0) return LGRECO_EINVAL;
     if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
     EarlyCompress ec{d_ef, d_payload, payload_capacity};
+    ec.d_q = d_q;
     int st = profile_solve_impl(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
                                 e_max, choice, total_size, total_error, stream, &ec);
     if (st != LGRECO_OK) return st;

@@ -247,418 +247,103 @@ __global__ __launch_bounds__(256) void dp_fetch_kernel(const uint4* __restrict__
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) dst[i] = src[i];
 }
 
-template <typename T, int KMAX, bool PADDED, int kDpThreads>
-__global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
-    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*threads-1 (cells above D stay infinite).
-    // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
-    extern __shared__ unsigned char dp_smem[];
-    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
-    __shared__ DpEntry s_entries[kDpStageEntries];      // [layers of the stage][max_count]
-    __shared__ int32_t s_count[kDpStageMax];
-    __shared__ int64_t s_val[kDpThreads / 64];
-    __shared__ int32_t s_idx[kDpThreads / 64];
+// ---- pieces shared by the sequential kernel and the kernel that traces a grouped solve
+
+// arg-min of src[0..D], lowest e among equal minima -> s_val[0], s_idx[0] (every thread calls)
+template <typename T, int kDpThreads>
+__device__ __forceinline__ void dp_argmin(const T* src, const int D, int64_t* const s_val, int32_t* const s_idx) {
     const int tid = threadIdx.x, lane = tid & 63;
-    const int D = p.D;
-    const int64_t width = p.pd_stride;
-    constexpr T kInf = DpInf<T>::v;
-    // back-trace tables behind the row when they fit (the host decides): the bin of every entry
-    // (16 bits: D <= 16384) and the picked entry per layer
-    const bool lds_bins = p.bt_lds != 0;
-    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
-    const int bstride = p.max_count;
-    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
-    // Entry lists built on the device (dp_build_kernel): the number of swept layers and the status
-    // it found come from memory; anything but "ok" there ends the solve.
-    int L = p.L;
-    if (p.L_dev) {
-        if (p.L_dev[1] != 0) {            // the build kernel reported the status; only the hand-over is left
-            if (p.apply.layers)
-                for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
-            if (tid == 0) {
-                p.result[8] = 0;
-                __threadfence_system();
-                p.result[7] = p.seq;
-            }
-            return;
-        }
-        L = p.L_dev[0];
+    int64_t bv = (int64_t)DpInf<T>::v;
+    int32_t be = 0x7FFFFFFF;
+    for (int e = tid; e <= D; e += kDpThreads) {
+        const int64_t v = (int64_t)src[e];
+        if (v < bv) { bv = v; be = e; }              // e ascending per thread -> keeps the lowest
     }
-
-    // for the apply step at the end (see DpApply): the build's report for this thread's layer,
-    // fetched now so that the tail does not wait for it
-    int32_t pre_fixed = 0, pre_sweep = 0;
-    if (p.apply.layers) {
-        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
-        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
+    for (int o = 1; o < 64; o <<= 1) {
+        const int64_t ov = __shfl_xor(bv, o, 64);
+        const int32_t oe = __shfl_xor(be, o, 64);
+        if (ov < bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
     }
-    const uint64_t t_begin = wall_clock64();
-    if (p.host_in) {
-        // fetch the input block from the host's pinned memory: one 16-byte word per thread and
-        // round, all in flight together; the barrier below orders it before the first read
-        for (int i = tid; i < p.in_vec; i += kDpThreads) p.dev_in[i] = p.host_in[i];
-        __threadfence_block();
-    }
-
-    // arg-min of the row in LDS, lowest e among equal minima -> s_val[0], s_idx[0] (all threads call)
-    auto argmin_row = [&]() {
-        int64_t bv = (int64_t)kInf;
-        int32_t be = 0x7FFFFFFF;
-        for (int e = tid; e <= D; e += kDpThreads) {
-            const int64_t v = (int64_t)row[e];
-            if (v < bv) { bv = v; be = e; }              // e ascending per thread -> keeps the lowest
-        }
-        for (int o = 1; o < 64; o <<= 1) {
-            const int64_t ov = __shfl_xor(bv, o, 64);
-            const int32_t oe = __shfl_xor(be, o, 64);
-            if (ov < bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
-        }
-        __syncthreads();                              // earlier readers of s_val / s_idx are done
-        if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
-        __syncthreads();
-        if (tid < 64) {
-            // the first wavefront: every lane joins the per-wavefront minima the same way
-            for (int w = 1; w < kDpThreads / 64; ++w)
-                if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
-        }
-        __syncthreads();
-        if (tid == 0) { s_val[0] = bv; s_idx[0] = be; }
-        __syncthreads();
-    };
-
-    // The walk is a chain of dependent loads: one PD byte per layer from global memory, the bin it
-    // stands for from LDS when the table fits there.  One wavefront walks the swept layers
-    // [l_lo, l_hi) downwards from cell e, writes the picked entry of every layer to out[layer]
-    // and returns the cell it ends in (0 if all is consistent).
-    // Two layers per load latency: lane j holds the bin of entry j of layer l, so while PD[l][e]
-    // is on its way lane j already fetches PD[l-1][e - bin_j], the byte the walk needs next if
-    // entry j is the one picked.  A wavefront runs alone here and every instruction costs its
-    // full issue latency, so the loop is kept short: rows by a running pointer, no branches,
-    // consistency checks joined into one flag (a bad byte still gives in-row addresses: e only
-    // shrinks and is clamped at 0, lanes past the list hold bin 0).
-    auto walk = [&](const int l_hi, const int l_lo, int e, uint8_t* const out) -> int {
-        auto bins_of = [&](int layer) -> uint32_t {
-            return lane < bstride ? (uint32_t)s_bins[max(layer, 0) * bstride + lane] : 0u;
-        };
-        int l = l_hi - 1;
-        uint32_t bins_cur = bins_of(l), bins_prev = bins_of(l - 1);
-        const uint8_t* __restrict__ row_l = p.pd + (size_t)max(l, 0) * width;
-        int bad = 0;
-        for (; l >= l_lo + 1; l -= 2, row_l -= 2 * width) {
-            const uint32_t bins_n1 = bins_of(l - 2), bins_n2 = bins_of(l - 3);
-            const uint32_t ka_v = row_l[e];
-            const uint32_t kb_v = (row_l - width)[max(e - (int)bins_cur, 0)];
-            const int ka = __builtin_amdgcn_readfirstlane((int)ka_v);
-            const int kb = (int)readlane_u32(kb_v, ka);
-            out[l] = (uint8_t)ka;                  // every lane writes the same byte
-            out[l - 1] = (uint8_t)kb;
-            e -= (int)readlane_u32(bins_cur, ka) + (int)readlane_u32(bins_prev, kb);
-            bad |= (ka >= bstride) | (kb >= bstride) | (e < 0);
-            e = max(e, 0);
-            bins_cur = bins_n1;
-            bins_prev = bins_n2;
-        }
-        if (l == l_lo && l_hi > l_lo) {
-            const int ka = __builtin_amdgcn_readfirstlane((int)row_l[e]);
-            out[l] = (uint8_t)ka;
-            e -= (int)readlane_u32(bins_cur, ka);
-            bad |= (ka >= bstride) | (e < 0);
-        }
-        return bad ? -1 : e;                        // -1: an internal inconsistency
-    };
-
-    // Grouped mode (see dp_group_kernel / dp_conv_kernel): the layers were swept in G groups side
-    // by side and the groups' cost functions joined pairwise; node 0 of the tree is the last row of
-    // the whole table.  Walking down the tree gives every group its share of the bins: at an inner
-    // node holding e bins the split is the e2 with Y[e2] + X[e - e2] = T[e].  Where several e2
-    // attain it, Algorithm 1's tie-breaks decide (lowest candidate index, last layer first): the
-    // split whose higher-layer child Y traces back to the lexicographically smallest sequence of
-    // picks, compared from Y's last layer down (slow path below).  A solve the slow path gives up
-    // on (too many candidates) is swept here as if there were no groups.
-    constexpr int kSplitCap = 16, kWalkBudget = 96, kTreeDepth = 3;
-    static_assert((1 << kTreeDepth) == kDpMaxGroups, "the slow path is written out for this depth");
-    __shared__ int32_t s_alloc[2 * kDpMaxGroups], s_ncnt[2 * kDpMaxGroups], s_nlast[2 * kDpMaxGroups];
-    __shared__ int32_t s_tie, s_walk_bad, s_slow_ok;
-    const int G = p.groups.G;
-    const DpGroups& gr = p.groups;
-    // every e2 with Y[e2] + X[e - e2] = T[e] of an inner node, up to kSplitCap of them in out[] (in
-    // no particular order); the whole block scans (every thread calls, with the same arguments);
-    // returns how many there are, which may be more than fit out[]
-    __shared__ int32_t s_nsplit;
-    auto splits_of = [&](const int node, const int e, int32_t* const out) -> int {
-        const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
-        const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
-        const uint32_t target = gr.nodes[(size_t)node * gr.stride + e];
-        __syncthreads();                              // earlier readers of s_nsplit / out are done
-        if (tid == 0) s_nsplit = 0;
-        __syncthreads();
-        if (target < (uint32_t)kInf) {
-#pragma unroll 4
-            for (int e2 = tid; e2 <= e; e2 += kDpThreads) {
-                if (Y[e2] + X[e - e2] == target) {
-                    const int pos = atomicAdd(&s_nsplit, 1);
-                    if (pos < kSplitCap) out[pos] = e2;
-                }
-            }
-        }
-        __syncthreads();
-        return s_nsplit;
-    };
-    // first and last swept layer of the leaves under a node of the tree
-    auto layers_of = [&](int node, int* lo, int* hi) {
-        int a = node, b = node;
-        while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
-        *lo = gr.range[2 * (a - (G - 1))];
-        *hi = gr.range[2 * (b - (G - 1)) + 1];
-    };
-    enum { kSeq = 0, kGroupedWalk = 1, kGroupedInfeasible = 3 };
-    int mode = kSeq;                                  // block-uniform
-    bool resolved = false;                            // ambiguous splits were met and resolved
-    if (G > 1) {
-        for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads)
-            row[e] = (e >= 0 && e <= D) ? (T)gr.nodes[e] : kInf;
-        if (tid == 0) { s_tie = 0; s_walk_bad = 0; s_slow_ok = 0; }
-        __syncthreads();
-        argmin_row();
-        if (s_val[0] >= (int64_t)kInf) {
-            mode = kGroupedInfeasible;                // no assignment fits: nothing to trace
-        } else {
-            // the bin of every entry, for the walks (in sequential mode the sweep leaves them)
-            for (int i = tid; i < L * bstride; i += kDpThreads) s_bins[i] = (uint16_t)p.entries[i].bin;
-            if (tid == 0) s_alloc[0] = s_idx[0];
-            // fast path, level by level: the threads share out the nodes of a level and each node's
-            // e2 range; a node where not exactly one e2 matches ends it
-            for (int first = 0; first < G - 1; first = 2 * first + 1) {         // nodes first .. 2 first
-                if (tid < 2 * kDpMaxGroups) { s_ncnt[tid] = 0; s_nlast[tid] = -1; }
-                __syncthreads();
-                const int tpn = kDpThreads / (first + 1);                       // threads per node
-                const int node = first + tid / tpn, t_in = tid % tpn;
-                const bool live = s_tie == 0;                                   // else the shares above are not set
-                const int a = live ? s_alloc[node] : 0;
-                const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
-                const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
-                const uint32_t target = gr.nodes[(size_t)node * gr.stride + a];
-                int cnt = 0, last = -1;
-                if (live) {
-#pragma unroll 4
-                    for (int e2 = t_in; e2 <= a; e2 += tpn) {
-                        const bool ok = Y[e2] + X[a - e2] == target;
-                        cnt += ok ? 1 : 0;
-                        last = ok ? e2 : last;
-                    }
-                }
-                if (cnt) {
-                    atomicAdd(&s_ncnt[node], cnt);
-                    atomicMax(&s_nlast[node], last);
-                }
-                __syncthreads();
-                if (t_in == 0 && live) {
-                    if (s_ncnt[node] != 1) {
-                        s_tie = 1;
-                    } else {
-                        s_alloc[2 * node + 2] = s_nlast[node];
-                        s_alloc[2 * node + 1] = a - s_nlast[node];
-                    }
-                }
-                __syncthreads();
-            }
-            __syncthreads();
-            if (s_tie == 0) {
-                mode = kGroupedWalk;
-            } else {
-                // slow path: resolve every ambiguous split by comparing the sequences of picks its
-                // candidates lead to in the higher-layer child, then walk as above.  Every thread
-                // runs the same control flow (all decisions come from LDS); the scans use the whole
-                // block, the walks one wavefront per group, the comparisons the first wavefront.
-                {
-                    uint8_t* const bufs = reinterpret_cast<uint8_t*>(s_entries) + 1024;     // [depth][2][L <= 1024]
-                    int32_t* const cands = reinterpret_cast<int32_t*>(s_entries) + 2048;    // behind the buffers: [depth][cap]
-                    int32_t* const saved = cands + kTreeDepth * kSplitCap;                  // [depth][2 G] shares of the best candidate
-                    static_assert(sizeof(s_entries) >= 8192 + 4 * kTreeDepth * (kSplitCap + 2 * kDpMaxGroups),
-                                  "staging area too small");
-                    int budget = kWalkBudget;         // candidates looked at; the same in every thread
-                    // picks of [lo, hi) compared from the last layer down: is a before b?
-                    auto before = [&](const uint8_t* a, const uint8_t* b, int lo, int hi) -> bool {
-                        if (tid < 64) {
-                            int res = 0;
-                            for (int top = hi - 1; top >= lo; top -= 64) {
-                                const int l = top - lane;
-                                const int da = l >= lo ? a[l] : 0, db = l >= lo ? b[l] : 0;
-                                const unsigned long long m = __ballot(da != db);
-                                if (m) {
-                                    const int firstl = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
-                                    res = (int)readlane_u32((uint32_t)(da < db), firstl);
-                                    break;
-                                }
-                            }
-                            if (lane == 0) s_nlast[0] = res;
-                        }
-                        __syncthreads();
-                        const bool r = s_nlast[0] != 0;
-                        __syncthreads();
-                        return r;
-                    };
-                    // picks of every group under `node`, each from the share s_alloc gives it: one
-                    // wavefront per group, side by side
-                    auto walk_under = [&](int node, uint8_t* out) -> bool {
-                        int a = node, b = node;
-                        while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
-                        if (tid == 0) s_nlast[1] = 0;
-                        __syncthreads();
-                        const int leafn = a + (tid >> 6);
-                        if (leafn <= b) {
-                            const int g = leafn - (G - 1);
-                            const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
-                                                   __builtin_amdgcn_readfirstlane(s_alloc[leafn]), out);
-                            if (lane == 0 && e_end != 0) s_nlast[1] = 1;
-                        }
-                        __syncthreads();
-                        const bool ok = s_nlast[1] == 0;
-                        __syncthreads();
-                        return ok;
-                    };
-                    // the shares of every node under `node` holding e bins -> s_alloc
-                    auto share = [&](auto&& deeper, int level, int node, int e) -> bool {
-                        if (tid == 0) s_alloc[node] = e;
-                        if (node >= G - 1) return true;
-                        int32_t* const cd = cands + level * kSplitCap;
-                        const int cnt = splits_of(node, e, cd);
-                        if (cnt < 1 || cnt > kSplitCap) return false;
-                        int pick = 0;
-                        if (cnt > 1) {
-                            int lo, hi;
-                            layers_of(2 * node + 2, &lo, &hi);
-                            uint8_t* best = bufs + (size_t)(2 * level) * 1024;
-                            uint8_t* cur = bufs + (size_t)(2 * level + 1) * 1024;
-                            int32_t* const keep = saved + level * 2 * kDpMaxGroups;
-                            for (int i = 0; i < cnt; ++i) {
-                                if (--budget < 0) return false;
-                                if (!deeper(2 * node + 2, cd[i])) return false;
-                                if (!walk_under(2 * node + 2, i == 0 ? best : cur)) return false;
-                                const bool better = i > 0 && before(cur, best, lo, hi);
-                                if (better) {
-                                    uint8_t* t = best; best = cur; cur = t;
-                                    pick = i;
-                                }
-                                if (i == 0 || better) {
-                                    if (tid < 2 * kDpMaxGroups) keep[tid] = s_alloc[tid];
-                                    __syncthreads();
-                                }
-                            }
-                            if (tid < 2 * kDpMaxGroups) s_alloc[tid] = keep[tid];     // the best candidate's shares
-                            __syncthreads();
-                        } else if (!deeper(2 * node + 2, cd[0])) {
-                            return false;
-                        }
-                        return deeper(2 * node + 1, e - cd[pick]);
-                    };
-                    auto leaf_share = [&](int n, int ee) -> bool {
-                        if (tid == 0) s_alloc[n] = ee;
-                        return true;
-                    };
-                    auto share2 = [&](int node, int e) -> bool { return share(leaf_share, 2, node, e); };
-                    auto share1 = [&](int node, int e) -> bool { return share(share2, 1, node, e); };
-                    const bool ok = share(share1, 0, 0, s_idx[0]);
-                    __syncthreads();
-                    if (tid == 0) s_slow_ok = ok ? 1 : 0;
-                }
-                __syncthreads();
-                mode = s_slow_ok ? kGroupedWalk : kSeq;
-                resolved = s_slow_ok != 0;
-            }
-            if (mode == kGroupedWalk) {
-                // every group walked back from its share, one wavefront each
-                const int g = tid >> 6;
-                if (g < G) {
-                    const int e_end = walk(gr.range[2 * g + 1], gr.range[2 * g],
-                                           __builtin_amdgcn_readfirstlane(s_alloc[G - 1 + g]), s_pick);
-                    if (lane == 0 && e_end != 0) s_walk_bad = 1;
-                }
-                __syncthreads();
-                // The assignment must add up to the root's cell: bins to e*, sizes to the minimum
-                // found there.  Whatever does not (it never should) is swept sequentially instead.
-                long long sum_b = 0, sum_s = 0;
-                int ok = 1;
-                for (int l = tid; l < L; l += kDpThreads) {
-                    const int k = s_pick[l];
-                    ok &= k < p.count[l] ? 1 : 0;
-                    const DpEntry en = p.entries[(size_t)l * bstride + min(k, bstride - 1)];
-                    sum_b += en.bin;
-                    sum_s += en.size;
-                }
-                for (int o = 1; o < 64; o <<= 1) {
-                    sum_b += __shfl_xor(sum_b, o, 64);
-                    sum_s += __shfl_xor(sum_s, o, 64);
-                    ok &= __shfl_xor(ok, o, 64);
-                }
-                long long* const s_tot = reinterpret_cast<long long*>(s_entries);      // [waves][2]: staging is free
-                if (lane == 0) {
-                    s_tot[2 * (tid >> 6)] = sum_b;
-                    s_tot[2 * (tid >> 6) + 1] = sum_s;
-                    if (!ok) s_walk_bad = 1;
-                }
-                __syncthreads();
-                if (tid == 0) {
-                    long long tb = 0, ts = 0;
-                    for (int w = 0; w < kDpThreads / 64; ++w) { tb += s_tot[2 * w]; ts += s_tot[2 * w + 1]; }
-                    if (tb != (long long)s_idx[0] || ts != (long long)s_val[0]) s_walk_bad = 1;
-                }
-                __syncthreads();
-                if (s_walk_bad) {
-                    mode = kSeq;
-                    resolved = false;
-                } else if (tid == 0) {
-                    s_idx[1] = 0;
-                }
-            }
-        }
-    }
-    if (mode == kSeq) {
-        for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
-        dp_sweep_layers<T, KMAX, PADDED, kDpThreads>(p, row, s_entries, s_count, lds_bins ? s_bins : nullptr, 0, L);
-        __syncthreads();
-        argmin_row();
-    }
-    const bool grouped = mode != kSeq;
-    uint64_t t_sweep = 0;
-    if (tid == 0) t_sweep = wall_clock64();
-
-    if (mode == kSeq && tid < 64) {
-        if (s_val[0] < (int64_t)kInf) {
-            int e = __builtin_amdgcn_readfirstlane(s_idx[0]);
-            if (lds_bins && bstride <= 64) {
-                e = walk(L, 0, e, s_pick);
-            } else if (tid == 0) {
-                if (lds_bins) {
-                    for (int l = L - 1; l >= 0; --l) {
-                        const int k = p.pd[(size_t)l * width + e];
-                        s_pick[l] = (uint8_t)k;
-                        e -= s_bins[l * bstride + k];
-                    }
-                } else {
-                    for (int l = L - 1; l >= 0; --l) {
-                        const int k = p.pd[(size_t)l * width + e];
-                        const DpEntry en = p.entries[(size_t)l * bstride + k];
-                        p.choice[l] = en.cand;
-                        e -= en.bin;
-                    }
-                }
-            }
-            if (tid == 0) s_idx[1] = e;
-        }
+    __syncthreads();                              // earlier readers of s_val / s_idx are done
+    if (lane == 0) { s_val[tid >> 6] = bv; s_idx[tid >> 6] = be; }
+    __syncthreads();
+    if (tid < 64) {
+        // the first wavefront: every lane joins the per-wavefront minima the same way
+        for (int w = 1; w < kDpThreads / 64; ++w)
+            if (s_val[w] < bv || (s_val[w] == bv && s_idx[w] < be)) { bv = s_val[w]; be = s_idx[w]; }
     }
     __syncthreads();
+    if (tid == 0) { s_val[0] = bv; s_idx[0] = be; }
+    __syncthreads();
+}
+
+// The walk is a chain of dependent loads: one PD byte per layer from global memory, the bin it
+// stands for from LDS.  One wavefront walks the swept layers [l_lo, l_hi) downwards from cell e,
+// writes the picked entry of every layer to out[layer] and returns the cell it ends in (0 if all
+// is consistent, -1 after a byte that cannot be).
+// Two layers per load latency: lane j holds the bin of entry j of layer l, so while PD[l][e]
+// is on its way lane j already fetches PD[l-1][e - bin_j], the byte the walk needs next if
+// entry j is the one picked.  A wavefront pays the full issue latency of every instruction here,
+// so the loop is kept short: rows by a running pointer, no branches, consistency checks joined
+// into one flag (a bad byte still gives in-row addresses: e only shrinks and is clamped at 0,
+// lanes past the list hold bin 0).  Lists of at most 64 entries.
+__device__ __forceinline__ int dp_walk(const uint8_t* __restrict__ pd, const int64_t width,
+                                       const uint16_t* const s_bins, const int bstride, const int l_hi,
+                                       const int l_lo, int e, uint8_t* const out) {
+    const int lane = threadIdx.x & 63;
+    auto bins_of = [&](int layer) -> uint32_t {
+        return lane < bstride ? (uint32_t)s_bins[max(layer, 0) * bstride + lane] : 0u;
+    };
+    int l = l_hi - 1;
+    uint32_t bins_cur = bins_of(l), bins_prev = bins_of(l - 1);
+    const uint8_t* __restrict__ row_l = pd + (size_t)max(l, 0) * width;
+    int bad = 0;
+    for (; l >= l_lo + 1; l -= 2, row_l -= 2 * width) {
+        const uint32_t bins_n1 = bins_of(l - 2), bins_n2 = bins_of(l - 3);
+        const uint32_t ka_v = row_l[e];
+        const uint32_t kb_v = (row_l - width)[max(e - (int)bins_cur, 0)];
+        const int ka = __builtin_amdgcn_readfirstlane((int)ka_v);
+        const int kb = (int)readlane_u32(kb_v, ka);
+        out[l] = (uint8_t)ka;                  // every lane writes the same byte
+        out[l - 1] = (uint8_t)kb;
+        e -= (int)readlane_u32(bins_cur, ka) + (int)readlane_u32(bins_prev, kb);
+        bad |= (ka >= bstride) | (kb >= bstride) | (e < 0);
+        e = max(e, 0);
+        bins_cur = bins_n1;
+        bins_prev = bins_n2;
+    }
+    if (l == l_lo && l_hi > l_lo) {
+        const int ka = __builtin_amdgcn_readfirstlane((int)row_l[e]);
+        out[l] = (uint8_t)ka;
+        e -= (int)readlane_u32(bins_cur, ka);
+        bad |= (ka >= bstride) | (e < 0);
+    }
+    return bad ? -1 : e;
+}
+
+// What a solve ends with, once s_val[0] / s_idx[0] hold the minimum of the last row and its cell,
+// s_idx[1] the cell the walk ended in and s_pick the picked entry of every swept layer: the
+// compression's layer records (see DpApply), the assignment and the result block.  `staging`:
+// 16 KB of LDS free by now.  Every thread calls; the threads past the first wavefront return
+// before the hand-over.
+template <typename T, int kDpThreads>
+__device__ __forceinline__ void dp_finish(const DpParams& p, const int L, const bool lds_bins, const uint8_t* const s_pick,
+                                          unsigned char* const staging, const int64_t* const s_val,
+                                          const int32_t* const s_idx, const int32_t pre_fixed, const int32_t pre_sweep,
+                                          const uint64_t t_begin, const uint64_t t_sweep, const int64_t how) {
+    constexpr T kInf = DpInf<T>::v;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int bstride = p.max_count;
     const bool feasible = s_val[0] < (int64_t)kInf;
     const bool traced = feasible && lds_bins && s_idx[1] == 0;
     if (p.apply.layers) {
-        // The compression's layer records from the assignment (see DpApply), one thread per
-        // layer.  The staging area of the entry lists is free now: candidate per layer first
-        // (fixed layers from the build's report, swept ones from the back-trace), then the payload
-        // offsets, a running sum of the chosen sizes rounded up to 16 bytes.
+        // The compression's layer records from the assignment, one thread per layer: candidate per
+        // layer first (fixed layers from the build's report, swept ones from the back-trace), then
+        // the payload offsets, a running sum of the chosen sizes rounded up to 16 bytes.
         const DpApply& A = p.apply;
         static_assert(kDpThreads >= kBuildThreads, "one thread per layer");
-        static_assert(sizeof(s_entries) >= kDpThreads + 8 * (kDpThreads / 64) + 8, "staging area too small");
-        uint8_t* const s_chosen = reinterpret_cast<uint8_t*>(s_entries);                          // [threads]
-        int64_t* const s_wtot = reinterpret_cast<int64_t*>(s_entries) + kDpThreads / 8;            // [waves]
+        uint8_t* const s_chosen = staging;                                                         // [threads]
+        int64_t* const s_wtot = reinterpret_cast<int64_t*>(staging) + kDpThreads / 8;              // [waves]
         int32_t* const s_bad = reinterpret_cast<int32_t*>(s_wtot + kDpThreads / 64);
         const int wave = tid >> 6;
         bool ok = traced && A.L <= kDpThreads;          // workgroup-uniform
@@ -731,15 +416,383 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
             p.result[2] = s_idx[0];
         }
         // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace;
-        // how the table was swept: 0 in this kernel, G in G groups, 1000 + G in G groups with
-        // ambiguous splits resolved by comparing traced sequences, -G in this kernel after that
-        // resolution gave up
+        // how the table was swept: 0 sequentially, G in G groups, 1000 + G in G groups with
+        // ambiguous splits resolved by comparing traced sequences, -G sequentially after the
+        // grouped route gave up
         p.result[3] = (int64_t)(t_sweep - t_begin);
         p.result[4] = (int64_t)(wall_clock64() - t_sweep);
-        p.result[9] = G > 1 ? (grouped ? (resolved ? 1000 + G : G) : -G) : 0;
+        p.result[9] = how;
     }
     __threadfence_system();
     if (tid == 0) p.result[7] = p.seq;
+}
+
+// The build kernel found nothing to solve (a NaN, a layer without usable candidate): only the
+// hand-over is left.  Every thread calls.
+template <int kDpThreads>
+__device__ __forceinline__ void dp_hand_over_unsolved(const DpParams& p) {
+    const int tid = threadIdx.x;
+    if (p.apply.layers)
+        for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
+    if (tid == 0) {
+        p.result[8] = 0;
+        __threadfence_system();
+        p.result[7] = p.seq;
+    }
+}
+
+// ---- the sequential solve: one workgroup sweeps every layer, traces back and finishes
+template <typename T, int KMAX, bool PADDED, int kDpThreads>
+__global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
+    // In a grouped solve this kernel is queued behind dp_trace_kernel and has work only if that
+    // one gave up (it then left flag = 1 and no result).
+    const int G = p.groups.G;
+    if (G > 1 && p.groups.flag[0] == 0) return;
+    // LDS row: [pad] cells of infinity, then cells 0 .. KMAX*threads-1 (cells above D stay infinite).
+    // With PADDED the pad is at least the largest bin, so row[e - b] needs no range check.
+    extern __shared__ unsigned char dp_smem[];
+    T* const row = reinterpret_cast<T*>(dp_smem) + p.pad;
+    __shared__ DpEntry s_entries[kDpStageEntries];      // [layers of the stage][max_count]
+    __shared__ int32_t s_count[kDpStageMax];
+    __shared__ int64_t s_val[kDpThreads / 64];
+    __shared__ int32_t s_idx[kDpThreads / 64];
+    const int tid = threadIdx.x;
+    const int64_t width = p.pd_stride;
+    constexpr T kInf = DpInf<T>::v;
+    // back-trace tables behind the row when they fit (the host decides): the bin of every entry
+    // (16 bits: D <= 16384) and the picked entry per layer
+    const bool lds_bins = p.bt_lds != 0;
+    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(row + KMAX * kDpThreads);
+    const int bstride = p.max_count;
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
+    // Entry lists built on the device (dp_build_kernel): the number of swept layers and the status
+    // it found come from memory; anything but "ok" there ends the solve.
+    int L = p.L;
+    if (p.L_dev) {
+        if (p.L_dev[1] != 0) {
+            dp_hand_over_unsolved<kDpThreads>(p);
+            return;
+        }
+        L = p.L_dev[0];
+    }
+    // for the apply step at the end (see DpApply): the build's report for this thread's layer,
+    // fetched now so that the tail does not wait for it
+    int32_t pre_fixed = 0, pre_sweep = 0;
+    if (p.apply.layers) {
+        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
+        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
+    }
+    const uint64_t t_begin = wall_clock64();
+    if (p.host_in) {
+        // fetch the input block from the host's pinned memory: one 16-byte word per thread and
+        // round, all in flight together; the barrier below orders it before the first read
+        for (int i = tid; i < p.in_vec; i += kDpThreads) p.dev_in[i] = p.host_in[i];
+        __threadfence_block();
+    }
+    for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
+    dp_sweep_layers<T, KMAX, PADDED, kDpThreads>(p, row, s_entries, s_count, lds_bins ? s_bins : nullptr, 0, L);
+    __syncthreads();
+    dp_argmin<T, kDpThreads>(row, p.D, s_val, s_idx);
+    uint64_t t_sweep = 0;
+    if (tid == 0) t_sweep = wall_clock64();
+    if (tid < 64 && s_val[0] < (int64_t)kInf) {
+        int e = __builtin_amdgcn_readfirstlane(s_idx[0]);
+        if (lds_bins && bstride <= 64) {
+            e = dp_walk(p.pd, width, s_bins, bstride, L, 0, e, s_pick);
+        } else if (tid == 0) {
+            if (lds_bins) {
+                for (int l = L - 1; l >= 0; --l) {
+                    const int k = p.pd[(size_t)l * width + e];
+                    s_pick[l] = (uint8_t)k;
+                    e -= s_bins[l * bstride + k];
+                }
+            } else {
+                for (int l = L - 1; l >= 0; --l) {
+                    const int k = p.pd[(size_t)l * width + e];
+                    const DpEntry en = p.entries[(size_t)l * bstride + k];
+                    p.choice[l] = en.cand;
+                    e -= en.bin;
+                }
+            }
+        }
+        if (tid == 0) s_idx[1] = e;
+    }
+    __syncthreads();
+    dp_finish<T, kDpThreads>(p, L, lds_bins, s_pick, reinterpret_cast<unsigned char*>(s_entries), s_val, s_idx, pre_fixed,
+                             pre_sweep, t_begin, t_sweep, G > 1 ? -(int64_t)G : 0);
+}
+
+// ---- tracing a grouped solve (see dp_group_kernel / dp_conv_kernel): one workgroup
+// The layers were swept in G groups side by side and the groups' cost functions joined pairwise;
+// node 0 of the tree is the last row of the whole table.  Walking down the tree gives every
+// group its share of the bins: at an inner node holding e bins the split is the e2 with
+// Y[e2] + X[e - e2] = T[e].  Where several e2 attain it, Algorithm 1's tie-breaks decide (lowest
+// candidate index, last layer first): the split whose higher-layer child Y traces back to the
+// lexicographically smallest sequence of picks, compared from Y's last layer down (slow path
+// below).  Every group is then walked back from its share by a wavefront of its own, the
+// assignment is checked against the root cell (bins and size must add up to it) and the solve is
+// finished as in the sequential kernel.  A solve this kernel gives up on (too many candidates to
+// compare, a check that fails) gets flag = 1 and is swept by the sequential kernel queued next.
+// Dynamic LDS: the bin of every entry (16 bits) and the picked entry per layer.
+template <int kDpThreads>
+__global__ __launch_bounds__(kDpThreads) void dp_trace_kernel(DpParams p) {
+    using T = uint32_t;
+    extern __shared__ unsigned char dp_smem[];
+    __shared__ __align__(16) unsigned char s_stage[16384];       // buffers of the slow path, then the finish
+    __shared__ int64_t s_val[kDpThreads / 64];
+    __shared__ int32_t s_idx[kDpThreads / 64];
+    constexpr int kSplitCap = 16, kWalkBudget = 96, kTreeDepth = 3;
+    static_assert((1 << kTreeDepth) == kDpMaxGroups, "the slow path is written out for this depth");
+    __shared__ int32_t s_alloc[2 * kDpMaxGroups], s_ncnt[2 * kDpMaxGroups], s_nlast[2 * kDpMaxGroups];
+    __shared__ int32_t s_tie, s_walk_bad, s_slow_ok, s_nsplit;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int D = p.D;
+    const int64_t width = p.pd_stride;
+    constexpr T kInf = DpInf<T>::v;
+    const int bstride = p.max_count;
+    uint16_t* const s_bins = reinterpret_cast<uint16_t*>(dp_smem);
+    uint8_t* const s_pick = reinterpret_cast<uint8_t*>(s_bins + (size_t)p.L * bstride);   // p.L: capacity
+    const int G = p.groups.G;
+    const DpGroups& gr = p.groups;
+    if (tid == 0) gr.flag[0] = 0;
+    int L = p.L;
+    if (p.L_dev) {
+        if (p.L_dev[1] != 0) {
+            dp_hand_over_unsolved<kDpThreads>(p);
+            return;
+        }
+        L = p.L_dev[0];
+    }
+    int32_t pre_fixed = 0, pre_sweep = 0;
+    if (p.apply.layers) {
+        if (tid < p.apply.L) pre_fixed = p.apply.fixed_choice[tid];
+        if (tid < L) pre_sweep = p.apply.sweep_layer[tid];
+    }
+    const uint64_t t_begin = wall_clock64();
+    // the bin of every entry, for the walks
+    for (int i = tid; i < L * bstride; i += kDpThreads) s_bins[i] = (uint16_t)p.entries[i].bin;
+    if (tid == 0) { s_tie = 0; s_walk_bad = 0; s_slow_ok = 0; }
+    dp_argmin<T, kDpThreads>(gr.nodes, D, s_val, s_idx);
+    bool resolved = false;                            // ambiguous splits were met and resolved
+    bool give_up = false;
+    if (s_val[0] < (int64_t)kInf) {
+        // every e2 with Y[e2] + X[e - e2] = T[e] of an inner node, up to kSplitCap of them in out[]
+        // (in no particular order); the whole block scans (every thread calls, with the same
+        // arguments); returns how many there are, which may be more than fit out[]
+        auto splits_of = [&](const int node, const int e, int32_t* const out) -> int {
+            const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
+            const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
+            const uint32_t target = gr.nodes[(size_t)node * gr.stride + e];
+            __syncthreads();                              // earlier readers of s_nsplit / out are done
+            if (tid == 0) s_nsplit = 0;
+            __syncthreads();
+            if (target < (uint32_t)kInf) {
+#pragma unroll 4
+                for (int e2 = tid; e2 <= e; e2 += kDpThreads) {
+                    if (Y[e2] + X[e - e2] == target) {
+                        const int pos = atomicAdd(&s_nsplit, 1);
+                        if (pos < kSplitCap) out[pos] = e2;
+                    }
+                }
+            }
+            __syncthreads();
+            return s_nsplit;
+        };
+        // first and last swept layer of the leaves under a node of the tree
+        auto layers_of = [&](int node, int* lo, int* hi) {
+            int a = node, b = node;
+            while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
+            *lo = gr.range[2 * (a - (G - 1))];
+            *hi = gr.range[2 * (b - (G - 1)) + 1];
+        };
+        if (tid == 0) s_alloc[0] = s_idx[0];
+        // fast path, level by level: the threads share out the nodes of a level and each node's
+        // e2 range; a node where not exactly one e2 matches ends it
+        for (int first = 0; first < G - 1; first = 2 * first + 1) {         // nodes first .. 2 first
+            if (tid < 2 * kDpMaxGroups) { s_ncnt[tid] = 0; s_nlast[tid] = -1; }
+            __syncthreads();
+            const int tpn = kDpThreads / (first + 1);                       // threads per node
+            const int node = first + tid / tpn, t_in = tid % tpn;
+            const bool live = s_tie == 0;                                   // else the shares above are not set
+            const int a = live ? s_alloc[node] : 0;
+            const uint32_t* __restrict__ X = gr.nodes + (size_t)(2 * node + 1) * gr.stride;
+            const uint32_t* __restrict__ Y = gr.nodes + (size_t)(2 * node + 2) * gr.stride;
+            const uint32_t target = gr.nodes[(size_t)node * gr.stride + a];
+            int cnt = 0, last = -1;
+            if (live) {
+#pragma unroll 4
+                for (int e2 = t_in; e2 <= a; e2 += tpn) {
+                    const bool ok = Y[e2] + X[a - e2] == target;
+                    cnt += ok ? 1 : 0;
+                    last = ok ? e2 : last;
+                }
+            }
+            if (cnt) {
+                atomicAdd(&s_ncnt[node], cnt);
+                atomicMax(&s_nlast[node], last);
+            }
+            __syncthreads();
+            if (t_in == 0 && live) {
+                if (s_ncnt[node] != 1) {
+                    s_tie = 1;
+                } else {
+                    s_alloc[2 * node + 2] = s_nlast[node];
+                    s_alloc[2 * node + 1] = a - s_nlast[node];
+                }
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+        if (s_tie != 0) {
+            // slow path: resolve every ambiguous split by comparing the sequences of picks its
+            // candidates lead to in the higher-layer child.  Every thread runs the same control
+            // flow (all decisions come from LDS); the scans use the whole block, the walks one
+            // wavefront per group, the comparisons the first wavefront.
+            uint8_t* const bufs = s_stage;                                      // [depth][2][L <= 1024]
+            int32_t* const cands = reinterpret_cast<int32_t*>(s_stage) + 2048;  // behind the buffers: [depth][cap]
+            int32_t* const saved = cands + kTreeDepth * kSplitCap;              // [depth][2 G] shares of the best candidate
+            static_assert(sizeof(s_stage) >= 8192 + 4 * kTreeDepth * (kSplitCap + 2 * kDpMaxGroups),
+                          "staging area too small");
+            int budget = kWalkBudget;         // candidates looked at; the same in every thread
+            // picks of [lo, hi) compared from the last layer down: is a before b?
+            auto before = [&](const uint8_t* a, const uint8_t* b, int lo, int hi) -> bool {
+                if (tid < 64) {
+                    int res = 0;
+                    for (int top = hi - 1; top >= lo; top -= 64) {
+                        const int l = top - lane;
+                        const int da = l >= lo ? a[l] : 0, db = l >= lo ? b[l] : 0;
+                        const unsigned long long m = __ballot(da != db);
+                        if (m) {
+                            const int firstl = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+                            res = (int)readlane_u32((uint32_t)(da < db), firstl);
+                            break;
+                        }
+                    }
+                    if (lane == 0) s_nlast[0] = res;
+                }
+                __syncthreads();
+                const bool r = s_nlast[0] != 0;
+                __syncthreads();
+                return r;
+            };
+            // picks of every group under `node`, each from the share s_alloc gives it: one
+            // wavefront per group, side by side
+            auto walk_under = [&](int node, uint8_t* out) -> bool {
+                int a = node, b = node;
+                while (a < G - 1) { a = 2 * a + 1; b = 2 * b + 2; }
+                if (tid == 0) s_nlast[1] = 0;
+                __syncthreads();
+                const int leafn = a + (tid >> 6);
+                if (leafn <= b) {
+                    const int g = leafn - (G - 1);
+                    const int e_end = dp_walk(p.pd, width, s_bins, bstride, gr.range[2 * g + 1], gr.range[2 * g],
+                                              __builtin_amdgcn_readfirstlane(s_alloc[leafn]), out);
+                    if (lane == 0 && e_end != 0) s_nlast[1] = 1;
+                }
+                __syncthreads();
+                const bool ok = s_nlast[1] == 0;
+                __syncthreads();
+                return ok;
+            };
+            // the shares of every node under `node` holding e bins -> s_alloc
+            auto share = [&](auto&& deeper, int level, int node, int e) -> bool {
+                if (tid == 0) s_alloc[node] = e;
+                if (node >= G - 1) return true;
+                int32_t* const cd = cands + level * kSplitCap;
+                const int cnt = splits_of(node, e, cd);
+                if (cnt < 1 || cnt > kSplitCap) return false;
+                int pick = 0;
+                if (cnt > 1) {
+                    int lo, hi;
+                    layers_of(2 * node + 2, &lo, &hi);
+                    uint8_t* best = bufs + (size_t)(2 * level) * 1024;
+                    uint8_t* cur = bufs + (size_t)(2 * level + 1) * 1024;
+                    int32_t* const keep = saved + level * 2 * kDpMaxGroups;
+                    for (int i = 0; i < cnt; ++i) {
+                        if (--budget < 0) return false;
+                        if (!deeper(2 * node + 2, cd[i])) return false;
+                        if (!walk_under(2 * node + 2, i == 0 ? best : cur)) return false;
+                        const bool better = i > 0 && before(cur, best, lo, hi);
+                        if (better) {
+                            uint8_t* t = best; best = cur; cur = t;
+                            pick = i;
+                        }
+                        if (i == 0 || better) {
+                            if (tid < 2 * kDpMaxGroups) keep[tid] = s_alloc[tid];
+                            __syncthreads();
+                        }
+                    }
+                    if (tid < 2 * kDpMaxGroups) s_alloc[tid] = keep[tid];     // the best candidate's shares
+                    __syncthreads();
+                } else if (!deeper(2 * node + 2, cd[0])) {
+                    return false;
+                }
+                return deeper(2 * node + 1, e - cd[pick]);
+            };
+            auto leaf_share = [&](int n, int ee) -> bool {
+                if (tid == 0) s_alloc[n] = ee;
+                return true;
+            };
+            auto share2 = [&](int node, int e) -> bool { return share(leaf_share, 2, node, e); };
+            auto share1 = [&](int node, int e) -> bool { return share(share2, 1, node, e); };
+            const bool ok = share(share1, 0, 0, s_idx[0]);
+            __syncthreads();
+            if (tid == 0) s_slow_ok = ok ? 1 : 0;
+            __syncthreads();
+            give_up = s_slow_ok == 0;
+            resolved = !give_up;
+        }
+        if (!give_up) {
+            // every group walked back from its share, one wavefront each
+            const int g = tid >> 6;
+            if (g < G) {
+                const int e_end = dp_walk(p.pd, width, s_bins, bstride, gr.range[2 * g + 1], gr.range[2 * g],
+                                          __builtin_amdgcn_readfirstlane(s_alloc[G - 1 + g]), s_pick);
+                if (lane == 0 && e_end != 0) s_walk_bad = 1;
+            }
+            __syncthreads();
+            // The assignment must add up to the root's cell: bins to e*, sizes to the minimum
+            // found there.  Whatever does not (it never should) is swept sequentially instead.
+            long long sum_b = 0, sum_s = 0;
+            int ok = 1;
+            for (int l = tid; l < L; l += kDpThreads) {
+                const int k = s_pick[l];
+                ok &= k < p.count[l] ? 1 : 0;
+                const DpEntry en = p.entries[(size_t)l * bstride + min(k, bstride - 1)];
+                sum_b += en.bin;
+                sum_s += en.size;
+            }
+            for (int o = 1; o < 64; o <<= 1) {
+                sum_b += __shfl_xor(sum_b, o, 64);
+                sum_s += __shfl_xor(sum_s, o, 64);
+                ok &= __shfl_xor(ok, o, 64);
+            }
+            long long* const s_tot = reinterpret_cast<long long*>(s_stage);      // [waves][2]
+            if (lane == 0) {
+                s_tot[2 * (tid >> 6)] = sum_b;
+                s_tot[2 * (tid >> 6) + 1] = sum_s;
+                if (!ok) s_walk_bad = 1;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                long long tb = 0, ts = 0;
+                for (int w = 0; w < kDpThreads / 64; ++w) { tb += s_tot[2 * w]; ts += s_tot[2 * w + 1]; }
+                if (tb != (long long)s_idx[0] || ts != (long long)s_val[0]) s_walk_bad = 1;
+                s_idx[1] = 0;
+            }
+            __syncthreads();
+            give_up = s_walk_bad != 0;
+        }
+    }
+    if (give_up) {                                    // block-uniform: the sequential kernel takes over
+        if (tid == 0) gr.flag[0] = 1;
+        return;
+    }
+    uint64_t t_sweep = 0;
+    if (tid == 0) t_sweep = wall_clock64();
+    __syncthreads();
+    dp_finish<T, kDpThreads>(p, L, true, s_pick, s_stage, s_val, s_idx, pre_fixed, pre_sweep, t_begin, t_sweep,
+                             resolved ? 1000 + G : G);
 }
 
 // ------------------------------------------------------------------ entry lists on the device
@@ -949,7 +1002,7 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* s
     // layer groups: 32-bit costs, the padded row, the back-trace tables in LDS, one thread per layer
     int G = p.groups.G;
     const bool can_group = sizeof(T) == 4 && padded && p.bt_lds && p.max_count <= 64 && p.L <= THREADS &&
-                           p.groups.nodes && p.groups.range &&
+                           p.groups.nodes && p.groups.range && p.groups.flag &&
                            2 * (size_t)(p.D + 1) * sizeof(uint32_t) <= kDpLdsBudget;
     if (G == 0) G = auto_groups(p);
     if (!can_group || G < 2) G = 1;
@@ -1002,6 +1055,18 @@ static hipError_t launch_dp_t(DpParams p, int max_bin, hipStream_t s, Section* s
             hipLaunchKernelGGL(dp_conv_kernel, dim3(per_node, nodes), dim3(kConvThreads), conv_lds, s, p.groups,
                                nodes - 1, (int)p.D, p.L_dev);
         }
+        {
+            static bool configured = false;
+            if (!configured) {
+                err = hipFuncSetAttribute((const void*)dp_trace_kernel<THREADS>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDpLdsBudget);
+                if (err != hipSuccess) return err;
+                configured = true;
+            }
+        }
+        // the trace finishes the solve; the sequential kernel behind it returns at once unless the
+        // trace gave up (it also closes the section's bracket)
+        hipLaunchKernelGGL(dp_trace_kernel<THREADS>, dim3(1), dim3(THREADS), bt, s, p);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }

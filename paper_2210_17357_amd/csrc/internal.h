@@ -158,6 +158,7 @@ struct DpGroups {
     int32_t stride = 0;           // cells per node array (set by launch_dp, > D)
     uint32_t* nodes = nullptr;    // [(2G-1) x stride] smallest size of a node's layers per exact bin sum (null: groups off)
     int32_t* range = nullptr;     // [G x 2] swept layers [begin, end) of every group, written by the group sweeps
+    int32_t* flag = nullptr;      // [1] written by dp_trace_kernel: 1 = it gave up, the sequential kernel behind it solves
 };
 struct DpParams {
     const DpEntry* entries;   // [L x max_count] swept layers only, in candidate order
@@ -312,6 +313,9 @@ hipError_t lowrank_profile(LowrankScratch* t, const float* g, const float* e, co
 hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers,
                             const DevLayer* h_layers, int L, float* q, int r_max, uint8_t* payload, Timing* tm,
                             hipStream_t s);
+// low-rank layers of a compression queued right behind a profile of the same data (see topk_compress_known)
+hipError_t lowrank_compress_known(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers, float* q,
+                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s);
 // receiver side: out (+)= Phat Q^T from the payload
 hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L, int r_max, const uint8_t* payload,
                               float* out, bool accumulate, Timing* tm, hipStream_t s);

@@ -86,6 +86,7 @@ struct LrParams {
     int32_t col[LGRECO_MAX_CANDS];
     int32_t accumulate;      // decode: add the image to the output instead of replacing it
     int32_t q_from_scratch;  // P = X Q reads the previous step's Q instead of the warm start
+    const DevLayer* dev_layers;   // KNOWN kernels: the caller's layer records (family, rank, payload offset) on the device
 };
 
 // 4 consecutive elements of x = g + e starting at idx of a row that has `left` elements left.
@@ -685,14 +686,23 @@ __global__ __launch_bounds__(256) void lr_errors_kernel(LrParams p) {
 // ------------------------------------------------------------------ e' = X - Phat Q^T
 // DECODE (receiver side): the factors come from the payload (row stride = rank) and the product
 // is written, or added, to the output buffer instead of being subtracted from x.
-template <bool DECODE>
+// KNOWN (compression right behind a profile of the same data): the factors are the leading columns
+// of the profile's rank-64 run, still in its scratch; whether the layer takes part and its rank
+// come from the layer records the solver kernel wrote.
+template <bool DECODE, bool KNOWN = false>
 __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
     __shared__ float Ps[64][kLrCols + 1];
     __shared__ float Qs[kLrCols][kLrCols + 1];
     __shared__ float Ms[64][kLrCols + 4];
     const LrTile tile = p.ef_tiles[blockIdx.x];
     const LrLayer L = p.layers[tile.layer];
-    const int m = L.rows, n = L.cols, r = L.rank;
+    int r = L.rank;
+    if (KNOWN) {
+        const DevLayer& dl = p.dev_layers[L.index];
+        if (dl.family != LGRECO_LOWRANK || dl.iparam < 1 || dl.iparam > kLrCols) return;
+        r = dl.iparam;
+    }
+    const int m = L.rows, n = L.cols;
     const int kmax = (r + 1) & ~1;
     const float* __restrict__ g = DECODE ? (p.accumulate ? p.e_out + L.offset : nullptr) : p.g + L.offset;
     const float* __restrict__ ein = DECODE ? nullptr : p.e;
@@ -809,6 +819,38 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
                     if (left > 3) e[idx + 3] = o.w;
                 }
             }
+        }
+    }
+}
+
+// Payload and warm-start update of a layer from the profile's scratch (KNOWN, see lr_ef_kernel):
+// the first `rank` columns of Phat (row tiles, blockIdx < n_row_tiles) and of Q (chunks of
+// kLrQChunk rows after them); Q also replaces the first `rank` columns of the layer's warm start.
+__global__ __launch_bounds__(256) void lr_emit_known_kernel(LrParams p, int n_row_tiles) {
+    const bool is_p = (int)blockIdx.x < n_row_tiles;
+    const LrTile tile = is_p ? p.row_tiles[blockIdx.x] : p.q_chunks[blockIdx.x - n_row_tiles];
+    const LrLayer L = p.layers[tile.layer];
+    const DevLayer& dl = p.dev_layers[L.index];
+    if (dl.family != LGRECO_LOWRANK || dl.iparam < 1 || dl.iparam > kLrCols) return;
+    const int r = dl.iparam;
+    float* const pay = reinterpret_cast<float*>(p.payload + dl.payload);
+    const int tid = threadIdx.x;
+    if (is_p) {
+        const float* __restrict__ P = p.P + L.p_off;
+        const int nr = min(kLrBM, L.rows - tile.a0);
+        for (int f = tid; f < nr * r; f += 256) {
+            const int rr = f / r, c = f - rr * r;
+            pay[(int64_t)(tile.a0 + rr) * r + c] = P[(int64_t)(tile.a0 + rr) * kLrCols + c];
+        }
+    } else {
+        const float* __restrict__ Q = p.Q + L.qs_off;
+        float* const payq = pay + (int64_t)L.rows * r;
+        const int nr = min(tile.split, L.cols - tile.a0);      // tile.split = rows of this chunk
+        for (int f = tid; f < nr * r; f += 256) {
+            const int rr = f / r, c = f - rr * r;
+            const float v = Q[(int64_t)(tile.a0 + rr) * kLrCols + c];
+            payq[(int64_t)(tile.a0 + rr) * r + c] = v;
+            p.q_out[L.q_off + (int64_t)(tile.a0 + rr) * p.r_max + c] = v;
         }
     }
 }
@@ -1110,6 +1152,35 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
     LR_CHECK(lr_factorize(H, p, t->power_iters, tm, s));
     Section sec(tm, "lowrank_ef", true);
     launch_timed(&sec, true, true, lr_ef_kernel<false>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// Low-rank layers of a compression queued right behind a profile of the same data and the solver
+// kernel that wrote the layer records: the profile's rank-64 factors are still in its scratch and
+// every rank's factors are their leading columns, so nothing is contracted again.  Uses the
+// profile's work tables (all layers); needs nothing from the host.
+hipError_t lowrank_compress_known(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers, float* q,
+                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s) {
+    LrHost* H = &((LrHost*)t->host)[kLrSlotProfile];
+    if (H->layers.empty()) return hipSuccess;
+    LrParams p{};
+    lr_fill_params(H, &p);
+    p.g = g;
+    p.e = e;
+    p.e_out = e;
+    p.q0 = q;
+    p.q_out = q;
+    p.r_max = r_max;
+    p.payload = payload;
+    p.dev_layers = d_layers;
+    {
+        Section sec(tm, "lowrank_emit");
+        hipLaunchKernelGGL(lr_emit_known_kernel, dim3((unsigned)(H->row_tiles.size() + H->q_chunks.size())), dim3(256), 0,
+                           s, p, (int)H->row_tiles.size());
+        LR_CHECK(hipGetLastError());
+    }
+    Section sec(tm, "lowrank_ef", true);
+    launch_timed(&sec, true, true, lr_ef_kernel<false, true>, dim3((unsigned)H->ef_tiles.size()), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -52,9 +52,8 @@ struct TopkLayer {
 constexpr int kRefTiles = 8;        // largest tiles per refinement / sample workgroup (fewer elements never: with
                                     // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
-constexpr int kRefSlots = 512;      // refinement workgroups the chip runs at a time (256 CUs x 2)
 constexpr int kBinsA = 1024, kBinsB = 512;
-constexpr int kPickThreads = 1024;
+constexpr int kPickThreads = 512;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 constexpr uint32_t kHintMargin = 2; // coarse bins (4.4 % in magnitude each) between a remembered threshold and the bound derived from it
 
@@ -1242,7 +1241,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
-    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile / 4)) + 2 * max_layers + 2;   // smallest work items
+    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile)) + 2 * max_layers + 2;
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
     t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
@@ -1339,29 +1338,7 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                       const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
     (void)n_tiles;
-    // Tiles per work item of the sample / refinement kernels: at most 2^19 elements, and no less than
-    // a quarter of that.  Those kernels run two 1024-thread workgroups per CU, kRefSlots at a time,
-    // and take (rounds of kRefSlots work items) x (tiles per item): the size is picked to fill its
-    // last round (355 M elements in 292 layers: 11 tiles of 32768 instead of 16, two full rounds
-    // instead of one and a third).
-    const int group_max = kRefTiles * (kTile / tile_elems);
-    int group = group_max;
-    {
-        double best = 0.0;
-        for (int g = group_max; g >= std::max(1, group_max / 4); --g) {
-            int64_t items = 0;                                   // work items that hold at least half a share
-            for (int l = 0; l < L; ++l) {
-                if (!ks[(size_t)l * kMaxTopk]) continue;
-                const int nt = h_layers[l].tile_end - h_layers[l].tile_begin;
-                items += nt / g + ((nt % g) * 2 >= g ? 1 : 0);
-            }
-            const double cost = (double)((items + kRefSlots - 1) / kRefSlots) * g;
-            if (g == group_max || cost < best * 0.97) {          // a smaller size has to pay for its extra partial sums
-                best = cost;
-                group = g;
-            }
-        }
-    }
+    const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
     TK_CHECK(ctl_writable(t));
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
