@@ -153,6 +153,11 @@ int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand
  *   choice       host [L]: candidate index per layer
  *   total_size   sum of the chosen sizes (may be NULL)
  *   total_error  sum of the chosen real errors (may be NULL)
+ * The constraint is on the discretised errors: every bin rounds its error down by less than one
+ * step, so an assignment the solver accepts has total_error < e_max * (1 + L / n_bins), not
+ * total_error <= e_max.  The return value is still LGRECO_OK then (the paper's algorithm accepts
+ * the same assignments); a caller that needs the strict bound compares total_error with e_max
+ * itself, or solves with e_max / (1 + L / n_bins).
  * Returns LGRECO_EINFEASIBLE if no assignment fits; choice then holds each layer's
  * minimum-error candidate.  n_bins <= LGRECO_MAX_BINS. */
 int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes, int32_t L,

@@ -7,7 +7,7 @@ knapsack-style table DP[l][e] = min total size of the first l layers whose binne
 sum to exactly e is filled layer by layer; PD keeps the arg-min candidate for the
 back-trace (Algorithm 1).
 
-Readings where the listing is silent or breaks:
+Readings where the paper's listing is silent or breaks:
   * bin(l,c) = floor((error * D) / E_max) in fp64, in that operation order; negative errors
     count as 0; a bin above D makes the candidate unusable for that layer.  With floor the
     uniform default always stays feasible.  If E_max <= 0 only zero-error candidates are usable
@@ -43,46 +43,49 @@ def discretise(errors: np.ndarray, e_max: float, n_bins: int) -> np.ndarray:
 
 
 def dp_tables(bins: np.ndarray, sizes: np.ndarray, n_bins: int):
-    """Fill DP and PD (Algorithm 1, sweep).  Row 0 of DP is the virtual start row."""
+    """DP and PD from the recurrence the table is defined by (section "The L-GreCo Framework";
+    Algorithm 1 fills the same table): with the virtual start row DP[0] = (0, inf, inf, ...),
+
+        DP[l][e] = min over usable candidates c of layer l with bin(l, c) <= e
+                   of DP[l-1][e - bin(l, c)] + size(l, c),
+        PD[l][e] = the lowest such c that attains the minimum (-1 where no c applies).
+
+    Every cell is evaluated on its own, straight from this definition."""
     n_layers, n_cands = bins.shape
     dp = np.full((n_layers + 1, n_bins + 1), INF, np.int64)
     pd = np.full((n_layers + 1, n_bins + 1), -1, np.int64)
     dp[0][0] = 0
     for l in range(1, n_layers + 1):
-        for c in range(n_cands):
-            b = int(bins[l - 1][c])
-            if b == UNUSABLE or b > n_bins:
-                continue
-            cost = int(sizes[l - 1][c])
-            for e in range(b, n_bins + 1):
-                prev = dp[l - 1][e - b]
-                if prev >= INF:
-                    continue
-                t = prev + cost
-                if t < dp[l][e]:
-                    dp[l][e] = t
-                    pd[l][e] = c
+        usable = [(c, int(bins[l - 1][c]), int(sizes[l - 1][c])) for c in range(n_cands)
+                  if bins[l - 1][c] != UNUSABLE and bins[l - 1][c] <= n_bins]
+        for e in range(n_bins + 1):
+            reach = [(int(dp[l - 1][e - b]) + cost, c) for c, b, cost in usable
+                     if b <= e and dp[l - 1][e - b] < INF]
+            if reach:
+                dp[l][e], pd[l][e] = min(reach)        # smallest total, then lowest candidate index
     return dp, pd
 
 
 def dp_tables_fast(bins: np.ndarray, sizes: np.ndarray, n_bins: int):
-    """Same table, with the innermost loop over e written as one array statement (the cells
-    of a row do not depend on each other).  Used where the scalar loops would take minutes."""
+    """Same recurrence, one row at a time as a (min, +) step: candidate c contributes the previous
+    row shifted right by bin(l, c) plus size(l, c); the new row is the element-wise minimum of
+    the contributions and PD the first (lowest c) contribution attaining it.  Used where the
+    cell-by-cell form would take minutes."""
     n_layers, n_cands = bins.shape
     dp = np.full((n_layers + 1, n_bins + 1), INF, np.int64)
     pd = np.full((n_layers + 1, n_bins + 1), -1, np.int64)
     dp[0][0] = 0
     for l in range(1, n_layers + 1):
+        contrib = np.full((n_cands, n_bins + 1), INF, np.int64)
         for c in range(n_cands):
             b = int(bins[l - 1][c])
             if b == UNUSABLE or b > n_bins:
                 continue
             prev = dp[l - 1][:n_bins + 1 - b]
-            t = np.where(prev >= INF, INF, prev + np.int64(sizes[l - 1][c]))
-            row = dp[l][b:]
-            better = t < row
-            row[better] = t[better]
-            pd[l][b:][better] = c
+            contrib[c][b:] = np.where(prev >= INF, INF, prev + np.int64(sizes[l - 1][c]))
+        dp[l] = contrib.min(axis=0)
+        first = contrib.argmin(axis=0)                 # numpy argmin: the first minimum along c
+        pd[l] = np.where(dp[l] < INF, first, -1)
     return dp, pd
 
 
