@@ -145,12 +145,14 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #undef LGRECO_CAND
         };
         // Two register sets take turns: while one chunk is worked on, the loads of the next are in
-        // flight.  Past the range's end the last chunk is loaded once more and not used.
+        // flight.  Nothing is loaded past the range's end (streaming loads of a chunk that was
+        // already read would go to memory again).
         const int lane_off = (lane >> 4) * kBucket + j * 4;
         const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
         auto load = [&](const int c, float4& a, float4& b, float4& ea, float4& eb)
             __attribute__((always_inline)) {
-            const int base = min(c, c_end - 1) * kChunk + lane_off;
+            if (c >= c_end) return;                     // uniform over the wavefront
+            const int base = c * kChunk + lane_off;
             a = load_stream(reinterpret_cast<const float4*>(g + base));
             b = load_stream(reinterpret_cast<const float4*>(g + base + 64));
             ea = HAS_EF ? load_stream(reinterpret_cast<const float4*>(e + base)) : zero4;
