@@ -45,6 +45,11 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 DEFAULT_WORKLOAD = "c4_gpt2_medium_mixed"
 OTHER_WORKLOADS = ("c1_resnet18_quant", "c2_resnet50_topk", "c3_transformer_lm_lowrank")
 DRIFT = (1.0, 1.03, 0.97, 1.015, 0.985)      # scale of gradient buffer v (and of its error feedback)
+# timed sections of the library that get a roofline figure (streaming kernels in bytes, contractions in flops)
+STREAMING_SECTIONS = ("profile/quant_profile", "profile/quant_profile_topk_collect", "profile/topk_collect",
+                      "compress/quant_compress", "compress/topk_collect", "compress/lowrank_ef")
+CONTRACTION_SECTIONS = ("profile/lowrank_gemm_p", "profile/lowrank_gemm_q", "compress/lowrank_gemm_p",
+                        "compress/lowrank_gemm_q")
 
 
 def measured_traffic(workload: str) -> dict:
