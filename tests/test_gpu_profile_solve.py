@@ -263,3 +263,73 @@ def test_whole_path_call_at_the_layer_limit_of_the_device_side_step(L):
         assert np.array_equal(out[1], errors) and out[3] == e_max
         assert torch.equal(pay, ref_pay) and torch.equal(ef.view(torch.int32), ref_ef.view(torch.int32)), rep
     h.close()
+
+
+@pytest.mark.parametrize("default,n_bins", [(3, 300), (4, 50), (2, 2000)])
+def test_whole_path_call_on_degenerate_topk_layers(default, n_bins):
+    """Top-K through the one call on layers that stress the threshold the compression takes over
+    from the profile's records: constant and two-valued layers (every candidate ties with the
+    threshold), all zeros, a layer of 1, 2, 3 elements, misaligned starts with gaps, densities up
+    to 1.  Payload and error feedback against the oracle's compressor at the choice the call made,
+    and against the separate calls."""
+    from oracle import pipeline
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    rng = np.random.default_rng(default * 1000 + n_bins)
+    numels = [4096, 70001, 1, 2, 3, 127, 129, 33000, 5000, 8192 + 77, 20000, 512]
+    pad = [0, 3, 1, 0, 5, 0, 2, 1, 0, 7, 0, 1]
+    offs, pos = [], 0
+    for n, p in zip(numels, pad):
+        pos += p
+        offs.append(pos)
+        pos += n
+    g = (rng.standard_t(3, pos) * 1e-3).astype(np.float32)
+    e = (rng.standard_normal(pos) * 1e-4).astype(np.float32)
+    def put(layer, values):
+        o, n = offs[layer], numels[layer]
+        g[o:o + n] = values
+        e[o:o + n] = 0
+    put(0, 0.25)                                                         # constant
+    put(5, 0.0)                                                          # all zeros
+    put(7, np.where(np.arange(33000) % 3 == 0, -1.0, 3.0))               # two-valued
+    put(8, np.float32(1e-41) * (np.arange(5000) % 50))                   # denormals and zeros
+    put(10, np.round(rng.standard_normal(20000) * 4) / 4)                # values on a coarse grid: many ties
+    batch = W.Batch(g, e, np.asarray(offs, np.int64), np.asarray(numels, np.int64),
+                    np.zeros(len(offs), np.int32), np.zeros(len(offs), np.int32),
+                    np.arange(len(offs), dtype=np.int64))
+    cands = [(W.TOPK, d) for d in (0.001, 0.01, 0.1, 0.3, 0.9, 1.0)]
+    layers, ctab = tables(batch, cands)
+    gd, ed, _ = to_device(batch)
+    L = len(numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    h = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    for rep in range(2):                                                 # the second call starts from the first's thresholds
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = ed.clone()
+        st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
+            gd, ef, layers, ctab, default, n_bins, pay)
+        torch.cuda.synchronize()
+        assert st == B.OK
+        ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, n_bins)
+        assert np.array_equal(choice, ref_choice) and tsize == ref_size
+        pay_h, ef_h = pay.cpu().numpy(), ef.cpu().numpy()
+        for l in range(L):
+            off, n = offs[l], numels[l]
+            p_ref, e_ref, _ = pipeline.compress_layer(batch.grads, batch.ef, off, n, 0, 0, cands[choice[l]], l)
+            assert np.array_equal(pay_h[offsets[l]:offsets[l] + p_ref.size], p_ref), (rep, l, cands[choice[l]])
+            assert np.array_equal(ef_h[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (rep, l)
+        # gaps between the layers stay as they were
+        mask = np.ones(pos, bool)
+        for off, n in zip(offs, numels):
+            mask[off:off + n] = False
+        assert np.array_equal(ef_h[mask], batch.ef[mask])
+    assert len(set(choice.tolist())) >= 2, "one density everywhere: the case does not exercise the choice"
+    # the separate calls on a fresh handle
+    h2 = B.Handle(int(batch.grads.size), L, len(cands))
+    pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef2 = ed.clone()
+    h2.compress(gd, ef2, layers, ctab, choice, pay2, offsets)
+    torch.cuda.synchronize()
+    assert torch.equal(pay2, pay) and torch.equal(ef2.view(torch.int32), ef.view(torch.int32))
+    h2.close()
+    h.close()
