@@ -253,6 +253,7 @@ struct TopkScratch {
     void* h_work = nullptr;
     void* h_work_range = nullptr;
     int max_work = 0, n_work = 0;
+    int max_items = 0;          // most work items of one layer in the current call
     uint32_t* h_k = nullptr;
     int64_t* h_cand_base = nullptr;
     int64_t max_elems = 0;

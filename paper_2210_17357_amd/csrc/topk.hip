@@ -52,8 +52,8 @@ struct TopkLayer {
 constexpr int kRefTiles = 8;        // largest tiles per refinement / sample workgroup (fewer elements never: with
                                     // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
+constexpr int kRefSlots = 512;      // refinement workgroups the chip runs at a time (256 CUs x 2)
 constexpr int kBinsA = 1024, kBinsB = 512;
-constexpr int kPickThreads = 512;
 constexpr int kSampleEvery = 16;    // one 512-element chunk out of 16 is sampled
 constexpr uint32_t kHintMargin = 2; // coarse bins (4.4 % in magnitude each) between a remembered threshold and the bound derived from it
 
@@ -762,7 +762,7 @@ __global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams
 // smallest.  The deviation from the exact dropped energy is therefore at most 1e-5 relative from
 // this step (plus 1.2e-7 from the truncated integer energies and the fp32 sums below the bound).
 constexpr double kInsideTolerance = 1e-5;
-template <bool ENERGY>
+template <bool ENERGY, int kPickThreads>
 __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams p) {
     __shared__ uint32_t s_hist[kBinsA];
     __shared__ unsigned long long s_en[ENERGY ? kBinsA : 1];
@@ -772,9 +772,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     __shared__ double s_sum[kPickThreads / 64];
     __shared__ double s_outside;        // error without the boundary sub-bin's dropped part
     __shared__ uint32_t s_exact[3];     // [0] resolve the sub-bin exactly, [1] its prefix (pattern >> 9), [2] entries kept in it
-    const int l = blockIdx.x / kMaxTopk, j = blockIdx.x % kMaxTopk;
+    const int l = blockIdx.x / p.ntk, j = blockIdx.x % p.ntk;      // the grid holds L x ntk workgroups
     TopkLayer& T = p.tl[l];
-    if (j >= p.ntk || T.sel[j].k == 0) return;
+    if (T.sel[j].k == 0) return;
     const TopkSel S = T.sel[j];
     const int2 wr = p.work_range[l];
     const int tid = threadIdx.x, t = tid & 255, grp = tid >> 8;
@@ -792,34 +792,48 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     double part = 0.0;
     if (ENERGY && tid < 256) {
         const DevLayer L = p.layers[l];
-        for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 256) part += p.base_part[tt];
+        // four loads in flight per round trip; summed in index order all the same
+        for (int tt = L.tile_begin + tid; tt < L.tile_end; tt += 4 * 256) {
+            double v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = tt + q * 256 < L.tile_end ? p.base_part[tt + q * 256] : 0.0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) part += v[q];
+        }
         for (int wg = wr.x + tid; wg < wr.y; wg += 256) part += p.below_part[(size_t)wg * kMaxTopk + j];
     }
     __syncthreads();
-    // sum the layer's workgroup partials of this k's list: 4 bins per thread, the workgroups dealt
-    // round-robin to the thread groups, integer LDS atomics join them (order does not matter)
+    // sum the layer's workgroup partials of this k's list: 4 bins per thread as 16-byte loads (two
+    // pairs of packed cells, or four counts), the workgroups dealt round-robin to the thread groups,
+    // integer LDS atomics join them (order does not matter).  The loop is a chain of memory round
+    // trips with a fixed number of loads in flight: wide loads halve its length.
     {
         uint32_t c[4] = {0, 0, 0, 0};
         unsigned long long e[4] = {0, 0, 0, 0};
-        const size_t off = (size_t)S.list * kBinsA + t;
-#pragma unroll 8
+        static_assert(kBinsA == 1024, "written out for 1024 cells and 256 threads per group");
+        const size_t off = (size_t)S.list * kBinsA;
+#pragma unroll(kPickThreads == 256 ? 8 : 4)
         for (int wg = wr.x + grp; wg < wr.y; wg += kPickThreads / 256) {
             const size_t i = (size_t)wg * kMaxTopk * kBinsA + off;
+            if (ENERGY) {
+                const ulonglong2 v0 = *reinterpret_cast<const ulonglong2*>(p.cell_a + i + 2 * t);
+                const ulonglong2 v1 = *reinterpret_cast<const ulonglong2*>(p.cell_a + i + 512 + 2 * t);
+                const unsigned long long v[4] = {v0.x, v0.y, v1.x, v1.y};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (ENERGY) {
-                    const unsigned long long v = p.cell_a[i + 256 * q];
-                    c[q] += (uint32_t)(v & ((1ull << kPackCountBits) - 1));
-                    e[q] += v >> kPackCountBits;
-                } else {
-                    c[q] += p.cnt_a[i + 256 * q];
+                for (int q = 0; q < 4; ++q) {
+                    c[q] += (uint32_t)(v[q] & ((1ull << kPackCountBits) - 1));
+                    e[q] += v[q] >> kPackCountBits;
                 }
+            } else {
+                const uint4 v = *reinterpret_cast<const uint4*>(p.cnt_a + i + 4 * t);
+                c[0] += v.x; c[1] += v.y; c[2] += v.z; c[3] += v.w;
             }
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (c[q]) atomicAdd(&s_hist[t + 256 * q], c[q]);
-            if (ENERGY && e[q]) atomicAdd(&s_en[t + 256 * q], e[q]);
+            const int cell = ENERGY ? (q >> 1) * 512 + 2 * t + (q & 1) : 4 * t + q;
+            if (c[q]) atomicAdd(&s_hist[cell], c[q]);
+            if (ENERGY && e[q]) atomicAdd(&s_en[cell], e[q]);
         }
     }
     __syncthreads();
@@ -894,14 +908,13 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick_a_kernel(RefineParams 
     block_kth_from_top(s_hist, kBinsB, need_a, s_scan, s_res);
     const uint32_t thr_b = s_res[0], keep_at_thr = need_a - s_res[1];
     // dropped inside the sub-bin: every pattern below the threshold pattern, and the entries equal
-    // to it that are not kept; one cell per thread, fixed tree
-    static_assert(kBinsB <= kPickThreads, "one cell per thread");
+    // to it that are not kept; a thread's cells in index order, then a fixed tree
     double mine = 0.0;
-    if (tid < kBinsB) {
-        const uint32_t c = s_hist[tid];
-        const uint32_t n_drop = (uint32_t)tid < thr_b ? c : ((uint32_t)tid == thr_b ? c - keep_at_thr : 0u);
-        const double v = (double)__uint_as_float((prefix << 9) | (uint32_t)tid);
-        mine = (double)n_drop * (v * v);
+    for (uint32_t b = tid; b < (uint32_t)kBinsB; b += kPickThreads) {
+        const uint32_t c = s_hist[b];
+        const uint32_t n_drop = b < thr_b ? c : (b == thr_b ? c - keep_at_thr : 0u);
+        const double v = (double)__uint_as_float((prefix << 9) | b);
+        mine += (double)n_drop * (v * v);
     }
     const double w = wave_sum(mine);
     __syncthreads();                                          // s_sum was read by thread 0 above
@@ -1241,7 +1254,7 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tinfo, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_base_part, sizeof(double) * (size_t)max_tiles));
-    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile)) + 2 * max_layers + 2;
+    t->max_work = (int)(max_elems / ((int64_t)kRefTiles * kTile)) + 2 * max_layers + 2 + 2 * kRefSlots;   // see topk_begin
     TK_CHECK(hipMalloc(&t->d_below_part, sizeof(double) * (size_t)t->max_work * kMaxTopk));
     t->ref_words = (size_t)t->max_work * kMaxTopk * (3 * kBinsA + kBinsB);      // u64 + u32 level A, u32 level B
     TK_CHECK(hipMalloc(&t->d_ref, sizeof(uint32_t) * t->ref_words));
@@ -1338,12 +1351,22 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
                       const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
                       const uint32_t* ks, int ntk, int slot, Timing* tm, hipStream_t s) {
     (void)n_tiles;
-    const int group = kRefTiles * (kTile / tile_elems);      // tiles per work item: 2^19 elements
+    // Tiles per work item of the sample / refinement kernels: 2^19 elements, fewer when that would
+    // leave part of the chip without a work item (two 1024-thread workgroups per CU, kRefSlots in
+    // all): a work item's time is proportional to its candidates, and a small problem's chain is as
+    // long as its largest item.
+    int group = kRefTiles * (kTile / tile_elems);
+    {
+        int64_t active = 0;
+        for (int l = 0; l < L; ++l)
+            if (ks[(size_t)l * kMaxTopk]) active += h_layers[l].tile_end - h_layers[l].tile_begin;
+        group = (int)std::max<int64_t>(1, std::min<int64_t>(group, active / kRefSlots));
+    }
     TK_CHECK(ctl_writable(t));
     int64_t base = 0;
     RefWork* const work = (RefWork*)t->h_work;
     int2* const wrange = (int2*)t->h_work_range;
-    int nw = 0;
+    int nw = 0, max_items = 0;
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < kMaxTopk; ++j) t->h_k[(size_t)l * kMaxTopk + j] = ks[(size_t)l * kMaxTopk + j];
         // the refinement relies on this order: an active layer asks for ntk values of k, none larger
@@ -1356,12 +1379,16 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
         wrange[l].x = nw;
         if (ks[(size_t)l * kMaxTopk]) {
             base += h_layers[l].numel;
-            for (int t0 = h_layers[l].tile_begin; t0 < h_layers[l].tile_end; t0 += group)
+            for (int t0 = h_layers[l].tile_begin; t0 < h_layers[l].tile_end; t0 += group) {
+                if (nw >= t->max_work) return hipErrorInvalidValue;      // cannot happen: see max_work
                 work[nw++] = RefWork{l, t0, std::min(h_layers[l].tile_end, t0 + group), 0};
+            }
         }
         wrange[l].y = nw;
+        max_items = std::max(max_items, wrange[l].y - wrange[l].x);
     }
     t->n_work = nw;
+    t->max_items = max_items;
     bool changed = true;
     TK_CHECK(upload_ctl(t, slot, s, &changed));
     t->cur_slot = slot;
@@ -1480,6 +1507,9 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
 hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d_tiles, int L, int ntk,
                          const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s) {
     if (t->n_work <= 0) return hipSuccess;
+    // the pick kernel's workgroups: small ones, so that all of them run at once, unless a layer has
+    // so many partial histograms to sum that its workgroup alone would outlast the rest
+    const bool wide_pick = t->max_items > 64;
     RefineParams p{};
     p.tl = (TopkLayer*)t->d_tl;
     p.layers = d_layers;
@@ -1519,12 +1549,14 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
         }
 #undef LG_REFINE_A
         TK_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(topk_pick_a_kernel<true>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
+        if (wide_pick) hipLaunchKernelGGL((topk_pick_a_kernel<true, 512>), dim3(L * ntk), dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((topk_pick_a_kernel<true, 256>), dim3(L * ntk), dim3(256), 0, s, p);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(topk_refine_a_kernel<0>, dim3(t->n_work), dim3(kRefThreads), refine_a_lds(ntk, false), s, p);
     TK_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(topk_pick_a_kernel<false>, dim3(L * kMaxTopk), dim3(kPickThreads), 0, s, p);
+    if (wide_pick) hipLaunchKernelGGL((topk_pick_a_kernel<false, 512>), dim3(L * ntk), dim3(512), 0, s, p);
+    else hipLaunchKernelGGL((topk_pick_a_kernel<false, 256>), dim3(L * ntk), dim3(256), 0, s, p);
     TK_CHECK(hipGetLastError());
     hipLaunchKernelGGL(topk_refine_b_kernel, dim3(t->n_work), dim3(kRefThreads), (size_t)ntk * kBinsB * 4, s, p);
     TK_CHECK(hipGetLastError());
