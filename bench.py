@@ -168,7 +168,9 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     def fresh_ef(i):
         return ef0_list[i % n_buf].clone() if has_ef else zeros.clone()
     # The one-call form hands one error-feedback buffer to profile and compression: a workload that
-    # states none gets a buffer of zeros (x = g + 0), as in the first step of a training run.
+    # states none gets a cleared buffer every step (x = g + 0, as in the first step of a training
+    # run) and the handle is told so (lgreco_set_ef_zero_on_entry): the profile does not read it,
+    # the compression reads and fills it.
     calls = args.calls
     level = 0 if args.no_kernel_timing else (2 if args.detail else 1)
     sizes_tab = B.sizes(layers, ctab, w.bucket)
@@ -182,6 +184,8 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
                      seed=w.seed, r_max=w.r_max, power_iters=args.power_iters, reuse_thresholds=reuse)
         h.set_timing(timing_level)
         h.set_timing_stride(max(1, args.time_every))
+        if not has_ef:
+            h.set_ef_zero_on_entry(True)
         ef_pool = [fresh_ef(i) for i in range(n_runs)]
         q_pool = [q0.clone() for _ in range(n_runs)] if q0 is not None else [None] * n_runs
         last = {}
@@ -241,7 +245,7 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     # algorithmic bytes per element and elements covered per launch, per timed section: streaming
     # reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g
     # and e and writes e
-    rd = 8.0 if (has_ef or calls == "one") else 4.0
+    rd = 8.0 if has_ef else 4.0
     algo, elems = {}, {}
     for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
         algo["profile/" + k], elems["profile/" + k] = rd, float(N)

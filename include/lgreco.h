@@ -328,6 +328,16 @@ int lgreco_get_timing_of(lgreco_handle_t* h, int32_t call, const char** names, f
 int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** names, double* total_ms,
                              int64_t* count, int32_t cap);
 
+/* A promise about d_ef of lgreco_profile_solve_compress, kept until changed: while `on` is not 0 the
+ * caller guarantees that the buffer holds zeros on entry of every such call (the first step of a
+ * run, or a caller that keeps no error feedback between calls and hands in a cleared buffer).  The
+ * profile then does not read it (x = fl32(g + 0) = g: 4 bytes per element less to fetch, which the
+ * memory-bound contractions of the low-rank profile feel most); the compression reads and updates
+ * it as ever, and every result is the one the call gives without the promise.  A buffer that is
+ * not zero under the promise gives a profile of g and a compression of g + e: not an error the
+ * library can see.  Off at creation. */
+int lgreco_set_ef_zero_on_entry(lgreco_handle_t* h, int32_t on);
+
 /* How the last successful solve on this handle swept its table: 0 sequentially, G > 0 in G layer
  * groups, 1000 + G in G groups where ties between ways of sharing the error bins among the groups
  * had to be resolved by Algorithm 1's tie-breaks, -G sequentially after that resolution gave up.

@@ -22,7 +22,8 @@ CALL_PROFILE, CALL_SOLVE, CALL_COMPRESS, CALL_RECEIVE = 0, 1, 2, 3
 EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", "lgreco_profile_solve", "lgreco_profile_solve_compress",
            "lgreco_candidate_range", "lgreco_emax",
            "lgreco_solve", "lgreco_solve_static", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
-           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error", "lgreco_last_solve_groups")
+           "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error", "lgreco_last_solve_groups",
+           "lgreco_set_ef_zero_on_entry")
 
 
 class Layer(C.Structure):
@@ -86,6 +87,7 @@ def lib() -> C.CDLL:
         l.lgreco_strerror.argtypes = [C.c_int]
         l.lgreco_strerror.restype = C.c_char_p
         l.lgreco_last_solve_groups.argtypes = [vp]
+        l.lgreco_set_ef_zero_on_entry.argtypes = [vp, C.c_int32]
         l.lgreco_last_hip_error.argtypes = [vp]
         l.lgreco_last_hip_error.restype = C.c_char_p
         for name in EXPORTS:
@@ -307,6 +309,11 @@ class Handle:
             raise ValueError("buffers differ in size")
         self._check(lib().lgreco_accumulate(self._h, _dptr(d_acc), _dptr(d_grads), int(d_grads.numel()),
                                             int(bool(reset)), _stream(stream)))
+
+    def set_ef_zero_on_entry(self, on: bool):
+        """Promise that the error-feedback buffer of profile_solve_compress holds zeros on entry (the
+        profile then skips reading it); results are unchanged."""
+        self._check(lib().lgreco_set_ef_zero_on_entry(self._h, int(bool(on))))
 
     def last_solve_groups(self) -> int:
         """0: sequential sweep; G: G layer groups; 1000 + G: groups with ties resolved; -G: sequential

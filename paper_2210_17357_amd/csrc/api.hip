@@ -71,6 +71,7 @@ struct lgreco_handle {
     int64_t dp_seq = 0;                  // sequence number of the last solver launch
     int64_t last_solve_groups = 0;       // how the last solve swept its table (the kernel's report)
     // layer groups of the solver (see DpGroups): tree nodes, group ranges
+    bool ef_zero_on_entry = false;          // lgreco_set_ef_zero_on_entry
     uint32_t* d_dp_nodes = nullptr;
     int32_t* d_dp_range = nullptr;
     // lgreco_profile_solve_compress: what the solver kernel needs to write the compression's layer
@@ -364,6 +365,12 @@ const char* lgreco_last_hip_error(const lgreco_handle_t* h) { return h ? h->hip_
 int lgreco_last_solve_groups(const lgreco_handle_t* h) {
     if (!h) return LGRECO_EINVAL;
     return (int)h->last_solve_groups;
+}
+
+int lgreco_set_ef_zero_on_entry(lgreco_handle_t* h, int32_t on) {
+    if (!h) return LGRECO_EINVAL;
+    h->ef_zero_on_entry = on != 0;
+    return LGRECO_OK;
 }
 
 int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max_elems, int32_t max_layers,
@@ -1160,7 +1167,9 @@ int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, floa
     if ((uintptr_t)d_grads % 16 || (uintptr_t)d_ef % 16 || (uintptr_t)d_payload % 16) return LGRECO_EINVAL;
     EarlyCompress ec{d_ef, d_payload, payload_capacity};
     ec.d_q = d_q;
-    int st = profile_solve_impl(h, d_grads, d_ef, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
+    // a buffer the caller promises to be all zeros is not read by the profile: x = fl32(g + 0) = g
+    const float* const d_ef_profile = h->ef_zero_on_entry ? nullptr : d_ef;
+    int st = profile_solve_impl(h, d_grads, d_ef_profile, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
                                 e_max, choice, total_size, total_error, stream, &ec);
     if (st != LGRECO_OK) return st;
     // the layout of lgreco_payload_layout, from the size table the profile just filled

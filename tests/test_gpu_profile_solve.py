@@ -333,3 +333,62 @@ def test_whole_path_call_on_degenerate_topk_layers(default, n_bins):
     assert torch.equal(pay2, pay) and torch.equal(ef2.view(torch.int32), ef.view(torch.int32))
     h2.close()
     h.close()
+
+
+@pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
+def test_zero_error_feedback_promise_changes_nothing(kind):
+    """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return
+    the same tables, assignment, payload, error feedback and warm start whether or not the caller
+    made the promise (the profile then skips the buffer), call after call on the same handle, and
+    go back to reading the buffer when the promise is withdrawn."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    if kind == "lowrank":
+        base = W.workload("c3_transformer_lm_lowrank")
+        shapes = tuple(s for s in W.transformer_lm_shapes(layers=1, d=256, d_ff=512, vocab=1024) if len(s) == 2)
+        w = W.Workload("zp_lowrank", shapes, base.candidates, base.default, 200, base.values, base.ef,
+                       base.scale_exp, only_2d=True, r_max=base.r_max)
+    else:
+        w = _workload(kind)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, q0 = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+
+    def run(h, ef_in):
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = ef_in.clone()
+        q = q0.clone() if q0 is not None else None
+        out = h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, pay, q)
+        torch.cuda.synchronize()
+        assert out[0] == B.OK
+        return out, pay, ef, q
+
+    def same(a, b):
+        (oa, pa, ea, qa), (ob, pb, eb, qb) = a, b
+        assert np.array_equal(oa[1], ob[1]) and oa[3] == ob[3] and np.array_equal(oa[4], ob[4])
+        assert np.array_equal(oa[7], ob[7])
+        assert torch.equal(pa, pb) and torch.equal(ea.view(torch.int32), eb.view(torch.int32))
+        if qa is not None:
+            assert torch.equal(qa.view(torch.int32), qb.view(torch.int32))
+
+    zeros = torch.zeros_like(g)
+
+    def handle():
+        return B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, r_max=w.r_max,
+                        reuse_thresholds=True)
+    # two handles side by side, call for call (with reuse_thresholds a handle's n-th call sums the
+    # energies below a bound that depends on its earlier calls, so only equal histories compare bit for bit)
+    plain, promised = handle(), handle()
+    promised.set_ef_zero_on_entry(True)
+    for _ in range(3):
+        same(run(promised, zeros), run(plain, zeros))
+    promised.set_ef_zero_on_entry(False)
+    same(run(promised, zeros), run(plain, zeros))
+    if e is not None:
+        # promise withdrawn: a buffer that is not zero is read again
+        same(run(promised, e), run(plain, e))
+    plain.close()
+    promised.close()
