@@ -307,26 +307,48 @@ void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
 }
 
 // Waits for the solver launch `seq` to hand over its result block.  The kernel writes the block
-// straight into pinned host memory and stores its sequence number last, behind a system-scope
-// fence: polling that word sees the end of the solve several microseconds before a stream
-// synchronisation returns (the stream is still retiring the kernel then; the caller's next
+// straight into pinned host memory and stores its sequence number last (slot 7), behind a
+// system-scope fence: polling that word sees the end of the solve several microseconds before a
+// stream synchronisation returns (the stream is still retiring the kernel then; the caller's next
 // launches queue behind it as usual).  Nothing else is asked of the stream meanwhile - a status
 // query can put a marker into the queue, which then sits between this call's kernels and the
-// next ones.  A word that does not arrive within the limit (a solve that long, or a launch that
-// failed) ends in an ordinary stream synchronisation, which also brings up any error.
-int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s) {
-    volatile const int64_t* const flag = h->h_result + 7;
+// next ones.
+// The hand-over does not lean on the order in which the kernel's stores reach host memory: both
+// 64-byte halves of the block carry a copy of the sequence number (slots 4 and 15, written with
+// the block's other slots by one store), and the assignment is covered by a check word (slot 10,
+// the sum of (candidate + 1) * (swept layer + 1)).  The block is taken as complete when all three
+// sequence words agree and, for a solved table, the assignment in memory adds up to the check
+// word; until then the host keeps polling.  Whatever does not arrive within the limit (a solve
+// that long, a launch that failed) ends in an ordinary stream synchronisation, which also brings
+// up any error, and a block that still does not add up then is reported, never used.
+//   n_choice: swept layers whose assignment follows the block; < 0: the list-building kernel's
+//   count in slot 5 (complete before the solver kernel started)
+int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s, int n_choice) {
+    volatile const int64_t* const r = h->h_result;
+    volatile const int32_t* const ch = h->h_choice;
+    auto complete = [&]() -> bool {
+        if (r[7] != seq || r[4] != seq || r[15] != seq) return false;
+        if (r[0] != 0) return true;                          // nothing was traced back
+        const int n = n_choice >= 0 ? n_choice : (int)r[5];
+        if (n < 0 || n > h->max_layers) return false;
+        uint64_t sum = 0;
+        for (int i = 0; i < n; ++i) sum += (uint64_t)(uint32_t)(ch[i] + 1) * (uint64_t)(i + 1);
+        return sum == (uint64_t)r[10];
+    };
     const auto t0 = std::chrono::steady_clock::now();
-    for (uint32_t polls = 1; *flag != seq; ++polls) {
+    bool ok = false;
+    for (uint32_t polls = 1;; ++polls) {
+        if (r[7] == seq && (ok = complete())) break;
         if ((polls & 0x3FFu) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(50)) break;
 #if !defined(__HIP_DEVICE_COMPILE__) && (defined(__x86_64__) || defined(__i386__))
         asm volatile("pause");
 #endif
     }
-    if (*flag != seq) {
+    if (!ok) {
         HIPCHK(hipStreamSynchronize(s));
-        if (*flag != seq) {
-            h->hip_error = "the solver kernel did not report";
+        if (!complete()) {
+            h->hip_error = r[7] != seq ? "the solver kernel did not report"
+                                       : "the solver's result block and its check words disagree";
             return LGRECO_EHIP;
         }
     }
@@ -337,9 +359,9 @@ int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s) {
 // Device-clock sub-sections of the solve (100 MHz constant-rate counter).
 void record_dp_sub(lgreco_handle* h) {
     h->sub_name[0] = "dp_solve.sweep";
-    h->sub_ms[0] = (float)((double)h->h_result[3] * 1e-5);
+    h->sub_ms[0] = (float)((double)((uint64_t)h->h_result[3] & 0xFFFFFFFFull) * 1e-5);
     h->sub_name[1] = "dp_solve.backtrace";
-    h->sub_ms[1] = (float)((double)h->h_result[4] * 1e-5);
+    h->sub_ms[1] = (float)((double)((uint64_t)h->h_result[3] >> 32) * 1e-5);
     h->n_sub = 2;
     for (int j = 0; j < 2; ++j) h->tms[LGRECO_CALL_SOLVE].add_total(h->sub_name[j], (double)h->sub_ms[j]);
 }
@@ -856,7 +878,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         }
         harvest_others(h);
         {
-            const int wst = wait_for_solver(h, h->dp_seq, s);     // the kernel wrote h_dp_out
+            const int wst = wait_for_solver(h, h->dp_seq, s, n_sweep);     // the kernel wrote h_dp_out
             if (wst != LGRECO_OK) return wst;
         }
         h->last_solve_groups = h->h_result[9];
@@ -997,7 +1019,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     harvest_others(h);
     {
         // error table, build report and solver output are in pinned memory
-        const int wst = wait_for_solver(h, h->dp_seq, s);
+        const int wst = wait_for_solver(h, h->dp_seq, s, -1);
         if (wst != LGRECO_OK) return wst;
     }
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);

@@ -336,6 +336,7 @@ __device__ __forceinline__ void dp_finish(const DpParams& p, const int L, const 
     const int bstride = p.max_count;
     const bool feasible = s_val[0] < (int64_t)kInf;
     const bool traced = feasible && lds_bins && s_idx[1] == 0;
+    int64_t applied = 0;                 // the layer records were written (workgroup-uniform)
     if (p.apply.layers) {
         // The compression's layer records from the assignment, one thread per layer: candidate per
         // layer first (fixed layers from the build's report, swept ones from the back-trace), then
@@ -395,34 +396,51 @@ __device__ __forceinline__ void dp_finish(const DpParams& p, const int L, const 
         }
         if (A.L > kDpThreads)
             for (int l = kDpThreads + tid; l < A.L; l += kDpThreads) A.layers[l].family = -1;
-        if (tid == 0) p.result[8] = ok ? 1 : 0;
+        applied = ok ? 1 : 0;
     }
     // The result block lies in the host's pinned memory and the host may be polling it: the first
     // wavefront alone writes it (the other writer of host memory, the back-trace without LDS
-    // tables, is its thread 0), puts a system-scope fence behind its stores and the launch's
-    // sequence number behind the fence.
+    // tables, is its thread 0).  What the host relies on does not depend on the order in which
+    // the stores arrive there: the slots of this kernel go out as ONE store of the wavefront (lane
+    // i holds slot i; the 128-byte block is two 64-byte halves, each carrying a copy of the
+    // launch's sequence number), the assignment is covered by a check word in the block, and the
+    // sequence number in slot 7, which the host polls, follows behind a system-scope fence.
     if (tid >= 64) return;
-    if (traced)
-        for (int l = lane; l < L; l += 64)
-            p.choice[l] = p.entries[(size_t)l * bstride + s_pick[l]].cand;
-    if (tid == 0) {
-        if (!feasible) {
-            p.result[0] = 1;
-            p.result[1] = 0;
-            p.result[2] = 0;
-        } else {
-            p.result[0] = (s_idx[1] == 0) ? 0 : 2;   // 2 would be an internal inconsistency
-            p.result[1] = s_val[0];
-            p.result[2] = s_idx[0];
+    unsigned long long check = 0;        // sum of (candidate + 1) * (swept layer + 1): see dp_result_check
+    if (traced) {
+        for (int l = lane; l < L; l += 64) {
+            const int32_t cand = p.entries[(size_t)l * bstride + s_pick[l]].cand;
+            p.choice[l] = cand;
+            check += (unsigned long long)(uint32_t)(cand + 1) * (unsigned long long)(l + 1);
         }
-        // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep and back-trace;
+        for (int o = 1; o < 64; o <<= 1) check += (unsigned long long)__shfl_xor((long long)check, o, 64);
+    } else if (!lds_bins) {
+        check = (unsigned long long)s_val[2];         // summed by the thread that wrote the assignment
+    }
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)t_sweep);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(t_sweep >> 32));
+    const uint64_t tsw = ((uint64_t)hi << 32) | lo;                  // thread 0 took the time
+    const uint64_t ticks_sweep = tsw - t_begin, ticks_trace = wall_clock64() - tsw;
+    int64_t v = 0;
+    bool mine = true;
+    switch (lane) {
+        case 0: v = !feasible ? 1 : ((s_idx[1] == 0) ? 0 : 2); break;      // 2 would be an internal inconsistency
+        case 1: v = feasible ? s_val[0] : 0; break;
+        case 2: v = feasible ? (int64_t)s_idx[0] : 0; break;
+        // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep (low half) and
+        // back-trace (high half)
+        case 3: v = (int64_t)((ticks_sweep & 0xFFFFFFFFull) | (ticks_trace << 32)); break;
+        case 4: v = p.seq; break;
+        case 8: v = applied; break;
         // how the table was swept: 0 sequentially, G in G groups, 1000 + G in G groups with
         // ambiguous splits resolved by comparing traced sequences, -G sequentially after the
         // grouped route gave up
-        p.result[3] = (int64_t)(t_sweep - t_begin);
-        p.result[4] = (int64_t)(wall_clock64() - t_sweep);
-        p.result[9] = how;
+        case 9: v = how; break;
+        case 10: v = (int64_t)check; break;
+        case 15: v = p.seq; break;
+        default: mine = false;                    // 5, 6: the list-building kernel's; 7: below
     }
+    if (mine) p.result[lane] = v;
     __threadfence_system();
     if (tid == 0) p.result[7] = p.seq;
 }
@@ -434,10 +452,13 @@ __device__ __forceinline__ void dp_hand_over_unsolved(const DpParams& p) {
     const int tid = threadIdx.x;
     if (p.apply.layers)
         for (int l = tid; l < p.apply.L; l += kDpThreads) p.apply.layers[l].family = -1;
-    if (tid == 0) {
-        p.result[8] = 0;
+    if (tid < 64) {
+        // slots as in dp_finish; the status in slot 0 is the list-building kernel's
+        const int lane = tid;
+        if (lane == 4 || lane == 15) p.result[lane] = p.seq;
+        if (lane == 8 || lane == 10) p.result[lane] = 0;
         __threadfence_system();
-        p.result[7] = p.seq;
+        if (tid == 0) p.result[7] = p.seq;
     }
 }
 
@@ -507,12 +528,15 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
                     e -= s_bins[l * bstride + k];
                 }
             } else {
+                unsigned long long check = 0;
                 for (int l = L - 1; l >= 0; --l) {
                     const int k = p.pd[(size_t)l * width + e];
                     const DpEntry en = p.entries[(size_t)l * bstride + k];
                     p.choice[l] = en.cand;
+                    check += (unsigned long long)(uint32_t)(en.cand + 1) * (unsigned long long)(l + 1);
                     e -= en.bin;
                 }
+                s_val[2] = (int64_t)check;
             }
         }
         if (tid == 0) s_idx[1] = e;

@@ -22,7 +22,10 @@ def _compare(h, errors, sizes, e_max, n_bins):
         assert np.array_equal(choice, np.argmin(errors, axis=1))
         return
     assert st == B.OK
-    assert np.array_equal(choice, ref_choice)
+    differ = np.flatnonzero(choice != ref_choice)
+    assert differ.size == 0, ("route", h.last_solve_groups(), "layers", differ.tolist()[:16], "got",
+                              choice[differ][:16].tolist(), "oracle", ref_choice[differ][:16].tolist(),
+                              "size", tsize, ref_size)
     assert tsize == ref_size and terr == pytest.approx(ref_err, rel=1e-15)
 
 
