@@ -406,14 +406,25 @@ __device__ __forceinline__ void dp_finish(const DpParams& p, const int L, const 
     // launch's sequence number), the assignment is covered by a check word in the block, and the
     // sequence number in slot 7, which the host polls, follows behind a system-scope fence.
     if (tid >= 64) return;
-    unsigned long long check = 0;        // sum of (candidate + 1) * (swept layer + 1): see dp_result_check
+    unsigned long long check = 0;        // sum of (candidate + 1) * (swept layer + 1): the host's check word
+    bool adds_up = true;
     if (traced) {
+        // the assignment goes out, and is held against the cell it was traced from on the way:
+        // its bins must sum to e*, its costs to the minimum found there
+        long long sum_bin = 0, sum_cost = 0;
         for (int l = lane; l < L; l += 64) {
-            const int32_t cand = p.entries[(size_t)l * bstride + s_pick[l]].cand;
-            p.choice[l] = cand;
-            check += (unsigned long long)(uint32_t)(cand + 1) * (unsigned long long)(l + 1);
+            const DpEntry en = p.entries[(size_t)l * bstride + s_pick[l]];
+            p.choice[l] = en.cand;
+            check += (unsigned long long)(uint32_t)(en.cand + 1) * (unsigned long long)(l + 1);
+            sum_bin += en.bin;
+            sum_cost += en.size;
         }
-        for (int o = 1; o < 64; o <<= 1) check += (unsigned long long)__shfl_xor((long long)check, o, 64);
+        for (int o = 1; o < 64; o <<= 1) {
+            check += (unsigned long long)__shfl_xor((long long)check, o, 64);
+            sum_bin += __shfl_xor(sum_bin, o, 64);
+            sum_cost += __shfl_xor(sum_cost, o, 64);
+        }
+        adds_up = sum_bin == (long long)s_idx[0] && sum_cost == (long long)s_val[0];
     } else if (!lds_bins) {
         check = (unsigned long long)s_val[2];         // summed by the thread that wrote the assignment
     }
@@ -424,7 +435,7 @@ __device__ __forceinline__ void dp_finish(const DpParams& p, const int L, const 
     int64_t v = 0;
     bool mine = true;
     switch (lane) {
-        case 0: v = !feasible ? 1 : ((s_idx[1] == 0) ? 0 : 2); break;      // 2 would be an internal inconsistency
+        case 0: v = !feasible ? 1 : ((s_idx[1] == 0 && adds_up) ? 0 : 2); break;      // 2: an internal inconsistency
         case 1: v = feasible ? s_val[0] : 0; break;
         case 2: v = feasible ? (int64_t)s_idx[0] : 0; break;
         // diagnostics: ticks of the constant-rate (100 MHz) counter spent in sweep (low half) and
