@@ -338,6 +338,11 @@ int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** name
  * library can see.  Off at creation. */
 int lgreco_set_ef_zero_on_entry(lgreco_handle_t* h, int32_t on);
 
+/* How many solves on this handle found the solver's result block incomplete when its sequence
+ * number had already arrived in host memory (the block's check words caught it and the call went
+ * on waiting until the block was whole).  Diagnostics only. */
+int64_t lgreco_late_handovers(const lgreco_handle_t* h);
+
 /* How the last successful solve on this handle swept its table: 0 sequentially, G > 0 in G layer
  * groups, 1000 + G in G groups where ties between ways of sharing the error bins among the groups
  * had to be resolved by Algorithm 1's tie-breaks, -G sequentially after that resolution gave up.

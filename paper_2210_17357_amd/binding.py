@@ -23,7 +23,7 @@ EXPORTS = ("lgreco_create", "lgreco_destroy", "lgreco_sizes", "lgreco_profile", 
            "lgreco_candidate_range", "lgreco_emax",
            "lgreco_solve", "lgreco_solve_static", "lgreco_solve_weighted", "lgreco_payload_layout", "lgreco_compress", "lgreco_decompress", "lgreco_accumulate", "lgreco_set_timing", "lgreco_set_timing_stride",
            "lgreco_get_timing", "lgreco_get_timing_of", "lgreco_get_timing_totals", "lgreco_strerror", "lgreco_last_hip_error", "lgreco_last_solve_groups",
-           "lgreco_set_ef_zero_on_entry")
+           "lgreco_set_ef_zero_on_entry", "lgreco_late_handovers")
 
 
 class Layer(C.Structure):
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
         l.lgreco_strerror.restype = C.c_char_p
         l.lgreco_last_solve_groups.argtypes = [vp]
         l.lgreco_set_ef_zero_on_entry.argtypes = [vp, C.c_int32]
+        l.lgreco_late_handovers.argtypes = [vp]
+        l.lgreco_late_handovers.restype = C.c_int64
         l.lgreco_last_hip_error.argtypes = [vp]
         l.lgreco_last_hip_error.restype = C.c_char_p
         for name in EXPORTS:
@@ -314,6 +316,11 @@ class Handle:
         """Promise that the error-feedback buffer of profile_solve_compress holds zeros on entry (the
         profile then skips reading it); results are unchanged."""
         self._check(lib().lgreco_set_ef_zero_on_entry(self._h, int(bool(on))))
+
+    def late_handovers(self) -> int:
+        """Solves whose result block was still incomplete in host memory when its sequence number had
+        arrived (caught by the block's check words)."""
+        return int(lib().lgreco_late_handovers(self._h))
 
     def last_solve_groups(self) -> int:
         """0: sequential sweep; G: G layer groups; 1000 + G: groups with ties resolved; -G: sequential

@@ -72,6 +72,7 @@ struct lgreco_handle {
     int64_t last_solve_groups = 0;       // how the last solve swept its table (the kernel's report)
     // layer groups of the solver (see DpGroups): tree nodes, group ranges
     bool ef_zero_on_entry = false;          // lgreco_set_ef_zero_on_entry
+    int64_t late_handovers = 0;             // solves whose result block was incomplete when its sequence number arrived
     uint32_t* d_dp_nodes = nullptr;
     int32_t* d_dp_range = nullptr;
     // lgreco_profile_solve_compress: what the solver kernel needs to write the compression's layer
@@ -337,8 +338,15 @@ int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s, int n_choice) 
     };
     const auto t0 = std::chrono::steady_clock::now();
     bool ok = false;
+    bool counted = false;
     for (uint32_t polls = 1;; ++polls) {
-        if (r[7] == seq && (ok = complete())) break;
+        if (r[7] == seq) {
+            if ((ok = complete())) break;
+            if (!counted) {                  // the sequence number was there before the rest of the block
+                ++h->late_handovers;
+                counted = true;
+            }
+        }
         if ((polls & 0x3FFu) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(50)) break;
 #if !defined(__HIP_DEVICE_COMPILE__) && (defined(__x86_64__) || defined(__i386__))
         asm volatile("pause");
@@ -388,6 +396,8 @@ int lgreco_last_solve_groups(const lgreco_handle_t* h) {
     if (!h) return LGRECO_EINVAL;
     return (int)h->last_solve_groups;
 }
+
+int64_t lgreco_late_handovers(const lgreco_handle_t* h) { return h ? h->late_handovers : 0; }
 
 int lgreco_set_ef_zero_on_entry(lgreco_handle_t* h, int32_t on) {
     if (!h) return LGRECO_EINVAL;

@@ -27,6 +27,8 @@ def _compare(h, errors, sizes, e_max, n_bins):
                               choice[differ][:16].tolist(), "oracle", ref_choice[differ][:16].tolist(),
                               "size", tsize, ref_size)
     assert tsize == ref_size and terr == pytest.approx(ref_err, rel=1e-15)
+    if h.late_handovers():
+        print("result blocks that arrived after their sequence number so far on this handle:", h.late_handovers())
 
 
 def test_random_small_tables_with_ties_and_unusable_candidates():
