@@ -322,16 +322,33 @@ void begin_call(lgreco_handle* h, hipStream_t s, int kind) {
 // word; until then the host keeps polling.  Whatever does not arrive within the limit (a solve
 // that long, a launch that failed) ends in an ordinary stream synchronisation, which also brings
 // up any error, and a block that still does not add up then is reported, never used.
-//   n_choice: swept layers whose assignment follows the block; < 0: the list-building kernel's
-//   count in slot 5 (complete before the solver kernel started)
-int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s, int n_choice) {
+// What the list-building kernel (an earlier launch of the same call) left in host memory - the
+// error table and its report of fixed and swept layers - has check words of its own (slots 11,
+// 12) and is held against them in the same way.
+//   n_choice: swept layers whose assignment follows the block; < 0: lists built on the device,
+//   the count is in slot 5 and the error table (L x P) and the report are checked as well
+int wait_for_solver(lgreco_handle* h, int64_t seq, hipStream_t s, int n_choice, int L = 0, int P = 0) {
     volatile const int64_t* const r = h->h_result;
     volatile const int32_t* const ch = h->h_choice;
     auto complete = [&]() -> bool {
         if (r[7] != seq || r[4] != seq || r[15] != seq) return false;
-        if (r[0] != 0) return true;                          // nothing was traced back
         const int n = n_choice >= 0 ? n_choice : (int)r[5];
         if (n < 0 || n > h->max_layers) return false;
+        if (n_choice < 0) {
+            volatile const uint64_t* const eb = reinterpret_cast<volatile const uint64_t*>(h->h_errors);
+            uint64_t ce = 0;
+            for (int i = 0; i < L * P; ++i) ce += eb[i] * (uint64_t)(i + 1);
+            if (ce != (uint64_t)r[11]) return false;
+            if (r[0] == 0) {                     // the report is read for a solved table only
+                volatile const int32_t* const sweep_layer = h->h_build;
+                volatile const int32_t* const fixed_choice = h->h_build + L;
+                uint64_t cb = 0;
+                for (int l = 0; l < L; ++l) cb += (uint64_t)(uint32_t)(fixed_choice[l] + 2) * (uint64_t)(l + 1);
+                for (int i = 0; i < n; ++i) cb += 65537ull * (uint64_t)(sweep_layer[i] + 1) * (uint64_t)(i + 1);
+                if (cb != (uint64_t)r[12]) return false;
+            }
+        }
+        if (r[0] != 0) return true;                          // nothing was traced back
         uint64_t sum = 0;
         for (int i = 0; i < n; ++i) sum += (uint64_t)(uint32_t)(ch[i] + 1) * (uint64_t)(i + 1);
         return sum == (uint64_t)r[10];
@@ -1029,7 +1046,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     harvest_others(h);
     {
         // error table, build report and solver output are in pinned memory
-        const int wst = wait_for_solver(h, h->dp_seq, s, -1);
+        const int wst = wait_for_solver(h, h->dp_seq, s, -1, L, P);
         if (wst != LGRECO_OK) return wst;
     }
     std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);

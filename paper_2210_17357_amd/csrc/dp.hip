@@ -850,10 +850,17 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
     __shared__ double s_emax;
     __shared__ int32_t s_wave[kBuildThreads / 64];
     __shared__ int32_t s_flags[2];          // [0] a layer without usable candidate, [1] invalid input
+    // check words over what this kernel writes into the host's memory (the host holds what it reads
+    // there against them): [0] the error table, sum of bit pattern * (index + 1); [1] the report,
+    // sum of (fixed choice + 2) * (layer + 1) plus 65537 * sum of (swept layer + 1) * (slot + 1)
+    __shared__ unsigned long long s_chk[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = p.L, P = p.P, LP = L * P;
     const double D = (double)p.D;
-    if (tid < 2) s_flags[tid] = 0;
+    if (tid < 2) {
+        s_flags[tid] = 0;
+        s_chk[tid] = 0;
+    }
     {
         // whole 16-byte words, then the odd last entry on its own: a caller's table ends at LP entries
         const int n16 = LP / 2;
@@ -874,6 +881,13 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         }
     }
     __syncthreads();
+    if (p.errors_host) {
+        unsigned long long c = 0;
+        for (int i = tid; i < LP; i += kBuildThreads)
+            c += __builtin_bit_cast(unsigned long long, s_err[i]) * (unsigned long long)(i + 1);
+        for (int o = 1; o < 64; o <<= 1) c += (unsigned long long)__shfl_xor((long long)c, o, 64);
+        if (lane == 0) atomicAdd(&s_chk[0], c);
+    }
     // This path sweeps with 32-bit costs.  A caller whose size table the host has not seen asks for
     // the check here: sizes must be non-negative and every layer's largest, summed, below 2^30.
     if (p.check_sizes) {
@@ -978,6 +992,13 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         total += s_wave[w];
     }
     const int slot = base + before;
+    {
+        unsigned long long c = 0;
+        if (active) c = (unsigned long long)(uint32_t)((fixed ? first_cand : -1) + 2) * (unsigned long long)(tid + 1);
+        if (swept) c += 65537ull * (unsigned long long)(tid + 1) * (unsigned long long)(slot + 1);
+        for (int o = 1; o < 64; o <<= 1) c += (unsigned long long)__shfl_xor((long long)c, o, 64);
+        if (lane == 0) atomicAdd(&s_chk[1], c);
+    }
     if (active) {
         p.fixed_choice[tid] = fixed ? first_cand : -1;
         p.fixed_choice_dev[tid] = fixed ? first_cand : -1;
@@ -991,6 +1012,7 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         for (int c = 0; c < P; ++c)
             if (s_kept[tid * P + c]) en[r++] = DpEntry{s_bin[tid * P + c], c, s_size[tid * P + c]};
     }
+    __syncthreads();                           // the check words are complete
     if (tid == 0) {
         const int status = s_flags[1] ? 3 : (s_flags[0] ? 1 : 0);  // 3: invalid input, 1: infeasible
         p.n_sweep[0] = total;
@@ -998,6 +1020,8 @@ __global__ __launch_bounds__(kBuildThreads) void dp_build_kernel(DpBuildParams p
         p.result[0] = status;
         p.result[5] = total;
         p.result[6] = (int64_t)__builtin_bit_cast(uint64_t, e_max);
+        p.result[11] = (int64_t)s_chk[0];
+        p.result[12] = (int64_t)s_chk[1];
     }
 }
 
