@@ -98,6 +98,11 @@ typedef struct {
                             * sweep; 2, 4, 8 = sweep the layers in that many groups side by side and
                             * join the groups' tables (results are the same in every case,
                             * Algorithm 1's tie-breaks included) */
+    int32_t  strict_budget; /* solver: 0 = Algorithm 1's constraint on the discretised errors, sum of
+                            * bins <= n_bins, under which the real errors may exceed e_max by up to
+                            * L steps (see lgreco_solve); 1 = only assignments whose bins sum to at
+                            * most n_bins - L are accepted, which keeps the sum of the real errors
+                            * below e_max (section "The Constrained Optimization Problem") */
 } lgreco_config_t;
 
 /* Create a handle for problems of at most max_elems gradient elements (sum of numel),
@@ -156,8 +161,11 @@ int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand
  * The constraint is on the discretised errors: every bin rounds its error down by less than one
  * step, so an assignment the solver accepts has total_error < e_max * (1 + L / n_bins), not
  * total_error <= e_max.  The return value is still LGRECO_OK then (the paper's algorithm accepts
- * the same assignments); a caller that needs the strict bound compares total_error with e_max
- * itself, or solves with e_max / (1 + L / n_bins).
+ * the same assignments); a caller that needs total_error <= e_max creates the handle with
+ * strict_budget = 1: the bins of an accepted assignment then sum to at most n_bins - L.  That
+ * tighter budget may leave no assignment (LGRECO_EINFEASIBLE) where the plain one has some;
+ * lgreco_profile_solve and lgreco_profile_solve_compress, which know the uniform default, return
+ * the default then (its total error is e_max itself).
  * Returns LGRECO_EINFEASIBLE if no assignment fits; choice then holds each layer's
  * minimum-error candidate.  n_bins <= LGRECO_MAX_BINS. */
 int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes, int32_t L,

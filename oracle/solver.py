@@ -89,11 +89,14 @@ def dp_tables_fast(bins: np.ndarray, sizes: np.ndarray, n_bins: int):
     return dp, pd
 
 
-def backtrace(dp: np.ndarray, pd: np.ndarray, bins: np.ndarray):
+def backtrace(dp: np.ndarray, pd: np.ndarray, bins: np.ndarray, e_limit=None):
     """Algorithm 1, reconstruction: lowest e among the minima of the last row, then walk back.
+    With e_limit only the cells 0..e_limit of the last row are looked at (see solve, strict).
     Returns None if no assignment fits."""
     n_layers = bins.shape[0]
-    last = dp[n_layers]
+    last = dp[n_layers] if e_limit is None else dp[n_layers][:max(e_limit + 1, 0)]
+    if last.size == 0:
+        return None
     best = int(last.min())
     if best >= INF:
         return None
@@ -107,13 +110,22 @@ def backtrace(dp: np.ndarray, pd: np.ndarray, bins: np.ndarray):
     return choice
 
 
-def solve(errors: np.ndarray, sizes: np.ndarray, e_max: float, n_bins: int, fast: bool = True):
-    """Returns (choice int32[L] or None, total_size, total_error)."""
+def strict_limit(n_layers: int, n_bins: int) -> int:
+    """Largest bin sum that guarantees sum error <= E_max: every bin rounds its error down by less
+    than one step E_max / D, so sum error < (sum bin + L) * E_max / D, which is at most E_max when
+    sum bin <= D - L (section "The Constrained Optimization Problem" asks for sum error <= E_max;
+    the discretised constraint sum bin <= D alone allows an overshoot of up to L steps)."""
+    return n_bins - n_layers
+
+
+def solve(errors: np.ndarray, sizes: np.ndarray, e_max: float, n_bins: int, fast: bool = True, strict: bool = False):
+    """Returns (choice int32[L] or None, total_size, total_error).  strict: accept only
+    assignments whose bins sum to at most strict_limit, so that the real errors stay within E_max."""
     errors = np.asarray(errors, np.float64)
     sizes = np.asarray(sizes, np.int64)
     bins = discretise(errors, e_max, n_bins)
     dp, pd = (dp_tables_fast if fast else dp_tables)(bins, sizes, n_bins)
-    choice = backtrace(dp, pd, bins)
+    choice = backtrace(dp, pd, bins, strict_limit(errors.shape[0], n_bins) if strict else None)
     if choice is None:
         return None, None, None
     rows = np.arange(errors.shape[0])

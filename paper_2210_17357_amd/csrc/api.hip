@@ -429,6 +429,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     if (cfg->bucket != kBucket) return LGRECO_EUNSUPPORTED;
     if (cfg->power_iters < 1 || cfg->power_iters > 16) return LGRECO_EUNSUPPORTED;
     if (cfg->r_max < 0 || cfg->r_max > 64) return LGRECO_EUNSUPPORTED;
+    if (cfg->strict_budget != 0 && cfg->strict_budget != 1) return LGRECO_EINVAL;
     if (cfg->dp_groups != 0 && cfg->dp_groups != 1 && cfg->dp_groups != 2 && cfg->dp_groups != 4 &&
         cfg->dp_groups != 8)
         return LGRECO_EINVAL;
@@ -888,6 +889,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         return LGRECO_EINFEASIBLE;
     };
     if (dead_layer) return infeasible();
+    if (h->cfg.strict_budget && n_bins - L < 0) return infeasible();      // more layers than bins: nothing is certain to fit
     if (n_sweep > 0) {
         const bool narrow = worst < ((int64_t)1 << 30);
         // the kernel's table has max_count entries per layer: the upload carries no unused slots
@@ -899,6 +901,7 @@ int lgreco_solve(lgreco_handle_t* h, const double* errors, const int64_t* sizes,
         DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, n_sweep, n_bins, 0, 0, 0, max_count,
                     h->d_dp_in_host, reinterpret_cast<uint4*>(h->d_dp_in), (int32_t)((in_bytes + 15) / 16), nullptr,
                     ++h->dp_seq, DpApply{}, dp_groups(h)};
+        if (h->cfg.strict_budget) dp.e_limit = n_bins - L;        // all L layers round down, the fixed ones too
         {
             Section sec(h->tm, "dp_solve", true);
             HIPCHK(launch_dp(dp, narrow, max_bin, s, &sec, true));
@@ -938,6 +941,21 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     if (default_cand < 0 || default_cand >= P || n_bins < 1 || n_bins > LGRECO_MAX_BINS) return LGRECO_EINVAL;
     if (L > h->max_layers || P > h->max_cands) return LGRECO_ENOSPACE;
     hipStream_t s = (hipStream_t)stream;
+    // strict budget, nothing fits it: the uniform default, whose total error is E_max itself (the
+    // device wrote no layer records then: a compression that follows takes the host's route)
+    auto strict_default = [&](const double* err, const int64_t* sz) {
+        double terr = 0.0;
+        int64_t tsize = 0;
+        for (int l = 0; l < L; ++l) {
+            choice[l] = default_cand;
+            terr += err[(size_t)l * P + default_cand];
+            tsize += sz[(size_t)l * P + default_cand];
+        }
+        h->last_solve_groups = 0;
+        if (total_size) *total_size = tsize;
+        if (total_error) *total_error = terr;
+        return (int)LGRECO_OK;
+    };
     // the device-side build reads the error table from device memory and passes it on to the host
     const bool on_device = L <= kBuildThreads && P <= kBuildMaxP && L * P <= kBuildMaxLP;
     int st = profile_enqueue(h, d_grads, d_ef, layers, L, cands, P, d_q0, sizes,
@@ -963,7 +981,9 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         std::memcpy(errors, h->h_errors, sizeof(double) * (size_t)L * P);
         st = lgreco_emax(errors, L, P, default_cand, e_max);
         if (st != LGRECO_OK) return st;
-        return lgreco_solve(h, errors, sizes, L, P, *e_max, n_bins, choice, total_size, total_error, stream);
+        st = lgreco_solve(h, errors, sizes, L, P, *e_max, n_bins, choice, total_size, total_error, stream);
+        if (st == LGRECO_EINFEASIBLE && h->cfg.strict_budget) return strict_default(errors, sizes);
+        return st;
     }
     begin_call(h, s, LGRECO_CALL_SOLVE);
     // the size table lives on the device and is uploaded when it changes (a training loop repeats it)
@@ -978,6 +998,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
                      h->d_nsweep, h->d_result};
     DpParams dp{h->d_entries, h->d_count, h->d_pd, h->d_choice, h->d_result, L, n_bins, 0, 0, 0, P,
                 nullptr, nullptr, 0, h->d_nsweep, ++h->dp_seq, DpApply{}, dp_groups(h)};
+    if (h->cfg.strict_budget) dp.e_limit = n_bins - L;
     if (ec) {
         // what every (layer, candidate) means to the compression kernels, as lgreco_compress works
         // it out for a choice: the solver kernel picks the chosen column
@@ -1059,6 +1080,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     }
     if (status == 3) return LGRECO_EINVAL;                  // a NaN in the error table
     if (h->tm->active && status == 0) record_dp_sub(h);
+    if (status == 1 && h->cfg.strict_budget) return strict_default(errors, sizes);
     if (status == 1) {                                      // report each layer's minimum-error candidate
         for (int l = 0; l < L; ++l) {
             int best = 0;

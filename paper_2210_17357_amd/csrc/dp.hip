@@ -524,7 +524,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_kernel(DpParams p) {
     for (int e = tid - p.pad; e < KMAX * kDpThreads; e += kDpThreads) row[e] = (e == 0) ? (T)0 : kInf;
     dp_sweep_layers<T, KMAX, PADDED, kDpThreads>(p, row, s_entries, s_count, lds_bins ? s_bins : nullptr, 0, L);
     __syncthreads();
-    dp_argmin<T, kDpThreads>(row, p.D, s_val, s_idx);
+    dp_argmin<T, kDpThreads>(row, min(p.D, p.e_limit), s_val, s_idx);
     uint64_t t_sweep = 0;
     if (tid == 0) t_sweep = wall_clock64();
     if (tid < 64 && s_val[0] < (int64_t)kInf) {
@@ -607,7 +607,7 @@ __global__ __launch_bounds__(kDpThreads) void dp_trace_kernel(DpParams p) {
     // the bin of every entry, for the walks
     for (int i = tid; i < L * bstride; i += kDpThreads) s_bins[i] = (uint16_t)p.entries[i].bin;
     if (tid == 0) { s_tie = 0; s_walk_bad = 0; s_slow_ok = 0; }
-    dp_argmin<T, kDpThreads>(gr.nodes, D, s_val, s_idx);
+    dp_argmin<T, kDpThreads>(gr.nodes, min(D, p.e_limit), s_val, s_idx);
     bool resolved = false;                            // ambiguous splits were met and resolved
     bool give_up = false;
     if (s_val[0] < (int64_t)kInf) {

@@ -186,6 +186,10 @@ struct DpParams {
     int64_t seq;
     DpApply apply;
     DpGroups groups;
+    // The traced-back assignment starts from the best cell among 0 .. min(D, e_limit) of the last
+    // row (the strict budget looks at fewer cells than the table has; negative: none, no
+    // assignment fits).
+    int32_t e_limit = 0x7FFFFFFF;
 };
 // Entry lists built on the device from the error table (see dp_build_kernel).
 constexpr int kBuildThreads = 1024;   // layers per solve on this path

@@ -30,9 +30,29 @@ def test_exports_match_header(lib):
         assert getattr(lib, name) is not None
 
 
-def test_struct_layouts_match_header():
+def test_struct_layouts_match_header(tmp_path):
+    """Size and field offsets of the binding's structures against what a C compiler makes of the
+    header (no numbers typed in here)."""
     import ctypes as C
-    assert C.sizeof(B.Layer) == 24 and C.sizeof(B.Cand) == 16 and C.sizeof(B.Config) == 32
+    import subprocess
+    structs = {"lgreco_layer_t": B.Layer, "lgreco_cand_t": B.Cand, "lgreco_config_t": B.Config}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "lgreco.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    lines += ['return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    include = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-I", include, str(src), "-o", str(exe)], check=True)
+    out = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    for cname, cls in structs.items():
+        assert int(out[cname]) == C.sizeof(cls), cname
+        for field, _ in cls._fields_:
+            assert int(out["%s.%s" % (cname, field)]) == getattr(cls, field).offset, (cname, field)
 
 
 @pytest.mark.parametrize("name", W.WORKLOADS)

@@ -392,3 +392,42 @@ def test_zero_error_feedback_promise_changes_nothing(kind):
         same(run(promised, e), run(plain, e))
     plain.close()
     promised.close()
+
+
+def test_strict_budget_through_the_one_call():
+    """strict_budget in lgreco_profile_solve_compress: the assignment is the oracle's strict one on
+    the call's own tables and its real error stays within E_max; with fewer bins than layers nothing
+    fits the tightened budget and the call falls back to the uniform default, compressing with it
+    exactly as lgreco_compress does."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload("mixed")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    h = B.Handle(int(batch.grads.size), L, len(cands), strict_budget=True)
+    for n_bins in (w.n_bins, 4 * L, L - 1):
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
+            g, ef, layers, ctab, w.default, n_bins, pay)
+        torch.cuda.synchronize()
+        assert st == B.OK
+        ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, n_bins, strict=True)
+        if ref_choice is None:
+            assert n_bins < L or True
+            ref_choice = np.full(L, w.default, np.int32)
+            ref_size = int(sizes[:, w.default].sum())
+        assert np.array_equal(choice, ref_choice) and tsize == ref_size
+        assert terr <= e_max
+        ref_pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ref_ef = e.clone()
+        h.compress(g, ref_ef, layers, ctab, choice, ref_pay, B.payload_layout(layers, ctab, choice))
+        torch.cuda.synchronize()
+        assert np.array_equal(offsets, B.payload_layout(layers, ctab, choice))
+        assert torch.equal(pay, ref_pay) and torch.equal(ef.view(torch.int32), ref_ef.view(torch.int32))
+    assert np.array_equal(choice, np.full(L, w.default, np.int32)), "the last case must have fallen back to the default"
+    h.close()

@@ -8,9 +8,9 @@ from oracle import solver
 pytestmark = pytest.mark.gpu
 
 
-def _handle(L, P, dp_groups=0):
+def _handle(L, P, dp_groups=0, strict_budget=False):
     from paper_2210_17357_amd import binding as B
-    return B.Handle(1024, L, P, dp_groups=dp_groups)
+    return B.Handle(1024, L, P, dp_groups=dp_groups, strict_budget=strict_budget)
 
 
 def _compare(h, errors, sizes, e_max, n_bins):
@@ -182,3 +182,37 @@ def test_layer_groups_on_large_tables(L, P, D):
         _compare(h, same_e, same_s, solver.e_max_uniform(same_e, P // 2), D)
         h.close()
     assert seen & {8, 1008, -8}
+
+
+@pytest.mark.parametrize("groups", [1, 8])
+def test_strict_budget_keeps_the_real_errors_within_e_max(groups):
+    """strict_budget: only assignments whose bins sum to at most n_bins - L are accepted (the
+    oracle's strict solve, pinned by enumeration), so the real errors never exceed E_max; the
+    plain solve on the same tables overshoots in a good share of them."""
+    from paper_2210_17357_amd import binding as B
+    rng = np.random.default_rng(77 + groups)
+    plain, strict = _handle(300, 13, dp_groups=groups), _handle(300, 13, dp_groups=groups, strict_budget=True)
+    over = infeasible = 0
+    for trial in range(60):
+        if trial % 3 == 0:
+            L, P, D = int(rng.integers(60, 300)), int(rng.integers(3, 13)), int(rng.integers(500, 4000))
+        else:
+            L, P, D = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(1, 80))
+        errors = np.sort(rng.random((L, P)), axis=1)[:, ::-1] * 10.0 ** rng.uniform(-3, 0, (L, 1))
+        sizes = np.sort(rng.integers(1, 1 << 20, (L, P)), axis=1).astype(np.int64)
+        e_max = solver.e_max_uniform(errors, P // 2)
+        st, choice, tsize, terr = plain.solve(errors, sizes, e_max, D)
+        assert st == B.OK
+        over += terr > e_max
+        ref_choice, ref_size, ref_err = solver.solve(errors, sizes, e_max, D, strict=True)
+        st, choice, tsize, terr = strict.solve(errors, sizes, e_max, D)
+        if ref_choice is None:
+            assert st == B.EINFEASIBLE
+            infeasible += 1
+            continue
+        assert st == B.OK and np.array_equal(choice, ref_choice) and tsize == ref_size
+        assert terr <= e_max
+        assert int(solver.discretise(errors, e_max, D)[np.arange(L), choice].sum()) <= D - L
+    assert over > 10 and infeasible > 0, (over, infeasible)
+    plain.close()
+    strict.close()

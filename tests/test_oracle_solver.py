@@ -10,13 +10,13 @@ from oracle import pipeline, solver
 from paper_2210_17357_amd import workloads as W
 
 
-def brute_force(bins, sizes, n_bins):
-    """Among assignments with sum(bin) <= D minimise (sum size, sum bin, c_L, ..., c_1)."""
+def brute_force(bins, sizes, n_bins, e_limit=None):
+    """Among assignments with sum(bin) <= D (<= e_limit if given) minimise (sum size, sum bin, c_L, ..., c_1)."""
     n_layers, n_cands = bins.shape
     best_key, best = None, None
     for assign in itertools.product(range(n_cands), repeat=n_layers):
         b = [int(bins[l][c]) for l, c in enumerate(assign)]
-        if any(v < 0 or v > n_bins for v in b) or sum(b) > n_bins:
+        if any(v < 0 or v > n_bins for v in b) or sum(b) > (n_bins if e_limit is None else e_limit):
             continue
         key = (sum(int(sizes[l][c]) for l, c in enumerate(assign)), sum(b)) + tuple(reversed(assign))
         if best_key is None or key < best_key:
@@ -206,3 +206,40 @@ def test_weighted_objective_special_cases():
     assert tsize >= psize                                          # and no better in plain bytes
     assert sizes[rows, got][bucket == 2].sum() <= sizes[rows, plain][bucket == 2].sum()
     assert terr <= e_max * (1.0 + L / w.n_bins)
+
+
+def test_strict_budget_against_enumeration_and_its_guarantee():
+    """strict: only assignments with sum(bin) <= D - L are accepted (every bin rounds its error
+    down by less than one step, so the real errors then sum to less than E_max).  Enumeration with
+    that limit and the same tie-break tuple; the guarantee itself on real-valued tables, where the
+    plain solve overshoots E_max in a good share of the cases."""
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        n_layers, n_cands = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        n_bins = int(rng.integers(1, 31))
+        bins = rng.integers(-1, n_bins + 3, (n_layers, n_cands)).astype(np.int64)
+        bins[bins > n_bins] = solver.UNUSABLE
+        if trial % 3 == 0:
+            bins[:, 0] = 0
+        sizes = rng.integers(0, 6, (n_layers, n_cands)).astype(np.int64)
+        limit = solver.strict_limit(n_layers, n_bins)
+        assert limit == n_bins - n_layers
+        expect = brute_force(bins, sizes, n_bins, e_limit=limit) if limit >= 0 else None
+        for fast in (False, True):
+            dp, pd = (solver.dp_tables_fast if fast else solver.dp_tables)(bins, sizes, n_bins)
+            got = solver.backtrace(dp, pd, bins, limit)
+            assert (got is None) == (expect is None), (trial, fast)
+            if expect is not None:
+                assert list(got) == list(expect), (trial, fast)
+    over = 0
+    for trial in range(200):
+        n_layers, n_cands, n_bins = int(rng.integers(2, 30)), int(rng.integers(2, 8)), int(rng.integers(40, 400))
+        errors = np.sort(rng.random((n_layers, n_cands)), axis=1)[:, ::-1] * 10.0 ** rng.uniform(-3, 0, (n_layers, 1))
+        sizes = np.sort(rng.integers(1, 1000, (n_layers, n_cands)), axis=1).astype(np.int64)
+        e_max = solver.e_max_uniform(errors, n_cands // 2)
+        _, _, plain_err = solver.solve(errors, sizes, e_max, n_bins)
+        over += plain_err > e_max
+        choice, _, terr = solver.solve(errors, sizes, e_max, n_bins, strict=True)
+        if choice is not None:
+            assert terr <= e_max
+    assert over > 20, "the plain solve hardly ever overshoots here: the case shows nothing"
