@@ -114,7 +114,6 @@ def cpu_baseline(w, sample_tensors, power_iters=1):
     kw = dict(bucket=w.bucket, stochastic=w.stochastic, seed=w.seed)
     if b.q0 is not None:
         kw.update(q0=b.q0, q_offsets=b.q_offsets, r_max=w.r_max, power_iters=power_iters)
-    c0 = time.process_time()          # CPU seconds of all threads of this process
     t0 = time.perf_counter()
     errors = pipeline.profile(b.grads, b.ef, b.offsets, b.numels, b.rows, b.cols, cands, **kw)
     sizes = pipeline.sizes_table(b.numels, b.rows, b.cols, cands, w.bucket)
@@ -131,7 +130,7 @@ def cpu_baseline(w, sample_tensors, power_iters=1):
                                 power_iters)
     t3 = time.perf_counter()
     return b, errors, choice, {"profile_s": t1 - t0, "solve_s": t2 - t1, "compress_s": t3 - t2,
-                               "elems": n, "total_s": t3 - t0, "cpu_s": time.process_time() - c0}
+                               "elems": n, "total_s": t3 - t0}
 
 
 def measure(wname, args, steps, warmup, with_cold, with_decompress):
@@ -425,16 +424,25 @@ def main():
             sample.append(t)
             acc += n
         sb, o_err, o_choice, tm = cpu_baseline(w, sample, args.power_iters)
+        lowrank_oracle = any(int(f) == 2 for f, _ in w.candidates)        # 2: the low-rank family
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()
+                                if i.get("user_api") == "blas"] or [1])
+        except Exception:
+            blas_threads = 1
         out["cpu_baseline"] = {
             "value": round(4.0 * tm["elems"] / tm["total_s"] / 1e9, 4), "unit": "GB/s",
-            # threads actually busy: CPU time of the process over wall time (numpy's element-wise
-            # code runs on one thread, its matrix products on the BLAS library's pool)
-            "cores": max(1, int(round(tm["cpu_s"] / tm["total_s"]))),
+            # threads the oracle's arithmetic runs on: numpy's element-wise code uses one, its matrix
+            # products (the low-rank family only) the BLAS library's pool.  (CPU time of the whole
+            # process over wall time would also count the runtimes' idle spinning threads.)
+            "cores": blas_threads if lowrank_oracle else 1,
             "kind": "oracle",
             "sample": "tensors %d..%d of %s (%d elements, largest tensor %d): oracle profile %.2fs + solve %.3fs + "
-                      "compress %.2fs; CPU time / wall time = %.2f (host has %d cores)"
+                      "compress %.2fs; numpy: element-wise code on one thread, matrix products on %d BLAS "
+                      "threads (host has %d cores)"
                       % (sample[0], sample[-1], w.name, tm["elems"], int(sb.numels.max()), tm["profile_s"],
-                         tm["solve_s"], tm["compress_s"], tm["cpu_s"] / tm["total_s"], os.cpu_count() or 0)}
+                         tm["solve_s"], tm["compress_s"], blas_threads, os.cpu_count() or 0)}
         # parity of the GPU profile on the sampled layers (gradient buffer 0 is the oracle's input)
         idx = [int(np.where(batch.tensor_index == t)[0][0]) for t in sb.tensor_index]
         if ctx["errors0"] is not None and (not w.stochastic or idx == list(range(len(idx)))):
