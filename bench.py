@@ -90,6 +90,9 @@ def parse_args():
                     help="Top-K: the main loop itself runs with reuse_thresholds = 0 (the default run reports "
                          "that case under \"cold\")")
     ap.add_argument("--no-cold", action="store_true", help="leave out the reuse_thresholds = 0 loop")
+    ap.add_argument("--keep-ef-on-failure", action="store_true",
+                    help="create the handle with keep_ef_on_failure = 1: the profile of the one call does not "
+                         "leave x in the error-feedback buffer (more memory traffic, same results)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="leave out the smaller workloads (they run only next to the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -181,7 +184,8 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     def loop(reuse, timing_level):
         """warm-up + timed steps on a handle of its own; returns (elapsed s, kernel totals, last results)."""
         h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
-                     seed=w.seed, r_max=w.r_max, power_iters=args.power_iters, reuse_thresholds=reuse)
+                     seed=w.seed, r_max=w.r_max, power_iters=args.power_iters, reuse_thresholds=reuse,
+                     keep_ef_on_failure=args.keep_ef_on_failure)
         h.set_timing(timing_level)
         h.set_timing_stride(max(1, args.time_every))
         if not has_ef:
@@ -242,20 +246,24 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     nlr = float(numels[fam == W.LOWRANK].sum())
     mean_bits = float((numels * par)[fam == W.QUANT].sum() / nq) if nq else 0.0
     chosen_bytes = last["sizes"][np.arange(L), choice].astype(np.float64)
-    # algorithmic bytes per element and elements covered per launch, per timed section: streaming
-    # reads of g (and e when there is one) = rd bytes per element in the profile; compress reads g
-    # and e and writes e
-    rd = 8.0 if has_ef else 4.0
+    # algorithmic bytes per element and elements covered per launch, per timed section.  The
+    # profile reads g (and e when there is one); the compression reads g and e and writes e.  In
+    # the one call over quantization / Top-K candidates the profile also WRITES x = g + e into the
+    # error-feedback buffer (12 bytes per element) and the compression reads x there: 4 bytes per
+    # element for a Top-K layer (what is not kept stays as it is), 8 for a quantized one.
+    lowrank = any(f == W.LOWRANK for f, _ in cands)
+    in_place = calls == "one" and has_ef and not lowrank and not args.keep_ef_on_failure
+    rd = (12.0 if in_place else 8.0) if has_ef else 4.0
+    cq, ct = (8.0, 4.0) if in_place else (12.0, 12.0)
     algo, elems = {}, {}
     for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
         algo["profile/" + k], elems["profile/" + k] = rd, float(N)
-    algo["compress/quant_compress"] = 12.0 + mean_bits / 8.0 + 8.0 / 128.0
+    algo["compress/quant_compress"] = cq + mean_bits / 8.0 + 8.0 / 128.0
     elems["compress/quant_compress"] = nq
-    algo["compress/topk_collect"], elems["compress/topk_collect"] = 12.0, ntk
+    algo["compress/topk_collect"], elems["compress/topk_collect"] = ct, ntk
     algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = 12.0, nlr
     # dense contractions of the low-rank path: flops per launch
     flops = {}
-    lowrank = any(f == W.LOWRANK for f, _ in cands)
     mn2d = float(sum(int(r) * int(c) for r, c in zip(batch.rows, batch.cols)))
     if lowrank:
         for k in ("lowrank_gemm_p", "lowrank_gemm_q"):
@@ -300,7 +308,8 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
         if name in kern and kern[name][1] > 0:
             phase_ms[key] = kern[name][0] / kern[name][1]
     profile_bytes = rd * N * (2.0 * args.power_iters if lowrank else 1.0)
-    compress_bytes = (float(((12.0 * numels + chosen_bytes)[fam != W.LOWRANK]).sum())
+    compress_bytes = (float(((cq * numels + chosen_bytes)[fam == W.QUANT]).sum())
+                      + float(((ct * numels + chosen_bytes)[fam == W.TOPK]).sum())
                       + float(((12.0 + 8.0 * args.power_iters) * numels + chosen_bytes)[fam == W.LOWRANK].sum()))
     roofline_phase = {}
     for key, nbytes in (("profile", profile_bytes), ("compress", compress_bytes)):
@@ -326,7 +335,8 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
         "config": {"workload": w.name, "elements": N, "layers": L, "candidates": len(cands),
                    "n_bins": w.n_bins, "stochastic": bool(w.stochastic), "power_iters": args.power_iters,
                    "reuse_thresholds": not args.sample_every_call, "grad_buffers": n_buf,
-                   "calls_per_step": calls, "steps": steps, "warmup": warmup,
+                   "calls_per_step": calls, "x_in_ef_buffer": bool(in_place),
+                   "steps": steps, "warmup": warmup,
                    "kernels_timed_every_n_steps": None if args.no_kernel_timing else max(1, args.time_every),
                    "host_generation_s": round(t_gen, 2)},
         "roofline": roofline,

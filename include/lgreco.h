@@ -103,6 +103,13 @@ typedef struct {
                             * L steps (see lgreco_solve); 1 = only assignments whose bins sum to at
                             * most n_bins - L are accepted, which keeps the sum of the real errors
                             * below e_max (section "The Constrained Optimization Problem") */
+    int32_t  keep_ef_on_failure; /* lgreco_profile_solve_compress with quantization / Top-K candidates
+                            * only: 0 = the profile leaves x = fl32(g + e) in d_ef as it forms it and
+                            * the compression reads x there (less memory traffic: g is read once,
+                            * and the Top-K layers need no pass that rewrites what is not kept); a
+                            * call that fails after its profile ran then leaves d_ef = x.  1 = d_ef
+                            * is written by the compression only and is untouched when the call
+                            * fails.  Results of a successful call are the same either way. */
 } lgreco_config_t;
 
 /* Create a handle for problems of at most max_elems gradient elements (sum of numel),
@@ -272,7 +279,11 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
  *             compressed
  *   offsets   host out [L+1], the layout used
  * Host outputs of the profile and the solve are valid on return; the compression kernels are
- * queued as with lgreco_compress.  LGRECO_EINFEASIBLE: as lgreco_solve, nothing compressed. */
+ * queued as with lgreco_compress.  LGRECO_EINFEASIBLE: as lgreco_solve, nothing compressed.
+ * Whenever nothing is compressed (a failed solve, a payload buffer too small, a table that is not
+ * finite) d_ef holds either what it held before or, with keep_ef_on_failure = 0 and no low-rank
+ * candidate, x = fl32(g + e): the gradient an uncompressed step would send, with the error
+ * feedback already added. */
 int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                                   const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
                                   int32_t P, float* d_q, int32_t default_cand, int32_t n_bins,

@@ -37,7 +37,8 @@ class Cand(C.Structure):
 class Config(C.Structure):
     _fields_ = [("bucket", C.c_int32), ("stochastic", C.c_int32), ("seed", C.c_uint64),
                 ("power_iters", C.c_int32), ("r_max", C.c_int32), ("reuse_thresholds", C.c_int32),
-                ("dp_groups", C.c_int32), ("strict_budget", C.c_int32)]
+                ("dp_groups", C.c_int32), ("strict_budget", C.c_int32),
+                ("keep_ef_on_failure", C.c_int32)]
 
 
 class LgrecoError(RuntimeError):
@@ -190,10 +191,11 @@ class Handle:
 
     def __init__(self, max_elems: int, max_layers: int, max_cands: int, bucket: int = 128,
                  stochastic: bool = False, seed: int = 0, power_iters: int = 1, r_max: int = 64,
-                 reuse_thresholds: bool = False, dp_groups: int = 0, strict_budget: bool = False):
+                 reuse_thresholds: bool = False, dp_groups: int = 0, strict_budget: bool = False,
+                 keep_ef_on_failure: bool = False):
         self._h = C.c_void_p()
         self.cfg = Config(bucket, int(stochastic), seed, power_iters, r_max, int(bool(reuse_thresholds)),
-                          int(dp_groups), int(bool(strict_budget)))
+                          int(dp_groups), int(bool(strict_budget)), int(bool(keep_ef_on_failure)))
         st = lib().lgreco_create(C.byref(self._h), C.byref(self.cfg), max_elems, max_layers, max_cands)
         if st != OK:
             raise LgrecoError(st, strerror(st))

@@ -125,6 +125,9 @@ struct EarlyCompress {
     bool topk_known = false; // the Top-K layers' kernels were queued too (see topk_compress_known)
     bool lowrank_known = false;   // ... and the low-rank layers' (see lowrank_compress_known)
     float* d_q = nullptr;    // warm start, updated by the low-rank compression
+    // the profile leaves x = fl32(g + e) in the error-feedback buffer and the compression reads it
+    // there (no second read of g, and no pass over the Top-K layers that rewrites what is not kept)
+    bool x_in_e = false;
     bool launched = false;   // the quantization kernel was queued right behind the solver kernel
     bool applied = false;    // ... and ran on layer records the solver kernel wrote from its result
 };
@@ -430,6 +433,7 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
     if (cfg->power_iters < 1 || cfg->power_iters > 16) return LGRECO_EUNSUPPORTED;
     if (cfg->r_max < 0 || cfg->r_max > 64) return LGRECO_EUNSUPPORTED;
     if (cfg->strict_budget != 0 && cfg->strict_budget != 1) return LGRECO_EINVAL;
+    if (cfg->keep_ef_on_failure != 0 && cfg->keep_ef_on_failure != 1) return LGRECO_EINVAL;
     if (cfg->dp_groups != 0 && cfg->dp_groups != 1 && cfg->dp_groups != 2 && cfg->dp_groups != 4 &&
         cfg->dp_groups != 8)
         return LGRECO_EINVAL;
@@ -667,9 +671,11 @@ int lgreco_emax(const double* errors, int32_t L, int32_t P, int32_t default_cand
 
 // Queues every kernel of the profile on s; they write the error table to d_err (device memory, or
 // the pinned host table as the kernels address it).
+// x_out (quantization / Top-K candidates only): not null = the main pass writes x = fl32(g + e) there as it
+// forms it (the error-feedback buffer itself in the one-call path) and everything after it reads x from there
 static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float* d_ef, const lgreco_layer_t* layers,
                            int32_t L, const lgreco_cand_t* cands, int32_t P, const float* d_q0, int64_t* sizes,
-                           double* d_err, hipStream_t s) {
+                           double* d_err, hipStream_t s, float* x_out = nullptr) {
     if (!h || !d_grads || !layers || !cands || L <= 0 || P <= 0) return LGRECO_EINVAL;
     if (P > h->max_cands) return LGRECO_ENOSPACE;
     begin_call(h, s, LGRECO_CALL_PROFILE);
@@ -703,6 +709,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
         }
     }
     h->last_nlr = nlr;
+    if (nlr && x_out) return LGRECO_EINVAL;          // the low-rank kernels read g and e themselves
     if (nlr) {
         if (!d_q0) return LGRECO_EINVAL;
         for (int l = 0; l < L; ++l)
@@ -746,6 +753,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
     if (qp.nq) {
         qp.g = d_grads;
         qp.e = d_ef;
+        qp.x_out = x_out;
         qp.layers = h->d_layers;
         qp.tiles = h->d_tiles;
         qp.partials = h->d_partials;
@@ -765,12 +773,15 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s, &sec));
     } else if (ntk) {
         Section sec(h->tm, "topk_collect", true);
-        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s, &sec));
+        HIPCHK(topk_collect(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, n_tiles, s, &sec, x_out));
     }
+    // behind the main pass x is read from where it was left
+    const float* const g_after = x_out ? x_out : d_grads;
+    const float* const e_after = x_out ? nullptr : d_ef;
     if (ntk) {
         // (the per-layer sums of the quantization errors ride on the scan's launch)
         const QuantReduce qr{h->d_partials, d_err, P, qp.col, qp.nq};
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
+        HIPCHK(topk_select(&h->topk, g_after, e_after, nullptr, h->d_layers, h->d_tiles, L, n_tiles, ntk, true,
                            ntk_all <= (int)kMaxTopk, h->tm, s, qp.nq ? &qr : nullptr));
     } else if (qp.nq) {
         Section sec(h->tm, "reduce_partials");
@@ -780,7 +791,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
     for (int first = kMaxTopk; first < ntk_all; first += kMaxTopk) {
         const int cnt = load_group(first);
         HIPCHK(topk_regroup(&h->topk, L, ks.data(), 0, s));
-        HIPCHK(topk_select(&h->topk, d_grads, d_ef, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
+        HIPCHK(topk_select(&h->topk, g_after, e_after, nullptr, h->d_layers, h->d_tiles, L, n_tiles, cnt, false,
                            first + (int)kMaxTopk >= ntk_all, h->tm, s, nullptr));
         HIPCHK(topk_finalize(&h->topk, h->d_layers, h->d_tiles, L, cnt, tk_col, d_err, P, h->tm, s));
     }
@@ -959,7 +970,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
     // the device-side build reads the error table from device memory and passes it on to the host
     const bool on_device = L <= kBuildThreads && P <= kBuildMaxP && L * P <= kBuildMaxLP;
     int st = profile_enqueue(h, d_grads, d_ef, layers, L, cands, P, d_q0, sizes,
-                             on_device ? h->d_errors_dev : h->d_errors, s);
+                             on_device ? h->d_errors_dev : h->d_errors, s, (ec && ec->x_in_e) ? ec->d_ef : nullptr);
     if (st != LGRECO_OK) return st;
     // The device-side build takes 32-bit costs only; anything it does not take goes the three
     // calls' route (same results, one more host round trip).
@@ -1042,15 +1053,16 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         for (int c = 0; c < P; ++c) any_quant = any_quant || cands[c].family == LGRECO_QUANT;
         if (any_quant) {
             Section sec(h->tm, "quant_compress", true);
-            HIPCHK(launch_quant_compress(d_grads, ec->d_ef, h->d_layers, h->d_tiles, (int)h->ht.size(), ec->d_payload,
-                                         h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
+            HIPCHK(launch_quant_compress(ec->x_in_e ? nullptr : d_grads, ec->d_ef, h->d_layers, h->d_tiles,
+                                         (int)h->ht.size(), ec->d_payload, h->cfg.stochastic != 0, h->cfg.seed, s,
+                                         &sec));
         }
         ec->launched = true;
         if (ec->topk_known) {
             // ... and the Top-K layers' part, from the selection records the profile left for
             // this very data: the chosen density's record is picked on the device
             HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
-                                       ec->d_payload, h->tm, s));
+                                       ec->d_payload, h->tm, s, ec->x_in_e));
         }
         ec->lowrank_known = h->last_nlr > 0 && ec->d_q != nullptr;
         if (ec->lowrank_known) {
@@ -1204,14 +1216,17 @@ static int compress_impl(lgreco_handle_t* h, const float* d_grads, float* d_ef, 
     if (st != LGRECO_OK) return st;
     const int n_tiles = (int)h->ht.size();
     const int phase = early ? ec->phase : h->tm->open_phase("phase_compress");
+    // behind a profile of the same call that left x in the error-feedback buffer, x is read from there
+    const bool x_in_e = ec && ec->x_in_e;                 // whether or not the early kernels were queued
+    if (x_in_e && any[LGRECO_LOWRANK]) return LGRECO_EINVAL;      // never set together (see the one-call entry point)
     if (any[LGRECO_QUANT] && !quant_done) {
         Section sec(h->tm, "quant_compress", true);
-        HIPCHK(launch_quant_compress(d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
+        HIPCHK(launch_quant_compress(x_in_e ? nullptr : d_grads, d_ef, h->d_layers, h->d_tiles, n_tiles, d_payload,
                                      h->cfg.stochastic != 0, h->cfg.seed, s, &sec));
     }
     if (any[LGRECO_TOPK] && !(quant_done && ec->topk_known)) {
-        HIPCHK(topk_compress(&h->topk, d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L, n_tiles,
-                             h->tile_elems, d_payload, h->tm, s));
+        HIPCHK(topk_compress(&h->topk, x_in_e ? d_ef : d_grads, d_ef, h->d_layers, h->hl.data(), h->d_tiles, L,
+                             n_tiles, h->tile_elems, d_payload, h->tm, s, x_in_e));
     }
     if (any[LGRECO_LOWRANK] && !(quant_done && ec->lowrank_known)) {
         HIPCHK(lowrank_compress(&h->lowrank, d_grads, d_ef, h->d_layers, h->hl.data(), L, d_q, h->cfg.r_max,
@@ -1240,6 +1255,13 @@ int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, floa
     ec.d_q = d_q;
     // a buffer the caller promises to be all zeros is not read by the profile: x = fl32(g + 0) = g
     const float* const d_ef_profile = h->ef_zero_on_entry ? nullptr : d_ef;
+    // x in place: unless the configuration asks for an untouched buffer on failure, the profile
+    // leaves x in d_ef and the compression reads it there (quantization and Top-K candidates only:
+    // the low-rank kernels read g and e themselves)
+    if (cands && P > 0 && !h->cfg.keep_ef_on_failure && d_ef_profile) {
+        ec.x_in_e = true;
+        for (int c = 0; c < P; ++c) ec.x_in_e = ec.x_in_e && cands[c].family != LGRECO_LOWRANK;
+    }
     int st = profile_solve_impl(h, d_grads, d_ef_profile, layers, L, cands, P, d_q, default_cand, n_bins, errors, sizes,
                                 e_max, choice, total_size, total_error, stream, &ec);
     if (st != LGRECO_OK) return st;

@@ -214,6 +214,9 @@ struct QuantParams {
     const int64_t* cand_base;  // [L] first candidate slot of every layer
     void* tinfo;               // [n_tiles] TopkTileInfo
     double* base_part;         // [n_tiles] energy of the elements below lo
+    // not null: x = fl32(g + e) is written here as it is formed, same layout as g (may be the
+    // error-feedback buffer itself: every element is read once, by the lane that then writes it)
+    float* x_out;
 };
 
 }  // namespace lgreco

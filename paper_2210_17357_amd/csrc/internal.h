@@ -275,7 +275,7 @@ hipError_t topk_regroup(TopkScratch* t, int L, const uint32_t* ks, int slot, hip
 // main pass (exact coarse histogram + candidate collection) when no quantization candidate shares
 // the read; otherwise the quantization profile kernel does the same work
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec);
+                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec, float* x_out = nullptr);
 // exact threshold bins from the histogram; layers whose predicted bound was too high are
 // collected again with the exact one
 // quant (may be null): the quantization profile's per-tile partial sums, reduced per layer by extra
@@ -295,13 +295,14 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
                          const int* col, double* d_errors, int stride, Timing* tm, hipStream_t s);
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
-                         uint8_t* payload, Timing* tm, hipStream_t s);
+                         uint8_t* payload, Timing* tm, hipStream_t s, bool x_in_e = false);
 
 // Top-K layers of a compression queued right behind a profile of the same data and the solver
 // kernel that wrote the layer records (family, k, payload offset, slot of the chosen density in
 // the profile's selection records): nothing here needs the host to know the assignment.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
-                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s);
+                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
+                               bool x_in_e = false);
 
 // ---- lowrank.hip
 struct LowrankScratch {

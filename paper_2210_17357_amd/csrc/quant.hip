@@ -49,7 +49,8 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
     const Tile t = p.tiles[blockIdx.x];
     const DevLayer L = p.layers[t.layer];
     const float* __restrict__ g = p.g + L.offset + t.pos;
-    const float* __restrict__ e = HAS_EF ? p.e + L.offset + t.pos : nullptr;
+    const float* e = HAS_EF ? p.e + L.offset + t.pos : nullptr;           // may be what xo points to
+    float* const xo = p.x_out ? p.x_out + L.offset + t.pos : nullptr;
     // the wavefront's number through a scalar register: its share of the tile, the loop over it and
     // the candidate slice's address are then uniform values
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -89,6 +90,10 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
             if (HAS_EF) {
                 a.x += ea.x; a.y += ea.y; a.z += ea.z; a.w += ea.w;
                 b.x += eb.x; b.y += eb.y; b.z += eb.z; b.w += eb.w;
+            }
+            if (xo) {                                   // uniform
+                store_stream(reinterpret_cast<float4*>(xo + base), a);
+                store_stream(reinterpret_cast<float4*>(xo + base + 64), b);
             }
             float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             if (HIST) {
@@ -188,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                 ok[k] = idx < t.count;
                 x[k] = 0.0f;
                 if (ok[k]) x[k] = HAS_EF ? g[idx] + e[idx] : g[idx];
+                if (ok[k] && xo) xo[idx] = x[k];
                 if (HIST) {
                     if (ok[k]) atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
                     col.take(x[k], ok[k]);
@@ -287,7 +293,9 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
     if (L.family != LGRECO_QUANT) return;
     const int bits = L.iparam;
     const float lv = (float)((1 << bits) - 1);
-    const float* __restrict__ g = p.g + L.offset + t.pos;
+    // g null: the buffer e already holds x = fl32(g + e) (the profile of the same call left it there)
+    const bool x_in_e = p.g == nullptr;
+    const float* __restrict__ g = x_in_e ? nullptr : p.g + L.offset + t.pos;
     float* __restrict__ e = p.e + L.offset + t.pos;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t nb_layer = (L.numel + kBucket - 1) / kBucket;
@@ -303,12 +311,14 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
         wave_range(t.count / kChunk, wave, &c_begin, &c_end);
         for (int c = c_begin; c < c_end; ++c) {
             const int base = c * kChunk + row * kBucket + j * 4;
-            float4 a = load_stream(reinterpret_cast<const float4*>(g + base));
-            float4 b = load_stream(reinterpret_cast<const float4*>(g + base + 64));
-            const float4 ea = load_stream(reinterpret_cast<const float4*>(e + base));
-            const float4 eb = load_stream(reinterpret_cast<const float4*>(e + base + 64));
-            a.x += ea.x; a.y += ea.y; a.z += ea.z; a.w += ea.w;
-            b.x += eb.x; b.y += eb.y; b.z += eb.z; b.w += eb.w;
+            float4 a = load_stream(reinterpret_cast<const float4*>(e + base));
+            float4 b = load_stream(reinterpret_cast<const float4*>(e + base + 64));
+            if (!x_in_e) {                              // uniform
+                const float4 ga = load_stream(reinterpret_cast<const float4*>(g + base));
+                const float4 gb = load_stream(reinterpret_cast<const float4*>(g + base + 64));
+                a.x = ga.x + a.x; a.y = ga.y + a.y; a.z = ga.z + a.z; a.w = ga.w + a.w;
+                b.x = gb.x + b.x; b.y = gb.y + b.y; b.z = gb.z + b.z; b.w = gb.w + b.w;
+            }
             float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             float mn = fminf(fminf(fminf(x[0], x[1]), fminf(x[2], x[3])),
                              fminf(fminf(x[4], x[5]), fminf(x[6], x[7])));
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void quant_compress_kernel(QuantCompressP
             for (int k = 0; k < 2; ++k) {
                 const int idx = bk * kBucket + lane + 64 * k;
                 ok[k] = lane + 64 * k < cnt;
-                x[k] = ok[k] ? g[idx] + e[idx] : 0.0f;
+                x[k] = ok[k] ? (x_in_e ? e[idx] : g[idx] + e[idx]) : 0.0f;
             }
             const float inf = __builtin_huge_valf();
             const float mn = wave_min(fminf(ok[0] ? x[0] : inf, ok[1] ? x[1] : inf));

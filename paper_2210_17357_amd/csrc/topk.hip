@@ -281,6 +281,12 @@ struct CollectParams {
     double* base_part;
     int32_t only_flagged;
     uint32_t* cnt_b;            // KNOWN: [L x kBinsB] last 9 pattern bits inside each layer's boundary sub-bin
+    // profile (no EMIT): not null = x is written here as it is formed (may be the buffer e points to:
+    // every element is read once, by the lane that then writes it)
+    float* x_out;
+    // KNOWN: the buffer behind g already holds x (e is null) and stays as it is: nothing is written
+    // to the error feedback in this pass, the emit kernel zeroes the kept entries
+    int32_t x_in_e;
 };
 
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
@@ -308,6 +314,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
     const float* gp = p.g + L.offset + t.pos;
     const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
     float* const eo = EMIT ? p.ef_out + L.offset + t.pos : nullptr;
+    float* const xo = (!EMIT && p.x_out) ? p.x_out + L.offset + t.pos : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (HIST || KNOWN) {
         for (int b = tid; b < (KNOWN ? kBinsB : kHistBins); b += kThreads) s_hist[b] = 0;
@@ -338,7 +345,10 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (EMIT && KNOWN) {
+                if (!EMIT && xo) store_stream(reinterpret_cast<float4*>(xo) + v + 64 * h, a[h]);
+                if (EMIT && KNOWN && p.x_in_e) {
+                    // the buffer holds x already: nothing to write here
+                } else if (EMIT && KNOWN) {
                     // nearly every candidate is kept here: candidates are written as zero at once, the
                     // emit step puts the few that are not kept back
                     float4 w = a[h];
@@ -377,7 +387,8 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             const bool valid = i < t.count;
             float x = 0.0f;
             if (valid) x = ep ? gp[i] + ep[i] : gp[i];
-            if (EMIT && valid) eo[i] = (KNOWN && mag_bits(x) >= bound) ? 0.0f : x;
+            if (EMIT && valid && !(KNOWN && p.x_in_e)) eo[i] = (KNOWN && mag_bits(x) >= bound) ? 0.0f : x;
+            if (!EMIT && valid && xo) xo[i] = x;
             if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
             if (KNOWN && valid && mag_bits(x) - bound < (uint32_t)kBinsB) atomicAdd(&s_hist[mag_bits(x) - bound], 1u);
             col.take(x, valid, (uint32_t)(t.pos + i));
@@ -1135,7 +1146,9 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
                                                               const uint32_t* __restrict__ cand_idx,
                                                               const uint2* __restrict__ wavecnt,
                                                               const uint2* __restrict__ wavebase,
-                                                              uint8_t* __restrict__ payload) {
+                                                              uint8_t* __restrict__ payload, int x_in_e) {
+    // x_in_e (KNOWN only): the main pass left the buffer as it was (x everywhere), so the kept
+    // entries are zeroed here, as without KNOWN, and nothing is put back
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int first = blockIdx.x * kSliceBatch;
     struct Slice {
@@ -1216,8 +1229,8 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
                 const uint32_t pos = S[q].out + lanes_below(kq, 0u);
                 S[q].values[pos] = __uint_as_float(pat[q] | (ix[q] & 0x80000000u));
                 S[q].indices[pos] = ix[q] & 0x7FFFFFFFu;
-                if (!KNOWN) S[q].ef[ix[q] & 0x7FFFFFFFu] = 0.0f;
-            } else if (KNOWN && ok) {
+                if (!KNOWN || x_in_e) S[q].ef[ix[q] & 0x7FFFFFFFu] = 0.0f;
+            } else if (KNOWN && !x_in_e && ok) {
                 // the main pass wrote zero for every candidate: the ones that are not kept get x back
                 S[q].ef[ix[q] & 0x7FFFFFFFu] = __uint_as_float(pat[q] | (ix[q] & 0x80000000u));
             }
@@ -1448,10 +1461,11 @@ static CollectParams collect_params(TopkScratch* t, const float* g, const float*
 // main pass without quantization candidates: histogram + collection in one read.  ef_out != null
 // (compress): also records index and sign of every candidate and writes x to the error feedback.
 hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* ef_out, const DevLayer* d_layers,
-                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec) {
+                        const Tile* d_tiles, int n_tiles, hipStream_t s, Section* sec, float* x_out) {
     if (n_tiles <= 0) return hipSuccess;
     CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
     p.ef_out = ef_out;
+    p.x_out = ef_out ? nullptr : x_out;        // profile only: x is left where the compression will look for it
     if (ef_out)
         launch_timed(sec, true, true, topk_collect_kernel<true, true>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     else
@@ -1564,18 +1578,20 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     return hipGetLastError();
 }
 
+// x_in_e: g is the error-feedback buffer itself, which already holds x = fl32(g + e) (nothing is added)
 hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                          const DevLayer* h_layers, const Tile* d_tiles, int L, int n_tiles, int tile_elems,
-                         uint8_t* payload, Timing* tm, hipStream_t s) {
+                         uint8_t* payload, Timing* tm, hipStream_t s, bool x_in_e) {
     std::vector<uint32_t> ks((size_t)L * kMaxTopk, 0u);
     for (int l = 0; l < L; ++l)
         if (h_layers[l].family == LGRECO_TOPK) ks[(size_t)l * kMaxTopk] = (uint32_t)h_layers[l].iparam;
-    TK_CHECK(topk_begin(t, g, e, d_layers, h_layers, d_tiles, L, n_tiles, tile_elems, ks.data(), 1, 1, tm, s));
+    const float* const e_in = x_in_e ? nullptr : e;
+    TK_CHECK(topk_begin(t, g, e_in, d_layers, h_layers, d_tiles, L, n_tiles, tile_elems, ks.data(), 1, 1, tm, s));
     {
         Section sec(tm, "topk_collect", true);
-        TK_CHECK(topk_collect(t, g, e, e, d_layers, d_tiles, n_tiles, s, &sec));
+        TK_CHECK(topk_collect(t, g, e_in, e, d_layers, d_tiles, n_tiles, s, &sec));
     }
-    TK_CHECK(topk_select(t, g, e, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s, nullptr));
+    TK_CHECK(topk_select(t, g, e_in, e, d_layers, d_tiles, L, n_tiles, 1, true, true, tm, s, nullptr));
     TK_CHECK(topk_finalize(t, d_layers, d_tiles, L, 1, nullptr, nullptr, 0, tm, s));
     {
         Section sec(tm, "topk_count");
@@ -1596,7 +1612,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
                            d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
                            (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
                            (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
-                           (const uint2*)t->d_tilebase, payload);
+                           (const uint2*)t->d_tilebase, payload, 0);
         TK_CHECK(hipGetLastError());
     }
     return hipSuccess;
@@ -1610,13 +1626,17 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // edge, counting the sub-bin's entries by their last 9 bits; then the exact threshold, the
 // per-wavefront counts, their scan and the ordered emit, as in topk_compress.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
-                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s) {
+                               const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
+                               bool x_in_e) {
     if (n_tiles <= 0) return hipSuccess;
     // the profile's control block (slot 0) holds every layer's candidate region
     uint8_t* const d = t->d_ctl[0];
     CollectParams p{};
-    p.g = g;
-    p.e = e;
+    // x_in_e: the profile left x = fl32(g + e) in the error-feedback buffer; the pass reads that
+    // alone and writes nothing back (the emit kernel zeroes the kept entries)
+    p.g = x_in_e ? e : g;
+    p.e = x_in_e ? nullptr : e;
+    p.x_in_e = x_in_e ? 1 : 0;
     p.ef_out = e;
     p.layers = d_layers;
     p.tiles = d_tiles;
@@ -1657,7 +1677,7 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
                            d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
                            (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
                            (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
-                           (const uint2*)t->d_tilebase, payload);
+                           (const uint2*)t->d_tilebase, payload, x_in_e ? 1 : 0);
         TK_CHECK(hipGetLastError());
     }
     return hipSuccess;

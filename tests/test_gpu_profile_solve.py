@@ -109,12 +109,15 @@ def test_more_candidates_than_the_device_side_step_takes():
     assert np.array_equal(one[4], three[4]) and one[5] == three[5] and one[6] == three[6]
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
-def test_whole_path_as_one_call_equals_the_separate_calls(kind):
+def test_whole_path_as_one_call_equals_the_separate_calls(kind, keep):
     """lgreco_profile_solve_compress against lgreco_profile_solve + lgreco_payload_layout +
     lgreco_compress on the same inputs (which the other tests hold against the oracle): tables,
     assignment, layout, payload bytes, error feedback and the new Q bit for bit; twice in a row on
-    one handle; a payload buffer that is too small is reported without touching the error feedback."""
+    one handle; with and without the profile leaving x in the error-feedback buffer for the
+    compression (keep_ef_on_failure); a payload buffer that is too small is reported and leaves the
+    error feedback as the configuration says: untouched, or holding x = fl32(g + e)."""
     from paper_2210_17357_amd import binding as B
     torch = torch_cuda()
     if kind == "lowrank":
@@ -135,7 +138,8 @@ def test_whole_path_as_one_call_equals_the_separate_calls(kind):
     capacity = int(sizes_tab.max(axis=1).sum()) + 16 * (L + 1)
 
     def handle():
-        return B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, r_max=w.r_max)
+        return B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, r_max=w.r_max,
+                        keep_ef_on_failure=keep)
 
     h = handle()
     st, errors, sizes, e_max, choice, tsize, terr = h.profile_solve(g, e, layers, ctab, w.default, w.n_bins, q0)
@@ -179,15 +183,17 @@ def test_whole_path_as_one_call_equals_the_separate_calls(kind):
         h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, small, q0.clone() if q0 is not None else None)
     assert err.value.status == B.ENOSPACE
     torch.cuda.synchronize()
-    assert torch.equal(ef.view(torch.int32), e.view(torch.int32)) and int(small.count_nonzero()) == 0
+    left = e if (keep or kind == "lowrank") else g + e        # low-rank candidates: x is never written in place
+    assert torch.equal(ef.view(torch.int32), left.view(torch.int32)) and int(small.count_nonzero()) == 0
     h.close()
 
 
-def test_whole_path_call_compresses_nothing_when_the_solve_fails():
+@pytest.mark.parametrize("keep", [False, True])
+def test_whole_path_call_compresses_nothing_when_the_solve_fails(keep):
     """A non-finite gradient makes the error table unusable (the solve reports invalid input or
     an infeasible budget).  The quantization kernel of the one-call form is queued before the
-    host knows: it must find no layer to work on.  Error feedback and payload stay as they were,
-    and the handle goes on working."""
+    host knows: it must find no layer to work on.  The payload stays as it was, the error feedback
+    too (keep_ef_on_failure) or holds x = fl32(g + e), and the handle goes on working."""
     from paper_2210_17357_amd import binding as B
     torch = torch_cuda()
     w = _workload("quant")
@@ -197,7 +203,7 @@ def test_whole_path_call_compresses_nothing_when_the_solve_fails():
     g, e, _ = to_device(batch)
     L = len(batch.numels)
     capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
-    h = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed)
+    h = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, keep_ef_on_failure=keep)
     good = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
     ef_good = e.clone()
     ref = h.profile_solve_compress(g, ef_good, layers, ctab, w.default, w.n_bins, good)
@@ -212,7 +218,8 @@ def test_whole_path_call_compresses_nothing_when_the_solve_fails():
         st = err.status
     assert st in (B.EINVAL, B.EINFEASIBLE)
     torch.cuda.synchronize()
-    assert torch.equal(ef.view(torch.int32), e.view(torch.int32)) and int(pay.count_nonzero()) == 0
+    left = e if keep else bad_g + e
+    assert torch.equal(ef.view(torch.int32), left.view(torch.int32)) and int(pay.count_nonzero()) == 0
     # the same handle, good data again: the layer records are uploaded anew
     pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
     ef2 = e.clone()
