@@ -2,8 +2,9 @@
 the rocprofv3 summaries under profiles/.  These tests hold the two together: the summaries parse,
 every section they name is one bench.py prices, the sections that dominate each workload are
 there, and the measured bytes of the profile passes (whose algorithmic bytes are known without a
-GPU: one read of the gradient and the error feedback, 8 bytes per element) are within the range a
-streaming pass can have."""
+GPU: one read of the gradient and the error feedback and one write of their sum into the error
+feedback buffer, 12 bytes per element in the one call the summaries are taken on) are within the
+range a streaming pass can have."""
 import os
 import re
 
@@ -57,10 +58,10 @@ def test_profile_pass_traffic_against_its_algorithmic_bytes(workload):
     n = sum(int(__import__("numpy").prod(s)) for s in w.shapes)
     traffic = bench.measured_traffic(workload)
     sec = next(s for s in DOMINANT[workload] if s.startswith("profile/"))
-    ratio = traffic[sec] / (8.0 * n)
-    # never below what must be read; a pass that re-reads more than a sixth of its input, or
+    # never below what must be read (written lines may still sit in the L2 when the dispatch ends,
+    # which shows on the small workloads); a pass that re-reads more than a sixth of its input, or
     # writes that much on the side, has a problem worth a look before the number is quoted
-    assert 0.995 <= ratio <= 1.17, (sec, ratio)
+    assert 0.995 * 8.0 * n <= traffic[sec] <= 1.17 * 12.0 * n, (sec, traffic[sec] / (12.0 * n))
 
 
 def test_every_summary_states_its_commands():
