@@ -249,12 +249,14 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     # algorithmic bytes per element and elements covered per launch, per timed section.  The
     # profile reads g (and e when there is one); the compression reads g and e and writes e.  In
     # the one call over quantization / Top-K candidates the profile also WRITES x = g + e into the
-    # error-feedback buffer (12 bytes per element) and the compression reads x there: 4 bytes per
-    # element for a Top-K layer (what is not kept stays as it is), 8 for a quantized one.
+    # error-feedback buffer (12 bytes per element) and the compression reads x there, 4 bytes per
+    # element and 4 for the new error feedback, for a quantized layer; a Top-K layer's kept entries come from the candidates the
+    # profile recorded (8 bytes per candidate written there and read here: some 13 % of the
+    # elements, data dependent and not priced on either side), so nothing per element.
     lowrank = any(f == W.LOWRANK for f, _ in cands)
     in_place = calls == "one" and has_ef and not lowrank and not args.keep_ef_on_failure
     rd = (12.0 if in_place else 8.0) if has_ef else 4.0
-    cq, ct = (8.0, 4.0) if in_place else (12.0, 12.0)
+    cq, ct = (8.0, 0.0) if in_place else (12.0, 12.0)
     algo, elems = {}, {}
     for k in ("quant_profile", "quant_profile_topk_collect", "topk_collect"):
         algo["profile/" + k], elems["profile/" + k] = rd, float(N)

@@ -27,6 +27,10 @@ struct lgreco_handle {
     std::vector<Tile> ht;
     int64_t total_elems = 0;
     bool layers_dirty = true;       // device copy of hl is stale
+    // second stream of the one-call path: the quantized layers' compression runs there beside the
+    // Top-K layers' chain of short kernels (default priority, joined before the call goes on)
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
     DevLayer* d_layers = nullptr;
     Tile* d_tiles = nullptr;
@@ -504,6 +508,9 @@ int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i) HIPCHK_C(hipEventCreate(&t.ev[i]));
         t.ready = true;
     }
+    HIPCHK_C(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
+    HIPCHK_C(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+    HIPCHK_C(hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
     {
         hipError_t e = topk_scratch_create(&h->topk, max_elems, max_layers, h->max_tiles);
         h->topk.reuse_thresholds = cfg->reuse_thresholds != 0;
@@ -539,6 +546,9 @@ int lgreco_destroy(lgreco_handle_t* h) {
     for (Timing& t : h->tms)
         for (int i = 0; i < 2 * Timing::kMaxSections; ++i)
             if (t.ev[i]) (void)hipEventDestroy(t.ev[i]);
+    if (h->side) (void)hipStreamDestroy(h->side);
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
     topk_scratch_destroy(&h->topk);
     lowrank_scratch_destroy(&h->lowrank);
     delete h;
@@ -768,6 +778,11 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
             qp.cand_base = h->topk.d_cand_base;
             qp.tinfo = h->topk.d_tinfo;
             qp.base_part = h->topk.d_base_part;
+            if (x_out) {
+                // the compression behind this profile works from the candidates: it needs to know where they are
+                qp.cand_idx = h->topk.d_cand_idx;
+                h->topk.cand_has_idx = true;
+            }
         }
         Section sec(h->tm, ntk ? "quant_profile_topk_collect" : "quant_profile", true);
         HIPCHK(launch_quant_profile(qp, n_tiles, ntk > 0, s, &sec));
@@ -1051,19 +1066,29 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         ec->phase = h->tm->open_phase("phase_compress");
         bool any_quant = false;
         for (int c = 0; c < P; ++c) any_quant = any_quant || cands[c].family == LGRECO_QUANT;
+        // With both families the quantized layers' one kernel goes to the second stream, behind
+        // the Top-K layers' main pass: the rest of their chain is a handful of short kernels that
+        // leave most of the chip idle, and the two parts write disjoint layers (error feedback
+        // and payload alike).
+        const bool beside = any_quant && ec->topk_known;
+        if (ec->topk_known) {
+            // the Top-K layers' part, from the selection records the profile left for this very
+            // data: the chosen density's record is picked on the device
+            HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
+                                       ec->d_payload, h->tm, s, ec->x_in_e, beside ? h->ev_fork : nullptr));
+        }
+        if (beside) HIPCHK(hipStreamWaitEvent(h->side, h->ev_fork, 0));
         if (any_quant) {
             Section sec(h->tm, "quant_compress", true);
             HIPCHK(launch_quant_compress(ec->x_in_e ? nullptr : d_grads, ec->d_ef, h->d_layers, h->d_tiles,
-                                         (int)h->ht.size(), ec->d_payload, h->cfg.stochastic != 0, h->cfg.seed, s,
-                                         &sec));
+                                         (int)h->ht.size(), ec->d_payload, h->cfg.stochastic != 0, h->cfg.seed,
+                                         beside ? h->side : s, &sec));
+        }
+        if (beside) {
+            HIPCHK(hipEventRecord(h->ev_join, h->side));
+            HIPCHK(hipStreamWaitEvent(s, h->ev_join, 0));
         }
         ec->launched = true;
-        if (ec->topk_known) {
-            // ... and the Top-K layers' part, from the selection records the profile left for
-            // this very data: the chosen density's record is picked on the device
-            HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
-                                       ec->d_payload, h->tm, s, ec->x_in_e));
-        }
         ec->lowrank_known = h->last_nlr > 0 && ec->d_q != nullptr;
         if (ec->lowrank_known) {
             // ... and the low-rank layers': the factors of every rank are the leading columns of

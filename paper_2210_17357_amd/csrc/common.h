@@ -211,6 +211,7 @@ struct QuantParams {
     uint32_t* hist;            // [L x kHistBins] coarse magnitude histogram, or null
     const uint32_t* lo;        // [L] lowest coarse key collected as a candidate (collection mode)
     uint32_t* cand;            // candidate buffer
+    uint32_t* cand_idx;        // not null: index within the layer and sign of every candidate, same slots
     const int64_t* cand_base;  // [L] first candidate slot of every layer
     void* tinfo;               // [n_tiles] TopkTileInfo
     double* base_part;         // [n_tiles] energy of the elements below lo

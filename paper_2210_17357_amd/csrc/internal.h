@@ -226,6 +226,11 @@ struct TopkScratch {
     uint32_t* d_cnt_known = nullptr;  // [max_layers x 512] sub-bin counts of topk_compress_known
     uint32_t* d_cand = nullptr;       // bit patterns of the candidates, tile i at its own first element
     uint32_t* d_cand_idx = nullptr;   // compress: index within the layer (+ sign bit) of every candidate
+    bool cand_has_idx = false;        // the current call's profile recorded d_cand_idx too
+    // compression from the profile's candidates: what is kept of them, in element order
+    uint32_t* d_kept = nullptr;
+    uint32_t* d_kept_idx = nullptr;
+    void* d_tinfo_kept = nullptr;
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
     uint32_t* d_lo = nullptr;         // [max_layers] lowest coarse key collected as a candidate
     uint32_t* d_hint[2] = {nullptr, nullptr};   // per kind of call: bound derived from the last thresholds
@@ -300,9 +305,10 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // Top-K layers of a compression queued right behind a profile of the same data and the solver
 // kernel that wrote the layer records (family, k, payload offset, slot of the chosen density in
 // the profile's selection records): nothing here needs the host to know the assignment.
+// after_main (may be null): recorded on s behind the pass that moves the bulk of the bytes.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                                const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
-                               bool x_in_e = false);
+                               bool x_in_e = false, hipEvent_t after_main = nullptr);
 
 // ---- lowrank.hip
 struct LowrankScratch {

@@ -41,8 +41,11 @@ __device__ __forceinline__ float quant_one(float xm, float m, float inv, float u
 
 // HIST: also build the coarse magnitude histogram of the Top-K path and collect its candidates
 // (elements whose coarse key is at or above the layer's predicted bound) in the same read.
-template <bool STOCH, bool HAS_EF, bool HIST>
+// IDX (with HIST): the candidates' indices and signs are recorded too (p.cand_idx), for a compression
+// that works from the candidates alone.
+template <bool STOCH, bool HAS_EF, bool HIST, bool IDX = false>
 __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) {
+    static_assert(HIST || !IDX, "indices are recorded with the candidates");
     __shared__ double s_part[kThreads / 64][kMaxQuant + 1];
     __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
 
@@ -65,10 +68,11 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #pragma unroll
     for (int c = 0; c < kMaxQuant; ++c) acc[c] = 0.0f;
 
-    __shared__ uint32_t s_stage[HIST ? kThreads / 64 : 1][HIST ? kStageWords : 1];
-    StagedCollector col;
+    __shared__ uint32_t s_stage[HIST ? kThreads / 64 : 1][HIST ? (IDX ? 2 : 1) * kStageWords : 1];
+    StagedCollector<IDX> col;
     uint32_t col_start = 0;
     uint32_t* const slice = HIST ? p.cand + p.cand_base[t.layer] + t.pos : nullptr;
+    uint32_t* const slice_idx = IDX ? p.cand_idx + p.cand_base[t.layer] + t.pos : nullptr;
     const uint32_t col_lo = HIST ? bound_of_key(p.lo[t.layer]) : 0xFFFFFFFFu;
 
     if (t.fast) {
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(t.count / kChunk, wave, &c_begin, &c_end);
         if (HIST) {
             col_start = (uint32_t)c_begin * kChunk;
-            col.init(slice + col_start, s_stage[wave], col_lo);
+            col.init(slice + col_start, IDX ? slice_idx + col_start : nullptr, s_stage[wave], col_lo);
         }
         // One chunk: 8 elements per lane (a: elements 4j..4j+3 of the lane's bucket, b: 64+4j..).
         auto chunk = [&](float4 a, float4 b, const float4 ea, const float4 eb, const int base)
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                     asm("" : "+v"(key));
                     atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_hist) + (key >> (kHistShift - 2))),
                               1u);
-                    col.take_keyed(x[k], key, true);
+                    col.take_keyed(x[k], key, true, (uint32_t)t.pos + (uint32_t)(base + (k < 4 ? k : 60 + k)));
                 }
             }
             float mn = fminf(min3f(min3f(min3f(x[0], x[1], x[2]), x[3], x[4]), x[5], x[6]), x[7]);
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
         wave_range(nb, wave, &b_begin, &b_end);
         if (HIST) {
             col_start = (uint32_t)b_begin * kBucket;
-            col.init(slice + col_start, s_stage[wave], col_lo);
+            col.init(slice + col_start, IDX ? slice_idx + col_start : nullptr, s_stage[wave], col_lo);
         }
         for (int bk = b_begin; bk < b_end; ++bk) {
             float x[2];
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                 if (ok[k] && xo) xo[idx] = x[k];
                 if (HIST) {
                     if (ok[k]) atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
-                    col.take(x[k], ok[k]);
+                    col.take(x[k], ok[k], (uint32_t)t.pos + (uint32_t)idx);
                 }
             }
             const float inf = __builtin_huge_valf();
@@ -441,6 +445,13 @@ hipError_t launch_quant_profile(const QuantParams& p, int n_tiles, bool hist, hi
     const bool st = p.stochastic != 0, ef = p.e != nullptr;
 #define LGRECO_LAUNCH(S, E, H) \
     launch_timed(sec, true, true, quant_profile_kernel<S, E, H>, grid, block, 0, s, p)
+    if (p.cand_idx) {
+        // recorded only by the variant the one call over both families uses
+        if (!hist || !ef) return hipErrorInvalidValue;
+        if (st) launch_timed(sec, true, true, quant_profile_kernel<true, true, true, true>, grid, block, 0, s, p);
+        else launch_timed(sec, true, true, quant_profile_kernel<false, true, true, true>, grid, block, 0, s, p);
+        return hipGetLastError();
+    }
     if (st) {
         if (ef) { if (hist) LGRECO_LAUNCH(true, true, true); else LGRECO_LAUNCH(true, true, false); }
         else    { if (hist) LGRECO_LAUNCH(true, false, true); else LGRECO_LAUNCH(true, false, false); }

@@ -287,6 +287,8 @@ struct CollectParams {
     // KNOWN: the buffer behind g already holds x (e is null) and stays as it is: nothing is written
     // to the error feedback in this pass, the emit kernel zeroes the kept entries
     int32_t x_in_e;
+    // profile (no EMIT): index and sign of every candidate are recorded as in compress
+    int32_t record_idx;
 };
 
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
@@ -322,14 +324,14 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
     }
     const int64_t slice_off = p.cand_base[t.layer] + t.pos;
     uint32_t* const slice = p.cand + slice_off;
-    uint32_t* const slice_idx = EMIT ? p.cand_idx + slice_off : nullptr;
+    uint32_t* const slice_idx = (EMIT || p.record_idx) ? p.cand_idx + slice_off : nullptr;
     Collector col;
     uint32_t start;
     if (t.fast) {
         int c0, c1;
         wave_range(t.count / kChunk, wave, &c0, &c1);
         start = (uint32_t)c0 * kChunk;
-        col.init(slice + start, EMIT ? slice_idx + start : nullptr, bound);
+        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound);
         // one 512-element chunk per iteration (uniform trip count): both halves are loaded before
         // either is used, so a lane keeps four 128-bit loads in flight
         for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += kChunk / 4) {
@@ -381,7 +383,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
         int b0, b1;
         wave_range((t.count + 63) / 64, wave, &b0, &b1);
         start = (uint32_t)b0 * 64;
-        col.init(slice + start, EMIT ? slice_idx + start : nullptr, bound);
+        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound);
         for (int b = b0; b < b1; ++b) {
             const int i = b * 64 + lane;
             const bool valid = i < t.count;
@@ -423,6 +425,143 @@ __global__ __launch_bounds__(kThreads) void topk_collect_known_kernel(CollectPar
     __shared__ uint32_t s_hist[kBinsB];
     __shared__ double s_red[kThreads / 64];
     collect_tile<false, true, true>(p, (int)blockIdx.x, s_hist, s_red);
+}
+
+// The same step from the profile's candidates instead of the data (the profile recorded index and
+// sign of every candidate and left x in the error-feedback buffer): every kept entry is among them,
+// so the data is not read again.  One workgroup per tile, a wavefront per candidate slice: the
+// candidates at or above the boundary sub-bin's lower edge are copied to the second candidate
+// buffer IN ELEMENT ORDER (the profile's main pass may store a slice in another order), and the
+// boundary sub-bin's entries are counted by their last 9 bits.  Order: every such candidate sets
+// the bit of its element in a bitmap of the wavefront's share of the tile (at most kFilterSpan
+// elements); its place in the output is the number of bits below its own.
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long m, uint32_t add);
+constexpr int kFilterSpan = kTile / (kThreads / 64);
+struct FilterParams {
+    const DevLayer* layers;
+    const Tile* tiles;
+    const TopkLayer* tl;
+    const int64_t* cand_base;
+    const TopkTileInfo* tinfo;      // what the profile's main pass wrote
+    const uint32_t* cand;
+    const uint32_t* cand_idx;
+    TopkTileInfo* tinfo_out;
+    uint32_t* cand_out;
+    uint32_t* cand_idx_out;
+    uint32_t* cnt_b;
+};
+constexpr int kFilterKeep = 512;    // kept candidates a wavefront holds in LDS between the two steps
+__global__ __launch_bounds__(kThreads) void topk_filter_known_kernel(FilterParams p) {
+    constexpr int kWords = kFilterSpan / 32;
+    static_assert(kFilterSpan <= 65536, "places inside a wavefront's share are kept in 16 bits");
+    __shared__ uint32_t s_bits[kThreads / 64][kWords];
+    __shared__ uint16_t s_before[kThreads / 64][kWords];
+    __shared__ uint2 s_keep[kThreads / 64][kFilterKeep];
+    __shared__ uint32_t s_hist[kBinsB];
+    const int tile = blockIdx.x;
+    const Tile t = p.tiles[tile];
+    const DevLayer L = p.layers[t.layer];
+    if (L.family != LGRECO_TOPK || L.slot < 0 || L.slot >= kMaxTopk) return;       // the whole workgroup
+    const TopkSel& S = p.tl[t.layer].sel[L.slot];
+    const uint32_t bound = ((S.tbin << 10) | S.bin_a) << 9;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t n = p.tinfo[tile].cnt[wave], start = p.tinfo[tile].start[wave];
+    const int64_t off = p.cand_base[t.layer] + t.pos + start;
+    const uint32_t* const pats = p.cand + off;
+    const uint32_t* const idxs = p.cand_idx + off;
+    const uint32_t first = (uint32_t)t.pos + start;          // index within the layer of the slice's first element
+    for (int b = tid; b < kBinsB; b += kThreads) s_hist[b] = 0;
+    for (int b = lane; b < kWords; b += 64) s_bits[wave][b] = 0;
+    __syncthreads();
+    // step 1: one read of the slice.  What passes sets its element's bit, is counted if it lies in
+    // the boundary sub-bin, and is put aside in LDS (the first kFilterKeep of the wavefront).
+    constexpr int kBatch = 4;                                 // pairs of loads a lane has in flight
+    uint32_t kept = 0;                                        // uniform
+    for (uint32_t i0 = 0; i0 < n; i0 += 64 * kBatch) {
+        uint32_t pat[kBatch], ix[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const uint32_t i = i0 + 64 * q + lane;
+            pat[q] = i < n ? pats[i] : 0u;
+            ix[q] = i < n ? idxs[i] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const uint32_t rel = (ix[q] & 0x7FFFFFFFu) - first;
+            const bool pass = i0 + 64 * q + lane < n && pat[q] >= bound && rel < (uint32_t)kFilterSpan;
+            const unsigned long long m = __ballot(pass);
+            if (pass) {
+                atomicOr(&s_bits[wave][rel >> 5], 1u << (rel & 31u));
+                if (pat[q] - bound < (uint32_t)kBinsB) atomicAdd(&s_hist[pat[q] - bound], 1u);
+                const uint32_t at = kept + lanes_below(m, 0u);
+                if (at < (uint32_t)kFilterKeep) s_keep[wave][at] = make_uint2(pat[q], ix[q]);
+            }
+            kept += (uint32_t)__popcll(m);
+        }
+    }
+    __syncthreads();
+    // exclusive prefix of the bitmap's population over the wavefront's words
+    {
+        constexpr int kPer = kWords / 64;
+        uint32_t c[kPer], mine = 0;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            c[j] = (uint32_t)__popc(s_bits[wave][lane * kPer + j]);
+            mine += c[j];
+        }
+        uint32_t inc = mine;
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += v;
+        }
+        uint32_t run = inc - mine;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            s_before[wave][lane * kPer + j] = (uint16_t)run;
+            run += c[j];
+        }
+    }
+    __syncthreads();
+    // step 2: every kept candidate goes to the place its element has among the kept ones
+    uint32_t* const out = p.cand_out + off;
+    uint32_t* const out_idx = p.cand_idx_out + off;
+    auto place = [&](const uint32_t pat, const uint32_t ix) __attribute__((always_inline)) {
+        const uint32_t rel = (ix & 0x7FFFFFFFu) - first;
+        const uint32_t w = rel >> 5;
+        const uint32_t at = s_before[wave][w] + (uint32_t)__popc(s_bits[wave][w] & ((1u << (rel & 31u)) - 1u));
+        out[at] = pat;
+        out_idx[at] = ix;
+    };
+    if (kept <= (uint32_t)kFilterKeep) {
+        for (uint32_t i = lane; i < kept; i += 64) {
+            const uint2 c = s_keep[wave][i];
+            place(c.x, c.y);
+        }
+    } else {                                                  // more than LDS holds: the slice is read again
+        for (uint32_t i0 = 0; i0 < n; i0 += 64 * kBatch) {
+            uint32_t pat[kBatch], ix[kBatch];
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                const uint32_t i = i0 + 64 * q + lane;
+                pat[q] = i < n ? pats[i] : 0u;
+                ix[q] = i < n ? idxs[i] : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                const uint32_t rel = (ix[q] & 0x7FFFFFFFu) - first;
+                if (i0 + 64 * q + lane < n && pat[q] >= bound && rel < (uint32_t)kFilterSpan) place(pat[q], ix[q]);
+            }
+        }
+    }
+    if (lane == 0) {
+        p.tinfo_out[tile].cnt[wave] = kept;
+        p.tinfo_out[tile].start[wave] = start;
+    }
+    uint32_t* gh = p.cnt_b + (size_t)t.layer * kBinsB;
+    for (int b = tid; b < kBinsB; b += kThreads) {
+        const uint32_t c = s_hist[b];
+        if (c) atomicAdd(&gh[b], c);
+    }
 }
 
 // One workgroup per layer: the exact threshold pattern and the number of entries equal to it that
@@ -1261,6 +1400,9 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMemset(t->d_cnt_known, 0, sizeof(uint32_t) * (size_t)max_layers * kBinsB));
     TK_CHECK(hipMalloc(&t->d_cand, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_cand_idx, sizeof(uint32_t) * (size_t)max_elems));
+    TK_CHECK(hipMalloc(&t->d_kept, sizeof(uint32_t) * (size_t)max_elems));
+    TK_CHECK(hipMalloc(&t->d_kept_idx, sizeof(uint32_t) * (size_t)max_elems));
+    TK_CHECK(hipMalloc(&t->d_tinfo_kept, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
     for (int i = 0; i < 2; ++i) TK_CHECK(hipMalloc(&t->d_hint[i], sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
@@ -1300,6 +1442,9 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_cnt_known);
     (void)hipFree(t->d_cand);
     (void)hipFree(t->d_cand_idx);
+    (void)hipFree(t->d_kept);
+    (void)hipFree(t->d_kept_idx);
+    (void)hipFree(t->d_tinfo_kept);
     (void)hipFree(t->d_lo);
     for (int i = 0; i < 2; ++i) (void)hipFree(t->d_hint[i]);
     (void)hipFree(t->d_tilecnt);
@@ -1402,6 +1547,7 @@ hipError_t topk_begin(TopkScratch* t, const float* g, const float* e, const DevL
     }
     t->n_work = nw;
     t->max_items = max_items;
+    t->cand_has_idx = false;
     bool changed = true;
     TK_CHECK(upload_ctl(t, slot, s, &changed));
     t->cur_slot = slot;
@@ -1466,6 +1612,9 @@ hipError_t topk_collect(TopkScratch* t, const float* g, const float* e, float* e
     CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
     p.ef_out = ef_out;
     p.x_out = ef_out ? nullptr : x_out;        // profile only: x is left where the compression will look for it
+    // ... and that compression works from the candidates, so it needs their indices and signs
+    p.record_idx = p.x_out ? 1 : 0;
+    t->cand_has_idx = p.record_idx != 0;
     if (ef_out)
         launch_timed(sec, true, true, topk_collect_kernel<true, true>, dim3(n_tiles), dim3(kThreads), 0, s, p);
     else
@@ -1504,6 +1653,7 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
         p.only_flagged = 1;
         p.ef_out = ef_out;
+        p.record_idx = (!ef_out && t->cand_has_idx) ? 1 : 0;
         // a second collection reads x = g + e again: in compress e already holds x, so g is not added
         const dim3 grid((n_tiles + kRecollectBatch - 1) / kRecollectBatch);
         if (ef_out) {
@@ -1627,8 +1777,11 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // per-wavefront counts, their scan and the ordered emit, as in topk_compress.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                                const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
-                               bool x_in_e) {
-    if (n_tiles <= 0) return hipSuccess;
+                               bool x_in_e, hipEvent_t after_main) {
+    if (n_tiles <= 0) {
+        if (after_main) TK_CHECK(hipEventRecord(after_main, s));
+        return hipSuccess;
+    }
     // the profile's control block (slot 0) holds every layer's candidate region
     uint8_t* const d = t->d_ctl[0];
     CollectParams p{};
@@ -1647,11 +1800,37 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
     p.tinfo = (TopkTileInfo*)t->d_tinfo;
     p.base_part = t->d_base_part;
     p.cnt_b = t->d_cnt_known;
-    {
+    const TopkTileInfo* tinfo = (const TopkTileInfo*)t->d_tinfo;
+    const uint32_t* cand = t->d_cand;
+    const uint32_t* cand_idx = t->d_cand_idx;
+    if (x_in_e) {
+        // the profile recorded where its candidates are: what is kept is taken from them
+        if (!t->cand_has_idx) return hipErrorInvalidValue;
+        FilterParams f{};
+        f.layers = d_layers;
+        f.tiles = d_tiles;
+        f.tl = p.tl;
+        f.cand_base = p.cand_base;
+        f.tinfo = tinfo;
+        f.cand = cand;
+        f.cand_idx = cand_idx;
+        f.tinfo_out = (TopkTileInfo*)t->d_tinfo_kept;
+        f.cand_out = t->d_kept;
+        f.cand_idx_out = t->d_kept_idx;
+        f.cnt_b = t->d_cnt_known;
+        Section sec(tm, "topk_filter", true);
+        launch_timed(&sec, true, true, topk_filter_known_kernel, dim3(n_tiles), dim3(kThreads), 0, s, f);
+        TK_CHECK(hipGetLastError());
+        tinfo = f.tinfo_out;
+        cand = f.cand_out;
+        cand_idx = f.cand_idx_out;
+    } else {
         Section sec(tm, "topk_collect", true);
         launch_timed(&sec, true, true, topk_collect_known_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
         TK_CHECK(hipGetLastError());
     }
+    // what follows are short kernels: work of another stream that waits for this event runs beside them
+    if (after_main) TK_CHECK(hipEventRecord(after_main, s));
     {
         Section sec(tm, "topk_pick");
         hipLaunchKernelGGL(topk_pick_known_kernel, dim3(L), dim3(256), 0, s, d_layers, (TopkLayer*)t->d_tl,
@@ -1661,8 +1840,7 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
     {
         Section sec(tm, "topk_count");
         hipLaunchKernelGGL(topk_count_kernel<true>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0,
-                           s, d_tiles, n_tiles, d_layers, (const TopkLayer*)t->d_tl, (const TopkTileInfo*)t->d_tinfo,
-                           (const uint32_t*)t->d_cand, (uint2*)t->d_tilecnt);
+                           s, d_tiles, n_tiles, d_layers, (const TopkLayer*)t->d_tl, tinfo, cand, (uint2*)t->d_tilecnt);
         TK_CHECK(hipGetLastError());
     }
     {
@@ -1674,9 +1852,8 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
     {
         Section sec(tm, "topk_emit");
         hipLaunchKernelGGL(topk_emit_kernel<true>, dim3((n_tiles + kSliceBatch - 1) / kSliceBatch), dim3(kThreads), 0, s, e,
-                           d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl,
-                           (const TopkTileInfo*)t->d_tinfo, (const uint32_t*)t->d_cand,
-                           (const uint32_t*)t->d_cand_idx, (const uint2*)t->d_tilecnt,
+                           d_layers, d_tiles, n_tiles, (const TopkLayer*)t->d_tl, tinfo, cand, cand_idx,
+                           (const uint2*)t->d_tilecnt,
                            (const uint2*)t->d_tilebase, payload, x_in_e ? 1 : 0);
         TK_CHECK(hipGetLastError());
     }

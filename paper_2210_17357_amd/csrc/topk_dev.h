@@ -90,27 +90,34 @@ struct Collector {
 // The same collection with the candidates staged in LDS: a wavefront appends to its own buffer of
 // kStageWords words and writes 128 candidates at a time, as two full 256-byte stores, instead of a
 // few scattered words per element slot.  Order and content of the slice are those of Collector.
-// (Patterns only: the variant that also records indices keeps the direct stores.)
+// IDX: index within the layer and sign of every candidate go the same way through a second buffer
+// of kStageWords words right behind the first, into dst_idx.
 constexpr int kStageFlush = 128;
 constexpr int kStageWords = kStageFlush + 64;     // below kStageFlush before an append of at most 64
+template <bool IDX>
 struct StagedCollector {
     uint32_t* dst;       // the wavefront's slice in global memory
-    uint32_t* stage;     // the wavefront's kStageWords words of LDS
+    uint32_t* dst_idx;   // IDX: the same slice of the index buffer
+    uint32_t* stage;     // the wavefront's kStageWords (IDX: 2 * kStageWords) words of LDS
     uint32_t lo_key;
     uint32_t cur;        // candidates written to global memory so far (uniform over the wavefront)
     uint32_t fill;       // candidates waiting in the buffer (uniform)
     float base;          // this lane's sum of x^2 over elements below the bound
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t* st, uint32_t bound) {
-        dst = d; stage = st; cur = 0; fill = 0; base = 0.0f;
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t* st, uint32_t bound) {
+        dst = d; dst_idx = di; stage = st; cur = 0; fill = 0; base = 0.0f;
         lo_key = bound;
     }
-    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid) {
+    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid, uint32_t idx = 0) {
         const uint32_t bits = __float_as_uint(x);
         const bool hit = valid && key >= lo_key;
         const unsigned long long m = __ballot(hit);
         const float low = (hit || !valid) ? 0.0f : x;
         base = __builtin_fmaf(low, low, base);
-        if (hit) stage[fill + Collector::below(m, 0u)] = bits & 0x7FFFFFFFu;
+        if (hit) {
+            const uint32_t at = fill + Collector::below(m, 0u);
+            stage[at] = bits & 0x7FFFFFFFu;
+            if (IDX) stage[kStageWords + at] = idx | (bits & 0x80000000u);
+        }
         fill += (uint32_t)__popcll(m);
         if (fill >= (uint32_t)kStageFlush) {          // uniform
             const uint32_t lane = threadIdx.x & 63u;
@@ -119,18 +126,28 @@ struct StagedCollector {
             const uint32_t v2 = stage[kStageFlush + lane];
             dst[cur + lane] = v0;
             dst[cur + 64 + lane] = v1;
+            if (IDX) {
+                const uint32_t i0 = stage[kStageWords + lane], i1 = stage[kStageWords + 64 + lane];
+                const uint32_t i2 = stage[kStageWords + kStageFlush + lane];
+                dst_idx[cur + lane] = i0;
+                dst_idx[cur + 64 + lane] = i1;
+                if (lane < rem) stage[kStageWords + lane] = i2;
+            }
             if (lane < rem) stage[lane] = v2;         // what is left moves to the front
             cur += kStageFlush;
             fill = rem;
         }
     }
-    __device__ __forceinline__ void take(float x, bool valid) {
-        take_keyed(x, __float_as_uint(x) & Collector::kKeyMask, valid);
+    __device__ __forceinline__ void take(float x, bool valid, uint32_t idx = 0) {
+        take_keyed(x, __float_as_uint(x) & Collector::kKeyMask, valid, idx);
     }
     // writes out what is left; afterwards cur is the wavefront's candidate count
     __device__ __forceinline__ void finish() {
         const uint32_t lane = threadIdx.x & 63u;
-        for (uint32_t i = lane; i < fill; i += 64) dst[cur + i] = stage[i];
+        for (uint32_t i = lane; i < fill; i += 64) {
+            dst[cur + i] = stage[i];
+            if (IDX) dst_idx[cur + i] = stage[kStageWords + i];
+        }
         cur += fill;
         fill = 0;
     }

@@ -342,6 +342,68 @@ def test_whole_path_call_on_degenerate_topk_layers(default, n_bins):
     h.close()
 
 
+@pytest.mark.parametrize("default,n_bins", [(3, 400), (5, 1000), (4, 60)])
+def test_whole_path_call_keeping_much_of_every_slice(default, n_bins):
+    """Quantization and Top-K candidates in one call, with densities up to 0.6 on layers of several
+    tiles: the compression takes the kept entries from the candidates the fused profile pass
+    recorded (which stores a slice in its own order), and a wavefront's share of a tile keeps more
+    entries than it holds on chip between its two steps.  Ties at the threshold (values on a grid),
+    misaligned layers, short tails.  Against the oracle's compressor layer by layer at the choice
+    the call made, and against the separate calls."""
+    from oracle import pipeline
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    rng = np.random.default_rng(77 + default)
+    numels = [70001, 8192 * 5, 33000, 1000, 8192 * 3 + 640, 50000, 129]
+    pad = [0, 0, 3, 1, 0, 2, 5]
+    offs, pos = [], 0
+    for n, p in zip(numels, pad):
+        pos += p
+        offs.append(pos)
+        pos += n
+    g = (rng.standard_t(3, pos) * 1e-3).astype(np.float32)
+    e = (rng.standard_normal(pos) * 1e-4).astype(np.float32)
+    o, n = offs[5], numels[5]
+    g[o:o + n] = np.round(rng.standard_normal(n) * 3) / 3 * 1e-3         # many equal magnitudes
+    e[o:o + n] = 0
+    for l in (0, 1, 2, 4):                                               # outliers in every bucket: quantization
+        g[offs[l]:offs[l] + numels[l]:97] *= 30                          # loses to a dense Top-K on these layers
+    batch = W.Batch(g, e, np.asarray(offs, np.int64), np.asarray(numels, np.int64),
+                    np.zeros(len(offs), np.int32), np.zeros(len(offs), np.int32),
+                    np.arange(len(offs), dtype=np.int64))
+    cands = [(W.QUANT, 2.0), (W.QUANT, 3.0), (W.TOPK, 0.05), (W.TOPK, 0.3), (W.TOPK, 0.6), (W.TOPK, 0.45)]
+    layers, ctab = tables(batch, cands)
+    gd, ed, _ = to_device(batch)
+    L = len(numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    h = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    for rep in range(2):
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = ed.clone()
+        st, errors, sizes, e_max, choice, tsize, terr, offsets = h.profile_solve_compress(
+            gd, ef, layers, ctab, default, n_bins, pay)
+        torch.cuda.synchronize()
+        assert st == B.OK
+        ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, n_bins)
+        assert np.array_equal(choice, ref_choice) and tsize == ref_size
+        pay_h, ef_h = pay.cpu().numpy(), ef.cpu().numpy()
+        for l in range(L):
+            off, n = offs[l], numels[l]
+            p_ref, e_ref, _ = pipeline.compress_layer(batch.grads, batch.ef, off, n, 0, 0, cands[choice[l]], l)
+            assert np.array_equal(pay_h[offsets[l]:offsets[l] + p_ref.size], p_ref), (rep, l, cands[choice[l]])
+            assert np.array_equal(ef_h[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (rep, l)
+    dense = [l for l in range(L) if cands[choice[l]][0] == W.TOPK and cands[choice[l]][1] >= 0.3 and numels[l] >= 30000]
+    assert dense, "no large layer was compressed at a density of 0.3 or more: the case misses its point"
+    h2 = B.Handle(int(batch.grads.size), L, len(cands))
+    pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef2 = ed.clone()
+    h2.compress(gd, ef2, layers, ctab, choice, pay2, offsets)
+    torch.cuda.synchronize()
+    assert torch.equal(pay2, pay) and torch.equal(ef2.view(torch.int32), ef.view(torch.int32))
+    h2.close()
+    h.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
 def test_zero_error_feedback_promise_changes_nothing(kind):
     """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return

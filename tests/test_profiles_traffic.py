@@ -16,9 +16,9 @@ from paper_2210_17357_amd import workloads as W
 PROFILES = os.path.join(os.path.dirname(os.path.abspath(bench.__file__)), "profiles")
 DOMINANT = {
     "c1_resnet18_quant": ("profile/quant_profile", "compress/quant_compress"),
-    "c2_resnet50_topk": ("profile/topk_collect", "compress/topk_collect"),
+    "c2_resnet50_topk": ("profile/topk_collect",),
     "c3_transformer_lm_lowrank": ("compress/lowrank_ef",),
-    "c4_gpt2_medium_mixed": ("profile/quant_profile_topk_collect", "compress/topk_collect", "compress/quant_compress"),
+    "c4_gpt2_medium_mixed": ("profile/quant_profile_topk_collect", "compress/quant_compress"),
 }
 
 
