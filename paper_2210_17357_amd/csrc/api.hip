@@ -210,10 +210,9 @@ int prepare_layers(lgreco_handle* h, const lgreco_layer_t* layers, int32_t L) {
     for (int l = 0; l < L; ++l) total += layers[l].numel;
     if (total > h->max_elems) return LGRECO_ENOSPACE;
 
-    // tile size: see kTilesFill / kTilesWanted
+    // tile size: see kTilesFill
     int tile = kTile;
     while (tile > kTileMin && total / tile < kTilesFill) tile /= 2;
-    while (tile > kTileSmooth && total / tile < kTilesWanted) tile /= 2;
     h->tile_elems = tile;
     h->hl.assign(L, DevLayer{});
     h->ht.clear();
@@ -780,7 +779,7 @@ static int profile_enqueue(lgreco_handle_t* h, const float* d_grads, const float
             qp.base_part = h->topk.d_base_part;
             if (x_out) {
                 // the compression behind this profile works from the candidates: it needs to know where they are
-                qp.cand_idx = h->topk.d_cand_idx;
+                qp.cand_idx = reinterpret_cast<uint16_t*>(h->topk.d_cand_idx);
                 h->topk.cand_has_idx = true;
             }
         }

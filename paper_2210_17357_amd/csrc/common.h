@@ -8,17 +8,14 @@
 
 namespace lgreco {
 
-constexpr int kTile = 65536;       // largest streaming tile in elements (512 buckets of 128)
+constexpr int kTile = 32768;       // largest streaming tile in elements (256 buckets of 128); a position inside a
+                                   // tile fits 15 bits (the Top-K candidate records rely on it)
 constexpr int kTileMin = 8192;     // smallest: small problems get smaller tiles so that the launch still fills the chip
 // Tile size: halved from kTile while there would be fewer than kTilesFill tiles (small problems
-// still fill the chip), down to kTileMin; then, no further than kTileSmooth, while there would be
-// fewer than kTilesWanted - several workgroups per slot of the chip (256 CUs x 8 workgroups), so
-// that the launch ends on many small tiles instead of a few large ones.  Measured on 355 M
-// elements: 5.4 k tiles of 65536 -> 10.8 k of 32768 took 4 % off the streaming kernels; 21.7 k of
-// 16384 cost the histogram pass more (one flush of 4096 bins per tile) than it gained.
+// still fill the chip), down to kTileMin.  Measured on 355 M elements: 10.8 k tiles of 32768
+// took 4 % off the streaming kernels against 5.4 k of 65536; 21.7 k of 16384 cost the histogram
+// pass more (one flush of 4096 bins per tile) than it gained.
 constexpr int kTilesFill = 2048;
-constexpr int kTilesWanted = 8192;
-constexpr int kTileSmooth = 32768;
 constexpr int kBucket = 128;       // quantization bucket (elements)
 constexpr int kChunk = 512;        // elements one wavefront handles per step (4 buckets)
 constexpr int kThreads = 256;      // workgroup size of the streaming kernels (4 wavefronts)
@@ -211,7 +208,7 @@ struct QuantParams {
     uint32_t* hist;            // [L x kHistBins] coarse magnitude histogram, or null
     const uint32_t* lo;        // [L] lowest coarse key collected as a candidate (collection mode)
     uint32_t* cand;            // candidate buffer
-    uint32_t* cand_idx;        // not null: index within the layer and sign of every candidate, same slots
+    uint16_t* cand_idx;        // not null: position within the tile (15 bits) and sign of every candidate, same slots
     const int64_t* cand_base;  // [L] first candidate slot of every layer
     void* tinfo;               // [n_tiles] TopkTileInfo
     double* base_part;         // [n_tiles] energy of the elements below lo

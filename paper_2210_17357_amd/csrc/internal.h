@@ -225,7 +225,8 @@ struct TopkScratch {
     void* d_tl = nullptr;             // per-layer selection records
     uint32_t* d_cnt_known = nullptr;  // [max_layers x 512] sub-bin counts of topk_compress_known
     uint32_t* d_cand = nullptr;       // bit patterns of the candidates, tile i at its own first element
-    uint32_t* d_cand_idx = nullptr;   // compress: index within the layer (+ sign bit) of every candidate
+    uint32_t* d_cand_idx = nullptr;   // compress: index within the layer (+ sign bit) of every candidate; a profile that
+                                      // records where its candidates are uses it for 16-bit entries (place in tile, sign)
     bool cand_has_idx = false;        // the current call's profile recorded d_cand_idx too
     // compression from the profile's candidates: what is kept of them, in element order
     uint32_t* d_kept = nullptr;
@@ -233,6 +234,8 @@ struct TopkScratch {
     void* d_tinfo_kept = nullptr;
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
     uint32_t* d_lo = nullptr;         // [max_layers] lowest coarse key collected as a candidate
+    uint32_t* d_any_again = nullptr;  // one word: number of the last scan that flagged a layer for a second collection
+    uint32_t scan_seq = 0;            // scans launched so far (never 0 once one has run)
     uint32_t* d_hint[2] = {nullptr, nullptr};   // per kind of call: bound derived from the last thresholds
     bool hint_valid[2] = {false, false};
     bool reuse_thresholds = false;

@@ -68,11 +68,11 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
 #pragma unroll
     for (int c = 0; c < kMaxQuant; ++c) acc[c] = 0.0f;
 
-    __shared__ uint32_t s_stage[HIST ? kThreads / 64 : 1][HIST ? (IDX ? 2 : 1) * kStageWords : 1];
+    __shared__ uint32_t s_stage[HIST ? kThreads / 64 : 1][HIST ? StagedCollector<IDX>::kWordsPerWave : 1];
     StagedCollector<IDX> col;
     uint32_t col_start = 0;
     uint32_t* const slice = HIST ? p.cand + p.cand_base[t.layer] + t.pos : nullptr;
-    uint32_t* const slice_idx = IDX ? p.cand_idx + p.cand_base[t.layer] + t.pos : nullptr;
+    uint16_t* const slice_idx = IDX ? p.cand_idx + p.cand_base[t.layer] + t.pos : nullptr;
     const uint32_t col_lo = HIST ? bound_of_key(p.lo[t.layer]) : 0xFFFFFFFFu;
 
     if (t.fast) {
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                     asm("" : "+v"(key));
                     atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s_hist) + (key >> (kHistShift - 2))),
                               1u);
-                    col.take_keyed(x[k], key, true, (uint32_t)t.pos + (uint32_t)(base + (k < 4 ? k : 60 + k)));
+                    col.take_keyed(x[k], key, true, (uint32_t)(base + (k < 4 ? k : 60 + k)));
                 }
             }
             float mn = fminf(min3f(min3f(min3f(x[0], x[1], x[2]), x[3], x[4]), x[5], x[6]), x[7]);
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void quant_profile_kernel(QuantParams p) 
                 if (ok[k] && xo) xo[idx] = x[k];
                 if (HIST) {
                     if (ok[k]) atomicAdd(&s_hist[mag_bits(x[k]) >> kHistShift], 1u);
-                    col.take(x[k], ok[k], (uint32_t)t.pos + (uint32_t)idx);
+                    col.take(x[k], ok[k], (uint32_t)idx);
                 }
             }
             const float inf = __builtin_huge_valf();

@@ -49,7 +49,7 @@ struct TopkLayer {
     TopkList lists[kMaxTopk];
     TopkSel sel[kMaxTopk];
 };
-constexpr int kRefTiles = 8;        // largest tiles per refinement / sample workgroup (fewer elements never: with
+constexpr int kRefTiles = 16;       // largest tiles per refinement / sample workgroup (fewer elements never: with
                                     // smaller tiles a workgroup takes proportionally more of them)
 constexpr int kRefThreads = 1024;
 constexpr int kRefSlots = 512;      // refinement workgroups the chip runs at a time (256 CUs x 2)
@@ -287,7 +287,7 @@ struct CollectParams {
     // KNOWN: the buffer behind g already holds x (e is null) and stays as it is: nothing is written
     // to the error feedback in this pass, the emit kernel zeroes the kept entries
     int32_t x_in_e;
-    // profile (no EMIT): index and sign of every candidate are recorded as in compress
+    // profile (no EMIT): where every candidate is goes to cand_idx too, as 16-bit entries (place16)
     int32_t record_idx;
 };
 
@@ -324,14 +324,16 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
     }
     const int64_t slice_off = p.cand_base[t.layer] + t.pos;
     uint32_t* const slice = p.cand + slice_off;
-    uint32_t* const slice_idx = (EMIT || p.record_idx) ? p.cand_idx + slice_off : nullptr;
+    uint32_t* const slice_idx = EMIT ? p.cand_idx + slice_off : nullptr;
+    uint16_t* const slice_at = (!EMIT && p.record_idx) ? reinterpret_cast<uint16_t*>(p.cand_idx) + slice_off : nullptr;
     Collector col;
     uint32_t start;
     if (t.fast) {
         int c0, c1;
         wave_range(t.count / kChunk, wave, &c0, &c1);
         start = (uint32_t)c0 * kChunk;
-        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound);
+        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound,
+                 slice_at ? slice_at + start : nullptr, (uint32_t)t.pos);
         // one 512-element chunk per iteration (uniform trip count): both halves are loaded before
         // either is used, so a lane keeps four 128-bit loads in flight
         for (int v = c0 * (kChunk / 4) + lane; v < c1 * (kChunk / 4); v += kChunk / 4) {
@@ -383,7 +385,8 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
         int b0, b1;
         wave_range((t.count + 63) / 64, wave, &b0, &b1);
         start = (uint32_t)b0 * 64;
-        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound);
+        col.init(slice + start, slice_idx ? slice_idx + start : nullptr, bound,
+                 slice_at ? slice_at + start : nullptr, (uint32_t)t.pos);
         for (int b = b0; b < b1; ++b) {
             const int i = b * 64 + lane;
             const bool valid = i < t.count;
@@ -468,8 +471,7 @@ __global__ __launch_bounds__(kThreads) void topk_filter_known_kernel(FilterParam
     const uint32_t n = p.tinfo[tile].cnt[wave], start = p.tinfo[tile].start[wave];
     const int64_t off = p.cand_base[t.layer] + t.pos + start;
     const uint32_t* const pats = p.cand + off;
-    const uint32_t* const idxs = p.cand_idx + off;
-    const uint32_t first = (uint32_t)t.pos + start;          // index within the layer of the slice's first element
+    const uint16_t* const idxs = reinterpret_cast<const uint16_t*>(p.cand_idx) + off;   // place16 entries
     for (int b = tid; b < kBinsB; b += kThreads) s_hist[b] = 0;
     for (int b = lane; b < kWords; b += 64) s_bits[wave][b] = 0;
     __syncthreads();
@@ -487,7 +489,7 @@ __global__ __launch_bounds__(kThreads) void topk_filter_known_kernel(FilterParam
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
-            const uint32_t rel = (ix[q] & 0x7FFFFFFFu) - first;
+            const uint32_t rel = (ix[q] & 0x7FFFu) - start;
             const bool pass = i0 + 64 * q + lane < n && pat[q] >= bound && rel < (uint32_t)kFilterSpan;
             const unsigned long long m = __ballot(pass);
             if (pass) {
@@ -526,11 +528,11 @@ __global__ __launch_bounds__(kThreads) void topk_filter_known_kernel(FilterParam
     uint32_t* const out = p.cand_out + off;
     uint32_t* const out_idx = p.cand_idx_out + off;
     auto place = [&](const uint32_t pat, const uint32_t ix) __attribute__((always_inline)) {
-        const uint32_t rel = (ix & 0x7FFFFFFFu) - first;
+        const uint32_t rel = (ix & 0x7FFFu) - start;
         const uint32_t w = rel >> 5;
         const uint32_t at = s_before[wave][w] + (uint32_t)__popc(s_bits[wave][w] & ((1u << (rel & 31u)) - 1u));
         out[at] = pat;
-        out_idx[at] = ix;
+        out_idx[at] = ((uint32_t)t.pos + (ix & 0x7FFFu)) | ((ix & 0x8000u) << 16);   // index within the layer, sign
     };
     if (kept <= (uint32_t)kFilterKeep) {
         for (uint32_t i = lane; i < kept; i += 64) {
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(kThreads) void topk_filter_known_kernel(FilterParam
             }
 #pragma unroll
             for (int q = 0; q < kBatch; ++q) {
-                const uint32_t rel = (ix[q] & 0x7FFFFFFFu) - first;
+                const uint32_t rel = (ix[q] & 0x7FFFu) - start;
                 if (i0 + 64 * q + lane < n && pat[q] >= bound && rel < (uint32_t)kFilterSpan) place(pat[q], ix[q]);
             }
         }
@@ -601,9 +603,13 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
 // do is short however many tiles there are.
 constexpr int kRecollectBatch = 8;
 template <bool EMIT>
-__global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams p, int n_tiles) {
+__global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams p, int n_tiles,
+                                                                   const uint32_t* __restrict__ any_again, uint32_t seq) {
     __shared__ uint32_t s_hist[1];
     __shared__ double s_red[kThreads / 64];
+    // no layer was flagged by the scan this launch follows (the usual case): one load and out.  (A
+    // stale word that happens to equal seq only costs the look at the per-layer flags below.)
+    if (*any_again != seq) return;
     const int first = (int)blockIdx.x * kRecollectBatch;
     // the flags of the batch's tiles first, every load of a level unconditional (indices clamped)
     // so that the chains tile -> layer -> flag run side by side
@@ -640,7 +646,8 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
                                                         const int64_t* __restrict__ cand_base,
                                                         const uint32_t* lo_in, uint32_t* lo_out,
                                                         TopkLayer* __restrict__ tl, uint32_t* hint, int clear,
-                                                        int n_layers, ScanReduce red) {
+                                                        int n_layers, ScanReduce red, uint32_t* any_again,
+                                                        uint32_t seq) {
     __shared__ __align__(16) unsigned char s_raw[sizeof(uint32_t) * kHistBins];   // 16 KB: the histogram, or the reduction's tree
     static_assert(sizeof(s_raw) >= sizeof(double) * kMaxQuant * 256, "shared by both jobs");
     if ((int)blockIdx.x >= n_layers) {
@@ -706,6 +713,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
         const uint32_t used = lo_in[l];
         sT.recollect = used > mn ? 1u : 0u;
         sT.pad = 0;
+        if (sT.recollect) *any_again = seq;        // this launch's number: the second collection has work
         lo_out[l] = sT.recollect ? mn : used;
         // collection bound for the next call of this kind: kHintMargin coarse bins (4.4 % in magnitude each)
         // under the lowest threshold found now
@@ -1404,6 +1412,9 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_kept_idx, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_tinfo_kept, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
+    TK_CHECK(hipMalloc(&t->d_any_again, 64));
+    TK_CHECK(hipMemset(t->d_any_again, 0, 64));
+    t->scan_seq = 0;
     for (int i = 0; i < 2; ++i) TK_CHECK(hipMalloc(&t->d_hint[i], sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
@@ -1446,6 +1457,7 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_kept_idx);
     (void)hipFree(t->d_tinfo_kept);
     (void)hipFree(t->d_lo);
+    (void)hipFree(t->d_any_again);
     for (int i = 0; i < 2; ++i) (void)hipFree(t->d_hint[i]);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
@@ -1642,7 +1654,7 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         hipLaunchKernelGGL(topk_scan_kernel, dim3(quant ? 2 * L : L), dim3(256), 0, s, t->d_hist,
                            (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base,
                            first_group ? t->lo_src : (const uint32_t*)t->d_lo, t->d_lo, (TopkLayer*)t->d_tl, hint,
-                           last_group ? 1 : 0, L, red);
+                           last_group ? 1 : 0, L, red, t->d_any_again, ++t->scan_seq);
         TK_CHECK(hipGetLastError());
         if (hint) t->hint_valid[t->cur_slot] = true;
         if (last_group) t->hist_clean = true;
@@ -1659,9 +1671,11 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         if (ef_out) {
             p.g = ef_out;
             p.e = nullptr;
-            hipLaunchKernelGGL(topk_recollect_kernel<true>, grid, dim3(kThreads), 0, s, p, n_tiles);
+            hipLaunchKernelGGL(topk_recollect_kernel<true>, grid, dim3(kThreads), 0, s, p, n_tiles,
+                               (const uint32_t*)t->d_any_again, t->scan_seq);
         } else {
-            hipLaunchKernelGGL(topk_recollect_kernel<false>, grid, dim3(kThreads), 0, s, p, n_tiles);
+            hipLaunchKernelGGL(topk_recollect_kernel<false>, grid, dim3(kThreads), 0, s, p, n_tiles,
+                               (const uint32_t*)t->d_any_again, t->scan_seq);
         }
         TK_CHECK(hipGetLastError());
     }

@@ -25,16 +25,24 @@ __device__ __forceinline__ uint32_t bound_of_key(uint32_t lo) {
     return (lo >= (uint32_t)kHistBins) ? 0xFFFFFFFFu : (lo << kHistShift);
 }
 
+// Where a candidate is, in 16 bits: position inside its tile (below kTile = 2^15) and the sign.
+__device__ __forceinline__ uint16_t place16(uint32_t in_tile, uint32_t bits) {
+    return (uint16_t)(in_tile | ((bits >> 16) & 0x8000u));
+}
+
 struct Collector {
     uint32_t* dst;
     uint32_t* dst_idx;   // optional: index (within the layer) and sign of every candidate
+    uint16_t* dst_idx16; // optional: the same as place16 of (index - idx_base)
+    uint32_t idx_base;   // the tile's first index within the layer
     uint32_t lo_key;   // lowest magnitude pattern collected (a multiple of a coarse key where the caller
                        // compares keys only; any pattern where it compares whole patterns)
     uint32_t cur;      // candidates written so far (uniform over the wavefront)
     float base;        // this lane's sum of x^2 over elements below the bound
     static constexpr uint32_t kKeyMask = (uint32_t)(kHistBins - 1) << kHistShift;
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t bound) {
-        dst = d; dst_idx = di; cur = 0; base = 0.0f;
+    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t bound, uint16_t* di16 = nullptr,
+                                         uint32_t tile_first = 0) {
+        dst = d; dst_idx = di; dst_idx16 = di16; idx_base = tile_first; cur = 0; base = 0.0f;
         lo_key = bound;
     }
     __device__ __forceinline__ static uint32_t below(unsigned long long m, uint32_t add) {
@@ -58,6 +66,7 @@ struct Collector {
             *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(dst) + off) = bits & 0x7FFFFFFFu;
             if (dst_idx)
                 *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(dst_idx) + off) = idx | (bits & 0x80000000u);
+            if (dst_idx16) dst_idx16[off >> 2] = place16(idx - idx_base, bits);
         }
         cur += (uint32_t)__popcll(m);
     }
@@ -78,6 +87,7 @@ struct Collector {
             if (hit[q]) {
                 dst[at] = pat[q];
                 if (dst_idx) dst_idx[at] = (idx0 + q) | (__float_as_uint(x[q]) & 0x80000000u);
+                if (dst_idx16) dst_idx16[at] = place16(idx0 + q - idx_base, __float_as_uint(x[q]));
                 ++at;
             } else {
                 base = __builtin_fmaf(x[q], x[q], base);
@@ -90,24 +100,28 @@ struct Collector {
 // The same collection with the candidates staged in LDS: a wavefront appends to its own buffer of
 // kStageWords words and writes 128 candidates at a time, as two full 256-byte stores, instead of a
 // few scattered words per element slot.  Order and content of the slice are those of Collector.
-// IDX: index within the layer and sign of every candidate go the same way through a second buffer
-// of kStageWords words right behind the first, into dst_idx.
+// IDX: where every candidate is (place16) goes the same way through a second buffer of kStageWords
+// 16-bit entries right behind the first, into dst_idx.
 constexpr int kStageFlush = 128;
 constexpr int kStageWords = kStageFlush + 64;     // below kStageFlush before an append of at most 64
 template <bool IDX>
 struct StagedCollector {
+    static constexpr int kWordsPerWave = IDX ? kStageWords + kStageWords / 2 : kStageWords;
     uint32_t* dst;       // the wavefront's slice in global memory
-    uint32_t* dst_idx;   // IDX: the same slice of the index buffer
-    uint32_t* stage;     // the wavefront's kStageWords (IDX: 2 * kStageWords) words of LDS
+    uint16_t* dst_idx;   // IDX: the same slice of the place buffer
+    uint32_t* stage;     // the wavefront's kWordsPerWave words of LDS
+    uint16_t* stage16;   // IDX: its second part
     uint32_t lo_key;
     uint32_t cur;        // candidates written to global memory so far (uniform over the wavefront)
     uint32_t fill;       // candidates waiting in the buffer (uniform)
     float base;          // this lane's sum of x^2 over elements below the bound
-    __device__ __forceinline__ void init(uint32_t* d, uint32_t* di, uint32_t* st, uint32_t bound) {
-        dst = d; dst_idx = di; stage = st; cur = 0; fill = 0; base = 0.0f;
+    __device__ __forceinline__ void init(uint32_t* d, uint16_t* di, uint32_t* st, uint32_t bound) {
+        dst = d; dst_idx = di; stage = st; stage16 = reinterpret_cast<uint16_t*>(st + kStageWords);
+        cur = 0; fill = 0; base = 0.0f;
         lo_key = bound;
     }
-    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid, uint32_t idx = 0) {
+    // in_tile: the element's position inside its tile (IDX only)
+    __device__ __forceinline__ void take_keyed(float x, uint32_t key, bool valid, uint32_t in_tile = 0) {
         const uint32_t bits = __float_as_uint(x);
         const bool hit = valid && key >= lo_key;
         const unsigned long long m = __ballot(hit);
@@ -116,7 +130,7 @@ struct StagedCollector {
         if (hit) {
             const uint32_t at = fill + Collector::below(m, 0u);
             stage[at] = bits & 0x7FFFFFFFu;
-            if (IDX) stage[kStageWords + at] = idx | (bits & 0x80000000u);
+            if (IDX) stage16[at] = place16(in_tile, bits);
         }
         fill += (uint32_t)__popcll(m);
         if (fill >= (uint32_t)kStageFlush) {          // uniform
@@ -127,26 +141,26 @@ struct StagedCollector {
             dst[cur + lane] = v0;
             dst[cur + 64 + lane] = v1;
             if (IDX) {
-                const uint32_t i0 = stage[kStageWords + lane], i1 = stage[kStageWords + 64 + lane];
-                const uint32_t i2 = stage[kStageWords + kStageFlush + lane];
+                const uint16_t i0 = stage16[lane], i1 = stage16[64 + lane];
+                const uint16_t i2 = stage16[kStageFlush + lane];
                 dst_idx[cur + lane] = i0;
                 dst_idx[cur + 64 + lane] = i1;
-                if (lane < rem) stage[kStageWords + lane] = i2;
+                if (lane < rem) stage16[lane] = i2;
             }
             if (lane < rem) stage[lane] = v2;         // what is left moves to the front
             cur += kStageFlush;
             fill = rem;
         }
     }
-    __device__ __forceinline__ void take(float x, bool valid, uint32_t idx = 0) {
-        take_keyed(x, __float_as_uint(x) & Collector::kKeyMask, valid, idx);
+    __device__ __forceinline__ void take(float x, bool valid, uint32_t in_tile = 0) {
+        take_keyed(x, __float_as_uint(x) & Collector::kKeyMask, valid, in_tile);
     }
     // writes out what is left; afterwards cur is the wavefront's candidate count
     __device__ __forceinline__ void finish() {
         const uint32_t lane = threadIdx.x & 63u;
         for (uint32_t i = lane; i < fill; i += 64) {
             dst[cur + i] = stage[i];
-            if (IDX) dst_idx[cur + i] = stage[kStageWords + i];
+            if (IDX) dst_idx[cur + i] = stage16[i];
         }
         cur += fill;
         fill = 0;
