@@ -1065,23 +1065,30 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         ec->phase = h->tm->open_phase("phase_compress");
         bool any_quant = false;
         for (int c = 0; c < P; ++c) any_quant = any_quant || cands[c].family == LGRECO_QUANT;
-        // With both families the quantized layers' one kernel goes to the second stream, behind
-        // the Top-K layers' main pass: the rest of their chain is a handful of short kernels that
-        // leave most of the chip idle, and the two parts write disjoint layers (error feedback
-        // and payload alike).
+        // With both families the quantized layers' one kernel goes to the second stream: the Top-K
+        // layers' part is one pass over the candidates and a handful of short kernels that leave
+        // most of the chip idle, and the two parts write disjoint layers (error feedback and
+        // payload alike).  The quantization kernel is launched with 30 KB of LDS it does not use,
+        // which holds it to five workgroups per compute unit instead of the six its registers
+        // allow: the room left (a quarter of the vector registers) is what lets the Top-K kernels'
+        // workgroups in beside it.  Measured on the 355 M-element mixed workload, the compression
+        // from the solver kernel's end to its last kernel's: 272 us on one stream, 217 with the
+        // quantization kernel queued behind the Top-K main pass, 213 beside it without the LDS,
+        // 197 with it (the two bandwidth-bound kernels alone take 192).
         const bool beside = any_quant && ec->topk_known;
+        if (beside) HIPCHK(hipEventRecord(h->ev_fork, s));
         if (ec->topk_known) {
             // the Top-K layers' part, from the selection records the profile left for this very
             // data: the chosen density's record is picked on the device
             HIPCHK(topk_compress_known(&h->topk, d_grads, ec->d_ef, h->d_layers, h->d_tiles, L, (int)h->ht.size(),
-                                       ec->d_payload, h->tm, s, ec->x_in_e, beside ? h->ev_fork : nullptr));
+                                       ec->d_payload, h->tm, s, ec->x_in_e, beside));
         }
         if (beside) HIPCHK(hipStreamWaitEvent(h->side, h->ev_fork, 0));
         if (any_quant) {
             Section sec(h->tm, "quant_compress", true);
             HIPCHK(launch_quant_compress(ec->x_in_e ? nullptr : d_grads, ec->d_ef, h->d_layers, h->d_tiles,
                                          (int)h->ht.size(), ec->d_payload, h->cfg.stochastic != 0, h->cfg.seed,
-                                         beside ? h->side : s, &sec));
+                                         beside ? h->side : s, &sec, beside ? 30 * 1024 : 0));
         }
         if (beside) {
             HIPCHK(hipEventRecord(h->ev_join, h->side));

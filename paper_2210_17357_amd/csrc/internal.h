@@ -125,7 +125,7 @@ hipError_t launch_reduce_partials(const double* partials, int stride, const int*
                                   const DevLayer* layers, int n_layers, double* errors, hipStream_t s);
 hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
                                  int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
-                                 hipStream_t s, Section* sec);
+                                 hipStream_t s, Section* sec, size_t lds_pad = 0);   // lds_pad: LDS bytes requested and not used
 
 // ---- dp.hip
 struct DpEntry {            // one usable candidate of a layer (equal bins merged by the host)
@@ -308,10 +308,11 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // Top-K layers of a compression queued right behind a profile of the same data and the solver
 // kernel that wrote the layer records (family, k, payload offset, slot of the chosen density in
 // the profile's selection records): nothing here needs the host to know the assignment.
-// after_main (may be null): recorded on s behind the pass that moves the bulk of the bytes.
+// shared_chip: another stream's kernel fills most of the chip meanwhile (the scan of the counts
+// then runs in workgroups small enough to be placed beside it).
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                                const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
-                               bool x_in_e = false, hipEvent_t after_main = nullptr);
+                               bool x_in_e = false, bool shared_chip = false);
 
 // ---- lowrank.hip
 struct LowrankScratch {

@@ -476,13 +476,13 @@ hipError_t launch_reduce_partials(const double* partials, int stride, const int*
 
 hipError_t launch_quant_compress(const float* g, float* e, const DevLayer* layers, const Tile* tiles,
                                  int n_tiles, uint8_t* payload, bool stochastic, uint64_t seed,
-                                 hipStream_t s, Section* sec) {
+                                 hipStream_t s, Section* sec, size_t lds_pad) {
     if (n_tiles <= 0) return hipSuccess;
     QuantCompressParams p{g, e, layers, tiles, payload, (uint32_t)seed, (uint32_t)(seed >> 32)};
     if (stochastic)
-        launch_timed(sec, true, true, quant_compress_kernel<true>, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, quant_compress_kernel<true>, dim3(n_tiles), dim3(kThreads), lds_pad, s, p);
     else
-        launch_timed(sec, true, true, quant_compress_kernel<false>, dim3(n_tiles), dim3(kThreads), 0, s, p);
+        launch_timed(sec, true, true, quant_compress_kernel<false>, dim3(n_tiles), dim3(kThreads), lds_pad, s, p);
     return hipGetLastError();
 }
 

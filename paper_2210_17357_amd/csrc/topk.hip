@@ -610,7 +610,8 @@ __global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams 
     // no layer was flagged by the scan this launch follows (the usual case): one load and out.  (A
     // stale word that happens to equal seq only costs the look at the per-layer flags below.)
     if (*any_again != seq) return;
-    const int first = (int)blockIdx.x * kRecollectBatch;
+    // (the grid is capped: a workgroup goes on to further batches)
+    for (int first = (int)blockIdx.x * kRecollectBatch; first < n_tiles; first += (int)gridDim.x * kRecollectBatch) {
     // the flags of the batch's tiles first, every load of a level unconditional (indices clamped)
     // so that the chains tile -> layer -> flag run side by side
     int layer[kRecollectBatch];
@@ -627,6 +628,7 @@ __global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams 
         if (!(todo >> q & 1u)) continue;                // workgroup-uniform
         collect_tile<false, EMIT>(p, first + q, s_hist, s_red);
         __syncthreads();                                // s_red is reused
+    }
     }
 }
 
@@ -1231,9 +1233,11 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(const Tile* __rest
 
 // per layer: exclusive prefix of the per-wavefront counts, in element order.  Both counts travel
 // in one 64-bit word (each stays below 2^31: a layer has fewer elements than that) and a thread
-// takes four consecutive entries, so a round of the 1024 threads covers 4096 entries with one scan
-// (the largest layer's entries, tiles x 4, are the critical path of this kernel).
-constexpr int kScanThreads = 1024;
+// takes four consecutive entries, so a round of 1024 threads covers 4096 entries with one scan
+// (the largest layer's entries, tiles x 4, are the critical path of this kernel); 256 threads when
+// the chip is shared with another stream's kernel and a workgroup of 16 wavefronts would wait long
+// for a compute unit with that much room.
+template <int kScanThreads>
 __global__ __launch_bounds__(kScanThreads) void topk_tilescan_kernel(const DevLayer* __restrict__ layers,
                                                             const uint2* __restrict__ wavecnt,
                                                             uint2* __restrict__ wavebase) {
@@ -1667,7 +1671,8 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         p.ef_out = ef_out;
         p.record_idx = (!ef_out && t->cand_has_idx) ? 1 : 0;
         // a second collection reads x = g + e again: in compress e already holds x, so g is not added
-        const dim3 grid((n_tiles + kRecollectBatch - 1) / kRecollectBatch);
+        // at most two workgroups per compute unit: the launch that finds nothing to do ends at once
+        const dim3 grid(std::min((n_tiles + kRecollectBatch - 1) / kRecollectBatch, 512));
         if (ef_out) {
             p.g = ef_out;
             p.e = nullptr;
@@ -1766,7 +1771,7 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
     }
     {
         Section sec(tm, "topk_tilescan");
-        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(kScanThreads), 0, s, d_layers, (const uint2*)t->d_tilecnt,
+        hipLaunchKernelGGL(topk_tilescan_kernel<1024>, dim3(L), dim3(1024), 0, s, d_layers, (const uint2*)t->d_tilecnt,
                            (uint2*)t->d_tilebase);
         TK_CHECK(hipGetLastError());
     }
@@ -1791,11 +1796,8 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // per-wavefront counts, their scan and the ordered emit, as in topk_compress.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                                const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
-                               bool x_in_e, hipEvent_t after_main) {
-    if (n_tiles <= 0) {
-        if (after_main) TK_CHECK(hipEventRecord(after_main, s));
-        return hipSuccess;
-    }
+                               bool x_in_e, bool shared_chip) {
+    if (n_tiles <= 0) return hipSuccess;
     // the profile's control block (slot 0) holds every layer's candidate region
     uint8_t* const d = t->d_ctl[0];
     CollectParams p{};
@@ -1843,8 +1845,6 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
         launch_timed(&sec, true, true, topk_collect_known_kernel, dim3(n_tiles), dim3(kThreads), 0, s, p);
         TK_CHECK(hipGetLastError());
     }
-    // what follows are short kernels: work of another stream that waits for this event runs beside them
-    if (after_main) TK_CHECK(hipEventRecord(after_main, s));
     {
         Section sec(tm, "topk_pick");
         hipLaunchKernelGGL(topk_pick_known_kernel, dim3(L), dim3(256), 0, s, d_layers, (TopkLayer*)t->d_tl,
@@ -1859,8 +1859,12 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
     }
     {
         Section sec(tm, "topk_tilescan");
-        hipLaunchKernelGGL(topk_tilescan_kernel, dim3(L), dim3(kScanThreads), 0, s, d_layers, (const uint2*)t->d_tilecnt,
-                           (uint2*)t->d_tilebase);
+        if (shared_chip)
+            hipLaunchKernelGGL(topk_tilescan_kernel<256>, dim3(L), dim3(256), 0, s, d_layers, (const uint2*)t->d_tilecnt,
+                               (uint2*)t->d_tilebase);
+        else
+            hipLaunchKernelGGL(topk_tilescan_kernel<1024>, dim3(L), dim3(1024), 0, s, d_layers,
+                               (const uint2*)t->d_tilecnt, (uint2*)t->d_tilebase);
         TK_CHECK(hipGetLastError());
     }
     {
