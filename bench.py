@@ -322,6 +322,13 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     step_gbps = (profile_bytes + compress_bytes) / (ms_per_step * 1e-3) / 1e9
     roofline_phase["step"] = {"algorithmic_bytes": round(profile_bytes + compress_bytes), "ms": round(ms_per_step, 4),
                               "GBps": round(step_gbps, 1), "frac": round(step_gbps / HBM_PEAK_GBS, 4)}
+    if in_place:
+        # The step also against what the path moves when profile and compression each read g and e
+        # (8 bytes per element, then 12 and the payload: the accounting of the separate calls): a
+        # step that avoids bytes should not look worse for it.
+        two_pass = 8.0 * N + float((12.0 * numels + chosen_bytes).sum())
+        roofline_phase["step"].update(two_pass_bytes=round(two_pass),
+                                      two_pass_frac=round(two_pass / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
     if lowrank:
         # the contraction-bound part: flops of the factor GEMMs over the time of the whole phase
         for key, fl in (("profile", 4.0 * mn2d * w.r_max * args.power_iters),

@@ -106,7 +106,8 @@ typedef struct {
     int32_t  keep_ef_on_failure; /* lgreco_profile_solve_compress with quantization / Top-K candidates
                             * only: 0 = the profile leaves x = fl32(g + e) in d_ef as it forms it and
                             * the compression reads x there (less memory traffic: g is read once,
-                            * and the Top-K layers need no pass that rewrites what is not kept); a
+                            * and the Top-K layers are compressed from the candidates the profile
+                            * recorded, with no further pass over their data); a
                             * call that fails after its profile ran then leaves d_ef = x.  1 = d_ef
                             * is written by the compression only and is untouched when the call
                             * fails.  Results of a successful call are the same either way. */
@@ -283,7 +284,11 @@ int lgreco_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
  * Whenever nothing is compressed (a failed solve, a payload buffer too small, a table that is not
  * finite) d_ef holds either what it held before or, with keep_ef_on_failure = 0 and no low-rank
  * candidate, x = fl32(g + e): the gradient an uncompressed step would send, with the error
- * feedback already added. */
+ * feedback already added.
+ * With quantization and Top-K candidates in one list part of the compression is queued on a
+ * stream the handle owns (default priority); it starts behind the solver's kernel on `stream` and
+ * `stream` waits for it before the call returns, so for the caller everything is in `stream`'s
+ * order as before. */
 int lgreco_profile_solve_compress(lgreco_handle_t* h, const float* d_grads, float* d_ef,
                                   const lgreco_layer_t* layers, int32_t L, const lgreco_cand_t* cands,
                                   int32_t P, float* d_q, int32_t default_cand, int32_t n_bins,

@@ -1075,7 +1075,9 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
         // from the solver kernel's end to its last kernel's: 272 us on one stream, 217 with the
         // quantization kernel queued behind the Top-K main pass, 213 beside it without the LDS,
         // 197 with it (the two bandwidth-bound kernels alone take 192).
-        const bool beside = any_quant && ec->topk_known;
+        // (Only when the Top-K part works from the candidates: its pass over the whole data, which
+        // the keep_ef_on_failure path makes, is as bandwidth-bound as the quantization kernel.)
+        const bool beside = any_quant && ec->topk_known && ec->x_in_e;
         if (beside) HIPCHK(hipEventRecord(h->ev_fork, s));
         if (ec->topk_known) {
             // the Top-K layers' part, from the selection records the profile left for this very
