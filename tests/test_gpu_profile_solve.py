@@ -404,6 +404,55 @@ def test_whole_path_call_keeping_much_of_every_slice(default, n_bins):
     h.close()
 
 
+@pytest.mark.parametrize("kind", ["mixed", "topk"])
+def test_whole_path_call_when_the_data_moves_past_the_remembered_thresholds(kind):
+    """The one call on a handle that starts every profile from the previous call's thresholds,
+    with data that is scaled far down between calls (every remembered bound is too high: the
+    layers are collected a second time, from the buffer the first collection left x in, and the
+    compression works from the second collection's candidate records), far up (everything becomes
+    a candidate) and by the few per cent of a training loop.  Payload and error feedback of every
+    call against the separate calls on a handle that samples every time, and against the oracle's
+    compressor on a sample of layers."""
+    from oracle import pipeline
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload(kind)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    reuse = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    plain = B.Handle(int(batch.grads.size), L, len(cands))
+    big = sorted(range(L), key=lambda l: -int(batch.numels[l]))[:3]
+    for factor in (1.0, 1.0, 1e-3, 1.0, 1e3, 1.03, 0.97):
+        gh = (batch.grads * np.float32(factor)).astype(np.float32)
+        eh = (batch.ef * np.float32(factor)).astype(np.float32)
+        g, e = torch.from_numpy(gh).cuda(), torch.from_numpy(eh).cuda()
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        st, errors, sizes, e_max, choice, tsize, terr, offsets = reuse.profile_solve_compress(
+            g, ef, layers, ctab, w.default, w.n_bins, pay)
+        torch.cuda.synchronize()
+        assert st == B.OK, factor
+        ref_choice, ref_size, _ = solver.solve(errors, sizes, e_max, w.n_bins)
+        assert np.array_equal(choice, ref_choice) and tsize == ref_size, factor
+        pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef2 = e.clone()
+        plain.compress(g, ef2, layers, ctab, choice, pay2, offsets)
+        torch.cuda.synchronize()
+        assert torch.equal(pay, pay2), factor
+        assert torch.equal(ef.view(torch.int32), ef2.view(torch.int32)), factor
+        pay_h, ef_h = pay.cpu().numpy(), ef.cpu().numpy()
+        for l in big + [0, L - 1]:
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            p_ref, e_ref, _ = pipeline.compress_layer(gh, eh, off, n, 0, 0, cands[choice[l]], l)
+            assert np.array_equal(pay_h[offsets[l]:offsets[l] + p_ref.size], p_ref), (factor, l, cands[choice[l]])
+            assert np.array_equal(ef_h[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (factor, l)
+    reuse.close()
+    plain.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
 def test_zero_error_feedback_promise_changes_nothing(kind):
     """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return
