@@ -25,6 +25,9 @@
 //      nothing depends on the order of atomics.
 // Compression then counts kept entries per tile from the candidates, scans the tile counts, and
 // writes values and indices in ascending index order (equal magnitudes: lowest indices first).
+// A compression queued right behind a profile of the same data takes the candidates from that
+// profile, whose main pass then also records where each candidate is (16 bits: position in the
+// tile, sign), and reads the data no second time.
 #include <cstdlib>
 #include <cstring>
 
@@ -284,9 +287,6 @@ struct CollectParams {
     // profile (no EMIT): not null = x is written here as it is formed (may be the buffer e points to:
     // every element is read once, by the lane that then writes it)
     float* x_out;
-    // KNOWN: the buffer behind g already holds x (e is null) and stays as it is: nothing is written
-    // to the error feedback in this pass, the emit kernel zeroes the kept entries
-    int32_t x_in_e;
     // profile (no EMIT): where every candidate is goes to cand_idx too, as 16-bit entries (place16)
     int32_t record_idx;
 };
@@ -350,9 +350,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if (!EMIT && xo) store_stream(reinterpret_cast<float4*>(xo) + v + 64 * h, a[h]);
-                if (EMIT && KNOWN && p.x_in_e) {
-                    // the buffer holds x already: nothing to write here
-                } else if (EMIT && KNOWN) {
+                if (EMIT && KNOWN) {
                     // nearly every candidate is kept here: candidates are written as zero at once, the
                     // emit step puts the few that are not kept back
                     float4 w = a[h];
@@ -392,7 +390,7 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
             const bool valid = i < t.count;
             float x = 0.0f;
             if (valid) x = ep ? gp[i] + ep[i] : gp[i];
-            if (EMIT && valid && !(KNOWN && p.x_in_e)) eo[i] = (KNOWN && mag_bits(x) >= bound) ? 0.0f : x;
+            if (EMIT && valid) eo[i] = (KNOWN && mag_bits(x) >= bound) ? 0.0f : x;
             if (!EMIT && valid && xo) xo[i] = x;
             if (HIST && valid) atomicAdd(&s_hist[mag_bits(x) >> kHistShift], 1u);
             if (KNOWN && valid && mag_bits(x) - bound < (uint32_t)kBinsB) atomicAdd(&s_hist[mag_bits(x) - bound], 1u);
@@ -1790,10 +1788,12 @@ hipError_t topk_compress(TopkScratch* t, const float* g, float* e, const DevLaye
 // Compression of the Top-K layers right behind a profile of the same data (the one-call entry
 // point): the layer records the solver kernel wrote say which layers take part and which of the
 // profile's selection records (threshold bin, sub-bin, entries to take) applies, so nothing is
-// sampled, no histogram is built and nothing depends on the host knowing the assignment.  One
-// pass writes x to the error feedback and collects what lies at or above the sub-bin's lower
-// edge, counting the sub-bin's entries by their last 9 bits; then the exact threshold, the
-// per-wavefront counts, their scan and the ordered emit, as in topk_compress.
+// sampled, no histogram is built and nothing depends on the host knowing the assignment.
+// x_in_e (the profile left x in the error-feedback buffer and recorded where its candidates are):
+// what lies at or above the sub-bin's lower edge is taken from the profile's candidates, the
+// sub-bin's entries counted by their last 9 bits, and the data is not read at all.  Otherwise one
+// pass over g and e writes x to the error feedback and collects the same set.  Then the exact
+// threshold, the per-wavefront counts, their scan and the ordered emit, as in topk_compress.
 hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const DevLayer* d_layers,
                                const Tile* d_tiles, int L, int n_tiles, uint8_t* payload, Timing* tm, hipStream_t s,
                                bool x_in_e, bool shared_chip) {
@@ -1801,11 +1801,8 @@ hipError_t topk_compress_known(TopkScratch* t, const float* g, float* e, const D
     // the profile's control block (slot 0) holds every layer's candidate region
     uint8_t* const d = t->d_ctl[0];
     CollectParams p{};
-    // x_in_e: the profile left x = fl32(g + e) in the error-feedback buffer; the pass reads that
-    // alone and writes nothing back (the emit kernel zeroes the kept entries)
-    p.g = x_in_e ? e : g;
-    p.e = x_in_e ? nullptr : e;
-    p.x_in_e = x_in_e ? 1 : 0;
+    p.g = g;
+    p.e = e;
     p.ef_out = e;
     p.layers = d_layers;
     p.tiles = d_tiles;
