@@ -453,6 +453,49 @@ def test_whole_path_call_when_the_data_moves_past_the_remembered_thresholds(kind
     plain.close()
 
 
+@pytest.mark.parametrize("kind", ["mixed", "topk"])
+def test_whole_path_calls_back_to_back_without_waiting_for_the_gpu(kind):
+    """A training loop's use: the one call returns when the host has the assignment, with the
+    compression still queued (part of it on the handle's second stream), and the next call, on
+    other buffers, is issued at once.  Six calls over three sets of buffers, one wait at the end:
+    every payload and error feedback equals what the separate calls give for that set."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload(kind)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    sets = []
+    for f in (1.0, 1.03, 0.97):
+        g = torch.from_numpy((batch.grads * np.float32(f)).astype(np.float32)).cuda()
+        e = torch.from_numpy((batch.ef * np.float32(f)).astype(np.float32)).cuda()
+        sets.append((g, e))
+    h = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    runs = []
+    for step in range(6):
+        g, e = sets[step % 3]
+        ef = e.clone()
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        out = h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, pay, stream=stream)
+        assert out[0] == B.OK
+        runs.append((step % 3, out, ef, pay))
+    torch.cuda.synchronize()
+    ref = B.Handle(int(batch.grads.size), L, len(cands))
+    for which, out, ef, pay in runs:
+        g, e = sets[which]
+        choice, offsets = out[4], out[7]
+        ef2 = e.clone()
+        pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ref.compress(g, ef2, layers, ctab, choice, pay2, offsets)
+        torch.cuda.synchronize()
+        assert torch.equal(pay, pay2) and torch.equal(ef.view(torch.int32), ef2.view(torch.int32)), which
+    h.close()
+    ref.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
 def test_zero_error_feedback_promise_changes_nothing(kind):
     """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return
