@@ -496,6 +496,110 @@ def test_whole_path_calls_back_to_back_without_waiting_for_the_gpu(kind):
     ref.close()
 
 
+def _one_call_against_separate(reuse, plain, g, e, layers, ctab, default, n_bins, capacity, tag, strict=False):
+    """One call on `reuse`; the same assignment compressed by the separate call on `plain`."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef = e.clone()
+    out = reuse.profile_solve_compress(g, ef, layers, ctab, default, n_bins, pay)
+    torch.cuda.synchronize()
+    assert out[0] == B.OK, tag
+    ref_choice, ref_size, _ = solver.solve(out[1], out[2], out[3], n_bins, strict=strict)
+    if ref_choice is not None:          # (None: nothing fits the strict budget, the call falls back to the default)
+        assert np.array_equal(out[4], ref_choice) and out[5] == ref_size, tag
+    pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+    ef2 = e.clone()
+    plain.compress(g, ef2, layers, ctab, out[4], pay2, out[7])
+    torch.cuda.synchronize()
+    assert torch.equal(pay, pay2), tag
+    assert torch.equal(ef.view(torch.int32), ef2.view(torch.int32)), tag
+    return out
+
+
+def test_whole_path_call_when_the_assignment_changes_between_calls():
+    """One handle with history on (every profile starts from the previous call's thresholds, the
+    device's layer records are those the previous call's solver kernel wrote), and an assignment
+    that changes from call to call: the budget and the default move so that layers go from
+    quantization to Top-K and back.  Nothing a call leaves behind may leak into the next: every
+    call against the separate calls and the oracle's solver; the last calls repeat one setting."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload("mixed")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    nq = sum(1 for f, _ in cands if f == W.QUANT)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    reuse = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    plain = B.Handle(int(batch.grads.size), L, len(cands))
+    fams = []
+    settings = [(w.default, w.n_bins), (len(cands) - 1, 300), (0, 50), (nq, 1000), (nq - 1, 2000),
+                (w.default, w.n_bins), (w.default, w.n_bins)]
+    for i, (default, n_bins) in enumerate(settings):
+        out = _one_call_against_separate(reuse, plain, g, e, layers, ctab, default, n_bins, capacity, (i, default, n_bins))
+        fams.append(np.array([cands[c][0] for c in out[4]]))
+    to_topk = sum(int(((a == W.QUANT) & (b == W.TOPK)).sum()) for a, b in zip(fams, fams[1:]))
+    to_quant = sum(int(((a == W.TOPK) & (b == W.QUANT)).sum()) for a, b in zip(fams, fams[1:]))
+    assert to_topk > 0 and to_quant > 0, "no layer changed family between calls: the case misses its point"
+    reuse.close()
+    plain.close()
+
+
+def test_whole_path_call_failing_after_good_calls_with_history_on():
+    """History on, a good call, then calls that end without compressing (payload buffer too small,
+    a non-finite gradient): the error-feedback buffer must hold x = fl32(g + e) everywhere and the
+    payload buffer nothing, and the handle goes on working; a call whose solve falls back to the
+    uniform default (strict budget, nothing fits) compresses through the host's route, which
+    reads x from the buffer the profile left it in."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload("mixed")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    plain = B.Handle(int(batch.grads.size), L, len(cands))
+    for strict in (0, 1):
+        reuse = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True, strict_budget=strict)
+        first = _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, w.n_bins, capacity, "first", bool(strict))
+        assert any(cands[c][0] == W.QUANT for c in first[4])
+        # payload buffer too small
+        small = torch.zeros(64, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        with pytest.raises(B.LgrecoError) as err:
+            reuse.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, small)
+        assert err.value.status == B.ENOSPACE
+        torch.cuda.synchronize()
+        assert torch.equal(ef.view(torch.int32), (g + e).view(torch.int32)) and int(small.count_nonzero()) == 0
+        # a good call again, then a non-finite gradient
+        _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, w.n_bins, capacity, "again", bool(strict))
+        bad_g = g.clone()
+        bad_g[int(batch.offsets[2]) + 5] = float("inf")
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        try:
+            st = reuse.profile_solve_compress(bad_g, ef, layers, ctab, w.default, w.n_bins, pay)[0]
+        except B.LgrecoError as err2:
+            st = err2.status
+        assert st in (B.EINVAL, B.EINFEASIBLE)
+        torch.cuda.synchronize()
+        assert torch.equal(ef.view(torch.int32), (bad_g + e).view(torch.int32)) and int(pay.count_nonzero()) == 0
+        _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, w.n_bins, capacity, "after inf", bool(strict))
+        if strict:
+            # fewer bins than layers: nothing fits the strict budget, the call returns the uniform
+            # default and compresses through the host's route
+            out = _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, L - 1, capacity, "strict fallback", True)
+            assert (out[4] == w.default).all()
+            _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, w.n_bins, capacity, "after fallback", True)
+        reuse.close()
+    plain.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
 def test_zero_error_feedback_promise_changes_nothing(kind):
     """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return
