@@ -26,6 +26,7 @@ __device__ __forceinline__ uint32_t bound_of_key(uint32_t lo) {
 }
 
 // Where a candidate is, in 16 bits: position inside its tile (below kTile = 2^15) and the sign.
+static_assert(kTile <= (1 << 15), "a position inside a tile must fit 15 bits");
 __device__ __forceinline__ uint16_t place16(uint32_t in_tile, uint32_t bits) {
     return (uint16_t)(in_tile | ((bits >> 16) & 0x8000u));
 }
