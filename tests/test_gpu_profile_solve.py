@@ -496,6 +496,48 @@ def test_whole_path_calls_back_to_back_without_waiting_for_the_gpu(kind):
     ref.close()
 
 
+@pytest.mark.parametrize("name", ["c1_resnet18_quant", "c2_resnet50_topk"])
+def test_whole_path_call_at_full_size_of_the_smaller_workloads(name):
+    """The one call as the benchmark times it (history on, three steps over buffers scaled by
+    1, 1.03, 0.97) on the whole 11.7 M-element quantization workload (stochastic rounding) and the
+    whole 25.6 M-element Top-K workload: assignment against the oracle's solver on the call's own
+    tables, payload and error feedback against the separate calls bit for bit and, on the largest
+    layers and the first and last one, against the oracle's compressor."""
+    from oracle import pipeline
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = W.workload(name)
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    reuse = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed, reuse_thresholds=True)
+    plain = B.Handle(int(batch.grads.size), L, len(cands), stochastic=w.stochastic, seed=w.seed)
+    big = sorted(range(L), key=lambda l: -int(batch.numels[l]))[:2]
+    for step, factor in enumerate((1.0, 1.03, 0.97)):
+        gh = (batch.grads * np.float32(factor)).astype(np.float32)
+        eh = (batch.ef * np.float32(factor)).astype(np.float32)
+        g, e = torch.from_numpy(gh).cuda(), torch.from_numpy(eh).cuda()
+        out = _one_call_against_separate(reuse, plain, g, e, layers, ctab, w.default, w.n_bins, capacity, (name, step))
+        choice, offsets = out[4], out[7]
+        if step != 1:
+            continue
+        pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ef = e.clone()
+        plain.compress(g, ef, layers, ctab, choice, pay, offsets)      # equal to the one call's (checked above)
+        torch.cuda.synchronize()
+        pay_h, ef_h = pay.cpu().numpy(), ef.cpu().numpy()
+        for l in big + [0, L - 1]:
+            off, n = int(batch.offsets[l]), int(batch.numels[l])
+            p_ref, e_ref, _ = pipeline.compress_layer(gh, eh, off, n, 0, 0, cands[choice[l]], l,
+                                                      stochastic=bool(w.stochastic), seed=w.seed)
+            assert np.array_equal(pay_h[offsets[l]:offsets[l] + p_ref.size], p_ref), (name, l, cands[choice[l]])
+            assert np.array_equal(ef_h[off:off + n].view(np.uint32), e_ref.view(np.uint32)), (name, l)
+    reuse.close()
+    plain.close()
+
+
 def _one_call_against_separate(reuse, plain, g, e, layers, ctab, default, n_bins, capacity, tag, strict=False):
     """One call on `reuse`; the same assignment compressed by the separate call on `plain`."""
     from paper_2210_17357_amd import binding as B
