@@ -263,7 +263,9 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     algo["compress/quant_compress"] = cq + mean_bits / 8.0 + 8.0 / 128.0
     elems["compress/quant_compress"] = nq
     algo["compress/topk_collect"], elems["compress/topk_collect"] = ct, ntk
-    algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = 12.0, nlr
+    # (with the promise of a zero buffer the one call's low-rank update reads g and writes e' only)
+    lr_ef_bytes = 8.0 if (calls == "one" and not has_ef) else 12.0
+    algo["compress/lowrank_ef"], elems["compress/lowrank_ef"] = lr_ef_bytes, nlr
     # dense contractions of the low-rank path: flops per launch
     flops = {}
     mn2d = float(sum(int(r) * int(c) for r, c in zip(batch.rows, batch.cols)))
@@ -312,7 +314,10 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
     profile_bytes = rd * N * (2.0 * args.power_iters if lowrank else 1.0)
     compress_bytes = (float(((cq * numels + chosen_bytes)[fam == W.QUANT]).sum())
                       + float(((ct * numels + chosen_bytes)[fam == W.TOPK]).sum())
-                      + float(((12.0 + 8.0 * args.power_iters) * numels + chosen_bytes)[fam == W.LOWRANK].sum()))
+                      # low rank: the one call reuses the profile's factors (only the update of the error
+                      # feedback moves data); the separate compression contracts the matrix again
+                      + float(((lr_ef_bytes + (0.0 if calls == "one" else 8.0 * args.power_iters)) * numels
+                               + chosen_bytes)[fam == W.LOWRANK].sum()))
     roofline_phase = {}
     for key, nbytes in (("profile", profile_bytes), ("compress", compress_bytes)):
         if key in phase_ms and phase_ms[key] > 0:

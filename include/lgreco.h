@@ -356,10 +356,11 @@ int lgreco_get_timing_totals(lgreco_handle_t* h, int32_t call, const char** name
  * caller guarantees that the buffer holds zeros on entry of every such call (the first step of a
  * run, or a caller that keeps no error feedback between calls and hands in a cleared buffer).  The
  * profile then does not read it (x = fl32(g + 0) = g: 4 bytes per element less to fetch, which the
- * memory-bound contractions of the low-rank profile feel most); the compression reads and updates
- * it as ever, and every result is the one the call gives without the promise.  A buffer that is
- * not zero under the promise gives a profile of g and a compression of g + e: not an error the
- * library can see.  Off at creation. */
+ * memory-bound contractions of the low-rank profile feel most), nor does the low-rank layers'
+ * compression of the same call, which writes the new error feedback without fetching the old;
+ * the other families' compression reads and updates it as ever, and every result is the one the
+ * call gives without the promise.  A buffer that is not zero under the promise gives results
+ * that ignore part or all of its content: not an error the library can see.  Off at creation. */
 int lgreco_set_ef_zero_on_entry(lgreco_handle_t* h, int32_t on);
 
 /* How many solves on this handle found the solver's result block incomplete when its sequence

@@ -1102,7 +1102,7 @@ static int profile_solve_impl(lgreco_handle_t* h, const float* d_grads, const fl
             // ... and the low-rank layers': the factors of every rank are the leading columns of
             // the rank-64 run the profile just made on this data
             HIPCHK(lowrank_compress_known(&h->lowrank, d_grads, ec->d_ef, h->d_layers, ec->d_q, h->cfg.r_max,
-                                          ec->d_payload, h->tm, s));
+                                          ec->d_payload, h->tm, s, h->ef_zero_on_entry));
         }
         // the compress call stays open until lgreco_compress's part has queued the rest: nobody
         // reads its events out before (that would wait for the kernel just queued)

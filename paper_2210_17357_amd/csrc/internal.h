@@ -331,7 +331,8 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
                             hipStream_t s);
 // low-rank layers of a compression queued right behind a profile of the same data (see topk_compress_known)
 hipError_t lowrank_compress_known(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers, float* q,
-                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s);
+                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s,
+                                  bool e_is_zero = false);   // e_is_zero: e holds zeros on entry (the caller's promise) and is not read
 // receiver side: out (+)= Phat Q^T from the payload
 hipError_t lowrank_decompress(LowrankScratch* t, const DevLayer* h_layers, int L, int r_max, const uint8_t* payload,
                               float* out, bool accumulate, Timing* tm, hipStream_t s);

@@ -86,6 +86,7 @@ struct LrParams {
     int32_t col[LGRECO_MAX_CANDS];
     int32_t accumulate;      // decode: add the image to the output instead of replacing it
     int32_t q_from_scratch;  // P = X Q reads the previous step's Q instead of the warm start
+    int32_t e_is_zero;       // compression: e is null because the caller promised zeros; x = fl32(g + 0) all the same
     const DevLayer* dev_layers;   // KNOWN kernels: the caller's layer records (family, rank, payload offset) on the device
 };
 
@@ -721,76 +722,83 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
         const int rr = f >> 6, c = f & 63;
         Ps[rr][c] = (row0 + rr < m && c < r) ? P[(int64_t)(row0 + rr) * pstride + c] : 0.0f;
     }
-    // Software pipeline over the 64-column tiles of the span: the loads of tile t+1 (x and the
-    // rows of Q) are issued before the MFMAs of tile t and first touched at the top of the next
-    // iteration.  Interior tiles of aligned layers take a path without per-load conditions.
-    float4 xn[4], en[4], qn[4];
-    float qs[16];
-    bool fast_x = false, fast_q = false, add_e = false;
+    // Software pipeline over the 64-column tiles of the span, two tiles deep: the loads of tiles
+    // t+1 and t+2 (x and the rows of Q) are in flight while tile t is worked on, in two register
+    // sets that take turns (a workgroup has few neighbours on its compute unit - LDS allows three -
+    // so the bytes in flight per workgroup are what the memory latency is hidden with).  Interior
+    // tiles of aligned layers take a path without per-load conditions.
+    struct Stage {
+        float4 xn[4], en[4], qn[4];
+        float qs[16];
+        bool fast_x, fast_q, add_e;
+    };
     const float* __restrict__ ebase = ein ? ein + L.offset : nullptr;
-    auto fetch = [&](int c0) {
-        fast_x = vec && g != nullptr && row0 + 64 <= m && c0 + kLrCols <= n;
-        add_e = fast_x && ebase != nullptr;
-        if (fast_x) {
+    auto fetch = [&](Stage& S, int c0) __attribute__((always_inline)) {
+        S.fast_x = vec && g != nullptr && row0 + 64 <= m && c0 + kLrCols <= n;
+        S.add_e = S.fast_x && ebase != nullptr;
+        if (S.fast_x) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int f = tid + 256 * q;
                 const int64_t idx = (int64_t)(row0 + (f >> 4)) * n + c0 + (f & 15) * 4;
-                xn[q] = *reinterpret_cast<const float4*>(g + idx);
-                if (ebase) en[q] = *reinterpret_cast<const float4*>(ebase + idx);
+                S.xn[q] = *reinterpret_cast<const float4*>(g + idx);
+                if (ebase) S.en[q] = *reinterpret_cast<const float4*>(ebase + idx);
             }
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int f = tid + 256 * q;
                 const int row = row0 + (f >> 4), colx = c0 + (f & 15) * 4;
-                xn[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (g && row < m && colx < n) xn[q] = load_x4(g, ebase, (int64_t)row * n + colx, n - colx, vec);
+                S.xn[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g && row < m && colx < n) S.xn[q] = load_x4(g, ebase, (int64_t)row * n + colx, n - colx, vec);
             }
         }
-        fast_q = !DECODE && c0 + kLrCols <= n;        // scratch Q: 64 columns per row, 16-byte aligned
-        if (fast_q) {
+        S.fast_q = !DECODE && c0 + kLrCols <= n;        // scratch Q: 64 columns per row, 16-byte aligned
+        if (S.fast_q) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int f = tid + 256 * q;
-                qn[q] = *reinterpret_cast<const float4*>(Q + (int64_t)(c0 + (f >> 4)) * kLrCols + (f & 15) * 4);
+                S.qn[q] = *reinterpret_cast<const float4*>(Q + (int64_t)(c0 + (f >> 4)) * kLrCols + (f & 15) * 4);
             }
         } else {
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
                 const int f = tid + 256 * q;
                 const int cc = f >> 6, k = f & 63;
-                qs[q] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * pstride + k] : 0.0f;
+                S.qs[q] = (c0 + cc < n && k < r) ? Q[(int64_t)(c0 + cc) * pstride + k] : 0.0f;
             }
         }
     };
-    fetch(cbeg);
-    for (int c0 = cbeg; c0 < cend; c0 += kLrCols) {
+    // one tile from the stage that holds it; the stage is refilled with the tile two further on
+    auto step = [&](Stage& S, int c0) __attribute__((always_inline)) {
         float4 x[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            x[q] = xn[q];
-            if (add_e) { x[q].x += en[q].x; x[q].y += en[q].y; x[q].z += en[q].z; x[q].w += en[q].w; }
+            x[q] = S.xn[q];
+            if (S.add_e) { x[q].x += S.en[q].x; x[q].y += S.en[q].y; x[q].z += S.en[q].z; x[q].w += S.en[q].w; }
+            // zeros that are not read are still added (a gradient of -0 becomes the +0 the sum with
+            // a stored zero gives: every bit as without the promise)
+            if (!DECODE && p.e_is_zero) { x[q].x += 0.0f; x[q].y += 0.0f; x[q].z += 0.0f; x[q].w += 0.0f; }
         }
-        if (fast_q) {
+        if (S.fast_q) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int f = tid + 256 * q;
                 const int cc = f >> 4, k = (f & 15) * 4;
-                Qs[cc][k] = k < r ? qn[q].x : 0.0f;
-                Qs[cc][k + 1] = k + 1 < r ? qn[q].y : 0.0f;
-                Qs[cc][k + 2] = k + 2 < r ? qn[q].z : 0.0f;
-                Qs[cc][k + 3] = k + 3 < r ? qn[q].w : 0.0f;
+                Qs[cc][k] = k < r ? S.qn[q].x : 0.0f;
+                Qs[cc][k + 1] = k + 1 < r ? S.qn[q].y : 0.0f;
+                Qs[cc][k + 2] = k + 2 < r ? S.qn[q].z : 0.0f;
+                Qs[cc][k + 3] = k + 3 < r ? S.qn[q].w : 0.0f;
             }
         } else {
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
                 const int f = tid + 256 * q;
-                Qs[f >> 6][f & 63] = qs[q];
+                Qs[f >> 6][f & 63] = S.qs[q];
             }
         }
         __syncthreads();
-        if (c0 + kLrCols < cend) fetch(c0 + kLrCols);
+        if (c0 + 2 * kLrCols < cend) fetch(S, c0 + 2 * kLrCols);
         f32x16 acc = {0};
         for (int kk = 0; kk < kmax; kk += 2)
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[ar][kk + ak], Qs[bj][kk + ak], acc, 0, 0, 0);
@@ -820,6 +828,13 @@ __global__ __launch_bounds__(256) void lr_ef_kernel(LrParams p) {
                 }
             }
         }
+    };
+    Stage s0, s1;
+    fetch(s0, cbeg);
+    if (cbeg + kLrCols < cend) fetch(s1, cbeg + kLrCols);
+    for (int c0 = cbeg; c0 < cend; c0 += 2 * kLrCols) {
+        step(s0, c0);
+        if (c0 + kLrCols < cend) step(s1, c0 + kLrCols);
     }
 }
 
@@ -1160,13 +1175,14 @@ hipError_t lowrank_compress(LowrankScratch* t, const float* g, float* e, const D
 // every rank's factors are their leading columns, so nothing is contracted again.  Uses the
 // profile's work tables (all layers); needs nothing from the host.
 hipError_t lowrank_compress_known(LowrankScratch* t, const float* g, float* e, const DevLayer* d_layers, float* q,
-                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s) {
+                                  int r_max, uint8_t* payload, Timing* tm, hipStream_t s, bool e_is_zero) {
     LrHost* H = &((LrHost*)t->host)[kLrSlotProfile];
     if (H->layers.empty()) return hipSuccess;
     LrParams p{};
     lr_fill_params(H, &p);
     p.g = g;
-    p.e = e;
+    p.e = e_is_zero ? nullptr : e;       // promised zeros are not fetched
+    p.e_is_zero = e_is_zero ? 1 : 0;
     p.e_out = e;
     p.q0 = q;
     p.q_out = q;
