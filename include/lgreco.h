@@ -115,7 +115,9 @@ typedef struct {
 
 /* Create a handle for problems of at most max_elems gradient elements (sum of numel),
  * max_layers layers and max_cands candidates.  Allocates the scratch memory on the current
- * device; the handle must be used on that device only, by one thread at a time. */
+ * device (about 16 bytes per element of max_elems for the Top-K candidate buffers, the rest is
+ * small beside it; the low-rank buffers grow with the first call that needs them); the handle
+ * must be used on that device only, by one thread at a time. */
 int lgreco_create(lgreco_handle_t** out, const lgreco_config_t* cfg, int64_t max_elems,
                   int32_t max_layers, int32_t max_cands);
 int lgreco_destroy(lgreco_handle_t* h);
