@@ -302,6 +302,11 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
                         "traffic": measured_traffic(w.name).get(dom),
                         "algorithmic_bytes": round(algo[dom] * elems[dom]),
                         "avg_ms": timed[dom]["avg_ms"], "algo_bytes_per_elem": round(algo[dom], 4)}
+            if in_place and dom.startswith("profile/"):
+                # what the per-element figure stands for, since it is not the profile-only 8 bytes
+                roofline["note"] = ("the one call's profile pass reads g and e (8 B) and stores x = g + e into the "
+                                    "error-feedback buffer (4 B), which the compression then reads instead of g and e; "
+                                    "the candidate records it also writes (6 B per candidate) are not counted")
 
     # per phase: GPU time between the first and the last thing the phase queues, and what the phase
     # must move (profile: one read of g and e for every candidate; compress: read g, e, write e and
