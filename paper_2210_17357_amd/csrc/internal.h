@@ -234,8 +234,10 @@ struct TopkScratch {
     void* d_tinfo_kept = nullptr;
     uint32_t* d_k = nullptr;          // [max_layers x kMaxTopk] requested k (0 = layer inactive)
     uint32_t* d_lo = nullptr;         // [max_layers] lowest coarse key collected as a candidate
-    uint32_t* d_any_again = nullptr;  // one word: number of the last scan that flagged a layer for a second collection
-    uint32_t scan_seq = 0;            // scans launched so far (never 0 once one has run)
+    // what a second collection reads and writes (noted by topk_select for the refinement kernel)
+    const float* rc_g = nullptr;
+    const float* rc_e = nullptr;
+    float* rc_ef_out = nullptr;
     uint32_t* d_hint[2] = {nullptr, nullptr};   // per kind of call: bound derived from the last thresholds
     bool hint_valid[2] = {false, false};
     bool reuse_thresholds = false;

@@ -272,7 +272,7 @@ struct CollectParams {
     const DevLayer* layers;
     const Tile* tiles;
     const uint32_t* ks;
-    const TopkLayer* tl;        // only_flagged: layers to collect again
+    const TopkLayer* tl;        // KNOWN: the profile's selection records
     const uint32_t* lo;
     uint32_t* hist;
     uint32_t* cand;
@@ -282,7 +282,6 @@ struct CollectParams {
     const int64_t* cand_base;
     TopkTileInfo* tinfo;
     double* base_part;
-    int32_t only_flagged;
     uint32_t* cnt_b;            // KNOWN: [L x kBinsB] last 9 pattern bits inside each layer's boundary sub-bin
     // profile (no EMIT): not null = x is written here as it is formed (may be the buffer e points to:
     // every element is read once, by the lane that then writes it)
@@ -292,15 +291,25 @@ struct CollectParams {
 };
 
 // Main pass without quantization candidates: exact coarse histogram (HIST) and candidate
-// collection.  With only_flagged it collects again the layers whose predicted bound was too high.
+// collection.
 // KNOWN (compression right behind a profile of the same data): which layers take part and what
 // they keep comes from the layer records (family, slot of the chosen density in the profile's
 // selection records), the bound is the 22-bit prefix the profile resolved the k-th magnitude to
 // (nearly exactly the kept set qualifies), and the elements inside that boundary sub-bin are
 // counted by their last 9 pattern bits (s_hist: kBinsB cells) for the exact threshold.
-template <bool HIST, bool EMIT, bool KNOWN = false>
-__device__ __forceinline__ void collect_tile(const CollectParams& p, const int tile, uint32_t* s_hist, double* s_red) {
+// TEAM (the second collection, made by the refinement kernel's workgroup for its own tiles): the
+// workgroup is several teams of kThreads threads, each with a tile of its own (or none: `active`
+// false; the teams still meet at the barrier) and its own s_red; the caller has checked that the
+// layer takes part.
+template <bool HIST, bool EMIT, bool KNOWN = false, bool TEAM = false>
+__device__ __forceinline__ void collect_tile(const CollectParams& p, const int tile, uint32_t* s_hist, double* s_red,
+                                             const bool active = true) {
     static_assert(!(HIST && KNOWN), "the coarse histogram is not built when the thresholds are known");
+    static_assert(!TEAM || (!HIST && !KNOWN), "teams collect, nothing else");
+    if (TEAM && !active) {             // (uniform over the team)
+        __syncthreads();
+        return;
+    }
     const Tile t = p.tiles[tile];
     const DevLayer L = p.layers[t.layer];
     uint32_t bound;
@@ -309,15 +318,16 @@ __device__ __forceinline__ void collect_tile(const CollectParams& p, const int t
         const TopkSel& S = p.tl[t.layer].sel[L.slot];
         bound = ((S.tbin << 10) | S.bin_a) << 9;
     } else {
-        if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
-        if (p.only_flagged && !p.tl[t.layer].recollect) return;
+        if (!TEAM) {
+            if (p.ks[(size_t)t.layer * kMaxTopk] == 0) return;
+        }
         bound = bound_of_key(p.lo[t.layer]);
     }
     const float* gp = p.g + L.offset + t.pos;
     const float* ep = p.e ? p.e + L.offset + t.pos : nullptr;
     float* const eo = EMIT ? p.ef_out + L.offset + t.pos : nullptr;
     float* const xo = (!EMIT && p.x_out) ? p.x_out + L.offset + t.pos : nullptr;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = TEAM ? (int)(threadIdx.x % kThreads) : (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (HIST || KNOWN) {
         for (int b = tid; b < (KNOWN ? kBinsB : kHistBins); b += kThreads) s_hist[b] = 0;
         __syncthreads();
@@ -596,40 +606,6 @@ __global__ __launch_bounds__(kThreads) void topk_collect_kernel(CollectParams p)
     collect_tile<HIST, EMIT>(p, (int)blockIdx.x, s_hist, s_red);
 }
 
-// The second collection (layers whose predicted bound was too high; none in the usual call): a
-// workgroup looks at kRecollectBatch consecutive tiles, so that the launch that finds nothing to
-// do is short however many tiles there are.
-constexpr int kRecollectBatch = 8;
-template <bool EMIT>
-__global__ __launch_bounds__(kThreads) void topk_recollect_kernel(CollectParams p, int n_tiles,
-                                                                   const uint32_t* __restrict__ any_again, uint32_t seq) {
-    __shared__ uint32_t s_hist[1];
-    __shared__ double s_red[kThreads / 64];
-    // no layer was flagged by the scan this launch follows (the usual case): one load and out.  (A
-    // stale word that happens to equal seq only costs the look at the per-layer flags below.)
-    if (*any_again != seq) return;
-    // (the grid is capped: a workgroup goes on to further batches)
-    for (int first = (int)blockIdx.x * kRecollectBatch; first < n_tiles; first += (int)gridDim.x * kRecollectBatch) {
-    // the flags of the batch's tiles first, every load of a level unconditional (indices clamped)
-    // so that the chains tile -> layer -> flag run side by side
-    int layer[kRecollectBatch];
-    uint32_t todo = 0;
-#pragma unroll
-    for (int q = 0; q < kRecollectBatch; ++q) layer[q] = p.tiles[min(first + q, n_tiles - 1)].layer;
-#pragma unroll
-    for (int q = 0; q < kRecollectBatch; ++q) {
-        const uint32_t flagged = p.tl[layer[q]].recollect;
-        const uint32_t k = p.ks[(size_t)layer[q] * kMaxTopk];
-        if (flagged && k && first + q < n_tiles) todo |= 1u << q;
-    }
-    for (int q = 0; q < kRecollectBatch; ++q) {
-        if (!(todo >> q & 1u)) continue;                // workgroup-uniform
-        collect_tile<false, EMIT>(p, first + q, s_hist, s_red);
-        __syncthreads();                                // s_red is reused
-    }
-    }
-}
-
 // One workgroup per layer: threshold bin and in-bin rank for every requested k; threshold-bin
 // lists; check of the predicted bound.
 // Workgroups past the first n_layers (when the call also profiles quantization) sum that family's
@@ -646,8 +622,7 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
                                                         const int64_t* __restrict__ cand_base,
                                                         const uint32_t* lo_in, uint32_t* lo_out,
                                                         TopkLayer* __restrict__ tl, uint32_t* hint, int clear,
-                                                        int n_layers, ScanReduce red, uint32_t* any_again,
-                                                        uint32_t seq) {
+                                                        int n_layers, ScanReduce red) {
     __shared__ __align__(16) unsigned char s_raw[sizeof(uint32_t) * kHistBins];   // 16 KB: the histogram, or the reduction's tree
     static_assert(sizeof(s_raw) >= sizeof(double) * kMaxQuant * 256, "shared by both jobs");
     if ((int)blockIdx.x >= n_layers) {
@@ -713,7 +688,6 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(uint32_t* __restrict__ h
         const uint32_t used = lo_in[l];
         sT.recollect = used > mn ? 1u : 0u;
         sT.pad = 0;
-        if (sT.recollect) *any_again = seq;        // this launch's number: the second collection has work
         lo_out[l] = sT.recollect ? mn : used;
         // collection bound for the next call of this kind: kHintMargin coarse bins (4.4 % in magnitude each)
         // under the lowest threshold found now
@@ -743,7 +717,26 @@ struct RefineParams {
     int32_t stride;
     int32_t ntk;
     int32_t col[kMaxTopk];
+    // the second collection of a layer whose predicted bound was too high (flagged by the scan):
+    // every workgroup of the first refinement kernel makes it for its own tiles before it looks at
+    // their candidates (rc.ef_out not null: the compression's form, which also writes x)
+    CollectParams rc;
 };
+
+// The second collection for the tiles [t0, t1) of a flagged layer, by a refinement workgroup: four
+// teams of kThreads threads, a tile each per round.
+static_assert(kRefThreads % kThreads == 0, "whole teams");
+template <bool EMIT>
+__device__ __forceinline__ void collect_again(const CollectParams& rc, int t0, int t1) {
+    constexpr int kTeams = kRefThreads / kThreads;
+    __shared__ double s_team_red[kTeams][kThreads / 64];
+    const int team = threadIdx.x / kThreads;
+    for (int first = t0; first < t1; first += kTeams) {
+        const int tile = first + team;
+        collect_tile<false, EMIT, false, true>(rc, min(tile, t1 - 1), nullptr, s_team_red[team], tile < t1);
+        __syncthreads();                                // s_team_red is reused; the tile's records are written
+    }
+}
 
 // Walks the candidates of tiles [t0, t1): one (tile, wavefront slice) pair per wavefront at a
 // time, 8 loads in flight per lane; f(pattern) is called for every candidate, in a fixed order
@@ -840,13 +833,17 @@ __host__ __device__ constexpr size_t refine_a_lds(int ntk, bool energy) {
     return (size_t)ntk * kBinsA * (energy ? 8 : 4) + kHistBins;
 }
 template <int NTK>
-__global__ __launch_bounds__(kRefThreads) void topk_refine_a_kernel(RefineParams p) {
+__global__ __launch_bounds__(kRefThreads, 8) void topk_refine_a_kernel(RefineParams p) {
     constexpr bool ENERGY = NTK > 0;
     extern __shared__ unsigned char refine_smem[];
     __shared__ double s_red[kRefThreads / 64][kMaxTopk];
     const RefWork w = p.work[blockIdx.x];
     const int l = w.layer;
     const TopkLayer& T = p.tl[l];
+    if (T.recollect) {                  // workgroup-uniform; rare: the predicted bound was too high
+        if (ENERGY) collect_again<false>(p.rc, w.t0, w.t1);
+        else collect_again<true>(p.rc, w.t0, w.t1);
+    }
     const int nlists = (int)T.nlists;
     const int tid = threadIdx.x, ntk = p.ntk;
     unsigned long long* const s_cell = reinterpret_cast<unsigned long long*>(refine_smem);   // ENERGY
@@ -1414,9 +1411,6 @@ hipError_t topk_scratch_create(TopkScratch* t, int64_t max_elems, int max_layers
     TK_CHECK(hipMalloc(&t->d_kept_idx, sizeof(uint32_t) * (size_t)max_elems));
     TK_CHECK(hipMalloc(&t->d_tinfo_kept, sizeof(TopkTileInfo) * (size_t)max_tiles));
     TK_CHECK(hipMalloc(&t->d_lo, sizeof(uint32_t) * (size_t)max_layers));
-    TK_CHECK(hipMalloc(&t->d_any_again, 64));
-    TK_CHECK(hipMemset(t->d_any_again, 0, 64));
-    t->scan_seq = 0;
     for (int i = 0; i < 2; ++i) TK_CHECK(hipMalloc(&t->d_hint[i], sizeof(uint32_t) * (size_t)max_layers));
     TK_CHECK(hipMalloc(&t->d_tilecnt, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
     TK_CHECK(hipMalloc(&t->d_tilebase, sizeof(uint2) * (size_t)max_tiles * (kThreads / 64)));
@@ -1459,7 +1453,6 @@ void topk_scratch_destroy(TopkScratch* t) {
     (void)hipFree(t->d_kept_idx);
     (void)hipFree(t->d_tinfo_kept);
     (void)hipFree(t->d_lo);
-    (void)hipFree(t->d_any_again);
     for (int i = 0; i < 2; ++i) (void)hipFree(t->d_hint[i]);
     (void)hipFree(t->d_tilecnt);
     (void)hipFree(t->d_tilebase);
@@ -1656,32 +1649,20 @@ hipError_t topk_select(TopkScratch* t, const float* g, const float* e, float* ef
         hipLaunchKernelGGL(topk_scan_kernel, dim3(quant ? 2 * L : L), dim3(256), 0, s, t->d_hist,
                            (const uint32_t*)t->d_k, ntk, (const int64_t*)t->d_cand_base,
                            first_group ? t->lo_src : (const uint32_t*)t->d_lo, t->d_lo, (TopkLayer*)t->d_tl, hint,
-                           last_group ? 1 : 0, L, red, t->d_any_again, ++t->scan_seq);
+                           last_group ? 1 : 0, L, red);
         TK_CHECK(hipGetLastError());
         if (hint) t->hint_valid[t->cur_slot] = true;
         if (last_group) t->hist_clean = true;
         t->lo_src = t->d_lo;                     // a second collection uses the bound the scan wrote
     }
-    {
-        Section sec(tm, "topk_recollect");
-        CollectParams p = collect_params(t, g, e, d_layers, d_tiles);
-        p.only_flagged = 1;
-        p.ef_out = ef_out;
-        p.record_idx = (!ef_out && t->cand_has_idx) ? 1 : 0;
-        // a second collection reads x = g + e again: in compress e already holds x, so g is not added
-        // at most two workgroups per compute unit: the launch that finds nothing to do ends at once
-        const dim3 grid(std::min((n_tiles + kRecollectBatch - 1) / kRecollectBatch, 512));
-        if (ef_out) {
-            p.g = ef_out;
-            p.e = nullptr;
-            hipLaunchKernelGGL(topk_recollect_kernel<true>, grid, dim3(kThreads), 0, s, p, n_tiles,
-                               (const uint32_t*)t->d_any_again, t->scan_seq);
-        } else {
-            hipLaunchKernelGGL(topk_recollect_kernel<false>, grid, dim3(kThreads), 0, s, p, n_tiles,
-                               (const uint32_t*)t->d_any_again, t->scan_seq);
-        }
-        TK_CHECK(hipGetLastError());
-    }
+    // Layers whose predicted bound was too high (flagged by the scan; none in the usual call) are
+    // collected a second time with the exact bound, by the first refinement kernel's workgroups,
+    // each for its own tiles: what that collection reads and writes is noted here.  It reads
+    // x = g + e again; in compress e already holds x, so g is not added.
+    t->rc_g = ef_out ? ef_out : g;
+    t->rc_e = ef_out ? nullptr : e;
+    t->rc_ef_out = ef_out;
+    (void)n_tiles;
     return hipSuccess;
 }
 
@@ -1710,6 +1691,9 @@ hipError_t topk_finalize(TopkScratch* t, const DevLayer* d_layers, const Tile* d
     p.stride = stride;
     p.ntk = ntk;
     for (int j = 0; j < ntk; ++j) p.col[j] = col ? col[j] : 0;
+    p.rc = collect_params(t, t->rc_g, t->rc_e, d_layers, d_tiles);
+    p.rc.ef_out = t->rc_ef_out;
+    p.rc.record_idx = (!t->rc_ef_out && t->cand_has_idx) ? 1 : 0;
     Section sec(tm, "topk_refine");
     if (d_errors) {       // profile: level A gives the dropped energy, no exact threshold is needed
         const size_t lds = refine_a_lds(ntk, true);
