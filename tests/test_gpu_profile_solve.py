@@ -642,6 +642,43 @@ def test_whole_path_call_failing_after_good_calls_with_history_on():
     plain.close()
 
 
+def test_whole_path_call_on_a_stream_of_the_callers():
+    """Everything the one call queues (part of the compression goes through a stream the handle
+    owns) is ordered with the stream the caller passes, whichever that is: three steps on a stream
+    created by the caller, inputs prepared on it, one wait on THAT stream at the end; results
+    against the separate calls made the ordinary way."""
+    from paper_2210_17357_amd import binding as B
+    torch = torch_cuda()
+    w = _workload("mixed")
+    batch = W.generate(w)
+    cands = list(w.candidates)
+    layers, ctab = tables(batch, cands)
+    g, e, _ = to_device(batch)
+    L = len(batch.numels)
+    capacity = int(B.sizes(layers, ctab).max(axis=1).sum()) + 16 * (L + 1)
+    torch.cuda.synchronize()
+    mine = torch.cuda.Stream()                     # default priority
+    h = B.Handle(int(batch.grads.size), L, len(cands), reuse_thresholds=True)
+    runs = []
+    with torch.cuda.stream(mine):
+        for step in range(3):
+            ef = e.clone()
+            pay = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+            out = h.profile_solve_compress(g, ef, layers, ctab, w.default, w.n_bins, pay, stream=mine.cuda_stream)
+            assert out[0] == B.OK
+            runs.append((out, ef, pay))
+    mine.synchronize()
+    ref = B.Handle(int(batch.grads.size), L, len(cands))
+    for out, ef, pay in runs:
+        ef2 = e.clone()
+        pay2 = torch.zeros(capacity, dtype=torch.uint8, device="cuda")
+        ref.compress(g, ef2, layers, ctab, out[4], pay2, out[7])
+        torch.cuda.synchronize()
+        assert torch.equal(pay, pay2) and torch.equal(ef.view(torch.int32), ef2.view(torch.int32))
+    h.close()
+    ref.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed", "topk", "quant", "lowrank"])
 def test_zero_error_feedback_promise_changes_nothing(kind):
     """lgreco_set_ef_zero_on_entry: with a cleared error-feedback buffer the one call must return
