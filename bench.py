@@ -90,6 +90,9 @@ def parse_args():
                     help="Top-K: the main loop itself runs with reuse_thresholds = 0 (the default run reports "
                          "that case under \"cold\")")
     ap.add_argument("--no-cold", action="store_true", help="leave out the reuse_thresholds = 0 loop")
+    ap.add_argument("--dp-groups", type=int, default=0,
+                    help="layer groups of the solver: 0 = the library decides from the table's size, 1 = one "
+                         "sequential sweep, 2 / 4 / 8 = that many groups")
     ap.add_argument("--keep-ef-on-failure", action="store_true",
                     help="create the handle with keep_ef_on_failure = 1: the profile of the one call does not "
                          "leave x in the error-feedback buffer (more memory traffic, same results)")
@@ -185,7 +188,7 @@ def measure(wname, args, steps, warmup, with_cold, with_decompress):
         """warm-up + timed steps on a handle of its own; returns (elapsed s, kernel totals, last results)."""
         h = B.Handle(int(batch.grads.size), L, len(cands), bucket=w.bucket, stochastic=w.stochastic,
                      seed=w.seed, r_max=w.r_max, power_iters=args.power_iters, reuse_thresholds=reuse,
-                     keep_ef_on_failure=args.keep_ef_on_failure)
+                     keep_ef_on_failure=args.keep_ef_on_failure, dp_groups=args.dp_groups)
         h.set_timing(timing_level)
         h.set_timing_stride(max(1, args.time_every))
         if not has_ef:
